@@ -1,0 +1,155 @@
+"""Seeded synthetic rollouts and parameter initialisation.
+
+Stands in for the paper's simulator (Algorithm 1), which is not available:
+depth images are a 2.0 m background with 1-4 rectangles at U(0.2, 1.5) m,
+sigma = 0.01 pixel noise and 5 % zeroed pixels; stereo views are uniform [0,1]
+RGB with random coloured rectangles.  This module holds input generation only
+(no arithmetic of the learner) and is the one module used by both the HIP
+path's harness and the test oracle's harness.
+
+Everything is drawn from numpy's PCG64 with explicit seeds.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import torch
+
+from .configs import layer_shapes
+
+_CHUNK = 256
+
+
+def _rects(rng, n, h, w):
+    cnt = rng.integers(1, 5, size=n)
+    out = []
+    for k in range(4):
+        top = rng.integers(0, h, size=n)
+        left = rng.integers(0, w, size=n)
+        rh = rng.integers(max(1, h // 8), h // 2 + 1, size=n)
+        rw = rng.integers(max(1, w // 8), w // 2 + 1, size=n)
+        out.append((cnt > k, top, left, rh, rw))
+    return out
+
+
+def _paint(img, rects, values):
+    """img [n][c][h][w]; values[k] [n][c]; later rectangles overwrite earlier ones."""
+    n, c, h, w = img.shape
+    ys = np.arange(h)[None, :, None]
+    xs = np.arange(w)[None, None, :]
+    for (on, top, left, rh, rw), val in zip(rects, values):
+        m = (on[:, None, None] & (ys >= top[:, None, None]) & (ys < (top + rh)[:, None, None])
+             & (xs >= left[:, None, None]) & (xs < (left + rw)[:, None, None]))
+        img[...] = np.where(m[:, None], val[:, :, None, None], img)
+    return img
+
+
+def depth_images(rng, n, h, w):
+    """float32 [n][1][h][w] depth maps in metres (not yet narrowed)."""
+    out = np.empty((n, 1, h, w), np.float32)
+    for a in range(0, n, _CHUNK):
+        b = min(n, a + _CHUNK)
+        m = b - a
+        img = np.full((m, 1, h, w), 2.0, np.float32)
+        rects = _rects(rng, m, h, w)
+        vals = [rng.uniform(0.2, 1.5, size=(m, 1)).astype(np.float32) for _ in range(4)]
+        _paint(img, rects, vals)
+        img += 0.01 * rng.standard_normal(img.shape, dtype=np.float32)
+        img[rng.random(img.shape, dtype=np.float32) < 0.05] = 0.0
+        out[a:b] = img
+    return out
+
+
+def rgb_images(rng, n, h, w):
+    """float32 [n][3][h][w], uniform [0,1] texture with 1-4 random coloured rectangles."""
+    out = np.empty((n, 3, h, w), np.float32)
+    for a in range(0, n, _CHUNK):
+        b = min(n, a + _CHUNK)
+        m = b - a
+        img = rng.random((m, 3, h, w), dtype=np.float32)
+        rects = _rects(rng, m, h, w)
+        vals = [rng.random((m, 3), dtype=np.float32) for _ in range(4)]
+        out[a:b] = _paint(img, rects, vals)
+    return out
+
+
+def narrow_bf16(x: np.ndarray) -> np.ndarray:
+    """One round-to-nearest-even cast to bf16, widened back to float32 (torch's cast)."""
+    return torch.from_numpy(np.ascontiguousarray(x, np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
+
+
+def rollout_step(cfg: dict, rng) -> dict:
+    """One step's slab for all N envs, as float32/uint8 numpy arrays in canonical layout."""
+    net, N = cfg["net"], cfg["num_envs"]
+    V, Cc, H, W, P, A = net["n_views"], net["in_c"], net["in_h"], net["in_w"], net["proprio_dim"], net["act_dim"]
+    if Cc == 1:
+        obs = np.stack([depth_images(rng, N, H, W) for _ in range(V)], axis=1)
+    else:
+        obs = np.stack([rgb_images(rng, N, H, W) for _ in range(V)], axis=1)
+    if cfg["obs_dtype"] == "bf16":
+        obs = narrow_bf16(obs)
+    proprio = rng.standard_normal((N, P), dtype=np.float32)
+    action = rng.standard_normal((N, A), dtype=np.float32)
+    # behaviour log-prob: unit Gaussian density of the action plus a small perturbation, so that
+    # probability ratios fall on both sides of the clip range
+    logp = (-0.5 * (action.astype(np.float64) ** 2).sum(1) - 0.5 * A * math.log(2 * math.pi)
+            + 0.1 * rng.standard_normal(N)).astype(np.float32)
+    value = rng.standard_normal(N, dtype=np.float32)
+    reward = rng.standard_normal(N, dtype=np.float32)
+    done = (rng.random(N) < 0.01).astype(np.uint8)
+    return dict(obs=obs, proprio=proprio, action=action, logp_old=logp, value=value, reward=reward, done=done)
+
+
+def rollout(cfg: dict, seed: int | None = None) -> dict:
+    """All T steps stacked ([T][N]...), plus last_value [N]."""
+    rng = np.random.default_rng(cfg["seed"] if seed is None else seed)
+    steps = [rollout_step(cfg, rng) for _ in range(cfg["horizon"])]
+    out = {k: np.stack([s[k] for s in steps]) for k in steps[0]}
+    out["last_value"] = rng.standard_normal(cfg["num_envs"], dtype=np.float32)
+    return out
+
+
+def param_layout(net: dict):
+    """[(name, shape, fan_in)] in canonical order: conv W/b ..., fc W/b ..., mu W/b, [v w/b, logstd]."""
+    shp = layer_shapes(net)
+    k = net["conv_k"]
+    items = []
+    for i, ((ci, _, _), (co, _, _)) in enumerate(zip(shp[:-1], shp[1:])):
+        items += [(f"conv{i}.w", (co, ci, k, k), ci * k * k), (f"conv{i}.b", (co,), ci * k * k)]
+    c, h, w = shp[-1]
+    fin = net["n_views"] * c * h * w + net["proprio_dim"]
+    for i, f in enumerate(net["fc_dim"]):
+        items += [(f"fc{i}.w", (f, fin), fin), (f"fc{i}.b", (f,), fin)]
+        fin = f
+    A = net["act_dim"]
+    items += [("mu.w", (A, fin), fin), ("mu.b", (A,), fin)]
+    if net["has_value_head"]:
+        items += [("v.w", (fin,), fin), ("v.b", (1,), fin), ("logstd", (A,), 0)]
+    return items
+
+
+def param_slices(net: dict) -> dict:
+    out, off = {}, 0
+    for name, shape, _ in param_layout(net):
+        n = int(np.prod(shape))
+        out[name] = (off, off + n, shape)
+        off += n
+    return out
+
+
+def init_params(net: dict, seed: int) -> np.ndarray:
+    """Canonical float32 parameter vector: weights and biases U(+-1/sqrt(fan_in)), the action
+    head scaled by 0.01, log-std 0."""
+    rng = np.random.default_rng(seed + 7919)
+    parts = []
+    for name, shape, fan_in in param_layout(net):
+        if name == "logstd":
+            parts.append(np.zeros(shape, np.float32))
+            continue
+        bound = 1.0 / math.sqrt(fan_in)
+        x = rng.uniform(-bound, bound, size=shape).astype(np.float32)
+        if name.startswith("mu."):
+            x *= 0.01
+        parts.append(x)
+    return np.concatenate([p.reshape(-1) for p in parts])

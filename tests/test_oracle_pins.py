@@ -1,0 +1,398 @@
+"""Pins for the CPU oracle: closed forms, brute force, finite differences and
+library routines.  None of these touch the HIP path."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ppo_oracle as orc
+from paper_2509_16434_amd import configs, synth
+
+import torch_ref
+
+TINY = dict(n_views=1, in_c=1, in_h=9, in_w=11, proprio_dim=3, act_dim=2, conv_ch=[3, 4], conv_k=3,
+            conv_stride=2, conv_pad=1, fc_dim=[7, 5], has_value_head=1)
+TINY_STEREO = dict(n_views=2, in_c=3, in_h=8, in_w=10, proprio_dim=4, act_dim=3, conv_ch=[4, 5], conv_k=3,
+                   conv_stride=2, conv_pad=1, fc_dim=[6], has_value_head=0)
+
+
+def _batch(net, B, seed, smooth=True):
+    rng = np.random.default_rng(seed)
+    obs = rng.standard_normal((B, net["n_views"], net["in_c"], net["in_h"], net["in_w"])).astype(np.float32)
+    return dict(obs=obs, proprio=rng.standard_normal((B, net["proprio_dim"])),
+                action=rng.standard_normal((B, net["act_dim"])),
+                logp_old=-0.5 * net["act_dim"] * math.log(2 * math.pi) - rng.uniform(0.5, 2.5, B),
+                v_old=rng.standard_normal(B), adv=rng.standard_normal(B), ret=rng.standard_normal(B))
+
+
+def _params(net, seed):
+    rng = np.random.default_rng(seed)
+    p = rng.standard_normal(orc.param_count(net)) * 0.3
+    return p
+
+
+# ----------------------------------------------------------------- GAE
+def _gae_inputs(T, N, seed, p_done=0.2):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((T, N)), (rng.random((T, N)) < p_done).astype(np.uint8),
+            rng.standard_normal((T, N)), rng.standard_normal(N))
+
+
+def test_gae_lambda0_is_one_step_td_error():
+    r, d, v, lv = _gae_inputs(7, 5, 0)
+    adv, ret = orc.gae(r, d, v, lv, 0.97, 0.0)
+    vnext = np.concatenate([v[1:], lv[None]], 0)
+    np.testing.assert_allclose(adv, r + 0.97 * (1 - d) * vnext - v, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(ret, adv + v, rtol=0, atol=0)
+
+
+def test_gae_lambda1_is_discounted_return_minus_value():
+    T, N, g = 9, 4, 0.9
+    r, d, v, lv = _gae_inputs(T, N, 1)
+    adv, _ = orc.gae(r, d, v, lv, g, 1.0)
+    for n in range(N):
+        for t in range(T):
+            G, disc, alive = 0.0, 1.0, True
+            for k in range(t, T):
+                G += disc * r[k, n]
+                disc *= g
+                if d[k, n]:
+                    alive = False
+                    break
+            if alive:
+                G += disc * lv[n]
+            assert abs(adv[t, n] - (G - v[t, n])) < 1e-12
+
+
+def test_gae_brute_force_double_sum():
+    T, N, g, lam = 8, 6, 0.95, 0.8
+    r, d, v, lv = _gae_inputs(T, N, 2, p_done=0.15)
+    adv, _ = orc.gae(r, d, v, lv, g, lam)
+    vnext = np.concatenate([v[1:], lv[None]], 0)
+    delta = r + g * (1 - d) * vnext - v
+    for n in range(N):
+        for t in range(T):
+            s, w = 0.0, 1.0
+            for l in range(T - t):
+                s += w * delta[t + l, n]
+                w *= g * lam * (1 - d[t + l, n])
+            assert abs(adv[t, n] - s) < 1e-12
+
+
+def test_gae_all_done_and_gamma0():
+    r, _, v, lv = _gae_inputs(5, 3, 3)
+    adv, _ = orc.gae(r, np.ones((5, 3), np.uint8), v, lv, 0.99, 0.95)
+    np.testing.assert_allclose(adv, r - v, atol=1e-15)
+    adv, _ = orc.gae(r, np.zeros((5, 3), np.uint8), v, lv, 0.0, 0.95)
+    np.testing.assert_allclose(adv, r - v, atol=1e-15)
+
+
+def test_gae_empty():
+    adv, ret = orc.gae(np.zeros((4, 0)), np.zeros((4, 0), np.uint8), np.zeros((4, 0)), np.zeros(0), 0.9, 0.9)
+    assert adv.shape == (4, 0) and ret.shape == (4, 0)
+
+
+# ----------------------------------------------------------------- permutation
+def test_splitmix64_published_vectors():
+    # first outputs of the public-domain splitmix64 generator seeded with 1234567
+    with open(__file__.rsplit("/", 1)[0] + "/golden/splitmix64_seed1234567.txt") as f:
+        want = [int(x) for x in f.read().split() if not x.startswith("#") and x.isdigit()]
+    assert len(want) == 5
+    assert [orc.splitmix64_nth(1234567, i) for i in range(5)] == want
+
+
+def test_permutation_is_sort_by_key_bruteforce():
+    S = 37
+    p = orc.permutation(11, 3, 2, S)
+    keys = [orc.perm_key(11, 3, 2, i) for i in range(S)]
+    assert list(p) == sorted(range(S), key=lambda i: (keys[i], i))
+
+
+def test_permutation_bijection_partition_and_streams():
+    S, M = 4096, 4
+    p0 = orc.permutation(5, 0, 0, S)
+    assert np.array_equal(np.sort(p0), np.arange(S))
+    parts = p0.reshape(M, S // M)
+    assert len(set(map(tuple, parts))) == M and sum(len(set(x)) for x in parts) == S
+    assert np.array_equal(p0, orc.permutation(5, 0, 0, S))
+    for other in (orc.permutation(5, 0, 1, S), orc.permutation(5, 1, 0, S), orc.permutation(6, 0, 0, S)):
+        assert not np.array_equal(p0, other)
+    # roughly uniform: mean displacement of a random permutation is S/3
+    assert abs(np.abs(p0 - np.arange(S)).mean() / S - 1 / 3) < 0.03
+    assert orc.permutation(1, 0, 0, 0).size == 0 and list(orc.permutation(1, 0, 0, 1)) == [0]
+
+
+# ----------------------------------------------------------------- buffer arithmetic
+def test_buffer_size_example():
+    # Sec. III-B: 512 envs x 320x240 fp32 x 16 steps is about 2.5 GB
+    b = orc.buffer_image_bytes(512, 16, 1, 1, 240, 320, 4)
+    assert b == 2_516_582_400 and abs(b / 1e9 - 2.5) < 0.05
+    assert orc.buffer_image_bytes(4096, 16, 1, 1, 120, 160, 2) == b
+    assert abs(orc.buffer_image_bytes(16384, 32, 1, 1, 120, 160, 2) / 1e9 - 20.13) < 0.01
+
+
+def test_bf16_rne_matches_library_cast_and_ties():
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(2000).astype(np.float32) * 3,
+                        np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 2.0078125, 65504.0, 1e-40, 3.3e38,
+                                  np.inf, -np.inf], np.float32)])
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(orc.bf16_rne(x), want)
+    # exact ties go to the even mantissa: 1 + 2^-8 -> 1.0, 1 + 3*2^-8 -> 1 + 2^-6
+    assert orc.bf16_rne(np.array([1.00390625, 1.01171875], np.float32)).tolist() == [1.0, 1.015625]
+
+
+# ----------------------------------------------------------------- forward
+@pytest.mark.parametrize("net", [TINY, TINY_STEREO])
+def test_forward_matches_library_conv_and_linear(net):
+    b = _batch(net, 5, 1)
+    params = _params(net, 2)
+    mu, v = orc.forward(net, params, b["obs"], b["proprio"])
+    p, sl = torch_ref.unpack(net, params)
+    tmu, tv, _ = torch_ref.forward(net, p, sl, b["obs"], b["proprio"])
+    np.testing.assert_allclose(mu, tmu.detach().numpy(), rtol=1e-11, atol=1e-12)
+    if net["has_value_head"]:
+        np.testing.assert_allclose(v, tv.detach().numpy(), rtol=1e-11, atol=1e-12)
+
+
+def test_conv_padding_counts_inbounds_taps():
+    # one 3x3 stride-2 pad-1 conv of all-ones over an all-ones 5x6 image, exposed through an identity head:
+    # each output counts its in-bounds taps: 4 at the top-left corner, 6 on the top/left edges, 9 inside.
+    # Even width 6: the last output column reads columns 3..5, all inside.  Odd height 5: the last output
+    # row reads rows 3..5 and row 5 is outside, so it loses one tap row like the top edge does.
+    H, W = 5, 6
+    Ho, Wo = 3, 3
+    net = dict(n_views=1, in_c=1, in_h=H, in_w=W, proprio_dim=1, act_dim=Ho * Wo, conv_ch=[1], conv_k=3,
+               conv_stride=2, conv_pad=1, fc_dim=[], has_value_head=0)
+    sl = synth.param_slices(net)
+    p = np.zeros(orc.param_count(net))
+    p[sl["conv0.w"][0]:sl["conv0.w"][1]] = 1.0
+    a, b_, _ = sl["mu.w"]
+    p[a:b_] = np.eye(Ho * Wo, Ho * Wo + 1).reshape(-1)
+    mu, _ = orc.forward(net, p, np.ones((1, 1, 1, H, W), np.float32), np.zeros((1, 1)))
+    want = np.array([[4, 6, 6], [6, 9, 9], [4, 6, 6]], float)
+    np.testing.assert_array_equal(mu.reshape(Ho, Wo), want)
+
+
+def test_conv_single_tap_is_strided_shift():
+    H, W = 6, 8
+    net = dict(n_views=1, in_c=1, in_h=H, in_w=W, proprio_dim=1, act_dim=12, conv_ch=[1], conv_k=3,
+               conv_stride=2, conv_pad=1, fc_dim=[], has_value_head=0)
+    sl = synth.param_slices(net)
+    x = np.random.default_rng(0).uniform(0.5, 1.5, (1, 1, 1, H, W)).astype(np.float32)
+    for (u, v) in [(0, 0), (1, 1), (2, 1), (0, 2)]:
+        p = np.zeros(orc.param_count(net))
+        p[sl["conv0.w"][0] + u * 3 + v] = 1.0
+        a, b_, _ = sl["mu.w"]
+        p[a:b_] = np.eye(12, 13).reshape(-1)
+        mu, _ = orc.forward(net, p, x, np.zeros((1, 1)))
+        xp = np.pad(x[0, 0, 0].astype(np.float64), 1)
+        want = xp[u:u + 2 * 3:2, v:v + 2 * 4:2]
+        np.testing.assert_array_equal(mu.reshape(3, 4), want)
+
+
+# ----------------------------------------------------------------- loss closed forms
+def test_ratio_one_policy_loss_is_minus_mean_advantage():
+    rng = np.random.default_rng(4)
+    B, A = 64, 12
+    mu, act, logstd = rng.standard_normal((B, A)), rng.standard_normal((B, A)), rng.standard_normal(A) * 0.3
+    z = (act - mu) / np.exp(logstd)
+    logp = (-0.5 * z * z - logstd - 0.5 * math.log(2 * math.pi)).sum(1)
+    adv, v, ret = rng.standard_normal(B), rng.standard_normal(B), rng.standard_normal(B)
+    st, dmu, dv, dls = orc.ppo_loss(mu, v, logstd, act, logp, v, adv, ret, vf_coef=0.5)
+    assert abs(st["pi_loss"] + adv.mean()) < 1e-13
+    assert abs(st["approx_kl"]) < 1e-13 and st["clip_frac"] == 0
+    # d L_pi / d logp = -A/B  =>  d/dmu_j = -A/B * (a-mu)/sigma^2
+    np.testing.assert_allclose(dmu, (-adv / B)[:, None] * z / np.exp(logstd), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(dv, 0.5 * 2 * (v - ret) / B, rtol=1e-12)
+    assert abs(st["v_loss"] - ((v - ret) ** 2).mean()) < 1e-13
+
+
+def test_entropy_and_logprob_of_unit_gaussian():
+    for A, want in ((12, 17.027), (23, 32.636)):
+        z = np.zeros((1, A))
+        st, *_ = orc.ppo_loss(z, np.zeros(1), np.zeros(A), z, np.zeros(1), np.zeros(1), np.ones(1), np.zeros(1))
+        assert abs(st["entropy"] - A * 0.5 * math.log(2 * math.pi * math.e)) < 1e-12
+        assert abs(st["entropy"] - want) < 1e-3
+        # logp_old = 0 and a = mu: rho = exp(log N(0;0,I)) = (2 pi)^(-A/2); with A_hat = 1 and rho < 1-eps the
+        # unclipped term is the minimum so L_pi = -rho
+        assert abs(st["pi_loss"] + (2 * math.pi) ** (-A / 2)) < 1e-15
+
+
+def test_clipped_side_has_zero_policy_gradient_and_zero_adv():
+    B, A = 4, 3
+    rng = np.random.default_rng(5)
+    mu, act = rng.standard_normal((B, A)), rng.standard_normal((B, A))
+    logp = (-0.5 * (act - mu) ** 2 - 0.5 * math.log(2 * math.pi)).sum(1)
+    # rho = 1.5 with positive advantage, rho = 0.5 with negative advantage: both clipped -> no gradient;
+    # rho = 1.5 with negative advantage and rho = 0.5 with positive: unclipped -> gradient
+    logp_old = logp - np.log(np.array([1.5, 0.5, 1.5, 0.5]))
+    adv = np.array([1.0, -1.0, -1.0, 1.0])
+    st, dmu, _, _ = orc.ppo_loss(mu, np.zeros(B), np.zeros(A), act, logp_old, np.zeros(B), adv, np.zeros(B))
+    assert np.all(dmu[:2] == 0) and np.all(np.abs(dmu[2:]).sum(1) > 0)
+    assert abs(st["pi_loss"] - (-(1.2 * 1 + 0.8 * -1 + 1.5 * -1 + 0.5 * 1) / 4)) < 1e-12
+    assert st["clip_frac"] == 1.0
+    st, dmu, _, dls = orc.ppo_loss(mu, np.zeros(B), np.zeros(A), act, logp_old, np.zeros(B), np.zeros(B),
+                                   np.zeros(B))
+    assert st["pi_loss"] == 0 and np.all(dmu == 0) and np.all(dls == 0)
+
+
+def test_value_clipping_limits():
+    rng = np.random.default_rng(6)
+    B, A = 50, 2
+    v, vo, ret = rng.standard_normal(B), rng.standard_normal(B), rng.standard_normal(B)
+    z = np.zeros((B, A))
+    base, _, dv0, _ = orc.ppo_loss(z, v, np.zeros(A), z, np.zeros(B), vo, np.zeros(B), ret)
+    wide, _, dv1, _ = orc.ppo_loss(z, v, np.zeros(A), z, np.zeros(B), vo, np.zeros(B), ret, vclip_eps=1e9)
+    assert abs(wide["v_loss"] - base["v_loss"]) < 1e-13 and np.allclose(dv0, dv1, rtol=1e-12, atol=1e-15)
+    tight, _, dv2, _ = orc.ppo_loss(z, v, np.zeros(A), z, np.zeros(B), vo, np.zeros(B), ret, vclip_eps=0.2)
+    vc = vo + np.clip(v - vo, -0.2, 0.2)
+    assert abs(tight["v_loss"] - np.maximum((v - ret) ** 2, (vc - ret) ** 2).mean()) < 1e-13
+    assert tight["v_loss"] >= base["v_loss"]
+
+
+def test_mse_closed_forms():
+    rng = np.random.default_rng(7)
+    a = rng.standard_normal((6, 23))
+    st, d = orc.mse_loss(a, a)
+    assert st["total"] == 0 and np.all(d == 0)
+    b = a.copy()
+    b[2, 5] += 3.0
+    st, d = orc.mse_loss(b, a)
+    assert abs(st["total"] - 9.0 / (6 * 23)) < 1e-15
+    assert abs(d[2, 5] - 2 * 3.0 / (6 * 23)) < 1e-15 and np.count_nonzero(d) == 1
+
+
+# ----------------------------------------------------------------- gradients
+@pytest.mark.parametrize("vclip,ent", [(0.0, 0.0), (0.3, 0.01)])
+def test_ppo_gradients_match_autograd(vclip, ent):
+    net, B = TINY, 12
+    b, params = _batch(net, B, 10), _params(net, 11)
+    st, g = orc.ppo_loss_grad(net, params, b["obs"], b["proprio"], b["action"], b["logp_old"], b["v_old"],
+                              b["adv"], b["ret"], clip_eps=0.2, vclip_eps=vclip, vf_coef=0.5, ent_coef=ent)
+    p, sl = torch_ref.unpack(net, params)
+    mu, v, ls = torch_ref.forward(net, p, sl, b["obs"], b["proprio"])
+    loss, tst = torch_ref.ppo_loss(mu, v, ls, b["action"], b["logp_old"], b["v_old"], b["adv"], b["ret"], 0.2,
+                                   vclip, 0.5, ent)
+    loss.backward()
+    np.testing.assert_allclose(g, p.grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert abs(st["total"] - loss.item()) < 1e-12
+    for k in ("pi_loss", "v_loss", "entropy"):
+        assert abs(st[k] - tst[k]) < 1e-12
+    assert abs(st["grad_norm"] - np.linalg.norm(g)) < 1e-12
+    # both clip branches are exercised by this batch
+    assert 0 < st["clip_frac"] < 1
+
+
+def test_distill_gradients_match_autograd_shared_encoder():
+    net, B = TINY_STEREO, 9
+    b, params = _batch(net, B, 12), _params(net, 13)
+    st, g = orc.distill_loss_grad(net, params, b["obs"], b["proprio"], b["action"])
+    p, sl = torch_ref.unpack(net, params)
+    mu, _, _ = torch_ref.forward(net, p, sl, b["obs"], b["proprio"])
+    loss = ((mu - torch.as_tensor(b["action"])) ** 2).mean()
+    loss.backward()
+    np.testing.assert_allclose(g, p.grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert abs(st["total"] - loss.item()) < 1e-12
+
+
+def test_distill_view_swap_symmetry():
+    net, B = TINY_STEREO, 4
+    b, params = _batch(net, B, 14), _params(net, 15)
+    st0, _ = orc.distill_loss_grad(net, params, b["obs"], b["proprio"], b["action"])
+    sl = synth.param_slices(net)
+    a, e, shp = sl["fc0.w"]
+    flat = orc.flat_dim(net)
+    w = params[a:e].reshape(shp).copy()
+    w[:, :2 * flat] = np.concatenate([w[:, flat:2 * flat], w[:, :flat]], 1)
+    p2 = params.copy()
+    p2[a:e] = w.reshape(-1)
+    st1, _ = orc.distill_loss_grad(net, p2, b["obs"][:, ::-1].copy(), b["proprio"], b["action"])
+    assert abs(st0["total"] - st1["total"]) < 1e-13
+
+
+def test_gradients_central_finite_differences():
+    net, B = TINY, 6
+    b, params = _batch(net, B, 20), _params(net, 21)
+    args = (b["obs"], b["proprio"], b["action"], b["logp_old"], b["v_old"], b["adv"], b["ret"])
+    kw = dict(clip_eps=0.2, vclip_eps=0.3, vf_coef=0.5, ent_coef=0.01)
+    _, g = orc.ppo_loss_grad(net, params, *args, **kw)
+    rng = np.random.default_rng(22)
+    idx = rng.choice(params.size, 60, replace=False)
+    h, bad = 1e-6, 0
+    for i in idx:
+        pp, pm = params.copy(), params.copy()
+        pp[i] += h
+        pm[i] -= h
+        fd = (orc.ppo_loss_grad(net, pp, *args, **kw)[0]["total"] - orc.ppo_loss_grad(net, pm, *args, **kw)[0]["total"]) / (2 * h)
+        if abs(fd - g[i]) > 1e-6 * max(1.0, abs(g[i])):
+            bad += 1
+    # a kink (ReLU / clip / max) inside +-h is possible but rare
+    assert bad <= 1
+
+
+# ----------------------------------------------------------------- Adam
+def test_adam_closed_forms():
+    g = np.array([0.3, -2.0, 1e-3, 0.0, 5.0])
+    p, m, v = np.ones(5), np.zeros(5), np.zeros(5)
+    orc.adam_step(p, m, v, g, 1, lr=1e-2, eps=1e-8)
+    np.testing.assert_allclose(p, 1 - 1e-2 * g / (np.abs(g) + 1e-8), rtol=1e-13)
+    assert p[3] == 1.0
+    # a constant gradient gives the same step at every k (bias correction is exact)
+    prev = p.copy()
+    for k in range(2, 6):
+        orc.adam_step(p, m, v, g, k, lr=1e-2, eps=1e-8)
+        np.testing.assert_allclose(p - prev, -1e-2 * g / (np.abs(g) + 1e-8), rtol=1e-9, atol=1e-16)
+        prev = p.copy()
+
+
+def test_adam_matches_library_optimiser():
+    rng = np.random.default_rng(30)
+    n = 50
+    p, m, v = rng.standard_normal(n), np.zeros(n), np.zeros(n)
+    tp = torch.tensor(p.copy(), requires_grad=True)
+    opt = torch.optim.Adam([tp], lr=3e-4, betas=(0.9, 0.999), eps=1e-8)
+    for k in range(1, 8):
+        g = rng.standard_normal(n) * 10.0 ** rng.integers(-4, 2)
+        orc.adam_step(p, m, v, g, k)
+        tp.grad = torch.tensor(g)
+        opt.step()
+        np.testing.assert_allclose(p, tp.detach().numpy(), rtol=1e-12, atol=1e-15)
+
+
+# ----------------------------------------------------------------- composed update
+def test_update_loop_against_library_recomposition():
+    """The epochs x minibatches loop, re-composed from library pieces (autograd + optim.Adam)
+    around the oracle's own permutation."""
+    net = TINY
+    N, T, E, M = 6, 4, 2, 3
+    S = N * T
+    b, params = _batch(net, S, 40), _params(net, 41)
+    hp = dict(epochs=E, minibatches=M, clip_eps=0.2, vclip_eps=0.3, vf_coef=0.5, ent_coef=0.01, lr=1e-3, seed=99)
+    out = orc.ppo_update(net, params, np.zeros_like(params), np.zeros_like(params), 0, b["obs"], b["proprio"],
+                         b["action"], b["logp_old"], b["v_old"], b["adv"], b["ret"], hp, update_idx=2)
+    p, sl = torch_ref.unpack(net, params)
+    opt = torch.optim.Adam([p], lr=1e-3)
+    k = 0
+    for e in range(E):
+        perm = orc.permutation(99, 2, e, S)
+        for mb in range(M):
+            idx = perm[mb * (S // M):(mb + 1) * (S // M)]
+            opt.zero_grad()
+            mu, v, ls = torch_ref.forward(net, p, sl, b["obs"][idx], b["proprio"][idx])
+            loss, _ = torch_ref.ppo_loss(mu, v, ls, b["action"][idx], b["logp_old"][idx], b["v_old"][idx],
+                                         b["adv"][idx], b["ret"][idx], 0.2, 0.3, 0.5, 0.01)
+            loss.backward()
+            assert abs(out["stats"][k]["total"] - loss.item()) < 1e-10
+            opt.step()
+            k += 1
+    assert out["step"] == E * M
+    np.testing.assert_allclose(out["params"], p.detach().numpy(), rtol=1e-9, atol=1e-12)
+
+
+def test_param_counts_of_the_workloads():
+    want = [69_753, 1_156_975, 5_573_103, 10_786_455, 5_573_103]
+    for c, w in zip(configs.CONFIGS, want):
+        assert orc.param_count(c["net"]) == w == configs.param_count(c["net"])
+        assert sum(int(np.prod(s)) for _, s, _ in synth.param_layout(c["net"])) == w

@@ -1,0 +1,54 @@
+"""Independent fp64 re-statement of the actor-critic and its losses with PyTorch CPU
+library ops (conv2d, linear, autograd, optim.Adam).  Used only to pin the oracle."""
+import math
+
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+from paper_2509_16434_amd.synth import param_slices
+
+
+def unpack(net, params):
+    p = torch.as_tensor(np.asarray(params, np.float64)).clone().requires_grad_(True)
+    return p, {k: (a, b, s) for k, (a, b, s) in param_slices(net).items()}
+
+
+def forward(net, p, sl, obs, proprio):
+    def get(name):
+        a, b, s = sl[name]
+        return p[a:b].reshape(s)
+    obs = torch.as_tensor(np.asarray(obs, np.float64))
+    B = proprio.shape[0]
+    obs = obs.reshape(B, net["n_views"], net["in_c"], net["in_h"], net["in_w"])
+    feats = []
+    for v in range(net["n_views"]):
+        x = obs[:, v]
+        for i in range(len(net["conv_ch"])):
+            x = F.relu(F.conv2d(x, get(f"conv{i}.w"), get(f"conv{i}.b"), stride=net["conv_stride"],
+                                padding=net["conv_pad"]))
+        feats.append(x.reshape(B, -1))
+    x = torch.cat(feats + [torch.as_tensor(np.asarray(proprio, np.float64))], dim=1)
+    for i in range(len(net["fc_dim"])):
+        x = F.relu(F.linear(x, get(f"fc{i}.w"), get(f"fc{i}.b")))
+    mu = F.linear(x, get("mu.w"), get("mu.b"))
+    if net["has_value_head"]:
+        v = x @ get("v.w") + get("v.b")
+        return mu, v, get("logstd")
+    return mu, None, None
+
+
+def ppo_loss(mu, v, logstd, action, logp_old, v_old, adv, ret, clip_eps, vclip_eps, vf_coef, ent_coef):
+    t = lambda a: torch.as_tensor(np.asarray(a, np.float64))
+    action, logp_old, v_old, adv, ret = map(t, (action, logp_old, v_old, adv, ret))
+    dist = torch.distributions.Normal(mu, logstd.exp().expand_as(mu))
+    logp = dist.log_prob(action).sum(-1)
+    ratio = (logp - logp_old).exp()
+    l_pi = -torch.min(ratio * adv, ratio.clamp(1 - clip_eps, 1 + clip_eps) * adv).mean()
+    if vclip_eps > 0:
+        vc = v_old + (v - v_old).clamp(-vclip_eps, vclip_eps)
+        l_v = torch.max((v - ret) ** 2, (vc - ret) ** 2).mean()
+    else:
+        l_v = ((v - ret) ** 2).mean()
+    ent = dist.entropy().sum(-1).mean()
+    return l_pi + vf_coef * l_v - ent_coef * ent, dict(pi_loss=l_pi.item(), v_loss=l_v.item(), entropy=ent.item())
