@@ -1,0 +1,163 @@
+/*
+ * ppo_learner.h - C ABI of the MI355X PPO learner library (libppo_learner.so).
+ *
+ * One context = the dedicated learner GPU of the paper's disaggregated
+ * set-up (Sec. III-B, Fig. 2b, Algorithm 2): it owns the experience buffer
+ * of depth images + proprioception, the actor-critic parameters, their Adam
+ * state and all workspaces, and runs TrainPPO (Algorithm 2, last step) and
+ * the stereo-RGB distillation update (Sec. I, Sec. III-C) on them.
+ *
+ * Conventions
+ *  - Every function returns 0 or a negative PPO_E* code; ppo_last_error()
+ *    gives the text of the last failure on that context.  No exceptions and
+ *    no aborts cross this boundary.  Arguments are validated before any HIP
+ *    call is made.
+ *  - Pointers named d_* are DEVICE pointers owned by the caller; they must
+ *    stay valid until the work enqueued by the call has run on the context's
+ *    stream.  Pointers named h_* / host_* are HOST pointers.  The library
+ *    never frees or keeps caller memory.
+ *  - The library owns everything it allocates (in ppo_create) and releases it
+ *    in ppo_destroy.  ppo_buffer_write / ppo_gae / ppo_update /
+ *    distill_update allocate nothing.
+ *  - Work is enqueued on the HIP stream given to ppo_create (NULL = the
+ *    default stream).  Calls that fill host memory synchronise that stream;
+ *    all others return as soon as the work is enqueued.
+ *  - A flat sample index is s = t*num_envs + n.
+ *  - Canonical parameter order (fp32): for each conv layer W[Co][Ci][3][3],
+ *    b[Co]; for each hidden layer W[out][in], b[out] (the first hidden
+ *    layer's input is [flatten(view0) in (c,h,w) order, flatten(view1), ...,
+ *    proprio]); action head W[A][h], b[A]; and, with a value head, w_v[h],
+ *    b_v, logstd[A].
+ */
+#ifndef PPO_LEARNER_H
+#define PPO_LEARNER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PPO_OK 0
+#define PPO_EINVAL (-1) /* null pointer, NaN / out-of-range hyper-parameter            */
+#define PPO_ESHAPE (-2) /* geometry the kernels do not support, or sizes do not divide */
+#define PPO_ESTATE (-3) /* calls out of order (e.g. ppo_gae before all steps written)  */
+#define PPO_EHIP (-4)   /* a HIP runtime call failed                                   */
+#define PPO_ENOMEM (-5) /* device or host allocation failed                            */
+
+#define PPO_MAX_LAYERS 8
+
+typedef struct ppo_ctx ppo_ctx; /* opaque, library-owned */
+
+/* Network and buffer geometry.  The network is the feed-forward actor-critic
+ * of the benchmark configurations: a stack of 3x3 stride-2 pad-1 convolutions
+ * with ReLU on each view (shared weights), flatten, concatenate proprioception,
+ * ReLU hidden layers, a linear Gaussian-mean head and (optionally) a scalar
+ * value head with a state-independent log-std vector (cf. the CNN -> concat
+ * proprio -> MLP sketch of Sec. III-C, Fig. 3). */
+typedef struct {
+  int32_t num_envs, horizon;         /* N, T */
+  int32_t n_views, in_c, in_h, in_w; /* 1 x 1xHxW depth, or 2 x 3xHxW stereo RGB */
+  int32_t obs_dtype;                 /* element type the CALLER passes to ppo_buffer_write: 0 fp32, 1 bf16 */
+  int32_t proprio_dim, act_dim;      /* P (multiple of 8), A (<= 31) */
+  int32_t n_conv, conv_ch[PPO_MAX_LAYERS]; /* channel counts, each a multiple of 8 */
+  int32_t conv_k, conv_stride, conv_pad;   /* must be 3, 2, 1 */
+  int32_t n_fc, fc_dim[PPO_MAX_LAYERS];    /* hidden widths, each a multiple of 8, n_fc >= 1 */
+  int32_t has_value_head;            /* 1 actor-critic (PPO), 0 distillation student */
+  int32_t max_chunk;                 /* samples per forward/backward pass inside a minibatch; 0 = default */
+} ppo_net_desc;
+
+typedef struct {
+  float gamma, lambda;          /* used by ppo_gae only through its own arguments; kept for logging */
+  float clip_eps;               /* > 0 */
+  float vclip_eps;              /* <= 0: value clipping off */
+  float vf_coef, ent_coef;
+  float lr, beta1, beta2, adam_eps;
+  float max_grad_norm;          /* must be <= 0 (gradient clipping is not implemented) */
+  int32_t epochs, minibatches;  /* num_envs*horizon must be divisible by minibatches */
+  int32_t norm_adv;             /* must be 0 */
+  uint64_t seed;                /* permutation stream seed */
+} ppo_hparams;
+
+/* One record per optimiser step, in order epoch-major. */
+typedef struct {
+  float pi_loss, v_loss, entropy, approx_kl, clip_frac, grad_norm, total_loss;
+  int32_t nonfinite; /* 1 if the total loss was not finite */
+} ppo_mb_stats;
+
+/* Create a learner for `desc` on the current HIP device; all device memory is
+ * allocated here.  `hip_stream` is a hipStream_t (may be NULL).  Parameters
+ * start at zero: load them with ppo_set_params. */
+int ppo_create(ppo_ctx** out, const ppo_net_desc* desc, void* hip_stream);
+int ppo_destroy(ppo_ctx* ctx);
+const char* ppo_last_error(const ppo_ctx* ctx); /* ctx may be NULL: error of the last failed ppo_create */
+
+int64_t ppo_param_count(const ppo_ctx* ctx);
+/* Device bytes held by the experience buffer's image part (Sec. III-B sizing example). */
+int64_t ppo_buffer_image_bytes(const ppo_ctx* ctx);
+
+/* Parameters / gradients / optimiser state in canonical order, HOST fp32 arrays of
+ * n = ppo_param_count() elements.  All synchronise.  ppo_get_grads returns the gradient
+ * of the last minibatch processed.  Setting parameters or optimiser state is the
+ * checkpoint/resume path: after get -> (new ctx) set, the next update is bit-identical. */
+int ppo_set_params(ppo_ctx* ctx, const float* h_params, int64_t n);
+int ppo_get_params(ppo_ctx* ctx, float* h_params, int64_t n);
+int ppo_get_grads(ppo_ctx* ctx, float* h_grads, int64_t n);
+int ppo_set_opt_state(ppo_ctx* ctx, const float* h_m, const float* h_v, int64_t n, int64_t step, int64_t update_idx);
+int ppo_get_opt_state(ppo_ctx* ctx, float* h_m, float* h_v, int64_t n, int64_t* step, int64_t* update_idx);
+
+/* Append the step-t record of all N environments to the trajectory buffer
+ * (Algorithm 2: D <- D u {(obs, actions, rew, done)}), plus the behaviour
+ * policy's log-prob and value that PPO needs.  Device inputs:
+ *   d_obs     [N][n_views][in_c][in_h][in_w], fp32 or bf16 per desc.obs_dtype
+ *   d_proprio [N][P] fp32     d_action [N][A] fp32 (for distillation: the teacher's action)
+ *   d_logp, d_value, d_reward [N] fp32, d_done [N] uint8   (may all be NULL for a distillation student)
+ * Images are narrowed to bf16 (round to nearest even) and stored channel-last.
+ * t must be in [0, T); writing t = 0 starts a new rollout. */
+int ppo_buffer_write(ppo_ctx* ctx, int32_t t, const void* d_obs, const float* d_proprio, const float* d_action,
+                     const float* d_logp, const float* d_value, const float* d_reward, const uint8_t* d_done);
+
+/* Read back the step-t images as stored (bf16) into a DEVICE array in the caller's layout
+ * [N][n_views][in_c][in_h][in_w] (bf16).  Test hook for the write path. */
+int ppo_buffer_read_obs(ppo_ctx* ctx, int32_t t, void* d_obs_bf16);
+
+/* Generalised advantage estimation over the buffer, per environment, reverse in time:
+ *   delta_t = r_t + gamma (1-d_t) V_{t+1} - V_t,  A_t = delta_t + gamma lambda (1-d_t) A_{t+1},  R_t = A_t + V_t
+ * with V_T = d_last_value[n] (device, [N] fp32).  Needs all T steps written (else PPO_ESTATE). */
+int ppo_gae(ppo_ctx* ctx, const float* d_last_value, float gamma, float lambda);
+/* Copy advantages and returns ([T][N] fp32) to DEVICE arrays (either may be NULL). */
+int ppo_get_adv_ret(ppo_ctx* ctx, float* d_adv, float* d_ret);
+
+/* The permutation the next update will use for `epoch` (device kernel, result copied to
+ * HOST int32[N*T]); minibatch m is entries [m*B, (m+1)*B). */
+int ppo_permutation(ppo_ctx* ctx, uint64_t seed, uint64_t update_idx, uint64_t epoch, int32_t* h_perm);
+
+/* TrainPPO (Algorithm 2): epochs x minibatches of forward, clipped-surrogate + value +
+ * entropy loss, backward and one Adam step each.  Needs ppo_gae (else PPO_ESTATE).
+ * host_stats: HOST array [epochs*minibatches] or NULL (NULL = fully asynchronous). */
+int ppo_update(ppo_ctx* ctx, const ppo_hparams* hp, ppo_mb_stats* host_stats);
+
+/* Distillation update of a student (has_value_head = 0): MSE between the student's
+ * action and the teacher action stored in the buffer's action slot; no GAE needed. */
+int distill_update(ppo_ctx* ctx, const ppo_hparams* hp, ppo_mb_stats* host_stats);
+
+/* Forward only, on `count` buffer samples given by DEVICE int32 indices d_idx (NULL = samples
+ * 0..count-1): action means to d_mu [count][A] fp32 and values to d_v [count] fp32 (may be NULL). */
+int ppo_forward(ppo_ctx* ctx, const int32_t* d_idx, int64_t count, float* d_mu, float* d_v);
+
+/* Per-kernel-class timing (tracing aid, off by default).  ppo_profile(ctx, 1) clears the
+ * counters and starts bracketing every kernel class launched by the calls above with HIP events
+ * on the context's stream; ppo_profile(ctx, 0) stops.  ppo_profile_report synchronises and writes
+ * one text line per class into the HOST buffer: "name launches total_ms algorithmic_flops
+ * algorithmic_bytes"; returns the length written or a negative code. */
+int ppo_profile(ppo_ctx* ctx, int32_t enable);
+int64_t ppo_profile_report(ppo_ctx* ctx, char* h_buf, int64_t cap);
+
+/* Diagnostic: C[M][N] (fp32, host) = A[M][K] * B[N][K]^T with A, B given as HOST fp32 and
+ * narrowed to bf16, through the library's MFMA GEMM tile kernel.  K must be a multiple of 8. */
+int ppo_diag_gemm(int32_t M, int32_t N, int32_t K, const float* h_a, const float* h_b, float* h_c);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

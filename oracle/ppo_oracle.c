@@ -131,6 +131,21 @@ float orc_bf16_rne(float x) {
   float y; memcpy(&y, &u, 4); return y;
 }
 
+/* Operand-precision mode of the network arithmetic.
+ *   0: exact  - everything in fp64 (the definition).
+ *   1: bf16 operands - the arithmetic "bf16 matrix operands, wide accumulation": every STORED
+ *      activation (ReLU outputs, proprioception), every stored activation-gradient (loss
+ *      gradients w.r.t. the head outputs, each layer's masked input gradient) and the weight
+ *      matrices of every layer except the first convolution are rounded once to bf16 (RNE);
+ *      biases, log-std, the first convolution's weights, all sums and the loss stay wide.
+ * Mode 1 exists because the discrete decisions of the method (ReLU masks, which branch of the
+ * clipped surrogate / clipped value loss is active) must be taken in the same precision on both
+ * sides of a comparison; it changes no formula. */
+static int g_quant = 0;
+void orc_set_quant(int32_t mode) { g_quant = mode; }
+int32_t orc_get_quant(void) { return g_quant; }
+static double q(double x) { return g_quant ? (double)orc_bf16_rne((float)x) : x; }
+
 /* ------------------------------------------------------------------ */
 /* GAE (Schulman et al., generalized advantage estimation), per env,   */
 /* reverse in time.  The done flag of step t belongs to the transition */
@@ -304,23 +319,22 @@ static void sample_forward(const orc_net *n, const geom *g, const double *P, con
                            const double *proprio, acts *a) {
   for (int v = 0; v < n->n_views; ++v) {
     int64_t px = (int64_t)g->c[0] * g->h[0] * g->w[0];
-    for (int64_t i = 0; i < px; ++i) a->conv[v][0][i] = (double)obs[v * px + i];
+    for (int64_t i = 0; i < px; ++i) a->conv[v][0][i] = q((double)obs[v * px + i]);  /* the stored image */
     for (int l = 0; l < n->n_conv; ++l) {
       conv_fwd(a->conv[v][l], g->c[l], g->h[l], g->w[l], P + g->convW[l], P + g->convB[l],
                g->c[l + 1], n->conv_k, n->conv_stride, n->conv_pad, a->conv[v][l + 1], g->h[l + 1],
                g->w[l + 1]);
       int64_t m = (int64_t)g->c[l + 1] * g->h[l + 1] * g->w[l + 1];
       for (int64_t i = 0; i < m; ++i)
-        if (!(a->conv[v][l + 1][i] > 0.0)) a->conv[v][l + 1][i] = 0.0;
+        a->conv[v][l + 1][i] = (a->conv[v][l + 1][i] > 0.0) ? q(a->conv[v][l + 1][i]) : 0.0;
     }
     memcpy(a->feat + (size_t)v * g->flat, a->conv[v][n->n_conv], sizeof(double) * (size_t)g->flat);
   }
-  for (int i = 0; i < n->proprio_dim; ++i) a->feat[n->n_views * g->flat + i] = proprio[i];
+  for (int i = 0; i < n->proprio_dim; ++i) a->feat[n->n_views * g->flat + i] = q(proprio[i]);
   const double *x = a->feat;
   for (int l = 0; l < n->n_fc; ++l) {
     lin_fwd(x, g->fc_in[l], P + g->fcW[l], P + g->fcB[l], g->fc_out[l], a->fc[l]);
-    for (int i = 0; i < g->fc_out[l]; ++i)
-      if (!(a->fc[l][i] > 0.0)) a->fc[l][i] = 0.0;
+    for (int i = 0; i < g->fc_out[l]; ++i) a->fc[l][i] = (a->fc[l][i] > 0.0) ? q(a->fc[l][i]) : 0.0;
     x = a->fc[l];
   }
   lin_fwd(x, g->hid, P + g->muW, P + g->muB, n->act_dim, a->mu);
@@ -339,8 +353,7 @@ static void sample_backward(const orc_net *n, const geom *g, const double *P, ac
   if (n->has_value_head) lin_bwd(x, g->hid, P + g->vW, 1, &dv, G + g->vW, G + g->vB, dx);
   for (int l = n->n_fc - 1; l >= 0; --l) {
     double *dy = a->dfc[l];
-    for (int i = 0; i < g->fc_out[l]; ++i)
-      if (!(a->fc[l][i] > 0.0)) dy[i] = 0.0;
+    for (int i = 0; i < g->fc_out[l]; ++i) dy[i] = (a->fc[l][i] > 0.0) ? q(dy[i]) : 0.0;
     const double *xin = l ? a->fc[l - 1] : a->feat;
     double *dxin = l ? a->dfc[l - 1] : a->dfeat;
     memset(dxin, 0, sizeof(double) * (size_t)g->fc_in[l]);
@@ -352,7 +365,7 @@ static void sample_backward(const orc_net *n, const geom *g, const double *P, ac
     for (int l = L - 1; l >= 0; --l) {
       int64_t m = (int64_t)g->c[l + 1] * g->h[l + 1] * g->w[l + 1];
       for (int64_t i = 0; i < m; ++i)
-        if (!(a->conv[v][l + 1][i] > 0.0)) a->dconv[l + 1][i] = 0.0;
+        a->dconv[l + 1][i] = (a->conv[v][l + 1][i] > 0.0) ? q(a->dconv[l + 1][i]) : 0.0;
       double *dxl = l ? a->dconv[l] : NULL;
       if (dxl) memset(dxl, 0, sizeof(double) * (size_t)g->c[l] * g->h[l] * g->w[l]);
       conv_bwd(a->conv[v][l], g->c[l], g->h[l], g->w[l], P + g->convW[l], g->c[l + 1], n->conv_k,
@@ -362,10 +375,27 @@ static void sample_backward(const orc_net *n, const geom *g, const double *P, ac
   }
 }
 
+/* Copy of the parameters as the layers use them: in bf16-operand mode the weight matrices of
+ * every layer but the first convolution are rounded to bf16; everything else is unchanged. */
+static double *operand_params(const orc_net *n, const geom *g, const double *params) {
+  double *P = (double *)malloc(sizeof(double) * (size_t)g->total);
+  memcpy(P, params, sizeof(double) * (size_t)g->total);
+  if (!g_quant) return P;
+  for (int l = 1; l < n->n_conv; ++l)
+    for (int64_t i = g->convW[l]; i < g->convB[l]; ++i) P[i] = q(P[i]);
+  for (int l = 0; l < n->n_fc; ++l)
+    for (int64_t i = g->fcW[l]; i < g->fcB[l]; ++i) P[i] = q(P[i]);
+  for (int64_t i = g->muW; i < g->muB; ++i) P[i] = q(P[i]);
+  if (n->has_value_head)
+    for (int64_t i = g->vW; i < g->vB; ++i) P[i] = q(P[i]);
+  return P;
+}
+
 /* Network outputs for B samples: mu [B][A], v [B] (v untouched without a value head). */
-void orc_forward(const orc_net *n, const double *params, int64_t B, const float *obs,
+void orc_forward(const orc_net *n, const double *params_in, int64_t B, const float *obs,
                  const double *proprio, double *mu, double *v) {
   geom g; make_geom(n, &g);
+  double *params = operand_params(n, &g, params_in);
   int64_t obs_sz = (int64_t)n->n_views * g.c[0] * g.h[0] * g.w[0];
 #pragma omp parallel
   {
@@ -378,6 +408,7 @@ void orc_forward(const orc_net *n, const double *params, int64_t B, const float 
     }
     acts_free(n, &a);
   }
+  free(params);
 }
 
 /* ------------------------------------------------------------------ */
@@ -453,7 +484,7 @@ void orc_mse_loss(int64_t B, int32_t A, const double *pred, const double *target
 }
 
 /* forward all samples, evaluate loss on the outputs, backward all samples */
-static void minibatch_grad(const orc_net *n, const double *params, int64_t B, const float *obs,
+static void minibatch_grad(const orc_net *n, const double *params_in, int64_t B, const float *obs,
                            const double *proprio, const double *action, const double *logp_old,
                            const double *v_old, const double *adv, const double *ret,
                            const orc_loss_cfg *cfg, int distill, double *grads, double *stats) {
@@ -464,12 +495,16 @@ static void minibatch_grad(const orc_net *n, const double *params, int64_t B, co
   double *v = (double *)calloc((size_t)B, sizeof(double));
   double *dmu = (double *)malloc(sizeof(double) * (size_t)B * A);
   double *dv = (double *)calloc((size_t)B, sizeof(double));
-  orc_forward(n, params, B, obs, proprio, mu, v);
+  double *params = operand_params(n, &g, params_in);
+  orc_forward(n, params_in, B, obs, proprio, mu, v);
   memset(grads, 0, sizeof(double) * (size_t)g.total);
   if (distill) orc_mse_loss(B, A, mu, action, stats, dmu);
   else
     orc_ppo_loss(B, A, mu, v, params + g.logstd, action, logp_old, v_old, adv, ret, cfg, stats,
                  dmu, dv, grads + g.logstd);
+  /* the loss gradients w.r.t. the head outputs are stored activations-gradients */
+  for (int64_t i = 0; i < B * A; ++i) dmu[i] = q(dmu[i]);
+  for (int64_t i = 0; i < B; ++i) dv[i] = q(dv[i]);
   int nth = 1;
 #ifdef _OPENMP
   nth = omp_get_max_threads();
@@ -495,7 +530,7 @@ static void minibatch_grad(const orc_net *n, const double *params, int64_t B, co
   double gn = 0;
   for (int64_t i = 0; i < g.total; ++i) gn += grads[i] * grads[i];
   stats[ST_GNORM] = sqrt(gn);
-  free(tg); free(mu); free(v); free(dmu); free(dv);
+  free(tg); free(mu); free(v); free(dmu); free(dv); free(params);
 }
 
 /* Loss, stats and parameter gradients of the PPO objective on one minibatch. */

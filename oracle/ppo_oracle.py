@@ -263,5 +263,29 @@ def distill_update(net, params, m, v, step, obs, proprio, teacher, hp, update_id
     return _update("distill", net, params, m, v, step, obs, proprio, teacher, None, hp, update_idx)
 
 
+def set_quant(mode: int) -> None:
+    """0: exact fp64 (the definition); 1: bf16 operands (stored activations, activation gradients
+    and MFMA-layer weights rounded to bf16, wide accumulation)."""
+    lib().orc_set_quant(C.c_int32(int(mode)))
+
+
+def get_quant() -> int:
+    return int(lib().orc_get_quant())
+
+
+class quant:
+    """Context manager: `with quant(1): ...`."""
+
+    def __init__(self, mode):
+        self.mode = mode
+
+    def __enter__(self):
+        self.prev = get_quant()
+        set_quant(self.mode)
+
+    def __exit__(self, *a):
+        set_quant(self.prev)
+
+
 def num_threads() -> int:
     return int(lib().orc_num_threads())

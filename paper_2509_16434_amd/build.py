@@ -1,0 +1,44 @@
+"""Builds libppo_learner.so (HIP, gfx950) in-tree with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB = os.path.join(_HERE, "libppo_learner.so")
+SRC = os.path.join(_HERE, "csrc", "ppo_learner.hip")
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def sources():
+    d = os.path.join(_HERE, "csrc")
+    return [os.path.join(d, f) for f in sorted(os.listdir(d))] + [
+        os.path.join(os.path.dirname(_HERE), "include", "ppo_learner.h")]
+
+
+def stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(s) > t for s in sources())
+
+
+def build_lib(force: bool = True, verbose: bool = False) -> str:
+    """Compile the library; with force=False only when a source is newer than the .so."""
+    if force or stale():
+        cmd = [HIPCC] + FLAGS + ["-o", LIB, SRC]
+        if verbose:
+            print(" ".join(cmd))
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + err)
+        if verbose and err.strip():
+            print(err)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_lib(True, True))

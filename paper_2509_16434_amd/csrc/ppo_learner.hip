@@ -1,0 +1,913 @@
+// Host side of libppo_learner.so: context, argument validation, parameter layout, and the
+// launch sequences of ppo_buffer_write / ppo_gae / ppo_update / distill_update.
+// Every step of the learner's path runs in the HIP kernels of gemm.hip.h and mem_kernels.hip.h.
+#include "../../include/ppo_learner.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <map>
+#include <string>
+#include <vector>
+
+#include "gemm.hip.h"
+#include "mem_kernels.hip.h"
+
+static_assert(sizeof(DevStats) == sizeof(ppo_mb_stats), "device and host statistics records must match");
+
+namespace {
+
+thread_local std::string g_create_error;
+
+struct Ctx {
+  ppo_net_desc d;
+  hipStream_t stream = nullptr;
+  std::string err;
+  // geometry
+  int N = 0, T = 0, S = 0, V = 1, A = 0, P = 0, NH = 0, nconv = 0, nfc = 0;
+  int cC[PPO_MAX_LAYERS + 1], cH[PPO_MAX_LAYERS + 1], cW[PPO_MAX_LAYERS + 1];
+  int fin[PPO_MAX_LAYERS], fout[PPO_MAX_LAYERS];
+  int flat = 0, feat_ld = 0, hid = 0;
+  int64_t img_elems = 0;  // per view
+  // internal parameter layout (fp32 master, bf16 shadow share the offsets)
+  int64_t convW[PPO_MAX_LAYERS], convB[PPO_MAX_LAYERS], fcW[PPO_MAX_LAYERS], fcB[PPO_MAX_LAYERS];
+  int64_t headW = 0, headB = 0, logstd = -1, total = 0;
+  std::vector<int32_t> i2c;  // internal index -> canonical index
+  // device: parameters
+  float *p = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
+  bf16_t* shadow = nullptr;
+  bf16_t* wd[PPO_MAX_LAYERS][4];  // transposed-conv weights per parity class (conv layers >= 1)
+  bf16_t* fcT[PPO_MAX_LAYERS];    // [in][out]
+  bf16_t* headT = nullptr;        // [hid][32]
+  // device: rollout buffer (SoA)
+  bf16_t *obs = nullptr, *proprio = nullptr;
+  float *action = nullptr, *logp = nullptr, *value = nullptr, *reward = nullptr, *adv = nullptr, *ret = nullptr;
+  uint8_t* done = nullptr;
+  // device: permutation
+  int32_t *perm = nullptr, *ptmp = nullptr, *phist = nullptr, *pstart = nullptr, *pcursor = nullptr;
+  int nb = 1, shift = 64;
+  // device: workspaces for one chunk of CH samples
+  int CH = 0;
+  bf16_t* act[PPO_MAX_LAYERS];    // conv outputs of layers 0..nconv-2, [CH*V][H][W][C]
+  bf16_t* feat = nullptr;         // [CH][feat_ld]: last conv output per view, then proprio
+  bf16_t* fcact[PPO_MAX_LAYERS];  // [CH][fout]
+  float* headout = nullptr;       // [CH][32]
+  bf16_t* dhead = nullptr;        // [CH][32]
+  bf16_t* gbuf[2] = {nullptr, nullptr};
+  float *partial = nullptr, *bias_partial = nullptr;
+  int64_t partial_elems = 0, bias_partial_elems = 0;
+  float *stat_part = nullptr, *dls_part = nullptr, *sq_part = nullptr;
+  int max_loss_blocks = 0, adam_blocks = 0;
+  DevStats* dstats = nullptr;
+  int max_steps = 4096;
+  // state
+  std::vector<char> written;
+  bool gae_done = false;
+  int64_t step = 0, update_idx = 0;
+  std::vector<void*> allocs;
+  // optional per-kernel-class timing with HIP events on the context's stream
+  bool prof_on = false;
+  struct ProfClass { std::string name; int64_t launches = 0; double flops = 0, bytes = 0; };
+  struct ProfRec { int cls; hipEvent_t a, b; };
+  std::vector<ProfClass> prof_cls;
+  std::map<std::string, int> prof_idx;
+  std::vector<ProfRec> prof_recs;
+  std::vector<hipEvent_t> prof_pool;
+};
+
+// Brackets the launches made during its lifetime with a pair of events (when profiling is on) and
+// books the algorithmic FLOPs / bytes of the work under `name`.
+struct ProfScope {
+  Ctx* c; int rec = -1;
+  ProfScope(Ctx* c_, const std::string& name, double flops, double bytes) : c(c_) {
+    if (!c->prof_on) return;
+    auto it = c->prof_idx.find(name);
+    int id;
+    if (it == c->prof_idx.end()) { id = (int)c->prof_cls.size(); c->prof_idx[name] = id; Ctx::ProfClass pc; pc.name = name; c->prof_cls.push_back(pc); }
+    else id = it->second;
+    c->prof_cls[id].launches += 1; c->prof_cls[id].flops += flops; c->prof_cls[id].bytes += bytes;
+    hipEvent_t ev[2];
+    for (int i = 0; i < 2; ++i) {
+      if (!c->prof_pool.empty()) { ev[i] = c->prof_pool.back(); c->prof_pool.pop_back(); }
+      else if (hipEventCreate(&ev[i]) != hipSuccess) return;
+    }
+    Ctx::ProfRec r; r.cls = id; r.a = ev[0]; r.b = ev[1];
+    (void)hipEventRecord(r.a, c->stream);
+    rec = (int)c->prof_recs.size();
+    c->prof_recs.push_back(r);
+  }
+  ~ProfScope() { if (rec >= 0) (void)hipEventRecord(c->prof_recs[rec].b, c->stream); }
+};
+
+int fail(Ctx* c, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf; else g_create_error = buf;
+  return code;
+}
+
+#define HIPCHK(c, call)                                                                          \
+  do {                                                                                           \
+    hipError_t e_ = (call);                                                                      \
+    if (e_ != hipSuccess) return fail(c, PPO_EHIP, "%s failed: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+#define LAUNCHCHK(c, what)                                                                              \
+  do {                                                                                                  \
+    hipError_t e_ = hipGetLastError();                                                                  \
+    if (e_ != hipSuccess) return fail(c, PPO_EHIP, "launch of %s failed: %s", what, hipGetErrorString(e_)); \
+  } while (0)
+
+template <typename T>
+int dalloc(Ctx* c, T** out, int64_t n) {
+  void* p = nullptr;
+  size_t bytes = (size_t)(n > 0 ? n : 1) * sizeof(T);
+  hipError_t e = hipMalloc(&p, bytes);
+  if (e != hipSuccess) return fail(c, e == hipErrorOutOfMemory ? PPO_ENOMEM : PPO_EHIP, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+  c->allocs.push_back(p);
+  *out = (T*)p;
+  return PPO_OK;
+}
+#define DALLOC(c, ptr, n)                          \
+  do {                                             \
+    int rc_ = dalloc(c, &(ptr), (int64_t)(n));     \
+    if (rc_ != PPO_OK) return rc_;                 \
+  } while (0)
+
+inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// ---------------------------------------------------------------- validation (no HIP calls)
+int validate_desc(const ppo_net_desc* d) {
+  if (!d) return fail(nullptr, PPO_EINVAL, "desc is NULL");
+  if (d->num_envs < 1 || d->horizon < 1) return fail(nullptr, PPO_ESHAPE, "num_envs and horizon must be >= 1");
+  if ((int64_t)d->num_envs * d->horizon > (1 << 30)) return fail(nullptr, PPO_ESHAPE, "num_envs*horizon too large");
+  if (d->n_views < 1 || d->n_views > 4) return fail(nullptr, PPO_ESHAPE, "n_views must be 1..4");
+  if (d->in_c != 1 && d->in_c != 3) return fail(nullptr, PPO_ESHAPE, "in_c must be 1 (depth) or 3 (RGB)");
+  if (d->in_h < 2 || d->in_w < 2 || d->in_h > 4096 || d->in_w > 4096) return fail(nullptr, PPO_ESHAPE, "image size out of range");
+  if (d->obs_dtype != 0 && d->obs_dtype != 1) return fail(nullptr, PPO_EINVAL, "obs_dtype must be 0 (fp32) or 1 (bf16)");
+  if (d->proprio_dim < 8 || d->proprio_dim % 8) return fail(nullptr, PPO_ESHAPE, "proprio_dim must be a positive multiple of 8");
+  if (d->act_dim < 1 || d->act_dim > 31) return fail(nullptr, PPO_ESHAPE, "act_dim must be 1..31");
+  if (d->conv_k != 3 || d->conv_stride != 2 || d->conv_pad != 1) return fail(nullptr, PPO_ESHAPE, "only 3x3 stride-2 pad-1 convolutions are supported");
+  if (d->n_conv < 2 || d->n_conv > PPO_MAX_LAYERS) return fail(nullptr, PPO_ESHAPE, "n_conv must be 2..%d", PPO_MAX_LAYERS);
+  for (int i = 0; i < d->n_conv; ++i)
+    if (d->conv_ch[i] < 8 || d->conv_ch[i] % 8 || d->conv_ch[i] > 1024) return fail(nullptr, PPO_ESHAPE, "conv_ch[%d] must be a multiple of 8 in 8..1024", i);
+  if (d->conv_ch[0] * (9 * d->in_c + 1) > 1024) return fail(nullptr, PPO_ESHAPE, "conv_ch[0]*(9*in_c+1) must be <= 1024");
+  if (d->n_fc < 1 || d->n_fc > PPO_MAX_LAYERS) return fail(nullptr, PPO_ESHAPE, "n_fc must be 1..%d", PPO_MAX_LAYERS);
+  for (int i = 0; i < d->n_fc; ++i)
+    if (d->fc_dim[i] < 8 || d->fc_dim[i] % 8 || d->fc_dim[i] > 16384) return fail(nullptr, PPO_ESHAPE, "fc_dim[%d] must be a multiple of 8 in 8..16384", i);
+  if (d->has_value_head != 0 && d->has_value_head != 1) return fail(nullptr, PPO_EINVAL, "has_value_head must be 0 or 1");
+  if (d->max_chunk < 0) return fail(nullptr, PPO_EINVAL, "max_chunk must be >= 0");
+  return PPO_OK;
+}
+
+int validate_hp(Ctx* c, const ppo_hparams* hp, bool distill) {
+  if (!hp) return fail(c, PPO_EINVAL, "hparams is NULL");
+  const float f[] = {hp->clip_eps, hp->vclip_eps, hp->vf_coef, hp->ent_coef, hp->lr, hp->beta1, hp->beta2, hp->adam_eps, hp->max_grad_norm};
+  for (float x : f) if (!isfinite(x)) return fail(c, PPO_EINVAL, "non-finite hyper-parameter");
+  if (!distill && !(hp->clip_eps > 0.f)) return fail(c, PPO_EINVAL, "clip_eps must be > 0");
+  if (!(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) || !(hp->adam_eps > 0.f))
+    return fail(c, PPO_EINVAL, "Adam hyper-parameters out of range");
+  if (hp->max_grad_norm > 0.f) return fail(c, PPO_EINVAL, "gradient-norm clipping is not implemented (max_grad_norm must be <= 0)");
+  if (hp->norm_adv != 0) return fail(c, PPO_EINVAL, "advantage normalisation is not implemented (norm_adv must be 0)");
+  if (hp->epochs < 1 || hp->minibatches < 1) return fail(c, PPO_EINVAL, "epochs and minibatches must be >= 1");
+  if (c->S % hp->minibatches) return fail(c, PPO_ESHAPE, "num_envs*horizon = %d is not divisible by minibatches = %d", c->S, hp->minibatches);
+  if ((int64_t)hp->epochs * hp->minibatches > c->max_steps) return fail(c, PPO_ESHAPE, "epochs*minibatches exceeds %d", c->max_steps);
+  return PPO_OK;
+}
+
+// ---------------------------------------------------------------- geometry and parameter layout
+void build_geometry(Ctx* c) {
+  const ppo_net_desc& d = c->d;
+  c->N = d.num_envs; c->T = d.horizon; c->S = c->N * c->T; c->V = d.n_views; c->A = d.act_dim; c->P = d.proprio_dim;
+  c->NH = d.act_dim + (d.has_value_head ? 1 : 0);
+  c->nconv = d.n_conv; c->nfc = d.n_fc;
+  c->cC[0] = d.in_c; c->cH[0] = d.in_h; c->cW[0] = d.in_w;
+  for (int l = 0; l < c->nconv; ++l) {
+    c->cC[l + 1] = d.conv_ch[l];
+    c->cH[l + 1] = (c->cH[l] + 2 - 3) / 2 + 1;
+    c->cW[l + 1] = (c->cW[l] + 2 - 3) / 2 + 1;
+  }
+  c->img_elems = (int64_t)d.in_c * d.in_h * d.in_w;
+  c->flat = c->cC[c->nconv] * c->cH[c->nconv] * c->cW[c->nconv];
+  c->feat_ld = c->V * c->flat + c->P;
+  int in = c->feat_ld;
+  for (int l = 0; l < c->nfc; ++l) { c->fin[l] = in; c->fout[l] = d.fc_dim[l]; in = d.fc_dim[l]; }
+  c->hid = in;
+
+  // canonical offsets
+  std::vector<int64_t> cConvW(c->nconv), cConvB(c->nconv), cFcW(c->nfc), cFcB(c->nfc);
+  int64_t off = 0;
+  for (int l = 0; l < c->nconv; ++l) { cConvW[l] = off; off += (int64_t)c->cC[l + 1] * c->cC[l] * 9; cConvB[l] = off; off += c->cC[l + 1]; }
+  for (int l = 0; l < c->nfc; ++l) { cFcW[l] = off; off += (int64_t)c->fin[l] * c->fout[l]; cFcB[l] = off; off += c->fout[l]; }
+  int64_t cMuW = off; off += (int64_t)c->A * c->hid;
+  int64_t cMuB = off; off += c->A;
+  int64_t cVW = -1, cVB = -1, cLs = -1;
+  if (d.has_value_head) { cVW = off; off += c->hid; cVB = off; off += 1; cLs = off; off += c->A; }
+  c->total = off;
+  c->i2c.assign((size_t)off, 0);
+
+  // internal layout: conv W as [Co][(u*3+v)*Ci + ci]; first hidden layer's columns follow the
+  // channel-last flatten (view, pixel, channel); heads stacked as one [NH][hid] matrix.
+  int64_t io = 0;
+  for (int l = 0; l < c->nconv; ++l) {
+    int Co = c->cC[l + 1], Ci = c->cC[l];
+    c->convW[l] = io;
+    for (int co = 0; co < Co; ++co)
+      for (int u = 0; u < 3; ++u)
+        for (int v = 0; v < 3; ++v)
+          for (int ci = 0; ci < Ci; ++ci)
+            c->i2c[(size_t)(io + (int64_t)co * 9 * Ci + (u * 3 + v) * Ci + ci)] = (int32_t)(cConvW[l] + (((int64_t)co * Ci + ci) * 3 + u) * 3 + v);
+    io += (int64_t)Co * 9 * Ci;
+    c->convB[l] = io;
+    for (int co = 0; co < Co; ++co) c->i2c[(size_t)(io + co)] = (int32_t)(cConvB[l] + co);
+    io += Co;
+  }
+  const int CL = c->cC[c->nconv], HWL = c->cH[c->nconv] * c->cW[c->nconv];
+  for (int l = 0; l < c->nfc; ++l) {
+    c->fcW[l] = io;
+    for (int o = 0; o < c->fout[l]; ++o)
+      for (int j = 0; j < c->fin[l]; ++j) {
+        int cj = j;
+        if (l == 0 && j < c->V * c->flat) {
+          int v = j / c->flat, r = j - v * c->flat, pix = r / CL, ch = r - pix * CL;
+          cj = v * c->flat + ch * HWL + pix;
+        }
+        c->i2c[(size_t)(io + (int64_t)o * c->fin[l] + j)] = (int32_t)(cFcW[l] + (int64_t)o * c->fin[l] + cj);
+      }
+    io += (int64_t)c->fin[l] * c->fout[l];
+    c->fcB[l] = io;
+    for (int o = 0; o < c->fout[l]; ++o) c->i2c[(size_t)(io + o)] = (int32_t)(cFcB[l] + o);
+    io += c->fout[l];
+  }
+  c->headW = io;
+  for (int64_t i = 0; i < (int64_t)c->A * c->hid; ++i) c->i2c[(size_t)(io + i)] = (int32_t)(cMuW + i);
+  io += (int64_t)c->A * c->hid;
+  if (d.has_value_head) { for (int i = 0; i < c->hid; ++i) c->i2c[(size_t)(io + i)] = (int32_t)(cVW + i); io += c->hid; }
+  c->headB = io;
+  for (int i = 0; i < c->A; ++i) c->i2c[(size_t)(io + i)] = (int32_t)(cMuB + i);
+  io += c->A;
+  if (d.has_value_head) {
+    c->i2c[(size_t)io] = (int32_t)cVB; io += 1;
+    c->logstd = io;
+    for (int i = 0; i < c->A; ++i) c->i2c[(size_t)(io + i)] = (int32_t)(cLs + i);
+    io += c->A;
+  }
+}
+
+// number of input pixels of parity `par` along an axis of length n
+inline int class_len(int n, int par) { return (n - par + 1) / 2; }
+
+// ---------------------------------------------------------------- launch helpers
+template <class AL, class EP>
+int launch_gemm(Ctx* c, const AL& al, int M, const bf16_t* Bm, int64_t ldb, int N, int K, const EP& ep, const std::string& name, double abytes) {
+  if (M <= 0) return PPO_OK;
+  const char* what = name.c_str();
+  ProfScope ps(c, name, 2.0 * M * (double)N * K, abytes);
+  dim3 blk(256);
+  if (N > 64) {
+    dim3 grid(cdiv(M, 128), cdiv(N, 128));
+    hipLaunchKernelGGL((k_gemm<128, 128, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, K, ep);
+  } else if (N > 32) {
+    dim3 grid(cdiv(M, 128), 1);
+    hipLaunchKernelGGL((k_gemm<128, 64, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, K, ep);
+  } else {
+    dim3 grid(cdiv(M, 128), 1);
+    hipLaunchKernelGGL((k_gemm<128, 32, 4, 1, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, K, ep);
+  }
+  LAUNCHCHK(c, what);
+  return PPO_OK;
+}
+
+ImgAddr plain_rows(const bf16_t* base, int64_t ld) { ImgAddr a; a.base = base; a.idx = nullptr; a.stride_b = ld; a.stride_v = 0; a.V = 1; return a; }
+
+// G[Nn][Kk] (+)= Dy^T * A over M rows, plus optional bias gradient gb[Nn].
+template <class DL, class AL>
+int launch_wgrad(Ctx* c, const DL& dl, const AL& al, int Nn, int Kk, int M, float* gw, float* gb, bool accumulate, const std::string& name, double abytes) {
+  if (M <= 0) return PPO_OK;
+  const char* what = name.c_str();
+  const int tiles = cdiv(Kk, 64) * cdiv(Nn, 64);
+  int splits = cdiv(1536, tiles);
+  const int max_by_rows = cdiv(M, 256);
+  if (splits > max_by_rows) splits = max_by_rows;
+  const int64_t per = (int64_t)Nn * Kk;
+  if ((int64_t)splits * per > c->partial_elems) splits = (int)(c->partial_elems / per);
+  if ((int64_t)splits * Nn > c->bias_partial_elems) splits = (int)(c->bias_partial_elems / Nn);
+  if (splits < 1) return fail(c, PPO_ENOMEM, "weight-gradient workspace too small for %s", what);
+  int rows = cdiv(M, splits);
+  rows = (rows + 31) / 32 * 32;
+  splits = cdiv(M, rows);
+  dim3 grid(cdiv(Kk, 64), cdiv(Nn, 64), splits);
+  {
+    ProfScope ps(c, name, 2.0 * M * (double)Nn * Kk, abytes);
+    hipLaunchKernelGGL((k_wgrad<DL, AL>), grid, dim3(256), 0, c->stream, dl, al, Nn, Kk, M, rows, c->partial, gb ? c->bias_partial : nullptr);
+    LAUNCHCHK(c, what);
+  }
+  ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)splits + 1.0) * (double)per);
+  hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 256)), dim3(256), 0, c->stream, c->partial, splits, per, gw, accumulate ? 1 : 0);
+  LAUNCHCHK(c, what);
+  if (gb) {
+    hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(Nn, 256)), dim3(256), 0, c->stream, c->bias_partial, splits, (int64_t)Nn, gb, accumulate ? 1 : 0);
+    LAUNCHCHK(c, what);
+  }
+  return PPO_OK;
+}
+
+// bf16 copies of the parameters in the layouts the backward GEMMs read
+int repack_weights(Ctx* c) {
+  ProfScope ps(c, "weight_repack", 0.0, 4.0 * (double)c->total);
+  for (int l = 1; l < c->nconv; ++l) {
+    int Co = c->cC[l + 1], Ci = c->cC[l];
+    for (int cls = 0; cls < 4; ++cls) {
+      int py = cls >> 1, px = cls & 1;
+      int64_t n = (int64_t)Ci * (1 + py) * (1 + px) * Co;
+      hipLaunchKernelGGL(k_pack_dgrad_w, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->shadow + c->convW[l], Co, Ci, py, px, c->wd[l][cls]);
+    }
+  }
+  for (int l = 0; l < c->nfc; ++l) {
+    int64_t n = (int64_t)c->fin[l] * c->fout[l];
+    hipLaunchKernelGGL(k_transpose_bf16, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->shadow + c->fcW[l], c->fout[l], c->fin[l], c->fcT[l], c->fout[l]);
+  }
+  hipLaunchKernelGGL(k_transpose_bf16, dim3(cdiv((int64_t)c->hid * HEAD_LD, 256)), dim3(256), 0, c->stream, c->shadow + c->headW, c->NH, c->hid, c->headT, HEAD_LD);
+  LAUNCHCHK(c, "weight repack");
+  return PPO_OK;
+}
+
+int refresh_shadow(Ctx* c) {
+  hipLaunchKernelGGL(k_cast_bf16, dim3(cdiv(c->total, 256)), dim3(256), 0, c->stream, c->p, c->shadow, c->total);
+  LAUNCHCHK(c, "k_cast_bf16");
+  return repack_weights(c);
+}
+
+ImgAddr conv_out_addr(Ctx* c, int l, const bf16_t* contiguous, const bf16_t* strided) {
+  // output of conv layer l (0-based) for a chunk: the last layer lives inside the feature matrix
+  ImgAddr a; a.idx = nullptr; a.V = c->V;
+  if (l == c->nconv - 1) { a.base = strided; a.stride_b = c->feat_ld; a.stride_v = c->flat; }
+  else { int64_t e = (int64_t)c->cC[l + 1] * c->cH[l + 1] * c->cW[l + 1]; a.base = contiguous; a.stride_b = e * c->V; a.stride_v = e; }
+  return a;
+}
+
+// Forward of `n` samples selected by device indices idx (NULL = 0..n-1 offset by `first`).
+int forward_chunk(Ctx* c, const int32_t* idx, int n) {
+  const int V = c->V, nimg = n * V;
+  {  // first convolution straight from the rollout buffer
+    ImgAddr in; in.base = c->obs; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
+    int Co = c->cC[1], Ho = c->cH[1], Wo = c->cW[1];
+    int64_t M = (int64_t)nimg * Ho * Wo;
+    size_t sh = (size_t)(9 * c->cC[0] * Co + Co) * sizeof(float);
+    ProfScope ps(c, "conv_fwd.0", 2.0 * (double)M * Co * 9 * c->cC[0], 2.0 * ((double)nimg * c->img_elems + (double)M * Co));
+    if (c->cC[0] == 1)
+      hipLaunchKernelGGL((k_conv1_fwd<1>), dim3(cdiv(M, 256)), dim3(256), sh, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->p + c->convW[0], c->p + c->convB[0], c->act[0]);
+    else
+      hipLaunchKernelGGL((k_conv1_fwd<3>), dim3(cdiv(M, 256)), dim3(256), sh, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->p + c->convW[0], c->p + c->convB[0], c->act[0]);
+    LAUNCHCHK(c, "k_conv1_fwd");
+  }
+  for (int l = 1; l < c->nconv; ++l) {
+    AConvFwd al;
+    al.in = conv_out_addr(c, l - 1, c->act[l - 1], nullptr);
+    al.H = c->cH[l]; al.W = c->cW[l]; al.Cin = c->cC[l]; al.Ho = c->cH[l + 1]; al.Wo = c->cW[l + 1];
+    al.M = nimg * al.Ho * al.Wo; al.K = 9 * al.Cin;
+    ImgAddr o = conv_out_addr(c, l, c->act[l], c->feat);
+    EpRows<bf16_t, true, true, false> ep;
+    ep.out = const_cast<bf16_t*>(o.base); ep.stride_b = o.stride_b; ep.stride_v = o.stride_v; ep.V = V;
+    ep.HW = al.Ho * al.Wo; ep.C = c->cC[l + 1]; ep.bias = c->p + c->convB[l]; ep.mask = nullptr; ep.M = al.M; ep.N = c->cC[l + 1];
+    double ab = 2.0 * ((double)nimg * al.H * al.W * al.Cin + (double)al.M * c->cC[l + 1] + (double)al.K * c->cC[l + 1]);
+    int rc = launch_gemm(c, al, al.M, c->shadow + c->convW[l], al.K, c->cC[l + 1], al.K, ep, "conv_fwd." + std::to_string(l), ab);
+    if (rc) return rc;
+  }
+  hipLaunchKernelGGL(k_gather_proprio, dim3(cdiv((int64_t)n * c->P, 256)), dim3(256), 0, c->stream, c->proprio, idx, n, c->P, c->feat, (int64_t)c->feat_ld, V * c->flat);
+  LAUNCHCHK(c, "k_gather_proprio");
+  const bf16_t* x = c->feat; int64_t ldx = c->feat_ld;
+  for (int l = 0; l < c->nfc; ++l) {
+    ARows al; al.a = plain_rows(x, ldx); al.HW = 1; al.C = 0; al.M = n; al.K = c->fin[l];
+    EpRows<bf16_t, true, true, false> ep;
+    ep.out = c->fcact[l]; ep.stride_b = c->fout[l]; ep.stride_v = 0; ep.V = 1; ep.HW = 1; ep.C = 0;
+    ep.bias = c->p + c->fcB[l]; ep.mask = nullptr; ep.M = n; ep.N = c->fout[l];
+    double ab = 2.0 * ((double)n * c->fin[l] + (double)n * c->fout[l] + (double)c->fin[l] * c->fout[l]);
+    int rc = launch_gemm(c, al, n, c->shadow + c->fcW[l], c->fin[l], c->fout[l], c->fin[l], ep, "fc_fwd." + std::to_string(l), ab);
+    if (rc) return rc;
+    x = c->fcact[l]; ldx = c->fout[l];
+  }
+  {
+    ARows al; al.a = plain_rows(x, ldx); al.HW = 1; al.C = 0; al.M = n; al.K = c->hid;
+    EpRows<float, true, false, false> ep;
+    ep.out = c->headout; ep.stride_b = HEAD_LD; ep.stride_v = 0; ep.V = 1; ep.HW = 1; ep.C = 0;
+    ep.bias = c->p + c->headB; ep.mask = nullptr; ep.M = n; ep.N = c->NH;
+    int rc = launch_gemm(c, al, n, c->shadow + c->headW, c->hid, c->NH, c->hid, ep, "head_fwd", 2.0 * n * c->hid + 4.0 * n * c->NH);
+    if (rc) return rc;
+  }
+  return PPO_OK;
+}
+
+// Backward of the chunk whose forward activations are in the workspaces and whose head
+// gradient is in dhead.  Gradients land in c->g (overwritten, or added when `acc`).
+int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
+  const int V = c->V, nimg = n * V;
+  int cur = 0;
+  const bf16_t* hlast = c->fcact[c->nfc - 1];
+  {  // heads
+    ARows dl; dl.a = plain_rows(c->dhead, HEAD_LD); dl.HW = 1; dl.C = 0; dl.M = n; dl.K = HEAD_LD;
+    ARows xl; xl.a = plain_rows(hlast, c->hid); xl.HW = 1; xl.C = 0; xl.M = n; xl.K = c->hid;
+    int rc = launch_wgrad(c, dl, xl, c->NH, c->hid, n, c->g + c->headW, c->g + c->headB, acc, "head_wgrad", 2.0 * n * (c->hid + HEAD_LD));
+    if (rc) return rc;
+    EpRows<bf16_t, false, false, true> ep;
+    ep.out = c->gbuf[cur]; ep.stride_b = c->hid; ep.stride_v = 0; ep.V = 1; ep.HW = 1; ep.C = 0; ep.bias = nullptr; ep.mask = hlast; ep.M = n; ep.N = c->hid;
+    rc = launch_gemm(c, dl, n, c->headT, HEAD_LD, c->hid, HEAD_LD, ep, "head_dgrad", 2.0 * n * (2.0 * c->hid + HEAD_LD));
+    if (rc) return rc;
+  }
+  for (int l = c->nfc - 1; l >= 0; --l) {
+    const bf16_t* x = l ? c->fcact[l - 1] : c->feat;
+    ARows dl; dl.a = plain_rows(c->gbuf[cur], c->fout[l]); dl.HW = 1; dl.C = 0; dl.M = n; dl.K = c->fout[l];
+    ARows xl; xl.a = plain_rows(x, c->fin[l]); xl.HW = 1; xl.C = 0; xl.M = n; xl.K = c->fin[l];
+    int rc = launch_wgrad(c, dl, xl, c->fout[l], c->fin[l], n, c->g + c->fcW[l], c->g + c->fcB[l], acc, "fc_wgrad." + std::to_string(l),
+                          2.0 * n * ((double)c->fin[l] + c->fout[l]) + 4.0 * (double)c->fin[l] * c->fout[l]);
+    if (rc) return rc;
+    EpRows<bf16_t, false, false, true> ep;
+    ep.out = c->gbuf[cur ^ 1]; ep.stride_b = c->fin[l]; ep.stride_v = 0; ep.V = 1; ep.HW = 1; ep.C = 0; ep.bias = nullptr; ep.mask = x; ep.M = n; ep.N = c->fin[l];
+    rc = launch_gemm(c, dl, n, c->fcT[l], c->fout[l], c->fin[l], c->fout[l], ep, "fc_dgrad." + std::to_string(l),
+                     2.0 * ((double)n * c->fout[l] + 2.0 * n * c->fin[l] + (double)c->fin[l] * c->fout[l]));
+    if (rc) return rc;
+    cur ^= 1;
+  }
+  // gbuf[cur] now holds d(feat) [n][feat_ld], already masked by the last conv layer's ReLU
+  for (int l = c->nconv - 1; l >= 1; --l) {
+    const int Co = c->cC[l + 1], Ci = c->cC[l], Ho = c->cH[l + 1], Wo = c->cW[l + 1], H = c->cH[l], W = c->cW[l];
+    ImgAddr dy = conv_out_addr(c, l, c->gbuf[cur], c->gbuf[cur]);
+    ARows dl; dl.a = dy; dl.HW = Ho * Wo; dl.C = Co; dl.M = nimg * Ho * Wo; dl.K = Co;
+    AConvFwd xl; xl.in = conv_out_addr(c, l - 1, c->act[l - 1], nullptr);
+    xl.H = H; xl.W = W; xl.Cin = Ci; xl.Ho = Ho; xl.Wo = Wo; xl.M = dl.M; xl.K = 9 * Ci;
+    int rc = launch_wgrad(c, dl, xl, Co, 9 * Ci, dl.M, c->g + c->convW[l], c->g + c->convB[l], acc, "conv_wgrad." + std::to_string(l),
+                          2.0 * ((double)dl.M * Co + (double)nimg * H * W * Ci) + 4.0 * 9.0 * Ci * Co);
+    if (rc) return rc;
+    for (int cls = 0; cls < 4; ++cls) {
+      const int py = cls >> 1, px = cls & 1;
+      AConvDgrad al; al.dy = dy; al.Ho = Ho; al.Wo = Wo; al.Cout = Co; al.Ha = class_len(H, py); al.Wa = class_len(W, px);
+      al.py = py; al.px = px; al.nv = 1 + px; al.M = nimg * al.Ha * al.Wa; al.K = (1 + py) * (1 + px) * Co;
+      EpConvDgrad ep;
+      ImgAddr xa = conv_out_addr(c, l - 1, c->act[l - 1], nullptr);
+      ep.act = xa;
+      ep.out.base = c->gbuf[cur ^ 1]; ep.out.stride_b = xa.stride_b; ep.out.stride_v = xa.stride_v; ep.out.V = V;
+      ep.H = H; ep.W = W; ep.Cin = Ci; ep.Ha = al.Ha; ep.Wa = al.Wa; ep.py = py; ep.px = px; ep.M = al.M;
+      // per class: a quarter of dY's reads and of the activation read / gradient write
+      double ab = 2.0 * ((double)nimg * Ho * Wo * Co / 4.0 + 2.0 * al.M * Ci + (double)al.K * Ci);
+      rc = launch_gemm(c, al, al.M, c->wd[l][cls], al.K, Ci, al.K, ep, "conv_dgrad." + std::to_string(l), ab);
+      if (rc) return rc;
+    }
+    cur ^= 1;
+  }
+  {  // first convolution: weight and bias gradient only
+    ImgAddr in; in.base = c->obs; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
+    const int Co = c->cC[1], Ho = c->cH[1], Wo = c->cW[1], K = 9 * c->cC[0];
+    int64_t M = (int64_t)nimg * Ho * Wo;
+    const int npair = Co * (K + 1);
+    int64_t max_blocks = c->partial_elems / npair;
+    if (max_blocks > 2048) max_blocks = 2048;
+    int64_t ppb = (M + max_blocks - 1) / max_blocks;
+    ppb = (ppb + 63) / 64 * 64;
+    int nblk = cdiv(M, ppb);
+    size_t sh = (size_t)(64 * Co + 64 * (K + 1)) * sizeof(float);
+    ProfScope ps(c, "conv_wgrad.0", 2.0 * (double)M * Co * (K + 1), 2.0 * ((double)M * Co + (double)nimg * c->img_elems));
+    if (c->cC[0] == 1)
+      hipLaunchKernelGGL((k_conv1_wgrad<1>), dim3(nblk), dim3(256), sh, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->gbuf[cur], (int)ppb, c->partial);
+    else
+      hipLaunchKernelGGL((k_conv1_wgrad<3>), dim3(nblk), dim3(256), sh, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->gbuf[cur], (int)ppb, c->partial);
+    LAUNCHCHK(c, "k_conv1_wgrad");
+    hipLaunchKernelGGL(k_conv1_wgrad_reduce, dim3(cdiv(npair, 256)), dim3(256), 0, c->stream, c->partial, nblk, Co, K, c->g + c->convW[0], c->g + c->convB[0], acc ? 1 : 0);
+    LAUNCHCHK(c, "k_conv1_wgrad_reduce");
+  }
+  return PPO_OK;
+}
+
+int gen_permutation(Ctx* c, uint64_t seed, uint64_t update, uint64_t epoch) {
+  const uint64_t stream = perm_stream(seed, update, epoch);
+  const int S = c->S, g = cdiv(S, 256);
+  ProfScope ps(c, "permutation", 0.0, 4.0 * S);
+  hipLaunchKernelGGL(k_fill_i32, dim3(cdiv(2 * c->nb, 256)), dim3(256), 0, c->stream, c->phist, (int64_t)2 * c->nb, 0);  // hist + cursor
+  hipLaunchKernelGGL(k_perm_hist, dim3(g), dim3(256), 0, c->stream, stream, S, c->shift, c->phist);
+  hipLaunchKernelGGL(k_perm_scan, dim3(1), dim3(1024), 0, c->stream, c->phist, c->pstart, c->nb);
+  hipLaunchKernelGGL(k_perm_scatter, dim3(g), dim3(256), 0, c->stream, stream, S, c->shift, c->pstart, c->pcursor, c->ptmp);
+  hipLaunchKernelGGL(k_perm_rank, dim3(g), dim3(256), 0, c->stream, stream, S, c->shift, c->pstart, c->phist, c->ptmp, c->perm);
+  LAUNCHCHK(c, "permutation kernels");
+  return PPO_OK;
+}
+
+int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool distill) {
+  const int B = c->S / hp->minibatches;
+  const int steps = hp->epochs * hp->minibatches;
+  const int blocks_per_chunk = cdiv(c->CH, 256);
+  int k = 0;
+  for (int e = 0; e < hp->epochs; ++e) {
+    int rc = gen_permutation(c, hp->seed, (uint64_t)c->update_idx, (uint64_t)e);
+    if (rc) return rc;
+    for (int mb = 0; mb < hp->minibatches; ++mb, ++k) {
+      const int32_t* idx = c->perm + (int64_t)mb * B;
+      int nblocks = 0;
+      for (int c0 = 0, ci = 0; c0 < B; c0 += c->CH, ++ci) {
+        const int n = (B - c0 < c->CH) ? B - c0 : c->CH;
+        rc = forward_chunk(c, idx + c0, n);
+        if (rc) return rc;
+        float* sp = c->stat_part + (int64_t)ci * blocks_per_chunk * LOSS_NSTAT;
+        float* dp = c->dls_part + (int64_t)ci * blocks_per_chunk * 32;
+        {
+        ProfScope ps(c, "loss", 0.0, (double)n * (HEAD_LD * 6.0 + 4.0 * c->A + 20.0));
+        if (distill)
+          hipLaunchKernelGGL(k_mse_loss, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, n, B, c->A, c->headout, idx + c0, c->action, c->dhead, sp);
+        else
+          hipLaunchKernelGGL(k_ppo_loss, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, n, B, c->A, c->headout, c->p + c->logstd, idx + c0, c->action,
+                             c->logp, c->value, c->adv, c->ret, hp->clip_eps, hp->vclip_eps, hp->vf_coef, c->dhead, sp, dp);
+        LAUNCHCHK(c, "loss kernel");
+        }
+        // partial slots of a ragged last chunk follow the full chunks contiguously
+        nblocks = ci * blocks_per_chunk + cdiv(n, 256);
+        rc = backward_chunk(c, idx + c0, n, c0 > 0);
+        if (rc) return rc;
+      }
+      hipLaunchKernelGGL(k_loss_finalize, dim3(1), dim3(64), 0, c->stream, nblocks, B, c->A, distill ? 1 : 0, c->stat_part, c->dls_part,
+                         distill ? nullptr : c->p + c->logstd, hp->vf_coef, hp->ent_coef, c->dstats + k, distill ? nullptr : c->g + c->logstd);
+      LAUNCHCHK(c, "k_loss_finalize");
+      c->step += 1;
+      {
+      ProfScope ps(c, "adam", 0.0, 30.0 * (double)c->total);
+      const double c1 = 1.0 - pow((double)hp->beta1, (double)c->step), c2 = 1.0 - pow((double)hp->beta2, (double)c->step);
+      hipLaunchKernelGGL(k_adam, dim3(c->adam_blocks), dim3(256), 0, c->stream, c->total, c->p, c->m, c->v, c->g, c->shadow, hp->lr, hp->beta1, hp->beta2,
+                         hp->adam_eps, (float)(1.0 / c1), (float)(1.0 / c2), c->sq_part);
+      LAUNCHCHK(c, "k_adam");
+      hipLaunchKernelGGL(k_gnorm_finalize, dim3(1), dim3(64), 0, c->stream, c->sq_part, c->adam_blocks, c->dstats + k);
+      LAUNCHCHK(c, "k_gnorm_finalize");
+      }
+      rc = repack_weights(c);
+      if (rc) return rc;
+    }
+  }
+  c->update_idx += 1;
+  if (host_stats) {
+    HIPCHK(c, hipMemcpyAsync(host_stats, c->dstats, sizeof(DevStats) * (size_t)steps, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+  }
+  return PPO_OK;
+}
+
+int create_impl(Ctx* c) {
+  build_geometry(c);
+  const int V = c->V;
+  int CH = c->d.max_chunk > 0 ? c->d.max_chunk : 16384 / V;
+  if (CH > c->S) CH = c->S;
+  if (CH < 1) CH = 1;
+  c->CH = CH;
+  // the kernels index rows with 32-bit integers
+  if ((int64_t)CH * V * c->cH[1] * c->cW[1] >= (1LL << 31) || (int64_t)CH * c->feat_ld >= (1LL << 40))
+    return fail(c, PPO_ESHAPE, "chunk of %d samples is too large for 32-bit row indices; lower max_chunk", CH);
+  const int64_t S = c->S;
+  // parameters
+  DALLOC(c, c->p, c->total); DALLOC(c, c->m, c->total); DALLOC(c, c->v, c->total); DALLOC(c, c->g, c->total);
+  DALLOC(c, c->shadow, c->total + 8);
+  for (int l = 1; l < c->nconv; ++l)
+    for (int cls = 0; cls < 4; ++cls) DALLOC(c, c->wd[l][cls], (int64_t)c->cC[l] * (1 + (cls >> 1)) * (1 + (cls & 1)) * c->cC[l + 1]);
+  for (int l = 0; l < c->nfc; ++l) DALLOC(c, c->fcT[l], (int64_t)c->fin[l] * c->fout[l]);
+  DALLOC(c, c->headT, (int64_t)c->hid * HEAD_LD);
+  // rollout buffer
+  DALLOC(c, c->obs, S * V * c->img_elems);
+  DALLOC(c, c->proprio, S * c->P); DALLOC(c, c->action, S * c->A);
+  DALLOC(c, c->logp, S); DALLOC(c, c->value, S); DALLOC(c, c->reward, S); DALLOC(c, c->adv, S); DALLOC(c, c->ret, S); DALLOC(c, c->done, S);
+  // permutation: about 32 keys per bucket
+  int nb = 1, lg = 0;
+  while ((int64_t)nb * 32 < S && nb < (1 << 20)) { nb <<= 1; ++lg; }
+  c->nb = nb; c->shift = 64 - lg;
+  DALLOC(c, c->perm, S); DALLOC(c, c->ptmp, S); DALLOC(c, c->phist, 2 * (int64_t)nb); DALLOC(c, c->pstart, nb);
+  c->pcursor = c->phist + nb;
+  // workspaces
+  int64_t gmax = (int64_t)CH * c->feat_ld;
+  for (int l = 0; l < c->nconv - 1; ++l) {
+    int64_t e = (int64_t)CH * V * c->cC[l + 1] * c->cH[l + 1] * c->cW[l + 1];
+    DALLOC(c, c->act[l], e);
+    if (e > gmax) gmax = e;
+  }
+  DALLOC(c, c->feat, (int64_t)CH * c->feat_ld);
+  for (int l = 0; l < c->nfc; ++l) { DALLOC(c, c->fcact[l], (int64_t)CH * c->fout[l]); if ((int64_t)CH * c->fout[l] > gmax) gmax = (int64_t)CH * c->fout[l]; }
+  DALLOC(c, c->headout, (int64_t)CH * HEAD_LD); DALLOC(c, c->dhead, (int64_t)CH * HEAD_LD);
+  DALLOC(c, c->gbuf[0], gmax); DALLOC(c, c->gbuf[1], gmax);
+  // weight-gradient partials: room for every layer at its preferred split count
+  int64_t pe = 2048LL * c->cC[1] * (9 * c->cC[0] + 1), bpe = 0;
+  auto want = [&](int Nn, int Kk, int64_t M) {
+    int tiles = cdiv(Kk, 64) * cdiv(Nn, 64);
+    int splits = cdiv(1536, tiles), mr = cdiv(M, 256);
+    if (splits > mr) splits = mr;
+    if (splits < 1) splits = 1;
+    if ((int64_t)splits * Nn * Kk > pe) pe = (int64_t)splits * Nn * Kk;
+    if ((int64_t)splits * Nn > bpe) bpe = (int64_t)splits * Nn;
+  };
+  for (int l = 1; l < c->nconv; ++l) want(c->cC[l + 1], 9 * c->cC[l], (int64_t)CH * V * c->cH[l + 1] * c->cW[l + 1]);
+  for (int l = 0; l < c->nfc; ++l) want(c->fout[l], c->fin[l], CH);
+  want(c->NH, c->hid, CH);
+  c->partial_elems = pe; c->bias_partial_elems = bpe;
+  DALLOC(c, c->partial, pe); DALLOC(c, c->bias_partial, bpe);
+  // loss / Adam partials
+  c->max_loss_blocks = cdiv(S, CH) * cdiv(CH, 256) + 1;
+  DALLOC(c, c->stat_part, (int64_t)c->max_loss_blocks * LOSS_NSTAT); DALLOC(c, c->dls_part, (int64_t)c->max_loss_blocks * 32);
+  c->adam_blocks = cdiv(c->total, 1024); if (c->adam_blocks > 2048) c->adam_blocks = 2048;
+  DALLOC(c, c->sq_part, c->adam_blocks);
+  DALLOC(c, c->dstats, c->max_steps);
+  HIPCHK(c, hipMemsetAsync(c->p, 0, sizeof(float) * (size_t)c->total, c->stream));
+  HIPCHK(c, hipMemsetAsync(c->m, 0, sizeof(float) * (size_t)c->total, c->stream));
+  HIPCHK(c, hipMemsetAsync(c->v, 0, sizeof(float) * (size_t)c->total, c->stream));
+  HIPCHK(c, hipMemsetAsync(c->g, 0, sizeof(float) * (size_t)c->total, c->stream));
+  HIPCHK(c, hipMemsetAsync(c->shadow, 0, sizeof(bf16_t) * (size_t)(c->total + 8), c->stream));
+  int rc = refresh_shadow(c);
+  if (rc) return rc;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->written.assign((size_t)c->T, 0);
+  return PPO_OK;
+}
+
+void free_all(Ctx* c) {
+  for (void* p : c->allocs) (void)hipFree(p);
+  c->allocs.clear();
+}
+
+int to_internal(Ctx* c, const float* canon, float* dev) {
+  std::vector<float> tmp((size_t)c->total);
+  for (int64_t i = 0; i < c->total; ++i) tmp[(size_t)i] = canon[c->i2c[(size_t)i]];
+  HIPCHK(c, hipMemcpyAsync(dev, tmp.data(), sizeof(float) * (size_t)c->total, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return PPO_OK;
+}
+int to_canonical(Ctx* c, const float* dev, float* canon) {
+  std::vector<float> tmp((size_t)c->total);
+  HIPCHK(c, hipMemcpyAsync(tmp.data(), dev, sizeof(float) * (size_t)c->total, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  for (int64_t i = 0; i < c->total; ++i) canon[c->i2c[(size_t)i]] = tmp[(size_t)i];
+  return PPO_OK;
+}
+
+}  // namespace
+
+struct ppo_ctx : Ctx {};
+
+extern "C" {
+
+int ppo_create(ppo_ctx** out, const ppo_net_desc* desc, void* hip_stream) {
+  if (!out) return fail(nullptr, PPO_EINVAL, "out is NULL");
+  *out = nullptr;
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  ppo_ctx* c = new (std::nothrow) ppo_ctx();
+  if (!c) return fail(nullptr, PPO_ENOMEM, "host allocation failed");
+  c->d = *desc;
+  c->stream = (hipStream_t)hip_stream;
+  rc = create_impl(c);
+  if (rc) { g_create_error = c->err; free_all(c); delete c; return rc; }
+  *out = c;
+  return PPO_OK;
+}
+
+int ppo_destroy(ppo_ctx* c) {
+  if (!c) return PPO_EINVAL;
+  (void)hipStreamSynchronize(c->stream);
+  for (auto& r : c->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (auto e : c->prof_pool) (void)hipEventDestroy(e);
+  free_all(c);
+  delete c;
+  return PPO_OK;
+}
+
+const char* ppo_last_error(const ppo_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+int64_t ppo_param_count(const ppo_ctx* c) { return c ? c->total : PPO_EINVAL; }
+int64_t ppo_buffer_image_bytes(const ppo_ctx* c) { return c ? (int64_t)c->S * c->V * c->img_elems * (int64_t)sizeof(bf16_t) : PPO_EINVAL; }
+
+int ppo_set_params(ppo_ctx* c, const float* h, int64_t n) {
+  if (!c) return PPO_EINVAL;
+  if (!h) return fail(c, PPO_EINVAL, "h_params is NULL");
+  if (n != c->total) return fail(c, PPO_ESHAPE, "expected %lld parameters, got %lld", (long long)c->total, (long long)n);
+  int rc = to_internal(c, h, c->p);
+  if (rc) return rc;
+  rc = refresh_shadow(c);
+  if (rc) return rc;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return PPO_OK;
+}
+int ppo_get_params(ppo_ctx* c, float* h, int64_t n) {
+  if (!c) return PPO_EINVAL;
+  if (!h) return fail(c, PPO_EINVAL, "h_params is NULL");
+  if (n != c->total) return fail(c, PPO_ESHAPE, "expected %lld parameters, got %lld", (long long)c->total, (long long)n);
+  return to_canonical(c, c->p, h);
+}
+int ppo_get_grads(ppo_ctx* c, float* h, int64_t n) {
+  if (!c) return PPO_EINVAL;
+  if (!h) return fail(c, PPO_EINVAL, "h_grads is NULL");
+  if (n != c->total) return fail(c, PPO_ESHAPE, "expected %lld parameters, got %lld", (long long)c->total, (long long)n);
+  return to_canonical(c, c->g, h);
+}
+int ppo_set_opt_state(ppo_ctx* c, const float* hm, const float* hv, int64_t n, int64_t step, int64_t update_idx) {
+  if (!c) return PPO_EINVAL;
+  if (!hm || !hv) return fail(c, PPO_EINVAL, "h_m / h_v is NULL");
+  if (n != c->total) return fail(c, PPO_ESHAPE, "expected %lld parameters, got %lld", (long long)c->total, (long long)n);
+  if (step < 0 || update_idx < 0) return fail(c, PPO_EINVAL, "step and update_idx must be >= 0");
+  int rc = to_internal(c, hm, c->m);
+  if (rc) return rc;
+  rc = to_internal(c, hv, c->v);
+  if (rc) return rc;
+  c->step = step; c->update_idx = update_idx;
+  return PPO_OK;
+}
+int ppo_get_opt_state(ppo_ctx* c, float* hm, float* hv, int64_t n, int64_t* step, int64_t* update_idx) {
+  if (!c) return PPO_EINVAL;
+  if (!hm || !hv) return fail(c, PPO_EINVAL, "h_m / h_v is NULL");
+  if (n != c->total) return fail(c, PPO_ESHAPE, "expected %lld parameters, got %lld", (long long)c->total, (long long)n);
+  int rc = to_canonical(c, c->m, hm);
+  if (rc) return rc;
+  rc = to_canonical(c, c->v, hv);
+  if (rc) return rc;
+  if (step) *step = c->step;
+  if (update_idx) *update_idx = c->update_idx;
+  return PPO_OK;
+}
+
+int ppo_buffer_write(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, const float* d_action, const float* d_logp,
+                     const float* d_value, const float* d_reward, const uint8_t* d_done) {
+  if (!c) return PPO_EINVAL;
+  if (t < 0 || t >= c->T) return fail(c, PPO_EINVAL, "t = %d outside [0, %d)", t, c->T);
+  if (!d_obs || !d_proprio || !d_action) return fail(c, PPO_EINVAL, "d_obs, d_proprio and d_action must not be NULL");
+  if (c->d.has_value_head && (!d_logp || !d_value || !d_reward || !d_done))
+    return fail(c, PPO_EINVAL, "an actor-critic buffer needs d_logp, d_value, d_reward and d_done");
+  const int N = c->N, V = c->V, HW = c->d.in_h * c->d.in_w, C = c->d.in_c;
+  const int64_t nimg = (int64_t)N * V, groups = (HW + 7) / 8;
+  bf16_t* dst = c->obs + (int64_t)t * N * V * c->img_elems;
+  ProfScope ps(c, "buffer_write", 0.0, (double)nimg * c->img_elems * (c->d.obs_dtype == 0 ? 6.0 : 4.0) + (double)N * (6.0 * c->P + 8.0 * c->A + 26.0));
+  if (c->d.obs_dtype == 0)
+    hipLaunchKernelGGL((k_write_obs<float>), dim3(cdiv(nimg * groups, 256)), dim3(256), 0, c->stream, (const float*)d_obs, dst, nimg, C, HW);
+  else
+    hipLaunchKernelGGL((k_write_obs<bf16_t>), dim3(cdiv(nimg * groups, 256)), dim3(256), 0, c->stream, (const bf16_t*)d_obs, dst, nimg, C, HW);
+  LAUNCHCHK(c, "k_write_obs");
+  const int64_t off = (int64_t)t * N;
+  const int mx = c->P > c->A ? c->P : c->A;
+  hipLaunchKernelGGL(k_write_scalars, dim3(cdiv((int64_t)N * mx, 256)), dim3(256), 0, c->stream, N, c->P, c->A, d_proprio, d_action, d_logp, d_value,
+                     d_reward, d_done, c->proprio + off * c->P, c->action + off * c->A, c->logp + off, c->value + off, c->reward + off, c->done + off);
+  LAUNCHCHK(c, "k_write_scalars");
+  if (t == 0) { c->written.assign((size_t)c->T, 0); }
+  c->written[(size_t)t] = 1;
+  c->gae_done = false;
+  return PPO_OK;
+}
+
+int ppo_buffer_read_obs(ppo_ctx* c, int32_t t, void* d_obs_bf16) {
+  if (!c) return PPO_EINVAL;
+  if (t < 0 || t >= c->T) return fail(c, PPO_EINVAL, "t = %d outside [0, %d)", t, c->T);
+  if (!d_obs_bf16) return fail(c, PPO_EINVAL, "d_obs_bf16 is NULL");
+  if (!c->written[(size_t)t]) return fail(c, PPO_ESTATE, "step %d has not been written", t);
+  const int64_t nimg = (int64_t)c->N * c->V, n = nimg * c->img_elems;
+  hipLaunchKernelGGL(k_read_obs, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->obs + (int64_t)t * n, (bf16_t*)d_obs_bf16, nimg, c->d.in_c,
+                     c->d.in_h * c->d.in_w);
+  LAUNCHCHK(c, "k_read_obs");
+  return PPO_OK;
+}
+
+static int all_written(ppo_ctx* c) {
+  for (char w : c->written) if (!w) return 0;
+  return 1;
+}
+
+int ppo_gae(ppo_ctx* c, const float* d_last_value, float gamma, float lambda) {
+  if (!c) return PPO_EINVAL;
+  if (!d_last_value) return fail(c, PPO_EINVAL, "d_last_value is NULL");
+  if (!isfinite(gamma) || !isfinite(lambda) || gamma < 0.f || gamma > 1.f || lambda < 0.f || lambda > 1.f)
+    return fail(c, PPO_EINVAL, "gamma and lambda must be in [0, 1]");
+  if (!c->d.has_value_head) return fail(c, PPO_ESTATE, "this context has no value head (distillation student)");
+  if (!all_written(c)) return fail(c, PPO_ESTATE, "ppo_gae needs all %d steps written", c->T);
+  ProfScope ps(c, "gae", 6.0 * c->S, 17.0 * c->S + 4.0 * c->N);
+  hipLaunchKernelGGL(k_gae, dim3(cdiv(c->N, 64)), dim3(64), 0, c->stream, c->T, c->N, c->reward, c->done, c->value, d_last_value, gamma, lambda, c->adv, c->ret);
+  LAUNCHCHK(c, "k_gae");
+  c->gae_done = true;
+  return PPO_OK;
+}
+
+int ppo_get_adv_ret(ppo_ctx* c, float* d_adv, float* d_ret) {
+  if (!c) return PPO_EINVAL;
+  if (!c->gae_done) return fail(c, PPO_ESTATE, "ppo_gae has not run on this rollout");
+  if (d_adv) HIPCHK(c, hipMemcpyAsync(d_adv, c->adv, sizeof(float) * (size_t)c->S, hipMemcpyDeviceToDevice, c->stream));
+  if (d_ret) HIPCHK(c, hipMemcpyAsync(d_ret, c->ret, sizeof(float) * (size_t)c->S, hipMemcpyDeviceToDevice, c->stream));
+  return PPO_OK;
+}
+
+int ppo_permutation(ppo_ctx* c, uint64_t seed, uint64_t update_idx, uint64_t epoch, int32_t* h_perm) {
+  if (!c) return PPO_EINVAL;
+  if (!h_perm) return fail(c, PPO_EINVAL, "h_perm is NULL");
+  int rc = gen_permutation(c, seed, update_idx, epoch);
+  if (rc) return rc;
+  HIPCHK(c, hipMemcpyAsync(h_perm, c->perm, sizeof(int32_t) * (size_t)c->S, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return PPO_OK;
+}
+
+int ppo_update(ppo_ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats) {
+  if (!c) return PPO_EINVAL;
+  if (!c->d.has_value_head) return fail(c, PPO_ESTATE, "ppo_update needs a value head; use distill_update for a student");
+  int rc = validate_hp(c, hp, false);
+  if (rc) return rc;
+  if (!c->gae_done) return fail(c, PPO_ESTATE, "ppo_update needs ppo_gae on the current rollout");
+  return run_update(c, hp, host_stats, false);
+}
+
+int distill_update(ppo_ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats) {
+  if (!c) return PPO_EINVAL;
+  if (c->d.has_value_head) return fail(c, PPO_ESTATE, "distill_update needs a student context (has_value_head = 0)");
+  int rc = validate_hp(c, hp, true);
+  if (rc) return rc;
+  if (!all_written(c)) return fail(c, PPO_ESTATE, "distill_update needs all %d steps written", c->T);
+  return run_update(c, hp, host_stats, true);
+}
+
+__global__ void k_copy_heads(int n, int A, int has_v, const float* __restrict__ out, float* __restrict__ mu, float* __restrict__ v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)n * HEAD_LD) return;
+  int b = (int)(i / HEAD_LD), j = (int)(i - (int64_t)b * HEAD_LD);
+  if (j < A) mu[(int64_t)b * A + j] = out[i];
+  else if (j == A && has_v && v) v[b] = out[i];
+}
+
+int ppo_forward(ppo_ctx* c, const int32_t* d_idx, int64_t count, float* d_mu, float* d_v) {
+  if (!c) return PPO_EINVAL;
+  if (!d_mu) return fail(c, PPO_EINVAL, "d_mu is NULL");
+  if (count < 0 || (!d_idx && count > c->S)) return fail(c, PPO_EINVAL, "count out of range");
+  if (!all_written(c)) return fail(c, PPO_ESTATE, "ppo_forward needs all %d steps written", c->T);
+  for (int64_t c0 = 0; c0 < count; c0 += c->CH) {
+    int n = (int)((count - c0 < c->CH) ? count - c0 : c->CH);
+    const int32_t* idx = d_idx ? d_idx + c0 : nullptr;
+    if (!d_idx) {
+      // identity indices: reuse the permutation scratch
+      hipLaunchKernelGGL(k_iota_i32, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->ptmp, n, (int32_t)c0);
+      LAUNCHCHK(c, "k_iota_i32");
+      idx = c->ptmp;
+    }
+    int rc = forward_chunk(c, idx, n);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_copy_heads, dim3(cdiv((int64_t)n * HEAD_LD, 256)), dim3(256), 0, c->stream, n, c->A, c->d.has_value_head, c->headout,
+                       d_mu + c0 * c->A, d_v ? d_v + c0 : nullptr);
+    LAUNCHCHK(c, "k_copy_heads");
+  }
+  return PPO_OK;
+}
+
+int ppo_profile(ppo_ctx* c, int32_t enable) {
+  if (!c) return PPO_EINVAL;
+  (void)hipStreamSynchronize(c->stream);
+  for (auto& r : c->prof_recs) { c->prof_pool.push_back(r.a); c->prof_pool.push_back(r.b); }
+  c->prof_recs.clear(); c->prof_cls.clear(); c->prof_idx.clear();
+  c->prof_on = enable != 0;
+  return PPO_OK;
+}
+
+int64_t ppo_profile_report(ppo_ctx* c, char* buf, int64_t cap) {
+  if (!c || !buf || cap < 1) return PPO_EINVAL;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, PPO_EHIP, "hipStreamSynchronize failed");
+  std::vector<double> ms(c->prof_cls.size(), 0.0);
+  for (auto& r : c->prof_recs) {
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) ms[(size_t)r.cls] += t;
+  }
+  std::string out;
+  char line[256];
+  for (size_t i = 0; i < c->prof_cls.size(); ++i) {
+    const auto& pc = c->prof_cls[i];
+    snprintf(line, sizeof line, "%s %lld %.6f %.6e %.6e\n", pc.name.c_str(), (long long)pc.launches, ms[i], pc.flops, pc.bytes);
+    out += line;
+  }
+  if ((int64_t)out.size() + 1 > cap) return fail(c, PPO_EINVAL, "report needs %zu bytes", out.size() + 1);
+  memcpy(buf, out.c_str(), out.size() + 1);
+  return (int64_t)out.size();
+}
+
+int ppo_diag_gemm(int32_t M, int32_t N, int32_t K, const float* h_a, const float* h_b, float* h_c) {
+  if (!h_a || !h_b || !h_c || M < 1 || N < 1 || K < 8 || K % 8) return PPO_EINVAL;
+  Ctx tmp;
+  Ctx* c = &tmp;
+  float *da = nullptr, *db = nullptr, *dc = nullptr;
+  bf16_t *ba = nullptr, *bb = nullptr;
+  int rc = PPO_OK;
+  auto body = [&]() -> int {
+    DALLOC(c, da, (int64_t)M * K); DALLOC(c, db, (int64_t)N * K); DALLOC(c, dc, (int64_t)M * N);
+    DALLOC(c, ba, (int64_t)M * K); DALLOC(c, bb, (int64_t)N * K);
+    HIPCHK(c, hipMemcpy(da, h_a, sizeof(float) * (size_t)M * K, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(db, h_b, sizeof(float) * (size_t)N * K, hipMemcpyHostToDevice));
+    hipLaunchKernelGGL(k_cast_bf16, dim3(cdiv((int64_t)M * K, 256)), dim3(256), 0, c->stream, da, ba, (int64_t)M * K);
+    hipLaunchKernelGGL(k_cast_bf16, dim3(cdiv((int64_t)N * K, 256)), dim3(256), 0, c->stream, db, bb, (int64_t)N * K);
+    LAUNCHCHK(c, "k_cast_bf16");
+    ARows al; al.a = plain_rows(ba, K); al.HW = 1; al.C = 0; al.M = M; al.K = K;
+    EpRows<float, false, false, false> ep;
+    ep.out = dc; ep.stride_b = N; ep.stride_v = 0; ep.V = 1; ep.HW = 1; ep.C = 0; ep.bias = nullptr; ep.mask = nullptr; ep.M = M; ep.N = N;
+    int r = launch_gemm(c, al, M, bb, K, N, K, ep, "diag_gemm", 0.0);
+    if (r) return r;
+    HIPCHK(c, hipDeviceSynchronize());
+    HIPCHK(c, hipMemcpy(h_c, dc, sizeof(float) * (size_t)M * N, hipMemcpyDeviceToHost));
+    return PPO_OK;
+  };
+  rc = body();
+  if (rc) g_create_error = c->err;
+  free_all(c);
+  return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,279 @@
+"""GPU parity tests: every entry point of libppo_learner.so against the CPU oracle on the same
+seeded inputs.  Tolerances: GAE/returns 1e-5 (fp32); losses, gradients and updated parameters
+2e-2 (bf16 MFMA with fp32 accumulation; per-tensor relative L2 for tensors); permutations and
+the stored bf16 images bit-exact.
+
+Network outputs and loss statistics are held to 2e-2 against the oracle's exact fp64 mode.
+Gradients and updated parameters are held to 2e-2 against the oracle's bf16-operand mode (same
+formulas, operands rounded to bf16 where the kernels store bf16, fp64 accumulation): the ReLU
+masks and the active branch of the clipped losses are discrete decisions and both sides must take
+them in the same precision.  Against the exact mode the gradients of these synthetic rollouts
+(pure-noise returns, so the batch gradient is a sqrt(B)-cancelled sum) differ by a few percent
+for ANY bf16-operand implementation; that distance is checked against a loose bound only."""
+import numpy as np
+import pytest
+
+from oracle import ppo_oracle as orc
+from paper_2509_16434_amd import configs, synth
+
+from helpers import TOL_BF16, TOL_GAE, fill_learner, flat_rollout, per_tensor_errors, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2509_16434_amd import learner
+    return learner
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _setup(L, cfg, max_chunk=0, seed=None):
+    ro = synth.rollout(cfg, seed)
+    lrn = L.Learner(cfg["net"], cfg["num_envs"], cfg["horizon"], cfg["obs_dtype"], max_chunk=max_chunk)
+    params = synth.init_params(cfg["net"], cfg["seed"])
+    lrn.set_params(params)
+    fill_learner(lrn, cfg, ro, distill=(cfg["kind"] == "distill"))
+    return lrn, ro, params
+
+
+# ------------------------------------------------------------------ MFMA tile kernel
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (200, 24, 72), (300, 64, 288), (129, 130, 8), (64, 512, 1056), (1, 1, 8)])
+def test_mfma_gemm_tiles(L, M, N, K):
+    rng = np.random.default_rng(M * 7 + N)
+    a = synth.narrow_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    b = synth.narrow_bf16(rng.standard_normal((N, K)).astype(np.float32))
+    c = L.diag_gemm(a, b)
+    want = a.astype(np.float64) @ b.astype(np.float64).T
+    assert np.abs(c - want).max() <= 1e-4 * max(1.0, np.abs(want).max())
+
+
+# ------------------------------------------------------------------ buffer
+@pytest.mark.parametrize("ci", [0, 1, 3])
+def test_buffer_write_read_back(L, ci):
+    torch = _torch()
+    cfg = configs.get_config(ci, num_envs=24, horizon=2)
+    lrn, ro, _ = _setup(L, cfg)
+    for t in range(cfg["horizon"]):
+        got = lrn.buffer_read_obs(t).to(torch.float32).cpu().numpy()
+        want = torch.from_numpy(ro["obs"][t]).to(torch.bfloat16).to(torch.float32).numpy()
+        np.testing.assert_array_equal(got, want)
+    net = cfg["net"]
+    assert lrn.buffer_image_bytes() == orc.buffer_image_bytes(24, 2, net["n_views"], net["in_c"], net["in_h"], net["in_w"], 2)
+
+
+def test_buffer_write_odd_image_size(L):
+    torch = _torch()
+    cfg = configs.get_config(0, num_envs=5, horizon=2)
+    cfg["net"].update(in_h=9, in_w=11)
+    lrn, ro, _ = _setup(L, cfg)
+    got = lrn.buffer_read_obs(1).to(torch.float32).cpu().numpy()
+    want = torch.from_numpy(ro["obs"][1]).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(got, want)
+
+
+# ------------------------------------------------------------------ GAE
+@pytest.mark.parametrize("N,T", [(64, 16), (1000, 16), (16384, 32), (1, 1), (3, 7)])
+def test_gae_matches_oracle(L, N, T):
+    torch = _torch()
+    cfg = configs.get_config(0, num_envs=N, horizon=T)
+    cfg["net"].update(in_h=8, in_w=8)
+    rng = np.random.default_rng(N + T)
+    lrn = L.Learner(cfg["net"], N, T, "fp32")
+    r = rng.standard_normal((T, N)).astype(np.float32)
+    v = rng.standard_normal((T, N)).astype(np.float32)
+    d = (rng.random((T, N)) < 0.05).astype(np.uint8)
+    lv = rng.standard_normal(N).astype(np.float32)
+    net = cfg["net"]
+    z = lambda *s: torch.zeros(*s, device="cuda")
+    obs = z(N, 1, 1, 8, 8)
+    for t in range(T):
+        lrn.buffer_write(t, obs, z(N, net["proprio_dim"]), z(N, net["act_dim"]), z(N), torch.from_numpy(v[t]).cuda(),
+                         torch.from_numpy(r[t]).cuda(), torch.from_numpy(d[t]).cuda())
+    lrn.gae(torch.from_numpy(lv).cuda(), 0.99, 0.95)
+    adv, ret = lrn.get_adv_ret()
+    oadv, oret = orc.gae(r, d, v, lv, 0.99, 0.95)
+    for got, want in ((adv, oadv), (ret, oret)):
+        got = got.cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - want) <= TOL_GAE * np.maximum(1.0, np.abs(want)))
+    # returns are one fp32 add on top of the advantage
+    np.testing.assert_array_equal(ret.cpu().numpy(), adv.cpu().numpy() + v)
+
+
+# ------------------------------------------------------------------ permutation
+@pytest.mark.parametrize("S", [1, 37, 1024, 16384, 65536, 524288])
+def test_permutation_bit_exact(L, S):
+    cfg = configs.get_config(0, num_envs=S, horizon=1)
+    cfg["net"].update(in_h=2, in_w=2)
+    lrn = L.Learner(cfg["net"], S, 1, "fp32")
+    for (seed, upd, ep) in [(0, 0, 0), (1234, 5, 3)]:
+        got = lrn.permutation(seed, upd, ep)
+        np.testing.assert_array_equal(got, orc.permutation(seed, upd, ep, S))
+
+
+# ------------------------------------------------------------------ forward
+FWD_CASES = [(0, 64, 16), (1, 40, 4), (2, 12, 4), (3, 8, 4)]
+
+
+@pytest.mark.parametrize("ci,N,T", FWD_CASES)
+def test_forward_matches_oracle(L, ci, N, T):
+    cfg = configs.get_config(ci, num_envs=N, horizon=T)
+    lrn, ro, params = _setup(L, cfg)
+    fr = flat_rollout(ro)
+    mu, v = lrn.forward()
+    omu, ov = orc.forward(cfg["net"], params, fr["obs"], fr["proprio"])
+    assert rel_l2(mu.cpu().numpy(), omu) <= TOL_BF16
+    if v is not None:
+        assert rel_l2(v.cpu().numpy(), ov) <= TOL_BF16
+    with orc.quant(1):
+        qmu, qv = orc.forward(cfg["net"], params, fr["obs"], fr["proprio"])
+    assert rel_l2(mu.cpu().numpy(), qmu) <= 2e-3
+    if v is not None:
+        assert rel_l2(v.cpu().numpy(), qv) <= 2e-3
+
+
+# ------------------------------------------------------------------ one minibatch: loss and gradients
+def _oracle_inputs(cfg, ro, lrn):
+    fr = flat_rollout(ro)
+    adv, ret = orc.gae(ro["reward"], ro["done"], ro["value"], ro["last_value"], cfg["hp"]["gamma"], cfg["hp"]["lam"])
+    return fr, adv.reshape(-1), ret.reshape(-1)
+
+
+GRAD_CASES = [(0, 64, 16, 0), (0, 64, 16, 100), (1, 40, 4, 0), (2, 12, 4, 0), (2, 12, 4, 20)]
+
+
+@pytest.mark.parametrize("ci,N,T,chunk", GRAD_CASES)
+def test_ppo_single_minibatch_gradients(L, ci, N, T, chunk):
+    torch = _torch()
+    cfg = configs.get_config(ci, num_envs=N, horizon=T)
+    lrn, ro, params = _setup(L, cfg, max_chunk=chunk)
+    hp = dict(cfg["hp"], epochs=1, minibatches=1, seed=3)
+    lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
+    st = lrn.update(hp)[0]
+    g = lrn.get_grads()
+    fr, adv, ret = _oracle_inputs(cfg, ro, lrn)
+    args = (cfg["net"], params, fr["obs"], fr["proprio"], fr["action"], fr["logp_old"], fr["value"], adv, ret)
+    kw = dict(clip_eps=hp["clip_eps"], vclip_eps=hp["vclip_eps"], vf_coef=hp["vf_coef"], ent_coef=hp["ent_coef"])
+    ost, og = orc.ppo_loss_grad(*args, **kw)          # exact fp64
+    with orc.quant(1):
+        qst, qg = orc.ppo_loss_grad(*args, **kw)      # bf16 operands, fp64 accumulation
+    for ref in (ost, qst):
+        for k_gpu, k_or in (("pi_loss", "pi_loss"), ("v_loss", "v_loss"), ("entropy", "entropy"), ("approx_kl", "approx_kl"),
+                            ("clip_frac", "clip_frac"), ("total_loss", "total")):
+            assert abs(st[k_gpu] - ref[k_or]) <= TOL_BF16 * max(abs(ref[k_or]), 1e-3), (k_gpu, st[k_gpu], ref[k_or])
+    assert abs(st["grad_norm"] - qst["grad_norm"]) <= TOL_BF16 * qst["grad_norm"]
+    assert st["nonfinite"] == 0
+    errs = per_tensor_errors(cfg["net"], g, qg)
+    assert max(errs.values()) <= TOL_BF16, errs
+    # distance to the exact-arithmetic gradient: bf16 operand rounding on a noise-dominated batch gradient
+    loose = per_tensor_errors(cfg["net"], g, og)
+    assert max(loose.values()) <= 0.15, loose
+
+
+# ------------------------------------------------------------------ whole update
+def _compare_update(L, cfg, lrn, ro, params, out, stats):
+    errs = per_tensor_errors(cfg["net"], lrn.get_params(), out["params"])
+    assert max(errs.values()) <= TOL_BF16, errs
+    # the update itself (parameter change), compared as a direction and a size
+    d_gpu = lrn.get_params().astype(np.float64) - params
+    d_or = out["params"] - params
+    cos = float(d_gpu @ d_or / (np.linalg.norm(d_gpu) * np.linalg.norm(d_or)))
+    assert cos > 0.98, cos
+    for s, o in zip(stats, out["stats"]):
+        for k_gpu, k_or in (("pi_loss", "pi_loss"), ("v_loss", "v_loss"), ("total_loss", "total"), ("grad_norm", "grad_norm")):
+            assert abs(s[k_gpu] - o[k_or]) <= TOL_BF16 * max(abs(o[k_or]), 1e-3), (k_gpu, s[k_gpu], o[k_or])
+
+
+@pytest.mark.parametrize("ci,N,T", [(0, 64, 16), (1, 32, 4)])
+def test_ppo_update_matches_oracle(L, ci, N, T):
+    torch = _torch()
+    cfg = configs.get_config(ci, num_envs=N, horizon=T)
+    lrn, ro, params = _setup(L, cfg)
+    hp = dict(cfg["hp"], seed=11)
+    lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
+    stats = lrn.update(hp)
+    fr, adv, ret = _oracle_inputs(cfg, ro, lrn)
+    z = np.zeros_like(params, dtype=np.float64)
+    with orc.quant(1):
+        out = orc.ppo_update(cfg["net"], params, z, z, 0, fr["obs"], fr["proprio"], fr["action"], fr["logp_old"], fr["value"],
+                             adv, ret, hp, update_idx=0)
+    _compare_update(L, cfg, lrn, ro, params, out, stats)
+    assert rel_l2(lrn.get_grads(), out["grads_last"]) <= TOL_BF16
+    m, v, step, upd = lrn.get_opt_state()
+    assert step == out["step"] and upd == 1
+    assert rel_l2(m, out["m"]) <= TOL_BF16 and rel_l2(v, out["v"]) <= 2 * TOL_BF16
+
+
+def test_distill_update_matches_oracle(L):
+    cfg = configs.get_config(3, num_envs=8, horizon=4)
+    lrn, ro, params = _setup(L, cfg)
+    hp = dict(cfg["hp"], minibatches=2, seed=5)
+    stats = lrn.distill_update(hp)
+    fr = flat_rollout(ro)
+    z = np.zeros_like(params, dtype=np.float64)
+    with orc.quant(1):
+        out = orc.distill_update(cfg["net"], params, z, z, 0, fr["obs"], fr["proprio"], fr["action"], hp, update_idx=0)
+    errs = per_tensor_errors(cfg["net"], lrn.get_grads(), out["grads_last"])
+    assert max(errs.values()) <= TOL_BF16, errs
+    for s, o in zip(stats, out["stats"]):
+        assert abs(s["total_loss"] - o["total"]) <= TOL_BF16 * abs(o["total"])
+    errs = per_tensor_errors(cfg["net"], lrn.get_params(), out["params"])
+    assert max(errs.values()) <= TOL_BF16, errs
+
+
+# ------------------------------------------------------------------ host logic on a live context
+def test_call_order_and_argument_errors(L):
+    torch = _torch()
+    cfg = configs.get_config(0, num_envs=8, horizon=3)
+    lrn = L.Learner(cfg["net"], 8, 3, "fp32")
+    lv = torch.zeros(8, device="cuda")
+    with pytest.raises(L.LearnerError) as e:
+        lrn.gae(lv, 0.99, 0.95)
+    assert e.value.code == L.PPO_ESTATE
+    ro = synth.rollout(cfg)
+    fill_learner(lrn, cfg, ro)
+    with pytest.raises(L.LearnerError) as e:
+        lrn.update(dict(cfg["hp"], epochs=1, minibatches=1))
+    assert e.value.code == L.PPO_ESTATE
+    lrn.gae(lv, 0.99, 0.95)
+    with pytest.raises(L.LearnerError) as e:
+        lrn.update(dict(cfg["hp"], epochs=1, minibatches=5))
+    assert e.value.code == L.PPO_ESHAPE
+    with pytest.raises(L.LearnerError) as e:
+        lrn.update(dict(cfg["hp"], epochs=1, minibatches=1, lr=float("nan")))
+    assert e.value.code == L.PPO_EINVAL
+    with pytest.raises(L.LearnerError) as e:
+        lrn.distill_update(dict(cfg["hp"], epochs=1, minibatches=1))
+    assert e.value.code == L.PPO_ESTATE
+    with pytest.raises(L.LearnerError) as e:
+        lrn.gae(lv, 1.5, 0.95)
+    assert e.value.code == L.PPO_EINVAL
+
+
+def test_update_is_deterministic_and_resumable(L):
+    torch = _torch()
+    cfg = configs.get_config(0, num_envs=64, horizon=16)
+    hp = dict(cfg["hp"], epochs=2, seed=7)
+    runs = []
+    for _ in range(2):
+        lrn, ro, params = _setup(L, cfg)
+        lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
+        lrn.update(hp)
+        runs.append((lrn.get_params(), lrn.get_opt_state(), lrn))
+    np.testing.assert_array_equal(runs[0][0], runs[1][0])
+    # checkpoint -> fresh context -> the next update is bit-identical
+    a = runs[0][2]
+    b = L.Learner(cfg["net"], cfg["num_envs"], cfg["horizon"], cfg["obs_dtype"])
+    b.set_params(runs[0][0])
+    m, v, step, upd = runs[0][1]
+    b.set_opt_state(m, v, step, upd)
+    ro = synth.rollout(cfg)
+    fill_learner(b, cfg, ro)
+    for x in (a, b):
+        x.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
+        x.update(hp)
+    np.testing.assert_array_equal(a.get_params(), b.get_params())

@@ -332,6 +332,39 @@ def test_gradients_central_finite_differences():
     assert bad <= 1
 
 
+@pytest.mark.parametrize("net,distill", [(TINY, False), (TINY_STEREO, True)])
+def test_bf16_operand_mode_matches_library_restatement(net, distill):
+    """Mode 1 of the oracle (bf16 operands, wide accumulation) against the same arithmetic restated with
+    library ops and custom rounding points; and it differs from the exact mode by bf16-sized amounts only."""
+    B = 16
+    b, params = _batch(net, B, 50), _params(net, 51)
+    p, sl = torch_ref.unpack(net, params)
+    mu, v, ls = torch_ref.forward_bf16_operands(net, p, sl, b["obs"], b["proprio"])
+    if distill:
+        loss = ((mu - torch.as_tensor(b["action"])) ** 2).mean()
+    else:
+        loss, _ = torch_ref.ppo_loss(mu, v, ls, b["action"], b["logp_old"], b["v_old"], b["adv"], b["ret"], 0.2, 0.3, 0.5, 0.01)
+    loss.backward()
+    with orc.quant(1):
+        if distill:
+            st, g = orc.distill_loss_grad(net, params, b["obs"], b["proprio"], b["action"])
+        else:
+            st, g = orc.ppo_loss_grad(net, params, b["obs"], b["proprio"], b["action"], b["logp_old"], b["v_old"],
+                                      b["adv"], b["ret"], clip_eps=0.2, vclip_eps=0.3, vf_coef=0.5, ent_coef=0.01)
+        omu, _ = orc.forward(net, params, b["obs"], b["proprio"])
+    assert orc.get_quant() == 0
+    np.testing.assert_allclose(omu, mu.detach().numpy(), rtol=1e-10, atol=1e-12)
+    assert abs(st["total"] - loss.item()) < 1e-10
+    np.testing.assert_allclose(g, p.grad.numpy(), rtol=1e-8, atol=1e-11)
+    if distill:
+        _, g0 = orc.distill_loss_grad(net, params, b["obs"], b["proprio"], b["action"])
+    else:
+        _, g0 = orc.ppo_loss_grad(net, params, b["obs"], b["proprio"], b["action"], b["logp_old"], b["v_old"],
+                                  b["adv"], b["ret"], clip_eps=0.2, vclip_eps=0.3, vf_coef=0.5, ent_coef=0.01)
+    rel = np.linalg.norm(g - g0) / np.linalg.norm(g0)
+    assert 1e-5 < rel < 0.1
+
+
 # ----------------------------------------------------------------- Adam
 def test_adam_closed_forms():
     g = np.array([0.3, -2.0, 1e-3, 0.0, 5.0])

@@ -52,3 +52,83 @@ def ppo_loss(mu, v, logstd, action, logp_old, v_old, adv, ret, clip_eps, vclip_e
         l_v = ((v - ret) ** 2).mean()
     ent = dist.entropy().sum(-1).mean()
     return l_pi + vf_coef * l_v - ent_coef * ent, dict(pi_loss=l_pi.item(), v_loss=l_v.item(), entropy=ent.item())
+
+
+# ---------------------------------------------------------------------------------------------
+# bf16-operand arithmetic restated with library ops: weights of every layer but the first conv,
+# stored activations and stored activation-gradients rounded to bf16, fp64 accumulation.
+def _r(x):
+    return x.to(torch.bfloat16).to(torch.float64)
+
+
+class _Conv(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, w, b, first):
+        ctx.save_for_backward(x, w)
+        ctx.first = first
+        return F.conv2d(x, w if first else _r(w), b, stride=2, padding=1)
+
+    @staticmethod
+    def backward(ctx, g):
+        x, w = ctx.saved_tensors
+        gw = torch.nn.grad.conv2d_weight(x, w.shape, g, stride=2, padding=1)
+        gx = None if ctx.first else torch.nn.grad.conv2d_input(x.shape, _r(w), g, stride=2, padding=1)
+        return gx, gw, g.sum((0, 2, 3)), None
+
+
+class _Lin(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, w, b):
+        ctx.save_for_backward(x, w)
+        return x @ _r(w).T + b
+
+    @staticmethod
+    def backward(ctx, g):
+        x, w = ctx.saved_tensors
+        return g @ _r(w), g.T @ x, g.sum(0)
+
+
+class _ReluStore(torch.autograd.Function):
+    """ReLU whose output is stored in bf16 and whose masked input-gradient is stored in bf16."""
+    @staticmethod
+    def forward(ctx, x):
+        y = _r(torch.relu(x))
+        ctx.save_for_backward(y)
+        return y
+
+    @staticmethod
+    def backward(ctx, g):
+        (y,) = ctx.saved_tensors
+        return _r(torch.where(y > 0, g, torch.zeros_like(g)))
+
+
+class _StoreGrad(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x):
+        return x.clone()
+
+    @staticmethod
+    def backward(ctx, g):
+        return _r(g)
+
+
+def forward_bf16_operands(net, p, sl, obs, proprio):
+    def get(name):
+        a, b, s = sl[name]
+        return p[a:b].reshape(s)
+    B = proprio.shape[0]
+    obs = _r(torch.as_tensor(np.asarray(obs, np.float64))).reshape(B, net["n_views"], net["in_c"], net["in_h"], net["in_w"])
+    feats = []
+    for v in range(net["n_views"]):
+        x = obs[:, v]
+        for i in range(len(net["conv_ch"])):
+            x = _ReluStore.apply(_Conv.apply(x, get(f"conv{i}.w"), get(f"conv{i}.b"), i == 0))
+        feats.append(x.reshape(B, -1))
+    x = torch.cat(feats + [_r(torch.as_tensor(np.asarray(proprio, np.float64)))], dim=1)
+    for i in range(len(net["fc_dim"])):
+        x = _ReluStore.apply(_Lin.apply(x, get(f"fc{i}.w"), get(f"fc{i}.b")))
+    mu = _StoreGrad.apply(_Lin.apply(x, get("mu.w"), get("mu.b")))
+    if net["has_value_head"]:
+        v = _StoreGrad.apply(_Lin.apply(x, get("v.w")[None], get("v.b"))[:, 0])
+        return mu, v, get("logstd")
+    return mu, None, None
