@@ -39,3 +39,16 @@ def fill_learner(lrn, cfg, ro, distill=False):
 def per_tensor_errors(net, got, want):
     """{tensor name: relative L2 error} over the canonical parameter layout."""
     return {name: rel_l2(got[a:b], want[a:b]) for name, (a, b, _) in synth.param_slices(net).items()}
+
+
+def per_tensor_param_errors(net, got, want, steps, lr):
+    """Relative L2 error of updated parameters per tensor.  The scale of a tensor is the larger of its
+    own norm and sqrt(n)*steps*lr, the farthest Adam can have moved it: a tensor initialised near zero
+    (the 0.01-scaled action head) consists almost entirely of Adam steps, whose per-element sign for
+    gradient elements below the bf16 noise floor is not determined by the arithmetic being compared."""
+    out = {}
+    for name, (a, b, _) in synth.param_slices(net).items():
+        w = np.asarray(want[a:b], np.float64)
+        scale = max(np.linalg.norm(w), np.sqrt(b - a) * steps * lr)
+        out[name] = float(np.linalg.norm(np.asarray(got[a:b], np.float64) - w) / scale)
+    return out
