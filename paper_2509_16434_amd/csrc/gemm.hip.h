@@ -288,12 +288,19 @@ __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int
   if (bias_partial && blockIdx.x == 0 && tid < 64 && n0 + tid < Nn) bias_partial[(int64_t)split * Nn + n0 + tid] = bsum;
 }
 
-// dst[i] = (accumulate ? dst[i] : 0) + sum_s partial[s][i], s ascending.
+// dst[i] = (accumulate ? dst[i] : 0) + sum_s partial[s][i]; four interleaved running sums
+// (s mod 4) combined as (s0+s1)+(s2+s3), always in the same order.
 __global__ void k_reduce_partials(const float* __restrict__ partial, int splits, int64_t n, float* __restrict__ dst,
                                   int accumulate) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
-  float s = accumulate ? dst[i] : 0.f;
-  for (int k = 0; k < splits; ++k) s += partial[(int64_t)k * n + i];
-  dst[i] = s;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int k = 0;
+  for (; k + 4 <= splits; k += 4) {
+    s0 += partial[(int64_t)k * n + i]; s1 += partial[(int64_t)(k + 1) * n + i];
+    s2 += partial[(int64_t)(k + 2) * n + i]; s3 += partial[(int64_t)(k + 3) * n + i];
+  }
+  for (; k < splits; ++k) s0 += partial[(int64_t)k * n + i];
+  float s = (s0 + s1) + (s2 + s3);
+  dst[i] = accumulate ? dst[i] + s : s;
 }

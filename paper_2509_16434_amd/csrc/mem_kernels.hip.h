@@ -200,68 +200,104 @@ __global__ __launch_bounds__(256) void k_conv1_fwd(ImgAddr in, int n_img, int H,
   }
 }
 
-// Weight/bias gradient of the first convolution: dW[co][k] = sum_m dY[m][co] * x[m][k].
-// Each block stages TILE pixels (their dY rows and im2col patches) in LDS; thread pairs (co,k)
-// accumulate over the tile.  Per-block partial sums go to `partial[block][Cout*K + Cout]`.
-template <int CIN>
+// Weight/bias gradient of the first convolution: dW[co][k] = sum_m dY[m][co] * x[m][k], db[co] =
+// sum_m dY[m][co].  TPP = Cout/COG threads share a pixel, each owning COG output channels and all
+// 9*CIN taps (+1 bias column) as a register tile; a block walks its pixel range, then the tiles
+// are summed across the wave with xor-shuffles, across the four waves through LDS, and written as
+// one partial per block (summed later in block order).
+template <int CIN, int COG>
 __global__ __launch_bounds__(256) void k_conv1_wgrad(ImgAddr in, int n_img, int H, int W, int Ho, int Wo, int Cout,
                                                      const bf16_t* __restrict__ dy, int pixels_per_block,
                                                      float* __restrict__ partial) {
-  constexpr int K = 9 * CIN, TILE = 64, KP = K + 1;  // last patch column is 1 (bias gradient)
-  extern __shared__ float smem[];                    // dys[TILE][Cout], xs[TILE][KP]
-  float* dys = smem; float* xs = smem + TILE * Cout;
-  const int npair = Cout * KP;
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};  // pairs tid, tid+256, ... (npair <= 1024)
-  int64_t M = (int64_t)n_img * Ho * Wo;
-  int64_t mbeg = (int64_t)blockIdx.x * pixels_per_block, mend = mbeg + pixels_per_block;
-  if (mend > M) mend = M;
-  const int hw = Ho * Wo;
-  for (int64_t mt = mbeg; mt < mend; mt += TILE) {
-    __syncthreads();
-    for (int i = threadIdx.x; i < TILE * Cout; i += 256) {
-      int r = i / Cout, c = i - r * Cout; int64_t m = mt + r;
-      dys[i] = (m < mend) ? bf2f(dy[m * Cout + c]) : 0.f;
-    }
-    for (int i = threadIdx.x; i < TILE * KP; i += 256) {
-      int r = i / KP, k = i - r * KP; int64_t m = mt + r;
-      float val = 0.f;
-      if (m < mend) {
-        if (k == K) val = 1.f;
-        else {
-          int img = (int)(m / hw), q = (int)(m - (int64_t)img * hw), oy = q / Wo, ox = q - oy * Wo;
-          int tap = k / CIN, c = k - tap * CIN, u = tap / 3, v = tap - 3 * u;
-          int iy = 2 * oy - 1 + u, ix = 2 * ox - 1 + v;
-          if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) val = bf2f(in.ptr(img)[((int64_t)iy * W + ix) * CIN + c]);
-        }
-      }
-      xs[i] = val;
-    }
-    __syncthreads();
+  constexpr int K = 9 * CIN, KP = K + 1;
+  __shared__ float wsum[4 * 64 * KP];
+  const int TPP = Cout / COG, PPI = 256 / TPP;
+  const int tid = threadIdx.x, cg = tid % TPP, pl = tid / TPP;
+  float acc[COG][KP];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int pr = threadIdx.x + j * 256;
-      if (pr < npair) {
-        int co = pr / KP, k = pr - co * KP;
-        float s = acc[j];
-        for (int r = 0; r < TILE; ++r) s += dys[r * Cout + co] * xs[r * KP + k];
-        acc[j] = s;
+  for (int j = 0; j < COG; ++j)
+#pragma unroll
+    for (int k = 0; k < KP; ++k) acc[j][k] = 0.f;
+  const int64_t M = (int64_t)n_img * Ho * Wo;
+  const int64_t mbeg = (int64_t)blockIdx.x * pixels_per_block;
+  const int64_t mend = (mbeg + pixels_per_block < M) ? mbeg + pixels_per_block : M;
+  int64_t m = mbeg + pl;
+  const int hw = Ho * Wo;
+  int img = (int)(m / hw), q = (int)(m - (int64_t)img * hw), oy = q / Wo, ox = q - oy * Wo;
+  const bf16_t* p = (m < mend) ? in.ptr(img) : nullptr;
+  for (; m < mend; m += PPI) {
+    float x[K];
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+#pragma unroll
+      for (int v = 0; v < 3; ++v) {
+        const int iy = 2 * oy - 1 + u, ix = 2 * ox - 1 + v;
+        const bool ok = (unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W;
+#pragma unroll
+        for (int c = 0; c < CIN; ++c) x[(u * 3 + v) * CIN + c] = ok ? bf2f(p[((int64_t)iy * W + ix) * CIN + c]) : 0.f;
       }
+    float d[COG];
+    const bf16_t* dp = dy + m * Cout + cg * COG;
+    if constexpr (COG == 8) {
+      uint4 r = *reinterpret_cast<const uint4*>(dp);
+      const uint32_t w4[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { d[2 * j] = __uint_as_float(w4[j] << 16); d[2 * j + 1] = __uint_as_float(w4[j] & 0xffff0000u); }
+    } else {
+      uint2 r = *reinterpret_cast<const uint2*>(dp);
+      d[0] = __uint_as_float(r.x << 16); d[1] = __uint_as_float(r.x & 0xffff0000u);
+      d[2] = __uint_as_float(r.y << 16); d[3] = __uint_as_float(r.y & 0xffff0000u);
+    }
+#pragma unroll
+    for (int j = 0; j < COG; ++j) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) acc[j][k] += d[j] * x[k];
+      acc[j][K] += d[j];
+    }
+    // next pixel of this thread
+    ox += PPI;
+    while (ox >= Wo) { ox -= Wo; ++oy; }
+    if (oy >= Ho) {
+      while (oy >= Ho) { oy -= Ho; ++img; }
+      p = (m + PPI < mend) ? in.ptr(img) : nullptr;
     }
   }
-  float* P = partial + (int64_t)blockIdx.x * npair;
+  // sum over the lanes of the wave that share cg (lane = (pl % (64/TPP)) * TPP + cg)
 #pragma unroll
-  for (int j = 0; j < 4; ++j) { int pr = threadIdx.x + j * 256; if (pr < npair) P[pr] = acc[j]; }
+  for (int j = 0; j < COG; ++j)
+#pragma unroll
+    for (int k = 0; k < KP; ++k) {
+      float v = acc[j][k];
+      for (int off = TPP; off < 64; off <<= 1) v += __shfl_xor(v, off);
+      acc[j][k] = v;
+    }
+  const int lane = tid & 63, wave = tid >> 6, npair = Cout * KP;
+  if (lane < TPP) {
+#pragma unroll
+    for (int j = 0; j < COG; ++j)
+#pragma unroll
+      for (int k = 0; k < KP; ++k) wsum[wave * npair + (cg * COG + j) * KP + k] = acc[j][k];
+  }
+  __syncthreads();
+  float* P = partial + (int64_t)blockIdx.x * npair;
+  for (int pr = tid; pr < npair; pr += 256) P[pr] = (wsum[pr] + wsum[npair + pr]) + (wsum[2 * npair + pr] + wsum[3 * npair + pr]);
 }
-// Sum conv1 partials in block order: partial[nb][Cout][K+1] -> gw[Cout][K], gb[Cout].
-__global__ void k_conv1_wgrad_reduce(const float* __restrict__ partial, int nb, int Cout, int K, float* __restrict__ gw,
-                                     float* __restrict__ gb, int accumulate) {
-  int pr = blockIdx.x * blockDim.x + threadIdx.x, KP = K + 1;
-  if (pr >= Cout * KP) return;
-  int co = pr / KP, k = pr - co * KP;
-  float* dst = (k == K) ? gb + co : gw + co * K + k;
-  float s = accumulate ? *dst : 0.f;
-  for (int b = 0; b < nb; ++b) s += partial[(int64_t)b * Cout * KP + pr];
-  *dst = s;
+// Sum conv1 partials: partial[nb][Cout][K+1] -> gw[Cout][K], gb[Cout].  One block per output
+// element; strided partial sums, then a fixed-order tree.
+__global__ __launch_bounds__(256) void k_conv1_wgrad_reduce(const float* __restrict__ partial, int nb, int Cout, int K,
+                                                            float* __restrict__ gw, float* __restrict__ gb, int accumulate) {
+  __shared__ float red[256];
+  const int pr = blockIdx.x, KP = K + 1, npair = Cout * KP, tid = threadIdx.x;
+  float s = 0.f;
+  for (int b = tid; b < nb; b += 256) s += partial[(int64_t)b * npair + pr];
+  red[tid] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) { if (tid < w) red[tid] += red[tid + w]; __syncthreads(); }
+  if (tid == 0) {
+    const int co = pr / KP, k = pr - co * KP;
+    float* dst = (k == K) ? gb + co : gw + co * K + k;
+    *dst = (accumulate ? *dst : 0.f) + red[0];
+  }
 }
 
 // ---------------------------------------------------------------- gather of small per-sample data
@@ -455,12 +491,17 @@ __global__ __launch_bounds__(256) void k_adam(int64_t n, float* __restrict__ p, 
   for (int s = 128; s > 0; s >>= 1) { if (tid < s) red[tid] += red[tid + s]; __syncthreads(); }
   if (tid == 0) sq_part[blockIdx.x] = red[0];
 }
-__global__ void k_gnorm_finalize(const float* __restrict__ sq_part, int nb, DevStats* __restrict__ st) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    float s = 0.f;
-    for (int b = 0; b < nb; ++b) s += sq_part[b];
-    st->grad_norm = sqrtf(s);
-    if (!isfinite(s)) st->nonfinite = 1;
+__global__ __launch_bounds__(256) void k_gnorm_finalize(const float* __restrict__ sq_part, int nb, DevStats* __restrict__ st) {
+  __shared__ float red[256];
+  const int tid = threadIdx.x;
+  float s = 0.f;
+  for (int b = tid; b < nb; b += 256) s += sq_part[b];
+  red[tid] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) { if (tid < w) red[tid] += red[tid + w]; __syncthreads(); }
+  if (tid == 0) {
+    st->grad_norm = sqrtf(red[0]);
+    if (!isfinite(red[0])) st->nonfinite = 1;
   }
 }
 __global__ void k_cast_bf16(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n) {

@@ -155,7 +155,7 @@ int validate_desc(const ppo_net_desc* d) {
   if (d->n_conv < 2 || d->n_conv > PPO_MAX_LAYERS) return fail(nullptr, PPO_ESHAPE, "n_conv must be 2..%d", PPO_MAX_LAYERS);
   for (int i = 0; i < d->n_conv; ++i)
     if (d->conv_ch[i] < 8 || d->conv_ch[i] % 8 || d->conv_ch[i] > 1024) return fail(nullptr, PPO_ESHAPE, "conv_ch[%d] must be a multiple of 8 in 8..1024", i);
-  if (d->conv_ch[0] * (9 * d->in_c + 1) > 1024) return fail(nullptr, PPO_ESHAPE, "conv_ch[0]*(9*in_c+1) must be <= 1024");
+  if (d->conv_ch[0] != 8 && d->conv_ch[0] != 16 && d->conv_ch[0] != 32 && d->conv_ch[0] != 64) return fail(nullptr, PPO_ESHAPE, "conv_ch[0] must be 8, 16, 32 or 64");
   if (d->n_fc < 1 || d->n_fc > PPO_MAX_LAYERS) return fail(nullptr, PPO_ESHAPE, "n_fc must be 1..%d", PPO_MAX_LAYERS);
   for (int i = 0; i < d->n_fc; ++i)
     if (d->fc_dim[i] < 8 || d->fc_dim[i] % 8 || d->fc_dim[i] > 16384) return fail(nullptr, PPO_ESHAPE, "fc_dim[%d] must be a multiple of 8 in 8..16384", i);
@@ -290,7 +290,7 @@ int launch_wgrad(Ctx* c, const DL& dl, const AL& al, int Nn, int Kk, int M, floa
   if (M <= 0) return PPO_OK;
   const char* what = name.c_str();
   const int tiles = cdiv(Kk, 64) * cdiv(Nn, 64);
-  int splits = cdiv(1536, tiles);
+  int splits = cdiv(1024, tiles);
   const int max_by_rows = cdiv(M, 256);
   if (splits > max_by_rows) splits = max_by_rows;
   const int64_t per = (int64_t)Nn * Kk;
@@ -463,19 +463,19 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
     const int Co = c->cC[1], Ho = c->cH[1], Wo = c->cW[1], K = 9 * c->cC[0];
     int64_t M = (int64_t)nimg * Ho * Wo;
     const int npair = Co * (K + 1);
+    const int cog = c->cC[0] == 1 ? 8 : 4, ppi = 256 / (Co / cog);
     int64_t max_blocks = c->partial_elems / npair;
     if (max_blocks > 2048) max_blocks = 2048;
     int64_t ppb = (M + max_blocks - 1) / max_blocks;
-    ppb = (ppb + 63) / 64 * 64;
+    ppb = (ppb + ppi - 1) / ppi * ppi;
     int nblk = cdiv(M, ppb);
-    size_t sh = (size_t)(64 * Co + 64 * (K + 1)) * sizeof(float);
     ProfScope ps(c, "conv_wgrad.0", 2.0 * (double)M * Co * (K + 1), 2.0 * ((double)M * Co + (double)nimg * c->img_elems));
     if (c->cC[0] == 1)
-      hipLaunchKernelGGL((k_conv1_wgrad<1>), dim3(nblk), dim3(256), sh, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->gbuf[cur], (int)ppb, c->partial);
+      hipLaunchKernelGGL((k_conv1_wgrad<1, 8>), dim3(nblk), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->gbuf[cur], (int)ppb, c->partial);
     else
-      hipLaunchKernelGGL((k_conv1_wgrad<3>), dim3(nblk), dim3(256), sh, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->gbuf[cur], (int)ppb, c->partial);
+      hipLaunchKernelGGL((k_conv1_wgrad<3, 4>), dim3(nblk), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->gbuf[cur], (int)ppb, c->partial);
     LAUNCHCHK(c, "k_conv1_wgrad");
-    hipLaunchKernelGGL(k_conv1_wgrad_reduce, dim3(cdiv(npair, 256)), dim3(256), 0, c->stream, c->partial, nblk, Co, K, c->g + c->convW[0], c->g + c->convB[0], acc ? 1 : 0);
+    hipLaunchKernelGGL(k_conv1_wgrad_reduce, dim3(npair), dim3(256), 0, c->stream, c->partial, nblk, Co, K, c->g + c->convW[0], c->g + c->convB[0], acc ? 1 : 0);
     LAUNCHCHK(c, "k_conv1_wgrad_reduce");
   }
   return PPO_OK;
@@ -535,7 +535,7 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
       hipLaunchKernelGGL(k_adam, dim3(c->adam_blocks), dim3(256), 0, c->stream, c->total, c->p, c->m, c->v, c->g, c->shadow, hp->lr, hp->beta1, hp->beta2,
                          hp->adam_eps, (float)(1.0 / c1), (float)(1.0 / c2), c->sq_part);
       LAUNCHCHK(c, "k_adam");
-      hipLaunchKernelGGL(k_gnorm_finalize, dim3(1), dim3(64), 0, c->stream, c->sq_part, c->adam_blocks, c->dstats + k);
+      hipLaunchKernelGGL(k_gnorm_finalize, dim3(1), dim3(256), 0, c->stream, c->sq_part, c->adam_blocks, c->dstats + k);
       LAUNCHCHK(c, "k_gnorm_finalize");
       }
       rc = repack_weights(c);
@@ -593,7 +593,7 @@ int create_impl(Ctx* c) {
   int64_t pe = 2048LL * c->cC[1] * (9 * c->cC[0] + 1), bpe = 0;
   auto want = [&](int Nn, int Kk, int64_t M) {
     int tiles = cdiv(Kk, 64) * cdiv(Nn, 64);
-    int splits = cdiv(1536, tiles), mr = cdiv(M, 256);
+    int splits = cdiv(1024, tiles), mr = cdiv(M, 256);
     if (splits > mr) splits = mr;
     if (splits < 1) splits = 1;
     if ((int64_t)splits * Nn * Kk > pe) pe = (int64_t)splits * Nn * Kk;
