@@ -14,15 +14,33 @@
 __device__ __forceinline__ uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
 
 // ---------------------------------------------------------------- A-row loaders
+// Every loader offers row(m) -> Row, load(Row, k) -> 8 consecutive k of that row (zero outside),
+// advance(Row&, delta, M) -> the row delta further on without integer division (weight-gradient
+// kernel), and cls(z) -> the per-grid.z parameter set (row count M, depth K, weight matrix).
+
 // Rows of a channel-last tensor: row m = (img, q) with img = m / HW, q = m % HW, each row C
 // elements wide, images addressed through ImgAddr (plain matrices: HW = 1, V = 1, stride_b = lda).
 struct ARows {
   ImgAddr a; int HW, C, M, K;
-  struct Row { const bf16_t* p; };
+  bool plain;  // HW == 1, one view, no gather: consecutive rows are stride_b apart
+  struct Row { const bf16_t* p; int img, q; };
+  struct Cls { int M, K; };
+  __device__ __forceinline__ Cls cls(int) const { Cls c; c.M = M; c.K = K; return c; }
+  __device__ __forceinline__ Row row(int m, const Cls&) const { return row(m); }
+  __device__ __forceinline__ uint4 load(const Row& r, int k, const Cls&) const { return load(r, k); }
+  __device__ __forceinline__ const bf16_t* bmat(const Cls&, const bf16_t* dflt) const { return dflt; }
   __device__ __forceinline__ Row row(int m) const {
-    Row r; r.p = nullptr;
-    if (m < M) { int img = m / HW, q = m - img * HW; r.p = a.ptr(img) + (int64_t)q * C; }
+    Row r; r.p = nullptr; r.img = 0; r.q = 0;
+    if (m < M) { r.img = m / HW; r.q = m - r.img * HW; r.p = a.ptr(r.img) + (int64_t)r.q * C; }
     return r;
+  }
+  __device__ __forceinline__ void advance(Row& r, int delta, int m_new) const {
+    if (m_new >= M) { r.p = nullptr; return; }
+    if (plain) { r.p += (int64_t)delta * a.stride_b; return; }
+    r.q += delta;
+    if (r.q < HW) { r.p += (int64_t)delta * C; return; }
+    while (r.q >= HW) { r.q -= HW; ++r.img; }
+    r.p = a.ptr(r.img) + (int64_t)r.q * C;
   }
   __device__ __forceinline__ uint4 load(const Row& r, int k) const {
     if (!r.p || k >= K) return zero16();
@@ -31,104 +49,141 @@ struct ARows {
 };
 
 // Row m = (img, oy, ox) of the im2col matrix of a channel-last image; k = (u*3+v)*Cin + ci.
+// Cin is a power of two (lc = log2 Cin).
 struct AConvFwd {
-  ImgAddr in; int H, W, Cin, Ho, Wo, M, K;
-  struct Row { const bf16_t* p; int iy0, ix0; };
+  ImgAddr in; int H, W, Cin, lc, Ho, Wo, M, K;
+  struct Row { const bf16_t* p; int iy0, ix0, img; };
+  struct Cls { int M, K; };
+  __device__ __forceinline__ Cls cls(int) const { Cls c; c.M = M; c.K = K; return c; }
+  __device__ __forceinline__ Row row(int m, const Cls&) const { return row(m); }
+  __device__ __forceinline__ uint4 load(const Row& r, int k, const Cls&) const { return load(r, k); }
+  __device__ __forceinline__ const bf16_t* bmat(const Cls&, const bf16_t* dflt) const { return dflt; }
   __device__ __forceinline__ Row row(int m) const {
-    Row r; r.p = nullptr; r.iy0 = 0; r.ix0 = 0;
+    Row r; r.p = nullptr; r.iy0 = 0; r.ix0 = 0; r.img = 0;
     if (m < M) {
       int hw = Ho * Wo, img = m / hw, q = m - img * hw, oy = q / Wo, ox = q - oy * Wo;
-      r.p = in.ptr(img); r.iy0 = 2 * oy - 1; r.ix0 = 2 * ox - 1;
+      r.p = in.ptr(img); r.iy0 = 2 * oy - 1; r.ix0 = 2 * ox - 1; r.img = img;
     }
     return r;
   }
+  __device__ __forceinline__ void advance(Row& r, int delta, int m_new) const {
+    if (m_new >= M) { r.p = nullptr; return; }
+    r.ix0 += 2 * delta;
+    if (r.ix0 < 2 * Wo - 1) return;
+    while (r.ix0 >= 2 * Wo - 1) { r.ix0 -= 2 * Wo; r.iy0 += 2; }
+    if (r.iy0 >= 2 * Ho - 1) {
+      while (r.iy0 >= 2 * Ho - 1) { r.iy0 -= 2 * Ho; ++r.img; }
+      r.p = in.ptr(r.img);
+    }
+  }
   __device__ __forceinline__ uint4 load(const Row& r, int k) const {
     if (!r.p || k >= K) return zero16();
-    int tap = k / Cin, ci = k - tap * Cin, u = tap / 3, v = tap - 3 * u;
+    int tap = k >> lc, ci = k & (Cin - 1), u = tap / 3, v = tap - 3 * u;
     int iy = r.iy0 + u, ix = r.ix0 + v;
     if ((unsigned)iy >= (unsigned)H || (unsigned)ix >= (unsigned)W) return zero16();
-    return *reinterpret_cast<const uint4*>(r.p + ((int64_t)iy * W + ix) * Cin + ci);
+    return *reinterpret_cast<const uint4*>(r.p + (((int64_t)iy * W + ix) << lc) + ci);
   }
 };
 
-// Transposed convolution, one input-pixel parity class (py, px): rows are the input pixels
-// (img, 2a+py, 2b+px); k = (tu*nv+tv)*Cout + co runs over the 1, 2 or 4 kernel taps that reach
-// this class and the output channels.  Tap tu of an odd row is u = 2*tu (reads output row
-// a+1-tu); an even row has the single tap u = 1 (output row a).  Same along x.
+// Transposed convolution, the four input-pixel parity classes (py, px) = (z >> 1, z & 1) selected by
+// grid.z: rows are the input pixels (img, 2a+py, 2b+px); k = (tu*nv+tv)*Cout + co runs over the 1,
+// 2 or 4 kernel taps that reach this class and the output channels (Cout a power of two).  Tap tu
+// of an odd row is u = 2*tu (reads output row a+1-tu); an even row has the single tap u = 1
+// (output row a).  Same along x.  Each class has its own packed weight matrix.
 struct AConvDgrad {
-  ImgAddr dy; int Ho, Wo, Cout, Ha, Wa, py, px, nv, M, K;
+  ImgAddr dy; int Ho, Wo, Cout, lco, H, W, dy_imgs;
+  const bf16_t *w00, *w01, *w10, *w11;  // packed weights of class (py, px)
   struct Row { const bf16_t* p; int a, b; };
-  __device__ __forceinline__ Row row(int m) const {
+  struct Cls { int Ha, Wa, py, px, M, K; const bf16_t* w; };
+  __device__ __forceinline__ Cls cls(int z) const {
+    Cls c; c.py = z >> 1; c.px = z & 1;
+    c.Ha = (H - c.py + 1) >> 1; c.Wa = (W - c.px + 1) >> 1;
+    c.M = dy_imgs * c.Ha * c.Wa; c.K = ((1 + c.py) * (1 + c.px)) << lco;
+    c.w = c.py ? (c.px ? w11 : w10) : (c.px ? w01 : w00);
+    return c;
+  }
+  __device__ __forceinline__ const bf16_t* bmat(const Cls& c, const bf16_t*) const { return c.w; }
+  __device__ __forceinline__ Row row(int m, const Cls& c) const {
     Row r; r.p = nullptr; r.a = 0; r.b = 0;
-    if (m < M) {
-      int hw = Ha * Wa, img = m / hw, q = m - img * hw;
-      r.a = q / Wa; r.b = q - r.a * Wa; r.p = dy.ptr(img);
+    if (m < c.M) {
+      int hw = c.Ha * c.Wa, img = m / hw, q = m - img * hw;
+      r.a = q / c.Wa; r.b = q - r.a * c.Wa; r.p = dy.ptr(img);
     }
     return r;
   }
-  __device__ __forceinline__ uint4 load(const Row& r, int k) const {
-    if (!r.p || k >= K) return zero16();
-    int t = k / Cout, co = k - t * Cout, tu = t / nv, tv = t - tu * nv;
-    int oy = r.a + (py ? 1 - tu : 0), ox = r.b + (px ? 1 - tv : 0);
+  __device__ __forceinline__ uint4 load(const Row& r, int k, const Cls& c) const {
+    if (!r.p || k >= c.K) return zero16();
+    int t = k >> lco, co = k & (Cout - 1), tu = c.px ? (t >> 1) : t, tv = c.px ? (t & 1) : 0;
+    int oy = r.a + (c.py ? 1 - tu : 0), ox = r.b + (c.px ? 1 - tv : 0);
     if (oy >= Ho || ox >= Wo) return zero16();
-    return *reinterpret_cast<const uint4*>(r.p + ((int64_t)oy * Wo + ox) * Cout + co);
+    return *reinterpret_cast<const uint4*>(r.p + (((int64_t)oy * Wo + ox) << lco) + co);
   }
 };
 
 // ---------------------------------------------------------------- epilogues
-// Output rows use the same (img, q) addressing as ARows; optional bias, ReLU, and a
-// ReLU-derivative mask read from `mask` at the output's own offset.
-template <typename OutT, bool BIAS, bool RELU, bool MASK>
-struct EpRows {
-  OutT* out; int64_t stride_b, stride_v; int V, HW, C; const float* bias; const bf16_t* mask; int M, N;
-  __device__ __forceinline__ int64_t row_offset(int m) const {
+// Output row addressing: the same (img, q) scheme as ARows ...
+struct MapRows {
+  int64_t stride_b, stride_v; int V, HW, C, M;
+  struct Cls {};
+  __device__ __forceinline__ Cls cls(int) const { return Cls(); }
+  __device__ __forceinline__ int64_t row_offset(int m, const Cls&) const {
     if (m >= M) return -1;
     int img = m / HW, q = m - img * HW, b = img / V, v = img - b * V;
     return (int64_t)b * stride_b + (int64_t)v * stride_v + (int64_t)q * C;
   }
-  __device__ __forceinline__ void store(int64_t off, int n, float v) const {
-    if (n >= N) return;
-    if (BIAS) v += bias[n];
-    if (RELU) v = v > 0.f ? v : 0.f;
-    if (MASK) { if (!(bf2f(mask[off + n]) > 0.f)) v = 0.f; }
-    if (sizeof(OutT) == 2) reinterpret_cast<bf16_t*>(out)[off + n] = f2bf(v);
-    else reinterpret_cast<float*>(out)[off + n] = v;
+};
+// ... or the input pixels of one parity class of a transposed convolution.
+struct MapDgrad {
+  int64_t stride_b, stride_v; int V, H, W, Cin, imgs;
+  struct Cls { int Ha, Wa, py, px, M; };
+  __device__ __forceinline__ Cls cls(int z) const {
+    Cls c; c.py = z >> 1; c.px = z & 1;
+    c.Ha = (H - c.py + 1) >> 1; c.Wa = (W - c.px + 1) >> 1; c.M = imgs * c.Ha * c.Wa;
+    return c;
+  }
+  __device__ __forceinline__ int64_t row_offset(int m, const Cls& c) const {
+    if (m >= c.M) return -1;
+    int hw = c.Ha * c.Wa, img = m / hw, q = m - img * hw, a = q / c.Wa, bb = q - a * c.Wa, b = img / V, v = img - b * V;
+    return (int64_t)b * stride_b + (int64_t)v * stride_v + ((int64_t)(2 * a + c.py) * W + (2 * bb + c.px)) * Cin;
   }
 };
-
-// Output rows are the input pixels of one parity class of a transposed convolution; the
-// result is masked by the ReLU derivative of the activation stored at the same address.
-struct EpConvDgrad {
-  ImgAddrW out; ImgAddr act; int H, W, Cin, Ha, Wa, py, px, M;
-  __device__ __forceinline__ int64_t row_offset(int m) const {
-    if (m >= M) return -1;
-    int hw = Ha * Wa, img = m / hw, q = m - img * hw, a = q / Wa, b = q - a * Wa;
-    int64_t pix = ((int64_t)(2 * a + py) * W + (2 * b + px)) * Cin;
-    // out and act share one addressing scheme; keep the image base in the offset
-    return (out.ptr(img) - out.base) + pix;
-  }
-  __device__ __forceinline__ void store(int64_t off, int n, float v) const {
-    if (n >= Cin) return;
-    if (!(bf2f(act.base[off + n]) > 0.f)) v = 0.f;
-    out.base[off + n] = f2bf(v);
-  }
+// out[off + n] = f(acc): optional bias, ReLU, and ReLU-derivative mask read from `mask` at the
+// output's own offset (the stored activation whose gradient is being formed).
+template <class MAP, typename OutT, bool BIAS, bool RELU, bool MASK>
+struct Ep {
+  typedef OutT out_t;
+  static constexpr bool kBias = BIAS, kRelu = RELU, kMask = MASK;
+  MAP map; OutT* out; const float* bias; const bf16_t* mask; int N;
 };
 
 // ---------------------------------------------------------------- C = A * B^T
-// B is a plain [N][K] matrix (row stride ldb).  256 threads = 4 waves laid out WGM x WGN, each
-// computing TM x TN 32x32 MFMA tiles.  K is walked in steps of 32 through double-buffered LDS.
+// B is a plain [N][K] matrix (row stride ldb; loaders with per-class weights override it).  256
+// threads = 4 waves laid out WGM x WGN, each computing TM x TN 32x32 MFMA tiles.  K is walked in
+// steps of 32 through double-buffered LDS.  bf16 results are staged through LDS and leave as
+// 16-byte row segments.
 template <int BM, int BN, int WGM, int WGN, class AL, class EP>
-__global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ Bm, int64_t ldb, int N, int K, EP ep) {
+__global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ Bm_, int64_t ldb_, int N, EP ep) {
   constexpr int TM = BM / (WGM * 32), TN = BN / (WGN * 32);
   static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1, "tile shape");
-  constexpr int ACH = BM * 4 / 256, BCH = (BN * 4 + 255) / 256;  // 16-byte chunks per thread
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * GEMM_PITCH];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * GEMM_PITCH];
+  constexpr int ACH = (BM * 4 + 255) / 256, BCH = (BN * 4 + 255) / 256;  // 16-byte chunks per thread
+  constexpr int AB_ELEMS = 2 * (BM + BN) * GEMM_PITCH;
+  constexpr int SP = BN + 8;  // staging pitch (bf16 elements)
+  static_assert(BM * SP <= AB_ELEMS, "staging tile must fit in the operand buffers");
+  __shared__ __attribute__((aligned(16))) bf16_t smem[AB_ELEMS];
   __shared__ int64_t rowoff[BM];
+  bf16_t* As = smem;                         // [2][BM*PITCH]
+  bf16_t* Bs = smem + 2 * BM * GEMM_PITCH;   // [2][BN*PITCH]
+
+  const typename AL::Cls acls = al.cls(blockIdx.z);
+  const auto mcls = ep.map.cls(blockIdx.z);
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  if (m0 >= acls.M) return;
+  const int K = acls.K;
+  const bf16_t* Bm = al.bmat(acls, Bm_);
+  const int64_t ldb = (Bm == Bm_) ? ldb_ : (int64_t)K;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
 
   typename AL::Row arow[ACH];
   int a_r[ACH], a_k[ACH];
@@ -136,7 +191,7 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
   for (int c = 0; c < ACH; ++c) {
     int ch = tid + c * 256;
     a_r[c] = ch >> 2; a_k[c] = (ch & 3) * 8;
-    arow[c] = al.row(m0 + a_r[c]);
+    arow[c] = al.row(a_r[c] < BM ? m0 + a_r[c] : acls.M, acls);
   }
   const bf16_t* brow[BCH]; int b_r[BCH], b_k[BCH];
 #pragma unroll
@@ -158,7 +213,7 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
   uint4 ra[ACH], rb[BCH];
   auto gload = [&](int k0) {
 #pragma unroll
-    for (int c = 0; c < ACH; ++c) ra[c] = al.load(arow[c], k0 + a_k[c]);
+    for (int c = 0; c < ACH; ++c) ra[c] = al.load(arow[c], k0 + a_k[c], acls);
 #pragma unroll
     for (int c = 0; c < BCH; ++c) {
       int k = k0 + b_k[c];
@@ -167,10 +222,11 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
   };
   auto sstore = [&](int buf) {
 #pragma unroll
-    for (int c = 0; c < ACH; ++c) *reinterpret_cast<uint4*>(&As[buf][a_r[c] * GEMM_PITCH + a_k[c]]) = ra[c];
+    for (int c = 0; c < ACH; ++c)
+      if (a_r[c] < BM) *reinterpret_cast<uint4*>(&As[buf * BM * GEMM_PITCH + a_r[c] * GEMM_PITCH + a_k[c]]) = ra[c];
 #pragma unroll
     for (int c = 0; c < BCH; ++c)
-      if (b_r[c] < BN) *reinterpret_cast<uint4*>(&Bs[buf][b_r[c] * GEMM_PITCH + b_k[c]]) = rb[c];
+      if (b_r[c] < BN) *reinterpret_cast<uint4*>(&Bs[buf * BN * GEMM_PITCH + b_r[c] * GEMM_PITCH + b_k[c]]) = rb[c];
   };
 
   const int nk = (K + GEMM_BK - 1) / GEMM_BK;
@@ -180,16 +236,18 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
     if (kt + 1 < nk) gload((kt + 1) * GEMM_BK);
+    const bf16_t* Ab = As + buf * BM * GEMM_PITCH;
+    const bf16_t* Bb = Bs + buf * BN * GEMM_PITCH;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       bf16x8_t a[TM], b[TN];
       const int kk = ks * 16 + (lane >> 5) * 8;
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        a[i] = *reinterpret_cast<const bf16x8_t*>(&As[buf][((wm * TM + i) * 32 + (lane & 31)) * GEMM_PITCH + kk]);
+        a[i] = *reinterpret_cast<const bf16x8_t*>(&Ab[((wm * TM + i) * 32 + (lane & 31)) * GEMM_PITCH + kk]);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        b[j] = *reinterpret_cast<const bf16x8_t*>(&Bs[buf][((wn * TN + j) * 32 + (lane & 31)) * GEMM_PITCH + kk]);
+        b[j] = *reinterpret_cast<const bf16x8_t*>(&Bb[((wn * TN + j) * 32 + (lane & 31)) * GEMM_PITCH + kk]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -199,108 +257,195 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
     __syncthreads();
   }
 
-  for (int r = tid; r < BM; r += 256) rowoff[r] = ep.row_offset(m0 + r);
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int r = tid; r < BM; r += 256) rowoff[r] = ep.map.row_offset(m0 + r, mcls);
+  typedef typename EP::out_t OutT;
+  if constexpr (sizeof(OutT) == 2) {
+    // stage the bf16 tile in LDS (the operand buffers are free now), then write 16-byte segments
+    bf16_t* stage = smem;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+      const int cl = (wn * TN + j) * 32 + (lane & 31), col = n0 + cl;
+      float bv = 0.f;
+      if (EP::kBias) bv = (col < N) ? ep.bias[col] : 0.f;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int rl = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        const int64_t off = rowoff[rl];
-        if (off >= 0) ep.store(off, col, acc[i][j][e]);
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int rl = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          float v = acc[i][j][e] + bv;
+          if (EP::kRelu) v = v > 0.f ? v : 0.f;
+          stage[rl * SP + cl] = f2bf(v);
+        }
+    }
+    __syncthreads();
+    constexpr int CPR = BN / 8;  // 16-byte chunks per row
+    bf16_t* out = reinterpret_cast<bf16_t*>(ep.out);
+    for (int ch = tid; ch < BM * CPR; ch += 256) {
+      const int rl = ch / CPR, cg = ch - rl * CPR, n = n0 + cg * 8;
+      const int64_t off = rowoff[rl];
+      if (off < 0 || n >= N) continue;
+      uint4 v = *reinterpret_cast<const uint4*>(&stage[rl * SP + cg * 8]);
+      if (n + 8 <= N) {
+        if (EP::kMask) {
+          // keep a half where the stored activation is > 0 (sign bit clear and not zero)
+          const uint4 mk = *reinterpret_cast<const uint4*>(ep.mask + off + n);
+          auto keep = [](uint32_t m) -> uint32_t {
+            return (((short)(m & 0xffffu) > 0) ? 0x0000ffffu : 0u) | (((short)(m >> 16) > 0) ? 0xffff0000u : 0u);
+          };
+          v.x &= keep(mk.x); v.y &= keep(mk.y); v.z &= keep(mk.z); v.w &= keep(mk.w);
+        }
+        *reinterpret_cast<uint4*>(out + off + n) = v;
+      } else {
+        for (int q = 0; q < 8 && n + q < N; ++q) {
+          bf16_t o = stage[rl * SP + cg * 8 + q];
+          if (EP::kMask) { if (!((short)ep.mask[off + n + q] > 0)) o = 0; }
+          out[off + n + q] = o;
+        }
       }
     }
+  } else {
+    __syncthreads();
+    float* out = reinterpret_cast<float*>(ep.out);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+        if (col >= N) continue;
+        const float bv = EP::kBias ? ep.bias[col] : 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int rl = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          const int64_t off = rowoff[rl];
+          if (off < 0) continue;
+          float v = acc[i][j][e] + bv;
+          if (EP::kRelu) v = v > 0.f ? v : 0.f;
+          if (EP::kMask) { if (!((short)ep.mask[off + col] > 0)) v = 0.f; }
+          out[off + col] = v;
+        }
+      }
+  }
 }
 
 // ---------------------------------------------------------------- weight gradient
 // G[n][k] (+)= sum_m Dy[m][n] * A[m][k]: both operands are row-major over the contracted index m,
 // so 16-byte chunks (8 consecutive n or k of one row m) are written transposed into LDS and the
-// MFMA operands are then read as 8 consecutive m.  Block tile 64 (n) x 64 (k), 32 rows of m per
-// step; grid.z splits the m range, each split writing its own fp32 partial tile (summed later in
-// a fixed order).  Block (x == 0) also accumulates the column sums of Dy (the bias gradient).
-template <class DL, class AL>
+// MFMA operands are then read as 8 consecutive m.  Block tile: 64 (n) x 128*KTW (k), 32 rows of m
+// per step; wave w owns the k-tiles w, w+4, ... (KTW of them) for both 32-row n-tiles, so Dy is
+// read once per 128*KTW columns of k.  grid.z splits the m range, each split writing its own fp32
+// partial tile (summed later in a fixed order).  Block (x == 0) also accumulates the column sums of
+// Dy (the bias gradient).  Rows are tracked incrementally (no integer division in the loop).
+template <int KTW, class DL, class AL>
 __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int M, int rows_per_split,
                                                float* __restrict__ partial, float* __restrict__ bias_partial) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ds[2][64 * GEMM_PITCH];
-  __shared__ __attribute__((aligned(16))) bf16_t Xs[2][64 * GEMM_PITCH];
+  constexpr int BKC = 128 * KTW;             // k columns per block
+  constexpr int XCH = BKC / 8 * 32 / 256;    // X chunks per thread per step (= KTW * 2)
+  __shared__ __attribute__((aligned(16))) bf16_t Ds[64 * GEMM_PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Xs[BKC * GEMM_PITCH];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wn = wave >> 1, wk = wave & 1;
-  const int k0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+  const int k0 = blockIdx.x * BKC, n0 = blockIdx.y * 64;
   const int split = blockIdx.z;
   const int mbeg = split * rows_per_split;
   const int mend = min(M, mbeg + rows_per_split);
-  const int ml = tid & 31, g8 = (tid >> 5) * 8;  // this thread's row within the step and its 8-wide column group
+  const int ml = tid & 31, g8 = (tid >> 5) * 8;  // this thread's row within the step and its first 8-wide column group
 
-  f32x16_t acc;
+  f32x16_t acc[KTW][2];
 #pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  for (int t = 0; t < KTW; ++t)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
   float bsum = 0.f;
 
-  uint4 rd, rx;
-  auto gload = [&](int mb) {
-    int m = mb + ml;
-    bool ok = m < mend;
-    typename DL::Row dr = dl.row(ok ? m : M);
-    typename AL::Row ar = al.row(ok ? m : M);
-    rd = dl.load(dr, n0 + g8);
-    rx = al.load(ar, k0 + g8);
-  };
-  auto sstore = [&](int buf) {
-    const bf16_t* d = reinterpret_cast<const bf16_t*>(&rd);
-    const bf16_t* x = reinterpret_cast<const bf16_t*>(&rx);
+  int m = mbeg + ml;
+  typename DL::Row dr = dl.row(m < mend ? m : M);
+  typename AL::Row ar = al.row(m < mend ? m : M);
+  uint4 rd, rx[XCH];
+  auto gload = [&]() {
+    const bool ok = m < mend;
+    rd = ok ? dl.load(dr, n0 + g8) : zero16();
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      Ds[buf][(g8 + j) * GEMM_PITCH + ml] = d[j];
-      Xs[buf][(g8 + j) * GEMM_PITCH + ml] = x[j];
+    for (int c = 0; c < XCH; ++c) rx[c] = ok ? al.load(ar, k0 + g8 + c * 64) : zero16();
+  };
+  auto sstore = [&]() {
+    const bf16_t* d = reinterpret_cast<const bf16_t*>(&rd);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) Ds[(g8 + j) * GEMM_PITCH + ml] = d[j];
+#pragma unroll
+    for (int c = 0; c < XCH; ++c) {
+      const bf16_t* x = reinterpret_cast<const bf16_t*>(&rx[c]);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) Xs[(g8 + c * 64 + j) * GEMM_PITCH + ml] = x[j];
     }
   };
   const int nsteps = (mend > mbeg) ? (mend - mbeg + 31) / 32 : 0;
-  if (nsteps > 0) { gload(mbeg); sstore(0); }
+  if (nsteps > 0) { gload(); sstore(); }
   __syncthreads();
   for (int st = 0; st < nsteps; ++st) {
-    const int buf = st & 1;
-    if (st + 1 < nsteps) gload(mbeg + (st + 1) * 32);
+    if (st + 1 < nsteps) {
+      m += 32;
+      dl.advance(dr, 32, m < mend ? m : M);
+      al.advance(ar, 32, m < mend ? m : M);
+      gload();
+    }
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       const int kk = ks * 16 + (lane >> 5) * 8;
-      bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&Ds[buf][(wn * 32 + (lane & 31)) * GEMM_PITCH + kk]);
-      bf16x8_t b = *reinterpret_cast<const bf16x8_t*>(&Xs[buf][(wk * 32 + (lane & 31)) * GEMM_PITCH + kk]);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+      const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(&Ds[(lane & 31) * GEMM_PITCH + kk]);
+      const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(&Ds[(32 + (lane & 31)) * GEMM_PITCH + kk]);
+#pragma unroll
+      for (int t = 0; t < KTW; ++t) {
+        const int ktile = wave + 4 * t;
+        if (k0 + ktile * 32 < Kk) {
+          const bf16x8_t b = *reinterpret_cast<const bf16x8_t*>(&Xs[(ktile * 32 + (lane & 31)) * GEMM_PITCH + kk]);
+          acc[t][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[t][0], 0, 0, 0);
+          acc[t][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[t][1], 0, 0, 0);
+        }
+      }
     }
     if (bias_partial && blockIdx.x == 0 && tid < 64) {
-      const bf16_t* r = &Ds[buf][tid * GEMM_PITCH];
+      const bf16_t* r = &Ds[tid * GEMM_PITCH];
 #pragma unroll
-      for (int m = 0; m < 32; ++m) bsum += bf2f(r[m]);
+      for (int q = 0; q < 32; ++q) bsum += bf2f(r[q]);
     }
-    if (st + 1 < nsteps) sstore(buf ^ 1);
+    __syncthreads();
+    if (st + 1 < nsteps) sstore();
     __syncthreads();
   }
   float* P = partial + (int64_t)split * Nn * Kk;
-  const int k = k0 + wk * 32 + (lane & 31);
 #pragma unroll
-  for (int e = 0; e < 16; ++e) {
-    const int n = n0 + wn * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-    if (n < Nn && k < Kk) P[(int64_t)n * Kk + k] = acc[e];
+  for (int t = 0; t < KTW; ++t) {
+    const int k = k0 + (wave + 4 * t) * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int n = n0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        if (n < Nn && k < Kk) P[(int64_t)n * Kk + k] = acc[t][i][e];
+      }
   }
   if (bias_partial && blockIdx.x == 0 && tid < 64 && n0 + tid < Nn) bias_partial[(int64_t)split * Nn + n0 + tid] = bsum;
 }
 
-// dst[i] = (accumulate ? dst[i] : 0) + sum_s partial[s][i]; four interleaved running sums
-// (s mod 4) combined as (s0+s1)+(s2+s3), always in the same order.
-__global__ void k_reduce_partials(const float* __restrict__ partial, int splits, int64_t n, float* __restrict__ dst,
-                                  int accumulate) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-  int k = 0;
-  for (; k + 4 <= splits; k += 4) {
-    s0 += partial[(int64_t)k * n + i]; s1 += partial[(int64_t)(k + 1) * n + i];
-    s2 += partial[(int64_t)(k + 2) * n + i]; s3 += partial[(int64_t)(k + 3) * n + i];
+// dst[i] = (accumulate ? dst[i] : 0) + sum_s partial[s][i].  A block covers 32 outputs with 8
+// lanes of splits each (lane j sums s = j, j+8, ... with two running sums); the 8 lane sums are
+// combined in a fixed order, so the result does not depend on scheduling.
+__global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ partial, int splits, int64_t n,
+                                                         float* __restrict__ dst, int accumulate) {
+  __shared__ float red[8][33];
+  const int o = threadIdx.x & 31, sl = threadIdx.x >> 5;
+  const int64_t i = (int64_t)blockIdx.x * 32 + o;
+  float s0 = 0.f, s1 = 0.f;
+  if (i < n) {
+    int k = sl;
+    for (; k + 8 < splits; k += 16) { s0 += partial[(int64_t)k * n + i]; s1 += partial[(int64_t)(k + 8) * n + i]; }
+    if (k < splits) s0 += partial[(int64_t)k * n + i];
   }
-  for (; k < splits; ++k) s0 += partial[(int64_t)k * n + i];
-  float s = (s0 + s1) + (s2 + s3);
-  dst[i] = accumulate ? dst[i] + s : s;
+  red[sl][o] = s0 + s1;
+  __syncthreads();
+  if (sl == 0 && i < n) {
+    float s = ((red[0][o] + red[1][o]) + (red[2][o] + red[3][o])) + ((red[4][o] + red[5][o]) + (red[6][o] + red[7][o]));
+    dst[i] = accumulate ? dst[i] + s : s;
+  }
 }

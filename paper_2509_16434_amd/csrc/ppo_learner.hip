@@ -154,7 +154,7 @@ int validate_desc(const ppo_net_desc* d) {
   if (d->conv_k != 3 || d->conv_stride != 2 || d->conv_pad != 1) return fail(nullptr, PPO_ESHAPE, "only 3x3 stride-2 pad-1 convolutions are supported");
   if (d->n_conv < 2 || d->n_conv > PPO_MAX_LAYERS) return fail(nullptr, PPO_ESHAPE, "n_conv must be 2..%d", PPO_MAX_LAYERS);
   for (int i = 0; i < d->n_conv; ++i)
-    if (d->conv_ch[i] < 8 || d->conv_ch[i] % 8 || d->conv_ch[i] > 1024) return fail(nullptr, PPO_ESHAPE, "conv_ch[%d] must be a multiple of 8 in 8..1024", i);
+    if (d->conv_ch[i] < 8 || d->conv_ch[i] > 1024 || (d->conv_ch[i] & (d->conv_ch[i] - 1))) return fail(nullptr, PPO_ESHAPE, "conv_ch[%d] must be a power of two in 8..1024", i);
   if (d->conv_ch[0] != 8 && d->conv_ch[0] != 16 && d->conv_ch[0] != 32 && d->conv_ch[0] != 64) return fail(nullptr, PPO_ESHAPE, "conv_ch[0] must be 8, 16, 32 or 64");
   if (d->n_fc < 1 || d->n_fc > PPO_MAX_LAYERS) return fail(nullptr, PPO_ESHAPE, "n_fc must be 1..%d", PPO_MAX_LAYERS);
   for (int i = 0; i < d->n_fc; ++i)
@@ -262,36 +262,54 @@ void build_geometry(Ctx* c) {
 inline int class_len(int n, int par) { return (n - par + 1) / 2; }
 
 // ---------------------------------------------------------------- launch helpers
+inline int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
+
 template <class AL, class EP>
-int launch_gemm(Ctx* c, const AL& al, int M, const bf16_t* Bm, int64_t ldb, int N, int K, const EP& ep, const std::string& name, double abytes) {
+int launch_gemm(Ctx* c, const AL& al, int M, const bf16_t* Bm, int64_t ldb, int N, int K, const EP& ep, const std::string& name, double abytes,
+                int zdim = 1, double flops = -1.0) {
   if (M <= 0) return PPO_OK;
   const char* what = name.c_str();
-  ProfScope ps(c, name, 2.0 * M * (double)N * K, abytes);
+  ProfScope ps(c, name, flops >= 0.0 ? flops : 2.0 * M * (double)N * K, abytes);
   dim3 blk(256);
   if (N > 64) {
-    dim3 grid(cdiv(M, 128), cdiv(N, 128));
-    hipLaunchKernelGGL((k_gemm<128, 128, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, K, ep);
+    if ((int64_t)cdiv(M, 128) * cdiv(N, 128) * zdim >= 256 || M <= 64) {
+      dim3 grid(cdiv(M, 128), cdiv(N, 128), zdim);
+      hipLaunchKernelGGL((k_gemm<128, 128, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);
+    } else {
+      dim3 grid(cdiv(M, 64), cdiv(N, 64), zdim);
+      hipLaunchKernelGGL((k_gemm<64, 64, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);
+    }
   } else if (N > 32) {
-    dim3 grid(cdiv(M, 128), 1);
-    hipLaunchKernelGGL((k_gemm<128, 64, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, K, ep);
+    if ((int64_t)cdiv(M, 128) * zdim >= 256 || M <= 64) {
+      dim3 grid(cdiv(M, 128), 1, zdim);
+      hipLaunchKernelGGL((k_gemm<128, 64, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);
+    } else {
+      dim3 grid(cdiv(M, 64), 1, zdim);
+      hipLaunchKernelGGL((k_gemm<64, 64, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);
+    }
   } else {
-    dim3 grid(cdiv(M, 128), 1);
-    hipLaunchKernelGGL((k_gemm<128, 32, 4, 1, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, K, ep);
+    dim3 grid(cdiv(M, 128), 1, zdim);
+    hipLaunchKernelGGL((k_gemm<128, 32, 4, 1, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);
   }
   LAUNCHCHK(c, what);
   return PPO_OK;
 }
 
 ImgAddr plain_rows(const bf16_t* base, int64_t ld) { ImgAddr a; a.base = base; a.idx = nullptr; a.stride_b = ld; a.stride_v = 0; a.V = 1; return a; }
+ARows plain_arows(const bf16_t* base, int64_t ld, int M, int K) {
+  ARows r; r.a = plain_rows(base, ld); r.HW = 1; r.C = 0; r.M = M; r.K = K; r.plain = true; return r;
+}
+MapRows plain_map(int64_t ld, int M) { MapRows m; m.stride_b = ld; m.stride_v = 0; m.V = 1; m.HW = 1; m.C = 0; m.M = M; return m; }
 
 // G[Nn][Kk] (+)= Dy^T * A over M rows, plus optional bias gradient gb[Nn].
 template <class DL, class AL>
 int launch_wgrad(Ctx* c, const DL& dl, const AL& al, int Nn, int Kk, int M, float* gw, float* gb, bool accumulate, const std::string& name, double abytes) {
   if (M <= 0) return PPO_OK;
   const char* what = name.c_str();
-  const int tiles = cdiv(Kk, 64) * cdiv(Nn, 64);
-  int splits = cdiv(1024, tiles);
-  const int max_by_rows = cdiv(M, 256);
+  const int ktw = Kk <= 128 ? 1 : (Kk <= 256 ? 2 : 3);
+  const int tiles = cdiv(Kk, 128 * ktw) * cdiv(Nn, 64);
+  int splits = cdiv(768, tiles);
+  const int max_by_rows = cdiv(M, 128);
   if (splits > max_by_rows) splits = max_by_rows;
   const int64_t per = (int64_t)Nn * Kk;
   if ((int64_t)splits * per > c->partial_elems) splits = (int)(c->partial_elems / per);
@@ -300,17 +318,20 @@ int launch_wgrad(Ctx* c, const DL& dl, const AL& al, int Nn, int Kk, int M, floa
   int rows = cdiv(M, splits);
   rows = (rows + 31) / 32 * 32;
   splits = cdiv(M, rows);
-  dim3 grid(cdiv(Kk, 64), cdiv(Nn, 64), splits);
+  dim3 grid(cdiv(Kk, 128 * ktw), cdiv(Nn, 64), splits);
   {
     ProfScope ps(c, name, 2.0 * M * (double)Nn * Kk, abytes);
-    hipLaunchKernelGGL((k_wgrad<DL, AL>), grid, dim3(256), 0, c->stream, dl, al, Nn, Kk, M, rows, c->partial, gb ? c->bias_partial : nullptr);
+    float* bp = gb ? c->bias_partial : nullptr;
+    if (ktw == 1) hipLaunchKernelGGL((k_wgrad<1, DL, AL>), grid, dim3(256), 0, c->stream, dl, al, Nn, Kk, M, rows, c->partial, bp);
+    else if (ktw == 2) hipLaunchKernelGGL((k_wgrad<2, DL, AL>), grid, dim3(256), 0, c->stream, dl, al, Nn, Kk, M, rows, c->partial, bp);
+    else hipLaunchKernelGGL((k_wgrad<3, DL, AL>), grid, dim3(256), 0, c->stream, dl, al, Nn, Kk, M, rows, c->partial, bp);
     LAUNCHCHK(c, what);
   }
   ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)splits + 1.0) * (double)per);
-  hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 256)), dim3(256), 0, c->stream, c->partial, splits, per, gw, accumulate ? 1 : 0);
+  hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 32)), dim3(256), 0, c->stream, c->partial, splits, per, gw, accumulate ? 1 : 0);
   LAUNCHCHK(c, what);
   if (gb) {
-    hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(Nn, 256)), dim3(256), 0, c->stream, c->bias_partial, splits, (int64_t)Nn, gb, accumulate ? 1 : 0);
+    hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(Nn, 32)), dim3(256), 0, c->stream, c->bias_partial, splits, (int64_t)Nn, gb, accumulate ? 1 : 0);
     LAUNCHCHK(c, what);
   }
   return PPO_OK;
@@ -368,12 +389,12 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n) {
   for (int l = 1; l < c->nconv; ++l) {
     AConvFwd al;
     al.in = conv_out_addr(c, l - 1, c->act[l - 1], nullptr);
-    al.H = c->cH[l]; al.W = c->cW[l]; al.Cin = c->cC[l]; al.Ho = c->cH[l + 1]; al.Wo = c->cW[l + 1];
+    al.H = c->cH[l]; al.W = c->cW[l]; al.Cin = c->cC[l]; al.lc = ilog2(al.Cin); al.Ho = c->cH[l + 1]; al.Wo = c->cW[l + 1];
     al.M = nimg * al.Ho * al.Wo; al.K = 9 * al.Cin;
     ImgAddr o = conv_out_addr(c, l, c->act[l], c->feat);
-    EpRows<bf16_t, true, true, false> ep;
-    ep.out = const_cast<bf16_t*>(o.base); ep.stride_b = o.stride_b; ep.stride_v = o.stride_v; ep.V = V;
-    ep.HW = al.Ho * al.Wo; ep.C = c->cC[l + 1]; ep.bias = c->p + c->convB[l]; ep.mask = nullptr; ep.M = al.M; ep.N = c->cC[l + 1];
+    Ep<MapRows, bf16_t, true, true, false> ep;
+    ep.map.stride_b = o.stride_b; ep.map.stride_v = o.stride_v; ep.map.V = V; ep.map.HW = al.Ho * al.Wo; ep.map.C = c->cC[l + 1]; ep.map.M = al.M;
+    ep.out = const_cast<bf16_t*>(o.base); ep.bias = c->p + c->convB[l]; ep.mask = nullptr; ep.N = c->cC[l + 1];
     double ab = 2.0 * ((double)nimg * al.H * al.W * al.Cin + (double)al.M * c->cC[l + 1] + (double)al.K * c->cC[l + 1]);
     int rc = launch_gemm(c, al, al.M, c->shadow + c->convW[l], al.K, c->cC[l + 1], al.K, ep, "conv_fwd." + std::to_string(l), ab);
     if (rc) return rc;
@@ -382,20 +403,18 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n) {
   LAUNCHCHK(c, "k_gather_proprio");
   const bf16_t* x = c->feat; int64_t ldx = c->feat_ld;
   for (int l = 0; l < c->nfc; ++l) {
-    ARows al; al.a = plain_rows(x, ldx); al.HW = 1; al.C = 0; al.M = n; al.K = c->fin[l];
-    EpRows<bf16_t, true, true, false> ep;
-    ep.out = c->fcact[l]; ep.stride_b = c->fout[l]; ep.stride_v = 0; ep.V = 1; ep.HW = 1; ep.C = 0;
-    ep.bias = c->p + c->fcB[l]; ep.mask = nullptr; ep.M = n; ep.N = c->fout[l];
+    ARows al = plain_arows(x, ldx, n, c->fin[l]);
+    Ep<MapRows, bf16_t, true, true, false> ep;
+    ep.map = plain_map(c->fout[l], n); ep.out = c->fcact[l]; ep.bias = c->p + c->fcB[l]; ep.mask = nullptr; ep.N = c->fout[l];
     double ab = 2.0 * ((double)n * c->fin[l] + (double)n * c->fout[l] + (double)c->fin[l] * c->fout[l]);
     int rc = launch_gemm(c, al, n, c->shadow + c->fcW[l], c->fin[l], c->fout[l], c->fin[l], ep, "fc_fwd." + std::to_string(l), ab);
     if (rc) return rc;
     x = c->fcact[l]; ldx = c->fout[l];
   }
   {
-    ARows al; al.a = plain_rows(x, ldx); al.HW = 1; al.C = 0; al.M = n; al.K = c->hid;
-    EpRows<float, true, false, false> ep;
-    ep.out = c->headout; ep.stride_b = HEAD_LD; ep.stride_v = 0; ep.V = 1; ep.HW = 1; ep.C = 0;
-    ep.bias = c->p + c->headB; ep.mask = nullptr; ep.M = n; ep.N = c->NH;
+    ARows al = plain_arows(x, ldx, n, c->hid);
+    Ep<MapRows, float, true, false, false> ep;
+    ep.map = plain_map(HEAD_LD, n); ep.out = c->headout; ep.bias = c->p + c->headB; ep.mask = nullptr; ep.N = c->NH;
     int rc = launch_gemm(c, al, n, c->shadow + c->headW, c->hid, c->NH, c->hid, ep, "head_fwd", 2.0 * n * c->hid + 4.0 * n * c->NH);
     if (rc) return rc;
   }
@@ -409,24 +428,24 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
   int cur = 0;
   const bf16_t* hlast = c->fcact[c->nfc - 1];
   {  // heads
-    ARows dl; dl.a = plain_rows(c->dhead, HEAD_LD); dl.HW = 1; dl.C = 0; dl.M = n; dl.K = HEAD_LD;
-    ARows xl; xl.a = plain_rows(hlast, c->hid); xl.HW = 1; xl.C = 0; xl.M = n; xl.K = c->hid;
+    ARows dl = plain_arows(c->dhead, HEAD_LD, n, HEAD_LD);
+    ARows xl = plain_arows(hlast, c->hid, n, c->hid);
     int rc = launch_wgrad(c, dl, xl, c->NH, c->hid, n, c->g + c->headW, c->g + c->headB, acc, "head_wgrad", 2.0 * n * (c->hid + HEAD_LD));
     if (rc) return rc;
-    EpRows<bf16_t, false, false, true> ep;
-    ep.out = c->gbuf[cur]; ep.stride_b = c->hid; ep.stride_v = 0; ep.V = 1; ep.HW = 1; ep.C = 0; ep.bias = nullptr; ep.mask = hlast; ep.M = n; ep.N = c->hid;
+    Ep<MapRows, bf16_t, false, false, true> ep;
+    ep.map = plain_map(c->hid, n); ep.out = c->gbuf[cur]; ep.bias = nullptr; ep.mask = hlast; ep.N = c->hid;
     rc = launch_gemm(c, dl, n, c->headT, HEAD_LD, c->hid, HEAD_LD, ep, "head_dgrad", 2.0 * n * (2.0 * c->hid + HEAD_LD));
     if (rc) return rc;
   }
   for (int l = c->nfc - 1; l >= 0; --l) {
     const bf16_t* x = l ? c->fcact[l - 1] : c->feat;
-    ARows dl; dl.a = plain_rows(c->gbuf[cur], c->fout[l]); dl.HW = 1; dl.C = 0; dl.M = n; dl.K = c->fout[l];
-    ARows xl; xl.a = plain_rows(x, c->fin[l]); xl.HW = 1; xl.C = 0; xl.M = n; xl.K = c->fin[l];
+    ARows dl = plain_arows(c->gbuf[cur], c->fout[l], n, c->fout[l]);
+    ARows xl = plain_arows(x, c->fin[l], n, c->fin[l]);
     int rc = launch_wgrad(c, dl, xl, c->fout[l], c->fin[l], n, c->g + c->fcW[l], c->g + c->fcB[l], acc, "fc_wgrad." + std::to_string(l),
                           2.0 * n * ((double)c->fin[l] + c->fout[l]) + 4.0 * (double)c->fin[l] * c->fout[l]);
     if (rc) return rc;
-    EpRows<bf16_t, false, false, true> ep;
-    ep.out = c->gbuf[cur ^ 1]; ep.stride_b = c->fin[l]; ep.stride_v = 0; ep.V = 1; ep.HW = 1; ep.C = 0; ep.bias = nullptr; ep.mask = x; ep.M = n; ep.N = c->fin[l];
+    Ep<MapRows, bf16_t, false, false, true> ep;
+    ep.map = plain_map(c->fin[l], n); ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = x; ep.N = c->fin[l];
     rc = launch_gemm(c, dl, n, c->fcT[l], c->fout[l], c->fin[l], c->fout[l], ep, "fc_dgrad." + std::to_string(l),
                      2.0 * ((double)n * c->fout[l] + 2.0 * n * c->fin[l] + (double)c->fin[l] * c->fout[l]));
     if (rc) return rc;
@@ -436,26 +455,24 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
   for (int l = c->nconv - 1; l >= 1; --l) {
     const int Co = c->cC[l + 1], Ci = c->cC[l], Ho = c->cH[l + 1], Wo = c->cW[l + 1], H = c->cH[l], W = c->cW[l];
     ImgAddr dy = conv_out_addr(c, l, c->gbuf[cur], c->gbuf[cur]);
-    ARows dl; dl.a = dy; dl.HW = Ho * Wo; dl.C = Co; dl.M = nimg * Ho * Wo; dl.K = Co;
+    ARows dl; dl.a = dy; dl.HW = Ho * Wo; dl.C = Co; dl.M = nimg * Ho * Wo; dl.K = Co; dl.plain = false;
     AConvFwd xl; xl.in = conv_out_addr(c, l - 1, c->act[l - 1], nullptr);
-    xl.H = H; xl.W = W; xl.Cin = Ci; xl.Ho = Ho; xl.Wo = Wo; xl.M = dl.M; xl.K = 9 * Ci;
+    xl.H = H; xl.W = W; xl.Cin = Ci; xl.lc = ilog2(Ci); xl.Ho = Ho; xl.Wo = Wo; xl.M = dl.M; xl.K = 9 * Ci;
     int rc = launch_wgrad(c, dl, xl, Co, 9 * Ci, dl.M, c->g + c->convW[l], c->g + c->convB[l], acc, "conv_wgrad." + std::to_string(l),
                           2.0 * ((double)dl.M * Co + (double)nimg * H * W * Ci) + 4.0 * 9.0 * Ci * Co);
     if (rc) return rc;
-    for (int cls = 0; cls < 4; ++cls) {
-      const int py = cls >> 1, px = cls & 1;
-      AConvDgrad al; al.dy = dy; al.Ho = Ho; al.Wo = Wo; al.Cout = Co; al.Ha = class_len(H, py); al.Wa = class_len(W, px);
-      al.py = py; al.px = px; al.nv = 1 + px; al.M = nimg * al.Ha * al.Wa; al.K = (1 + py) * (1 + px) * Co;
-      EpConvDgrad ep;
-      ImgAddr xa = conv_out_addr(c, l - 1, c->act[l - 1], nullptr);
-      ep.act = xa;
-      ep.out.base = c->gbuf[cur ^ 1]; ep.out.stride_b = xa.stride_b; ep.out.stride_v = xa.stride_v; ep.out.V = V;
-      ep.H = H; ep.W = W; ep.Cin = Ci; ep.Ha = al.Ha; ep.Wa = al.Wa; ep.py = py; ep.px = px; ep.M = al.M;
-      // per class: a quarter of dY's reads and of the activation read / gradient write
-      double ab = 2.0 * ((double)nimg * Ho * Wo * Co / 4.0 + 2.0 * al.M * Ci + (double)al.K * Ci);
-      rc = launch_gemm(c, al, al.M, c->wd[l][cls], al.K, Ci, al.K, ep, "conv_dgrad." + std::to_string(l), ab);
-      if (rc) return rc;
-    }
+    // transposed convolution: the four input-pixel parity classes in one launch (grid.z)
+    AConvDgrad al; al.dy = dy; al.Ho = Ho; al.Wo = Wo; al.Cout = Co; al.lco = ilog2(Co); al.H = H; al.W = W; al.dy_imgs = nimg;
+    al.w00 = c->wd[l][0]; al.w01 = c->wd[l][1]; al.w10 = c->wd[l][2]; al.w11 = c->wd[l][3];
+    const int M0 = nimg * class_len(H, 0) * class_len(W, 0);  // the largest class sizes the grid
+    ImgAddr xa = conv_out_addr(c, l - 1, c->act[l - 1], nullptr);
+    Ep<MapDgrad, bf16_t, false, false, true> ep;
+    ep.map.stride_b = xa.stride_b; ep.map.stride_v = xa.stride_v; ep.map.V = V; ep.map.H = H; ep.map.W = W; ep.map.Cin = Ci; ep.map.imgs = nimg;
+    ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = xa.base; ep.N = Ci;
+    const double pix = (double)nimg * H * W;
+    double ab = 2.0 * ((double)nimg * Ho * Wo * Co + 2.0 * pix * Ci + 9.0 * Ci * Co);
+    rc = launch_gemm(c, al, M0, nullptr, 0, Ci, 4 * Co, ep, "conv_dgrad." + std::to_string(l), ab, 4, 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co);
+    if (rc) return rc;
     cur ^= 1;
   }
   {  // first convolution: weight and bias gradient only
@@ -592,8 +609,9 @@ int create_impl(Ctx* c) {
   // weight-gradient partials: room for every layer at its preferred split count
   int64_t pe = 2048LL * c->cC[1] * (9 * c->cC[0] + 1), bpe = 0;
   auto want = [&](int Nn, int Kk, int64_t M) {
-    int tiles = cdiv(Kk, 64) * cdiv(Nn, 64);
-    int splits = cdiv(1024, tiles), mr = cdiv(M, 256);
+    int ktw = Kk <= 128 ? 1 : (Kk <= 256 ? 2 : 3);
+    int tiles = cdiv(Kk, 128 * ktw) * cdiv(Nn, 64);
+    int splits = cdiv(768, tiles), mr = cdiv(M, 128);
     if (splits > mr) splits = mr;
     if (splits < 1) splits = 1;
     if ((int64_t)splits * Nn * Kk > pe) pe = (int64_t)splits * Nn * Kk;
@@ -895,9 +913,9 @@ int ppo_diag_gemm(int32_t M, int32_t N, int32_t K, const float* h_a, const float
     hipLaunchKernelGGL(k_cast_bf16, dim3(cdiv((int64_t)M * K, 256)), dim3(256), 0, c->stream, da, ba, (int64_t)M * K);
     hipLaunchKernelGGL(k_cast_bf16, dim3(cdiv((int64_t)N * K, 256)), dim3(256), 0, c->stream, db, bb, (int64_t)N * K);
     LAUNCHCHK(c, "k_cast_bf16");
-    ARows al; al.a = plain_rows(ba, K); al.HW = 1; al.C = 0; al.M = M; al.K = K;
-    EpRows<float, false, false, false> ep;
-    ep.out = dc; ep.stride_b = N; ep.stride_v = 0; ep.V = 1; ep.HW = 1; ep.C = 0; ep.bias = nullptr; ep.mask = nullptr; ep.M = M; ep.N = N;
+    ARows al = plain_arows(ba, K, M, K);
+    Ep<MapRows, float, false, false, false> ep;
+    ep.map = plain_map(N, M); ep.out = dc; ep.bias = nullptr; ep.mask = nullptr; ep.N = N;
     int r = launch_gemm(c, al, M, bb, K, N, K, ep, "diag_gemm", 0.0);
     if (r) return r;
     HIPCHK(c, hipDeviceSynchronize());
