@@ -27,7 +27,7 @@ struct ARows {
   struct Cls { int M, K; };
   __device__ __forceinline__ Cls cls(int) const { Cls c; c.M = M; c.K = K; return c; }
   __device__ __forceinline__ Row row(int m, const Cls&) const { return row(m); }
-  __device__ __forceinline__ uint4 load(const Row& r, int k, const Cls&) const { return load(r, k); }
+  template <bool U32> __device__ __forceinline__ uint4 load(const Row& r, int k0, int koff, const Cls&) const { return load(r, k0 + koff); }
   __device__ __forceinline__ const bf16_t* bmat(const Cls&, const bf16_t* dflt) const { return dflt; }
   __device__ __forceinline__ Row row(int m) const {
     Row r; r.p = nullptr; r.img = 0; r.q = 0;
@@ -56,7 +56,18 @@ struct AConvFwd {
   struct Cls { int M, K; };
   __device__ __forceinline__ Cls cls(int) const { Cls c; c.M = M; c.K = K; return c; }
   __device__ __forceinline__ Row row(int m, const Cls&) const { return row(m); }
-  __device__ __forceinline__ uint4 load(const Row& r, int k, const Cls&) const { return load(r, k); }
+  // U32: k0 is a multiple of 32 and koff < 32, so with Cin >= 32 the whole chunk group lies in one
+  // kernel tap and the tap arithmetic is wave-uniform.
+  template <bool U32> __device__ __forceinline__ uint4 load(const Row& r, int k0, int koff, const Cls&) const {
+    if (U32 && lc >= 5) {
+      if (!r.p || k0 >= K) return zero16();
+      const int tap = k0 >> lc, u = tap / 3, v = tap - 3 * u, ci = (k0 & (Cin - 1)) + koff;
+      const int iy = r.iy0 + u, ix = r.ix0 + v;
+      if ((unsigned)iy >= (unsigned)H || (unsigned)ix >= (unsigned)W) return zero16();
+      return *reinterpret_cast<const uint4*>(r.p + ((iy * W + ix) << lc) + ci);
+    }
+    return load(r, k0 + koff);
+  }
   __device__ __forceinline__ const bf16_t* bmat(const Cls&, const bf16_t* dflt) const { return dflt; }
   __device__ __forceinline__ Row row(int m) const {
     Row r; r.p = nullptr; r.iy0 = 0; r.ix0 = 0; r.img = 0;
@@ -85,38 +96,44 @@ struct AConvFwd {
   }
 };
 
-// Transposed convolution, the four input-pixel parity classes (py, px) = (z >> 1, z & 1) selected by
-// grid.z: rows are the input pixels (img, 2a+py, 2b+px); k = (tu*nv+tv)*Cout + co runs over the 1,
-// 2 or 4 kernel taps that reach this class and the output channels (Cout a power of two).  Tap tu
-// of an odd row is u = 2*tu (reads output row a+1-tu); an even row has the single tap u = 1
-// (output row a).  Same along x.  Each class has its own packed weight matrix.
+// Transposed convolution.  A row is a horizontal PAIR of input pixels (img, iy, 2b), (img, iy, 2b+1)
+// with iy = 2a+py and the row parity py selected by grid.z; its 2*Cin outputs are contiguous in
+// memory (full 128-byte lines for Cin = 32).  The pair receives from output columns ox = b and
+// b+1 (contiguous 2*Cout elements of dY) and from output rows oy = a (tap u = 1 for an even row;
+// u = 2 for an odd row) and oy = a+1 (u = 0, odd rows only), so k = (tu*2 + dx)*Cout + co with tu
+// over the 1 or 2 row taps and dx over the two columns.  The packed weight matrix of the parity
+// holds zeros where a (pixel, column) combination has no tap (even pixel with dx = 1).
 struct AConvDgrad {
   ImgAddr dy; int Ho, Wo, Cout, lco, H, W, dy_imgs;
-  const bf16_t *w00, *w01, *w10, *w11;  // packed weights of class (py, px)
+  const bf16_t *w0, *w1;  // packed weights [2*Cin][nu*2*Cout] of row parity 0 / 1
   struct Row { const bf16_t* p; int a, b; };
-  struct Cls { int Ha, Wa, py, px, M, K; const bf16_t* w; };
+  struct Cls { int Ha, Wb, py, M, K; const bf16_t* w; };
   __device__ __forceinline__ Cls cls(int z) const {
-    Cls c; c.py = z >> 1; c.px = z & 1;
-    c.Ha = (H - c.py + 1) >> 1; c.Wa = (W - c.px + 1) >> 1;
-    c.M = dy_imgs * c.Ha * c.Wa; c.K = ((1 + c.py) * (1 + c.px)) << lco;
-    c.w = c.py ? (c.px ? w11 : w10) : (c.px ? w01 : w00);
+    Cls c; c.py = z;
+    c.Ha = (H - z + 1) >> 1; c.Wb = (W + 1) >> 1;
+    c.M = dy_imgs * c.Ha * c.Wb; c.K = (1 + z) << (lco + 1);
+    c.w = z ? w1 : w0;
     return c;
   }
   __device__ __forceinline__ const bf16_t* bmat(const Cls& c, const bf16_t*) const { return c.w; }
   __device__ __forceinline__ Row row(int m, const Cls& c) const {
     Row r; r.p = nullptr; r.a = 0; r.b = 0;
     if (m < c.M) {
-      int hw = c.Ha * c.Wa, img = m / hw, q = m - img * hw;
-      r.a = q / c.Wa; r.b = q - r.a * c.Wa; r.p = dy.ptr(img);
+      int hw = c.Ha * c.Wb, img = m / hw, q = m - img * hw;
+      r.a = q / c.Wb; r.b = q - r.a * c.Wb; r.p = dy.ptr(img);
     }
     return r;
   }
-  __device__ __forceinline__ uint4 load(const Row& r, int k, const Cls& c) const {
+  template <bool U32> __device__ __forceinline__ uint4 load(const Row& r, int k0, int koff, const Cls& c) const {
+    const int k = k0 + koff;
     if (!r.p || k >= c.K) return zero16();
-    int t = k >> lco, co = k & (Cout - 1), tu = c.px ? (t >> 1) : t, tv = c.px ? (t & 1) : 0;
-    int oy = r.a + (c.py ? 1 - tu : 0), ox = r.b + (c.px ? 1 - tv : 0);
+    int t, co;  // t = tu*2 + dx
+    if (U32 && lco >= 5) { t = k0 >> lco; co = (k0 & (Cout - 1)) + koff; }  // wave-uniform tap
+    else { t = k >> lco; co = k & (Cout - 1); }
+    const int tu = t >> 1, dx = t & 1;
+    const int oy = r.a + (c.py ? 1 - tu : 0), ox = r.b + dx;
     if (oy >= Ho || ox >= Wo) return zero16();
-    return *reinterpret_cast<const uint4*>(r.p + (((int64_t)oy * Wo + ox) << lco) + co);
+    return *reinterpret_cast<const uint4*>(r.p + ((oy * Wo + ox) << lco) + co);
   }
 };
 
@@ -128,23 +145,29 @@ struct MapRows {
   __device__ __forceinline__ Cls cls(int) const { return Cls(); }
   __device__ __forceinline__ int64_t row_offset(int m, const Cls&) const {
     if (m >= M) return -1;
+    if (HW == 1 && V == 1) return (int64_t)m * stride_b;
     int img = m / HW, q = m - img * HW, b = img / V, v = img - b * V;
     return (int64_t)b * stride_b + (int64_t)v * stride_v + (int64_t)q * C;
   }
+  __device__ __forceinline__ int row_cols(int, const Cls&) const { return 0x7fffffff; }
 };
-// ... or the input pixels of one parity class of a transposed convolution.
+// ... or horizontal pixel pairs of the rows of one parity of a transposed convolution's input.
 struct MapDgrad {
   int64_t stride_b, stride_v; int V, H, W, Cin, imgs;
-  struct Cls { int Ha, Wa, py, px, M; };
+  struct Cls { int Ha, Wb, py, M; };
   __device__ __forceinline__ Cls cls(int z) const {
-    Cls c; c.py = z >> 1; c.px = z & 1;
-    c.Ha = (H - c.py + 1) >> 1; c.Wa = (W - c.px + 1) >> 1; c.M = imgs * c.Ha * c.Wa;
+    Cls c; c.py = z; c.Ha = (H - z + 1) >> 1; c.Wb = (W + 1) >> 1; c.M = imgs * c.Ha * c.Wb;
     return c;
   }
   __device__ __forceinline__ int64_t row_offset(int m, const Cls& c) const {
     if (m >= c.M) return -1;
-    int hw = c.Ha * c.Wa, img = m / hw, q = m - img * hw, a = q / c.Wa, bb = q - a * c.Wa, b = img / V, v = img - b * V;
-    return (int64_t)b * stride_b + (int64_t)v * stride_v + ((int64_t)(2 * a + c.py) * W + (2 * bb + c.px)) * Cin;
+    int hw = c.Ha * c.Wb, img = m / hw, q = m - img * hw, a = q / c.Wb, bb = q - a * c.Wb, b = img / V, v = img - b * V;
+    return (int64_t)b * stride_b + (int64_t)v * stride_v + ((int64_t)(2 * a + c.py) * W + 2 * bb) * Cin;
+  }
+  // number of valid columns of the row: the last pair of an odd-width image has one pixel
+  __device__ __forceinline__ int row_cols(int m, const Cls& c) const {
+    int bb = m % c.Wb;
+    return (2 * bb + 1 < W) ? 2 * Cin : Cin;
   }
 };
 // out[off + n] = f(acc): optional bias, ReLU, and ReLU-derivative mask read from `mask` at the
@@ -159,8 +182,11 @@ struct Ep {
 // ---------------------------------------------------------------- C = A * B^T
 // B is a plain [N][K] matrix (row stride ldb; loaders with per-class weights override it).  256
 // threads = 4 waves laid out WGM x WGN, each computing TM x TN 32x32 MFMA tiles.  K is walked in
-// steps of 32 through double-buffered LDS.  bf16 results are staged through LDS and leave as
-// 16-byte row segments.
+// steps of 32 through double-buffered LDS.  The MFMA is issued with the weight tile as its first
+// operand, so a lane ends up holding, for ONE output row m, four groups of four consecutive
+// columns n.  bf16 results are packed four at a time, staged through LDS (8-byte writes) and
+// leave as 16-byte row segments (with the ReLU mask read the same way); fp32 results are written
+// directly.
 template <int BM, int BN, int WGM, int WGN, class AL, class EP>
 __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ Bm_, int64_t ldb_, int N, EP ep) {
   constexpr int TM = BM / (WGM * 32), TN = BN / (WGN * 32);
@@ -171,6 +197,7 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
   static_assert(BM * SP <= AB_ELEMS, "staging tile must fit in the operand buffers");
   __shared__ __attribute__((aligned(16))) bf16_t smem[AB_ELEMS];
   __shared__ int64_t rowoff[BM];
+  __shared__ int rowcols[BM];
   bf16_t* As = smem;                         // [2][BM*PITCH]
   bf16_t* Bs = smem + 2 * BM * GEMM_PITCH;   // [2][BN*PITCH]
 
@@ -213,7 +240,7 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
   uint4 ra[ACH], rb[BCH];
   auto gload = [&](int k0) {
 #pragma unroll
-    for (int c = 0; c < ACH; ++c) ra[c] = al.load(arow[c], k0 + a_k[c], acls);
+    for (int c = 0; c < ACH; ++c) ra[c] = al.template load<true>(arow[c], k0, a_k[c], acls);
 #pragma unroll
     for (int c = 0; c < BCH; ++c) {
       int k = k0 + b_k[c];
@@ -251,79 +278,72 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) sstore(buf ^ 1);
     __syncthreads();
   }
 
-  for (int r = tid; r < BM; r += 256) rowoff[r] = ep.map.row_offset(m0 + r, mcls);
+  // acc[i][j][g*4+q] = C[m][n] with m = m0 + (wm*TM+i)*32 + lane%32, n = n0 + (wn*TN+j)*32 + g*8 + (lane/32)*4 + q
   typedef typename EP::out_t OutT;
   if constexpr (sizeof(OutT) == 2) {
-    // stage the bf16 tile in LDS (the operand buffers are free now), then write 16-byte segments
-    bf16_t* stage = smem;
+    for (int r = tid; r < BM; r += 256) { rowoff[r] = ep.map.row_offset(m0 + r, mcls); rowcols[r] = ep.map.row_cols(m0 + r, mcls); }
+    bf16_t* stage = smem;  // the operand buffers are free now
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int cl = (wn * TN + j) * 32 + (lane & 31), col = n0 + cl;
-      float bv = 0.f;
-      if (EP::kBias) bv = (col < N) ? ep.bias[col] : 0.f;
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int g = 0; g < 4; ++g) {
+        const int cl = (wn * TN + j) * 32 + g * 8 + (lane >> 5) * 4, nb = n0 + cl;
+        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (EP::kBias) { if (nb < N) bv = *reinterpret_cast<const float4*>(ep.bias + nb); }  // N is a multiple of 8
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int rl = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-          float v = acc[i][j][e] + bv;
-          if (EP::kRelu) v = v > 0.f ? v : 0.f;
-          stage[rl * SP + cl] = f2bf(v);
+        for (int i = 0; i < TM; ++i) {
+          float v0 = acc[i][j][g * 4] + bv.x, v1 = acc[i][j][g * 4 + 1] + bv.y, v2 = acc[i][j][g * 4 + 2] + bv.z, v3 = acc[i][j][g * 4 + 3] + bv.w;
+          if (EP::kRelu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+          uint2 o; o.x = pack2bf(v0, v1); o.y = pack2bf(v2, v3);
+          *reinterpret_cast<uint2*>(&stage[((wm * TM + i) * 32 + (lane & 31)) * SP + cl]) = o;
         }
-    }
+      }
     __syncthreads();
     constexpr int CPR = BN / 8;  // 16-byte chunks per row
     bf16_t* out = reinterpret_cast<bf16_t*>(ep.out);
     for (int ch = tid; ch < BM * CPR; ch += 256) {
       const int rl = ch / CPR, cg = ch - rl * CPR, n = n0 + cg * 8;
       const int64_t off = rowoff[rl];
-      if (off < 0 || n >= N) continue;
+      if (off < 0 || n >= N || n >= rowcols[rl]) continue;
       uint4 v = *reinterpret_cast<const uint4*>(&stage[rl * SP + cg * 8]);
-      if (n + 8 <= N) {
-        if (EP::kMask) {
-          // keep a half where the stored activation is > 0 (sign bit clear and not zero)
-          const uint4 mk = *reinterpret_cast<const uint4*>(ep.mask + off + n);
-          auto keep = [](uint32_t m) -> uint32_t {
-            return (((short)(m & 0xffffu) > 0) ? 0x0000ffffu : 0u) | (((short)(m >> 16) > 0) ? 0xffff0000u : 0u);
-          };
-          v.x &= keep(mk.x); v.y &= keep(mk.y); v.z &= keep(mk.z); v.w &= keep(mk.w);
-        }
-        *reinterpret_cast<uint4*>(out + off + n) = v;
-      } else {
-        for (int q = 0; q < 8 && n + q < N; ++q) {
-          bf16_t o = stage[rl * SP + cg * 8 + q];
-          if (EP::kMask) { if (!((short)ep.mask[off + n + q] > 0)) o = 0; }
-          out[off + n + q] = o;
-        }
+      if (EP::kMask) {
+        // keep a half where the stored activation is > 0 (sign bit clear and not zero)
+        const uint4 mk = *reinterpret_cast<const uint4*>(ep.mask + off + n);
+        auto keep = [](uint32_t m) -> uint32_t {
+          return (((short)(m & 0xffffu) > 0) ? 0x0000ffffu : 0u) | (((short)(m >> 16) > 0) ? 0xffff0000u : 0u);
+        };
+        v.x &= keep(mk.x); v.y &= keep(mk.y); v.z &= keep(mk.z); v.w &= keep(mk.w);
       }
+      *reinterpret_cast<uint4*>(out + off + n) = v;
     }
   } else {
-    __syncthreads();
     float* out = reinterpret_cast<float*>(ep.out);
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+      const int64_t off = ep.map.row_offset(m0 + (wm * TM + i) * 32 + (lane & 31), mcls);
+      if (off < 0) continue;
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
-        if (col >= N) continue;
-        const float bv = EP::kBias ? ep.bias[col] : 0.f;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int rl = (wm * TM + i) * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-          const int64_t off = rowoff[rl];
-          if (off < 0) continue;
-          float v = acc[i][j][e] + bv;
-          if (EP::kRelu) v = v > 0.f ? v : 0.f;
-          if (EP::kMask) { if (!((short)ep.mask[off + col] > 0)) v = 0.f; }
-          out[off + col] = v;
+        for (int g = 0; g < 4; ++g) {
+          const int nb = n0 + (wn * TN + j) * 32 + g * 8 + (lane >> 5) * 4;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (nb + q >= N) continue;
+            float x = acc[i][j][g * 4 + q];
+            if (EP::kBias) x += ep.bias[nb + q];
+            if (EP::kRelu) x = x > 0.f ? x : 0.f;
+            if (EP::kMask) { if (!((short)ep.mask[off + nb + q] > 0)) x = 0.f; }
+            out[off + nb + q] = x;
+          }
         }
-      }
+    }
   }
 }
 
@@ -364,9 +384,9 @@ __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int
   uint4 rd, rx[XCH];
   auto gload = [&]() {
     const bool ok = m < mend;
-    rd = ok ? dl.load(dr, n0 + g8) : zero16();
+    rd = ok ? dl.template load<false>(dr, n0, g8, dl.cls(0)) : zero16();
 #pragma unroll
-    for (int c = 0; c < XCH; ++c) rx[c] = ok ? al.load(ar, k0 + g8 + c * 64) : zero16();
+    for (int c = 0; c < XCH; ++c) rx[c] = ok ? al.template load<false>(ar, k0 + c * 64, g8, al.cls(0)) : zero16();
   };
   auto sstore = [&]() {
     const bf16_t* d = reinterpret_cast<const bf16_t*>(&rd);

@@ -517,13 +517,17 @@ __global__ void k_transpose_bf16(const bf16_t* __restrict__ src, int rows, int c
   int c = (int)(i / ld_dst), r = (int)(i - (int64_t)c * ld_dst);
   dst[i] = r < rows ? src[(int64_t)r * cols + c] : (bf16_t)0;
 }
-// Transposed-convolution weights of parity class (py, px): dst[ci][(tu*nv+tv)*Cout + co] =
-// W[co][(u*3+v)*Cin + ci] with u = py ? 2*tu : 1, v = px ? 2*tv : 1.
-__global__ void k_pack_dgrad_w(const bf16_t* __restrict__ w, int Cout, int Cin, int py, int px, bf16_t* __restrict__ dst) {
-  const int nu = 1 + py, nv = 1 + px, Kc = nu * nv * Cout;
+// Transposed-convolution weights of row parity py for pixel-pair rows:
+// dst[px*Cin + ci][(tu*2 + dx)*Cout + co] = W[co][(u*3+v)*Cin + ci] with u = py ? 2*tu : 1 and the
+// column tap v given by (px, dx): even pixel (px = 0) takes v = 1 from dx = 0 and nothing from
+// dx = 1; odd pixel takes v = 2 from dx = 0 and v = 0 from dx = 1.
+__global__ void k_pack_dgrad_w(const bf16_t* __restrict__ w, int Cout, int Cin, int py, bf16_t* __restrict__ dst) {
+  const int Kc = (1 + py) * 2 * Cout;
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)Cin * Kc) return;
-  int ci = (int)(i / Kc), k = (int)(i - (int64_t)ci * Kc), t = k / Cout, co = k - t * Cout, tu = t / nv, tv = t - tu * nv;
-  int u = py ? 2 * tu : 1, v = px ? 2 * tv : 1;
-  dst[i] = w[(int64_t)co * 9 * Cin + (u * 3 + v) * Cin + ci];
+  if (i >= (int64_t)2 * Cin * Kc) return;
+  int n = (int)(i / Kc), k = (int)(i - (int64_t)n * Kc), px = n / Cin, ci = n - px * Cin;
+  int t = k / Cout, co = k - t * Cout, tu = t >> 1, dx = t & 1;
+  int u = py ? 2 * tu : 1;
+  int v = px ? (dx ? 0 : 2) : (dx ? -1 : 1);
+  dst[i] = v < 0 ? (bf16_t)0 : w[(int64_t)co * 9 * Cin + (u * 3 + v) * Cin + ci];
 }

@@ -38,7 +38,7 @@ struct Ctx {
   // device: parameters
   float *p = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
   bf16_t* shadow = nullptr;
-  bf16_t* wd[PPO_MAX_LAYERS][4];  // transposed-conv weights per parity class (conv layers >= 1)
+  bf16_t* wd[PPO_MAX_LAYERS][2];  // transposed-conv weights per row parity (conv layers >= 1)
   bf16_t* fcT[PPO_MAX_LAYERS];    // [in][out]
   bf16_t* headT = nullptr;        // [hid][32]
   // device: rollout buffer (SoA)
@@ -342,10 +342,9 @@ int repack_weights(Ctx* c) {
   ProfScope ps(c, "weight_repack", 0.0, 4.0 * (double)c->total);
   for (int l = 1; l < c->nconv; ++l) {
     int Co = c->cC[l + 1], Ci = c->cC[l];
-    for (int cls = 0; cls < 4; ++cls) {
-      int py = cls >> 1, px = cls & 1;
-      int64_t n = (int64_t)Ci * (1 + py) * (1 + px) * Co;
-      hipLaunchKernelGGL(k_pack_dgrad_w, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->shadow + c->convW[l], Co, Ci, py, px, c->wd[l][cls]);
+    for (int py = 0; py < 2; ++py) {
+      int64_t n = (int64_t)2 * Ci * (1 + py) * 2 * Co;
+      hipLaunchKernelGGL(k_pack_dgrad_w, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->shadow + c->convW[l], Co, Ci, py, c->wd[l][py]);
     }
   }
   for (int l = 0; l < c->nfc; ++l) {
@@ -461,17 +460,17 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
     int rc = launch_wgrad(c, dl, xl, Co, 9 * Ci, dl.M, c->g + c->convW[l], c->g + c->convB[l], acc, "conv_wgrad." + std::to_string(l),
                           2.0 * ((double)dl.M * Co + (double)nimg * H * W * Ci) + 4.0 * 9.0 * Ci * Co);
     if (rc) return rc;
-    // transposed convolution: the four input-pixel parity classes in one launch (grid.z)
+    // transposed convolution over horizontal pixel pairs, both row parities in one launch (grid.z)
     AConvDgrad al; al.dy = dy; al.Ho = Ho; al.Wo = Wo; al.Cout = Co; al.lco = ilog2(Co); al.H = H; al.W = W; al.dy_imgs = nimg;
-    al.w00 = c->wd[l][0]; al.w01 = c->wd[l][1]; al.w10 = c->wd[l][2]; al.w11 = c->wd[l][3];
-    const int M0 = nimg * class_len(H, 0) * class_len(W, 0);  // the largest class sizes the grid
+    al.w0 = c->wd[l][0]; al.w1 = c->wd[l][1];
+    const int M0 = nimg * class_len(H, 0) * class_len(W, 0);  // the even-row parity sizes the grid
     ImgAddr xa = conv_out_addr(c, l - 1, c->act[l - 1], nullptr);
     Ep<MapDgrad, bf16_t, false, false, true> ep;
     ep.map.stride_b = xa.stride_b; ep.map.stride_v = xa.stride_v; ep.map.V = V; ep.map.H = H; ep.map.W = W; ep.map.Cin = Ci; ep.map.imgs = nimg;
-    ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = xa.base; ep.N = Ci;
+    ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = xa.base; ep.N = 2 * Ci;
     const double pix = (double)nimg * H * W;
     double ab = 2.0 * ((double)nimg * Ho * Wo * Co + 2.0 * pix * Ci + 9.0 * Ci * Co);
-    rc = launch_gemm(c, al, M0, nullptr, 0, Ci, 4 * Co, ep, "conv_dgrad." + std::to_string(l), ab, 4, 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co);
+    rc = launch_gemm(c, al, M0, nullptr, 0, 2 * Ci, 4 * Co, ep, "conv_dgrad." + std::to_string(l), ab, 2, 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co);
     if (rc) return rc;
     cur ^= 1;
   }
@@ -582,7 +581,7 @@ int create_impl(Ctx* c) {
   DALLOC(c, c->p, c->total); DALLOC(c, c->m, c->total); DALLOC(c, c->v, c->total); DALLOC(c, c->g, c->total);
   DALLOC(c, c->shadow, c->total + 8);
   for (int l = 1; l < c->nconv; ++l)
-    for (int cls = 0; cls < 4; ++cls) DALLOC(c, c->wd[l][cls], (int64_t)c->cC[l] * (1 + (cls >> 1)) * (1 + (cls & 1)) * c->cC[l + 1]);
+    for (int py = 0; py < 2; ++py) DALLOC(c, c->wd[l][py], (int64_t)2 * c->cC[l] * (1 + py) * 2 * c->cC[l + 1]);
   for (int l = 0; l < c->nfc; ++l) DALLOC(c, c->fcT[l], (int64_t)c->fin[l] * c->fout[l]);
   DALLOC(c, c->headT, (int64_t)c->hid * HEAD_LD);
   // rollout buffer
