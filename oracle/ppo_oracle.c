@@ -134,10 +134,10 @@ float orc_bf16_rne(float x) {
 /* Operand-precision mode of the network arithmetic.
  *   0: exact  - everything in fp64 (the definition).
  *   1: bf16 operands - the arithmetic "bf16 matrix operands, wide accumulation": every STORED
- *      activation (ReLU outputs, proprioception), every stored activation-gradient (loss
- *      gradients w.r.t. the head outputs, each layer's masked input gradient) and the weight
- *      matrices of every layer except the first convolution are rounded once to bf16 (RNE);
- *      biases, log-std, the first convolution's weights, all sums and the loss stay wide.
+ *      activation (images, ReLU outputs, proprioception), every stored activation-gradient
+ *      (loss gradients w.r.t. the head outputs, each layer's masked input gradient) and the
+ *      weight matrix of every layer are rounded once to bf16 (RNE); biases, log-std, all sums
+ *      and the loss stay wide.
  * Mode 1 exists because the discrete decisions of the method (ReLU masks, which branch of the
  * clipped surrogate / clipped value loss is active) must be taken in the same precision on both
  * sides of a comparison; it changes no formula. */
@@ -376,12 +376,12 @@ static void sample_backward(const orc_net *n, const geom *g, const double *P, ac
 }
 
 /* Copy of the parameters as the layers use them: in bf16-operand mode the weight matrices of
- * every layer but the first convolution are rounded to bf16; everything else is unchanged. */
+ * every layer are rounded to bf16; everything else is unchanged. */
 static double *operand_params(const orc_net *n, const geom *g, const double *params) {
   double *P = (double *)malloc(sizeof(double) * (size_t)g->total);
   memcpy(P, params, sizeof(double) * (size_t)g->total);
   if (!g_quant) return P;
-  for (int l = 1; l < n->n_conv; ++l)
+  for (int l = 0; l < n->n_conv; ++l)
     for (int64_t i = g->convW[l]; i < g->convB[l]; ++i) P[i] = q(P[i]);
   for (int l = 0; l < n->n_fc; ++l)
     for (int64_t i = g->fcW[l]; i < g->fcB[l]; ++i) P[i] = q(P[i]);

@@ -155,132 +155,181 @@ __global__ void k_perm_rank(uint64_t stream, int S, int shift, const int32_t* __
 }
 
 // ---------------------------------------------------------------- first convolution
-// 3x3 stride-2 pad-1 convolution of a 1- or 3-channel image read straight from the rollout
-// buffer through the minibatch index (the gather is fused into the loader).  One thread per
-// output pixel computes all Cout channels in fp32 and stores them channel-last as bf16.
-// Weights are the fp32 master copy in [Cout][9*Cin] order, staged in LDS as [k][Cout].
-template <int CIN>
+// 3x3 stride-2 pad-1 convolution of a 1- or 3-channel image read straight from the rollout buffer
+// through the minibatch index (the gather is fused into the loader).  K = 9*CIN (9 or 27) is padded
+// to 16 / 32 and fed to the matrix cores: one 32x32x16 MFMA produces 32 pixels x 32 channels.
+// The work is bound by the 64 B/pixel (Cout = 32) of activation traffic, not by arithmetic.
+
+// flat output-pixel index -> (img, oy, ox), then stepped without divisions
+struct PixCursor {
+  int img, oy, ox;
+  __device__ __forceinline__ void init(int64_t m, int Ho, int Wo) {
+    const int hw = Ho * Wo;
+    img = (int)(m / hw);
+    const int q = (int)(m - (int64_t)img * hw);
+    oy = q / Wo; ox = q - oy * Wo;
+  }
+  __device__ __forceinline__ void advance(int d, int Ho, int Wo) {
+    ox += d;
+    while (ox >= Wo) { ox -= Wo; ++oy; }
+    while (oy >= Ho) { oy -= Ho; ++img; }
+  }
+};
+
+__device__ __forceinline__ bf16x8_t pack8(const bf16_t (&x)[8]) {
+  uint4 u;
+  u.x = (uint32_t)x[0] | ((uint32_t)x[1] << 16); u.y = (uint32_t)x[2] | ((uint32_t)x[3] << 16);
+  u.z = (uint32_t)x[4] | ((uint32_t)x[5] << 16); u.w = (uint32_t)x[6] | ((uint32_t)x[7] << 16);
+  return __builtin_bit_cast(bf16x8_t, u);
+}
+
+// Forward.  A wave handles TPW tiles of 32 consecutive output pixels.  MFMA operands: weights
+// [co][k] first (lane: co = lane%32, k = (lane/32)*8..+7), patches second (lane: pixel = lane%32),
+// so a lane ends up with 4 groups of 4 consecutive channels of ONE pixel; bias + ReLU, pack, stage
+// in wave-private LDS, and leave as 16-byte pieces of the contiguous [pixel][Cout] output.
+template <int CIN, int TPW>
 __global__ __launch_bounds__(256) void k_conv1_fwd(ImgAddr in, int n_img, int H, int W, int Ho, int Wo, int Cout,
-                                                   const float* __restrict__ Wt, const float* __restrict__ bias,
+                                                   const bf16_t* __restrict__ Wb, const float* __restrict__ bias,
                                                    bf16_t* __restrict__ out) {
-  constexpr int K = 9 * CIN;
-  extern __shared__ float smem[];  // [K][Cout] weights, then [Cout] bias
-  float* w = smem; float* bs = smem + K * Cout;
-  for (int i = threadIdx.x; i < K * Cout; i += blockDim.x) { int co = i / K, k = i - co * K; w[k * Cout + co] = Wt[i]; }
-  for (int i = threadIdx.x; i < Cout; i += blockDim.x) bs[i] = bias[i];
-  __syncthreads();
-  int64_t m = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  int64_t M = (int64_t)n_img * Ho * Wo;
-  if (m >= M) return;
-  int hw = Ho * Wo, img = (int)(m / hw), q = (int)(m - (int64_t)img * hw), oy = q / Wo, ox = q - oy * Wo;
-  const bf16_t* p = in.ptr(img);
-  float x[K];
+  constexpr int K = 9 * CIN, KS = (K + 15) / 16;
+  __shared__ __attribute__((aligned(16))) bf16_t stage[4][32 * 72];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, h = lane >> 5;
+  const int64_t M = (int64_t)n_img * Ho * Wo;
+  const int NJ = (Cout + 31) / 32, SP = Cout + 8;
+  bf16x8_t bw[2][KS];
+  float bs[2][16];
 #pragma unroll
-  for (int u = 0; u < 3; ++u)
+  for (int jn = 0; jn < 2; ++jn) {
+    const int co = jn * 32 + l32;
 #pragma unroll
-    for (int v = 0; v < 3; ++v) {
-      int iy = 2 * oy - 1 + u, ix = 2 * ox - 1 + v;
-      bool ok = (unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W;
+    for (int ks = 0; ks < KS; ++ks) {
+      bf16_t t[8];
 #pragma unroll
-      for (int c = 0; c < CIN; ++c) x[(u * 3 + v) * CIN + c] = ok ? bf2f(p[((int64_t)iy * W + ix) * CIN + c]) : 0.f;
+      for (int j = 0; j < 8; ++j) { const int k = ks * 16 + h * 8 + j; t[j] = (k < K && co < Cout) ? Wb[co * K + k] : (bf16_t)0; }
+      bw[jn][ks] = pack8(t);
     }
-  bf16_t* o = out + m * Cout;
-  for (int c0 = 0; c0 < Cout; c0 += 8) {
-    float acc[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = bs[c0 + j];
+    for (int e = 0; e < 16; ++e) { const int c2 = jn * 32 + (e >> 2) * 8 + h * 4 + (e & 3); bs[jn][e] = c2 < Cout ? bias[c2] : 0.f; }
+  }
+  for (int t = 0; t < TPW; ++t) {
+    const int64_t m0 = ((int64_t)(blockIdx.x * 4 + wave) * TPW + t) * 32;
+    const int64_t m = m0 + l32;
+    const bool valid = m < M;
+    PixCursor pc; pc.init(valid ? m : 0, Ho, Wo);
+    const bf16_t* p = in.ptr(valid ? pc.img : 0);
+    bf16x8_t a[KS];
 #pragma unroll
-    for (int k = 0; k < K; ++k)
+    for (int ks = 0; ks < KS; ++ks) {
+      bf16_t x[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc[j] += x[k] * w[k * Cout + c0 + j];
-    uint4 pk;
-    pk.x = pack2bf(fmaxf(acc[0], 0.f), fmaxf(acc[1], 0.f)); pk.y = pack2bf(fmaxf(acc[2], 0.f), fmaxf(acc[3], 0.f));
-    pk.z = pack2bf(fmaxf(acc[4], 0.f), fmaxf(acc[5], 0.f)); pk.w = pack2bf(fmaxf(acc[6], 0.f), fmaxf(acc[7], 0.f));
-    *reinterpret_cast<uint4*>(o + c0) = pk;
+      for (int j = 0; j < 8; ++j) {
+        const int k = ks * 16 + h * 8 + j, tap = k / CIN, c = k - tap * CIN, u = tap / 3, v = tap - 3 * u;
+        const int iy = 2 * pc.oy - 1 + u, ix = 2 * pc.ox - 1 + v;
+        const bool ok = valid && k < K && (unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W;
+        x[j] = ok ? p[(iy * W + ix) * CIN + c] : (bf16_t)0;
+      }
+      a[ks] = pack8(x);
+    }
+    __syncthreads();  // previous tile's staging reads are done
+#pragma unroll
+    for (int jn = 0; jn < 2; ++jn) {
+      if (jn >= NJ) break;
+      f32x16_t acc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw[jn][ks], a[ks], acc, 0, 0, 0);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int cl = jn * 32 + g * 8 + h * 4;
+        if (cl < Cout) {
+          uint2 o;
+          o.x = pack2bf(fmaxf(acc[g * 4] + bs[jn][g * 4], 0.f), fmaxf(acc[g * 4 + 1] + bs[jn][g * 4 + 1], 0.f));
+          o.y = pack2bf(fmaxf(acc[g * 4 + 2] + bs[jn][g * 4 + 2], 0.f), fmaxf(acc[g * 4 + 3] + bs[jn][g * 4 + 3], 0.f));
+          *reinterpret_cast<uint2*>(&stage[wave][l32 * SP + cl]) = o;
+        }
+      }
+    }
+    __syncthreads();
+    const int cpr = Cout >> 3;  // 16-byte chunks per pixel
+    for (int ch = lane; ch < 32 * cpr; ch += 64) {
+      const int r = ch / cpr, cg = ch - r * cpr;
+      if (m0 + r < M) *reinterpret_cast<uint4*>(out + (m0 + r) * Cout + cg * 8) = *reinterpret_cast<const uint4*>(&stage[wave][r * SP + cg * 8]);
+    }
   }
 }
 
-// Weight/bias gradient of the first convolution: dW[co][k] = sum_m dY[m][co] * x[m][k], db[co] =
-// sum_m dY[m][co].  TPP = Cout/COG threads share a pixel, each owning COG output channels and all
-// 9*CIN taps (+1 bias column) as a register tile; a block walks its pixel range, then the tiles
-// are summed across the wave with xor-shuffles, across the four waves through LDS, and written as
-// one partial per block (summed later in block order).
-template <int CIN, int COG>
+// Weight/bias gradient: dW[co][k] = sum_m dY[m][co] * x[m][k], db[co] = sum_m dY[m][co] (k = K is a
+// column of ones).  The contraction runs over pixels, 16 per MFMA: first operand dY^T (lane: co =
+// lane%32, 8 consecutive pixels), second operand the patches (lane: k = lane%32, the same 8 pixels).
+// A block walks its pixel range (waves interleaved in steps of 16 pixels), sums the four wave
+// accumulators through LDS and writes one partial per block (summed later in block order).
+template <int CIN>
 __global__ __launch_bounds__(256) void k_conv1_wgrad(ImgAddr in, int n_img, int H, int W, int Ho, int Wo, int Cout,
                                                      const bf16_t* __restrict__ dy, int pixels_per_block,
                                                      float* __restrict__ partial) {
-  constexpr int K = 9 * CIN, KP = K + 1;
-  __shared__ float wsum[4 * 64 * KP];
-  const int TPP = Cout / COG, PPI = 256 / TPP;
-  const int tid = threadIdx.x, cg = tid % TPP, pl = tid / TPP;
-  float acc[COG][KP];
-#pragma unroll
-  for (int j = 0; j < COG; ++j)
-#pragma unroll
-    for (int k = 0; k < KP; ++k) acc[j][k] = 0.f;
+  constexpr int K = 9 * CIN, KP1 = K + 1;
+  __shared__ float wsum[4][64 * 32];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, h = lane >> 5;
+  const int NJ = (Cout + 31) / 32;
   const int64_t M = (int64_t)n_img * Ho * Wo;
   const int64_t mbeg = (int64_t)blockIdx.x * pixels_per_block;
   const int64_t mend = (mbeg + pixels_per_block < M) ? mbeg + pixels_per_block : M;
-  int64_t m = mbeg + pl;
-  const int hw = Ho * Wo;
-  int img = (int)(m / hw), q = (int)(m - (int64_t)img * hw), oy = q / Wo, ox = q - oy * Wo;
-  const bf16_t* p = (m < mend) ? in.ptr(img) : nullptr;
-  for (; m < mend; m += PPI) {
-    float x[K];
+  // this lane's patch column
+  const int tap = l32 / CIN, cch = l32 - tap * CIN, u = tap / 3, v = tap - 3 * u;
+  const bool kcol = l32 < K, kone = l32 == K;
+  f32x16_t acc[2];
 #pragma unroll
-    for (int u = 0; u < 3; ++u)
+  for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
-      for (int v = 0; v < 3; ++v) {
-        const int iy = 2 * oy - 1 + u, ix = 2 * ox - 1 + v;
-        const bool ok = (unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W;
+    for (int e = 0; e < 16; ++e) acc[jn][e] = 0.f;
+  int64_t mb = mbeg + wave * 16 + h * 8;  // first of this lane's 8 pixels
+  PixCursor pc; pc.init(mb < mend ? mb : 0, Ho, Wo);
+  const bf16_t* p = in.ptr(mb < mend ? pc.img : 0);
+  int pimg = pc.img;
+  for (; mb - h * 8 < mend; mb += 64) {
+    bf16_t xs[8], ds[2][8];
+    PixCursor q = pc;
 #pragma unroll
-        for (int c = 0; c < CIN; ++c) x[(u * 3 + v) * CIN + c] = ok ? bf2f(p[((int64_t)iy * W + ix) * CIN + c]) : 0.f;
+    for (int j = 0; j < 8; ++j) {
+      const bool ok = mb + j < mend;
+      bf16_t xv = 0;
+      if (ok && kone) xv = 0x3F80;  // 1.0
+      if (ok && kcol) {
+        const bf16_t* pj = (q.img == pimg) ? p : in.ptr(q.img);
+        const int iy = 2 * q.oy - 1 + u, ix = 2 * q.ox - 1 + v;
+        if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) xv = pj[(iy * W + ix) * CIN + cch];
       }
-    float d[COG];
-    const bf16_t* dp = dy + m * Cout + cg * COG;
-    if constexpr (COG == 8) {
-      uint4 r = *reinterpret_cast<const uint4*>(dp);
-      const uint32_t w4[4] = {r.x, r.y, r.z, r.w};
+      xs[j] = xv;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { d[2 * j] = __uint_as_float(w4[j] << 16); d[2 * j + 1] = __uint_as_float(w4[j] & 0xffff0000u); }
-    } else {
-      uint2 r = *reinterpret_cast<const uint2*>(dp);
-      d[0] = __uint_as_float(r.x << 16); d[1] = __uint_as_float(r.x & 0xffff0000u);
-      d[2] = __uint_as_float(r.y << 16); d[3] = __uint_as_float(r.y & 0xffff0000u);
+      for (int jn = 0; jn < 2; ++jn) {
+        const int co = jn * 32 + l32;
+        ds[jn][j] = (ok && co < Cout) ? dy[(mb + j) * Cout + co] : (bf16_t)0;
+      }
+      q.advance(1, Ho, Wo);
     }
+    const bf16x8_t xb = pack8(xs);
 #pragma unroll
-    for (int j = 0; j < COG; ++j) {
-#pragma unroll
-      for (int k = 0; k < K; ++k) acc[j][k] += d[j] * x[k];
-      acc[j][K] += d[j];
+    for (int jn = 0; jn < 2; ++jn) {
+      if (jn >= NJ) break;
+      acc[jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pack8(ds[jn]), xb, acc[jn], 0, 0, 0);
     }
-    // next pixel of this thread
-    ox += PPI;
-    while (ox >= Wo) { ox -= Wo; ++oy; }
-    if (oy >= Ho) {
-      while (oy >= Ho) { oy -= Ho; ++img; }
-      p = (m + PPI < mend) ? in.ptr(img) : nullptr;
+    if (mb + 64 < mend) {
+      pc.advance(64, Ho, Wo);
+      if (pc.img != pimg) { pimg = pc.img; p = in.ptr(pimg); }
     }
   }
-  // sum over the lanes of the wave that share cg (lane = (pl % (64/TPP)) * TPP + cg)
+  // acc[jn][g*4+q] = D[co = jn*32 + g*8 + h*4 + q][k = l32]
 #pragma unroll
-  for (int j = 0; j < COG; ++j)
+  for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
-    for (int k = 0; k < KP; ++k) {
-      float v = acc[j][k];
-      for (int off = TPP; off < 64; off <<= 1) v += __shfl_xor(v, off);
-      acc[j][k] = v;
-    }
-  const int lane = tid & 63, wave = tid >> 6, npair = Cout * KP;
-  if (lane < TPP) {
-#pragma unroll
-    for (int j = 0; j < COG; ++j)
-#pragma unroll
-      for (int k = 0; k < KP; ++k) wsum[wave * npair + (cg * COG + j) * KP + k] = acc[j][k];
-  }
+    for (int e = 0; e < 16; ++e) wsum[wave][(jn * 32 + (e >> 2) * 8 + h * 4 + (e & 3)) * 32 + l32] = acc[jn][e];
   __syncthreads();
-  float* P = partial + (int64_t)blockIdx.x * npair;
-  for (int pr = tid; pr < npair; pr += 256) P[pr] = (wsum[pr] + wsum[npair + pr]) + (wsum[2 * npair + pr] + wsum[3 * npair + pr]);
+  float* P = partial + (int64_t)blockIdx.x * Cout * KP1;
+  for (int i = tid; i < Cout * KP1; i += 256) {
+    const int co = i / KP1, k = i - co * KP1, s = co * 32 + k;
+    P[i] = (wsum[0][s] + wsum[1][s]) + (wsum[2][s] + wsum[3][s]);
+  }
 }
 // Sum conv1 partials: partial[nb][Cout][K+1] -> gw[Cout][K], gb[Cout].  One block per output
 // element; strided partial sums, then a fixed-order tree.

@@ -377,12 +377,13 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n) {
     ImgAddr in; in.base = c->obs; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
     int Co = c->cC[1], Ho = c->cH[1], Wo = c->cW[1];
     int64_t M = (int64_t)nimg * Ho * Wo;
-    size_t sh = (size_t)(9 * c->cC[0] * Co + Co) * sizeof(float);
     ProfScope ps(c, "conv_fwd.0", 2.0 * (double)M * Co * 9 * c->cC[0], 2.0 * ((double)nimg * c->img_elems + (double)M * Co));
+    constexpr int TPW = 2;
+    const int grid = cdiv(M, 32 * 4 * TPW);
     if (c->cC[0] == 1)
-      hipLaunchKernelGGL((k_conv1_fwd<1>), dim3(cdiv(M, 256)), dim3(256), sh, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->p + c->convW[0], c->p + c->convB[0], c->act[0]);
+      hipLaunchKernelGGL((k_conv1_fwd<1, TPW>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->shadow + c->convW[0], c->p + c->convB[0], c->act[0]);
     else
-      hipLaunchKernelGGL((k_conv1_fwd<3>), dim3(cdiv(M, 256)), dim3(256), sh, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->p + c->convW[0], c->p + c->convB[0], c->act[0]);
+      hipLaunchKernelGGL((k_conv1_fwd<3, TPW>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->shadow + c->convW[0], c->p + c->convB[0], c->act[0]);
     LAUNCHCHK(c, "k_conv1_fwd");
   }
   for (int l = 1; l < c->nconv; ++l) {
@@ -479,17 +480,16 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
     const int Co = c->cC[1], Ho = c->cH[1], Wo = c->cW[1], K = 9 * c->cC[0];
     int64_t M = (int64_t)nimg * Ho * Wo;
     const int npair = Co * (K + 1);
-    const int cog = c->cC[0] == 1 ? 8 : 4, ppi = 256 / (Co / cog);
     int64_t max_blocks = c->partial_elems / npair;
     if (max_blocks > 2048) max_blocks = 2048;
     int64_t ppb = (M + max_blocks - 1) / max_blocks;
-    ppb = (ppb + ppi - 1) / ppi * ppi;
+    ppb = (ppb + 63) / 64 * 64;
     int nblk = cdiv(M, ppb);
     ProfScope ps(c, "conv_wgrad.0", 2.0 * (double)M * Co * (K + 1), 2.0 * ((double)M * Co + (double)nimg * c->img_elems));
     if (c->cC[0] == 1)
-      hipLaunchKernelGGL((k_conv1_wgrad<1, 8>), dim3(nblk), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->gbuf[cur], (int)ppb, c->partial);
+      hipLaunchKernelGGL((k_conv1_wgrad<1>), dim3(nblk), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->gbuf[cur], (int)ppb, c->partial);
     else
-      hipLaunchKernelGGL((k_conv1_wgrad<3, 4>), dim3(nblk), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->gbuf[cur], (int)ppb, c->partial);
+      hipLaunchKernelGGL((k_conv1_wgrad<3>), dim3(nblk), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->gbuf[cur], (int)ppb, c->partial);
     LAUNCHCHK(c, "k_conv1_wgrad");
     hipLaunchKernelGGL(k_conv1_wgrad_reduce, dim3(npair), dim3(256), 0, c->stream, c->partial, nblk, Co, K, c->g + c->convW[0], c->g + c->convB[0], acc ? 1 : 0);
     LAUNCHCHK(c, "k_conv1_wgrad_reduce");

@@ -55,8 +55,8 @@ def ppo_loss(mu, v, logstd, action, logp_old, v_old, adv, ret, clip_eps, vclip_e
 
 
 # ---------------------------------------------------------------------------------------------
-# bf16-operand arithmetic restated with library ops: weights of every layer but the first conv,
-# stored activations and stored activation-gradients rounded to bf16, fp64 accumulation.
+# bf16-operand arithmetic restated with library ops: weights of every layer, stored activations
+# and stored activation-gradients rounded to bf16, fp64 accumulation.
 def _r(x):
     return x.to(torch.bfloat16).to(torch.float64)
 
@@ -66,7 +66,7 @@ class _Conv(torch.autograd.Function):
     def forward(ctx, x, w, b, first):
         ctx.save_for_backward(x, w)
         ctx.first = first
-        return F.conv2d(x, w if first else _r(w), b, stride=2, padding=1)
+        return F.conv2d(x, _r(w), b, stride=2, padding=1)
 
     @staticmethod
     def backward(ctx, g):
