@@ -211,22 +211,36 @@ __global__ __launch_bounds__(256) void k_conv1_fwd(ImgAddr in, int n_img, int H,
 #pragma unroll
     for (int e = 0; e < 16; ++e) { const int c2 = jn * 32 + (e >> 2) * 8 + h * 4 + (e & 3); bs[jn][e] = c2 < Cout ? bias[c2] : 0.f; }
   }
+  // this lane's eight patch entries k = ks*16 + h*8 + j as (row tap u, element offset v*CIN + c)
+  const int64_t mw = (int64_t)(blockIdx.x * 4 + wave) * TPW * 32;  // first pixel of this wave
+  PixCursor pc; pc.init((mw + l32 < M) ? mw + l32 : 0, Ho, Wo);
+  int pimg = pc.img;
+  const bf16_t* p = in.ptr(pimg);
   for (int t = 0; t < TPW; ++t) {
-    const int64_t m0 = ((int64_t)(blockIdx.x * 4 + wave) * TPW + t) * 32;
+    const int64_t m0 = mw + t * 32;
     const int64_t m = m0 + l32;
     const bool valid = m < M;
-    PixCursor pc; pc.init(valid ? m : 0, Ho, Wo);
-    const bf16_t* p = in.ptr(valid ? pc.img : 0);
+    const int iyb = 2 * pc.oy - 1, ixb = 2 * pc.ox - 1;
+    const bool rok[3] = {iyb >= 0, true, iyb + 2 < H};
+    const bool cok[3] = {ixb >= 0, true, ixb + 2 < W};
+    const bf16_t* pb = p + (iyb * W + ixb) * CIN;
     bf16x8_t a[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       bf16_t x[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const int k = ks * 16 + h * 8 + j, tap = k / CIN, c = k - tap * CIN, u = tap / 3, v = tap - 3 * u;
-        const int iy = 2 * pc.oy - 1 + u, ix = 2 * pc.ox - 1 + v;
-        const bool ok = valid && k < K && (unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W;
-        x[j] = ok ? p[(iy * W + ix) * CIN + c] : (bf16_t)0;
+        // both halves' k are compile-time; pick by h
+        constexpr int dummy = 0; (void)dummy;
+        const int k0 = ks * 16 + j, k1 = ks * 16 + 8 + j;
+        const int t0 = k0 / CIN, c0 = k0 - t0 * CIN, u0 = t0 / 3, v0 = t0 - 3 * u0;
+        const int t1 = k1 / CIN, c1 = k1 - t1 * CIN, u1 = t1 / 3, v1 = t1 - 3 * u1;
+        const bool in0 = k0 < K, in1 = k1 < K;
+        const bool ok0 = in0 && rok[in0 ? u0 : 0] && cok[in0 ? v0 : 0];
+        const bool ok1 = in1 && rok[in1 ? u1 : 0] && cok[in1 ? v1 : 0];
+        const int off0 = in0 ? (u0 * W + v0) * CIN + c0 : 0, off1 = in1 ? (u1 * W + v1) * CIN + c1 : 0;
+        const bool ok = valid && (h ? ok1 : ok0);
+        x[j] = ok ? pb[h ? off1 : off0] : (bf16_t)0;
       }
       a[ks] = pack8(x);
     }
@@ -255,6 +269,10 @@ __global__ __launch_bounds__(256) void k_conv1_fwd(ImgAddr in, int n_img, int H,
     for (int ch = lane; ch < 32 * cpr; ch += 64) {
       const int r = ch / cpr, cg = ch - r * cpr;
       if (m0 + r < M) *reinterpret_cast<uint4*>(out + (m0 + r) * Cout + cg * 8) = *reinterpret_cast<const uint4*>(&stage[wave][r * SP + cg * 8]);
+    }
+    if (t + 1 < TPW && m + 32 < M) {
+      pc.advance(32, Ho, Wo);
+      if (pc.img != pimg) { pimg = pc.img; p = in.ptr(pimg); }
     }
   }
 }

@@ -378,7 +378,7 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n) {
     int Co = c->cC[1], Ho = c->cH[1], Wo = c->cW[1];
     int64_t M = (int64_t)nimg * Ho * Wo;
     ProfScope ps(c, "conv_fwd.0", 2.0 * (double)M * Co * 9 * c->cC[0], 2.0 * ((double)nimg * c->img_elems + (double)M * Co));
-    constexpr int TPW = 2;
+    constexpr int TPW = 4;
     const int grid = cdiv(M, 32 * 4 * TPW);
     if (c->cC[0] == 1)
       hipLaunchKernelGGL((k_conv1_fwd<1, TPW>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->shadow + c->convW[0], c->p + c->convB[0], c->act[0]);
