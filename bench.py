@@ -29,14 +29,16 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 PEAK_MFMA_BF16_TF = 2500.0  # dense bf16 MFMA, published
 PEAK_FP32_VALU_TF = 157.3   # fp32 vector, published
 
-# kernel classes that are dense contractions on the matrix cores; the rest are HBM-bound
-MFMA_PREFIXES = ("conv_fwd.", "conv_dgrad.", "conv_wgrad.", "fc_fwd.", "fc_dgrad.", "fc_wgrad.", "head_")
+RIDGE_FLOP_PER_BYTE = PEAK_MFMA_BF16_TF * 1e12 / (PEAK_HBM_GBS * 1e9)  # 312.5
 
 
-def kernel_bound(name: str) -> str:
-    if name in ("conv_fwd.0", "conv_wgrad.0"):
-        return "hbm"  # first layer: K = 9*Cin, fp32 vector arithmetic, limited by the activation traffic
-    return "mfma" if name.startswith(MFMA_PREFIXES) else "hbm"
+def kernel_bound(rec: dict) -> str:
+    """Roofline side of a kernel class: its algorithmic intensity (booked FLOPs / booked bytes) against the
+    ridge point of the bf16-MFMA and HBM peaks.  The convolutions of the first layers have K = 9*Cin of a
+    few hundred at most and sit on the HBM side; the wide linear layers sit on the MFMA side."""
+    if rec["bytes"] <= 0:
+        return "mfma"
+    return "mfma" if rec["flops"] / rec["bytes"] > RIDGE_FLOP_PER_BYTE else "hbm"
 
 
 def main():
@@ -118,11 +120,11 @@ def main():
     dom = max(rep, key=lambda k: rep[k]["ms"])
     r = rep[dom]
     avg_s = r["ms"] / r["launches"] * 1e-3
-    if kernel_bound(dom) == "mfma":
+    if kernel_bound(r) == "mfma":
         ach, peak, unit = r["flops"] / r["launches"] / avg_s / 1e12, PEAK_MFMA_BF16_TF, "TFLOP/s"
     else:
         ach, peak, unit = r["bytes"] / r["launches"] / avg_s / 1e9, PEAK_HBM_GBS, "GB/s"
-    roofline = dict(bound=kernel_bound(dom), kernel=dom, achieved=round(ach, 3), peak=peak, unit=unit,
+    roofline = dict(bound=kernel_bound(r), kernel=dom, intensity_flop_per_byte=round(r["flops"] / max(r["bytes"], 1.0), 1), achieved=round(ach, 3), peak=peak, unit=unit,
                     frac=round(ach / peak, 5), traffic=None, avg_launch_us=round(avg_s * 1e6, 2),
                     launches_per_step=r["launches"] / args.steps, share_of_kernel_time=round(r["ms"] / tot_ms, 4))
     fl = configs.flops_per_sample(net)

@@ -394,7 +394,6 @@ __global__ __launch_bounds__(256) void k_ppo_loss(int B, int Bfull, int A, const
                                                   const float* __restrict__ ret, float clip_eps, float vclip_eps,
                                                   float vf_coef, bf16_t* __restrict__ dout, float* __restrict__ stat_part,
                                                   float* __restrict__ dls_part) {
-  __shared__ float red[256];
   __shared__ float sig_inv[32], ls[32];
   const int tid = threadIdx.x;
   if (tid < A) { ls[tid] = logstd[tid]; sig_inv[tid] = __expf(-logstd[tid]); }
@@ -439,19 +438,23 @@ __global__ __launch_bounds__(256) void k_ppo_loss(int B, int Bfull, int A, const
       d[j] = f2bf(g);
     }
   }
-  // block reductions in a fixed tree order
-  auto block_sum = [&](float v) -> float {
-    red[tid] = v;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) { if (tid < s) red[tid] += red[tid + s]; __syncthreads(); }
-    float r = red[0];
-    __syncthreads();
-    return r;
+  // block reductions in a fixed order: xor-butterfly inside each wave, then the four wave sums
+  __shared__ float wred[4][36];
+  const int lane = tid & 63, wave = tid >> 6;
+  auto wave_sum = [&](float v) -> float {
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
   };
-  for (int k = 0; k < 4; ++k) { float r = block_sum(st[k]); if (tid == 0) stat_part[(int64_t)blockIdx.x * LOSS_NSTAT + k] = r; }
-  for (int j = 0; j < A; ++j) {
-    float r = block_sum(ok ? dlogp * (z[j] * z[j] - 1.f) : 0.f);
-    if (tid == 0) dls_part[(int64_t)blockIdx.x * 32 + j] = r;
+  for (int k = 0; k < 4; ++k) { float r = wave_sum(st[k]); if (lane == 0) wred[wave][k] = r; }
+#pragma unroll
+  for (int j = 0; j < 32; ++j) {
+    if (j < A) { float r = wave_sum(ok ? dlogp * (z[j] * z[j] - 1.f) : 0.f); if (lane == 0) wred[wave][4 + j] = r; }
+  }
+  __syncthreads();
+  if (tid < 4) stat_part[(int64_t)blockIdx.x * LOSS_NSTAT + tid] = (wred[0][tid] + wred[1][tid]) + (wred[2][tid] + wred[3][tid]);
+  else if (tid >= 32 && tid < 32 + A) {
+    const int j = tid - 32;
+    dls_part[(int64_t)blockIdx.x * 32 + j] = (wred[0][4 + j] + wred[1][4 + j]) + (wred[2][4 + j] + wred[3][4 + j]);
   }
 }
 

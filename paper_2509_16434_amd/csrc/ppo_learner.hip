@@ -14,6 +14,7 @@
 
 #include "gemm.hip.h"
 #include "mem_kernels.hip.h"
+#include "fused.hip.h"
 
 static_assert(sizeof(DevStats) == sizeof(ppo_mb_stats), "device and host statistics records must match");
 
@@ -470,6 +471,31 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
     ep.map.stride_b = xa.stride_b; ep.map.stride_v = xa.stride_v; ep.map.V = V; ep.map.H = H; ep.map.W = W; ep.map.Cin = Ci; ep.map.imgs = nimg;
     ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = xa.base; ep.N = 2 * Ci;
     const double pix = (double)nimg * H * W;
+    if (l == 1) {
+      // fused with the first layer's weight gradient: its input gradient never leaves the chip
+      ImgAddr in; in.base = c->obs; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
+      const int K0 = 9 * c->cC[0], npair = Ci * (K0 + 1), tpp = cdiv(M0, 128);
+      int grid = 2 * tpp < 1024 ? 2 * tpp : 1024;
+      if ((int64_t)grid * npair > c->partial_elems) grid = (int)(c->partial_elems / npair);
+      const int N2 = 2 * Ci;
+      {
+        ProfScope ps(c, "conv_dgrad.1+wgrad.0", 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co + 2.0 * pix * Ci * (K0 + 1),
+                     2.0 * ((double)nimg * Ho * Wo * Co + pix * Ci + (double)nimg * c->img_elems + 9.0 * Ci * Co));
+#define LAUNCH_FUSED(BN_, WM_, WN_)                                                                                                      \
+        do {                                                                                                                               \
+          if (c->cC[0] == 1) hipLaunchKernelGGL((k_dgrad1_wgrad0<BN_, WM_, WN_, 1>), dim3(grid), dim3(256), 0, c->stream, al, ep.map, xa.base, in, c->cH[0], c->cW[0], tpp, c->partial); \
+          else hipLaunchKernelGGL((k_dgrad1_wgrad0<BN_, WM_, WN_, 3>), dim3(grid), dim3(256), 0, c->stream, al, ep.map, xa.base, in, c->cH[0], c->cW[0], tpp, c->partial);             \
+        } while (0)
+        if (N2 > 64) LAUNCH_FUSED(128, 2, 2);
+        else if (N2 > 32) LAUNCH_FUSED(64, 2, 2);
+        else LAUNCH_FUSED(32, 4, 1);
+#undef LAUNCH_FUSED
+        LAUNCHCHK(c, "k_dgrad1_wgrad0");
+      }
+      hipLaunchKernelGGL(k_conv1_wgrad_reduce, dim3(npair), dim3(256), 0, c->stream, c->partial, grid, Ci, K0, c->g + c->convW[0], c->g + c->convB[0], acc ? 1 : 0);
+      LAUNCHCHK(c, "k_conv1_wgrad_reduce");
+      return PPO_OK;
+    }
     double ab = 2.0 * ((double)nimg * Ho * Wo * Co + 2.0 * pix * Ci + 9.0 * Ci * Co);
     rc = launch_gemm(c, al, M0, nullptr, 0, 2 * Ci, 4 * Co, ep, "conv_dgrad." + std::to_string(l), ab, 2, 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co);
     if (rc) return rc;
