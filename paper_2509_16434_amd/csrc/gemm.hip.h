@@ -187,19 +187,23 @@ struct Ep {
 // columns n.  bf16 results are packed four at a time, staged through LDS (8-byte writes) and
 // leave as 16-byte row segments (with the ReLU mask read the same way); fp32 results are written
 // directly.
-template <int BM, int BN, int WGM, int WGN, class AL, class EP>
+template <int BM, int BN, int WGM, int WGN, int BK, class AL, class EP>
 __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ Bm_, int64_t ldb_, int N, EP ep) {
+  // BK = 32: double-buffered LDS, one barrier per step.  BK = 64: single LDS buffer with the next
+  // step's tiles held in registers (twice the bytes in flight per block at the same LDS footprint).
   constexpr int TM = BM / (WGM * 32), TN = BN / (WGN * 32);
-  static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1, "tile shape");
-  constexpr int ACH = (BM * 4 + 255) / 256, BCH = (BN * 4 + 255) / 256;  // 16-byte chunks per thread
-  constexpr int AB_ELEMS = 2 * (BM + BN) * GEMM_PITCH;
+  static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && (BK == 32 || BK == 64), "tile shape");
+  constexpr int CPK = BK / 8;                     // 16-byte chunks per row
+  constexpr int PITCH = BK + 8, NBUF = (BK == 32) ? 2 : 1;
+  constexpr int ACH = (BM * CPK + 255) / 256, BCH = (BN * CPK + 255) / 256;  // chunks per thread
+  constexpr int AB_ELEMS = NBUF * (BM + BN) * PITCH;
   constexpr int SP = BN + 8;  // staging pitch (bf16 elements)
   static_assert(BM * SP <= AB_ELEMS, "staging tile must fit in the operand buffers");
   __shared__ __attribute__((aligned(16))) bf16_t smem[AB_ELEMS];
   __shared__ int64_t rowoff[BM];
   __shared__ int rowcols[BM];
-  bf16_t* As = smem;                         // [2][BM*PITCH]
-  bf16_t* Bs = smem + 2 * BM * GEMM_PITCH;   // [2][BN*PITCH]
+  bf16_t* As = smem;                          // [NBUF][BM*PITCH]
+  bf16_t* Bs = smem + NBUF * BM * PITCH;      // [NBUF][BN*PITCH]
 
   const typename AL::Cls acls = al.cls(blockIdx.z);
   const auto mcls = ep.map.cls(blockIdx.z);
@@ -217,14 +221,14 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
 #pragma unroll
   for (int c = 0; c < ACH; ++c) {
     int ch = tid + c * 256;
-    a_r[c] = ch >> 2; a_k[c] = (ch & 3) * 8;
+    a_r[c] = ch / CPK; a_k[c] = (ch % CPK) * 8;
     arow[c] = al.row(a_r[c] < BM ? m0 + a_r[c] : acls.M, acls);
   }
   const bf16_t* brow[BCH]; int b_r[BCH], b_k[BCH];
 #pragma unroll
   for (int c = 0; c < BCH; ++c) {
     int ch = tid + c * 256;
-    b_r[c] = ch >> 2; b_k[c] = (ch & 3) * 8;
+    b_r[c] = ch / CPK; b_k[c] = (ch % CPK) * 8;
     int n = n0 + b_r[c];
     brow[c] = (b_r[c] < BN && n < N) ? Bm + (int64_t)n * ldb : nullptr;
   }
@@ -240,7 +244,7 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
   uint4 ra[ACH], rb[BCH];
   auto gload = [&](int k0) {
 #pragma unroll
-    for (int c = 0; c < ACH; ++c) ra[c] = al.template load<true>(arow[c], k0, a_k[c], acls);
+    for (int c = 0; c < ACH; ++c) ra[c] = al.template load<BK == 32>(arow[c], k0, a_k[c], acls);
 #pragma unroll
     for (int c = 0; c < BCH; ++c) {
       int k = k0 + b_k[c];
@@ -250,37 +254,38 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
   auto sstore = [&](int buf) {
 #pragma unroll
     for (int c = 0; c < ACH; ++c)
-      if (a_r[c] < BM) *reinterpret_cast<uint4*>(&As[buf * BM * GEMM_PITCH + a_r[c] * GEMM_PITCH + a_k[c]]) = ra[c];
+      if (a_r[c] < BM) *reinterpret_cast<uint4*>(&As[buf * BM * PITCH + a_r[c] * PITCH + a_k[c]]) = ra[c];
 #pragma unroll
     for (int c = 0; c < BCH; ++c)
-      if (b_r[c] < BN) *reinterpret_cast<uint4*>(&Bs[buf * BN * GEMM_PITCH + b_r[c] * GEMM_PITCH + b_k[c]]) = rb[c];
+      if (b_r[c] < BN) *reinterpret_cast<uint4*>(&Bs[buf * BN * PITCH + b_r[c] * PITCH + b_k[c]]) = rb[c];
   };
 
-  const int nk = (K + GEMM_BK - 1) / GEMM_BK;
+  const int nk = (K + BK - 1) / BK;
   gload(0);
   sstore(0);
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) gload((kt + 1) * GEMM_BK);
-    const bf16_t* Ab = As + buf * BM * GEMM_PITCH;
-    const bf16_t* Bb = Bs + buf * BN * GEMM_PITCH;
+    const int buf = (NBUF == 2) ? (kt & 1) : 0;
+    if (kt + 1 < nk) gload((kt + 1) * BK);
+    const bf16_t* Ab = As + buf * BM * PITCH;
+    const bf16_t* Bb = Bs + buf * BN * PITCH;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8_t a[TM], b[TN];
       const int kk = ks * 16 + (lane >> 5) * 8;
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        a[i] = *reinterpret_cast<const bf16x8_t*>(&Ab[((wm * TM + i) * 32 + (lane & 31)) * GEMM_PITCH + kk]);
+        a[i] = *reinterpret_cast<const bf16x8_t*>(&Ab[((wm * TM + i) * 32 + (lane & 31)) * PITCH + kk]);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        b[j] = *reinterpret_cast<const bf16x8_t*>(&Bb[((wn * TN + j) * 32 + (lane & 31)) * GEMM_PITCH + kk]);
+        b[j] = *reinterpret_cast<const bf16x8_t*>(&Bb[((wn * TN + j) * 32 + (lane & 31)) * PITCH + kk]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) sstore(buf ^ 1);
+    if (NBUF == 1) __syncthreads();  // everyone is done reading the single buffer
+    if (kt + 1 < nk) sstore(NBUF == 2 ? (buf ^ 1) : 0);
     __syncthreads();
   }
 

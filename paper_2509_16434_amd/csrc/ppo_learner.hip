@@ -272,26 +272,23 @@ int launch_gemm(Ctx* c, const AL& al, int M, const bf16_t* Bm, int64_t ldb, int 
   const char* what = name.c_str();
   ProfScope ps(c, name, flops >= 0.0 ? flops : 2.0 * M * (double)N * K, abytes);
   dim3 blk(256);
+  // deep reductions use 64-wide k steps (more bytes in flight per block)
+#define LAUNCH_GEMM(BM_, BN_, WM_, WN_, GX, GY)                                                                        \
+  do {                                                                                                                   \
+    dim3 grid(GX, GY, zdim);                                                                                             \
+    if (K >= 128) hipLaunchKernelGGL((k_gemm<BM_, BN_, WM_, WN_, 64, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep); \
+    else hipLaunchKernelGGL((k_gemm<BM_, BN_, WM_, WN_, 32, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);        \
+  } while (0)
   if (N > 64) {
-    if ((int64_t)cdiv(M, 128) * cdiv(N, 128) * zdim >= 256 || M <= 64) {
-      dim3 grid(cdiv(M, 128), cdiv(N, 128), zdim);
-      hipLaunchKernelGGL((k_gemm<128, 128, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);
-    } else {
-      dim3 grid(cdiv(M, 64), cdiv(N, 64), zdim);
-      hipLaunchKernelGGL((k_gemm<64, 64, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);
-    }
+    if ((int64_t)cdiv(M, 128) * cdiv(N, 128) * zdim >= 256 || M <= 64) LAUNCH_GEMM(128, 128, 2, 2, cdiv(M, 128), cdiv(N, 128));
+    else LAUNCH_GEMM(64, 64, 2, 2, cdiv(M, 64), cdiv(N, 64));
   } else if (N > 32) {
-    if ((int64_t)cdiv(M, 128) * zdim >= 256 || M <= 64) {
-      dim3 grid(cdiv(M, 128), 1, zdim);
-      hipLaunchKernelGGL((k_gemm<128, 64, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);
-    } else {
-      dim3 grid(cdiv(M, 64), 1, zdim);
-      hipLaunchKernelGGL((k_gemm<64, 64, 2, 2, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);
-    }
+    if ((int64_t)cdiv(M, 128) * zdim >= 256 || M <= 64) LAUNCH_GEMM(128, 64, 2, 2, cdiv(M, 128), 1);
+    else LAUNCH_GEMM(64, 64, 2, 2, cdiv(M, 64), 1);
   } else {
-    dim3 grid(cdiv(M, 128), 1, zdim);
-    hipLaunchKernelGGL((k_gemm<128, 32, 4, 1, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);
+    LAUNCH_GEMM(128, 32, 4, 1, cdiv(M, 128), 1);
   }
+#undef LAUNCH_GEMM
   LAUNCHCHK(c, what);
   return PPO_OK;
 }
