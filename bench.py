@@ -68,21 +68,21 @@ def main():
     distill = cfg["kind"] == "distill"
     S = N * T
 
-    # ---- synthetic rollout, generated on the host per step and made resident in HBM
+    # ---- synthetic rollout, drawn per step on the GPU (seeded) and kept resident in HBM
     stream = torch.cuda.Stream()
     lrn = learner.Learner(net, N, T, cfg["obs_dtype"], stream=stream)
     lrn.set_params(synth.init_params(net, cfg["seed"]))
-    rng = np.random.default_rng(cfg["seed"])
-    odt = torch.float32 if cfg["obs_dtype"] == "fp32" else torch.bfloat16
-    steps_dev, sample_host = [], None
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg["seed"])
+    fl = configs.flops_per_sample(net)
+    n_cpu = int(max(8, min(S, 4.0e11 / fl["fwd_bwd"])))  # ~4e11 FLOPs of oracle work, about 10-30 s of CPU time
+    steps_dev, host_steps = [], []
     for t in range(T):
-        st = synth.rollout_step(cfg, rng)
-        if t == 0:
-            sample_host = st
-        d = {k: torch.from_numpy(v).cuda() for k, v in st.items()}
-        d["obs"] = d["obs"].to(odt).contiguous()
+        d = synth.rollout_step_torch(cfg, gen)
+        if len(host_steps) * N < n_cpu:
+            host_steps.append({k: v.float().cpu().numpy() if v.dtype != torch.uint8 else v.cpu().numpy() for k, v in d.items()})
         steps_dev.append(d)
-    last_value = torch.from_numpy(rng.standard_normal(N, dtype=np.float32)).cuda()
+    last_value = torch.randn(N, generator=gen, device="cuda")
     torch.cuda.synchronize()
 
     def one_step():
@@ -127,7 +127,6 @@ def main():
     roofline = dict(bound=kernel_bound(r), kernel=dom, intensity_flop_per_byte=round(r["flops"] / max(r["bytes"], 1.0), 1), achieved=round(ach, 3), peak=peak, unit=unit,
                     frac=round(ach / peak, 5), traffic=None, avg_launch_us=round(avg_s * 1e6, 2),
                     launches_per_step=r["launches"] / args.steps, share_of_kernel_time=round(r["ms"] / tot_ms, 4))
-    fl = configs.flops_per_sample(net)
     step_flops = fl["fwd_bwd"] * S * hp["epochs"]
     if args.profile_table:
         print(f"{'class':<16}{'launches':>9}{'ms/step':>10}{'share':>8}{'TFLOP/s':>10}{'GB/s':>10}", file=sys.stderr)
@@ -142,10 +141,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import ppo_oracle as orc
-        per_sample = fl["fwd_bwd"]
-        n_sub = int(max(8, min(N, 7.0e10 / per_sample)))  # ~7e10 FLOPs of oracle work, about 10-30 s of CPU time
-        n_sub = min(n_sub, N)
-        sub = {k: v[:n_sub] for k, v in sample_host.items()}
+        n_sub = min(n_cpu, len(host_steps) * N)
+        sub = {k: np.concatenate([h[k] for h in host_steps])[:n_sub] for k in host_steps[0]}
         p = synth.init_params(net, cfg["seed"])
         t1 = time.perf_counter()
         if distill:

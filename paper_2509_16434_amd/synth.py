@@ -153,3 +153,52 @@ def init_params(net: dict, seed: int) -> np.ndarray:
             x *= 0.01
         parts.append(x)
     return np.concatenate([p.reshape(-1) for p in parts])
+
+
+# ---------------------------------------------------------------------------------------------
+# The same recipe drawn on the GPU with torch's seeded generator: used by the benchmark, where the
+# large workloads (up to 10^10 pixels) would take minutes to draw on the host.  Same distributions,
+# different random stream than the numpy generators above (which feed the parity tests).
+def _rects_torch(gen, n, h, w, dev):
+    ri = lambda lo, hi: torch.randint(lo, hi, (n,), generator=gen, device=dev)
+    cnt = ri(1, 5)
+    return [(cnt > k, ri(0, h), ri(0, w), ri(max(1, h // 8), h // 2 + 1), ri(max(1, w // 8), w // 2 + 1)) for k in range(4)]
+
+
+def _paint_torch(img, rects, values):
+    n, c, h, w = img.shape
+    ys = torch.arange(h, device=img.device)[None, :, None]
+    xs = torch.arange(w, device=img.device)[None, None, :]
+    for (on, top, left, rh, rw), val in zip(rects, values):
+        m = (on[:, None, None] & (ys >= top[:, None, None]) & (ys < (top + rh)[:, None, None])
+             & (xs >= left[:, None, None]) & (xs < (left + rw)[:, None, None]))
+        img = torch.where(m[:, None], val[:, :, None, None], img)
+    return img
+
+
+def rollout_step_torch(cfg: dict, gen, device="cuda") -> dict:
+    """One step's slab for all N envs as CUDA tensors (obs already in the config's dtype)."""
+    net, N = cfg["net"], cfg["num_envs"]
+    V, Cc, H, W, P, A = net["n_views"], net["in_c"], net["in_h"], net["in_w"], net["proprio_dim"], net["act_dim"]
+    u = lambda *s: torch.rand(*s, generator=gen, device=device)
+    g = lambda *s: torch.randn(*s, generator=gen, device=device)
+    views = []
+    for _ in range(V):
+        chunks = []
+        for a in range(0, N, 2048):
+            m = min(N, a + 2048) - a
+            rects = _rects_torch(gen, m, H, W, device)
+            if Cc == 1:
+                img = torch.full((m, 1, H, W), 2.0, device=device)
+                img = _paint_torch(img, rects, [0.2 + 1.3 * u(m, 1) for _ in range(4)])
+                img = img + 0.01 * g(m, 1, H, W)
+                img = torch.where(u(m, 1, H, W) < 0.05, torch.zeros_like(img), img)
+            else:
+                img = _paint_torch(u(m, Cc, H, W), rects, [u(m, Cc) for _ in range(4)])
+            chunks.append(img.to(torch.float32 if cfg["obs_dtype"] == "fp32" else torch.bfloat16))
+        views.append(torch.cat(chunks))
+    obs = torch.stack(views, dim=1).contiguous()
+    action = g(N, A)
+    logp = (-0.5 * (action.double() ** 2).sum(1) - 0.5 * A * math.log(2 * math.pi) + 0.1 * g(N).double()).float()
+    return dict(obs=obs, proprio=g(N, P), action=action, logp_old=logp, value=g(N), reward=g(N),
+                done=(u(N) < 0.01).to(torch.uint8))
