@@ -20,22 +20,32 @@ __global__ __launch_bounds__(256) void k_dgrad1_wgrad0(AConvDgrad al, MapDgrad m
                                                        ImgAddr img_in, int H0, int W0, int tiles_per_parity,
                                                        float* __restrict__ partial) {
   constexpr int BM = 128, TM = BM / (WGM * 32), TN = BN / (WGN * 32);
-  constexpr int ACH = (BM * 4 + 255) / 256, BCH = (BN * 4 + 255) / 256;
-  constexpr int AB_ELEMS = 2 * (BM + BN) * GEMM_PITCH, SP = BN + 8;
+  constexpr int BK = 64, PITCH = BK + 8, ACH = BM * (BK / 8) / 256;
+  constexpr int SP = BN + 8;
+  constexpr int SM_ELEMS = (BM * PITCH > BM * SP) ? BM * PITCH : BM * SP;
   constexpr int K0 = 9 * CIN0, KP1 = K0 + 1;
-  static_assert(BM * SP <= AB_ELEMS, "staging tile must fit in the operand buffers");
-  __shared__ __attribute__((aligned(16))) bf16_t smem[AB_ELEMS];
+  __shared__ __attribute__((aligned(16))) bf16_t smem[SM_ELEMS];   // A tile, later the staged output tile
   __shared__ int64_t rowoff[BM];
   __shared__ int64_t rowbase[BM];
   __shared__ int rowyx[BM], rowcols[BM];
   constexpr int XR = (KP1 <= 16) ? 16 : 32, XP = 2 * BM + 8;  // patch table rows (taps, padded) and pitch
   __shared__ __attribute__((aligned(16))) bf16_t xT[XR * XP];
+  // the packed transposed-conv weights of both row parities stay in LDS for the whole kernel, as
+  // [k/8][BN][8] so that a lane's 8 consecutive k of column n are one conflict-free 16-byte read
+  extern __shared__ __attribute__((aligned(16))) bf16_t wl[];
   bf16_t* As = smem;
-  bf16_t* Bs = smem + 2 * BM * GEMM_PITCH;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, h = lane >> 5;
   const int wm = wave / WGN, wn = wave % WGN;
   const int Cin = map.Cin, N = 2 * Cin, NJ = (Cin + 31) / 32;
+  const int Kp0 = 2 << al.lco, Kp1 = 4 << al.lco;  // depth of parity 0 / 1
+  for (int i = tid; i < (Kp0 + Kp1) / 8 * BN; i += 256) {
+    const int k8 = i / BN, n = i - k8 * BN;
+    uint4 v = zero16();
+    if (n < N) v = (k8 < Kp0 / 8) ? *reinterpret_cast<const uint4*>(al.w0 + (int64_t)n * Kp0 + k8 * 8)
+                                  : *reinterpret_cast<const uint4*>(al.w1 + (int64_t)n * Kp1 + (k8 - Kp0 / 8) * 8);
+    *reinterpret_cast<uint4*>(&wl[(int64_t)i * 8]) = v;
+  }
   // the patch table's unused rows stay zero for the whole kernel
   for (int i = tid; i < XR * XP; i += 256) xT[i] = 0;
 
@@ -51,22 +61,15 @@ __global__ __launch_bounds__(256) void k_dgrad1_wgrad0(AConvDgrad al, MapDgrad m
     const MapDgrad::Cls mcls = map.cls(z);
     if (m0 >= acls.M) continue;  // block-uniform
     const int K = acls.K;
-    const bf16_t* Bm = acls.w;
+    const bf16_t* Wz = wl + (z ? (Kp0 / 8) * BN * 8 : 0);
 
     AConvDgrad::Row arow[ACH];
     int a_r[ACH], a_k[ACH];
 #pragma unroll
     for (int c = 0; c < ACH; ++c) {
       int ch = tid + c * 256;
-      a_r[c] = ch >> 2; a_k[c] = (ch & 3) * 8;
-      arow[c] = al.row(a_r[c] < BM ? m0 + a_r[c] : acls.M, acls);
-    }
-    const bf16_t* brow[BCH]; int b_r[BCH], b_k[BCH];
-#pragma unroll
-    for (int c = 0; c < BCH; ++c) {
-      int ch = tid + c * 256;
-      b_r[c] = ch >> 2; b_k[c] = (ch & 3) * 8;
-      brow[c] = (b_r[c] < BN && b_r[c] < N) ? Bm + (int64_t)b_r[c] * K : nullptr;
+      a_r[c] = ch >> 3; a_k[c] = (ch & 7) * 8;
+      arow[c] = al.row(m0 + a_r[c], acls);
     }
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -76,24 +79,12 @@ __global__ __launch_bounds__(256) void k_dgrad1_wgrad0(AConvDgrad al, MapDgrad m
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    uint4 ra[ACH], rb[BCH];
+    uint4 ra[ACH];
     auto gload = [&](int k0) {
 #pragma unroll
-      for (int c = 0; c < ACH; ++c) ra[c] = al.template load<true>(arow[c], k0, a_k[c], acls);
-#pragma unroll
-      for (int c = 0; c < BCH; ++c) {
-        int k = k0 + b_k[c];
-        rb[c] = (brow[c] && k < K) ? *reinterpret_cast<const uint4*>(brow[c] + k) : zero16();
-      }
+      for (int c = 0; c < ACH; ++c) ra[c] = al.template load<false>(arow[c], k0, a_k[c], acls);
     };
-    auto sstore = [&](int buf) {
-#pragma unroll
-      for (int c = 0; c < ACH; ++c)
-        if (a_r[c] < BM) *reinterpret_cast<uint4*>(&As[buf * BM * GEMM_PITCH + a_r[c] * GEMM_PITCH + a_k[c]]) = ra[c];
-#pragma unroll
-      for (int c = 0; c < BCH; ++c)
-        if (b_r[c] < BN) *reinterpret_cast<uint4*>(&Bs[buf * BN * GEMM_PITCH + b_r[c] * GEMM_PITCH + b_k[c]]) = rb[c];
-    };
+    gload(0);
     __syncthreads();  // the previous tile's LDS readers are done
     // ---- 0. row tables, then issue the loads the epilogue will need (ReLU mask segments of the stored
     //         activation, this thread's image patch) so that their latency overlaps the main loop
@@ -137,31 +128,31 @@ __global__ __launch_bounds__(256) void k_dgrad1_wgrad0(AConvDgrad al, MapDgrad m
             xv[(u * 3 + v) * CIN0 + c] = (ok && rok[u] && cok[v]) ? pb[(u * W0 + v) * CIN0 + c] : (bf16_t)0;
       xv[K0] = ok ? (bf16_t)0x3F80 : (bf16_t)0;  // 1.0
     }
-    const int nk = (K + GEMM_BK - 1) / GEMM_BK;
-    gload(0);
-    sstore(0);
-    __syncthreads();
+    // ---- main loop: 64-wide k steps, A through one LDS buffer with the next step held in registers
+    const int nk = (K + BK - 1) / BK;
     for (int kt = 0; kt < nk; ++kt) {
-      const int buf = kt & 1;
-      if (kt + 1 < nk) gload((kt + 1) * GEMM_BK);
-      const bf16_t* Ab = As + buf * BM * GEMM_PITCH;
-      const bf16_t* Bb = Bs + buf * BN * GEMM_PITCH;
+      if (kt > 0) __syncthreads();  // the previous step's readers are done
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
+      for (int c = 0; c < ACH; ++c) *reinterpret_cast<uint4*>(&As[a_r[c] * PITCH + a_k[c]]) = ra[c];
+      __syncthreads();
+      if (kt + 1 < nk) gload((kt + 1) * BK);
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
         bf16x8_t a[TM], b[TN];
         const int kk = ks * 16 + h * 8;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(&Ab[((wm * TM + i) * 32 + l32) * GEMM_PITCH + kk]);
+        for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(&As[((wm * TM + i) * 32 + l32) * PITCH + kk]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8_t*>(&Bb[((wn * TN + j) * 32 + l32) * GEMM_PITCH + kk]);
+        for (int j = 0; j < TN; ++j)
+          b[j] = (kt * BK + kk < K) ? *reinterpret_cast<const bf16x8_t*>(&Wz[(((kt * BK + kk) >> 3) * BN + (wn * TN + j) * 32 + l32) * 8])
+                                    : __builtin_bit_cast(bf16x8_t, zero16());
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
       }
-      if (kt + 1 < nk) sstore(buf ^ 1);
-      __syncthreads();
     }
+    __syncthreads();  // all waves are done with the A tile; its LDS becomes the staging tile
 
     // ---- 1. the unmasked bf16 tile
     bf16_t* stage = smem;

@@ -468,24 +468,28 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
     ep.map.stride_b = xa.stride_b; ep.map.stride_v = xa.stride_v; ep.map.V = V; ep.map.H = H; ep.map.W = W; ep.map.Cin = Ci; ep.map.imgs = nimg;
     ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = xa.base; ep.N = 2 * Ci;
     const double pix = (double)nimg * H * W;
-    if (l == 1) {
+    const int N2 = 2 * Ci, BNf = N2 > 64 ? 128 : (N2 > 32 ? 64 : 32);
+    const size_t wlds = (size_t)6 * Co * BNf * sizeof(bf16_t);  // both parities' packed weights, resident in LDS
+    if (l == 1 && wlds <= 56 * 1024) {
       // fused with the first layer's weight gradient: its input gradient never leaves the chip
       ImgAddr in; in.base = c->obs; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
       const int K0 = 9 * c->cC[0], npair = Ci * (K0 + 1), tpp = cdiv(M0, 128);
-      int grid = 2 * tpp < 1024 ? 2 * tpp : 1024;
+      int grid = 2 * tpp < 512 ? 2 * tpp : 512;
       if ((int64_t)grid * npair > c->partial_elems) grid = (int)(c->partial_elems / npair);
-      const int N2 = 2 * Ci;
       {
         ProfScope ps(c, "conv_dgrad.1+wgrad.0", 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co + 2.0 * pix * Ci * (K0 + 1),
                      2.0 * ((double)nimg * Ho * Wo * Co + pix * Ci + (double)nimg * c->img_elems + 9.0 * Ci * Co));
-#define LAUNCH_FUSED(BN_, WM_, WN_)                                                                                                      \
-        do {                                                                                                                               \
-          if (c->cC[0] == 1) hipLaunchKernelGGL((k_dgrad1_wgrad0<BN_, WM_, WN_, 1>), dim3(grid), dim3(256), 0, c->stream, al, ep.map, xa.base, in, c->cH[0], c->cW[0], tpp, c->partial); \
-          else hipLaunchKernelGGL((k_dgrad1_wgrad0<BN_, WM_, WN_, 3>), dim3(grid), dim3(256), 0, c->stream, al, ep.map, xa.base, in, c->cH[0], c->cW[0], tpp, c->partial);             \
+#define LAUNCH_FUSED(BN_, WM_, WN_, CI0_)                                                                                                  \
+        do {                                                                                                                                 \
+          auto kfn = k_dgrad1_wgrad0<BN_, WM_, WN_, CI0_>;                                                                                   \
+          HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)wlds));                            \
+          hipLaunchKernelGGL(kfn, dim3(grid), dim3(256), wlds, c->stream, al, ep.map, xa.base, in, c->cH[0], c->cW[0], tpp, c->partial);      \
         } while (0)
-        if (N2 > 64) LAUNCH_FUSED(128, 2, 2);
-        else if (N2 > 32) LAUNCH_FUSED(64, 2, 2);
-        else LAUNCH_FUSED(32, 4, 1);
+        if (c->cC[0] == 1) {
+          if (BNf == 128) LAUNCH_FUSED(128, 2, 2, 1); else if (BNf == 64) LAUNCH_FUSED(64, 2, 2, 1); else LAUNCH_FUSED(32, 4, 1, 1);
+        } else {
+          if (BNf == 128) LAUNCH_FUSED(128, 2, 2, 3); else if (BNf == 64) LAUNCH_FUSED(64, 2, 2, 3); else LAUNCH_FUSED(32, 4, 1, 3);
+        }
 #undef LAUNCH_FUSED
         LAUNCHCHK(c, "k_dgrad1_wgrad0");
       }
