@@ -28,6 +28,10 @@ struct ARows {
   __device__ __forceinline__ Cls cls(int) const { Cls c; c.M = M; c.K = K; return c; }
   __device__ __forceinline__ Row row(int m, const Cls&) const { return row(m); }
   template <bool U32> __device__ __forceinline__ uint4 load(const Row& r, int k0, int koff, const Cls&) const { return load(r, k0 + koff); }
+  // address of the 8 elements load() would return, nullptr where it returns zeros
+  template <bool U32> __device__ __forceinline__ const bf16_t* addr(const Row& r, int k0, int koff, const Cls&) const {
+    return (!r.p || k0 + koff >= K) ? nullptr : r.p + k0 + koff;
+  }
   __device__ __forceinline__ const bf16_t* bmat(const Cls&, const bf16_t* dflt) const { return dflt; }
   __device__ __forceinline__ Row row(int m) const {
     Row r; r.p = nullptr; r.img = 0; r.q = 0;
@@ -67,6 +71,14 @@ struct AConvFwd {
       return *reinterpret_cast<const uint4*>(r.p + ((iy * W + ix) << lc) + ci);
     }
     return load(r, k0 + koff);
+  }
+  template <bool U32> __device__ __forceinline__ const bf16_t* addr(const Row& r, int k0, int koff, const Cls&) const {
+    const int k = k0 + koff;
+    if (!r.p || k >= K) return nullptr;
+    const int tap = k >> lc, ci = k & (Cin - 1), u = tap / 3, v = tap - 3 * u;
+    const int iy = r.iy0 + u, ix = r.ix0 + v;
+    if ((unsigned)iy >= (unsigned)H || (unsigned)ix >= (unsigned)W) return nullptr;
+    return r.p + ((iy * W + ix) << lc) + ci;
   }
   __device__ __forceinline__ const bf16_t* bmat(const Cls&, const bf16_t* dflt) const { return dflt; }
   __device__ __forceinline__ Row row(int m) const {
@@ -124,16 +136,20 @@ struct AConvDgrad {
     }
     return r;
   }
-  template <bool U32> __device__ __forceinline__ uint4 load(const Row& r, int k0, int koff, const Cls& c) const {
+  template <bool U32> __device__ __forceinline__ const bf16_t* addr(const Row& r, int k0, int koff, const Cls& c) const {
     const int k = k0 + koff;
-    if (!r.p || k >= c.K) return zero16();
+    if (!r.p || k >= c.K) return nullptr;
     int t, co;  // t = tu*2 + dx
     if (U32 && lco >= 5) { t = k0 >> lco; co = (k0 & (Cout - 1)) + koff; }  // wave-uniform tap
     else { t = k >> lco; co = k & (Cout - 1); }
     const int tu = t >> 1, dx = t & 1;
     const int oy = r.a + (c.py ? 1 - tu : 0), ox = r.b + dx;
-    if (oy >= Ho || ox >= Wo) return zero16();
-    return *reinterpret_cast<const uint4*>(r.p + ((oy * Wo + ox) << lco) + co);
+    if (oy >= Ho || ox >= Wo) return nullptr;
+    return r.p + ((oy * Wo + ox) << lco) + co;
+  }
+  template <bool U32> __device__ __forceinline__ uint4 load(const Row& r, int k0, int koff, const Cls& c) const {
+    const bf16_t* p = addr<U32>(r, k0, koff, c);
+    return p ? *reinterpret_cast<const uint4*>(p) : zero16();
   }
 };
 
@@ -178,6 +194,77 @@ struct Ep {
   static constexpr bool kBias = BIAS, kRelu = RELU, kMask = MASK;
   MAP map; OutT* out; const float* bias; const bf16_t* mask; int N;
 };
+
+// Epilogue shared by the tile kernels.  acc[i][j][g*4+q] = C[m][n] with m = m0 + (wm*TM+i)*32 +
+// lane%32, n = n0 + (wn*TN+j)*32 + g*8 + (lane/32)*4 + q.  bf16 results are packed four at a
+// time, staged through `stage` (BM x (BN+8) elements of LDS no longer in use) and leave as
+// 16-byte row segments; fp32 results are written directly.
+template <int BM, int BN, int TM, int TN, class EP, class MCLS>
+__device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[TM][TN], const EP& ep, const MCLS& mcls, int m0, int n0, int N, int wm, int wn,
+                                              bf16_t* stage, int64_t* rowoff, int* rowcols) {
+  constexpr int SP = BN + 8;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // acc[i][j][g*4+q] = C[m][n] with m = m0 + (wm*TM+i)*32 + lane%32, n = n0 + (wn*TN+j)*32 + g*8 + (lane/32)*4 + q
+  typedef typename EP::out_t OutT;
+  if constexpr (sizeof(OutT) == 2) {
+    for (int r = tid; r < BM; r += 256) { rowoff[r] = ep.map.row_offset(m0 + r, mcls); rowcols[r] = ep.map.row_cols(m0 + r, mcls); }
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int cl = (wn * TN + j) * 32 + g * 8 + (lane >> 5) * 4, nb = n0 + cl;
+        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (EP::kBias) { if (nb < N) bv = *reinterpret_cast<const float4*>(ep.bias + nb); }  // N is a multiple of 8
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          float v0 = acc[i][j][g * 4] + bv.x, v1 = acc[i][j][g * 4 + 1] + bv.y, v2 = acc[i][j][g * 4 + 2] + bv.z, v3 = acc[i][j][g * 4 + 3] + bv.w;
+          if (EP::kRelu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+          uint2 o; o.x = pack2bf(v0, v1); o.y = pack2bf(v2, v3);
+          *reinterpret_cast<uint2*>(&stage[((wm * TM + i) * 32 + (lane & 31)) * SP + cl]) = o;
+        }
+      }
+    __syncthreads();
+    constexpr int CPR = BN / 8;  // 16-byte chunks per row
+    bf16_t* out = reinterpret_cast<bf16_t*>(ep.out);
+    for (int ch = tid; ch < BM * CPR; ch += 256) {
+      const int rl = ch / CPR, cg = ch - rl * CPR, n = n0 + cg * 8;
+      const int64_t off = rowoff[rl];
+      if (off < 0 || n >= N || n >= rowcols[rl]) continue;
+      uint4 v = *reinterpret_cast<const uint4*>(&stage[rl * SP + cg * 8]);
+      if (EP::kMask) {
+        // keep a half where the stored activation is > 0 (sign bit clear and not zero)
+        const uint4 mk = *reinterpret_cast<const uint4*>(ep.mask + off + n);
+        auto keep = [](uint32_t m) -> uint32_t {
+          return (((short)(m & 0xffffu) > 0) ? 0x0000ffffu : 0u) | (((short)(m >> 16) > 0) ? 0xffff0000u : 0u);
+        };
+        v.x &= keep(mk.x); v.y &= keep(mk.y); v.z &= keep(mk.z); v.w &= keep(mk.w);
+      }
+      *reinterpret_cast<uint4*>(out + off + n) = v;
+    }
+  } else {
+    float* out = reinterpret_cast<float*>(ep.out);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int64_t off = ep.map.row_offset(m0 + (wm * TM + i) * 32 + (lane & 31), mcls);
+      if (off < 0) continue;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int nb = n0 + (wn * TN + j) * 32 + g * 8 + (lane >> 5) * 4;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (nb + q >= N) continue;
+            float x = acc[i][j][g * 4 + q];
+            if (EP::kBias) x += ep.bias[nb + q];
+            if (EP::kRelu) x = x > 0.f ? x : 0.f;
+            if (EP::kMask) { if (!((short)ep.mask[off + nb + q] > 0)) x = 0.f; }
+            out[off + nb + q] = x;
+          }
+        }
+    }
+  }
+}
 
 // ---------------------------------------------------------------- C = A * B^T
 // B is a plain [N][K] matrix (row stride ldb; loaders with per-class weights override it).  256
@@ -289,90 +376,49 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
     __syncthreads();
   }
 
-  // acc[i][j][g*4+q] = C[m][n] with m = m0 + (wm*TM+i)*32 + lane%32, n = n0 + (wn*TN+j)*32 + g*8 + (lane/32)*4 + q
-  typedef typename EP::out_t OutT;
-  if constexpr (sizeof(OutT) == 2) {
-    for (int r = tid; r < BM; r += 256) { rowoff[r] = ep.map.row_offset(m0 + r, mcls); rowcols[r] = ep.map.row_cols(m0 + r, mcls); }
-    bf16_t* stage = smem;  // the operand buffers are free now
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int cl = (wn * TN + j) * 32 + g * 8 + (lane >> 5) * 4, nb = n0 + cl;
-        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (EP::kBias) { if (nb < N) bv = *reinterpret_cast<const float4*>(ep.bias + nb); }  // N is a multiple of 8
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          float v0 = acc[i][j][g * 4] + bv.x, v1 = acc[i][j][g * 4 + 1] + bv.y, v2 = acc[i][j][g * 4 + 2] + bv.z, v3 = acc[i][j][g * 4 + 3] + bv.w;
-          if (EP::kRelu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
-          uint2 o; o.x = pack2bf(v0, v1); o.y = pack2bf(v2, v3);
-          *reinterpret_cast<uint2*>(&stage[((wm * TM + i) * 32 + (lane & 31)) * SP + cl]) = o;
-        }
-      }
-    __syncthreads();
-    constexpr int CPR = BN / 8;  // 16-byte chunks per row
-    bf16_t* out = reinterpret_cast<bf16_t*>(ep.out);
-    for (int ch = tid; ch < BM * CPR; ch += 256) {
-      const int rl = ch / CPR, cg = ch - rl * CPR, n = n0 + cg * 8;
-      const int64_t off = rowoff[rl];
-      if (off < 0 || n >= N || n >= rowcols[rl]) continue;
-      uint4 v = *reinterpret_cast<const uint4*>(&stage[rl * SP + cg * 8]);
-      if (EP::kMask) {
-        // keep a half where the stored activation is > 0 (sign bit clear and not zero)
-        const uint4 mk = *reinterpret_cast<const uint4*>(ep.mask + off + n);
-        auto keep = [](uint32_t m) -> uint32_t {
-          return (((short)(m & 0xffffu) > 0) ? 0x0000ffffu : 0u) | (((short)(m >> 16) > 0) ? 0xffff0000u : 0u);
-        };
-        v.x &= keep(mk.x); v.y &= keep(mk.y); v.z &= keep(mk.z); v.w &= keep(mk.w);
-      }
-      *reinterpret_cast<uint4*>(out + off + n) = v;
-    }
-  } else {
-    float* out = reinterpret_cast<float*>(ep.out);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int64_t off = ep.map.row_offset(m0 + (wm * TM + i) * 32 + (lane & 31), mcls);
-      if (off < 0) continue;
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int nb = n0 + (wn * TN + j) * 32 + g * 8 + (lane >> 5) * 4;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            if (nb + q >= N) continue;
-            float x = acc[i][j][g * 4 + q];
-            if (EP::kBias) x += ep.bias[nb + q];
-            if (EP::kRelu) x = x > 0.f ? x : 0.f;
-            if (EP::kMask) { if (!((short)ep.mask[off + nb + q] > 0)) x = 0.f; }
-            out[off + nb + q] = x;
-          }
-        }
-    }
-  }
+  gemm_epilogue<BM, BN, TM, TN>(acc, ep, mcls, m0, n0, N, wm, wn, smem, rowoff, rowcols);
 }
 
 // ---------------------------------------------------------------- weight gradient
 // G[n][k] (+)= sum_m Dy[m][n] * A[m][k]: both operands are row-major over the contracted index m,
-// so 16-byte chunks (8 consecutive n or k of one row m) are written transposed into LDS and the
-// MFMA operands are then read as 8 consecutive m.  Block tile: 64 (n) x 128*KTW (k), 32 rows of m
-// per step; wave w owns the k-tiles w, w+4, ... (KTW of them) for both 32-row n-tiles, so Dy is
-// read once per 128*KTW columns of k.  grid.z splits the m range, each split writing its own fp32
-// partial tile (summed later in a fixed order).  Block (x == 0) also accumulates the column sums of
-// Dy (the bias gradient).  Rows are tracked incrementally (no integer division in the loop).
+// while an MFMA lane needs 8 consecutive m of ONE column.  The tiles are stored in LDS as they
+// come (16-byte row chunks, rows = m) and read back through ds_read_b64_tr_b16, which transposes
+// within groups of 16 lanes: when lane r of a group supplies the address of 4 consecutive columns
+// c0 + 4*(r%4) .. +3 of row m0 + r/4, lane i of the group receives column c0 + i of rows m0 .. m0+3.
+// Two such reads give a lane its 8 m-values; the order of m inside the contraction is the same
+// for both operands, which is all the sum needs.  Row pitches are 64 bytes mod 256, so the four
+// rows a half-wave reads fall into disjoint banks.
+//
+// Block tile: 64 (n) x 128*KTW (k), 32 rows of m per step, double-buffered (one barrier per step);
+// 8 consecutive lanes fetch 128 contiguous bytes of one row.  Wave w owns the k-tiles w, w+4, ...
+// (KTW of them) for both 32-row n-tiles, so Dy is read once per 128*KTW columns of k.  grid.z splits
+// the m range, each split writing its own fp32 partial tile (summed later in a fixed order).
+// Block (x == 0) also accumulates the column sums of Dy (the bias gradient).  Rows are tracked
+// incrementally (no integer division in the loop).
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8_t lds_read_tr8(const bf16_t* p, int rows4_elems) {
+  // p: this lane's source address for the first 4 rows; the second 4 rows are rows4_elems further on
+  struct { s16x4_t lo, hi; } v;
+  v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p));
+  v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p + rows4_elems));
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+
 template <int KTW, class DL, class AL>
 __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int M, int rows_per_split,
                                                float* __restrict__ partial, float* __restrict__ bias_partial) {
   constexpr int BKC = 128 * KTW;             // k columns per block
-  constexpr int XCH = BKC / 8 * 32 / 256;    // X chunks per thread per step (= KTW * 2)
-  __shared__ __attribute__((aligned(16))) bf16_t Ds[64 * GEMM_PITCH];
-  __shared__ __attribute__((aligned(16))) bf16_t Xs[BKC * GEMM_PITCH];
+  constexpr int XCH = 2 * KTW;               // X chunks per thread per step
+  constexpr int DP = 64 + 32, XP = BKC + 32; // row pitches (elements): 192 and 256*KTW + 64 bytes
+  __shared__ __attribute__((aligned(16))) bf16_t Dt[2][32 * DP];
+  __shared__ __attribute__((aligned(16))) bf16_t Xt[2][32 * XP];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int k0 = blockIdx.x * BKC, n0 = blockIdx.y * 64;
   const int split = blockIdx.z;
   const int mbeg = split * rows_per_split;
   const int mend = min(M, mbeg + rows_per_split);
-  const int ml = tid & 31, g8 = (tid >> 5) * 8;  // this thread's row within the step and its first 8-wide column group
+  const int ml = tid >> 3, c8 = (tid & 7) * 8;  // this thread's row within the step and its first column
+  const bool do_bias = bias_partial && blockIdx.x == 0;
 
   f32x16_t acc[KTW][2];
 #pragma unroll
@@ -381,7 +427,9 @@ __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
-  float bsum = 0.f;
+  float bs[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) bs[j] = 0.f;
 
   int m = mbeg + ml;
   typename DL::Row dr = dl.row(m < mend ? m : M);
@@ -389,25 +437,30 @@ __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int
   uint4 rd, rx[XCH];
   auto gload = [&]() {
     const bool ok = m < mend;
-    rd = ok ? dl.template load<false>(dr, n0, g8, dl.cls(0)) : zero16();
+    rd = ok ? dl.template load<false>(dr, n0, c8, dl.cls(0)) : zero16();
 #pragma unroll
-    for (int c = 0; c < XCH; ++c) rx[c] = ok ? al.template load<false>(ar, k0 + c * 64, g8, al.cls(0)) : zero16();
+    for (int c = 0; c < XCH; ++c) rx[c] = ok ? al.template load<false>(ar, k0 + c * 64, c8, al.cls(0)) : zero16();
   };
-  auto sstore = [&]() {
-    const bf16_t* d = reinterpret_cast<const bf16_t*>(&rd);
+  auto sstore = [&](int buf) {
+    *reinterpret_cast<uint4*>(&Dt[buf][ml * DP + c8]) = rd;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) Ds[(g8 + j) * GEMM_PITCH + ml] = d[j];
-#pragma unroll
-    for (int c = 0; c < XCH; ++c) {
-      const bf16_t* x = reinterpret_cast<const bf16_t*>(&rx[c]);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) Xs[(g8 + c * 64 + j) * GEMM_PITCH + ml] = x[j];
+    for (int c = 0; c < XCH; ++c) *reinterpret_cast<uint4*>(&Xt[buf][ml * XP + c * 64 + c8]) = rx[c];
+    if (do_bias) {
+      bs[0] += bf2f((bf16_t)(rd.x & 0xffffu)); bs[1] += bf2f((bf16_t)(rd.x >> 16));
+      bs[2] += bf2f((bf16_t)(rd.y & 0xffffu)); bs[3] += bf2f((bf16_t)(rd.y >> 16));
+      bs[4] += bf2f((bf16_t)(rd.z & 0xffffu)); bs[5] += bf2f((bf16_t)(rd.z >> 16));
+      bs[6] += bf2f((bf16_t)(rd.w & 0xffffu)); bs[7] += bf2f((bf16_t)(rd.w >> 16));
     }
   };
+  // transposing reads: source row / column of this lane within a 16-row k-step and a 32-column tile
+  const int g = lane >> 4, r16 = lane & 15;
+  const int srow = 8 * (g >> 1) + (r16 >> 2), scol = 16 * (g & 1) + 4 * (r16 & 3);
+
   const int nsteps = (mend > mbeg) ? (mend - mbeg + 31) / 32 : 0;
-  if (nsteps > 0) { gload(); sstore(); }
+  if (nsteps > 0) { gload(); sstore(0); }
   __syncthreads();
   for (int st = 0; st < nsteps; ++st) {
+    const int buf = st & 1;
     if (st + 1 < nsteps) {
       m += 32;
       dl.advance(dr, 32, m < mend ? m : M);
@@ -416,26 +469,20 @@ __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int
     }
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      const int kk = ks * 16 + (lane >> 5) * 8;
-      const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(&Ds[(lane & 31) * GEMM_PITCH + kk]);
-      const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(&Ds[(32 + (lane & 31)) * GEMM_PITCH + kk]);
+      const bf16_t* dsrc = &Dt[buf][(ks * 16 + srow) * DP + scol];
+      const bf16x8_t a0 = lds_read_tr8(dsrc, 4 * DP);
+      const bf16x8_t a1 = lds_read_tr8(dsrc + 32, 4 * DP);
 #pragma unroll
       for (int t = 0; t < KTW; ++t) {
         const int ktile = wave + 4 * t;
         if (k0 + ktile * 32 < Kk) {
-          const bf16x8_t b = *reinterpret_cast<const bf16x8_t*>(&Xs[(ktile * 32 + (lane & 31)) * GEMM_PITCH + kk]);
+          const bf16x8_t b = lds_read_tr8(&Xt[buf][(ks * 16 + srow) * XP + ktile * 32 + scol], 4 * XP);
           acc[t][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[t][0], 0, 0, 0);
           acc[t][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[t][1], 0, 0, 0);
         }
       }
     }
-    if (bias_partial && blockIdx.x == 0 && tid < 64) {
-      const bf16_t* r = &Ds[tid * GEMM_PITCH];
-#pragma unroll
-      for (int q = 0; q < 32; ++q) bsum += bf2f(r[q]);
-    }
-    __syncthreads();
-    if (st + 1 < nsteps) sstore();
+    if (st + 1 < nsteps) sstore(buf ^ 1);
     __syncthreads();
   }
   float* P = partial + (int64_t)split * Nn * Kk;
@@ -450,7 +497,18 @@ __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int
         if (n < Nn && k < Kk) P[(int64_t)n * Kk + k] = acc[t][i][e];
       }
   }
-  if (bias_partial && blockIdx.x == 0 && tid < 64 && n0 + tid < Nn) bias_partial[(int64_t)split * Nn + n0 + tid] = bsum;
+  if (do_bias) {
+    // column sums: thread (row ml, columns c8..c8+7) -> sum over the 32 rows in a fixed order
+    float* red = reinterpret_cast<float*>(&Xt[0][0]);  // 32 x 64 floats = 8 KB (the loop's last barrier has passed)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) red[ml * 64 + c8 + j] = bs[j];
+    __syncthreads();
+    if (tid < 64 && n0 + tid < Nn) {
+      float s = 0.f;
+      for (int q = 0; q < 32; ++q) s += red[q * 64 + tid];
+      bias_partial[(int64_t)split * Nn + n0 + tid] = s;
+    }
+  }
 }
 
 // dst[i] = (accumulate ? dst[i] : 0) + sum_s partial[s][i].  A block covers 32 outputs with 8

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "gemm.hip.h"
+#include "gemm_dma.hip.h"
 #include "mem_kernels.hip.h"
 #include "fused.hip.h"
 
@@ -58,6 +59,7 @@ struct Ctx {
   bf16_t* dhead = nullptr;        // [CH][32]
   bf16_t* gbuf[2] = {nullptr, nullptr};
   float *partial = nullptr, *bias_partial = nullptr;
+  bf16_t* zpage = nullptr;  // 256 bytes of zeros: source of out-of-range operand fetches
   int64_t partial_elems = 0, bias_partial_elems = 0;
   float *stat_part = nullptr, *dls_part = nullptr, *sq_part = nullptr;
   int max_loss_blocks = 0, adam_blocks = 0;
@@ -272,11 +274,19 @@ int launch_gemm(Ctx* c, const AL& al, int M, const bf16_t* Bm, int64_t ldb, int 
   const char* what = name.c_str();
   ProfScope ps(c, name, flops >= 0.0 ? flops : 2.0 * M * (double)N * K, abytes);
   dim3 blk(256);
-  // deep reductions use 64-wide k steps (more bytes in flight per block)
+  // Very deep reductions stream their operands through a three-stage LDS ring (two 64-wide k steps
+  // in flight per block); medium ones take 64-wide steps through registers, where the smaller LDS
+  // footprint lets more blocks share a CU and hide the prologue and epilogue of their short loops.
 #define LAUNCH_GEMM(BM_, BN_, WM_, WN_, GX, GY)                                                                        \
   do {                                                                                                                   \
     dim3 grid(GX, GY, zdim);                                                                                             \
-    if (K >= 128) hipLaunchKernelGGL((k_gemm<BM_, BN_, WM_, WN_, 64, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep); \
+    if (K >= 1024) {                                                                                                     \
+      auto kfn = k_gemm_dma<BM_, BN_, WM_, WN_, 3, AL, EP>;                                                              \
+      constexpr int lds = 3 * (BM_ + BN_) * 128;                                                                         \
+      static bool attr_set = false;                                                                                      \
+      if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, lds)); attr_set = true; } \
+      hipLaunchKernelGGL(kfn, grid, blk, lds, c->stream, al, Bm, ldb, N, ep, c->zpage);                                   \
+    } else if (K >= 128) hipLaunchKernelGGL((k_gemm<BM_, BN_, WM_, WN_, 64, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep); \
     else hipLaunchKernelGGL((k_gemm<BM_, BN_, WM_, WN_, 32, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);        \
   } while (0)
   if (N > 64) {
@@ -648,6 +658,8 @@ int create_impl(Ctx* c) {
   want(c->NH, c->hid, CH);
   c->partial_elems = pe; c->bias_partial_elems = bpe;
   DALLOC(c, c->partial, pe); DALLOC(c, c->bias_partial, bpe);
+  DALLOC(c, c->zpage, 128);
+  HIPCHK(c, hipMemsetAsync(c->zpage, 0, 256, c->stream));
   // loss / Adam partials
   c->max_loss_blocks = cdiv(S, CH) * cdiv(CH, 256) + 1;
   DALLOC(c, c->stat_part, (int64_t)c->max_loss_blocks * LOSS_NSTAT); DALLOC(c, c->dls_part, (int64_t)c->max_loss_blocks * 32);
@@ -934,6 +946,8 @@ int ppo_diag_gemm(int32_t M, int32_t N, int32_t K, const float* h_a, const float
   auto body = [&]() -> int {
     DALLOC(c, da, (int64_t)M * K); DALLOC(c, db, (int64_t)N * K); DALLOC(c, dc, (int64_t)M * N);
     DALLOC(c, ba, (int64_t)M * K); DALLOC(c, bb, (int64_t)N * K);
+    DALLOC(c, c->zpage, 128);
+    HIPCHK(c, hipMemset(c->zpage, 0, 256));
     HIPCHK(c, hipMemcpy(da, h_a, sizeof(float) * (size_t)M * K, hipMemcpyHostToDevice));
     HIPCHK(c, hipMemcpy(db, h_b, sizeof(float) * (size_t)N * K, hipMemcpyHostToDevice));
     hipLaunchKernelGGL(k_cast_bf16, dim3(cdiv((int64_t)M * K, 256)), dim3(256), 0, c->stream, da, ba, (int64_t)M * K);
