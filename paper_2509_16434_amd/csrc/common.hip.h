@@ -17,7 +17,29 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
 __device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
-  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));  // one v_cvt_pk_bf16_f32
+}
+
+// Division of n < 2^31 by a launch constant d >= 1 without a divide: with 2^sh < d <= 2^(sh+1)
+// and mul = floor(2^(32+sh) / d) + 1, floor(n / d) = (n * mul) >> (32 + sh) exactly (the error
+// term n * (mul*d - 2^(32+sh)) stays below 2^(32+sh)).  d == 0 marks "not prepared".
+struct FastDiv {
+  uint32_t mul = 0, sh = 0, d = 0;
+  __device__ __forceinline__ uint32_t div(uint32_t n) const { return d == 1u ? n : (__umulhi(n, mul) >> sh); }
+};
+inline FastDiv make_fastdiv(int32_t d) {
+  FastDiv f;
+  f.d = (uint32_t)d;
+  if (d > 1) {
+    uint32_t sh = 0;
+    while ((2u << sh) < (uint32_t)d) ++sh;
+    f.sh = sh;
+    f.mul = (uint32_t)((((uint64_t)1 << (32 + sh)) / (uint32_t)d) + 1);
+  }
+  return f;
 }
 
 // Address of image `img` (= sample*V + view) inside a tensor whose samples may be gathered
@@ -28,8 +50,11 @@ struct ImgAddr {
   int64_t stride_b;    // elements between consecutive samples
   int64_t stride_v;    // elements between views of one sample
   int32_t V;
+  FastDiv dv;          // optional: set by prepare()
+  void prepare() { dv = make_fastdiv(V); }
   __device__ __forceinline__ const bf16_t* ptr(int img) const {
-    int b = img / V, v = img - b * V;
+    int b = img, v = 0;
+    if (V != 1) { b = (dv.d == (uint32_t)V) ? (int)dv.div((uint32_t)img) : img / V; v = img - b * V; }
     int64_t s = idx ? (int64_t)idx[b] : (int64_t)b;
     return base + s * stride_b + (int64_t)v * stride_v;
   }

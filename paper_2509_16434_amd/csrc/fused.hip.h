@@ -64,13 +64,14 @@ __global__ __launch_bounds__(256) void k_dgrad1_wgrad0(AConvDgrad al, MapDgrad m
     const bf16_t* Wz = wl + (z ? (Kp0 / 8) * BN * 8 : 0);
 
     AConvDgrad::Row arow[ACH];
-    int a_r[ACH], a_k[ACH];
+    int a_r[ACH];
+    const int ck = (tid & 7) * 8;  // the same column group for all of a thread's chunks
 #pragma unroll
     for (int c = 0; c < ACH; ++c) {
-      int ch = tid + c * 256;
-      a_r[c] = ch >> 3; a_k[c] = (ch & 7) * 8;
+      a_r[c] = (tid + c * 256) >> 3;
       arow[c] = al.row(m0 + a_r[c], acls);
     }
+    AConvDgrad::KCur acur = al.kcur(ck, acls);
     f32x16_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -80,11 +81,12 @@ __global__ __launch_bounds__(256) void k_dgrad1_wgrad0(AConvDgrad al, MapDgrad m
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     uint4 ra[ACH];
-    auto gload = [&](int k0) {
+    auto gload = [&]() {
 #pragma unroll
-      for (int c = 0; c < ACH; ++c) ra[c] = al.template load<false>(arow[c], k0, a_k[c], acls);
+      for (int c = 0; c < ACH; ++c) ra[c] = a_load(al, arow[c], acur, acls);
+      al.kstep(acur, BK, acls);
     };
-    gload(0);
+    gload();
     __syncthreads();  // the previous tile's LDS readers are done
     // ---- 0. row tables, then issue the loads the epilogue will need (ReLU mask segments of the stored
     //         activation, this thread's image patch) so that their latency overlaps the main loop
@@ -92,8 +94,9 @@ __global__ __launch_bounds__(256) void k_dgrad1_wgrad0(AConvDgrad al, MapDgrad m
       const int m = m0 + r;
       int64_t off = -1, base = 0; int yx = 0, cols = 0;
       if (m < mcls.M) {
-        const int hw = mcls.Ha * mcls.Wb, img = m / hw, q = m - img * hw, a = q / mcls.Wb, bb = q - a * mcls.Wb;
-        const int b = img / map.V, v = img - b * map.V;
+        const int hw = mcls.Ha * mcls.Wb, img = (int)mcls.dhw.div((uint32_t)m), q = m - img * hw;
+        const int a = (int)map.dwb.div((uint32_t)q), bb = q - a * mcls.Wb;
+        const int b = (int)map.dv.div((uint32_t)img), v = img - b * map.V;
         const int iy = 2 * a + mcls.py, ix0 = 2 * bb;
         off = (int64_t)b * map.stride_b + (int64_t)v * map.stride_v + ((int64_t)iy * map.W + ix0) * Cin;
         base = img_in.ptr(img) - img_in.base;
@@ -133,9 +136,9 @@ __global__ __launch_bounds__(256) void k_dgrad1_wgrad0(AConvDgrad al, MapDgrad m
     for (int kt = 0; kt < nk; ++kt) {
       if (kt > 0) __syncthreads();  // the previous step's readers are done
 #pragma unroll
-      for (int c = 0; c < ACH; ++c) *reinterpret_cast<uint4*>(&As[a_r[c] * PITCH + a_k[c]]) = ra[c];
+      for (int c = 0; c < ACH; ++c) *reinterpret_cast<uint4*>(&As[a_r[c] * PITCH + ck]) = ra[c];
       __syncthreads();
-      if (kt + 1 < nk) gload((kt + 1) * BK);
+      if (kt + 1 < nk) gload();
 #pragma unroll
       for (int ks = 0; ks < BK / 16; ++ks) {
         bf16x8_t a[TM], b[TN];

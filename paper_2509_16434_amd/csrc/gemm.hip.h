@@ -14,28 +14,35 @@
 __device__ __forceinline__ uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
 
 // ---------------------------------------------------------------- A-row loaders
-// Every loader offers row(m) -> Row, load(Row, k) -> 8 consecutive k of that row (zero outside),
-// advance(Row&, delta, M) -> the row delta further on without integer division (weight-gradient
-// kernel), and cls(z) -> the per-grid.z parameter set (row count M, depth K, weight matrix).
+// A loader describes the rows of the A matrix of an implicit GEMM, split so that nothing that
+// depends on the row alone or on the column alone is recomputed per fetch:
+//   cls(z)                    per-grid.z parameter set (row count M, depth K, weight matrix)
+//   row(m, cls) -> Row        the row's base address, pixel offset and tap-validity bits
+//   advance(Row&, delta, m)   the row delta further on (weight-gradient kernel)
+//   kcur(k, cls) -> KCur      the column's tap / channel / element offset (k a multiple of 8)
+//   kstep(KCur&, dk, cls)     the column dk further on
+//   addr(Row, KCur, cls)      address of A[m][k..k+7], nullptr where those are zeros
+// prepare() (host) fills the division constants from the geometry fields.
 
 // Rows of a channel-last tensor: row m = (img, q) with img = m / HW, q = m % HW, each row C
 // elements wide, images addressed through ImgAddr (plain matrices: HW = 1, V = 1, stride_b = lda).
 struct ARows {
   ImgAddr a; int HW, C, M, K;
   bool plain;  // HW == 1, one view, no gather: consecutive rows are stride_b apart
+  FastDiv dhw;
+  void prepare() { a.prepare(); dhw = make_fastdiv(HW); }
   struct Row { const bf16_t* p; int img, q; };
+  struct KCur { int k; };
   struct Cls { int M, K; };
   __device__ __forceinline__ Cls cls(int) const { Cls c; c.M = M; c.K = K; return c; }
-  __device__ __forceinline__ Row row(int m, const Cls&) const { return row(m); }
-  template <bool U32> __device__ __forceinline__ uint4 load(const Row& r, int k0, int koff, const Cls&) const { return load(r, k0 + koff); }
-  // address of the 8 elements load() would return, nullptr where it returns zeros
-  template <bool U32> __device__ __forceinline__ const bf16_t* addr(const Row& r, int k0, int koff, const Cls&) const {
-    return (!r.p || k0 + koff >= K) ? nullptr : r.p + k0 + koff;
-  }
   __device__ __forceinline__ const bf16_t* bmat(const Cls&, const bf16_t* dflt) const { return dflt; }
+  __device__ __forceinline__ Row row(int m, const Cls&) const { return row(m); }
   __device__ __forceinline__ Row row(int m) const {
     Row r; r.p = nullptr; r.img = 0; r.q = 0;
-    if (m < M) { r.img = m / HW; r.q = m - r.img * HW; r.p = a.ptr(r.img) + (int64_t)r.q * C; }
+    if (m < M) {
+      if (plain) { r.img = m; r.p = a.base + (int64_t)m * a.stride_b; }
+      else { r.img = (int)dhw.div((uint32_t)m); r.q = m - r.img * HW; r.p = a.ptr(r.img) + (int64_t)r.q * C; }
+    }
     return r;
   }
   __device__ __forceinline__ void advance(Row& r, int delta, int m_new) const {
@@ -46,65 +53,66 @@ struct ARows {
     while (r.q >= HW) { r.q -= HW; ++r.img; }
     r.p = a.ptr(r.img) + (int64_t)r.q * C;
   }
-  __device__ __forceinline__ uint4 load(const Row& r, int k) const {
-    if (!r.p || k >= K) return zero16();
-    return *reinterpret_cast<const uint4*>(r.p + k);
+  __device__ __forceinline__ KCur kcur(int k, const Cls&) const { KCur c; c.k = k; return c; }
+  __device__ __forceinline__ void kstep(KCur& c, int dk, const Cls&) const { c.k += dk; }
+  __device__ __forceinline__ const bf16_t* addr(const Row& r, const KCur& c, const Cls&) const {
+    return (!r.p || c.k >= K) ? nullptr : r.p + c.k;
   }
 };
 
-// Row m = (img, oy, ox) of the im2col matrix of a channel-last image; k = (u*3+v)*Cin + ci.
-// Cin is a power of two (lc = log2 Cin).
+// Row m = (img, oy, ox) of the im2col matrix of a channel-last image under a 3x3 stride-2 pad-1
+// window; k = (u*3+v)*Cin + ci.  Cin is a power of two (lc = log2 Cin).  A row keeps the element
+// offset of its window's corner pixel (iy0, ix0) = (2oy-1, 2ox-1), which may lie outside the
+// image, and one validity bit per tap; a column keeps its tap and the tap's element offset.
 struct AConvFwd {
   ImgAddr in; int H, W, Cin, lc, Ho, Wo, M, K;
-  struct Row { const bf16_t* p; int iy0, ix0, img; };
+  FastDiv dhw, dwo;
+  void prepare() { in.prepare(); dhw = make_fastdiv(Ho * Wo); dwo = make_fastdiv(Wo); }
+  struct Row { const bf16_t* base; int poff, iy0, ix0, img; uint32_t vm; };
+  struct KCur { int tap, ci, off; };
   struct Cls { int M, K; };
   __device__ __forceinline__ Cls cls(int) const { Cls c; c.M = M; c.K = K; return c; }
-  __device__ __forceinline__ Row row(int m, const Cls&) const { return row(m); }
-  // U32: k0 is a multiple of 32 and koff < 32, so with Cin >= 32 the whole chunk group lies in one
-  // kernel tap and the tap arithmetic is wave-uniform.
-  template <bool U32> __device__ __forceinline__ uint4 load(const Row& r, int k0, int koff, const Cls&) const {
-    if (U32 && lc >= 5) {
-      if (!r.p || k0 >= K) return zero16();
-      const int tap = k0 >> lc, u = tap / 3, v = tap - 3 * u, ci = (k0 & (Cin - 1)) + koff;
-      const int iy = r.iy0 + u, ix = r.ix0 + v;
-      if ((unsigned)iy >= (unsigned)H || (unsigned)ix >= (unsigned)W) return zero16();
-      return *reinterpret_cast<const uint4*>(r.p + ((iy * W + ix) << lc) + ci);
-    }
-    return load(r, k0 + koff);
-  }
-  template <bool U32> __device__ __forceinline__ const bf16_t* addr(const Row& r, int k0, int koff, const Cls&) const {
-    const int k = k0 + koff;
-    if (!r.p || k >= K) return nullptr;
-    const int tap = k >> lc, ci = k & (Cin - 1), u = tap / 3, v = tap - 3 * u;
-    const int iy = r.iy0 + u, ix = r.ix0 + v;
-    if ((unsigned)iy >= (unsigned)H || (unsigned)ix >= (unsigned)W) return nullptr;
-    return r.p + ((iy * W + ix) << lc) + ci;
-  }
   __device__ __forceinline__ const bf16_t* bmat(const Cls&, const bf16_t* dflt) const { return dflt; }
+  __device__ __forceinline__ void finish(Row& r) const {
+    r.poff = (r.iy0 * W + r.ix0) << lc;
+    const uint32_t cv = (r.ix0 >= 0 ? 1u : 0u) | 2u | (r.ix0 + 2 < W ? 4u : 0u);  // taps v = 0, 1, 2
+    r.vm = (r.iy0 >= 0 ? cv : 0u) | (cv << 3) | (r.iy0 + 2 < H ? (cv << 6) : 0u);
+  }
+  __device__ __forceinline__ Row row(int m, const Cls&) const { return row(m); }
   __device__ __forceinline__ Row row(int m) const {
-    Row r; r.p = nullptr; r.iy0 = 0; r.ix0 = 0; r.img = 0;
+    Row r; r.base = nullptr; r.poff = 0; r.iy0 = 0; r.ix0 = 0; r.img = 0; r.vm = 0u;
     if (m < M) {
-      int hw = Ho * Wo, img = m / hw, q = m - img * hw, oy = q / Wo, ox = q - oy * Wo;
-      r.p = in.ptr(img); r.iy0 = 2 * oy - 1; r.ix0 = 2 * ox - 1; r.img = img;
+      const int hw = Ho * Wo, img = (int)dhw.div((uint32_t)m), q = m - img * hw;
+      const int oy = (int)dwo.div((uint32_t)q), ox = q - oy * Wo;
+      r.base = in.ptr(img); r.iy0 = 2 * oy - 1; r.ix0 = 2 * ox - 1; r.img = img;
+      finish(r);
     }
     return r;
   }
   __device__ __forceinline__ void advance(Row& r, int delta, int m_new) const {
-    if (m_new >= M) { r.p = nullptr; return; }
+    if (m_new >= M) { r.base = nullptr; r.vm = 0u; return; }
     r.ix0 += 2 * delta;
-    if (r.ix0 < 2 * Wo - 1) return;
-    while (r.ix0 >= 2 * Wo - 1) { r.ix0 -= 2 * Wo; r.iy0 += 2; }
-    if (r.iy0 >= 2 * Ho - 1) {
-      while (r.iy0 >= 2 * Ho - 1) { r.iy0 -= 2 * Ho; ++r.img; }
-      r.p = in.ptr(r.img);
+    if (r.ix0 >= 2 * Wo - 1) {
+      while (r.ix0 >= 2 * Wo - 1) { r.ix0 -= 2 * Wo; r.iy0 += 2; }
+      if (r.iy0 >= 2 * Ho - 1) {
+        while (r.iy0 >= 2 * Ho - 1) { r.iy0 -= 2 * Ho; ++r.img; }
+        r.base = in.ptr(r.img);
+      }
     }
+    finish(r);
   }
-  __device__ __forceinline__ uint4 load(const Row& r, int k) const {
-    if (!r.p || k >= K) return zero16();
-    int tap = k >> lc, ci = k & (Cin - 1), u = tap / 3, v = tap - 3 * u;
-    int iy = r.iy0 + u, ix = r.ix0 + v;
-    if ((unsigned)iy >= (unsigned)H || (unsigned)ix >= (unsigned)W) return zero16();
-    return *reinterpret_cast<const uint4*>(r.p + (((int64_t)iy * W + ix) << lc) + ci);
+  __device__ __forceinline__ void set_off(KCur& c) const {
+    const int u = (c.tap * 11) >> 5, v = c.tap - 3 * u;  // tap / 3 for tap < 32
+    c.off = ((u * W + v) << lc) + c.ci;
+  }
+  __device__ __forceinline__ KCur kcur(int k, const Cls&) const {
+    KCur c; c.tap = k >> lc; c.ci = k & (Cin - 1); set_off(c); return c;
+  }
+  __device__ __forceinline__ void kstep(KCur& c, int dk, const Cls&) const {
+    c.ci += dk; c.tap += c.ci >> lc; c.ci &= Cin - 1; set_off(c);
+  }
+  __device__ __forceinline__ const bf16_t* addr(const Row& r, const KCur& c, const Cls&) const {
+    return ((r.vm >> (c.tap & 31)) & 1u) ? r.base + (r.poff + c.off) : nullptr;  // vm has no bits beyond tap 8
   }
 };
 
@@ -118,51 +126,70 @@ struct AConvFwd {
 struct AConvDgrad {
   ImgAddr dy; int Ho, Wo, Cout, lco, H, W, dy_imgs;
   const bf16_t *w0, *w1;  // packed weights [2*Cin][nu*2*Cout] of row parity 0 / 1
-  struct Row { const bf16_t* p; int a, b; };
-  struct Cls { int Ha, Wb, py, M, K; const bf16_t* w; };
+  FastDiv dhw[2], dwb;
+  void prepare() {
+    dy.prepare();
+    const int Wb = (W + 1) >> 1;
+    dwb = make_fastdiv(Wb);
+    for (int z = 0; z < 2; ++z) { const int Ha = (H - z + 1) >> 1; dhw[z] = make_fastdiv(Ha * Wb > 0 ? Ha * Wb : 1); }
+  }
+  struct Row { const bf16_t* base; int poff, a, b; uint32_t vm; };
+  struct KCur { int t, co, off; };
+  struct Cls { int Ha, Wb, py, M, K; const bf16_t* w; FastDiv dhw; };
   __device__ __forceinline__ Cls cls(int z) const {
     Cls c; c.py = z;
     c.Ha = (H - z + 1) >> 1; c.Wb = (W + 1) >> 1;
     c.M = dy_imgs * c.Ha * c.Wb; c.K = (1 + z) << (lco + 1);
     c.w = z ? w1 : w0;
+    c.dhw = z ? dhw[1] : dhw[0];
     return c;
   }
   __device__ __forceinline__ const bf16_t* bmat(const Cls& c, const bf16_t*) const { return c.w; }
   __device__ __forceinline__ Row row(int m, const Cls& c) const {
-    Row r; r.p = nullptr; r.a = 0; r.b = 0;
+    Row r; r.base = nullptr; r.poff = 0; r.a = 0; r.b = 0; r.vm = 0u;
     if (m < c.M) {
-      int hw = c.Ha * c.Wb, img = m / hw, q = m - img * hw;
-      r.a = q / c.Wb; r.b = q - r.a * c.Wb; r.p = dy.ptr(img);
+      const int hw = c.Ha * c.Wb, img = (int)c.dhw.div((uint32_t)m), q = m - img * hw;
+      r.a = (int)dwb.div((uint32_t)q); r.b = q - r.a * c.Wb; r.base = dy.ptr(img);
+      r.poff = (r.a * Wo + r.b) << lco;
+      const uint32_t cx = 1u | (r.b + 1 < Wo ? 2u : 0u);  // dx = 0, 1
+      // even rows: one row tap (oy = a); odd rows: tu = 0 -> oy = a+1, tu = 1 -> oy = a
+      r.vm = c.py ? ((r.a + 1 < Ho ? cx : 0u) | (cx << 2)) : cx;
     }
     return r;
   }
-  template <bool U32> __device__ __forceinline__ const bf16_t* addr(const Row& r, int k0, int koff, const Cls& c) const {
-    const int k = k0 + koff;
-    if (!r.p || k >= c.K) return nullptr;
-    int t, co;  // t = tu*2 + dx
-    if (U32 && lco >= 5) { t = k0 >> lco; co = (k0 & (Cout - 1)) + koff; }  // wave-uniform tap
-    else { t = k >> lco; co = k & (Cout - 1); }
-    const int tu = t >> 1, dx = t & 1;
-    const int oy = r.a + (c.py ? 1 - tu : 0), ox = r.b + dx;
-    if (oy >= Ho || ox >= Wo) return nullptr;
-    return r.p + ((oy * Wo + ox) << lco) + co;
+  __device__ __forceinline__ void set_off(KCur& k, const Cls& c) const {
+    const int tu = k.t >> 1, dx = k.t & 1;
+    k.off = (((c.py ? 1 - tu : 0) * Wo + dx) << lco) + k.co;
   }
-  template <bool U32> __device__ __forceinline__ uint4 load(const Row& r, int k0, int koff, const Cls& c) const {
-    const bf16_t* p = addr<U32>(r, k0, koff, c);
-    return p ? *reinterpret_cast<const uint4*>(p) : zero16();
+  __device__ __forceinline__ KCur kcur(int kk, const Cls& c) const {
+    KCur k; k.t = kk >> lco; k.co = kk & (Cout - 1); set_off(k, c); return k;
+  }
+  __device__ __forceinline__ void kstep(KCur& k, int dk, const Cls& c) const {
+    k.co += dk; k.t += k.co >> lco; k.co &= Cout - 1; set_off(k, c);
+  }
+  __device__ __forceinline__ const bf16_t* addr(const Row& r, const KCur& k, const Cls&) const {
+    return ((r.vm >> (k.t & 31)) & 1u) ? r.base + (r.poff + k.off) : nullptr;  // vm has no bits beyond the parity's taps
   }
 };
+
+template <class AL>
+__device__ __forceinline__ uint4 a_load(const AL& al, const typename AL::Row& r, const typename AL::KCur& c, const typename AL::Cls& cls) {
+  const bf16_t* p = al.addr(r, c, cls);
+  return p ? *reinterpret_cast<const uint4*>(p) : zero16();
+}
 
 // ---------------------------------------------------------------- epilogues
 // Output row addressing: the same (img, q) scheme as ARows ...
 struct MapRows {
   int64_t stride_b, stride_v; int V, HW, C, M;
+  FastDiv dhw, dv;
+  void prepare() { dhw = make_fastdiv(HW); dv = make_fastdiv(V); }
   struct Cls {};
   __device__ __forceinline__ Cls cls(int) const { return Cls(); }
   __device__ __forceinline__ int64_t row_offset(int m, const Cls&) const {
     if (m >= M) return -1;
     if (HW == 1 && V == 1) return (int64_t)m * stride_b;
-    int img = m / HW, q = m - img * HW, b = img / V, v = img - b * V;
+    const int img = (int)dhw.div((uint32_t)m), q = m - img * HW, b = (int)dv.div((uint32_t)img), v = img - b * V;
     return (int64_t)b * stride_b + (int64_t)v * stride_v + (int64_t)q * C;
   }
   __device__ __forceinline__ int row_cols(int, const Cls&) const { return 0x7fffffff; }
@@ -170,19 +197,27 @@ struct MapRows {
 // ... or horizontal pixel pairs of the rows of one parity of a transposed convolution's input.
 struct MapDgrad {
   int64_t stride_b, stride_v; int V, H, W, Cin, imgs;
-  struct Cls { int Ha, Wb, py, M; };
+  FastDiv dhw[2], dwb, dv;
+  void prepare() {
+    const int Wb = (W + 1) >> 1;
+    dwb = make_fastdiv(Wb); dv = make_fastdiv(V);
+    for (int z = 0; z < 2; ++z) { const int Ha = (H - z + 1) >> 1; dhw[z] = make_fastdiv(Ha * Wb > 0 ? Ha * Wb : 1); }
+  }
+  struct Cls { int Ha, Wb, py, M; FastDiv dhw; };
   __device__ __forceinline__ Cls cls(int z) const {
     Cls c; c.py = z; c.Ha = (H - z + 1) >> 1; c.Wb = (W + 1) >> 1; c.M = imgs * c.Ha * c.Wb;
+    c.dhw = z ? dhw[1] : dhw[0];
     return c;
   }
   __device__ __forceinline__ int64_t row_offset(int m, const Cls& c) const {
     if (m >= c.M) return -1;
-    int hw = c.Ha * c.Wb, img = m / hw, q = m - img * hw, a = q / c.Wb, bb = q - a * c.Wb, b = img / V, v = img - b * V;
+    const int hw = c.Ha * c.Wb, img = (int)c.dhw.div((uint32_t)m), q = m - img * hw;
+    const int a = (int)dwb.div((uint32_t)q), bb = q - a * c.Wb, b = (int)dv.div((uint32_t)img), v = img - b * V;
     return (int64_t)b * stride_b + (int64_t)v * stride_v + ((int64_t)(2 * a + c.py) * W + 2 * bb) * Cin;
   }
   // number of valid columns of the row: the last pair of an odd-width image has one pixel
   __device__ __forceinline__ int row_cols(int m, const Cls& c) const {
-    int bb = m % c.Wb;
+    const int bb = m - (int)dwb.div((uint32_t)m) * c.Wb;
     return (2 * bb + 1 < W) ? 2 * Cin : Cin;
   }
 };
@@ -303,21 +338,22 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
+  // every chunk of a thread sits in the same 8-wide column group (256 is a multiple of CPK)
+  const int ck = (tid % CPK) * 8;
   typename AL::Row arow[ACH];
-  int a_r[ACH], a_k[ACH];
+  int a_r[ACH];
 #pragma unroll
   for (int c = 0; c < ACH; ++c) {
-    int ch = tid + c * 256;
-    a_r[c] = ch / CPK; a_k[c] = (ch % CPK) * 8;
+    a_r[c] = (tid + c * 256) / CPK;
     arow[c] = al.row(a_r[c] < BM ? m0 + a_r[c] : acls.M, acls);
   }
-  const bf16_t* brow[BCH]; int b_r[BCH], b_k[BCH];
+  typename AL::KCur acur = al.kcur(ck, acls);
+  const bf16_t* brow[BCH]; int b_r[BCH];
 #pragma unroll
   for (int c = 0; c < BCH; ++c) {
-    int ch = tid + c * 256;
-    b_r[c] = ch / CPK; b_k[c] = (ch % CPK) * 8;
+    b_r[c] = (tid + c * 256) / CPK;
     int n = n0 + b_r[c];
-    brow[c] = (b_r[c] < BN && n < N) ? Bm + (int64_t)n * ldb : nullptr;
+    brow[c] = (b_r[c] < BN && n < N) ? Bm + (int64_t)n * ldb + ck : nullptr;
   }
 
   f32x16_t acc[TM][TN];
@@ -329,31 +365,31 @@ __global__ __launch_bounds__(256) void k_gemm(AL al, const bf16_t* __restrict__ 
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   uint4 ra[ACH], rb[BCH];
-  auto gload = [&](int k0) {
+  int kb = 0;  // k of the tile being fetched
+  auto gload = [&]() {
 #pragma unroll
-    for (int c = 0; c < ACH; ++c) ra[c] = al.template load<BK == 32>(arow[c], k0, a_k[c], acls);
+    for (int c = 0; c < ACH; ++c) ra[c] = a_load(al, arow[c], acur, acls);
 #pragma unroll
-    for (int c = 0; c < BCH; ++c) {
-      int k = k0 + b_k[c];
-      rb[c] = (brow[c] && k < K) ? *reinterpret_cast<const uint4*>(brow[c] + k) : zero16();
-    }
+    for (int c = 0; c < BCH; ++c) rb[c] = (brow[c] && kb + ck < K) ? *reinterpret_cast<const uint4*>(brow[c] + kb) : zero16();
+    al.kstep(acur, BK, acls);
+    kb += BK;
   };
   auto sstore = [&](int buf) {
 #pragma unroll
     for (int c = 0; c < ACH; ++c)
-      if (a_r[c] < BM) *reinterpret_cast<uint4*>(&As[buf * BM * PITCH + a_r[c] * PITCH + a_k[c]]) = ra[c];
+      if (a_r[c] < BM) *reinterpret_cast<uint4*>(&As[buf * BM * PITCH + a_r[c] * PITCH + ck]) = ra[c];
 #pragma unroll
     for (int c = 0; c < BCH; ++c)
-      if (b_r[c] < BN) *reinterpret_cast<uint4*>(&Bs[buf * BN * PITCH + b_r[c] * PITCH + b_k[c]]) = rb[c];
+      if (b_r[c] < BN) *reinterpret_cast<uint4*>(&Bs[buf * BN * PITCH + b_r[c] * PITCH + ck]) = rb[c];
   };
 
   const int nk = (K + BK - 1) / BK;
-  gload(0);
+  gload();
   sstore(0);
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = (NBUF == 2) ? (kt & 1) : 0;
-    if (kt + 1 < nk) gload((kt + 1) * BK);
+    if (kt + 1 < nk) gload();
     const bf16_t* Ab = As + buf * BM * PITCH;
     const bf16_t* Bb = Bs + buf * BN * PITCH;
 #pragma unroll
@@ -432,14 +468,20 @@ __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int
   for (int j = 0; j < 8; ++j) bs[j] = 0.f;
 
   int m = mbeg + ml;
+  const typename DL::Cls dcls = dl.cls(0);
+  const typename AL::Cls xcls = al.cls(0);
   typename DL::Row dr = dl.row(m < mend ? m : M);
   typename AL::Row ar = al.row(m < mend ? m : M);
+  const typename DL::KCur dcur = dl.kcur(n0 + c8, dcls);  // this thread's columns never change
+  typename AL::KCur xcur[XCH];
+#pragma unroll
+  for (int c = 0; c < XCH; ++c) xcur[c] = al.kcur(k0 + c * 64 + c8, xcls);
   uint4 rd, rx[XCH];
   auto gload = [&]() {
     const bool ok = m < mend;
-    rd = ok ? dl.template load<false>(dr, n0, c8, dl.cls(0)) : zero16();
+    rd = ok ? a_load(dl, dr, dcur, dcls) : zero16();
 #pragma unroll
-    for (int c = 0; c < XCH; ++c) rx[c] = ok ? al.template load<false>(ar, k0 + c * 64, c8, al.cls(0)) : zero16();
+    for (int c = 0; c < XCH; ++c) rx[c] = ok ? a_load(al, ar, xcur[c], xcls) : zero16();
   };
   auto sstore = [&](int buf) {
     *reinterpret_cast<uint4*>(&Dt[buf][ml * DP + c8]) = rd;

@@ -71,14 +71,14 @@ __global__ __launch_bounds__(256) void k_gemm_dma(AL al, const bf16_t* __restric
   const int wm = wave / WGN, wn = wave % WGN;
   const int dr = lane >> 3, dpos = lane & 7;
 
+  // rows r = (wave*AI + j)*8 + dr: the swizzle (r >> 1) & 7 depends on j only through its parity
+  static_assert(AI % 2 == 0, "row groups per wave");
   typename AL::Row arow[AI];
-  int a_k[AI];
 #pragma unroll
-  for (int j = 0; j < AI; ++j) {
-    const int r = (wave * AI + j) * 8 + dr;
-    arow[j] = al.row(m0 + r, acls);
-    a_k[j] = (dpos ^ ((r >> 1) & 7)) * 8;
-  }
+  for (int j = 0; j < AI; ++j) arow[j] = al.row(m0 + (wave * AI + j) * 8 + dr, acls);
+  typename AL::KCur acur[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) acur[j] = al.kcur((dpos ^ ((j * 4 + (dr >> 1)) & 7)) * 8, acls);
   const bf16_t* brow[BI];
   int b_k[BI];
 #pragma unroll
@@ -88,11 +88,12 @@ __global__ __launch_bounds__(256) void k_gemm_dma(AL al, const bf16_t* __restric
     b_k[j] = (dpos ^ ((r >> 1) & 7)) * 8;
   }
   char* const ring_b = reinterpret_cast<char*>(ring);
+  // stages are issued in order of k, so the column cursors simply step along
   auto issue = [&](int stage, int k0) {
     char* sb = ring_b + stage * ST_BYTES;
 #pragma unroll
     for (int j = 0; j < AI; ++j) {
-      const bf16_t* p = al.template addr<false>(arow[j], k0, a_k[j], acls);
+      const bf16_t* p = al.addr(arow[j], acur[j & 1], acls);
       if (!p) p = zpage;
       __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(sb + (wave * AI + j) * 1024), 16, 0, 0);
     }
@@ -102,6 +103,8 @@ __global__ __launch_bounds__(256) void k_gemm_dma(AL al, const bf16_t* __restric
       const bf16_t* p = (brow[j] && k < K) ? brow[j] + k : zpage;
       __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(sb + A_BYTES + (wave * BI + j) * 1024), 16, 0, 0);
     }
+    al.kstep(acur[0], BK, acls);
+    al.kstep(acur[1], BK, acls);
   };
 
   f32x16_t acc[TM][TN];

@@ -268,9 +268,11 @@ inline int class_len(int n, int par) { return (n - par + 1) / 2; }
 inline int ilog2(int x) { int l = 0; while ((1 << l) < x) ++l; return l; }
 
 template <class AL, class EP>
-int launch_gemm(Ctx* c, const AL& al, int M, const bf16_t* Bm, int64_t ldb, int N, int K, const EP& ep, const std::string& name, double abytes,
+int launch_gemm(Ctx* c, const AL& al_, int M, const bf16_t* Bm, int64_t ldb, int N, int K, const EP& ep_, const std::string& name, double abytes,
                 int zdim = 1, double flops = -1.0) {
   if (M <= 0) return PPO_OK;
+  AL al = al_; EP ep = ep_;
+  al.prepare(); ep.map.prepare();
   const char* what = name.c_str();
   ProfScope ps(c, name, flops >= 0.0 ? flops : 2.0 * M * (double)N * K, abytes);
   dim3 blk(256);
@@ -311,8 +313,10 @@ MapRows plain_map(int64_t ld, int M) { MapRows m; m.stride_b = ld; m.stride_v = 
 
 // G[Nn][Kk] (+)= Dy^T * A over M rows, plus optional bias gradient gb[Nn].
 template <class DL, class AL>
-int launch_wgrad(Ctx* c, const DL& dl, const AL& al, int Nn, int Kk, int M, float* gw, float* gb, bool accumulate, const std::string& name, double abytes) {
+int launch_wgrad(Ctx* c, const DL& dl_, const AL& al_, int Nn, int Kk, int M, float* gw, float* gb, bool accumulate, const std::string& name, double abytes) {
   if (M <= 0) return PPO_OK;
+  DL dl = dl_; AL al = al_;
+  dl.prepare(); al.prepare();
   const char* what = name.c_str();
   const int ktw = Kk <= 128 ? 1 : (Kk <= 256 ? 2 : 3);
   const int tiles = cdiv(Kk, 128 * ktw) * cdiv(Nn, 64);
@@ -483,6 +487,7 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
     if (l == 1 && wlds <= 56 * 1024) {
       // fused with the first layer's weight gradient: its input gradient never leaves the chip
       ImgAddr in; in.base = c->obs; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
+      in.prepare(); al.prepare(); ep.map.prepare();
       const int K0 = 9 * c->cC[0], npair = Ci * (K0 + 1), tpp = cdiv(M0, 128);
       int grid = 2 * tpp < 512 ? 2 * tpp : 512;
       if ((int64_t)grid * npair > c->partial_elems) grid = (int)(c->partial_elems / npair);
