@@ -16,6 +16,7 @@
 #include "gemm_dma.hip.h"
 #include "mem_kernels.hip.h"
 #include "fused.hip.h"
+#include "conv_tile.hip.h"
 
 static_assert(sizeof(DevStats) == sizeof(ppo_mb_stats), "device and host statistics records must match");
 
@@ -59,7 +60,7 @@ struct Ctx {
   bf16_t* dhead = nullptr;        // [CH][32]
   bf16_t* gbuf[2] = {nullptr, nullptr};
   float *partial = nullptr, *bias_partial = nullptr;
-  bf16_t* zpage = nullptr;  // 256 bytes of zeros: source of out-of-range operand fetches
+  bf16_t* zpage = nullptr;  // 1 KiB of zeros: source of out-of-range operand fetches
   int64_t partial_elems = 0, bias_partial_elems = 0;
   float *stat_part = nullptr, *dls_part = nullptr, *sq_part = nullptr;
   int max_loss_blocks = 0, adam_blocks = 0;
@@ -382,6 +383,40 @@ ImgAddr conv_out_addr(Ctx* c, int l, const bf16_t* contiguous, const bf16_t* str
   return a;
 }
 
+// Forward convolution through the LDS-image kernel; returns 1 when the layer's shape is not one
+// it covers (the caller then takes the implicit-GEMM path).
+template <int CIN>
+int launch_conv_fwd_tile_t(Ctx* c, const ConvTileArgs& a, const std::string& name, double flops, double abytes) {
+  typedef ConvTileShape<CIN> S;
+  const int segs = cdiv(a.W * S::PIX, 1024), ni = cdiv(2 * a.TR + 1, 4) * segs;  // loads per loader wave per band
+  const int lds = S::lds_bytes(a.W, a.TR);
+  if (segs > S::MAXSEG || ni > 63 || lds > 160 * 1024) return 1;
+  const int gy = cdiv(a.Cout, S::BN);
+  int gx = 256 / gy; if (gx > a.ntiles) gx = a.ntiles; if (gx < 1) gx = 1;
+  auto kfn = k_conv_fwd_tile<CIN>;
+  static bool attr_set = false;
+  if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_set = true; }
+  ProfScope ps(c, name, flops, abytes);
+  hipLaunchKernelGGL(kfn, dim3(gx, gy), dim3(S::THREADS), lds, c->stream, a);
+  LAUNCHCHK(c, "k_conv_fwd_tile");
+  return PPO_OK;
+}
+int launch_conv_fwd_tile(Ctx* c, const AConvFwd& al, const ImgAddr& o, int Cout, const bf16_t* w, const float* bias, int nimg,
+                         const std::string& name, double abytes) {
+  if ((al.Cin != 32 && al.Cin != 64) || Cout % 8 || nimg < 1 || al.in.idx) return 1;
+  const int BM = al.Cin == 32 ? 128 : 64;
+  if (al.Wo > BM) return 1;
+  ConvTileArgs a;
+  a.in = al.in; a.in.prepare();
+  a.out = const_cast<bf16_t*>(o.base); a.out_stride_b = o.stride_b; a.out_stride_v = o.stride_v;
+  a.w = w; a.bias = bias; a.zpage = c->zpage; a.V = o.V; a.H = al.H; a.W = al.W; a.Ho = al.Ho; a.Wo = al.Wo; a.Cout = Cout;
+  const int trmax = BM / al.Wo < al.Ho ? BM / al.Wo : al.Ho;
+  a.NB = cdiv(al.Ho, trmax); a.TR = cdiv(al.Ho, a.NB);  // balanced bands
+  a.ntiles = nimg * a.NB;
+  const double flops = 2.0 * (double)al.M * Cout * al.K;
+  return al.Cin == 32 ? launch_conv_fwd_tile_t<32>(c, a, name, flops, abytes) : launch_conv_fwd_tile_t<64>(c, a, name, flops, abytes);
+}
+
 // Forward of `n` samples selected by device indices idx (NULL = 0..n-1 offset by `first`).
 int forward_chunk(Ctx* c, const int32_t* idx, int n) {
   const int V = c->V, nimg = n * V;
@@ -408,7 +443,8 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n) {
     ep.map.stride_b = o.stride_b; ep.map.stride_v = o.stride_v; ep.map.V = V; ep.map.HW = al.Ho * al.Wo; ep.map.C = c->cC[l + 1]; ep.map.M = al.M;
     ep.out = const_cast<bf16_t*>(o.base); ep.bias = c->p + c->convB[l]; ep.mask = nullptr; ep.N = c->cC[l + 1];
     double ab = 2.0 * ((double)nimg * al.H * al.W * al.Cin + (double)al.M * c->cC[l + 1] + (double)al.K * c->cC[l + 1]);
-    int rc = launch_gemm(c, al, al.M, c->shadow + c->convW[l], al.K, c->cC[l + 1], al.K, ep, "conv_fwd." + std::to_string(l), ab);
+    int rc = launch_conv_fwd_tile(c, al, o, c->cC[l + 1], c->shadow + c->convW[l], c->p + c->convB[l], nimg, "conv_fwd." + std::to_string(l), ab);
+    if (rc == PPO_OK + 1) rc = launch_gemm(c, al, al.M, c->shadow + c->convW[l], al.K, c->cC[l + 1], al.K, ep, "conv_fwd." + std::to_string(l), ab);
     if (rc) return rc;
   }
   hipLaunchKernelGGL(k_gather_proprio, dim3(cdiv((int64_t)n * c->P, 256)), dim3(256), 0, c->stream, c->proprio, idx, n, c->P, c->feat, (int64_t)c->feat_ld, V * c->flat);
@@ -663,8 +699,8 @@ int create_impl(Ctx* c) {
   want(c->NH, c->hid, CH);
   c->partial_elems = pe; c->bias_partial_elems = bpe;
   DALLOC(c, c->partial, pe); DALLOC(c, c->bias_partial, bpe);
-  DALLOC(c, c->zpage, 128);
-  HIPCHK(c, hipMemsetAsync(c->zpage, 0, 256, c->stream));
+  DALLOC(c, c->zpage, 512);
+  HIPCHK(c, hipMemsetAsync(c->zpage, 0, 1024, c->stream));
   // loss / Adam partials
   c->max_loss_blocks = cdiv(S, CH) * cdiv(CH, 256) + 1;
   DALLOC(c, c->stat_part, (int64_t)c->max_loss_blocks * LOSS_NSTAT); DALLOC(c, c->dls_part, (int64_t)c->max_loss_blocks * 32);
@@ -951,8 +987,8 @@ int ppo_diag_gemm(int32_t M, int32_t N, int32_t K, const float* h_a, const float
   auto body = [&]() -> int {
     DALLOC(c, da, (int64_t)M * K); DALLOC(c, db, (int64_t)N * K); DALLOC(c, dc, (int64_t)M * N);
     DALLOC(c, ba, (int64_t)M * K); DALLOC(c, bb, (int64_t)N * K);
-    DALLOC(c, c->zpage, 128);
-    HIPCHK(c, hipMemset(c->zpage, 0, 256));
+    DALLOC(c, c->zpage, 512);
+    HIPCHK(c, hipMemset(c->zpage, 0, 1024));
     HIPCHK(c, hipMemcpy(da, h_a, sizeof(float) * (size_t)M * K, hipMemcpyHostToDevice));
     HIPCHK(c, hipMemcpy(db, h_b, sizeof(float) * (size_t)N * K, hipMemcpyHostToDevice));
     hipLaunchKernelGGL(k_cast_bf16, dim3(cdiv((int64_t)M * K, 256)), dim3(256), 0, c->stream, da, ba, (int64_t)M * K);
