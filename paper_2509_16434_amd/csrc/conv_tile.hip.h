@@ -51,6 +51,18 @@ struct ConvTileShape {
   static int lds_bytes(int W, int TR) { return NBUF * image_bytes(W, TR) + STAGE_BYTES + BN * 4; }
 };
 
+// LDS image rows hold pixel slots of CIN*2 bytes (slot 0 and slot W+1 are zero pads).  A byte at
+// logical in-row offset `off` is stored at off ^ tile_swz_bits<CIN>(off): the 16-byte chunks of a
+// pixel are permuted by bits of the slot index (which the permutation leaves unchanged, so it is
+// its own inverse).  Reads that walk over every second slot then use all banks evenly, two lanes
+// per bank group.
+template <int CIN>
+__device__ __forceinline__ uint32_t tile_swz_bits(uint32_t off) {
+  if (CIN == 32) return ((off >> 8) & 3u) << 4;          // slot >> 2
+  const uint32_t t = (off >> 8) & 7u;                    // slot >> 1
+  return (((t & 1u) << 2) | (t >> 1)) << 4;              // rotated, so neighbours differ in the top bit
+}
+
 // wait until at most n (wave-uniform, < 64) of this wave's vector-memory operations are outstanding
 __device__ __forceinline__ void vm_wait_dyn(int n) {
   switch (n) {
@@ -76,8 +88,6 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
   const int image_bytes = nrows * WP * PIX;
   // tiles of this block: blockIdx.x, + gridDim.x, ...
   const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
-  // chunk permutation of the pixel in slot xs (slot 0 is the left pad)
-  auto swz = [](int xs) -> int { return (CIN == 32) ? ((xs >> 2) & 3) : ((xs >> 1) & 7); };
 
   // zero the pad pixels of all ring images once
   for (int i = tid; i < NBUF * nrows * 2 * CPP; i += S::THREADS) {
@@ -92,8 +102,9 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
     int goff[S::MAXSEG];  // byte offset within an image row of the chunk this lane fetches, -1 = none
 #pragma unroll
     for (int sg = 0; sg < S::MAXSEG; ++sg) {
-      const int L = sg * 64 + lane, xi = L / CPP, cip = L - xi * CPP;
-      goff[sg] = (sg < segs && L < W * CPP) ? (xi * CPP + (cip ^ swz(xi + 1))) * 16 : -1;
+      // this lane's 16 bytes land at in-row offset PIX + sg*1024 + lane*16: fetch what belongs there
+      const uint32_t phys = PIX + sg * 1024 + lane * 16, logi = phys ^ tile_swz_bits<CIN>(phys);
+      goff[sg] = (sg < segs && (int)phys < (W + 1) * PIX) ? (int)logi - PIX : -1;
     }
     auto issue = [&](int q) {
       const int t = blockIdx.x + q * gridDim.x;
@@ -149,7 +160,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
   const uint32_t abase = (uint32_t)(((2 * oyl) * WP + 2 * ox) * PIX);
   uint32_t hx[3];
 #pragma unroll
-  for (int v = 0; v < 3; ++v) hx[v] = (uint32_t)((h ^ swz(2 * ox + v)) * 16);
+  for (int v = 0; v < 3; ++v) hx[v] = (uint32_t)(h * 16) ^ tile_swz_bits<CIN>((uint32_t)((2 * ox + v) * PIX));
 
   __builtin_amdgcn_s_barrier();  // pad fill and bias table done
   for (int q = 0; q < nq; ++q) {
@@ -202,5 +213,207 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
           *reinterpret_cast<uint4*>(dst + (int64_t)p * a.Cout + n) = *reinterpret_cast<const uint4*>(stage + (rl * SP + cg * 8) * 2);
       }
     }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Weight gradient of the same convolution: G[n][k] = sum over pixels p of dY[p][n] * X[win(p)][k],
+// k = (u*3+v)*CIN + ci, with the same organisation.  A tile is (image, band of TR output rows); the
+// loader waves copy the band's input rows (LDS image as above) and the band's dY pixels (64 output
+// channels of this block, 128 bytes per pixel, NSTEP*16 pixels with zeros beyond the band) into a
+// ring of three buffers.  The contraction runs over pixels, 16 per MFMA step; both operands are
+// read through ds_read_b64_tr_b16 (lane r of a 16-lane group supplies 4 consecutive channels of
+// pixel r/4, lane i receives channel i of 4 pixels), the im2col being the per-lane pixel address.
+// Compute wave w owns the 32-wide k-tiles w, w+4, ... of both 32-row n-tiles; the accumulators live
+// in registers across all tiles of the block and leave once, as this block's fp32 partial
+// [Cout][9*CIN] (partials are summed in a fixed order by the caller).  Wave 3 also accumulates the
+// column sums of dY (the bias gradient) with an all-ones operand.
+// dY pixels are 128 bytes apart; bit 6 of the offset is flipped for every second pixel pair so that
+// the four pixels of one transposing read fall into different banks.
+struct ConvWgradArgs {
+  ImgAddr in;                 // layer input X, images [H][W][CIN], dense
+  ImgAddr dy;                 // gradient of the layer output, images [Ho][Wo][Cout]
+  const bf16_t* zpage;        // 1 KiB of zeros
+  float* partial;             // [gridDim.x][Cout][9*CIN]
+  float* bias_partial;        // [gridDim.x][Cout]
+  int H, W, Ho, Wo, Cout;
+  int TR, NB, ntiles, nstep;  // output rows per band, bands per image, nimg * NB, ceil(TR*Wo / 16)
+};
+
+template <int CIN>
+struct ConvWgradShape {
+  static constexpr int PIX = CIN * 2, KT = 9 * CIN / 32, KTW = (KT + 3) / 4;
+  static constexpr int MAXSEG = 6, MAXSTEP = (CIN == 32) ? 5 : 4, NBUF = 3, THREADS = 512;
+  static_assert(3 + 4 * (KTW - 1) >= KT, "wave 3's last accumulator pair must be free for the bias sums");
+  static int image_bytes(int W, int TR) { return (2 * TR + 1) * (W + 2) * PIX; }
+  static int buf_bytes(int W, int TR, int nstep) { return image_bytes(W, TR) + nstep * 16 * 128; }
+  static int lds_bytes(int W, int TR, int nstep) { return NBUF * buf_bytes(W, TR, nstep) + 4 * 64 * 4; }
+};
+
+__device__ __forceinline__ bf16x8_t lds_read_tr8_2(const char* p_lo, const char* p_hi) {
+  typedef short s16x4_t_ __attribute__((ext_vector_type(4)));
+  struct { s16x4_t_ lo, hi; } v;
+  v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t_ __attribute__((address_space(3)))*)(p_lo));
+  v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t_ __attribute__((address_space(3)))*)(p_hi));
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+
+template <int CIN>
+__global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
+  typedef ConvWgradShape<CIN> S;
+  constexpr int PIX = S::PIX, KT = S::KT, KTW = S::KTW, NBUF = S::NBUF, MAXSTEP = S::MAXSTEP;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int W = a.W, WP = W + 2, TR = a.TR, Wo = a.Wo, nstep = a.nstep;
+  const int nrows = 2 * TR + 1, rowbytes = W * PIX, segs = (rowbytes + 1023) >> 10;
+  const int image_bytes = nrows * WP * PIX, dy_bytes = nstep * 16 * 128, buf_bytes = image_bytes + dy_bytes;
+  const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
+  const int nb0 = blockIdx.y * 64;
+
+  // zero the pad pixels of all ring images once
+  for (int i = tid; i < NBUF * nrows * 2 * (PIX / 16); i += S::THREADS) {
+    const int chunk = i % (PIX / 16), side = (i / (PIX / 16)) & 1, row = i / (2 * (PIX / 16));
+    const int b = row / nrows, rr = row - b * nrows;
+    *reinterpret_cast<uint4*>(lds + b * buf_bytes + (int64_t)rr * WP * PIX + (side ? (W + 1) * PIX : 0) + chunk * 16) = make_uint4(0u, 0u, 0u, 0u);
+  }
+
+  if (wave >= 4) {
+    // ------------------------------------------------------------------ loaders
+    // loader lw copies the image rows lw, lw+4, ... and the 1 KiB dY pieces lw, lw+4, ... of a band
+    const int lw = wave - 4;
+    const int ni = ((nrows - lw + 3) >> 2) * segs + ((nstep * 2 - lw + 3) >> 2);  // this wave's loads per band
+    int xgoff[S::MAXSEG];
+#pragma unroll
+    for (int sg = 0; sg < S::MAXSEG; ++sg) {
+      const uint32_t phys = PIX + sg * 1024 + lane * 16, logi = phys ^ tile_swz_bits<CIN>(phys);
+      xgoff[sg] = (sg < segs && (int)phys < (W + 1) * PIX) ? (int)logi - PIX : -1;
+    }
+    auto issue = [&](int q) {
+      const int t = blockIdx.x + q * gridDim.x;
+      const int img = t / a.NB, band = t - img * a.NB;
+      const int iy_lo = 2 * band * TR - 1;
+      const char* xsrc = reinterpret_cast<const char*>(a.in.ptr(img)) + (int64_t)iy_lo * rowbytes;
+      const int plim = min(TR, a.Ho - band * TR) * Wo;  // pixels of the band that exist
+      const bf16_t* dsrc = a.dy.ptr(img) + (int64_t)band * TR * Wo * a.Cout + nb0;
+      char* buf = lds + (q % NBUF) * buf_bytes;
+      const char* zp = reinterpret_cast<const char*>(a.zpage) + lane * 16;
+      for (int row = lw; row < nrows; row += 4) {
+        const int iy = iy_lo + row;
+        const bool inside = iy >= 0 && iy < a.H;
+#pragma unroll
+        for (int sg = 0; sg < S::MAXSEG; ++sg)
+          if (sg < segs) {
+            const char* p = inside ? xsrc + (int64_t)row * rowbytes + xgoff[sg] : zp;
+            if (xgoff[sg] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(buf + row * WP * PIX + PIX + sg * 1024), 16, 0, 0);
+          }
+      }
+      for (int j = lw; j < nstep * 2; j += 4) {  // 1 KiB = 8 pixels of 128 bytes
+        const uint32_t phys = j * 1024 + lane * 16, logi = phys ^ (((phys >> 8) & 1u) << 6);
+        const int p_ = (int)(logi >> 7), cb = (int)(logi & 127u);
+        const bool ok = p_ < plim && nb0 + (cb >> 1) < a.Cout;
+        const char* p = ok ? reinterpret_cast<const char*>(dsrc + (int64_t)p_ * a.Cout) + cb : zp;
+        __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(buf + image_bytes + j * 1024), 16, 0, 0);
+      }
+    };
+    if (nq > 0) issue(0);
+    if (nq > 1) issue(1);
+    __builtin_amdgcn_s_barrier();
+    for (int q = 0; q < nq; ++q) {
+      vm_wait_dyn(q + 1 < nq ? ni : 0);
+      __builtin_amdgcn_s_barrier();
+      if (q + 2 < nq) issue(q + 2);
+    }
+    __builtin_amdgcn_s_barrier();  // pairs with the compute waves' barrier before the bias reduction
+    return;
+  }
+
+  // -------------------------------------------------------------------- compute waves
+  const int g = lane >> 4, r16 = lane & 15;
+  const int scolb = (16 * (g & 1) + 4 * (r16 & 3)) * 2;  // byte offset of this lane's 4 source channels in a 32-channel tile
+  // per step and half (pixels +0..3 / +4..7 of the lane's group): source addresses within a ring buffer
+  uint32_t xb[MAXSTEP][2][2];  // image: pixel (2*oyl, 2*ox) with the chunk permutation of tap columns v < 2 / v = 2
+  uint32_t db[MAXSTEP][2];     // dY: pixel p, n-tile 0
+#pragma unroll
+  for (int s = 0; s < MAXSTEP; ++s)
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      int p = s * 16 + 8 * (g >> 1) + (r16 >> 2) + 4 * hf;
+      const uint32_t dl = (uint32_t)(p * 128 + scolb);
+      db[s][hf] = (uint32_t)image_bytes + (dl ^ (((dl >> 8) & 1u) << 6));
+      if (p >= TR * Wo) p = 0;  // its dY is zero; any finite pixel will do
+      const int oyl = p / Wo, ox = p - oyl * Wo;
+      const uint32_t inrow = (uint32_t)(2 * ox * PIX + scolb), rowb = (uint32_t)(2 * oyl * WP * PIX);
+      xb[s][hf][0] = rowb + (inrow ^ tile_swz_bits<CIN>(inrow));
+      xb[s][hf][1] = rowb + (inrow ^ tile_swz_bits<CIN>(inrow + 2 * PIX));
+    }
+
+  f32x16_t acc[KTW][2];  // wave 3 has no k-tile for t = KTW-1: that pair holds the bias sums
+#pragma unroll
+  for (int t = 0; t < KTW; ++t)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[t][i][e] = 0.f;
+  const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
+  // byte offset of k-tile kt within the window: tap (u, v) and, for 64 channels, the pixel half
+  uint32_t tapc[KTW]; bool tapv2[KTW], taphi[KTW];
+#pragma unroll
+  for (int t = 0; t < KTW; ++t) {
+    const int kt = wave + 4 * t, tap = kt / (CIN / 32), u = tap / 3, v = tap - 3 * u;
+    tapc[t] = (uint32_t)((u * WP + v) * PIX); tapv2[t] = v == 2; taphi[t] = (CIN == 64) && (kt & 1);
+  }
+
+  __builtin_amdgcn_s_barrier();  // pad fill done
+  for (int q = 0; q < nq; ++q) {
+    __builtin_amdgcn_s_barrier();  // band q is in LDS
+    const char* buf = lds + (q % NBUF) * buf_bytes;
+#pragma unroll
+    for (int s = 0; s < MAXSTEP; ++s) {
+      if (s < nstep) {
+        const bf16x8_t a0 = lds_read_tr8_2(buf + db[s][0], buf + db[s][1]);
+        const bf16x8_t a1 = lds_read_tr8_2(buf + (db[s][0] ^ 64u), buf + (db[s][1] ^ 64u));
+#pragma unroll
+        for (int t = 0; t < KTW; ++t) {
+          if (wave + 4 * t < KT) {
+            uint32_t o0 = tapv2[t] ? xb[s][0][1] : xb[s][0][0], o1 = tapv2[t] ? xb[s][1][1] : xb[s][1][0];
+            if (taphi[t]) { o0 ^= 64u; o1 ^= 64u; }
+            const bf16x8_t b = lds_read_tr8_2(buf + o0 + tapc[t], buf + o1 + tapc[t]);
+            acc[t][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[t][0], 0, 0, 0);
+            acc[t][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[t][1], 0, 0, 0);
+          }
+        }
+        if (wave == 3 && a.bias_partial) {
+          acc[KTW - 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, ones, acc[KTW - 1][0], 0, 0, 0);
+          acc[KTW - 1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, ones, acc[KTW - 1][1], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // ---- this block's partial sums: acc[t][i][e] = G[n][k], k = (wave+4t)*32 + lane%32, n = nb0 + i*32 + (e/4)*8 + (lane/32)*4 + e%4
+  const int K = 9 * CIN;
+  float* P = a.partial + (int64_t)blockIdx.x * a.Cout * K;
+#pragma unroll
+  for (int t = 0; t < KTW; ++t) {
+    const int kt = wave + 4 * t, k = kt * 32 + (lane & 31);
+    if (kt < KT) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int n = nb0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+          if (n < a.Cout) P[(int64_t)n * K + k] = acc[t][i][e];
+        }
+    }
+  }
+  __builtin_amdgcn_s_barrier();
+  if (wave == 3 && a.bias_partial && (lane & 31) == 0) {
+    // every column of the pair holds the same sums; lanes 0 and 32 cover the 64 rows between them
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int n = nb0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        if (n < a.Cout) a.bias_partial[(int64_t)blockIdx.x * a.Cout + n] = acc[KTW - 1][i][e];
+      }
   }
 }

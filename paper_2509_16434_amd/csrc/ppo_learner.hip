@@ -417,6 +417,55 @@ int launch_conv_fwd_tile(Ctx* c, const AConvFwd& al, const ImgAddr& o, int Cout,
   return al.Cin == 32 ? launch_conv_fwd_tile_t<32>(c, a, name, flops, abytes) : launch_conv_fwd_tile_t<64>(c, a, name, flops, abytes);
 }
 
+// Weight (and bias) gradient of conv layer with 32 or 64 input channels through the LDS-image
+// kernel; returns 1 when the shape is not covered (the caller then takes the implicit-GEMM path).
+template <int CIN>
+int launch_conv_wgrad_tile_t(Ctx* c, ConvWgradArgs a, float* gw, float* gb, bool accumulate, const std::string& name, double flops, double abytes) {
+  typedef ConvWgradShape<CIN> S;
+  // largest band that fits the pixel-step table and three ring buffers, then balanced over the image
+  int TR = 0;
+  for (int tr = a.Ho; tr >= 1; --tr)
+    if (tr * a.Wo <= 16 * S::MAXSTEP && S::lds_bytes(a.W, tr, cdiv(tr * a.Wo, 16)) <= 158 * 1024) { TR = tr; break; }
+  if (TR == 0) return 1;
+  a.NB = cdiv(a.Ho, TR); a.TR = cdiv(a.Ho, a.NB); a.nstep = cdiv(a.TR * a.Wo, 16);
+  const int nimg = a.ntiles;  // passed in as the image count
+  a.ntiles = nimg * a.NB;
+  const int segs = cdiv(a.W * S::PIX, 1024);
+  if (segs > S::MAXSEG || cdiv(2 * a.TR + 1, 4) * segs + cdiv(a.nstep * 2, 4) > 63) return 1;
+  const int gy = cdiv(a.Cout, 64), K = 9 * CIN;
+  int gx = 256 / gy; if (gx > a.ntiles) gx = a.ntiles; if (gx < 1) gx = 1;
+  const int64_t per = (int64_t)a.Cout * K;
+  if ((int64_t)gx * per > c->partial_elems) gx = (int)(c->partial_elems / per);
+  if (gb && (int64_t)gx * a.Cout > c->bias_partial_elems) gx = (int)(c->bias_partial_elems / a.Cout);
+  if (gx < 1) return 1;
+  a.partial = c->partial; a.bias_partial = gb ? c->bias_partial : nullptr;
+  const int lds = S::lds_bytes(a.W, a.TR, a.nstep);
+  auto kfn = k_conv_wgrad_tile<CIN>;
+  static bool attr_set = false;
+  if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_set = true; }
+  {
+    ProfScope ps(c, name, flops, abytes);
+    hipLaunchKernelGGL(kfn, dim3(gx, gy), dim3(S::THREADS), lds, c->stream, a);
+    LAUNCHCHK(c, "k_conv_wgrad_tile");
+  }
+  ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)gx + 1.0) * (double)per);
+  hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 32)), dim3(256), 0, c->stream, c->partial, gx, per, gw, accumulate ? 1 : 0);
+  if (gb) hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(a.Cout, 32)), dim3(256), 0, c->stream, c->bias_partial, gx, (int64_t)a.Cout, gb, accumulate ? 1 : 0);
+  LAUNCHCHK(c, "k_reduce_partials");
+  return PPO_OK;
+}
+int launch_conv_wgrad_tile(Ctx* c, const ImgAddr& dy, const AConvFwd& xl, int Cout, int nimg, float* gw, float* gb, bool accumulate,
+                           const std::string& name, double abytes) {
+  if ((xl.Cin != 32 && xl.Cin != 64) || Cout % 8 || nimg < 1 || xl.in.idx || dy.idx) return 1;
+  ConvWgradArgs a;
+  a.in = xl.in; a.in.prepare(); a.dy = dy; a.dy.prepare(); a.zpage = c->zpage; a.partial = nullptr; a.bias_partial = nullptr;
+  a.H = xl.H; a.W = xl.W; a.Ho = xl.Ho; a.Wo = xl.Wo; a.Cout = Cout; a.TR = 0; a.NB = 0; a.nstep = 0;
+  a.ntiles = nimg;  // image count; the template turns it into tiles
+  const double flops = 2.0 * (double)xl.M * Cout * xl.K;
+  return xl.Cin == 32 ? launch_conv_wgrad_tile_t<32>(c, a, gw, gb, accumulate, name, flops, abytes)
+                      : launch_conv_wgrad_tile_t<64>(c, a, gw, gb, accumulate, name, flops, abytes);
+}
+
 // Forward of `n` samples selected by device indices idx (NULL = 0..n-1 offset by `first`).
 int forward_chunk(Ctx* c, const int32_t* idx, int n) {
   const int V = c->V, nimg = n * V;
@@ -506,8 +555,10 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
     ARows dl; dl.a = dy; dl.HW = Ho * Wo; dl.C = Co; dl.M = nimg * Ho * Wo; dl.K = Co; dl.plain = false;
     AConvFwd xl; xl.in = conv_out_addr(c, l - 1, c->act[l - 1], nullptr);
     xl.H = H; xl.W = W; xl.Cin = Ci; xl.lc = ilog2(Ci); xl.Ho = Ho; xl.Wo = Wo; xl.M = dl.M; xl.K = 9 * Ci;
-    int rc = launch_wgrad(c, dl, xl, Co, 9 * Ci, dl.M, c->g + c->convW[l], c->g + c->convB[l], acc, "conv_wgrad." + std::to_string(l),
-                          2.0 * ((double)dl.M * Co + (double)nimg * H * W * Ci) + 4.0 * 9.0 * Ci * Co);
+    const double wab = 2.0 * ((double)dl.M * Co + (double)nimg * H * W * Ci) + 4.0 * 9.0 * Ci * Co;
+    int rc = launch_conv_wgrad_tile(c, dy, xl, Co, nimg, c->g + c->convW[l], c->g + c->convB[l], acc, "conv_wgrad." + std::to_string(l), wab);
+    if (rc == PPO_OK + 1)
+      rc = launch_wgrad(c, dl, xl, Co, 9 * Ci, dl.M, c->g + c->convW[l], c->g + c->convB[l], acc, "conv_wgrad." + std::to_string(l), wab);
     if (rc) return rc;
     // transposed convolution over horizontal pixel pairs, both row parities in one launch (grid.z)
     AConvDgrad al; al.dy = dy; al.Ho = Ho; al.Wo = Wo; al.Cout = Co; al.lco = ilog2(Co); al.H = H; al.W = W; al.dy_imgs = nimg;
@@ -695,6 +746,11 @@ int create_impl(Ctx* c) {
     if ((int64_t)splits * Nn > bpe) bpe = (int64_t)splits * Nn;
   };
   for (int l = 1; l < c->nconv; ++l) want(c->cC[l + 1], 9 * c->cC[l], (int64_t)CH * V * c->cH[l + 1] * c->cW[l + 1]);
+  for (int l = 1; l < c->nconv; ++l) {  // one partial per block of the LDS-image weight-gradient kernel
+    const int64_t gy = cdiv(c->cC[l + 1], 64), gx = 256 / gy > 0 ? 256 / gy : 1, per = (int64_t)c->cC[l + 1] * 9 * c->cC[l];
+    if (gx * per > pe) pe = gx * per;
+    if (gx * c->cC[l + 1] > bpe) bpe = gx * c->cC[l + 1];
+  }
   for (int l = 0; l < c->nfc; ++l) want(c->fout[l], c->fin[l], CH);
   want(c->NH, c->hid, CH);
   c->partial_elems = pe; c->bias_partial_elems = bpe;
