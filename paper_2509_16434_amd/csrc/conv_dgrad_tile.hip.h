@@ -1,0 +1,252 @@
+// Transposed 3x3 stride-2 pad-1 convolution (input gradient) for 64 gradient channels and 32 or 64
+// input channels, in the LDS-image organisation of conv_tile.hip.h.
+//
+// The 2x2 block of input pixels (2a+py, 2b+px) - a "quad" - receives only from the four dY pixels
+// (a+dyo, b+dxo), dyo, dxo in {0,1}: pixel class (py, px) uses (1+py)*(1+px) of the nine taps, nine
+// tap applications per quad in all, so nothing is multiplied by zero.  A lane owns one quad: it reads
+// each of the four dY pixels once per 16 channels and feeds it to every (class, tap) that uses it,
+// accumulating the four pixels' CI/WGN columns in registers (64).  The weights, transposed per tap
+// to [ci][co], stay in registers for the whole kernel (144).
+//
+// Waves of a block (512 threads): four compute waves; two loader waves that copy dY bands
+// (TQ+1 rows) into a ring of three LDS images with LDS-writing loads; two finishing waves that,
+// one tile behind, apply the ReLU mask of the stored activation to the staged result and write it
+// out as 16-byte segments of the band (one contiguous span of the image).  The staging area is
+// double-buffered, so finishing tile q-1 overlaps computing tile q; two barriers per tile order the
+// three roles.  The finishing waves fetch the mask two tiles ahead with ordinary loads into two
+// register sets, so their only waits are the compiler's.
+//
+// dY pixels are 128 bytes; their 16-byte chunks are permuted by (slot >> 1) & 7, the staged pixels'
+// by tile_swz_bits<CI> of the band-linear offset: lanes of one access own consecutive quads.
+#pragma once
+#include "conv_tile.hip.h"
+#include <type_traits>
+
+struct ConvDgradArgs {
+  ImgAddr dy;                 // gradient of the layer output, images [Ho][Wo][64]
+  bf16_t* dx;                 // result, images [H][W][CI] at dx + b*x_stride_b + v*x_stride_v
+  const bf16_t* x;            // stored activation of the same layout: the ReLU mask
+  int64_t x_stride_b, x_stride_v;
+  const bf16_t* wt;           // [9][CI][64]: wt[(tap*CI + ci)*64 + co] = W[co][tap][ci]
+  const bf16_t* zpage;        // 1 KiB of zeros
+  int V, H, W, Ho, Wo;
+  int TQ, NB, ntiles;         // quad rows per band, bands per image, nimg * NB
+};
+
+template <int CI>
+struct ConvDgradShape {
+  static constexpr int CO = 64, WGN = CI / 32, WGM = 4 / WGN, BQ = WGM * 32;  // quads per tile
+  static constexpr int NBUF = 3, THREADS = 512, MAXSEG = 6, MAXCH = 16;
+  static int dyimg_bytes(int Wo, int TQ) { return (TQ + 1) * (Wo + 1) * 128; }
+  static int stage_bytes(int W, int TQ) { return 2 * TQ * W * CI * 2; }
+  static int lds_bytes(int W, int Wo, int TQ) { return NBUF * dyimg_bytes(Wo, TQ) + 2 * stage_bytes(W, TQ); }
+};
+
+__device__ __forceinline__ uint32_t dy_swz_bits(uint32_t off) { return ((off >> 8) & 7u) << 4; }
+
+__device__ __forceinline__ uint32_t relu_keep(uint32_t m) {
+  // all-ones halves where the stored bf16 is > 0 (sign clear and not zero)
+  return (((short)(m & 0xffffu) > 0) ? 0x0000ffffu : 0u) | (((short)(m >> 16) > 0) ? 0xffff0000u : 0u);
+}
+
+template <int CI>
+__global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
+  typedef ConvDgradShape<CI> S;
+  constexpr int CO = S::CO, CC = CO / 16, WGN = S::WGN, NBUF = S::NBUF;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int W = a.W, Wo = a.Wo, TQ = a.TQ;
+  const int RP = (Wo + 1) * 128;                       // dY image row pitch
+  const int dyimg_bytes = (TQ + 1) * RP;
+  const int stage_bytes = 2 * TQ * W * CI * 2;
+  char* const stage0 = lds + NBUF * dyimg_bytes;
+  const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
+
+  // zero the right pad slot of every dY image row once
+  for (int i = tid; i < NBUF * (TQ + 1) * 8; i += S::THREADS) {
+    const int chunk = i & 7, row = i >> 3;
+    *reinterpret_cast<uint4*>(lds + row * RP + Wo * 128 + chunk * 16) = make_uint4(0u, 0u, 0u, 0u);
+  }
+
+  if (wave == 4 || wave == 5) {
+    // ------------------------------------------------------------------ loaders: image row r belongs to loader r % 2
+    const int lw = wave - 4;
+    const int rowbytes = Wo * 128, segs = (rowbytes + 1023) >> 10;
+    const int ni = ((TQ + 1 - lw + 1) >> 1) * segs;  // this wave's loads per band
+    int goff[S::MAXSEG];
+#pragma unroll
+    for (int sg = 0; sg < S::MAXSEG; ++sg) {
+      const uint32_t phys = sg * 1024 + lane * 16, logi = phys ^ dy_swz_bits(phys);
+      goff[sg] = (sg < segs && (int)phys < rowbytes) ? (int)logi : -1;
+    }
+    auto issue = [&](int q) {
+      const int t = blockIdx.x + q * gridDim.x;
+      const int img = t / a.NB, band = t - img * a.NB;
+      const int oy_lo = band * TQ;
+      const char* src = reinterpret_cast<const char*>(a.dy.ptr(img)) + (int64_t)oy_lo * rowbytes;
+      char* dst = lds + (q % NBUF) * dyimg_bytes;
+      for (int row = lw; row <= TQ; row += 2) {
+        const bool inside = oy_lo + row < a.Ho;
+#pragma unroll
+        for (int sg = 0; sg < S::MAXSEG; ++sg)
+          if (sg < segs) {
+            const char* p = inside ? src + (int64_t)row * rowbytes + goff[sg] : reinterpret_cast<const char*>(a.zpage) + lane * 16;
+            if (goff[sg] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + row * RP + sg * 1024), 16, 0, 0);
+          }
+      }
+    };
+    if (nq > 0) issue(0);
+    if (nq > 1) issue(1);
+    __builtin_amdgcn_s_barrier();
+    for (int q = 0; q < nq; ++q) {
+      vm_wait_dyn(q + 1 < nq ? ni : 0);  // band q has landed
+      __builtin_amdgcn_s_barrier();      // A(q)
+      if (q + 2 < nq) issue(q + 2);
+      __builtin_amdgcn_s_barrier();      // B(q)
+    }
+    return;
+  }
+
+  if (wave >= 6) {
+    // ------------------------------------------------------------------ finishing waves
+    const int et = tid - 384;  // 0..127
+    const int nchunk = stage_bytes >> 4;
+    // two register sets: the mask of tile q+1 is fetched while tile q-1 is finished (two tiles of
+    // mask bytes in flight per CU)
+    uint4 mk[2][S::MAXCH];
+    int64_t band_off[2] = {0, 0};  // element offset of the set's band within dx / x
+    int nvalid[2] = {0, 0};        // its chunks that lie inside the image
+    auto load_mask = [&](int q, auto setc) {
+      constexpr int SET = decltype(setc)::value;
+      const int t = blockIdx.x + q * gridDim.x;
+      const int img = t / a.NB, band = t - img * a.NB;
+      const int b = img / a.V, vw = img - b * a.V;
+      const int rows = min(2 * TQ, a.H - 2 * band * TQ);
+      band_off[SET] = (int64_t)b * a.x_stride_b + (int64_t)vw * a.x_stride_v + (int64_t)(2 * band * TQ) * W * CI;
+      nvalid[SET] = rows * W * CI / 8;
+#pragma unroll
+      for (int i = 0; i < S::MAXCH; ++i) {
+        const int c = et + 128 * i;
+        mk[SET][i] = (c < nvalid[SET]) ? *reinterpret_cast<const uint4*>(a.x + band_off[SET] + (int64_t)c * 8) : make_uint4(0u, 0u, 0u, 0u);
+      }
+    };
+    auto finish = [&](int q, auto setc) {  // tile q was loaded into set q & 1
+      constexpr int SET = decltype(setc)::value;
+      const char* st = stage0 + (q & 1) * stage_bytes;
+      // One wait for everything outstanding (this set's mask, fetched two tiles ago, and the younger
+      // set's): otherwise every use of a mask register below waits for the store issued just before it.
+      vm_wait<0>();
+#pragma unroll
+      for (int i = 0; i < S::MAXCH; ++i) {
+        const int c = et + 128 * i;
+        if (c < nvalid[SET] && c < nchunk) {
+          const uint32_t L = (uint32_t)c * 16u;
+          uint4 v = *reinterpret_cast<const uint4*>(st + (L ^ tile_swz_bits<CI>(L)));
+          v.x &= relu_keep(mk[SET][i].x); v.y &= relu_keep(mk[SET][i].y); v.z &= relu_keep(mk[SET][i].z); v.w &= relu_keep(mk[SET][i].w);
+          *reinterpret_cast<uint4*>(a.dx + band_off[SET] + (int64_t)c * 8) = v;
+        }
+      }
+    };
+    typedef std::integral_constant<int, 0> set0;
+    typedef std::integral_constant<int, 1> set1;
+    auto step = [&](int q, auto par) {  // q & 1 == par
+      constexpr int P = decltype(par)::value;
+      typedef std::integral_constant<int, 1 - P> other;
+      __builtin_amdgcn_s_barrier();  // A(q)
+      if (q > 0) {
+        finish(q - 1, other());
+        if (q + 1 < nq) load_mask(q + 1, other());
+      }
+      __builtin_amdgcn_s_barrier();  // B(q): tile q is staged
+    };
+    if (nq > 0) load_mask(0, set0());
+    if (nq > 1) load_mask(1, set1());
+    __builtin_amdgcn_s_barrier();
+    for (int q = 0; q < nq; q += 2) {
+      step(q, set0());
+      if (q + 1 < nq) step(q + 1, set1());
+    }
+    if (nq > 0) { if ((nq - 1) & 1) finish(nq - 1, set1()); else finish(nq - 1, set0()); }
+    return;
+  }
+
+  // -------------------------------------------------------------------- compute waves
+  const int l32 = lane & 31, h = lane >> 5;
+  const int wm = wave / WGN, wn = wave % WGN;
+  // weights: lane (column ci = wn*32 + l32, 8 co at cc*16 + h*8) of tap s
+  bf16x8_t wr[9][CC];
+#pragma unroll
+  for (int s = 0; s < 9; ++s)
+#pragma unroll
+    for (int cc = 0; cc < CC; ++cc)
+      wr[s][cc] = *reinterpret_cast<const bf16x8_t*>(a.wt + ((int64_t)s * CI + wn * 32 + l32) * CO + cc * 16 + h * 8);
+
+  // this lane's quad within a band (lanes beyond the band work on quad 0 and store nothing)
+  const int qi = wm * 32 + l32;
+  const bool in_band = qi < TQ * Wo;
+  const int al = in_band ? qi / Wo : 0, b = in_band ? qi - al * Wo : 0;
+  const uint32_t abase = (uint32_t)(al * RP + b * 128);
+  uint32_t hx[2];
+#pragma unroll
+  for (int dxo = 0; dxo < 2; ++dxo) hx[dxo] = (uint32_t)(h * 16) ^ dy_swz_bits((uint32_t)((b + dxo) * 128));
+  // staged position of the lane's four pixels (class c = py*2 + px), columns wn*32 + h*4 + g*8
+  uint32_t sp[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const uint32_t L = (uint32_t)((((2 * al + (c >> 1)) * W + 2 * b + (c & 1)) * CI + wn * 32 + h * 4) * 2);
+    sp[c] = L ^ tile_swz_bits<CI>(L);
+  }
+  const bool col_ok[2] = {in_band, in_band && 2 * b + 1 < W};
+
+  __builtin_amdgcn_s_barrier();
+  for (int q = 0; q < nq; ++q) {
+    const int t = blockIdx.x + q * gridDim.x;
+    const int band = t % a.NB;
+    __builtin_amdgcn_s_barrier();  // A(q): band q is in LDS, staging buffer q&1 is free
+    const char* img_s = lds + (q % NBUF) * dyimg_bytes + abase;
+    f32x16_t acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
+#pragma unroll
+    for (int dyo = 0; dyo < 2; ++dyo)
+#pragma unroll
+      for (int dxo = 0; dxo < 2; ++dxo)
+#pragma unroll
+        for (int cc = 0; cc < CC; ++cc) {
+          const bf16x8_t av = *reinterpret_cast<const bf16x8_t*>(img_s + dyo * RP + dxo * 128 + ((uint32_t)(cc * 32) ^ hx[dxo]));
+          // class (py, px) takes tap u = py ? (dyo ? 0 : 2) : 1 from row offset dyo (even rows only from dyo = 0), same for columns
+          if (dyo == 0 && dxo == 0) {
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 1][cc], av, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 2][cc], av, acc[1], 0, 0, 0);
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 1][cc], av, acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 2][cc], av, acc[3], 0, 0, 0);
+          } else if (dyo == 0 && dxo == 1) {
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 0][cc], av, acc[1], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 0][cc], av, acc[3], 0, 0, 0);
+          } else if (dyo == 1 && dxo == 0) {
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 1][cc], av, acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 2][cc], av, acc[3], 0, 0, 0);
+          } else {
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 0][cc], av, acc[3], 0, 0, 0);
+          }
+        }
+    // ---- stage: lane holds, per class, columns wn*32 + g*8 + h*4 + 0..3 of its pixel
+    char* st = stage0 + (q & 1) * stage_bytes;
+    const int rows_here = a.H - 2 * band * TQ;  // image rows left from the band's first row
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (col_ok[c & 1] && 2 * al + (c >> 1) < rows_here) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          uint2 o;
+          o.x = pack2bf(acc[c][g * 4], acc[c][g * 4 + 1]);
+          o.y = pack2bf(acc[c][g * 4 + 2], acc[c][g * 4 + 3]);
+          *reinterpret_cast<uint2*>(st + (sp[c] ^ (uint32_t)(g * 16))) = o;
+        }
+      }
+    }
+    __builtin_amdgcn_s_barrier();  // B(q)
+  }
+}

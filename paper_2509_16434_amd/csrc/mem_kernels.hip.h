@@ -588,6 +588,14 @@ __global__ void k_transpose_bf16(const bf16_t* __restrict__ src, int rows, int c
   dst[i] = r < rows ? src[(int64_t)r * cols + c] : (bf16_t)0;
 }
 // Transposed-convolution weights of row parity py for pixel-pair rows:
+// Per-tap transpose for the quad-organised transposed convolution: dst[(tap*Cin + ci)*Cout + co] = W[co][tap*Cin + ci].
+__global__ void k_pack_dgrad_taps(const bf16_t* __restrict__ w, int Cout, int Cin, bf16_t* __restrict__ dst) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)9 * Cin * Cout) return;
+  const int tap = (int)(i / ((int64_t)Cin * Cout)), rem = (int)(i - (int64_t)tap * Cin * Cout), ci = rem / Cout, co = rem - ci * Cout;
+  dst[i] = w[(int64_t)co * 9 * Cin + tap * Cin + ci];
+}
+
 // dst[px*Cin + ci][(tu*2 + dx)*Cout + co] = W[co][(u*3+v)*Cin + ci] with u = py ? 2*tu : 1 and the
 // column tap v given by (px, dx): even pixel (px = 0) takes v = 1 from dx = 0 and nothing from
 // dx = 1; odd pixel takes v = 2 from dx = 0 and v = 0 from dx = 1.

@@ -17,6 +17,7 @@
 #include "mem_kernels.hip.h"
 #include "fused.hip.h"
 #include "conv_tile.hip.h"
+#include "conv_dgrad_tile.hip.h"
 
 static_assert(sizeof(DevStats) == sizeof(ppo_mb_stats), "device and host statistics records must match");
 
@@ -42,6 +43,7 @@ struct Ctx {
   float *p = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
   bf16_t* shadow = nullptr;
   bf16_t* wd[PPO_MAX_LAYERS][2];  // transposed-conv weights per row parity (conv layers >= 1)
+  bf16_t* wtap[PPO_MAX_LAYERS];   // the same weights transposed per tap: [9][Cin][Cout]
   bf16_t* fcT[PPO_MAX_LAYERS];    // [in][out]
   bf16_t* headT = nullptr;        // [hid][32]
   // device: rollout buffer (SoA)
@@ -359,6 +361,7 @@ int repack_weights(Ctx* c) {
       int64_t n = (int64_t)2 * Ci * (1 + py) * 2 * Co;
       hipLaunchKernelGGL(k_pack_dgrad_w, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->shadow + c->convW[l], Co, Ci, py, c->wd[l][py]);
     }
+    hipLaunchKernelGGL(k_pack_dgrad_taps, dim3(cdiv((int64_t)9 * Ci * Co, 256)), dim3(256), 0, c->stream, c->shadow + c->convW[l], Co, Ci, c->wtap[l]);
   }
   for (int l = 0; l < c->nfc; ++l) {
     int64_t n = (int64_t)c->fin[l] * c->fout[l];
@@ -464,6 +467,36 @@ int launch_conv_wgrad_tile(Ctx* c, const ImgAddr& dy, const AConvFwd& xl, int Co
   const double flops = 2.0 * (double)xl.M * Cout * xl.K;
   return xl.Cin == 32 ? launch_conv_wgrad_tile_t<32>(c, a, gw, gb, accumulate, name, flops, abytes)
                       : launch_conv_wgrad_tile_t<64>(c, a, gw, gb, accumulate, name, flops, abytes);
+}
+
+// Transposed convolution through the quad-organised LDS-image kernel; returns 1 when the shape is
+// not covered (the caller then takes the implicit-GEMM path).
+template <int CI>
+int launch_conv_dgrad_tile_t(Ctx* c, ConvDgradArgs a, int nimg, const std::string& name, double flops, double abytes) {
+  typedef ConvDgradShape<CI> S;
+  if (a.Wo > S::BQ) return 1;
+  int TQ = S::BQ / a.Wo < a.Ho ? S::BQ / a.Wo : a.Ho;
+  while (TQ > 1 && (S::stage_bytes(a.W, TQ) > S::MAXCH * 128 * 16 || S::lds_bytes(a.W, a.Wo, TQ) > 158 * 1024)) --TQ;
+  if (S::stage_bytes(a.W, TQ) > S::MAXCH * 128 * 16 || S::lds_bytes(a.W, a.Wo, TQ) > 158 * 1024) return 1;
+  a.NB = cdiv(a.Ho, TQ); a.TQ = cdiv(a.Ho, a.NB); a.ntiles = nimg * a.NB;
+  const int segs = cdiv(a.Wo * 128, 1024);
+  if (segs > S::MAXSEG || cdiv(a.TQ + 1, 2) * segs > 63) return 1;
+  int gx = a.ntiles < 256 ? a.ntiles : 256;
+  auto kfn = k_conv_dgrad_tile<CI>;
+  static bool attr_set = false;
+  if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_set = true; }
+  ProfScope ps(c, name, flops, abytes);
+  hipLaunchKernelGGL(kfn, dim3(gx), dim3(S::THREADS), S::lds_bytes(a.W, a.Wo, a.TQ), c->stream, a);
+  LAUNCHCHK(c, "k_conv_dgrad_tile");
+  return PPO_OK;
+}
+int launch_conv_dgrad_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, bf16_t* dx, const bf16_t* wt, int Co, int Ci, int H, int W, int Ho, int Wo,
+                           int nimg, const std::string& name, double flops, double abytes) {
+  if (Co != 64 || (Ci != 32 && Ci != 64) || dy.idx || nimg < 1) return 1;
+  ConvDgradArgs a;
+  a.dy = dy; a.dy.prepare(); a.dx = dx; a.x = xa.base; a.x_stride_b = xa.stride_b; a.x_stride_v = xa.stride_v;
+  a.wt = wt; a.zpage = c->zpage; a.V = xa.V; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.TQ = 0; a.NB = 0; a.ntiles = 0;
+  return Ci == 32 ? launch_conv_dgrad_tile_t<32>(c, a, nimg, name, flops, abytes) : launch_conv_dgrad_tile_t<64>(c, a, nimg, name, flops, abytes);
 }
 
 // Forward of `n` samples selected by device indices idx (NULL = 0..n-1 offset by `first`).
@@ -600,7 +633,9 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
       return PPO_OK;
     }
     double ab = 2.0 * ((double)nimg * Ho * Wo * Co + 2.0 * pix * Ci + 9.0 * Ci * Co);
-    rc = launch_gemm(c, al, M0, nullptr, 0, 2 * Ci, 4 * Co, ep, "conv_dgrad." + std::to_string(l), ab, 2, 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co);
+    const double dflops = 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co;
+    rc = launch_conv_dgrad_tile(c, dy, xa, c->gbuf[cur ^ 1], c->wtap[l], Co, Ci, H, W, Ho, Wo, nimg, "conv_dgrad." + std::to_string(l), dflops, ab);
+    if (rc == PPO_OK + 1) rc = launch_gemm(c, al, M0, nullptr, 0, 2 * Ci, 4 * Co, ep, "conv_dgrad." + std::to_string(l), ab, 2, dflops);
     if (rc) return rc;
     cur ^= 1;
   }
@@ -709,8 +744,10 @@ int create_impl(Ctx* c) {
   // parameters
   DALLOC(c, c->p, c->total); DALLOC(c, c->m, c->total); DALLOC(c, c->v, c->total); DALLOC(c, c->g, c->total);
   DALLOC(c, c->shadow, c->total + 8);
-  for (int l = 1; l < c->nconv; ++l)
+  for (int l = 1; l < c->nconv; ++l) {
     for (int py = 0; py < 2; ++py) DALLOC(c, c->wd[l][py], (int64_t)2 * c->cC[l] * (1 + py) * 2 * c->cC[l + 1]);
+    DALLOC(c, c->wtap[l], (int64_t)9 * c->cC[l] * c->cC[l + 1]);
+  }
   for (int l = 0; l < c->nfc; ++l) DALLOC(c, c->fcT[l], (int64_t)c->fin[l] * c->fout[l]);
   DALLOC(c, c->headT, (int64_t)c->hid * HEAD_LD);
   // rollout buffer
