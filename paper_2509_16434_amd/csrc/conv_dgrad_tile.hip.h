@@ -16,6 +16,15 @@
 // three roles.  The finishing waves fetch the mask two tiles ahead with ordinary loads into two
 // register sets, so their only waits are the compiler's.
 //
+// Fused form (C0 > 0, CI = 32): the layer below is the first convolution, whose only gradient is
+// its weight gradient G0[ci][k0] = sum over pixels of dXmasked[pixel][ci] * patch[pixel][k0] with
+// the pixel's 3x3 window of the C0-channel input image as patch (plus a constant 1 for the bias).
+// The loaders then also copy the band's input-image rows into an LDS ring; each finishing wave takes
+// half of the band's pixels: it writes the masked values back into the staging area instead of to
+// memory, builds the pixels' patch rows in LDS from the image rows, and contracts the two over its
+// pixels with transposing LDS reads and one MFMA per 16 pixels.  The input gradient of the first
+// layer's output therefore never reaches HBM.  Each block leaves one fp32 partial [CI][9*C0+1].
+//
 // dY pixels are 128 bytes; their 16-byte chunks are permuted by (slot >> 1) & 7, the staged pixels'
 // by tile_swz_bits<CI> of the band-linear offset: lanes of one access own consecutive quads.
 #pragma once
@@ -31,6 +40,10 @@ struct ConvDgradArgs {
   const bf16_t* zpage;        // 1 KiB of zeros
   int V, H, W, Ho, Wo;
   int TQ, NB, ntiles;         // quad rows per band, bands per image, nimg * NB
+  // fused first-layer weight gradient only:
+  ImgAddr img0;               // the first layer's input images [H0][W0][C0] (gathered through idx)
+  int H0, W0;
+  float* partial0;            // [gridDim.x][CI][9*C0 + 1]
 };
 
 template <int CI>
@@ -40,17 +53,29 @@ struct ConvDgradShape {
   static int dyimg_bytes(int Wo, int TQ) { return (TQ + 1) * (Wo + 1) * 128; }
   static int stage_bytes(int W, int TQ) { return 2 * TQ * W * CI * 2; }
   static int lds_bytes(int W, int Wo, int TQ) { return NBUF * dyimg_bytes(Wo, TQ) + 2 * stage_bytes(W, TQ); }
+  // fused form: image-row ring, one patch table per finishing wave, a zero chunk, the two waves' sums
+  static int kp(int C0) { return 9 * C0 + 1 <= 16 ? 16 : 32; }
+  static int img0_bytes(int W0, int C0, int TQ) { return (4 * TQ + 1) * W0 * C0 * 2; }
+  static int fused_extra(int W, int W0, int C0, int TQ) {
+    return NBUF * img0_bytes(W0, C0, TQ) + 2 * (TQ * W) * kp(C0) * 2 + 16 + 2 * 32 * 32 * 4;
+  }
 };
 
 __device__ __forceinline__ uint32_t dy_swz_bits(uint32_t off) { return ((off >> 8) & 7u) << 4; }
 
 __device__ __forceinline__ uint32_t relu_keep(uint32_t m) {
-  // all-ones halves where the stored bf16 is > 0 (sign clear and not zero)
-  return (((short)(m & 0xffffu) > 0) ? 0x0000ffffu : 0u) | (((short)(m >> 16) > 0) ? 0xffff0000u : 0u);
+  // all-ones halves where the stored bf16 is > 0 (as a 16-bit integer: positive), in packed 16-bit
+  // arithmetic: y = max(x, 0) is non-zero exactly there, and (0 - y) >> 15 spreads that to a mask
+  typedef short s16x2_t __attribute__((ext_vector_type(2)));
+  const s16x2_t x = __builtin_bit_cast(s16x2_t, m), zero = {0, 0};
+  const s16x2_t y = __builtin_elementwise_max(x, zero);
+  const s16x2_t k = (zero - y) >> 15;
+  return __builtin_bit_cast(uint32_t, k);
 }
 
-template <int CI>
+template <int CI, int C0>
 __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
+  static_assert(C0 == 0 || CI == 32, "the fused form is written for 32 input channels");
   typedef ConvDgradShape<CI> S;
   constexpr int CO = S::CO, CC = CO / 16, WGN = S::WGN, NBUF = S::NBUF;
   extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -60,6 +85,15 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
   const int dyimg_bytes = (TQ + 1) * RP;
   const int stage_bytes = 2 * TQ * W * CI * 2;
   char* const stage0 = lds + NBUF * dyimg_bytes;
+  // fused form
+  constexpr int K0 = 9 * C0, KP = (K0 + 1 <= 16) ? 16 : 32;
+  const int RB0 = a.W0 * C0 * 2, NR0 = 4 * TQ + 1, img0_bytes = NR0 * RB0;
+  const int half = TQ * W;  // pixels per finishing wave (a multiple of 16)
+  char* const img0_ring = stage0 + 2 * stage_bytes;
+  char* const patch0 = img0_ring + NBUF * img0_bytes;
+  char* const zero16 = patch0 + 2 * half * KP * 2;
+  float* const red = reinterpret_cast<float*>(zero16 + 16);
+  if (C0 > 0 && tid < 4) reinterpret_cast<uint32_t*>(zero16)[tid] = 0u;
   const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
 
   // zero the right pad slot of every dY image row once
@@ -72,7 +106,8 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     // ------------------------------------------------------------------ loaders: image row r belongs to loader r % 2
     const int lw = wave - 4;
     const int rowbytes = Wo * 128, segs = (rowbytes + 1023) >> 10;
-    const int ni = ((TQ + 1 - lw + 1) >> 1) * segs;  // this wave's loads per band
+    const int segs0 = (RB0 + 1023) >> 10;
+    const int ni = ((TQ + 1 - lw + 1) >> 1) * segs + (C0 > 0 ? ((NR0 - lw + 1) >> 1) * segs0 : 0);  // this wave's loads per band
     int goff[S::MAXSEG];
 #pragma unroll
     for (int sg = 0; sg < S::MAXSEG; ++sg) {
@@ -94,6 +129,20 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
             if (goff[sg] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + row * RP + sg * 1024), 16, 0, 0);
           }
       }
+      if constexpr (C0 > 0) {
+        // input-image rows 4*band*TQ - 1 ... + 4*TQ, as they are (rows outside the image: zeros)
+        const int iy0 = 4 * band * TQ - 1;
+        const char* isrc = reinterpret_cast<const char*>(a.img0.ptr(img)) + (int64_t)iy0 * RB0;
+        char* idst = img0_ring + (q % NBUF) * img0_bytes;
+        for (int row = lw; row < NR0; row += 2) {
+          const bool inside = iy0 + row >= 0 && iy0 + row < a.H0;
+          for (int sg = 0; sg < segs0; ++sg) {
+            const int o = sg * 1024 + lane * 16;
+            const char* p = inside ? isrc + (int64_t)row * RB0 + o : reinterpret_cast<const char*>(a.zpage) + lane * 16;
+            if (o < RB0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(idst + row * RB0 + sg * 1024), 16, 0, 0);
+          }
+        }
+      }
     };
     if (nq > 0) issue(0);
     if (nq > 1) issue(1);
@@ -104,13 +153,19 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       if (q + 2 < nq) issue(q + 2);
       __builtin_amdgcn_s_barrier();      // B(q)
     }
+    __builtin_amdgcn_s_barrier();        // C
     return;
   }
 
   if (wave >= 6) {
     // ------------------------------------------------------------------ finishing waves
-    const int et = tid - 384;  // 0..127
+    // Unfused: the two waves share the band's chunks (thread et of 128 takes et, et+128, ...).
+    // Fused: wave fw owns the pixels [fw*half, (fw+1)*half) and their chunks.
+    const int et = tid - 384, fw = wave - 6;
     const int nchunk = stage_bytes >> 4;
+    const int nchw = half * (CI / 8);  // chunks per finishing wave (fused)
+    auto chunk_of = [&](int i) -> int { return C0 > 0 ? fw * nchw + lane + 64 * i : et + 128 * i; };
+    auto chunk_mine = [&](int i) -> bool { return C0 > 0 ? lane + 64 * i < nchw : et + 128 * i < nchunk; };
     // two register sets: the mask of tile q+1 is fetched while tile q-1 is finished (two tiles of
     // mask bytes in flight per CU)
     uint4 mk[2][S::MAXCH];
@@ -126,24 +181,109 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       nvalid[SET] = rows * W * CI / 8;
 #pragma unroll
       for (int i = 0; i < S::MAXCH; ++i) {
-        const int c = et + 128 * i;
-        mk[SET][i] = (c < nvalid[SET]) ? *reinterpret_cast<const uint4*>(a.x + band_off[SET] + (int64_t)c * 8) : make_uint4(0u, 0u, 0u, 0u);
+        const int c = chunk_of(i);
+        // wave-uniform base + 32-bit lane offset, formed here (the empty asm keeps the compiler from
+        // carrying sixteen 64-bit addresses across the tile loop, which spills)
+        const char* xb = reinterpret_cast<const char*>(a.x + band_off[SET]);
+        uint32_t off = (uint32_t)c * 16u;
+        asm volatile("" : "+v"(off));
+        mk[SET][i] = (chunk_mine(i) && c < nvalid[SET]) ? *reinterpret_cast<const uint4*>(xb + off) : make_uint4(0u, 0u, 0u, 0u);
       }
     };
+
+    // ---- fused form: patch values of this lane's pixels, the patch table, the running sums
+    constexpr int PJ = 4, NV = K0 + 1, NREG = (NV + 1) / 2;
+    uint32_t tp[PJ][NREG > 0 ? NREG : 1];
+    int toff[PJ]; uint32_t tcol[PJ];
+    f32x16_t accw;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) accw[e] = 0.f;
+    char* const patch_w = patch0 + fw * half * KP * 2;
+    if constexpr (C0 > 0) {
+#pragma unroll
+      for (int j = 0; j < PJ; ++j) {
+        const int pj = lane + 64 * j, bp = fw * half + (pj < half ? pj : 0), prow = bp / W, ix = bp - prow * W;
+        toff[j] = (2 * prow) * RB0 + (2 * ix - 1) * C0 * 2;                  // window corner within the band's image rows
+        tcol[j] = (ix > 0 ? 1u : 0u) | 2u | (2 * ix + 1 < a.W0 ? 4u : 0u);   // window columns inside the image
+      }
+    }
+    auto load_taps = [&](int q) {  // from the image rows of tile q (in LDS since A(q)) into registers
+      if constexpr (C0 > 0) {
+        const char* im = img0_ring + (q % NBUF) * img0_bytes;
+#pragma unroll
+        for (int j = 0; j < PJ; ++j) {
+#pragma unroll
+          for (int r = 0; r < NREG; ++r) tp[j][r] = 0u;
+          if (lane + 64 * j < half) {
+#pragma unroll
+            for (int u = 0; u < 3; ++u)
+#pragma unroll
+              for (int v = 0; v < 3; ++v)
+#pragma unroll
+                for (int cch = 0; cch < C0; ++cch) {
+                  const int k = (u * 3 + v) * C0 + cch;
+                  // columns outside the image read the zero chunk (no branch around the load)
+                  const char* src = ((tcol[j] >> v) & 1u) ? im + toff[j] + u * RB0 + (v * C0 + cch) * 2 : zero16;
+                  const uint32_t x = (uint32_t)*reinterpret_cast<const unsigned short*>(src);
+                  tp[j][k >> 1] |= x << (16 * (k & 1));
+                }
+            tp[j][K0 >> 1] |= 0x3F80u << (16 * (K0 & 1));  // the bias column: 1.0
+          }
+        }
+      }
+    };
+
     auto finish = [&](int q, auto setc) {  // tile q was loaded into set q & 1
       constexpr int SET = decltype(setc)::value;
-      const char* st = stage0 + (q & 1) * stage_bytes;
+      char* st = stage0 + (q & 1) * stage_bytes;
       // One wait for everything outstanding (this set's mask, fetched two tiles ago, and the younger
       // set's): otherwise every use of a mask register below waits for the store issued just before it.
       vm_wait<0>();
 #pragma unroll
       for (int i = 0; i < S::MAXCH; ++i) {
-        const int c = et + 128 * i;
-        if (c < nvalid[SET] && c < nchunk) {
-          const uint32_t L = (uint32_t)c * 16u;
-          uint4 v = *reinterpret_cast<const uint4*>(st + (L ^ tile_swz_bits<CI>(L)));
+        const int c = chunk_of(i);
+        if (chunk_mine(i) && (C0 > 0 || c < nvalid[SET])) {
+          const uint32_t L = (uint32_t)c * 16u, ph = L ^ tile_swz_bits<CI>(L);
+          uint4 v = *reinterpret_cast<const uint4*>(st + ph);
           v.x &= relu_keep(mk[SET][i].x); v.y &= relu_keep(mk[SET][i].y); v.z &= relu_keep(mk[SET][i].z); v.w &= relu_keep(mk[SET][i].w);
-          *reinterpret_cast<uint4*>(a.dx + band_off[SET] + (int64_t)c * 8) = v;
+          if constexpr (C0 > 0) *reinterpret_cast<uint4*>(st + ph) = v;  // chunks outside the image become zeros
+          else {
+            uint32_t off = L;
+            asm volatile("" : "+v"(off));
+            *reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.dx + band_off[SET]) + off) = v;
+          }
+        }
+      }
+      if constexpr (C0 > 0) {
+#pragma unroll
+        for (int j = 0; j < PJ; ++j) {
+          const int pj = lane + 64 * j;
+          if (pj < half) {
+            uint32_t row[KP / 2];
+#pragma unroll
+            for (int r = 0; r < KP / 2; ++r) row[r] = r < NREG ? tp[j][r] : 0u;
+#pragma unroll
+            for (int r = 0; r < KP / 8; ++r)
+              *reinterpret_cast<uint4*>(patch_w + pj * KP * 2 + r * 16) = make_uint4(row[4 * r], row[4 * r + 1], row[4 * r + 2], row[4 * r + 3]);
+          }
+        }
+        // G0[ci][k0] += sum over this wave's pixels: both operands through transposing reads
+        // Sixteen pixels further on is 1 KiB further in the staging area, which leaves the permutation
+        // bits (8 and 9 of the offset) as they are: every address below is affine in the step.
+        const int g = lane >> 4, r16 = lane & 15, col = 16 * (g & 1) + 4 * (r16 & 3);
+        const int p = 8 * (g >> 1) + (r16 >> 2);
+        const uint32_t L0 = (uint32_t)(((fw * half + p) * CI + col) * 2), L1 = L0 + 4 * CI * 2;
+        const char* a0 = st + (L0 ^ tile_swz_bits<CI>(L0));
+        const char* a1 = st + (L1 ^ tile_swz_bits<CI>(L1));
+        const bool bz = col >= KP;  // table columns beyond KP read the zero chunk
+        const char* b0 = bz ? zero16 : patch_w + (p * KP + col) * 2;
+        const char* b1 = bz ? zero16 : b0 + 4 * KP * 2;
+        const int bstep = bz ? 0 : 16 * KP * 2;
+        for (int s0 = 0; s0 < half; s0 += 16) {
+          const bf16x8_t av = lds_read_tr8_2(a0, a1);
+          const bf16x8_t bv = lds_read_tr8_2(b0, b1);
+          accw = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, accw, 0, 0, 0);
+          a0 += 16 * CI * 2; a1 += 16 * CI * 2; b0 += bstep; b1 += bstep;
         }
       }
     };
@@ -157,6 +297,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
         finish(q - 1, other());
         if (q + 1 < nq) load_mask(q + 1, other());
       }
+      load_taps(q);
       __builtin_amdgcn_s_barrier();  // B(q): tile q is staged
     };
     if (nq > 0) load_mask(0, set0());
@@ -167,6 +308,21 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       if (q + 1 < nq) step(q + 1, set1());
     }
     if (nq > 0) { if ((nq - 1) & 1) finish(nq - 1, set1()); else finish(nq - 1, set0()); }
+    if constexpr (C0 > 0) {
+      // accw[e] = G0[ci][k0] with k0 = lane % 32, ci = (e/4)*8 + (lane/32)*4 + e%4
+#pragma unroll
+      for (int e = 0; e < 16; ++e) red[fw * 1024 + ((e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)) * 32 + (lane & 31)] = accw[e];
+    }
+    __builtin_amdgcn_s_barrier();    // C
+    if constexpr (C0 > 0) {
+      if (fw == 0) {
+        float* P = a.partial0 + (int64_t)blockIdx.x * CI * NV;
+        for (int i = lane; i < CI * NV; i += 64) {
+          const int ci = i / NV, k = i - ci * NV;
+          P[i] = red[ci * 32 + k] + red[1024 + ci * 32 + k];
+        }
+      }
+    }
     return;
   }
 
@@ -249,4 +405,5 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     }
     __builtin_amdgcn_s_barrier();  // B(q)
   }
+  __builtin_amdgcn_s_barrier();    // C
 }

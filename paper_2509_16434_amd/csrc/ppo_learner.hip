@@ -470,33 +470,71 @@ int launch_conv_wgrad_tile(Ctx* c, const ImgAddr& dy, const AConvFwd& xl, int Co
 }
 
 // Transposed convolution through the quad-organised LDS-image kernel; returns 1 when the shape is
-// not covered (the caller then takes the implicit-GEMM path).
-template <int CI>
-int launch_conv_dgrad_tile_t(Ctx* c, ConvDgradArgs a, int nimg, const std::string& name, double flops, double abytes) {
+// not covered (the caller then takes the implicit-GEMM path).  With C0 > 0 the kernel also forms
+// the first layer's weight-gradient partials (a.img0, a.H0, a.W0 set by the caller) and *grid_out
+// receives the number of partials.
+template <int CI, int C0>
+int launch_conv_dgrad_tile_t(Ctx* c, ConvDgradArgs a, int nimg, const std::string& name, double flops, double abytes, int* grid_out) {
   typedef ConvDgradShape<CI> S;
   if (a.Wo > S::BQ) return 1;
+  auto lds_of = [&](int tq) { return S::lds_bytes(a.W, a.Wo, tq) + (C0 > 0 ? S::fused_extra(a.W, a.W0, C0, tq) : 0); };
+  auto fits = [&](int tq) {
+    if (S::stage_bytes(a.W, tq) > S::MAXCH * 128 * 16 || lds_of(tq) > 158 * 1024) return false;
+    if (C0 > 0 && ((tq * a.W) % 16 != 0 || tq * a.W > 256)) return false;  // pixels per finishing wave
+    return true;
+  };
   int TQ = S::BQ / a.Wo < a.Ho ? S::BQ / a.Wo : a.Ho;
-  while (TQ > 1 && (S::stage_bytes(a.W, TQ) > S::MAXCH * 128 * 16 || S::lds_bytes(a.W, a.Wo, TQ) > 158 * 1024)) --TQ;
-  if (S::stage_bytes(a.W, TQ) > S::MAXCH * 128 * 16 || S::lds_bytes(a.W, a.Wo, TQ) > 158 * 1024) return 1;
-  a.NB = cdiv(a.Ho, TQ); a.TQ = cdiv(a.Ho, a.NB); a.ntiles = nimg * a.NB;
+  while (TQ > 1 && !fits(TQ)) --TQ;
+  if (!fits(TQ)) return 1;
+  a.NB = cdiv(a.Ho, TQ);
+  if (C0 == 0 || fits(cdiv(a.Ho, a.NB))) TQ = cdiv(a.Ho, a.NB);  // balanced bands
+  a.TQ = TQ; a.NB = cdiv(a.Ho, TQ); a.ntiles = nimg * a.NB;
   const int segs = cdiv(a.Wo * 128, 1024);
-  if (segs > S::MAXSEG || cdiv(a.TQ + 1, 2) * segs > 63) return 1;
+  int ni = cdiv(a.TQ + 1, 2) * segs;
+  if (C0 > 0) {
+    const int rb0 = a.W0 * C0 * 2;
+    if (rb0 % 16) return 1;
+    ni += cdiv(4 * a.TQ + 1, 2) * cdiv(rb0, 1024);
+  }
+  if (segs > S::MAXSEG || ni > 63) return 1;
   int gx = a.ntiles < 256 ? a.ntiles : 256;
-  auto kfn = k_conv_dgrad_tile<CI>;
+  if (C0 > 0) {
+    const int64_t npair = (int64_t)CI * (9 * C0 + 1);
+    if (gx * npair > c->partial_elems) gx = (int)(c->partial_elems / npair);
+    if (gx < 1) return 1;
+    a.partial0 = c->partial;
+    *grid_out = gx;
+  }
+  auto kfn = k_conv_dgrad_tile<CI, C0>;
   static bool attr_set = false;
   if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_set = true; }
   ProfScope ps(c, name, flops, abytes);
-  hipLaunchKernelGGL(kfn, dim3(gx), dim3(S::THREADS), S::lds_bytes(a.W, a.Wo, a.TQ), c->stream, a);
+  hipLaunchKernelGGL(kfn, dim3(gx), dim3(S::THREADS), lds_of(a.TQ), c->stream, a);
   LAUNCHCHK(c, "k_conv_dgrad_tile");
   return PPO_OK;
+}
+ConvDgradArgs conv_dgrad_args(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, bf16_t* dx, const bf16_t* wt, int H, int W, int Ho, int Wo) {
+  ConvDgradArgs a;
+  a.dy = dy; a.dy.prepare(); a.dx = dx; a.x = xa.base; a.x_stride_b = xa.stride_b; a.x_stride_v = xa.stride_v;
+  a.wt = wt; a.zpage = c->zpage; a.V = xa.V; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.TQ = 0; a.NB = 0; a.ntiles = 0;
+  a.img0 = ImgAddr(); a.img0.base = nullptr; a.img0.idx = nullptr; a.img0.stride_b = 0; a.img0.stride_v = 0; a.img0.V = 1;
+  a.H0 = 0; a.W0 = 0; a.partial0 = nullptr;
+  return a;
 }
 int launch_conv_dgrad_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, bf16_t* dx, const bf16_t* wt, int Co, int Ci, int H, int W, int Ho, int Wo,
                            int nimg, const std::string& name, double flops, double abytes) {
   if (Co != 64 || (Ci != 32 && Ci != 64) || dy.idx || nimg < 1) return 1;
-  ConvDgradArgs a;
-  a.dy = dy; a.dy.prepare(); a.dx = dx; a.x = xa.base; a.x_stride_b = xa.stride_b; a.x_stride_v = xa.stride_v;
-  a.wt = wt; a.zpage = c->zpage; a.V = xa.V; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.TQ = 0; a.NB = 0; a.ntiles = 0;
-  return Ci == 32 ? launch_conv_dgrad_tile_t<32>(c, a, nimg, name, flops, abytes) : launch_conv_dgrad_tile_t<64>(c, a, nimg, name, flops, abytes);
+  ConvDgradArgs a = conv_dgrad_args(c, dy, xa, dx, wt, H, W, Ho, Wo);
+  return Ci == 32 ? launch_conv_dgrad_tile_t<32, 0>(c, a, nimg, name, flops, abytes, nullptr)
+                  : launch_conv_dgrad_tile_t<64, 0>(c, a, nimg, name, flops, abytes, nullptr);
+}
+// The same with the first layer's weight gradient fused in (depth input, 32 channels after the first layer).
+int launch_conv_dgrad_wgrad0_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, const bf16_t* wt, int Co, int Ci, int H, int W, int Ho, int Wo,
+                                  const ImgAddr& img0, int C0, int H0, int W0, int nimg, const std::string& name, double flops, double abytes, int* grid_out) {
+  if (Co != 64 || Ci != 32 || C0 != 1 || dy.idx || nimg < 1) return 1;
+  ConvDgradArgs a = conv_dgrad_args(c, dy, xa, nullptr, wt, H, W, Ho, Wo);
+  a.img0 = img0; a.img0.prepare(); a.H0 = H0; a.W0 = W0;
+  return launch_conv_dgrad_tile_t<32, 1>(c, a, nimg, name, flops, abytes, grid_out);
 }
 
 // Forward of `n` samples selected by device indices idx (NULL = 0..n-1 offset by `first`).
@@ -611,7 +649,14 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
       const int K0 = 9 * c->cC[0], npair = Ci * (K0 + 1), tpp = cdiv(M0, 128);
       int grid = 2 * tpp < 512 ? 2 * tpp : 512;
       if ((int64_t)grid * npair > c->partial_elems) grid = (int)(c->partial_elems / npair);
-      {
+      const double fflops = 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co + 2.0 * pix * Ci * (K0 + 1);
+      const double fbytes = 2.0 * ((double)nimg * Ho * Wo * Co + pix * Ci + (double)nimg * c->img_elems + 9.0 * Ci * Co);
+      int tgrid = 0;
+      rc = launch_conv_dgrad_wgrad0_tile(c, dy, xa, c->wtap[l], Co, Ci, H, W, Ho, Wo, in, c->cC[0], c->cH[0], c->cW[0], nimg,
+                                         "conv_dgrad.1+wgrad.0", fflops, fbytes, &tgrid);
+      if (rc == PPO_OK) grid = tgrid;
+      else if (rc != PPO_OK + 1) return rc;
+      else {
         ProfScope ps(c, "conv_dgrad.1+wgrad.0", 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co + 2.0 * pix * Ci * (K0 + 1),
                      2.0 * ((double)nimg * Ho * Wo * Co + pix * Ci + (double)nimg * c->img_elems + 9.0 * Ci * Co));
 #define LAUNCH_FUSED(BN_, WM_, WN_, CI0_)                                                                                                  \
