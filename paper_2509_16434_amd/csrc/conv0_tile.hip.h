@@ -1,0 +1,160 @@
+// First convolution (1 or 3 input channels -> up to 64 output channels, 3x3 stride 2 pad 1),
+// forward.  The layer writes eight to thirty times more bytes than it reads, and its 3x3 windows
+// are nine 2-byte elements per pixel: fetched from global memory they cost nine load instructions
+// per 32 pixels, and the vector-memory instruction rate of a wave, not bandwidth, sets the pace.
+// Here one loader wave copies each band's image rows (a few KiB) into an LDS ring with
+// LDS-writing 16-byte loads, seven compute waves take the band's pixels in groups of 32 (lane =
+// pixel), gather the window from LDS with 2-byte reads, apply the weights with one or two MFMAs
+// (K = 9*C0 padded to 16 or 32), add bias, clamp, round to bf16, stage the 32 pixels in a private
+// LDS strip and write them as 16-byte segments of the band's contiguous output span.  The images
+// are addressed through the minibatch's gather list.
+#pragma once
+#include "conv_tile.hip.h"
+
+struct Conv0Args {
+  ImgAddr in;                 // input images [H][W][C0], gathered through in.idx
+  bf16_t* out;                // output images [Ho][Wo][Cout], dense, image i at out + i*Ho*Wo*Cout
+  const bf16_t* w;            // [Cout][9*C0]
+  const float* bias;
+  const bf16_t* zpage;        // 1 KiB of zeros
+  int H, W, Ho, Wo, Cout;
+  int TR, NB, ntiles;         // output rows per band, bands per image, nimg * NB
+};
+
+template <int C0>
+struct Conv0Shape {
+  static constexpr int K = 9 * C0, KS = (K + 15) / 16, NBUF = 3, THREADS = 512, NCW = 7;
+  static constexpr int MAXSEG = 2;
+  static int image_bytes(int W, int TR) { return (2 * TR + 1) * W * C0 * 2; }
+  static int lds_bytes(int W, int TR, int Cout) { return NBUF * image_bytes(W, TR) + 16 + NCW * 32 * (Cout + 8) * 2; }
+};
+
+template <int C0>
+__global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
+  typedef Conv0Shape<C0> S;
+  constexpr int K = S::K, KS = S::KS, NBUF = S::NBUF, NCW = S::NCW;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, h = lane >> 5;
+  const int W = a.W, TR = a.TR, Wo = a.Wo, Cout = a.Cout;
+  const int RB = W * C0 * 2, nrows = 2 * TR + 1, image_bytes = nrows * RB;
+  char* const zero16 = lds + NBUF * image_bytes;
+  const int SP = Cout + 8;  // staging pitch (elements)
+  const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
+  if (tid < 4) reinterpret_cast<uint32_t*>(zero16)[tid] = 0u;
+
+  if (wave == 7) {
+    // ------------------------------------------------------------------ loader
+    const int segs = (RB + 1023) >> 10, ni = nrows * segs;
+    auto issue = [&](int q) {
+      const int t = blockIdx.x + q * gridDim.x;
+      const int img = t / a.NB, band = t - img * a.NB;
+      const int iy_lo = 2 * band * TR - 1;
+      const char* src = reinterpret_cast<const char*>(a.in.ptr(img)) + (int64_t)iy_lo * RB;
+      char* dst = lds + (q % NBUF) * image_bytes;
+      for (int row = 0; row < nrows; ++row) {
+        const bool inside = iy_lo + row >= 0 && iy_lo + row < a.H;
+        for (int sg = 0; sg < segs; ++sg) {
+          const int o = sg * 1024 + lane * 16;
+          const char* p = inside ? src + (int64_t)row * RB + o : reinterpret_cast<const char*>(a.zpage) + lane * 16;
+          if (o < RB) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + row * RB + sg * 1024), 16, 0, 0);
+        }
+      }
+    };
+    if (nq > 0) issue(0);
+    if (nq > 1) issue(1);
+    __builtin_amdgcn_s_barrier();
+    for (int q = 0; q < nq; ++q) {
+      vm_wait_dyn(q + 1 < nq ? ni : 0);  // band q has landed
+      __builtin_amdgcn_s_barrier();
+      if (q + 2 < nq) issue(q + 2);
+    }
+    return;
+  }
+
+  // -------------------------------------------------------------------- compute waves
+  bf16_t* const stage = reinterpret_cast<bf16_t*>(zero16 + 16) + wave * 32 * SP;
+  const int NJ = (Cout + 31) / 32;
+  // weights (MFMA first operand: row co = jn*32 + l32, 8 k at ks*16 + h*8) and bias per accumulator element
+  bf16x8_t bw[2][KS];
+  float bs[2][16];
+#pragma unroll
+  for (int jn = 0; jn < 2; ++jn) {
+    const int co = jn * 32 + l32;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint32_t t[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int k = ks * 16 + h * 8 + j;
+        const uint32_t x = (k < K && co < Cout) ? (uint32_t)a.w[co * K + k] : 0u;
+        t[j >> 1] |= x << (16 * (j & 1));
+      }
+      bw[jn][ks] = __builtin_bit_cast(bf16x8_t, make_uint4(t[0], t[1], t[2], t[3]));
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { const int c2 = jn * 32 + (e >> 2) * 8 + h * 4 + (e & 3); bs[jn][e] = c2 < Cout ? a.bias[c2] : 0.f; }
+  }
+  const int npix = TR * Wo, ngroups = (npix + 31) >> 5;
+  const int cpr = Cout >> 3;  // 16-byte chunks per pixel
+
+  __builtin_amdgcn_s_barrier();
+  for (int q = 0; q < nq; ++q) {
+    const int t = blockIdx.x + q * gridDim.x;
+    const int img = t / a.NB, band = t - img * a.NB;
+    const int plim = min(TR, a.Ho - band * TR) * Wo;  // pixels of the band that exist
+    bf16_t* dst = a.out + ((int64_t)img * a.Ho + (int64_t)band * TR) * Wo * Cout;
+    __builtin_amdgcn_s_barrier();  // band q is in LDS
+    const char* im = lds + (q % NBUF) * image_bytes;
+    for (int gi = wave; gi < ngroups; gi += NCW) {
+      const int p = gi * 32 + l32, pc = p < npix ? p : 0;
+      const int oyl = pc / Wo, ox = pc - oyl * Wo;
+      const char* pb = im + (2 * oyl) * RB + (2 * ox - 1) * C0 * 2;  // window corner (column -1 for ox = 0)
+      const bool cok[3] = {ox > 0, true, 2 * ox + 1 < W};
+      bf16x8_t av[KS];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        uint32_t x4[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          // the two halves' k are compile-time; pick by h
+          const int k0 = ks * 16 + j, k1 = ks * 16 + 8 + j;
+          const int t0 = k0 / C0, c0 = k0 - t0 * C0, u0 = t0 / 3, v0 = t0 - 3 * u0;
+          const int t1 = k1 / C0, c1 = k1 - t1 * C0, u1 = t1 / 3, v1 = t1 - 3 * u1;
+          const bool in0 = k0 < K, in1 = k1 < K;
+          const bool ok = h ? (in1 && cok[in1 ? v1 : 1]) : (in0 && cok[in0 ? v0 : 1]);
+          const int off = h ? (in1 ? u1 * RB + (v1 * C0 + c1) * 2 : 0) : (in0 ? u0 * RB + (v0 * C0 + c0) * 2 : 0);
+          const char* src = ok ? pb + off : zero16;
+          x4[j >> 1] |= (uint32_t)*reinterpret_cast<const unsigned short*>(src) << (16 * (j & 1));
+        }
+        av[ks] = __builtin_bit_cast(bf16x8_t, make_uint4(x4[0], x4[1], x4[2], x4[3]));
+      }
+#pragma unroll
+      for (int jn = 0; jn < 2; ++jn) {
+        if (jn < NJ) {
+          f32x16_t acc;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw[jn][ks], av[ks], acc, 0, 0, 0);
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int cl = jn * 32 + g * 8 + h * 4;
+            if (cl < Cout) {
+              uint2 o;
+              o.x = pack2bf(fmaxf(acc[g * 4] + bs[jn][g * 4], 0.f), fmaxf(acc[g * 4 + 1] + bs[jn][g * 4 + 1], 0.f));
+              o.y = pack2bf(fmaxf(acc[g * 4 + 2] + bs[jn][g * 4 + 2], 0.f), fmaxf(acc[g * 4 + 3] + bs[jn][g * 4 + 3], 0.f));
+              *reinterpret_cast<uint2*>(&stage[l32 * SP + cl]) = o;
+            }
+          }
+        }
+      }
+      // the group's 32 pixels are contiguous in the output: 16-byte segments, lane after lane
+      for (int ch = lane; ch < 32 * cpr; ch += 64) {
+        const int r = ch / cpr, cg = ch - r * cpr;
+        if (gi * 32 + r < plim)
+          *reinterpret_cast<uint4*>(dst + (int64_t)(gi * 32 + r) * Cout + cg * 8) = *reinterpret_cast<const uint4*>(&stage[r * SP + cg * 8]);
+      }
+    }
+  }
+}

@@ -8,8 +8,10 @@
 // accumulating the four pixels' CI/WGN columns in registers (64).  The weights, transposed per tap
 // to [ci][co], stay in registers for the whole kernel (144).
 //
-// Waves of a block (512 threads): four compute waves; two loader waves that copy dY bands
-// (TQ+1 rows) into a ring of three LDS images with LDS-writing loads; two finishing waves that,
+// Waves of a block (512 threads): two compute waves (two 32-quad groups each per tile); two loader
+// waves that copy dY bands (TQ+1 rows) into a ring of three LDS images with LDS-writing loads; four
+// finishing waves (masking and writing out is the longest per-tile job, and a wave sustains only
+// about one vector-memory instruction per 190 cycles) that,
 // one tile behind, apply the ReLU mask of the stored activation to the staged result and write it
 // out as 16-byte segments of the band (one contiguous span of the image).  The staging area is
 // double-buffered, so finishing tile q-1 overlaps computing tile q; two barriers per tile order the
@@ -20,7 +22,7 @@
 // its weight gradient G0[ci][k0] = sum over pixels of dXmasked[pixel][ci] * patch[pixel][k0] with
 // the pixel's 3x3 window of the C0-channel input image as patch (plus a constant 1 for the bias).
 // The loaders then also copy the band's input-image rows into an LDS ring; each finishing wave takes
-// half of the band's pixels: it writes the masked values back into the staging area instead of to
+// a quarter of the band's pixels: it writes the masked values back into the staging area instead of to
 // memory, builds the pixels' patch rows in LDS from the image rows, and contracts the two over its
 // pixels with transposing LDS reads and one MFMA per 16 pixels.  The input gradient of the first
 // layer's output therefore never reaches HBM.  Each block leaves one fp32 partial [CI][9*C0+1].
@@ -48,8 +50,8 @@ struct ConvDgradArgs {
 
 template <int CI>
 struct ConvDgradShape {
-  static constexpr int CO = 64, WGN = CI / 32, WGM = 4 / WGN, BQ = WGM * 32;  // quads per tile
-  static constexpr int NBUF = 3, THREADS = 512, MAXSEG = 6, MAXCH = 16;
+  static constexpr int CO = 64, WGN = CI / 32, MT = 2, WGM = 2 / WGN, BQ = WGM * MT * 32;  // quads per tile
+  static constexpr int NBUF = 3, THREADS = 512, MAXSEG = 6, MAXCH = 8, NFW = 4;  // chunks per finishing thread, finishing waves
   static int dyimg_bytes(int Wo, int TQ) { return (TQ + 1) * (Wo + 1) * 128; }
   static int stage_bytes(int W, int TQ) { return 2 * TQ * W * CI * 2; }
   static int lds_bytes(int W, int Wo, int TQ) { return NBUF * dyimg_bytes(Wo, TQ) + 2 * stage_bytes(W, TQ); }
@@ -57,7 +59,7 @@ struct ConvDgradShape {
   static int kp(int C0) { return 9 * C0 + 1 <= 16 ? 16 : 32; }
   static int img0_bytes(int W0, int C0, int TQ) { return (4 * TQ + 1) * W0 * C0 * 2; }
   static int fused_extra(int W, int W0, int C0, int TQ) {
-    return NBUF * img0_bytes(W0, C0, TQ) + 2 * (TQ * W) * kp(C0) * 2 + 16 + 2 * 32 * 32 * 4;
+    return NBUF * img0_bytes(W0, C0, TQ) + 2 * (TQ * W) * kp(C0) * 2 + 16 + NFW * 32 * 32 * 4;
   }
 };
 
@@ -88,10 +90,10 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
   // fused form
   constexpr int K0 = 9 * C0, KP = (K0 + 1 <= 16) ? 16 : 32;
   const int RB0 = a.W0 * C0 * 2, NR0 = 4 * TQ + 1, img0_bytes = NR0 * RB0;
-  const int half = TQ * W;  // pixels per finishing wave (a multiple of 16)
+  const int half = TQ * W / 2;  // pixels per finishing wave (a multiple of 16)
   char* const img0_ring = stage0 + 2 * stage_bytes;
   char* const patch0 = img0_ring + NBUF * img0_bytes;
-  char* const zero16 = patch0 + 2 * half * KP * 2;
+  char* const zero16 = patch0 + S::NFW * half * KP * 2;
   float* const red = reinterpret_cast<float*>(zero16 + 16);
   if (C0 > 0 && tid < 4) reinterpret_cast<uint32_t*>(zero16)[tid] = 0u;
   const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
@@ -102,9 +104,9 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     *reinterpret_cast<uint4*>(lds + row * RP + Wo * 128 + chunk * 16) = make_uint4(0u, 0u, 0u, 0u);
   }
 
-  if (wave == 4 || wave == 5) {
+  if (wave == 2 || wave == 3) {
     // ------------------------------------------------------------------ loaders: image row r belongs to loader r % 2
-    const int lw = wave - 4;
+    const int lw = wave - 2;
     const int rowbytes = Wo * 128, segs = (rowbytes + 1023) >> 10;
     const int segs0 = (RB0 + 1023) >> 10;
     const int ni = ((TQ + 1 - lw + 1) >> 1) * segs + (C0 > 0 ? ((NR0 - lw + 1) >> 1) * segs0 : 0);  // this wave's loads per band
@@ -157,15 +159,15 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     return;
   }
 
-  if (wave >= 6) {
+  if (wave >= 4) {
     // ------------------------------------------------------------------ finishing waves
-    // Unfused: the two waves share the band's chunks (thread et of 128 takes et, et+128, ...).
+    // Unfused: the four waves share the band's chunks (thread et of 256 takes et, et+256, ...).
     // Fused: wave fw owns the pixels [fw*half, (fw+1)*half) and their chunks.
-    const int et = tid - 384, fw = wave - 6;
+    const int et = tid - 256, fw = wave - 4;
     const int nchunk = stage_bytes >> 4;
     const int nchw = half * (CI / 8);  // chunks per finishing wave (fused)
-    auto chunk_of = [&](int i) -> int { return C0 > 0 ? fw * nchw + lane + 64 * i : et + 128 * i; };
-    auto chunk_mine = [&](int i) -> bool { return C0 > 0 ? lane + 64 * i < nchw : et + 128 * i < nchunk; };
+    auto chunk_of = [&](int i) -> int { return C0 > 0 ? fw * nchw + lane + 64 * i : et + 256 * i; };
+    auto chunk_mine = [&](int i) -> bool { return C0 > 0 ? lane + 64 * i < nchw : et + 256 * i < nchunk; };
     // two register sets: the mask of tile q+1 is fetched while tile q-1 is finished (two tiles of
     // mask bytes in flight per CU)
     uint4 mk[2][S::MAXCH];
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     };
 
     // ---- fused form: patch values of this lane's pixels, the patch table, the running sums
-    constexpr int PJ = 4, NV = K0 + 1, NREG = (NV + 1) / 2;
+    constexpr int PJ = 2, NV = K0 + 1, NREG = (NV + 1) / 2;
     uint32_t tp[PJ][NREG > 0 ? NREG : 1];
     int toff[PJ]; uint32_t tcol[PJ];
     f32x16_t accw;
@@ -319,7 +321,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
         float* P = a.partial0 + (int64_t)blockIdx.x * CI * NV;
         for (int i = lane; i < CI * NV; i += 64) {
           const int ci = i / NV, k = i - ci * NV;
-          P[i] = red[ci * 32 + k] + red[1024 + ci * 32 + k];
+          P[i] = (red[ci * 32 + k] + red[1024 + ci * 32 + k]) + (red[2048 + ci * 32 + k] + red[3072 + ci * 32 + k]);
         }
       }
     }
@@ -328,6 +330,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
 
   // -------------------------------------------------------------------- compute waves
   const int l32 = lane & 31, h = lane >> 5;
+  constexpr int MT = S::MT;
   const int wm = wave / WGN, wn = wave % WGN;
   // weights: lane (column ci = wn*32 + l32, 8 co at cc*16 + h*8) of tap s
   bf16x8_t wr[9][CC];
@@ -337,69 +340,67 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     for (int cc = 0; cc < CC; ++cc)
       wr[s][cc] = *reinterpret_cast<const bf16x8_t*>(a.wt + ((int64_t)s * CI + wn * 32 + l32) * CO + cc * 16 + h * 8);
 
-  // this lane's quad within a band (lanes beyond the band work on quad 0 and store nothing)
-  const int qi = wm * 32 + l32;
-  const bool in_band = qi < TQ * Wo;
-  const int al = in_band ? qi / Wo : 0, b = in_band ? qi - al * Wo : 0;
-  const uint32_t abase = (uint32_t)(al * RP + b * 128);
-  uint32_t hx[2];
-#pragma unroll
-  for (int dxo = 0; dxo < 2; ++dxo) hx[dxo] = (uint32_t)(h * 16) ^ dy_swz_bits((uint32_t)((b + dxo) * 128));
-  // staged position of the lane's four pixels (class c = py*2 + px), columns wn*32 + h*4 + g*8
-  uint32_t sp[4];
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const uint32_t L = (uint32_t)((((2 * al + (c >> 1)) * W + 2 * b + (c & 1)) * CI + wn * 32 + h * 4) * 2);
-    sp[c] = L ^ tile_swz_bits<CI>(L);
-  }
-  const bool col_ok[2] = {in_band, in_band && 2 * b + 1 < W};
-
   __builtin_amdgcn_s_barrier();
   for (int q = 0; q < nq; ++q) {
     const int t = blockIdx.x + q * gridDim.x;
     const int band = t % a.NB;
     __builtin_amdgcn_s_barrier();  // A(q): band q is in LDS, staging buffer q&1 is free
-    const char* img_s = lds + (q % NBUF) * dyimg_bytes + abase;
-    f32x16_t acc[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
-#pragma unroll
-    for (int dyo = 0; dyo < 2; ++dyo)
-#pragma unroll
-      for (int dxo = 0; dxo < 2; ++dxo)
-#pragma unroll
-        for (int cc = 0; cc < CC; ++cc) {
-          const bf16x8_t av = *reinterpret_cast<const bf16x8_t*>(img_s + dyo * RP + dxo * 128 + ((uint32_t)(cc * 32) ^ hx[dxo]));
-          // class (py, px) takes tap u = py ? (dyo ? 0 : 2) : 1 from row offset dyo (even rows only from dyo = 0), same for columns
-          if (dyo == 0 && dxo == 0) {
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 1][cc], av, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 2][cc], av, acc[1], 0, 0, 0);
-            acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 1][cc], av, acc[2], 0, 0, 0);
-            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 2][cc], av, acc[3], 0, 0, 0);
-          } else if (dyo == 0 && dxo == 1) {
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 0][cc], av, acc[1], 0, 0, 0);
-            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 0][cc], av, acc[3], 0, 0, 0);
-          } else if (dyo == 1 && dxo == 0) {
-            acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 1][cc], av, acc[2], 0, 0, 0);
-            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 2][cc], av, acc[3], 0, 0, 0);
-          } else {
-            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 0][cc], av, acc[3], 0, 0, 0);
-          }
-        }
-    // ---- stage: lane holds, per class, columns wn*32 + g*8 + h*4 + 0..3 of its pixel
     char* st = stage0 + (q & 1) * stage_bytes;
     const int rows_here = a.H - 2 * band * TQ;  // image rows left from the band's first row
+#pragma unroll 1
+    for (int mt = 0; mt < MT; ++mt) {
+      // this lane's quad of the group (lanes beyond the band work on quad 0 and store nothing);
+      // recomputed per tile: registers are scarcer here than ALU cycles
+      const int qi = (wm * MT + mt) * 32 + l32;
+      const bool in_band = qi < TQ * Wo;
+      const int al = in_band ? qi / Wo : 0, b = in_band ? qi - al * Wo : 0;
+      const char* img_s = lds + (q % NBUF) * dyimg_bytes + al * RP + b * 128;
+      uint32_t hx[2];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      if (col_ok[c & 1] && 2 * al + (c >> 1) < rows_here) {
+      for (int dxo = 0; dxo < 2; ++dxo) hx[dxo] = (uint32_t)(h * 16) ^ dy_swz_bits((uint32_t)((b + dxo) * 128));
+      f32x16_t acc[4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          uint2 o;
-          o.x = pack2bf(acc[c][g * 4], acc[c][g * 4 + 1]);
-          o.y = pack2bf(acc[c][g * 4 + 2], acc[c][g * 4 + 3]);
-          *reinterpret_cast<uint2*>(st + (sp[c] ^ (uint32_t)(g * 16))) = o;
+      for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
+#pragma unroll
+      for (int dyo = 0; dyo < 2; ++dyo)
+#pragma unroll
+        for (int dxo = 0; dxo < 2; ++dxo)
+#pragma unroll
+          for (int cc = 0; cc < CC; ++cc) {
+            const bf16x8_t av = *reinterpret_cast<const bf16x8_t*>(img_s + dyo * RP + dxo * 128 + ((uint32_t)(cc * 32) ^ hx[dxo]));
+            // class (py, px) takes tap u = py ? (dyo ? 0 : 2) : 1 from row offset dyo (even rows only from dyo = 0), same for columns
+            if (dyo == 0 && dxo == 0) {
+              acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 1][cc], av, acc[0], 0, 0, 0);
+              acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 2][cc], av, acc[1], 0, 0, 0);
+              acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 1][cc], av, acc[2], 0, 0, 0);
+              acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 2][cc], av, acc[3], 0, 0, 0);
+            } else if (dyo == 0 && dxo == 1) {
+              acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 0][cc], av, acc[1], 0, 0, 0);
+              acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 0][cc], av, acc[3], 0, 0, 0);
+            } else if (dyo == 1 && dxo == 0) {
+              acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 1][cc], av, acc[2], 0, 0, 0);
+              acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 2][cc], av, acc[3], 0, 0, 0);
+            } else {
+              acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 0][cc], av, acc[3], 0, 0, 0);
+            }
+          }
+      // ---- stage: lane holds, per class, columns wn*32 + g*8 + h*4 + 0..3 of its pixel
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bool col_ok = in_band && ((c & 1) == 0 || 2 * b + 1 < W);
+        if (col_ok && 2 * al + (c >> 1) < rows_here) {
+          // staged position of pixel class c = py*2 + px, columns wn*32 + h*4 + g*8
+          const uint32_t L = (uint32_t)((((2 * al + (c >> 1)) * W + 2 * b + (c & 1)) * CI + wn * 32 + h * 4) * 2);
+          const uint32_t sp = L ^ tile_swz_bits<CI>(L);
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            uint2 o;
+            o.x = pack2bf(acc[c][g * 4], acc[c][g * 4 + 1]);
+            o.y = pack2bf(acc[c][g * 4 + 2], acc[c][g * 4 + 3]);
+            *reinterpret_cast<uint2*>(st + (sp ^ (uint32_t)(g * 16))) = o;
+          }
         }
       }
     }

@@ -18,6 +18,7 @@
 #include "fused.hip.h"
 #include "conv_tile.hip.h"
 #include "conv_dgrad_tile.hip.h"
+#include "conv0_tile.hip.h"
 
 static_assert(sizeof(DevStats) == sizeof(ppo_mb_stats), "device and host statistics records must match");
 
@@ -479,8 +480,8 @@ int launch_conv_dgrad_tile_t(Ctx* c, ConvDgradArgs a, int nimg, const std::strin
   if (a.Wo > S::BQ) return 1;
   auto lds_of = [&](int tq) { return S::lds_bytes(a.W, a.Wo, tq) + (C0 > 0 ? S::fused_extra(a.W, a.W0, C0, tq) : 0); };
   auto fits = [&](int tq) {
-    if (S::stage_bytes(a.W, tq) > S::MAXCH * 128 * 16 || lds_of(tq) > 158 * 1024) return false;
-    if (C0 > 0 && ((tq * a.W) % 16 != 0 || tq * a.W > 256)) return false;  // pixels per finishing wave
+    if (S::stage_bytes(a.W, tq) > S::MAXCH * 256 * 16 || lds_of(tq) > 158 * 1024) return false;
+    if (C0 > 0 && ((tq * a.W) % 32 != 0 || tq * a.W / 2 > 128)) return false;  // pixels per finishing wave: a multiple of 16, two per lane
     return true;
   };
   int TQ = S::BQ / a.Wo < a.Ho ? S::BQ / a.Wo : a.Ho;
@@ -537,6 +538,26 @@ int launch_conv_dgrad_wgrad0_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, 
   return launch_conv_dgrad_tile_t<32, 1>(c, a, nimg, name, flops, abytes, grid_out);
 }
 
+// First convolution forward through the LDS-ring kernel; returns 1 when the shape is not covered.
+template <int C0>
+int launch_conv0_fwd_tile_t(Ctx* c, Conv0Args a, int nimg) {
+  typedef Conv0Shape<C0> S;
+  const int rb = a.W * C0 * 2, segs = cdiv(rb, 1024);
+  if (rb % 16 || ((int64_t)a.H * rb) % 16 || segs > S::MAXSEG || a.Cout % 8 || a.Cout > 64) return 1;
+  int TR = 0;
+  for (int tr = a.Ho; tr >= 1; --tr)
+    if ((2 * tr + 1) * segs <= 63 && tr * a.Wo <= 1024 && S::lds_bytes(a.W, tr, a.Cout) <= 64 * 1024) { TR = tr; break; }
+  if (TR == 0) return 1;
+  a.NB = cdiv(a.Ho, TR); a.TR = cdiv(a.Ho, a.NB); a.ntiles = nimg * a.NB;
+  int gx = a.ntiles < 512 ? a.ntiles : 512;
+  auto kfn = k_conv0_fwd_tile<C0>;
+  static bool attr_set = false;
+  if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024)); attr_set = true; }
+  hipLaunchKernelGGL(kfn, dim3(gx), dim3(S::THREADS), S::lds_bytes(a.W, a.TR, a.Cout), c->stream, a);
+  LAUNCHCHK(c, "k_conv0_fwd_tile");
+  return PPO_OK;
+}
+
 // Forward of `n` samples selected by device indices idx (NULL = 0..n-1 offset by `first`).
 int forward_chunk(Ctx* c, const int32_t* idx, int n) {
   const int V = c->V, nimg = n * V;
@@ -547,7 +568,13 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n) {
     ProfScope ps(c, "conv_fwd.0", 2.0 * (double)M * Co * 9 * c->cC[0], 2.0 * ((double)nimg * c->img_elems + (double)M * Co));
     constexpr int TPW = 4;
     const int grid = cdiv(M, 32 * 4 * TPW);
-    if (c->cC[0] == 1)
+    Conv0Args ca;
+    ca.in = in; ca.in.prepare(); ca.out = c->act[0]; ca.w = c->shadow + c->convW[0]; ca.bias = c->p + c->convB[0]; ca.zpage = c->zpage;
+    ca.H = c->cH[0]; ca.W = c->cW[0]; ca.Ho = Ho; ca.Wo = Wo; ca.Cout = Co; ca.TR = 0; ca.NB = 0; ca.ntiles = 0;
+    int trc = c->cC[0] == 1 ? launch_conv0_fwd_tile_t<1>(c, ca, nimg) : (c->cC[0] == 3 ? launch_conv0_fwd_tile_t<3>(c, ca, nimg) : 1);
+    if (trc != PPO_OK && trc != 1) return trc;
+    if (trc == PPO_OK) {}
+    else if (c->cC[0] == 1)
       hipLaunchKernelGGL((k_conv1_fwd<1, TPW>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->shadow + c->convW[0], c->p + c->convB[0], c->act[0]);
     else
       hipLaunchKernelGGL((k_conv1_fwd<3, TPW>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->shadow + c->convW[0], c->p + c->convB[0], c->act[0]);
