@@ -31,6 +31,20 @@ PEAK_FP32_VALU_TF = 157.3   # fp32 vector, published
 
 RIDGE_FLOP_PER_BYTE = PEAK_MFMA_BF16_TF * 1e12 / (PEAK_HBM_GBS * 1e9)  # 312.5
 
+# HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE and WRITE_SIZE in two runs of this
+# script, each scaled by what the same counter reads for the plain copy kernel of ppo_buffer_write in the
+# same run: x1.987 and x1.000).  The runs, the raw counter values and the commands are in
+# profiles/c1_medium_hbm_traffic.md; a kernel class or workload that was not measured reports null.
+MEASURED_TRAFFIC_BYTES = {
+    ("c1_medium", "conv_dgrad.1+wgrad.0"): 452.3e6,
+    ("c1_medium", "conv_wgrad.1"): 444.4e6,
+    ("c1_medium", "conv_fwd.0"): 302.6e6,
+    ("c1_medium", "conv_fwd.1"): 409.8e6,
+    ("c1_medium", "conv_dgrad.2"): 301.9e6,
+    ("c1_medium", "conv_wgrad.2"): 204.9e6,
+    ("c1_medium", "conv_fwd.2"): 167.7e6,
+}
+
 
 def kernel_bound(rec: dict) -> str:
     """Roofline side of a kernel class: its algorithmic intensity (booked FLOPs / booked bytes) against the
@@ -125,7 +139,9 @@ def main():
     else:
         ach, peak, unit = r["bytes"] / r["launches"] / avg_s / 1e9, PEAK_HBM_GBS, "GB/s"
     roofline = dict(bound=kernel_bound(r), kernel=dom, intensity_flop_per_byte=round(r["flops"] / max(r["bytes"], 1.0), 1), achieved=round(ach, 3), peak=peak, unit=unit,
-                    frac=round(ach / peak, 5), traffic=None, avg_launch_us=round(avg_s * 1e6, 2),
+                    frac=round(ach / peak, 5),
+                    traffic=MEASURED_TRAFFIC_BYTES.get((cfg["name"], dom)) if args.num_envs is None else None,
+                    algorithmic_bytes_per_launch=round(r["bytes"] / r["launches"], 1), avg_launch_us=round(avg_s * 1e6, 2),
                     launches_per_step=r["launches"] / args.steps, share_of_kernel_time=round(r["ms"] / tot_ms, 4))
     step_flops = fl["fwd_bwd"] * S * hp["epochs"]
     if args.profile_table:
