@@ -2,8 +2,8 @@
 // forward.  The layer writes eight to thirty times more bytes than it reads, and its 3x3 windows
 // are nine 2-byte elements per pixel: fetched from global memory they cost nine load instructions
 // per 32 pixels, and the vector-memory instruction rate of a wave, not bandwidth, sets the pace.
-// Here one loader wave copies each band's image rows (a few KiB) into an LDS ring with
-// LDS-writing 16-byte loads, seven compute waves take the band's pixels in groups of 32 (lane =
+// Here one loader wave copies each band's image rows (a few KiB, 1 KiB per load) into an LDS ring
+// with LDS-writing 16-byte loads, seven compute waves take the band's pixels in groups of 32 (lane =
 // pixel), gather the window from LDS with 2-byte reads, apply the weights with one or two MFMAs
 // (K = 9*C0 padded to 16 or 32), add bias, clamp, round to bf16, stage the 32 pixels in a private
 // LDS strip and write them as 16-byte segments of the band's contiguous output span.  The images
@@ -45,20 +45,19 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
 
   if (wave == 7) {
     // ------------------------------------------------------------------ loader
-    const int segs = (RB + 1023) >> 10, ni = nrows * segs;
+    // the band's rows follow each other in memory and in LDS: 1 KiB per load whatever the row length
+    const int ni = (image_bytes + 1023) >> 10;
     auto issue = [&](int q) {
       const int t = blockIdx.x + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int iy_lo = 2 * band * TR - 1;
       const char* src = reinterpret_cast<const char*>(a.in.ptr(img)) + (int64_t)iy_lo * RB;
       char* dst = lds + (q % NBUF) * image_bytes;
-      for (int row = 0; row < nrows; ++row) {
-        const bool inside = iy_lo + row >= 0 && iy_lo + row < a.H;
-        for (int sg = 0; sg < segs; ++sg) {
-          const int o = sg * 1024 + lane * 16;
-          const char* p = inside ? src + (int64_t)row * RB + o : reinterpret_cast<const char*>(a.zpage) + lane * 16;
-          if (o < RB) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + row * RB + sg * 1024), 16, 0, 0);
-        }
+      for (int j = 0; j < ni; ++j) {
+        const int o = j * 1024 + lane * 16, iy = iy_lo + o / RB;
+        const bool inside = iy >= 0 && iy < a.H;
+        const char* p = inside ? src + o : reinterpret_cast<const char*>(a.zpage) + lane * 16;
+        if (o < image_bytes) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + j * 1024), 16, 0, 0);
       }
     };
     if (nq > 0) issue(0);

@@ -59,7 +59,8 @@ struct ConvDgradShape {
   static int kp(int C0) { return 9 * C0 + 1 <= 16 ? 16 : 32; }
   static int img0_bytes(int W0, int C0, int TQ) { return (4 * TQ + 1) * W0 * C0 * 2; }
   static int fused_extra(int W, int W0, int C0, int TQ) {
-    return NBUF * img0_bytes(W0, C0, TQ) + 2 * (TQ * W) * kp(C0) * 2 + 16 + NFW * 32 * 32 * 4;
+    const int patch = 2 * (TQ * W) * kp(C0) * 2, red = NFW * 32 * 32 * 4;  // the final sums reuse the patch tables
+    return NBUF * img0_bytes(W0, C0, TQ) + (patch > red ? patch : red) + 16;
   }
 };
 
@@ -93,8 +94,9 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
   const int half = TQ * W / 2;  // pixels per finishing wave (a multiple of 16)
   char* const img0_ring = stage0 + 2 * stage_bytes;
   char* const patch0 = img0_ring + NBUF * img0_bytes;
-  char* const zero16 = patch0 + S::NFW * half * KP * 2;
-  float* const red = reinterpret_cast<float*>(zero16 + 16);
+  const int patch_bytes = S::NFW * half * KP * 2, red_bytes = S::NFW * 32 * 32 * 4;
+  char* const zero16 = patch0 + (patch_bytes > red_bytes ? patch_bytes : red_bytes);
+  float* const red = reinterpret_cast<float*>(patch0);  // used after the last tile only
   if (C0 > 0 && tid < 4) reinterpret_cast<uint32_t*>(zero16)[tid] = 0u;
   const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
 
@@ -108,8 +110,8 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     // ------------------------------------------------------------------ loaders: image row r belongs to loader r % 2
     const int lw = wave - 2;
     const int rowbytes = Wo * 128, segs = (rowbytes + 1023) >> 10;
-    const int segs0 = (RB0 + 1023) >> 10;
-    const int ni = ((TQ + 1 - lw + 1) >> 1) * segs + (C0 > 0 ? ((NR0 - lw + 1) >> 1) * segs0 : 0);  // this wave's loads per band
+    const int nld0 = (img0_bytes + 1023) >> 10;  // the image rows are one contiguous span: 1 KiB pieces
+    const int ni = ((TQ + 1 - lw + 1) >> 1) * segs + (C0 > 0 ? ((nld0 - lw + 1) >> 1) : 0);  // this wave's loads per band
     int goff[S::MAXSEG];
 #pragma unroll
     for (int sg = 0; sg < S::MAXSEG; ++sg) {
@@ -132,17 +134,16 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
           }
       }
       if constexpr (C0 > 0) {
-        // input-image rows 4*band*TQ - 1 ... + 4*TQ, as they are (rows outside the image: zeros)
+        // input-image rows 4*band*TQ - 1 ... + 4*TQ, as they are (rows outside the image: zeros); the rows
+        // follow each other in memory and in LDS, so one load moves 1 KiB of them
         const int iy0 = 4 * band * TQ - 1;
         const char* isrc = reinterpret_cast<const char*>(a.img0.ptr(img)) + (int64_t)iy0 * RB0;
         char* idst = img0_ring + (q % NBUF) * img0_bytes;
-        for (int row = lw; row < NR0; row += 2) {
-          const bool inside = iy0 + row >= 0 && iy0 + row < a.H0;
-          for (int sg = 0; sg < segs0; ++sg) {
-            const int o = sg * 1024 + lane * 16;
-            const char* p = inside ? isrc + (int64_t)row * RB0 + o : reinterpret_cast<const char*>(a.zpage) + lane * 16;
-            if (o < RB0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(idst + row * RB0 + sg * 1024), 16, 0, 0);
-          }
+        for (int j = lw; j < nld0; j += 2) {
+          const int o = j * 1024 + lane * 16, iy = iy0 + o / RB0;
+          const bool inside = iy >= 0 && iy < a.H0;
+          const char* p = inside ? isrc + o : reinterpret_cast<const char*>(a.zpage) + lane * 16;
+          if (o < img0_bytes) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(idst + j * 1024), 16, 0, 0);
         }
       }
     };
@@ -156,6 +157,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       __builtin_amdgcn_s_barrier();      // B(q)
     }
     __builtin_amdgcn_s_barrier();        // C
+    __builtin_amdgcn_s_barrier();        // D
     return;
   }
 
@@ -310,12 +312,13 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       if (q + 1 < nq) step(q + 1, set1());
     }
     if (nq > 0) { if ((nq - 1) & 1) finish(nq - 1, set1()); else finish(nq - 1, set0()); }
+    __builtin_amdgcn_s_barrier();    // C: every finishing wave is done with its patch table
     if constexpr (C0 > 0) {
       // accw[e] = G0[ci][k0] with k0 = lane % 32, ci = (e/4)*8 + (lane/32)*4 + e%4
 #pragma unroll
       for (int e = 0; e < 16; ++e) red[fw * 1024 + ((e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)) * 32 + (lane & 31)] = accw[e];
     }
-    __builtin_amdgcn_s_barrier();    // C
+    __builtin_amdgcn_s_barrier();    // D
     if constexpr (C0 > 0) {
       if (fw == 0) {
         float* P = a.partial0 + (int64_t)blockIdx.x * CI * NV;
@@ -407,4 +410,5 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     __builtin_amdgcn_s_barrier();  // B(q)
   }
   __builtin_amdgcn_s_barrier();    // C
+  __builtin_amdgcn_s_barrier();    // D
 }

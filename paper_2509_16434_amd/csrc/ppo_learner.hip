@@ -495,7 +495,7 @@ int launch_conv_dgrad_tile_t(Ctx* c, ConvDgradArgs a, int nimg, const std::strin
   if (C0 > 0) {
     const int rb0 = a.W0 * C0 * 2;
     if (rb0 % 16) return 1;
-    ni += cdiv(4 * a.TQ + 1, 2) * cdiv(rb0, 1024);
+    ni += cdiv(cdiv((4 * a.TQ + 1) * rb0, 1024), 2);
   }
   if (segs > S::MAXSEG || ni > 63) return 1;
   int gx = a.ntiles < 256 ? a.ntiles : 256;
@@ -542,11 +542,11 @@ int launch_conv_dgrad_wgrad0_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, 
 template <int C0>
 int launch_conv0_fwd_tile_t(Ctx* c, Conv0Args a, int nimg) {
   typedef Conv0Shape<C0> S;
-  const int rb = a.W * C0 * 2, segs = cdiv(rb, 1024);
-  if (rb % 16 || ((int64_t)a.H * rb) % 16 || segs > S::MAXSEG || a.Cout % 8 || a.Cout > 64) return 1;
+  const int rb = a.W * C0 * 2;
+  if (rb % 16 || ((int64_t)a.H * rb) % 16 || a.Cout % 8 || a.Cout > 64) return 1;
   int TR = 0;
   for (int tr = a.Ho; tr >= 1; --tr)
-    if ((2 * tr + 1) * segs <= 63 && tr * a.Wo <= 1024 && S::lds_bytes(a.W, tr, a.Cout) <= 64 * 1024) { TR = tr; break; }
+    if (cdiv((2 * tr + 1) * rb, 1024) <= 63 && tr * a.Wo <= 1024 && S::lds_bytes(a.W, tr, a.Cout) <= 64 * 1024) { TR = tr; break; }
   if (TR == 0) return 1;
   a.NB = cdiv(a.Ho, TR); a.TR = cdiv(a.Ho, a.NB); a.ntiles = nimg * a.NB;
   int gx = a.ntiles < 512 ? a.ntiles : 512;
