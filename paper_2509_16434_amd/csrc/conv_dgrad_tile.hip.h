@@ -118,7 +118,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       const uint32_t phys = sg * 1024 + lane * 16, logi = phys ^ dy_swz_bits(phys);
       goff[sg] = (sg < segs && (int)phys < rowbytes) ? (int)logi : -1;
     }
-    auto issue = [&](int q) {
+    auto issue = [&](int q) __attribute__((always_inline)) {
       const int t = blockIdx.x + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int oy_lo = band * TQ;
@@ -172,10 +172,12 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     auto chunk_mine = [&](int i) -> bool { return C0 > 0 ? lane + 64 * i < nchw : et + 256 * i < nchunk; };
     // two register sets: the mask of tile q+1 is fetched while tile q-1 is finished (two tiles of
     // mask bytes in flight per CU)
-    uint4 mk[2][S::MAXCH];
+    // (the RGB fused form needs the registers for its 27-tap patches and keeps one set: one tile ahead)
+    constexpr int NSET = (C0 == 3) ? 1 : 2;
+    uint4 mk[NSET][S::MAXCH];
     int64_t band_off[2] = {0, 0};  // element offset of the set's band within dx / x
     int nvalid[2] = {0, 0};        // its chunks that lie inside the image
-    auto load_mask = [&](int q, auto setc) {
+    auto load_mask = [&](int q, auto setc) __attribute__((always_inline)) {
       constexpr int SET = decltype(setc)::value;
       const int t = blockIdx.x + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
@@ -211,7 +213,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
         tcol[j] = (ix > 0 ? 1u : 0u) | 2u | (2 * ix + 1 < a.W0 ? 4u : 0u);   // window columns inside the image
       }
     }
-    auto load_taps = [&](int q) {  // from the image rows of tile q (in LDS since A(q)) into registers
+    auto load_taps = [&](int q) __attribute__((always_inline)) {  // from the image rows of tile q (in LDS since A(q)) into registers
       if constexpr (C0 > 0) {
         const char* im = img0_ring + (q % NBUF) * img0_bytes;
 #pragma unroll
@@ -220,24 +222,20 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
           for (int r = 0; r < NREG; ++r) tp[j][r] = 0u;
           if (lane + 64 * j < half) {
 #pragma unroll
-            for (int u = 0; u < 3; ++u)
-#pragma unroll
-              for (int v = 0; v < 3; ++v)
-#pragma unroll
-                for (int cch = 0; cch < C0; ++cch) {
-                  const int k = (u * 3 + v) * C0 + cch;
-                  // columns outside the image read the zero chunk (no branch around the load)
-                  const char* src = ((tcol[j] >> v) & 1u) ? im + toff[j] + u * RB0 + (v * C0 + cch) * 2 : zero16;
-                  const uint32_t x = (uint32_t)*reinterpret_cast<const unsigned short*>(src);
-                  tp[j][k >> 1] |= x << (16 * (k & 1));
-                }
+            for (int k = 0; k < K0; ++k) {
+              const int tap = k / C0, cch = k - tap * C0, u = tap / 3, v = tap - 3 * u;
+              // columns outside the image read the zero chunk (no branch around the load)
+              const char* src = ((tcol[j] >> v) & 1u) ? im + toff[j] + u * RB0 + (v * C0 + cch) * 2 : zero16;
+              const uint32_t x = (uint32_t)*reinterpret_cast<const unsigned short*>(src);
+              tp[j][k >> 1] |= x << (16 * (k & 1));
+            }
             tp[j][K0 >> 1] |= 0x3F80u << (16 * (K0 & 1));  // the bias column: 1.0
           }
         }
       }
     };
 
-    auto finish = [&](int q, auto setc) {  // tile q was loaded into set q & 1
+    auto finish = [&](int q, auto setc) __attribute__((always_inline)) {  // tile q was loaded into set q & 1
       constexpr int SET = decltype(setc)::value;
       char* st = stage0 + (q & 1) * stage_bytes;
       // One wait for everything outstanding (this set's mask, fetched two tiles ago, and the younger
@@ -263,12 +261,13 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
         for (int j = 0; j < PJ; ++j) {
           const int pj = lane + 64 * j;
           if (pj < half) {
-            uint32_t row[KP / 2];
 #pragma unroll
-            for (int r = 0; r < KP / 2; ++r) row[r] = r < NREG ? tp[j][r] : 0u;
+            for (int r = 0; r < KP / 8; ++r) {
+              uint32_t w4[4];
 #pragma unroll
-            for (int r = 0; r < KP / 8; ++r)
-              *reinterpret_cast<uint4*>(patch_w + pj * KP * 2 + r * 16) = make_uint4(row[4 * r], row[4 * r + 1], row[4 * r + 2], row[4 * r + 3]);
+              for (int e = 0; e < 4; ++e) w4[e] = (4 * r + e < NREG) ? tp[j][(4 * r + e < NREG) ? 4 * r + e : 0] : 0u;
+              *reinterpret_cast<uint4*>(patch_w + pj * KP * 2 + r * 16) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+            }
           }
         }
         // G0[ci][k0] += sum over this wave's pixels: both operands through transposing reads
@@ -293,25 +292,35 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     };
     typedef std::integral_constant<int, 0> set0;
     typedef std::integral_constant<int, 1> set1;
-    auto step = [&](int q, auto par) {  // q & 1 == par
+    auto step = [&](int q, auto par) __attribute__((always_inline)) {  // q & 1 == par
       constexpr int P = decltype(par)::value;
       typedef std::integral_constant<int, 1 - P> other;
       __builtin_amdgcn_s_barrier();  // A(q)
-      if (q > 0) {
-        finish(q - 1, other());
-        if (q + 1 < nq) load_mask(q + 1, other());
+      if constexpr (NSET == 2) {
+        if (q > 0) {
+          finish(q - 1, other());
+          if (q + 1 < nq) load_mask(q + 1, other());
+        }
+      } else {
+        if (q > 0) finish(q - 1, set0());
+        load_mask(q, set0());
       }
       load_taps(q);
       __builtin_amdgcn_s_barrier();  // B(q): tile q is staged
     };
-    if (nq > 0) load_mask(0, set0());
-    if (nq > 1) load_mask(1, set1());
+    if constexpr (NSET == 2) {
+      if (nq > 0) load_mask(0, set0());
+      if (nq > 1) load_mask(1, set1());
+    }
     __builtin_amdgcn_s_barrier();
     for (int q = 0; q < nq; q += 2) {
       step(q, set0());
       if (q + 1 < nq) step(q + 1, set1());
     }
-    if (nq > 0) { if ((nq - 1) & 1) finish(nq - 1, set1()); else finish(nq - 1, set0()); }
+    if (nq > 0) {
+      if constexpr (NSET == 2) { if ((nq - 1) & 1) finish(nq - 1, set1()); else finish(nq - 1, set0()); }
+      else finish(nq - 1, set0());
+    }
     __builtin_amdgcn_s_barrier();    // C: every finishing wave is done with its patch table
     if constexpr (C0 > 0) {
       // accw[e] = G0[ci][k0] with k0 = lane % 32, ci = (e/4)*8 + (lane/32)*4 + e%4

@@ -226,7 +226,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
 // pixel r/4, lane i receives channel i of 4 pixels), the im2col being the per-lane pixel address.
 // Compute wave w owns the 32-wide k-tiles w, w+4, ... of both 32-row n-tiles; the accumulators live
 // in registers across all tiles of the block and leave once, as this block's fp32 partial
-// [Cout][9*CIN] (partials are summed in a fixed order by the caller).  Wave 3 also accumulates the
+// [9*CIN][Cout] (partials are summed in a fixed order by the caller).  Wave 3 also accumulates the
 // column sums of dY (the bias gradient) with an all-ones operand.
 // dY pixels are 128 bytes apart; bit 6 of the offset is flipped for every second pixel pair so that
 // the four pixels of one transposing read fall into different banks.
@@ -234,7 +234,7 @@ struct ConvWgradArgs {
   ImgAddr in;                 // layer input X, images [H][W][CIN], dense
   ImgAddr dy;                 // gradient of the layer output, images [Ho][Wo][Cout]
   const bf16_t* zpage;        // 1 KiB of zeros
-  float* partial;             // [gridDim.x][Cout][9*CIN]
+  float* partial;             // [gridDim.x][9*CIN][Cout]
   float* bias_partial;        // [gridDim.x][Cout]
   int H, W, Ho, Wo, Cout;
   int TR, NB, ntiles, nstep;  // output rows per band, bands per image, nimg * NB, ceil(TR*Wo / 16)
@@ -243,7 +243,7 @@ struct ConvWgradArgs {
 template <int CIN>
 struct ConvWgradShape {
   static constexpr int PIX = CIN * 2, KT = 9 * CIN / 32, KTW = (KT + 3) / 4;
-  static constexpr int MAXSEG = 6, MAXSTEP = (CIN == 32) ? 5 : 4, NBUF = 3, THREADS = 512;
+  static constexpr int MAXSEG = 6, MAXSTEP = (CIN == 32) ? 8 : 4, NBUF = 3, THREADS = 512;
   static_assert(3 + 4 * (KTW - 1) >= KT, "wave 3's last accumulator pair must be free for the bias sums");
   static int image_bytes(int W, int TR) { return (2 * TR + 1) * (W + 2) * PIX; }
   static int buf_bytes(int W, int TR, int nstep) { return image_bytes(W, TR) + nstep * 16 * 128; }
@@ -389,7 +389,9 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
       }
     }
   }
-  // ---- this block's partial sums: acc[t][i][e] = G[n][k], k = (wave+4t)*32 + lane%32, n = nb0 + i*32 + (e/4)*8 + (lane/32)*4 + e%4
+  // ---- this block's partial sums: acc[t][i][e] = G[n][k], k = (wave+4t)*32 + lane%32, n = nb0 + i*32 + (e/4)*8 + (lane/32)*4 + e%4.
+  // The partial is stored k-major ([9*CIN][Cout]) so that a lane's four consecutive n leave as one 16-byte store
+  // (a quarter of the store instructions; the reduction kernel transposes back).
   const int K = 9 * CIN;
   float* P = a.partial + (int64_t)blockIdx.x * a.Cout * K;
 #pragma unroll
@@ -399,9 +401,10 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int n = nb0 + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-          if (n < a.Cout) P[(int64_t)n * K + k] = acc[t][i][e];
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int n = nb0 + i * 32 + g4 * 8 + (lane >> 5) * 4;
+          if (n < a.Cout)  // Cout is a multiple of 8
+            *reinterpret_cast<float4*>(P + (int64_t)k * a.Cout + n) = make_float4(acc[t][i][g4 * 4], acc[t][i][g4 * 4 + 1], acc[t][i][g4 * 4 + 2], acc[t][i][g4 * 4 + 3]);
         }
     }
   }

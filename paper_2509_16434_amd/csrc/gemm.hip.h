@@ -553,6 +553,28 @@ __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int
   }
 }
 
+// The same for partials stored transposed: dst[n*K + k] (+)= sum_s partial[s][k*N + n].
+__global__ __launch_bounds__(256) void k_reduce_partials_t(const float* __restrict__ partial, int splits, int N, int K,
+                                                           float* __restrict__ dst, int accumulate) {
+  __shared__ float red[8][33];
+  const int o = threadIdx.x & 31, sl = threadIdx.x >> 5;
+  const int64_t n_all = (int64_t)N * K, i = (int64_t)blockIdx.x * 32 + o;
+  float s0 = 0.f, s1 = 0.f;
+  if (i < n_all) {
+    int k = sl;
+    for (; k + 8 < splits; k += 16) { s0 += partial[(int64_t)k * n_all + i]; s1 += partial[(int64_t)(k + 8) * n_all + i]; }
+    if (k < splits) s0 += partial[(int64_t)k * n_all + i];
+  }
+  red[sl][o] = s0 + s1;
+  __syncthreads();
+  if (sl == 0 && i < n_all) {
+    const float s = ((red[0][o] + red[1][o]) + (red[2][o] + red[3][o])) + ((red[4][o] + red[5][o]) + (red[6][o] + red[7][o]));
+    const int kk = (int)(i / N), n = (int)(i - (int64_t)kk * N);
+    float* d = dst + (int64_t)n * K + kk;
+    *d = accumulate ? *d + s : s;
+  }
+}
+
 // dst[i] = (accumulate ? dst[i] : 0) + sum_s partial[s][i].  A block covers 32 outputs with 8
 // lanes of splits each (lane j sums s = j, j+8, ... with two running sums); the 8 lane sums are
 // combined in a fixed order, so the result does not depend on scheduling.

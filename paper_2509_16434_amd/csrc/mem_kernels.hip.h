@@ -406,7 +406,12 @@ __global__ __launch_bounds__(256) void k_ppo_loss(int B, int Bfull, int A, const
   const float invB = 1.f / (float)Bfull;
   if (ok) {
     const int64_t s = idx[b];
-    const float* o = out + (int64_t)b * HEAD_LD;
+    float o[HEAD_LD];  // the head's output row: eight 16-byte loads
+#pragma unroll
+    for (int q = 0; q < HEAD_LD / 4; ++q) {
+      const float4 v4 = *reinterpret_cast<const float4*>(out + (int64_t)b * HEAD_LD + 4 * q);
+      o[4 * q] = v4.x; o[4 * q + 1] = v4.y; o[4 * q + 2] = v4.z; o[4 * q + 3] = v4.w;
+    }
     float logp = 0.f;
 #pragma unroll
     for (int j = 0; j < 32; ++j) {
@@ -422,21 +427,30 @@ __global__ __launch_bounds__(256) void k_ppo_loss(int B, int Bfull, int A, const
     dlogp = (s1 <= s2) ? -invB * a * rho : 0.f;
     st[2] = (rho - 1.f) - lr;
     st[3] = fabsf(rho - 1.f) > clip_eps ? 1.f : 0.f;
-    const float v = o[A], r = ret[s], err = v - r;
+    float v = 0.f;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) v = (j == A) ? o[j] : v;  // the value head's column (register array: no dynamic index)
+    const float r = ret[s], err = v - r;
     float dv;
     if (vclip_eps > 0.f) {
       const float d = v - v_old[s], dc = fminf(fmaxf(d, -vclip_eps), vclip_eps), errc = v_old[s] + dc - r;
       if (errc * errc > err * err) { st[1] = errc * errc; dv = (d >= -vclip_eps && d <= vclip_eps) ? 2.f * errc : 0.f; }
       else { st[1] = err * err; dv = 2.f * err; }
     } else { st[1] = err * err; dv = 2.f * err; }
-    bf16_t* d = dout + (int64_t)b * HEAD_LD;
+    // the row of 32 bf16 leaves as four 16-byte stores
+    uint32_t pk[16];
 #pragma unroll
-    for (int j = 0; j < 32; ++j) {
-      float g = 0.f;
-      if (j < A) g = dlogp * z[j] * sig_inv[j];
-      else if (j == A) g = vf_coef * invB * dv;
-      d[j] = f2bf(g);
+    for (int j = 0; j < 32; j += 2) {
+      float g0 = 0.f, g1 = 0.f;
+      if (j < A) g0 = dlogp * z[j] * sig_inv[j];
+      else if (j == A) g0 = vf_coef * invB * dv;
+      if (j + 1 < A) g1 = dlogp * z[j + 1] * sig_inv[j + 1];
+      else if (j + 1 == A) g1 = vf_coef * invB * dv;
+      pk[j >> 1] = pack2bf(g0, g1);
     }
+    uint4* d = reinterpret_cast<uint4*>(dout + (int64_t)b * HEAD_LD);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) d[q] = make_uint4(pk[4 * q], pk[4 * q + 1], pk[4 * q + 2], pk[4 * q + 3]);
   }
   // block reductions in a fixed order: xor-butterfly inside each wave, then the four wave sums
   __shared__ float wred[4][36];

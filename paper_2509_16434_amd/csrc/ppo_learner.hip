@@ -453,7 +453,7 @@ int launch_conv_wgrad_tile_t(Ctx* c, ConvWgradArgs a, float* gw, float* gb, bool
     LAUNCHCHK(c, "k_conv_wgrad_tile");
   }
   ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)gx + 1.0) * (double)per);
-  hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 32)), dim3(256), 0, c->stream, c->partial, gx, per, gw, accumulate ? 1 : 0);
+  hipLaunchKernelGGL(k_reduce_partials_t, dim3(cdiv(per, 32)), dim3(256), 0, c->stream, c->partial, gx, a.Cout, K, gw, accumulate ? 1 : 0);
   if (gb) hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(a.Cout, 32)), dim3(256), 0, c->stream, c->bias_partial, gx, (int64_t)a.Cout, gb, accumulate ? 1 : 0);
   LAUNCHCHK(c, "k_reduce_partials");
   return PPO_OK;
@@ -529,13 +529,14 @@ int launch_conv_dgrad_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, bf16_t*
   return Ci == 32 ? launch_conv_dgrad_tile_t<32, 0>(c, a, nimg, name, flops, abytes, nullptr)
                   : launch_conv_dgrad_tile_t<64, 0>(c, a, nimg, name, flops, abytes, nullptr);
 }
-// The same with the first layer's weight gradient fused in (depth input, 32 channels after the first layer).
+// The same with the first layer's weight gradient fused in (depth or RGB input, 32 channels after the first layer).
 int launch_conv_dgrad_wgrad0_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, const bf16_t* wt, int Co, int Ci, int H, int W, int Ho, int Wo,
                                   const ImgAddr& img0, int C0, int H0, int W0, int nimg, const std::string& name, double flops, double abytes, int* grid_out) {
-  if (Co != 64 || Ci != 32 || C0 != 1 || dy.idx || nimg < 1) return 1;
+  if (Co != 64 || Ci != 32 || (C0 != 1 && C0 != 3) || dy.idx || nimg < 1) return 1;
   ConvDgradArgs a = conv_dgrad_args(c, dy, xa, nullptr, wt, H, W, Ho, Wo);
   a.img0 = img0; a.img0.prepare(); a.H0 = H0; a.W0 = W0;
-  return launch_conv_dgrad_tile_t<32, 1>(c, a, nimg, name, flops, abytes, grid_out);
+  return C0 == 1 ? launch_conv_dgrad_tile_t<32, 1>(c, a, nimg, name, flops, abytes, grid_out)
+                 : launch_conv_dgrad_tile_t<32, 3>(c, a, nimg, name, flops, abytes, grid_out);
 }
 
 // First convolution forward through the LDS-ring kernel; returns 1 when the shape is not covered.
