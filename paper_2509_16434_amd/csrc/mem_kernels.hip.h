@@ -32,6 +32,30 @@ __global__ void k_write_obs(const InT* __restrict__ src, bf16_t* __restrict__ ds
     }
     return;
   }
+  if (C == 3 && p0 + 8 <= HW && (HW & 7) == 0) {
+    // planar RGB -> interleaved: three 8-pixel runs in (16 or 32 bytes each), 24 bf16 = three 16-byte stores out
+    bf16_t in[3][8];
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+      if constexpr (sizeof(InT) == 4) {
+        const float4* s4 = reinterpret_cast<const float4*>(s + (int64_t)c * HW + p0);
+        const float4 a = s4[0], b = s4[1];
+        in[c][0] = f2bf(a.x); in[c][1] = f2bf(a.y); in[c][2] = f2bf(a.z); in[c][3] = f2bf(a.w);
+        in[c][4] = f2bf(b.x); in[c][5] = f2bf(b.y); in[c][6] = f2bf(b.z); in[c][7] = f2bf(b.w);
+      } else {
+        *reinterpret_cast<uint4*>(in[c]) = *reinterpret_cast<const uint4*>(s + (int64_t)c * HW + p0);
+      }
+    }
+    bf16_t o[24];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int c = 0; c < 3; ++c) o[j * 3 + c] = in[c][j];
+    uint4* d4 = reinterpret_cast<uint4*>(d + (int64_t)p0 * 3);
+#pragma unroll
+    for (int q = 0; q < 3; ++q) d4[q] = reinterpret_cast<const uint4*>(o)[q];
+    return;
+  }
   for (int j = 0; j < 8; ++j) {
     int p = p0 + j;
     if (p >= HW) break;
