@@ -59,7 +59,8 @@ struct ConvDgradShape {
   static int kp(int C0) { return 9 * C0 + 1 <= 16 ? 16 : 32; }
   static int img0_bytes(int W0, int C0, int TQ) { return (4 * TQ + 1) * W0 * C0 * 2; }
   static int fused_extra(int W, int W0, int C0, int TQ) {
-    const int patch = 2 * (TQ * W) * kp(C0) * 2, red = NFW * 32 * 32 * 4;  // the final sums reuse the patch tables
+    const int hp16 = (TQ * W / 2 + 15) & ~15;
+    const int patch = NFW * hp16 * kp(C0) * 2, red = NFW * 32 * 32 * 4;  // the final sums reuse the patch tables
     return NBUF * img0_bytes(W0, C0, TQ) + (patch > red ? patch : red) + 16;
   }
 };
@@ -91,13 +92,21 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
   // fused form
   constexpr int K0 = 9 * C0, KP = (K0 + 1 <= 16) ? 16 : 32;
   const int RB0 = a.W0 * C0 * 2, NR0 = 4 * TQ + 1, img0_bytes = NR0 * RB0;
-  const int half = TQ * W / 2;  // pixels per finishing wave (a multiple of 16)
+  const int half = TQ * W / 2;      // pixels per finishing wave
+  const int hp16 = (half + 15) & ~15;  // rows of its patch table (the rows beyond `half` stay zero)
   char* const img0_ring = stage0 + 2 * stage_bytes;
   char* const patch0 = img0_ring + NBUF * img0_bytes;
-  const int patch_bytes = S::NFW * half * KP * 2, red_bytes = S::NFW * 32 * 32 * 4;
+  const int patch_bytes = S::NFW * hp16 * KP * 2, red_bytes = S::NFW * 32 * 32 * 4;
   char* const zero16 = patch0 + (patch_bytes > red_bytes ? patch_bytes : red_bytes);
   float* const red = reinterpret_cast<float*>(patch0);  // used after the last tile only
   if (C0 > 0 && tid < 4) reinterpret_cast<uint32_t*>(zero16)[tid] = 0u;
+  if (C0 > 0) {  // the patch tables' padding rows
+    const int padw = (hp16 - half) * KP / 2;  // dwords per table
+    for (int i = tid; i < S::NFW * padw; i += S::THREADS) {
+      const int w = i / padw, r = i - w * padw;
+      reinterpret_cast<uint32_t*>(patch0 + (w * hp16 + half) * KP * 2)[r] = 0u;
+    }
+  }
   const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
 
   // zero the right pad slot of every dY image row once
@@ -204,7 +213,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     f32x16_t accw;
 #pragma unroll
     for (int e = 0; e < 16; ++e) accw[e] = 0.f;
-    char* const patch_w = patch0 + fw * half * KP * 2;
+    char* const patch_w = patch0 + fw * hp16 * KP * 2;
     if constexpr (C0 > 0) {
 #pragma unroll
       for (int j = 0; j < PJ; ++j) {
@@ -282,11 +291,21 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
         const char* b0 = bz ? zero16 : patch_w + (p * KP + col) * 2;
         const char* b1 = bz ? zero16 : b0 + 4 * KP * 2;
         const int bstep = bz ? 0 : 16 * KP * 2;
-        for (int s0 = 0; s0 < half; s0 += 16) {
+        int s0 = 0;
+        for (; s0 + 16 <= half; s0 += 16) {
           const bf16x8_t av = lds_read_tr8_2(a0, a1);
           const bf16x8_t bv = lds_read_tr8_2(b0, b1);
           accw = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, accw, 0, 0, 0);
           a0 += 16 * CI * 2; a1 += 16 * CI * 2; b0 += bstep; b1 += bstep;
+        }
+        if (s0 < half) {
+          // ragged last step: pixels beyond the wave's range have zero patch rows; their staged operand is
+          // taken from the wave's last pixel so that nothing outside the range is read
+          const int pa = min(s0 + p, half - 1), pb = min(s0 + p + 4, half - 1);
+          const uint32_t M0 = (uint32_t)(((fw * half + pa) * CI + col) * 2), M1 = (uint32_t)(((fw * half + pb) * CI + col) * 2);
+          const bf16x8_t av = lds_read_tr8_2(st + (M0 ^ tile_swz_bits<CI>(M0)), st + (M1 ^ tile_swz_bits<CI>(M1)));
+          const bf16x8_t bv = lds_read_tr8_2(b0, b1);
+          accw = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, accw, 0, 0, 0);
         }
       }
     };

@@ -481,7 +481,7 @@ int launch_conv_dgrad_tile_t(Ctx* c, ConvDgradArgs a, int nimg, const std::strin
   auto lds_of = [&](int tq) { return S::lds_bytes(a.W, a.Wo, tq) + (C0 > 0 ? S::fused_extra(a.W, a.W0, C0, tq) : 0); };
   auto fits = [&](int tq) {
     if (S::stage_bytes(a.W, tq) > S::MAXCH * 256 * 16 || lds_of(tq) > 158 * 1024) return false;
-    if (C0 > 0 && ((tq * a.W) % 32 != 0 || tq * a.W / 2 > 128)) return false;  // pixels per finishing wave: a multiple of 16, two per lane
+    if (C0 > 0 && ((tq * a.W) % 2 != 0 || tq * a.W / 2 > 128)) return false;  // pixels per finishing wave: two per lane at most
     return true;
   };
   int TQ = S::BQ / a.Wo < a.Ho ? S::BQ / a.Wo : a.Ho;
