@@ -17,6 +17,7 @@ struct Conv0Args {
   const bf16_t* w;            // [Cout][9*C0]
   const float* bias;
   const bf16_t* zpage;        // 1 KiB of zeros
+  uint32_t* bits;             // optional sign-bit words of the output (layout as in ConvTileArgs)
   int H, W, Ho, Wo, Cout;
   int TR, NB, ntiles;         // output rows per band, bands per image, nimg * NB
 };
@@ -128,6 +129,7 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
         }
         av[ks] = __builtin_bit_cast(bf16x8_t, make_uint4(x4[0], x4[1], x4[2], x4[3]));
       }
+      uint32_t pw[2] = {0u, 0u};
 #pragma unroll
       for (int jn = 0; jn < 2; ++jn) {
         if (jn < NJ) {
@@ -144,8 +146,18 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
               o.x = pack2bf(fmaxf(acc[g * 4] + bs[jn][g * 4], 0.f), fmaxf(acc[g * 4 + 1] + bs[jn][g * 4 + 1], 0.f));
               o.y = pack2bf(fmaxf(acc[g * 4 + 2] + bs[jn][g * 4 + 2], 0.f), fmaxf(acc[g * 4 + 3] + bs[jn][g * 4 + 3], 0.f));
               *reinterpret_cast<uint2*>(&stage[l32 * SP + cl]) = o;
+              pw[jn] |= nonzero4(o.x, o.y) << (g * 8 + h * 4);
             }
           }
+        }
+      }
+      if (a.bits) {
+        const int wpp = (Cout + 31) >> 5;
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn) {
+          const uint32_t word = pw[jn] | (uint32_t)__shfl_xor((int)pw[jn], 32);
+          if (h == 0 && jn < wpp && p < plim)
+            a.bits[((int64_t)img * a.Ho * Wo + (int64_t)band * TR * Wo + p) * wpp + jn] = word;
         }
       }
       // the group's 32 pixels are contiguous in the output: 16-byte segments, lane after lane

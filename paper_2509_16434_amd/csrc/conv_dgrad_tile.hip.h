@@ -36,7 +36,8 @@
 struct ConvDgradArgs {
   ImgAddr dy;                 // gradient of the layer output, images [Ho][Wo][64]
   bf16_t* dx;                 // result, images [H][W][CI] at dx + b*x_stride_b + v*x_stride_v
-  const bf16_t* x;            // stored activation of the same layout: the ReLU mask
+  const uint32_t* xbits;      // ReLU mask: sign-bit words of the stored activation, written by the forward kernels
+                              // (word w of pixel p of image i at xbits[(i*H*W + p) * (CI/32) + w])
   int64_t x_stride_b, x_stride_v;
   const bf16_t* wt;           // [9][CI][64]: wt[(tap*CI + ci)*64 + co] = W[co][tap][ci]
   const bf16_t* zpage;        // 1 KiB of zeros
@@ -67,14 +68,11 @@ struct ConvDgradShape {
 
 __device__ __forceinline__ uint32_t dy_swz_bits(uint32_t off) { return ((off >> 8) & 7u) << 4; }
 
-__device__ __forceinline__ uint32_t relu_keep(uint32_t m) {
-  // all-ones halves where the stored bf16 is > 0 (as a 16-bit integer: positive), in packed 16-bit
-  // arithmetic: y = max(x, 0) is non-zero exactly there, and (0 - y) >> 15 spreads that to a mask
-  typedef short s16x2_t __attribute__((ext_vector_type(2)));
-  const s16x2_t x = __builtin_bit_cast(s16x2_t, m), zero = {0, 0};
-  const s16x2_t y = __builtin_elementwise_max(x, zero);
-  const s16x2_t k = (zero - y) >> 15;
-  return __builtin_bit_cast(uint32_t, k);
+// all-ones halves for the set bits among bits (2d, 2d+1) of b
+__device__ __forceinline__ uint32_t keep_pair(uint32_t b, int d) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_sbfe((int)b, 2 * d, 1) & 0xffffu;  // 0 or -1 from one bit
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_sbfe((int)b, 2 * d + 1, 1) << 16;
+  return lo | hi;
 }
 
 template <int CI, int C0>
@@ -183,8 +181,8 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     // mask bytes in flight per CU)
     // (the RGB fused form needs the registers for its 27-tap patches and keeps one set: one tile ahead)
     constexpr int NSET = (C0 == 3) ? 1 : 2;
-    uint4 mk[NSET][S::MAXCH];
-    int64_t band_off[2] = {0, 0};  // element offset of the set's band within dx / x
+    uint32_t mk[NSET][S::MAXCH];   // the word holding a chunk's eight mask bits
+    int64_t band_off[2] = {0, 0};  // element offset of the set's band within dx
     int nvalid[2] = {0, 0};        // its chunks that lie inside the image
     auto load_mask = [&](int q, auto setc) __attribute__((always_inline)) {
       constexpr int SET = decltype(setc)::value;
@@ -194,15 +192,16 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       const int rows = min(2 * TQ, a.H - 2 * band * TQ);
       band_off[SET] = (int64_t)b * a.x_stride_b + (int64_t)vw * a.x_stride_v + (int64_t)(2 * band * TQ) * W * CI;
       nvalid[SET] = rows * W * CI / 8;
+      // mask words of the band: pixel (band-linear) c / (CI/8), word (c % (CI/8)) / 4
+      const uint32_t* wb = a.xbits + ((int64_t)img * a.H + 2 * band * TQ) * W * (CI / 32);
 #pragma unroll
       for (int i = 0; i < S::MAXCH; ++i) {
         const int c = chunk_of(i);
         // wave-uniform base + 32-bit lane offset, formed here (the empty asm keeps the compiler from
-        // carrying sixteen 64-bit addresses across the tile loop, which spills)
-        const char* xb = reinterpret_cast<const char*>(a.x + band_off[SET]);
-        uint32_t off = (uint32_t)c * 16u;
+        // carrying per-chunk 64-bit addresses across the tile loop, which spills)
+        uint32_t off = (uint32_t)(c >> 2) * 4u;  // four chunks (32 channels) per word
         asm volatile("" : "+v"(off));
-        mk[SET][i] = (chunk_mine(i) && c < nvalid[SET]) ? *reinterpret_cast<const uint4*>(xb + off) : make_uint4(0u, 0u, 0u, 0u);
+        mk[SET][i] = (chunk_mine(i) && c < nvalid[SET]) ? *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(wb) + off) : 0u;
       }
     };
 
@@ -256,7 +255,8 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
         if (chunk_mine(i) && (C0 > 0 || c < nvalid[SET])) {
           const uint32_t L = (uint32_t)c * 16u, ph = L ^ tile_swz_bits<CI>(L);
           uint4 v = *reinterpret_cast<const uint4*>(st + ph);
-          v.x &= relu_keep(mk[SET][i].x); v.y &= relu_keep(mk[SET][i].y); v.z &= relu_keep(mk[SET][i].z); v.w &= relu_keep(mk[SET][i].w);
+          const uint32_t b8 = mk[SET][i] >> ((c & 3) * 8);  // this chunk's eight bits
+          v.x &= keep_pair(b8, 0); v.y &= keep_pair(b8, 1); v.z &= keep_pair(b8, 2); v.w &= keep_pair(b8, 3);
           if constexpr (C0 > 0) *reinterpret_cast<uint4*>(st + ph) = v;  // chunks outside the image become zeros
           else {
             uint32_t off = L;

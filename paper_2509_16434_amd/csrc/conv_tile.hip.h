@@ -32,9 +32,16 @@ struct ConvTileArgs {
   const bf16_t* w;            // [Cout][9*CIN], k = (u*3+v)*CIN + ci
   const float* bias;          // [Cout]
   const bf16_t* zpage;        // 1 KiB of zeros
+  uint32_t* bits;             // optional: one bit per output element (stored value > 0), word w of pixel p of image i at
+                              // bits[(i*Ho*Wo + p) * ceil(Cout/32) + w]; read by the transposed convolution as ReLU mask
   int V, H, W, Ho, Wo, Cout;
   int TR, NB, ntiles;         // output rows per band, bands per image, nimg * NB
 };
+
+// bits of the four bf16 packed in (lo, hi) that are non-zero (the values are >= +0 after the clamp)
+__device__ __forceinline__ uint32_t nonzero4(uint32_t lo, uint32_t hi) {
+  return ((lo & 0xffffu) ? 1u : 0u) | ((lo >> 16) ? 2u : 0u) | ((hi & 0xffffu) ? 4u : 0u) | ((hi >> 16) ? 8u : 0u);
+}
 
 template <int CIN>
 struct ConvTileShape {
@@ -187,8 +194,10 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
         }
       }
     // ---- epilogue: bias, ReLU, bf16; lane holds pixel l32 of the wave, columns j*32 + g*8 + h*4 + 0..3
+    uint32_t pw[TN];  // this lane's 16 sign bits of the pixel's 32-column group j
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+    for (int j = 0; j < TN; ++j) {
+      pw[j] = 0u;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int cl = j * 32 + g * 8 + h * 4;
@@ -197,12 +206,25 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
         o.x = pack2bf(fmaxf(acc[j][g * 4] + bv.x, 0.f), fmaxf(acc[j][g * 4 + 1] + bv.y, 0.f));
         o.y = pack2bf(fmaxf(acc[j][g * 4 + 2] + bv.z, 0.f), fmaxf(acc[j][g * 4 + 3] + bv.w, 0.f));
         *reinterpret_cast<uint2*>(stage + (l32 * SP + cl) * 2) = o;
+        pw[j] |= nonzero4(o.x, o.y) << (g * 8 + h * 4);
       }
+    }
     {
       const int img = t / a.NB, band = t - img * a.NB;
       const int b = img / a.V, vw = img - b * a.V;
       const int rows_here = min(TR, a.Ho - band * TR);
       const int plim = rows_here * Wo;  // pixels of the band that exist
+      if (a.bits) {
+        // the other half of the columns sits in lane ^ 32; lanes 0..31 write the pixel's words
+        const int wpp = (a.Cout + 31) >> 5, p = wm * 32 + l32;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const uint32_t word = pw[j] | (uint32_t)__shfl_xor((int)pw[j], 32);
+          const int wi = (n0 >> 5) + j;
+          if (h == 0 && p < plim && wi < wpp)
+            a.bits[((int64_t)img * a.Ho * Wo + (int64_t)band * TR * Wo + p) * wpp + wi] = word;
+        }
+      }
       bf16_t* dst = a.out + (int64_t)b * a.out_stride_b + (int64_t)vw * a.out_stride_v + (int64_t)band * TR * Wo * a.Cout;
       constexpr int CPRO = NW / 8;  // 16-byte chunks per staged row
 #pragma unroll

@@ -45,6 +45,8 @@ struct Ctx {
   bf16_t* shadow = nullptr;
   bf16_t* wd[PPO_MAX_LAYERS][2];  // transposed-conv weights per row parity (conv layers >= 1)
   bf16_t* wtap[PPO_MAX_LAYERS];   // the same weights transposed per tap: [9][Cin][Cout]
+  uint32_t* abits[PPO_MAX_LAYERS] = {};  // sign bits of conv layer l's stored output for the current chunk (ReLU mask of the backward pass)
+  bool abits_ok[PPO_MAX_LAYERS] = {};    // written by the forward kernel that ran for this chunk
   bf16_t* fcT[PPO_MAX_LAYERS];    // [in][out]
   bf16_t* headT = nullptr;        // [hid][32]
   // device: rollout buffer (SoA)
@@ -406,14 +408,14 @@ int launch_conv_fwd_tile_t(Ctx* c, const ConvTileArgs& a, const std::string& nam
   return PPO_OK;
 }
 int launch_conv_fwd_tile(Ctx* c, const AConvFwd& al, const ImgAddr& o, int Cout, const bf16_t* w, const float* bias, int nimg,
-                         const std::string& name, double abytes) {
+                         const std::string& name, double abytes, uint32_t* bits) {
   if ((al.Cin != 32 && al.Cin != 64) || Cout % 8 || nimg < 1 || al.in.idx) return 1;
   const int BM = al.Cin == 32 ? 128 : 64;
   if (al.Wo > BM) return 1;
   ConvTileArgs a;
   a.in = al.in; a.in.prepare();
   a.out = const_cast<bf16_t*>(o.base); a.out_stride_b = o.stride_b; a.out_stride_v = o.stride_v;
-  a.w = w; a.bias = bias; a.zpage = c->zpage; a.V = o.V; a.H = al.H; a.W = al.W; a.Ho = al.Ho; a.Wo = al.Wo; a.Cout = Cout;
+  a.w = w; a.bias = bias; a.zpage = c->zpage; a.bits = bits; a.V = o.V; a.H = al.H; a.W = al.W; a.Ho = al.Ho; a.Wo = al.Wo; a.Cout = Cout;
   const int trmax = BM / al.Wo < al.Ho ? BM / al.Wo : al.Ho;
   a.NB = cdiv(al.Ho, trmax); a.TR = cdiv(al.Ho, a.NB);  // balanced bands
   a.ntiles = nimg * a.NB;
@@ -514,26 +516,26 @@ int launch_conv_dgrad_tile_t(Ctx* c, ConvDgradArgs a, int nimg, const std::strin
   LAUNCHCHK(c, "k_conv_dgrad_tile");
   return PPO_OK;
 }
-ConvDgradArgs conv_dgrad_args(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, bf16_t* dx, const bf16_t* wt, int H, int W, int Ho, int Wo) {
+ConvDgradArgs conv_dgrad_args(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, const uint32_t* xbits, bf16_t* dx, const bf16_t* wt, int H, int W, int Ho, int Wo) {
   ConvDgradArgs a;
-  a.dy = dy; a.dy.prepare(); a.dx = dx; a.x = xa.base; a.x_stride_b = xa.stride_b; a.x_stride_v = xa.stride_v;
+  a.dy = dy; a.dy.prepare(); a.dx = dx; a.xbits = xbits; a.x_stride_b = xa.stride_b; a.x_stride_v = xa.stride_v;
   a.wt = wt; a.zpage = c->zpage; a.V = xa.V; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.TQ = 0; a.NB = 0; a.ntiles = 0;
   a.img0 = ImgAddr(); a.img0.base = nullptr; a.img0.idx = nullptr; a.img0.stride_b = 0; a.img0.stride_v = 0; a.img0.V = 1;
   a.H0 = 0; a.W0 = 0; a.partial0 = nullptr;
   return a;
 }
-int launch_conv_dgrad_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, bf16_t* dx, const bf16_t* wt, int Co, int Ci, int H, int W, int Ho, int Wo,
+int launch_conv_dgrad_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, const uint32_t* xbits, bf16_t* dx, const bf16_t* wt, int Co, int Ci, int H, int W, int Ho, int Wo,
                            int nimg, const std::string& name, double flops, double abytes) {
-  if (Co != 64 || (Ci != 32 && Ci != 64) || dy.idx || nimg < 1) return 1;
-  ConvDgradArgs a = conv_dgrad_args(c, dy, xa, dx, wt, H, W, Ho, Wo);
+  if (Co != 64 || (Ci != 32 && Ci != 64) || dy.idx || nimg < 1 || !xbits) return 1;
+  ConvDgradArgs a = conv_dgrad_args(c, dy, xa, xbits, dx, wt, H, W, Ho, Wo);
   return Ci == 32 ? launch_conv_dgrad_tile_t<32, 0>(c, a, nimg, name, flops, abytes, nullptr)
                   : launch_conv_dgrad_tile_t<64, 0>(c, a, nimg, name, flops, abytes, nullptr);
 }
 // The same with the first layer's weight gradient fused in (depth or RGB input, 32 channels after the first layer).
-int launch_conv_dgrad_wgrad0_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, const bf16_t* wt, int Co, int Ci, int H, int W, int Ho, int Wo,
+int launch_conv_dgrad_wgrad0_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, const uint32_t* xbits, const bf16_t* wt, int Co, int Ci, int H, int W, int Ho, int Wo,
                                   const ImgAddr& img0, int C0, int H0, int W0, int nimg, const std::string& name, double flops, double abytes, int* grid_out) {
-  if (Co != 64 || Ci != 32 || (C0 != 1 && C0 != 3) || dy.idx || nimg < 1) return 1;
-  ConvDgradArgs a = conv_dgrad_args(c, dy, xa, nullptr, wt, H, W, Ho, Wo);
+  if (Co != 64 || Ci != 32 || (C0 != 1 && C0 != 3) || dy.idx || nimg < 1 || !xbits) return 1;
+  ConvDgradArgs a = conv_dgrad_args(c, dy, xa, xbits, nullptr, wt, H, W, Ho, Wo);
   a.img0 = img0; a.img0.prepare(); a.H0 = H0; a.W0 = W0;
   return C0 == 1 ? launch_conv_dgrad_tile_t<32, 1>(c, a, nimg, name, flops, abytes, grid_out)
                  : launch_conv_dgrad_tile_t<32, 3>(c, a, nimg, name, flops, abytes, grid_out);
@@ -571,9 +573,11 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n) {
     const int grid = cdiv(M, 32 * 4 * TPW);
     Conv0Args ca;
     ca.in = in; ca.in.prepare(); ca.out = c->act[0]; ca.w = c->shadow + c->convW[0]; ca.bias = c->p + c->convB[0]; ca.zpage = c->zpage;
+    ca.bits = c->nconv > 1 ? c->abits[0] : nullptr;
     ca.H = c->cH[0]; ca.W = c->cW[0]; ca.Ho = Ho; ca.Wo = Wo; ca.Cout = Co; ca.TR = 0; ca.NB = 0; ca.ntiles = 0;
     int trc = c->cC[0] == 1 ? launch_conv0_fwd_tile_t<1>(c, ca, nimg) : (c->cC[0] == 3 ? launch_conv0_fwd_tile_t<3>(c, ca, nimg) : 1);
     if (trc != PPO_OK && trc != 1) return trc;
+    c->abits_ok[0] = trc == PPO_OK && c->nconv > 1;
     if (trc == PPO_OK) {}
     else if (c->cC[0] == 1)
       hipLaunchKernelGGL((k_conv1_fwd<1, TPW>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->shadow + c->convW[0], c->p + c->convB[0], c->act[0]);
@@ -591,7 +595,10 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n) {
     ep.map.stride_b = o.stride_b; ep.map.stride_v = o.stride_v; ep.map.V = V; ep.map.HW = al.Ho * al.Wo; ep.map.C = c->cC[l + 1]; ep.map.M = al.M;
     ep.out = const_cast<bf16_t*>(o.base); ep.bias = c->p + c->convB[l]; ep.mask = nullptr; ep.N = c->cC[l + 1];
     double ab = 2.0 * ((double)nimg * al.H * al.W * al.Cin + (double)al.M * c->cC[l + 1] + (double)al.K * c->cC[l + 1]);
-    int rc = launch_conv_fwd_tile(c, al, o, c->cC[l + 1], c->shadow + c->convW[l], c->p + c->convB[l], nimg, "conv_fwd." + std::to_string(l), ab);
+    const bool want_bits = l < c->nconv - 1;  // the last layer's mask is applied by the first linear layer's input gradient
+    int rc = launch_conv_fwd_tile(c, al, o, c->cC[l + 1], c->shadow + c->convW[l], c->p + c->convB[l], nimg, "conv_fwd." + std::to_string(l), ab,
+                                  want_bits ? c->abits[l] : nullptr);
+    c->abits_ok[l] = want_bits && rc == PPO_OK;
     if (rc == PPO_OK + 1) rc = launch_gemm(c, al, al.M, c->shadow + c->convW[l], al.K, c->cC[l + 1], al.K, ep, "conv_fwd." + std::to_string(l), ab);
     if (rc) return rc;
   }
@@ -678,9 +685,10 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
       int grid = 2 * tpp < 512 ? 2 * tpp : 512;
       if ((int64_t)grid * npair > c->partial_elems) grid = (int)(c->partial_elems / npair);
       const double fflops = 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co + 2.0 * pix * Ci * (K0 + 1);
-      const double fbytes = 2.0 * ((double)nimg * Ho * Wo * Co + pix * Ci + (double)nimg * c->img_elems + 9.0 * Ci * Co);
+      // the ReLU mask is one bit per element when the forward kernel left its sign-bit words, else the stored activation
+      const double fbytes = 2.0 * ((double)nimg * Ho * Wo * Co + (double)nimg * c->img_elems + 9.0 * Ci * Co) + (c->abits_ok[l - 1] ? pix * Ci / 8.0 : 2.0 * pix * Ci);
       int tgrid = 0;
-      rc = launch_conv_dgrad_wgrad0_tile(c, dy, xa, c->wtap[l], Co, Ci, H, W, Ho, Wo, in, c->cC[0], c->cH[0], c->cW[0], nimg,
+      rc = launch_conv_dgrad_wgrad0_tile(c, dy, xa, c->abits_ok[l - 1] ? c->abits[l - 1] : nullptr, c->wtap[l], Co, Ci, H, W, Ho, Wo, in, c->cC[0], c->cH[0], c->cW[0], nimg,
                                          "conv_dgrad.1+wgrad.0", fflops, fbytes, &tgrid);
       if (rc == PPO_OK) grid = tgrid;
       else if (rc != PPO_OK + 1) return rc;
@@ -705,9 +713,9 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
       LAUNCHCHK(c, "k_conv1_wgrad_reduce");
       return PPO_OK;
     }
-    double ab = 2.0 * ((double)nimg * Ho * Wo * Co + 2.0 * pix * Ci + 9.0 * Ci * Co);
+    double ab = 2.0 * ((double)nimg * Ho * Wo * Co + pix * Ci + 9.0 * Ci * Co) + (c->abits_ok[l - 1] && Co == 64 ? pix * Ci / 8.0 : 2.0 * pix * Ci);
     const double dflops = 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co;
-    rc = launch_conv_dgrad_tile(c, dy, xa, c->gbuf[cur ^ 1], c->wtap[l], Co, Ci, H, W, Ho, Wo, nimg, "conv_dgrad." + std::to_string(l), dflops, ab);
+    rc = launch_conv_dgrad_tile(c, dy, xa, c->abits_ok[l - 1] ? c->abits[l - 1] : nullptr, c->gbuf[cur ^ 1], c->wtap[l], Co, Ci, H, W, Ho, Wo, nimg, "conv_dgrad." + std::to_string(l), dflops, ab);
     if (rc == PPO_OK + 1) rc = launch_gemm(c, al, M0, nullptr, 0, 2 * Ci, 4 * Co, ep, "conv_dgrad." + std::to_string(l), ab, 2, dflops);
     if (rc) return rc;
     cur ^= 1;
@@ -838,6 +846,7 @@ int create_impl(Ctx* c) {
   for (int l = 0; l < c->nconv - 1; ++l) {
     int64_t e = (int64_t)CH * V * c->cC[l + 1] * c->cH[l + 1] * c->cW[l + 1];
     DALLOC(c, c->act[l], e);
+    DALLOC(c, c->abits[l], (int64_t)CH * V * c->cH[l + 1] * c->cW[l + 1] * ((c->cC[l + 1] + 31) / 32));
     if (e > gmax) gmax = e;
   }
   DALLOC(c, c->feat, (int64_t)CH * c->feat_ld);
