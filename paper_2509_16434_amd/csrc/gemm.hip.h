@@ -562,6 +562,14 @@ __global__ __launch_bounds__(256) void k_reduce_partials_t(const float* __restri
   float s0 = 0.f, s1 = 0.f;
   if (i < n_all) {
     int k = sl;
+    // four independent loads in flight per lane (the sums stay in a fixed order)
+    float s2 = 0.f, s3 = 0.f;
+    for (; k + 24 < splits; k += 32) {
+      const float v0 = partial[(int64_t)k * n_all + i], v1 = partial[(int64_t)(k + 8) * n_all + i];
+      const float v2 = partial[(int64_t)(k + 16) * n_all + i], v3 = partial[(int64_t)(k + 24) * n_all + i];
+      s0 += v0; s1 += v1; s2 += v2; s3 += v3;
+    }
+    s0 += s2; s1 += s3;
     for (; k + 8 < splits; k += 16) { s0 += partial[(int64_t)k * n_all + i]; s1 += partial[(int64_t)(k + 8) * n_all + i]; }
     if (k < splits) s0 += partial[(int64_t)k * n_all + i];
   }
@@ -586,6 +594,14 @@ __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict
   float s0 = 0.f, s1 = 0.f;
   if (i < n) {
     int k = sl;
+    // four independent loads in flight per lane (the sums stay in a fixed order)
+    float s2 = 0.f, s3 = 0.f;
+    for (; k + 24 < splits; k += 32) {
+      const float v0 = partial[(int64_t)k * n + i], v1 = partial[(int64_t)(k + 8) * n + i];
+      const float v2 = partial[(int64_t)(k + 16) * n + i], v3 = partial[(int64_t)(k + 24) * n + i];
+      s0 += v0; s1 += v1; s2 += v2; s3 += v3;
+    }
+    s0 += s2; s1 += s3;
     for (; k + 8 < splits; k += 16) { s0 += partial[(int64_t)k * n + i]; s1 += partial[(int64_t)(k + 8) * n + i]; }
     if (k < splits) s0 += partial[(int64_t)k * n + i];
   }

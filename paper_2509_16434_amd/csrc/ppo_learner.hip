@@ -47,6 +47,8 @@ struct Ctx {
   bf16_t* wtap[PPO_MAX_LAYERS];   // the same weights transposed per tap: [9][Cin][Cout]
   uint32_t* abits[PPO_MAX_LAYERS] = {};  // sign bits of conv layer l's stored output for the current chunk (ReLU mask of the backward pass)
   bool abits_ok[PPO_MAX_LAYERS] = {};    // written by the forward kernel that ran for this chunk
+  int64_t wver = 0;                      // bumped whenever the weights change (every repack_weights call)
+  int64_t wd_ver[PPO_MAX_LAYERS] = {};   // weight version that wd[l] holds (0: none); packed on demand
   bf16_t* fcT[PPO_MAX_LAYERS];    // [in][out]
   bf16_t* headT = nullptr;        // [hid][32]
   // device: rollout buffer (SoA)
@@ -356,14 +358,25 @@ int launch_wgrad(Ctx* c, const DL& dl_, const AL& al_, int Nn, int Kk, int M, fl
 }
 
 // bf16 copies of the parameters in the layouts the backward GEMMs read
+// Parity-class-packed transposed-conv weights of layer l for the implicit-GEMM paths: rebuilt when they
+// are first needed after a change of the weights (the LDS-image kernels use the per-tap transposes instead).
+int ensure_packed_dgrad_weights(Ctx* c, int l) {
+  if (c->wd_ver[l] == c->wver) return PPO_OK;
+  const int Co = c->cC[l + 1], Ci = c->cC[l];
+  for (int py = 0; py < 2; ++py) {
+    int64_t n = (int64_t)2 * Ci * (1 + py) * 2 * Co;
+    hipLaunchKernelGGL(k_pack_dgrad_w, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->shadow + c->convW[l], Co, Ci, py, c->wd[l][py]);
+  }
+  LAUNCHCHK(c, "k_pack_dgrad_w");
+  c->wd_ver[l] = c->wver;
+  return PPO_OK;
+}
+
 int repack_weights(Ctx* c) {
+  c->wver += 1;
   ProfScope ps(c, "weight_repack", 0.0, 4.0 * (double)c->total);
   for (int l = 1; l < c->nconv; ++l) {
     int Co = c->cC[l + 1], Ci = c->cC[l];
-    for (int py = 0; py < 2; ++py) {
-      int64_t n = (int64_t)2 * Ci * (1 + py) * 2 * Co;
-      hipLaunchKernelGGL(k_pack_dgrad_w, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->shadow + c->convW[l], Co, Ci, py, c->wd[l][py]);
-    }
     hipLaunchKernelGGL(k_pack_dgrad_taps, dim3(cdiv((int64_t)9 * Ci * Co, 256)), dim3(256), 0, c->stream, c->shadow + c->convW[l], Co, Ci, c->wtap[l]);
   }
   for (int l = 0; l < c->nfc; ++l) {
@@ -693,6 +706,8 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
       if (rc == PPO_OK) grid = tgrid;
       else if (rc != PPO_OK + 1) return rc;
       else {
+        rc = ensure_packed_dgrad_weights(c, l);
+        if (rc) return rc;
         ProfScope ps(c, "conv_dgrad.1+wgrad.0", 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co + 2.0 * pix * Ci * (K0 + 1),
                      2.0 * ((double)nimg * Ho * Wo * Co + pix * Ci + (double)nimg * c->img_elems + 9.0 * Ci * Co));
 #define LAUNCH_FUSED(BN_, WM_, WN_, CI0_)                                                                                                  \
@@ -716,7 +731,11 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
     double ab = 2.0 * ((double)nimg * Ho * Wo * Co + pix * Ci + 9.0 * Ci * Co) + (c->abits_ok[l - 1] && Co == 64 ? pix * Ci / 8.0 : 2.0 * pix * Ci);
     const double dflops = 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co;
     rc = launch_conv_dgrad_tile(c, dy, xa, c->abits_ok[l - 1] ? c->abits[l - 1] : nullptr, c->gbuf[cur ^ 1], c->wtap[l], Co, Ci, H, W, Ho, Wo, nimg, "conv_dgrad." + std::to_string(l), dflops, ab);
-    if (rc == PPO_OK + 1) rc = launch_gemm(c, al, M0, nullptr, 0, 2 * Ci, 4 * Co, ep, "conv_dgrad." + std::to_string(l), ab, 2, dflops);
+    if (rc == PPO_OK + 1) {
+      rc = ensure_packed_dgrad_weights(c, l);
+      if (rc) return rc;
+      rc = launch_gemm(c, al, M0, nullptr, 0, 2 * Ci, 4 * Co, ep, "conv_dgrad." + std::to_string(l), ab, 2, dflops);
+    }
     if (rc) return rc;
     cur ^= 1;
   }
