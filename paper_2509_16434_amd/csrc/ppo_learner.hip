@@ -326,9 +326,11 @@ int launch_wgrad(Ctx* c, const DL& dl_, const AL& al_, int Nn, int Kk, int M, fl
   DL dl = dl_; AL al = al_;
   dl.prepare(); al.prepare();
   const char* what = name.c_str();
-  const int ktw = Kk <= 128 ? 1 : (Kk <= 256 ? 2 : 3);
+  // wide outputs (the first hidden layer) have enough tiles with narrow blocks and few splits: the fp32 partials,
+  // not the operands, are then the larger part of the traffic
+  const int ktw = Kk <= 128 ? 1 : (Kk <= 256 ? 2 : (Kk >= 1024 ? 1 : 3));
   const int tiles = cdiv(Kk, 128 * ktw) * cdiv(Nn, 64);
-  int splits = cdiv(768, tiles);
+  int splits = cdiv(Kk >= 1024 ? 512 : 768, tiles);
   const int max_by_rows = cdiv(M, 128);
   if (splits > max_by_rows) splits = max_by_rows;
   const int64_t per = (int64_t)Nn * Kk;
