@@ -151,8 +151,26 @@ GRAD_CASES = [(0, 64, 16, 0), (0, 64, 16, 100), (1, 40, 4, 0), (2, 64, 4, 0), (2
 
 @pytest.mark.parametrize("ci,N,T,chunk", GRAD_CASES)
 def test_ppo_single_minibatch_gradients(L, ci, N, T, chunk):
+    _check_single_minibatch(L, configs.get_config(ci, num_envs=N, horizon=T), chunk)
+
+
+# Shapes that exercise the ragged paths of the LDS-image convolution kernels: odd heights and widths
+# (last quad row / column without a partner, right zero-pad pixel in use), bands that do not divide the
+# image, an image height whose first-layer output is odd.
+ODD_SHAPES = [(52, 76), (50, 72), (44, 88)]
+
+
+@pytest.mark.parametrize("h,w", ODD_SHAPES)
+def test_ppo_gradients_odd_image_shapes(L, h, w):
+    cfg = configs.get_config(1, num_envs=48, horizon=4)
+    cfg["net"].update(in_h=h, in_w=w)
+    # (the distance to exact arithmetic is a property of bf16 operands on the sampled batch, not of the
+    # kernels: the same gradient is within 2e-2 of the oracle's bf16-operand mode; it is only bounded loosely)
+    _check_single_minibatch(L, cfg, 0, loose_bound=0.3)
+
+
+def _check_single_minibatch(L, cfg, chunk, loose_bound=0.15):
     torch = _torch()
-    cfg = configs.get_config(ci, num_envs=N, horizon=T)
     lrn, ro, params = _setup(L, cfg, max_chunk=chunk)
     hp = dict(cfg["hp"], epochs=1, minibatches=1, seed=3)
     lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
@@ -174,7 +192,7 @@ def test_ppo_single_minibatch_gradients(L, ci, N, T, chunk):
     assert max(errs.values()) <= TOL_BF16, errs
     # distance to the exact-arithmetic gradient: bf16 operand rounding on a noise-dominated batch gradient
     loose = per_tensor_errors(cfg["net"], g, og)
-    assert max(loose.values()) <= 0.15, loose
+    assert max(loose.values()) <= loose_bound, loose
 
 
 # ------------------------------------------------------------------ Adam, from the library's own gradients
