@@ -195,6 +195,36 @@ def _check_single_minibatch(L, cfg, chunk, loose_bound=0.15):
     assert max(loose.values()) <= loose_bound, loose
 
 
+def test_full_size_bench_minibatch_matches_oracle(L):
+    """The benchmark's default workload at its full size and in its launch configuration (1024 envs x 16
+    steps, minibatches of 4096 samples, one chunk each).  With lr = 0 the parameters never move, so the
+    gradient left after the update is the initial-parameter gradient of the LAST minibatch of the epoch,
+    whose samples the oracle takes from the (bit-exact) permutation; its statistics are step 3's."""
+    torch = _torch()
+    cfg = configs.get_config(1)
+    lrn, ro, params = _setup(L, cfg)
+    hp = dict(cfg["hp"], epochs=1, minibatches=4, seed=11, lr=0.0)
+    lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
+    stats = lrn.update(hp)
+    np.testing.assert_array_equal(lrn.get_params(), params)
+    g = lrn.get_grads()
+    S = cfg["num_envs"] * cfg["horizon"]
+    perm = orc.permutation(hp["seed"], 0, 0, S)
+    B = S // 4
+    sel = perm[3 * B:]
+    fr, adv, ret = _oracle_inputs(cfg, ro, lrn)
+    with orc.quant(1):
+        qst, qg = orc.ppo_loss_grad(cfg["net"], params, fr["obs"][sel], fr["proprio"][sel], fr["action"][sel], fr["logp_old"][sel],
+                                    fr["value"][sel], adv[sel], ret[sel], clip_eps=hp["clip_eps"], vclip_eps=hp["vclip_eps"],
+                                    vf_coef=hp["vf_coef"], ent_coef=hp["ent_coef"])
+    st = stats[3]
+    for k_gpu, k_or in (("pi_loss", "pi_loss"), ("v_loss", "v_loss"), ("approx_kl", "approx_kl"), ("clip_frac", "clip_frac"), ("total_loss", "total")):
+        assert abs(st[k_gpu] - qst[k_or]) <= TOL_BF16 * max(abs(qst[k_or]), 1e-3), (k_gpu, st[k_gpu], qst[k_or])
+    assert abs(st["grad_norm"] - qst["grad_norm"]) <= TOL_BF16 * qst["grad_norm"]
+    errs = per_tensor_errors(cfg["net"], g, qg)
+    assert max(errs.values()) <= TOL_BF16, errs
+
+
 # ------------------------------------------------------------------ Adam, from the library's own gradients
 @pytest.mark.parametrize("ci,N,T", [(0, 64, 16), (1, 64, 4)])
 def test_adam_steps_replayed_exactly(L, ci, N, T):
