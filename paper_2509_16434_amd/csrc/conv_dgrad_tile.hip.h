@@ -394,29 +394,39 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
+      // The four dY pixels are fetched one pixel (all its channel chunks) ahead of the MFMAs that use
+      // them, so that the LDS latency of a lone wave per SIMD hides behind 4 to 16 MFMAs.
+      bf16x8_t av[2][CC];
+      auto fetch = [&](int pi, bf16x8_t (&dst)[CC]) __attribute__((always_inline)) {
+        const int dyo = pi >> 1, dxo = pi & 1;
 #pragma unroll
-      for (int dyo = 0; dyo < 2; ++dyo)
+        for (int cc = 0; cc < CC; ++cc)
+          dst[cc] = *reinterpret_cast<const bf16x8_t*>(img_s + dyo * RP + dxo * 128 + ((uint32_t)(cc * 32) ^ hx[dxo]));
+      };
+      fetch(0, av[0]);
 #pragma unroll
-        for (int dxo = 0; dxo < 2; ++dxo)
+      for (int pi = 0; pi < 4; ++pi) {
+        if (pi + 1 < 4) fetch(pi + 1, av[(pi + 1) & 1]);
+        const bf16x8_t (&x)[CC] = av[pi & 1];
+        // class (py, px) takes tap u = py ? (dyo ? 0 : 2) : 1 from row offset dyo (even rows only from dyo = 0), same for columns
 #pragma unroll
-          for (int cc = 0; cc < CC; ++cc) {
-            const bf16x8_t av = *reinterpret_cast<const bf16x8_t*>(img_s + dyo * RP + dxo * 128 + ((uint32_t)(cc * 32) ^ hx[dxo]));
-            // class (py, px) takes tap u = py ? (dyo ? 0 : 2) : 1 from row offset dyo (even rows only from dyo = 0), same for columns
-            if (dyo == 0 && dxo == 0) {
-              acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 1][cc], av, acc[0], 0, 0, 0);
-              acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 2][cc], av, acc[1], 0, 0, 0);
-              acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 1][cc], av, acc[2], 0, 0, 0);
-              acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 2][cc], av, acc[3], 0, 0, 0);
-            } else if (dyo == 0 && dxo == 1) {
-              acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 0][cc], av, acc[1], 0, 0, 0);
-              acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 0][cc], av, acc[3], 0, 0, 0);
-            } else if (dyo == 1 && dxo == 0) {
-              acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 1][cc], av, acc[2], 0, 0, 0);
-              acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 2][cc], av, acc[3], 0, 0, 0);
-            } else {
-              acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 0][cc], av, acc[3], 0, 0, 0);
-            }
+        for (int cc = 0; cc < CC; ++cc) {
+          if (pi == 0) {
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 1][cc], x[cc], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 2][cc], x[cc], acc[1], 0, 0, 0);
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 1][cc], x[cc], acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 2][cc], x[cc], acc[3], 0, 0, 0);
+          } else if (pi == 1) {
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[1 * 3 + 0][cc], x[cc], acc[1], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[2 * 3 + 0][cc], x[cc], acc[3], 0, 0, 0);
+          } else if (pi == 2) {
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 1][cc], x[cc], acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 2][cc], x[cc], acc[3], 0, 0, 0);
+          } else {
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[0 * 3 + 0][cc], x[cc], acc[3], 0, 0, 0);
           }
+        }
+      }
       // ---- stage: lane holds, per class, columns wn*32 + g*8 + h*4 + 0..3 of its pixel
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
