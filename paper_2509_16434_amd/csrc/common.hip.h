@@ -58,6 +58,18 @@ struct ImgAddr {
     int64_t s = idx ? (int64_t)idx[b] : (int64_t)b;
     return base + s * stride_b + (int64_t)v * stride_v;
   }
+  // The same for a wave-uniform image number.  The gather index is read through the constant address
+  // space, hence with a scalar load: a vector load here would make the caller wait for every
+  // vector-memory operation it has in flight (LDS-writing band loads included) before it can form
+  // the address.  The index list is never written by a kernel that reads it this way.
+  __device__ __forceinline__ const bf16_t* ptr_uniform(int img) const {
+    int b = img, v = 0;
+    if (V != 1) { b = (dv.d == (uint32_t)V) ? (int)dv.div((uint32_t)img) : img / V; v = img - b * V; }
+    b = __builtin_amdgcn_readfirstlane(b);
+    typedef const __attribute__((address_space(4))) int32_t* cidx_t;
+    int64_t s = idx ? (int64_t)reinterpret_cast<cidx_t>(reinterpret_cast<uintptr_t>(idx))[b] : (int64_t)b;
+    return base + s * stride_b + (int64_t)v * stride_v;
+  }
 };
 // Mutable twin for outputs.
 struct ImgAddrW {

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
       const int t = blockIdx.x + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int iy_lo = 2 * band * TR - 1;
-      const char* src = reinterpret_cast<const char*>(a.in.ptr(img)) + (int64_t)iy_lo * RB;
+      const char* src = reinterpret_cast<const char*>(a.in.ptr_uniform(img)) + (int64_t)iy_lo * RB;
       char* dst = lds + (q % NBUF) * image_bytes;
       for (int j = 0; j < ni; ++j) {
         const int o = j * 1024 + lane * 16, iy = iy_lo + o / RB;

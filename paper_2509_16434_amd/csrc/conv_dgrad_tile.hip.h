@@ -129,7 +129,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       const int t = blockIdx.x + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int oy_lo = band * TQ;
-      const char* src = reinterpret_cast<const char*>(a.dy.ptr(img)) + (int64_t)oy_lo * rowbytes;
+      const char* src = reinterpret_cast<const char*>(a.dy.ptr_uniform(img)) + (int64_t)oy_lo * rowbytes;
       char* dst = lds + (q % NBUF) * dyimg_bytes;
       for (int row = lw; row <= TQ; row += 2) {
         const bool inside = oy_lo + row < a.Ho;
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
         // input-image rows 4*band*TQ - 1 ... + 4*TQ, as they are (rows outside the image: zeros); the rows
         // follow each other in memory and in LDS, so one load moves 1 KiB of them
         const int iy0 = 4 * band * TQ - 1;
-        const char* isrc = reinterpret_cast<const char*>(a.img0.ptr(img)) + (int64_t)iy0 * RB0;
+        const char* isrc = reinterpret_cast<const char*>(a.img0.ptr_uniform(img)) + (int64_t)iy0 * RB0;
         char* idst = img0_ring + (q % NBUF) * img0_bytes;
         for (int j = lw; j < nld0; j += 2) {
           const int o = j * 1024 + lane * 16, iy = iy0 + o / RB0;

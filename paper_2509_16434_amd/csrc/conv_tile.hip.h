@@ -117,7 +117,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
       const int t = blockIdx.x + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int iy_lo = 2 * band * TR - 1;
-      const char* src = reinterpret_cast<const char*>(a.in.ptr(img)) + (int64_t)iy_lo * rowbytes;
+      const char* src = reinterpret_cast<const char*>(a.in.ptr_uniform(img)) + (int64_t)iy_lo * rowbytes;
       char* dst = lds + (q % NBUF) * image_bytes + PIX;  // skip the left pad
       for (int row = lw; row < nrows; row += 4) {
         const int iy = iy_lo + row;
@@ -314,9 +314,9 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
       const int t = blockIdx.x + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int iy_lo = 2 * band * TR - 1;
-      const char* xsrc = reinterpret_cast<const char*>(a.in.ptr(img)) + (int64_t)iy_lo * rowbytes;
+      const char* xsrc = reinterpret_cast<const char*>(a.in.ptr_uniform(img)) + (int64_t)iy_lo * rowbytes;
       const int plim = min(TR, a.Ho - band * TR) * Wo;  // pixels of the band that exist
-      const bf16_t* dsrc = a.dy.ptr(img) + (int64_t)band * TR * Wo * a.Cout + nb0;
+      const bf16_t* dsrc = a.dy.ptr_uniform(img) + (int64_t)band * TR * Wo * a.Cout + nb0;
       char* buf = lds + (q % NBUF) * buf_bytes;
       const char* zp = reinterpret_cast<const char*>(a.zpage) + lane * 16;
       for (int row = lw; row < nrows; row += 4) {
