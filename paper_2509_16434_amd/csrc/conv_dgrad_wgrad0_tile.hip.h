@@ -1,0 +1,271 @@
+// Input gradient of the second convolution (64 gradient channels -> 32 channels, 3x3 stride 2
+// pad 1, transposed) fused with the weight gradient of the first convolution, whose input is the
+// C0-channel observation image (C0 = 1 or 3).  The gradient of the first layer's output lives only
+// in registers: it goes from the accumulators of the transposed convolution straight into the
+// operands of the weight-gradient product.
+//
+// Quads (2x2 blocks of result pixels, see conv_dgrad_tile.hip.h) are the rows of the first product:
+// D1[quad][ci] = sum over co of dY[pixel of the quad][co] * Wt[tap][ci][co], one accumulator per
+// pixel class, with 16x16x32 MFMAs.  A lane of the result then holds, for ONE channel ci, four
+// consecutive quads of each class: exactly the shape of the first operand of the second product
+// G0[ci][k0] += sum over pixels of dXmasked[pixel][ci] * patch[pixel][k0], whose contraction index
+// (32 per MFMA) runs over 4 lane groups x (2 horizontal classes x 4 quads).  The other operand,
+// patch[pixel][k0], is gathered from the band's image rows in LDS with 2-byte reads by lane
+// (k0 = lane % 16, same pixels).  The ReLU mask of the first layer's output arrives as one 32-bit
+// word per pixel (bit = channel); a lane keeps its value when bit ci of the pixel's word is set.
+//
+// A block has four or eight compute waves and four loader waves.  Compute wave w works on channels
+// 16*(w&1) .. +15 (72 weight registers) and on quads 64*(w>>1) .. +63 of the tile (32 quads per
+// compute wave); with eight, two compute waves share a SIMD and hide each other's LDS latency.  The
+// loaders copy, per band, the dY rows (TQ+1), the image rows (4*TQ+1) and the mask words (2*TQ rows)
+// into a ring of three LDS slots with LDS-writing 16-byte loads, 1 KiB per instruction; rows outside
+// the images come from a page of zeros, so no lane tests a row bound.  One barrier per tile: the
+// loaders arrive when the band has landed, the compute waves when they are done with the previous
+// one.  Per-quad LDS offsets (mask words of both pixel rows, image window, left-edge flag) are the
+// same for every tile and sit in four small tables.  Each block leaves one fp32 partial
+// [32][9*C0+1] (last column: bias gradient, from a constant-one patch column).
+#pragma once
+#include "conv_dgrad_tile.hip.h"
+
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <int NCW>  // compute waves: 4 or 8
+struct ConvDgradW0Shape {
+  static constexpr int CI = 32, CO = 64, BQ = 32 * NCW, NBUF = 3, NLW = 4, THREADS = (NCW + NLW) * 64;
+  static int dyimg_bytes(int Wo, int TQ) { return (TQ + 1) * (Wo + 1) * 128; }
+  static int img0_bytes(int W0, int C0, int TQ) { return (4 * TQ + 1) * W0 * C0 * 2; }
+  static int mask_bytes(int W, int TQ) { return 2 * TQ * W * 4; }
+  static int slot_bytes(int W, int Wo, int W0, int C0, int TQ) { return dyimg_bytes(Wo, TQ) + img0_bytes(W0, C0, TQ) + 16 + mask_bytes(W, TQ) + 16; }
+  static int ring_bytes(int W, int Wo, int W0, int C0, int TQ) {
+    const int r = NBUF * slot_bytes(W, Wo, W0, C0, TQ);
+    return r > NCW * 2048 ? r : NCW * 2048;  // the final sums of the wave pairs reuse the ring
+  }
+  static int lds_bytes(int W, int Wo, int W0, int C0, int TQ) { return ring_bytes(W, Wo, W0, C0, TQ) + 4 * BQ * 4; }
+  static int loads_per_band(int W, int Wo, int W0, int C0, int TQ) {
+    return (TQ + 1) * ((Wo * 128 + 1023) / 1024) + (img0_bytes(W0, C0, TQ) + 1023) / 1024 + (mask_bytes(W, TQ) + 1023) / 1024;
+  }
+};
+
+// Requires (checked by the host): W % 4 == 0, (W0 * C0 * 2) % 16 == 0, Wo == W / 2 <= BQ, TQ * Wo <= BQ.
+template <int C0, int NCW>
+__global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvDgradArgs a) {
+  typedef ConvDgradW0Shape<NCW> S;
+  constexpr int BQ = S::BQ;
+  constexpr int NBUF = S::NBUF, K0 = 9 * C0, NV = K0 + 1, NT = (NV + 15) / 16;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int W = a.W, Wo = a.Wo, TQ = a.TQ;
+  const int RP = (Wo + 1) * 128, dyimg_bytes = (TQ + 1) * RP;  // dY image: row pitch, bytes
+  const int RB0 = a.W0 * C0 * 2, img0_bytes = (4 * TQ + 1) * RB0;
+  const int MRB = W * 4, mask_bytes = 2 * TQ * MRB;
+  // slot: dY image | image rows | 16 zero bytes | mask words | 16 zero bytes
+  const int OFF_IMG = dyimg_bytes, OFF_MSK = OFF_IMG + img0_bytes + 16, OFF_Z = OFF_MSK + mask_bytes, SLOT = OFF_Z + 16;
+  const int ring_bytes = NBUF * SLOT > NCW * 2048 ? NBUF * SLOT : NCW * 2048;
+  char* const tbl = lds + ring_bytes;  // int [4][BQ]: mask offset of pixel row 0, of row 1, image offset, left-edge keep mask
+  const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
+
+  // ---- once: the zero pads no load ever writes, and the quad tables
+  for (int i = tid; i < NBUF * (TQ + 1) * 8; i += S::THREADS) {
+    const int chunk = i & 7, row = i >> 3, s = row / (TQ + 1), rr = row - s * (TQ + 1);
+    *reinterpret_cast<uint4*>(lds + s * SLOT + rr * RP + Wo * 128 + chunk * 16) = make_uint4(0u, 0u, 0u, 0u);
+  }
+  if (tid < NBUF * 2) {
+    const int s = tid >> 1, off = (tid & 1) ? OFF_Z : OFF_IMG + img0_bytes;
+    *reinterpret_cast<uint4*>(lds + s * SLOT + off) = make_uint4(0u, 0u, 0u, 0u);
+  }
+  for (int qi = tid; qi < BQ; qi += S::THREADS) {
+    const bool valid = qi < TQ * Wo;
+    const int al = valid ? qi / Wo : 0, b = valid ? qi - al * Wo : 0;
+    int* t = reinterpret_cast<int*>(tbl);
+    // quads beyond the band read the zero words behind the mask (both pixel rows) and any real window
+    t[qi] = valid ? ((2 * al) * W + 2 * b) * 4 : mask_bytes;
+    t[BQ + qi] = valid ? ((2 * al + 1) * W + 2 * b) * 4 : mask_bytes;
+    t[2 * BQ + qi] = 4 * al * RB0 + 8 * b * C0;
+    t[3 * BQ + qi] = (valid && b == 0) ? 0 : -1;  // the window column left of the image is dropped for b == 0
+  }
+
+  if (wave >= NCW) {
+    // ------------------------------------------------------------------ loaders: piece i of a band belongs to loader i % 4
+    const int lw = wave - NCW;
+    const int rowbytes = Wo * 128, segs = (rowbytes + 1023) >> 10;
+    const int n_dy = (TQ + 1) * segs, n_im = (img0_bytes + 1023) >> 10, n_mk = (mask_bytes + 1023) >> 10;
+    const int nl = n_dy + n_im + n_mk;
+    const int ni = nl > lw ? (nl - lw + S::NLW - 1) / S::NLW : 0;  // this wave's loads per band
+    const char* const zp = reinterpret_cast<const char*>(a.zpage) + lane * 16;
+    auto issue = [&](int q) __attribute__((always_inline)) {
+      const int t = blockIdx.x + q * gridDim.x;
+      const int img = t / a.NB, band = t - img * a.NB;
+      char* const slot = lds + (q % NBUF) * SLOT;
+      const int oy_lo = band * TQ, iy0 = 4 * band * TQ - 1, my0 = 2 * band * TQ;
+      const char* dsrc = reinterpret_cast<const char*>(a.dy.ptr_uniform(img)) + (int64_t)oy_lo * rowbytes;
+      const char* isrc = reinterpret_cast<const char*>(a.img0.ptr_uniform(img)) + (int64_t)iy0 * RB0;
+      const char* msrc = reinterpret_cast<const char*>(a.xbits + ((int64_t)img * a.H + my0) * W);
+      for (int i = lw; i < nl; i += S::NLW) {
+        if (i < n_dy) {
+          // a dY row; the 16-byte chunks of a pixel are permuted (dy_swz_bits) through the source address
+          const int row = i / segs, sg = i - row * segs;
+          const uint32_t phys = sg * 1024 + lane * 16, logi = phys ^ dy_swz_bits(phys);
+          const char* p = (oy_lo + row < a.Ho) ? dsrc + (int64_t)row * rowbytes + logi : zp;
+          if ((int)phys < rowbytes) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + row * RP + sg * 1024), 16, 0, 0);
+        } else if (i < n_dy + n_im) {
+          // image rows iy0 ... iy0 + 4*TQ: one contiguous span in memory and in LDS
+          const int j = i - n_dy, o = j * 1024 + lane * 16, iy = iy0 + (int)a.dv_rb0.div((uint32_t)o);
+          const char* p = (iy >= 0 && iy < a.H0) ? isrc + o : zp;
+          if (o < img0_bytes) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + OFF_IMG + j * 1024), 16, 0, 0);
+        } else {
+          // mask words of pixel rows my0 ... my0 + 2*TQ - 1, contiguous as well
+          const int j = i - n_dy - n_im, o = j * 1024 + lane * 16, my = my0 + (int)a.dv_mrow.div((uint32_t)o);
+          const char* p = (my < a.H) ? msrc + o : zp;
+          if (o < mask_bytes) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + OFF_MSK + j * 1024), 16, 0, 0);
+        }
+      }
+    };
+    if (nq > 0) issue(0);
+    if (nq > 1) issue(1);
+    __builtin_amdgcn_s_barrier();
+    for (int q = 0; q < nq; ++q) {
+      vm_wait_dyn(q + 1 < nq ? ni : 0);  // band q has landed
+      __builtin_amdgcn_s_barrier();      // A(q); the compute waves have left band q - 1
+      if (q + 2 < nq) issue(q + 2);
+    }
+    __builtin_amdgcn_s_barrier();        // C
+    __builtin_amdgcn_s_barrier();        // D
+    return;
+  }
+
+  // -------------------------------------------------------------------- compute waves
+  const int l16 = lane & 15, r = lane >> 4, ch = wave & 1, gp = wave >> 1;
+  // weights, second operand of the first product: lane (column ci = ch*16 + l16, 8 co at ks*32 + r*8) of tap s
+  bf16x8_t wr[9][2];
+#pragma unroll
+  for (int s = 0; s < 9; ++s)
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+      wr[s][ks] = *reinterpret_cast<const bf16x8_t*>(a.wt + ((int64_t)s * 32 + ch * 16 + l16) * 64 + ks * 32 + r * 8);
+  // first operand: lane (row = quad gp*64 + m*16 + l16, 8 co at ks*32 + r*8); the quad's place in a dY image
+  int dyoff[4];
+  uint32_t cx[4][2];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const int qi = gp * 64 + m * 16 + l16;
+    const bool valid = qi < TQ * Wo;  // lanes beyond the band work on quad 0; their results meet zero mask words
+    const int al = valid ? qi / Wo : 0, b = valid ? qi - al * Wo : 0;
+    dyoff[m] = al * RP + b * 128;
+#pragma unroll
+    for (int dxo = 0; dxo < 2; ++dxo) cx[m][dxo] = (uint32_t)(r * 16) ^ dy_swz_bits((uint32_t)((b + dxo) * 128));
+  }
+  const int cibit = ch * 16 + l16;  // this lane's channel as a result column: its bit in a mask word
+  // second product, second operand: lane (column k0 = nt*16 + l16, pixels of lane group r)
+  int toffl[NT];
+  uint32_t lnv0[NT], lmask[NT], bconst[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int k0 = nt * 16 + l16;
+    const bool real = k0 < K0;
+    const int tap = real ? k0 / C0 : 1, cch = real ? k0 - tap * C0 : 0, u = tap / 3, v = tap - 3 * u;
+    toffl[nt] = u * RB0 + ((v - 1) * C0 + cch) * 2;  // window corner is (row - 1, column - 1)
+    lnv0[nt] = v != 0 ? 0xffffffffu : 0u;
+    lmask[nt] = real ? 0xffffffffu : 0u;
+    bconst[nt] = k0 == K0 ? 0x3F803F80u : 0u;  // the bias column: 1.0
+  }
+  const char* const tq = tbl + (gp * 64 + r * 4) * 4;  // this lane's four quads of M-tile m: + m*64 (+ BQ*4 per table)
+  f32x4_t accw[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) accw[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  auto dgrad = [&](const char* slot, int m, f32x4_t (&acc)[4]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const char* base = slot + dyoff[m];
+#pragma unroll
+    for (int pi = 0; pi < 4; ++pi) {
+      const int dyo = pi >> 1, dxo = pi & 1;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8_t x = *reinterpret_cast<const bf16x8_t*>(base + dyo * RP + dxo * 128 + ((uint32_t)(ks * 64) ^ cx[m][dxo]));
+        // class (py, px) takes tap row py ? (dyo ? 0 : 2) : 1 from row offset dyo (even rows only from dyo = 0), same for columns
+        if (pi == 0) {
+          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wr[1 * 3 + 1][ks], acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wr[1 * 3 + 2][ks], acc[1], 0, 0, 0);
+          acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wr[2 * 3 + 1][ks], acc[2], 0, 0, 0);
+          acc[3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wr[2 * 3 + 2][ks], acc[3], 0, 0, 0);
+        } else if (pi == 1) {
+          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wr[1 * 3 + 0][ks], acc[1], 0, 0, 0);
+          acc[3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wr[2 * 3 + 0][ks], acc[3], 0, 0, 0);
+        } else if (pi == 2) {
+          acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wr[0 * 3 + 1][ks], acc[2], 0, 0, 0);
+          acc[3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wr[0 * 3 + 2][ks], acc[3], 0, 0, 0);
+        } else {
+          acc[3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wr[0 * 3 + 0][ks], acc[3], 0, 0, 0);
+        }
+      }
+    }
+  };
+  // acc[c][i] = dX[quad gp*64 + m*16 + r*4 + i, class c][ci]
+  auto wgrad = [&](const char* slot, int m, const f32x4_t (&acc)[4]) __attribute__((always_inline)) {
+    const char* tp = tq + m * 64;
+    const int4 io4 = *reinterpret_cast<const int4*>(tp + 2 * BQ * 4);
+    const int4 kp4 = *reinterpret_cast<const int4*>(tp + 3 * BQ * 4);
+    const int io[4] = {io4.x, io4.y, io4.z, io4.w};
+    const int kp[4] = {kp4.x, kp4.y, kp4.z, kp4.w};
+#pragma unroll
+    for (int py = 0; py < 2; ++py) {
+      const int4 mo4 = *reinterpret_cast<const int4*>(tp + py * BQ * 4);
+      const int mo[4] = {mo4.x, mo4.y, mo4.z, mo4.w};
+      float v0[4], v1[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint2 w = *reinterpret_cast<const uint2*>(slot + OFF_MSK + mo[i]);  // the words of the quad's two pixels in this row
+        const int k0 = __builtin_amdgcn_sbfe((int)w.x, (uint32_t)cibit, 1u), k1 = __builtin_amdgcn_sbfe((int)w.y, (uint32_t)cibit, 1u);
+        const float d0 = acc[py * 2][i], d1 = acc[py * 2 + 1][i];
+        v0[i] = __int_as_float(__float_as_int(d0) & k0);
+        v1[i] = __int_as_float(__float_as_int(d1) & k1);
+      }
+      const bf16x8_t av = __builtin_bit_cast(bf16x8_t, make_uint4(pack2bf(v0[0], v0[1]), pack2bf(v0[2], v0[3]), pack2bf(v1[0], v1[1]), pack2bf(v1[2], v1[3])));
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        uint32_t x0[4], x1[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const char* p = slot + OFF_IMG + io[i] + 2 * py * RB0 + toffl[nt];
+          x0[i] = (uint32_t)*reinterpret_cast<const unsigned short*>(p) & ((uint32_t)kp[i] | lnv0[nt]);
+          x1[i] = (uint32_t)*reinterpret_cast<const unsigned short*>(p + 4 * C0);
+        }
+        uint4 bq = make_uint4(x0[0] | (x0[1] << 16), x0[2] | (x0[3] << 16), x1[0] | (x1[1] << 16), x1[2] | (x1[3] << 16));
+        bq.x = (bq.x & lmask[nt]) | bconst[nt]; bq.y = (bq.y & lmask[nt]) | bconst[nt];
+        bq.z = (bq.z & lmask[nt]) | bconst[nt]; bq.w = (bq.w & lmask[nt]) | bconst[nt];
+        accw[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8_t, bq), accw[nt], 0, 0, 0);
+      }
+    }
+  };
+
+  __builtin_amdgcn_s_barrier();
+  for (int q = 0; q < nq; ++q) {
+    __builtin_amdgcn_s_barrier();  // A(q): band q is in LDS
+    const char* slot = lds + (q % NBUF) * SLOT;
+    // the first product of M-tile m + 1 is independent of the second product of M-tile m
+    f32x4_t acc[2][4];
+    dgrad(slot, 0, acc[0]);
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      if (m + 1 < 4) dgrad(slot, m + 1, acc[(m + 1) & 1]);
+      wgrad(slot, m, acc[m & 1]);
+    }
+  }
+  __builtin_amdgcn_s_barrier();    // C: nobody reads the ring any more
+  float* const red = reinterpret_cast<float*>(lds);
+  // accw[nt][i] = G0[ci = ch*16 + r*4 + i][k0 = nt*16 + l16], summed over this wave's quads
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) red[(gp * 32 + ch * 16 + r * 4 + i) * 32 + nt * 16 + l16] = accw[nt][i];
+  __builtin_amdgcn_s_barrier();    // D
+  float* P = a.partial0 + (int64_t)blockIdx.x * 32 * NV;
+  for (int i = tid; i < 32 * NV; i += NCW * 64) {
+    const int ci = i / NV, k = i - ci * NV;
+    float sum = 0.f;
+#pragma unroll
+    for (int g = 0; g < NCW / 2; ++g) sum += red[g * 1024 + ci * 32 + k];
+    P[i] = sum;
+  }
+}

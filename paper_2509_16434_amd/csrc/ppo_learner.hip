@@ -18,6 +18,7 @@
 #include "fused.hip.h"
 #include "conv_tile.hip.h"
 #include "conv_dgrad_tile.hip.h"
+#include "conv_dgrad_wgrad0_tile.hip.h"
 #include "conv0_tile.hip.h"
 
 static_assert(sizeof(DevStats) == sizeof(ppo_mb_stats), "device and host statistics records must match");
@@ -546,12 +547,47 @@ int launch_conv_dgrad_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, const u
   return Ci == 32 ? launch_conv_dgrad_tile_t<32, 0>(c, a, nimg, name, flops, abytes, nullptr)
                   : launch_conv_dgrad_tile_t<64, 0>(c, a, nimg, name, flops, abytes, nullptr);
 }
+// Register-fused form of the same pair of layers (conv_dgrad_wgrad0_tile.hip.h); returns 1 when the shape is not covered.
+template <int C0, int NCW>
+int launch_conv_dgrad_wgrad0_reg_t(Ctx* c, ConvDgradArgs a, int nimg, const std::string& name, double flops, double abytes, int* grid_out) {
+  typedef ConvDgradW0Shape<NCW> S;
+  const int rb0 = a.W0 * C0 * 2;
+  if (a.W % 4 || rb0 % 16 || a.Wo * 2 != a.W || a.Wo > S::BQ || a.H != (a.H0 + 1) / 2 || a.W * 2 != a.W0) return 1;
+  auto fits = [&](int tq) {
+    return tq * a.Wo <= S::BQ && S::lds_bytes(a.W, a.Wo, a.W0, C0, tq) <= 158 * 1024 && cdiv(S::loads_per_band(a.W, a.Wo, a.W0, C0, tq), S::NLW) <= 63;
+  };
+  int TQ = S::BQ / a.Wo < a.Ho ? S::BQ / a.Wo : a.Ho;
+  while (TQ > 1 && !fits(TQ)) --TQ;
+  if (TQ < 1 || !fits(TQ)) return 1;
+  a.NB = cdiv(a.Ho, TQ); a.TQ = cdiv(a.Ho, a.NB); a.NB = cdiv(a.Ho, a.TQ); a.ntiles = nimg * a.NB;
+  a.dv_rb0 = make_fastdiv(rb0); a.dv_mrow = make_fastdiv(a.W * 4);
+  int gx = a.ntiles < 256 ? a.ntiles : 256;
+  const int64_t npair = (int64_t)S::CI * (9 * C0 + 1);
+  if (gx * npair > c->partial_elems) gx = (int)(c->partial_elems / npair);
+  if (gx < 1) return 1;
+  a.partial0 = c->partial;
+  *grid_out = gx;
+  auto kfn = k_conv_dgrad_wgrad0_tile<C0, NCW>;
+  static bool attr_set = false;
+  if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_set = true; }
+  ProfScope ps(c, name, flops, abytes);
+  hipLaunchKernelGGL(kfn, dim3(gx), dim3(S::THREADS), S::lds_bytes(a.W, a.Wo, a.W0, C0, a.TQ), c->stream, a);
+  LAUNCHCHK(c, "k_conv_dgrad_wgrad0_tile");
+  return PPO_OK;
+}
 // The same with the first layer's weight gradient fused in (depth or RGB input, 32 channels after the first layer).
 int launch_conv_dgrad_wgrad0_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, const uint32_t* xbits, const bf16_t* wt, int Co, int Ci, int H, int W, int Ho, int Wo,
                                   const ImgAddr& img0, int C0, int H0, int W0, int nimg, const std::string& name, double flops, double abytes, int* grid_out) {
   if (Co != 64 || Ci != 32 || (C0 != 1 && C0 != 3) || dy.idx || nimg < 1 || !xbits) return 1;
   ConvDgradArgs a = conv_dgrad_args(c, dy, xa, xbits, nullptr, wt, H, W, Ho, Wo);
   a.img0 = img0; a.img0.prepare(); a.H0 = H0; a.W0 = W0;
+  // eight compute waves (two per SIMD) when the larger tile fits, else four
+  int rrc = C0 == 1 ? launch_conv_dgrad_wgrad0_reg_t<1, 8>(c, a, nimg, name, flops, abytes, grid_out)
+                    : launch_conv_dgrad_wgrad0_reg_t<3, 8>(c, a, nimg, name, flops, abytes, grid_out);
+  if (rrc == 1)
+    rrc = C0 == 1 ? launch_conv_dgrad_wgrad0_reg_t<1, 4>(c, a, nimg, name, flops, abytes, grid_out)
+                  : launch_conv_dgrad_wgrad0_reg_t<3, 4>(c, a, nimg, name, flops, abytes, grid_out);
+  if (rrc != 1) return rrc;
   return C0 == 1 ? launch_conv_dgrad_tile_t<32, 1>(c, a, nimg, name, flops, abytes, grid_out)
                  : launch_conv_dgrad_tile_t<32, 3>(c, a, nimg, name, flops, abytes, grid_out);
 }
