@@ -21,9 +21,15 @@
 // into a ring of three LDS slots with LDS-writing 16-byte loads, 1 KiB per instruction; rows outside
 // the images come from a page of zeros, so no lane tests a row bound.  One barrier per tile: the
 // loaders arrive when the band has landed, the compute waves when they are done with the previous
-// one.  Per-quad LDS offsets (mask words of both pixel rows, image window, left-edge flag) are the
-// same for every tile and sit in four small tables.  Each block leaves one fp32 partial
-// [32][9*C0+1] (last column: bias gradient, from a constant-one patch column).
+// one.
+//
+// The LDS pipe is the scarce resource here, so the second product reads as little as it can: the
+// width in quads is a multiple of four, hence the four quads of a lane are neighbours in one row,
+// their eight mask words are 32 contiguous bytes (two 16-byte reads) and, for one-channel images,
+// the eight window values of a tap are the low or high halves of eight consecutive dwords (read as
+// dwords, halves picked with a byte permute).  Every LDS offset of the second product is a per-lane
+// constant plus an immediate.  Each block leaves one fp32 partial [32][9*C0+1] (last column: bias
+// gradient, from a constant-one patch column).
 #pragma once
 #include "conv_dgrad_tile.hip.h"
 
@@ -35,18 +41,18 @@ struct ConvDgradW0Shape {
   static int dyimg_bytes(int Wo, int TQ) { return (TQ + 1) * (Wo + 1) * 128; }
   static int img0_bytes(int W0, int C0, int TQ) { return (4 * TQ + 1) * W0 * C0 * 2; }
   static int mask_bytes(int W, int TQ) { return 2 * TQ * W * 4; }
-  static int slot_bytes(int W, int Wo, int W0, int C0, int TQ) { return dyimg_bytes(Wo, TQ) + img0_bytes(W0, C0, TQ) + 16 + mask_bytes(W, TQ) + 16; }
+  static int slot_bytes(int W, int Wo, int W0, int C0, int TQ) { return dyimg_bytes(Wo, TQ) + img0_bytes(W0, C0, TQ) + 16 + mask_bytes(W, TQ) + 32; }
   static int ring_bytes(int W, int Wo, int W0, int C0, int TQ) {
     const int r = NBUF * slot_bytes(W, Wo, W0, C0, TQ);
     return r > NCW * 2048 ? r : NCW * 2048;  // the final sums of the wave pairs reuse the ring
   }
-  static int lds_bytes(int W, int Wo, int W0, int C0, int TQ) { return ring_bytes(W, Wo, W0, C0, TQ) + 4 * BQ * 4; }
+  static int lds_bytes(int W, int Wo, int W0, int C0, int TQ) { return ring_bytes(W, Wo, W0, C0, TQ); }
   static int loads_per_band(int W, int Wo, int W0, int C0, int TQ) {
     return (TQ + 1) * ((Wo * 128 + 1023) / 1024) + (img0_bytes(W0, C0, TQ) + 1023) / 1024 + (mask_bytes(W, TQ) + 1023) / 1024;
   }
 };
 
-// Requires (checked by the host): W % 4 == 0, (W0 * C0 * 2) % 16 == 0, Wo == W / 2 <= BQ, TQ * Wo <= BQ.
+// Requires (checked by the host): W % 8 == 0 (Wo % 4 == 0), (W0 * C0 * 2) % 16 == 0, Wo == W / 2 <= BQ, TQ * Wo <= BQ.
 template <int C0, int NCW>
 __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvDgradArgs a) {
   typedef ConvDgradW0Shape<NCW> S;
@@ -58,30 +64,18 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
   const int RP = (Wo + 1) * 128, dyimg_bytes = (TQ + 1) * RP;  // dY image: row pitch, bytes
   const int RB0 = a.W0 * C0 * 2, img0_bytes = (4 * TQ + 1) * RB0;
   const int MRB = W * 4, mask_bytes = 2 * TQ * MRB;
-  // slot: dY image | image rows | 16 zero bytes | mask words | 16 zero bytes
-  const int OFF_IMG = dyimg_bytes, OFF_MSK = OFF_IMG + img0_bytes + 16, OFF_Z = OFF_MSK + mask_bytes, SLOT = OFF_Z + 16;
-  const int ring_bytes = NBUF * SLOT > NCW * 2048 ? NBUF * SLOT : NCW * 2048;
-  char* const tbl = lds + ring_bytes;  // int [4][BQ]: mask offset of pixel row 0, of row 1, image offset, left-edge keep mask
+  // slot: dY image | image rows | 16 zero bytes | mask words | 32 zero bytes
+  const int OFF_IMG = dyimg_bytes, OFF_MSK = OFF_IMG + img0_bytes + 16, OFF_Z = OFF_MSK + mask_bytes, SLOT = OFF_Z + 32;
   const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
 
-  // ---- once: the zero pads no load ever writes, and the quad tables
+  // ---- once: the zero pads no load ever writes
   for (int i = tid; i < NBUF * (TQ + 1) * 8; i += S::THREADS) {
     const int chunk = i & 7, row = i >> 3, s = row / (TQ + 1), rr = row - s * (TQ + 1);
     *reinterpret_cast<uint4*>(lds + s * SLOT + rr * RP + Wo * 128 + chunk * 16) = make_uint4(0u, 0u, 0u, 0u);
   }
-  if (tid < NBUF * 2) {
-    const int s = tid >> 1, off = (tid & 1) ? OFF_Z : OFF_IMG + img0_bytes;
+  if (tid < NBUF * 3) {
+    const int s = tid / 3, k = tid - 3 * s, off = k == 0 ? OFF_IMG + img0_bytes : OFF_Z + (k - 1) * 16;
     *reinterpret_cast<uint4*>(lds + s * SLOT + off) = make_uint4(0u, 0u, 0u, 0u);
-  }
-  for (int qi = tid; qi < BQ; qi += S::THREADS) {
-    const bool valid = qi < TQ * Wo;
-    const int al = valid ? qi / Wo : 0, b = valid ? qi - al * Wo : 0;
-    int* t = reinterpret_cast<int*>(tbl);
-    // quads beyond the band read the zero words behind the mask (both pixel rows) and any real window
-    t[qi] = valid ? ((2 * al) * W + 2 * b) * 4 : mask_bytes;
-    t[BQ + qi] = valid ? ((2 * al + 1) * W + 2 * b) * 4 : mask_bytes;
-    t[2 * BQ + qi] = 4 * al * RB0 + 8 * b * C0;
-    t[3 * BQ + qi] = (valid && b == 0) ? 0 : -1;  // the window column left of the image is dropped for b == 0
   }
 
   if (wave >= NCW) {
@@ -157,18 +151,34 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
   const int cibit = ch * 16 + l16;  // this lane's channel as a result column: its bit in a mask word
   // second product, second operand: lane (column k0 = nt*16 + l16, pixels of lane group r)
   int toffl[NT];
-  uint32_t lnv0[NT], lmask[NT], bconst[NT];
+  uint32_t lnv0[NT], lmask[NT], bconst[NT], hsel[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int k0 = nt * 16 + l16;
     const bool real = k0 < K0;
     const int tap = real ? k0 / C0 : 1, cch = real ? k0 - tap * C0 : 0, u = tap / 3, v = tap - 3 * u;
-    toffl[nt] = u * RB0 + ((v - 1) * C0 + cch) * 2;  // window corner is (row - 1, column - 1)
+    // window corner is (row - 1, column - 1).  One-channel images are read as dwords: column 4b + 2px + v - 1
+    // is the high half of dword 2b + px - 1 (v = 0), the low (v = 1) or high (v = 2) half of dword 2b + px.
+    toffl[nt] = C0 == 1 ? u * RB0 + (v == 0 ? -4 : 0) : u * RB0 + ((v - 1) * C0 + cch) * 2;
+    hsel[nt] = !real ? 0x0c0c0c0cu : (v == 1 ? 0x05040100u : 0x07060302u);  // selector bytes 0x0c give zero
     lnv0[nt] = v != 0 ? 0xffffffffu : 0u;
     lmask[nt] = real ? 0xffffffffu : 0u;
     bconst[nt] = k0 == K0 ? 0x3F803F80u : 0u;  // the bias column: 1.0
   }
-  const char* const tq = tbl + (gp * 64 + r * 4) * 4;  // this lane's four quads of M-tile m: + m*64 (+ BQ*4 per table)
+  // this lane's four quads of M-tile m are q0 .. q0 + 3, q0 = gp*64 + m*16 + r*4, neighbours in one quad row;
+  // groups beyond the band read the zero words behind the mask (both pixel rows) and any real window
+  int mo[4][2], go[4];
+  uint32_t kp[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const int q0 = gp * 64 + m * 16 + r * 4;
+    const bool valid = q0 < TQ * Wo;
+    const int al = valid ? q0 / Wo : 0, b = valid ? q0 - al * Wo : 0;
+    mo[m][0] = valid ? OFF_MSK + ((2 * al) * W + 2 * b) * 4 : OFF_Z;
+    mo[m][1] = valid ? mo[m][0] + MRB : OFF_Z;
+    go[m] = OFF_IMG + 4 * al * RB0 + 8 * b * C0;
+    kp[m] = (valid && b == 0) ? 0u : 0xffffffffu;  // the window column left of the image is dropped (lanes of column 0)
+  }
   f32x4_t accw[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) accw[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -203,20 +213,15 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
   };
   // acc[c][i] = dX[quad gp*64 + m*16 + r*4 + i, class c][ci]
   auto wgrad = [&](const char* slot, int m, const f32x4_t (&acc)[4]) __attribute__((always_inline)) {
-    const char* tp = tq + m * 64;
-    const int4 io4 = *reinterpret_cast<const int4*>(tp + 2 * BQ * 4);
-    const int4 kp4 = *reinterpret_cast<const int4*>(tp + 3 * BQ * 4);
-    const int io[4] = {io4.x, io4.y, io4.z, io4.w};
-    const int kp[4] = {kp4.x, kp4.y, kp4.z, kp4.w};
 #pragma unroll
     for (int py = 0; py < 2; ++py) {
-      const int4 mo4 = *reinterpret_cast<const int4*>(tp + py * BQ * 4);
-      const int mo[4] = {mo4.x, mo4.y, mo4.z, mo4.w};
+      // the mask words of the four quads' eight pixels in this row: word 2*i + px
+      const uint4 wa = *reinterpret_cast<const uint4*>(slot + mo[m][py]), wb = *reinterpret_cast<const uint4*>(slot + mo[m][py] + 16);
+      const uint32_t w[8] = {wa.x, wa.y, wa.z, wa.w, wb.x, wb.y, wb.z, wb.w};
       float v0[4], v1[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const uint2 w = *reinterpret_cast<const uint2*>(slot + OFF_MSK + mo[i]);  // the words of the quad's two pixels in this row
-        const int k0 = __builtin_amdgcn_sbfe((int)w.x, (uint32_t)cibit, 1u), k1 = __builtin_amdgcn_sbfe((int)w.y, (uint32_t)cibit, 1u);
+        const int k0 = __builtin_amdgcn_sbfe((int)w[2 * i], (uint32_t)cibit, 1u), k1 = __builtin_amdgcn_sbfe((int)w[2 * i + 1], (uint32_t)cibit, 1u);
         const float d0 = acc[py * 2][i], d1 = acc[py * 2 + 1][i];
         v0[i] = __int_as_float(__float_as_int(d0) & k0);
         v1[i] = __int_as_float(__float_as_int(d1) & k1);
@@ -224,16 +229,28 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
       const bf16x8_t av = __builtin_bit_cast(bf16x8_t, make_uint4(pack2bf(v0[0], v0[1]), pack2bf(v0[2], v0[3]), pack2bf(v1[0], v1[1]), pack2bf(v1[2], v1[3])));
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        uint32_t x0[4], x1[4];
+        const char* p = slot + go[m] + toffl[nt] + 2 * py * RB0;
+        const uint32_t km = kp[m] | lnv0[nt];
+        uint4 bq;
+        if constexpr (C0 == 1) {
+          uint32_t d[8];  // dword k = 2*i + px
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const char* p = slot + OFF_IMG + io[i] + 2 * py * RB0 + toffl[nt];
-          x0[i] = (uint32_t)*reinterpret_cast<const unsigned short*>(p) & ((uint32_t)kp[i] | lnv0[nt]);
-          x1[i] = (uint32_t)*reinterpret_cast<const unsigned short*>(p + 4 * C0);
+          for (int k = 0; k < 8; ++k) d[k] = *reinterpret_cast<const uint32_t*>(p + 4 * k);
+          d[0] &= km;
+          bq = make_uint4(__builtin_amdgcn_perm(d[2], d[0], hsel[nt]), __builtin_amdgcn_perm(d[6], d[4], hsel[nt]),
+                          __builtin_amdgcn_perm(d[3], d[1], hsel[nt]), __builtin_amdgcn_perm(d[7], d[5], hsel[nt]));
+        } else {
+          uint32_t x0[4], x1[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            x0[i] = (uint32_t)*reinterpret_cast<const unsigned short*>(p + 8 * C0 * i);
+            x1[i] = (uint32_t)*reinterpret_cast<const unsigned short*>(p + 8 * C0 * i + 4 * C0);
+          }
+          x0[0] &= km;
+          bq = make_uint4(x0[0] | (x0[1] << 16), x0[2] | (x0[3] << 16), x1[0] | (x1[1] << 16), x1[2] | (x1[3] << 16));
         }
-        uint4 bq = make_uint4(x0[0] | (x0[1] << 16), x0[2] | (x0[3] << 16), x1[0] | (x1[1] << 16), x1[2] | (x1[3] << 16));
-        bq.x = (bq.x & lmask[nt]) | bconst[nt]; bq.y = (bq.y & lmask[nt]) | bconst[nt];
-        bq.z = (bq.z & lmask[nt]) | bconst[nt]; bq.w = (bq.w & lmask[nt]) | bconst[nt];
+        if constexpr (C0 != 1) { bq.x &= lmask[nt]; bq.y &= lmask[nt]; bq.z &= lmask[nt]; bq.w &= lmask[nt]; }
+        bq.x |= bconst[nt]; bq.y |= bconst[nt]; bq.z |= bconst[nt]; bq.w |= bconst[nt];
         accw[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8_t, bq), accw[nt], 0, 0, 0);
       }
     }

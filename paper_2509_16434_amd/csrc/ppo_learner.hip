@@ -552,7 +552,7 @@ template <int C0, int NCW>
 int launch_conv_dgrad_wgrad0_reg_t(Ctx* c, ConvDgradArgs a, int nimg, const std::string& name, double flops, double abytes, int* grid_out) {
   typedef ConvDgradW0Shape<NCW> S;
   const int rb0 = a.W0 * C0 * 2;
-  if (a.W % 4 || rb0 % 16 || a.Wo * 2 != a.W || a.Wo > S::BQ || a.H != (a.H0 + 1) / 2 || a.W * 2 != a.W0) return 1;
+  if (a.W % 8 || rb0 % 16 || a.Wo * 2 != a.W || a.Wo > S::BQ || a.H != (a.H0 + 1) / 2 || a.W * 2 != a.W0) return 1;
   auto fits = [&](int tq) {
     return tq * a.Wo <= S::BQ && S::lds_bytes(a.W, a.Wo, a.W0, C0, tq) <= 158 * 1024 && cdiv(S::loads_per_band(a.W, a.Wo, a.W0, C0, tq), S::NLW) <= 63;
   };

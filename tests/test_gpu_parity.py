@@ -157,7 +157,9 @@ def test_ppo_single_minibatch_gradients(L, ci, N, T, chunk):
 # Shapes that exercise the ragged paths of the LDS-image convolution kernels: odd heights and widths
 # (last quad row / column without a partner, right zero-pad pixel in use), bands that do not divide the
 # image, an image height whose first-layer output is odd.
-ODD_SHAPES = [(52, 76), (50, 72), (44, 88)]
+# (50, 96) and (36, 80) have a first-layer output width that is a multiple of 8: the register-fused
+# first-layer weight gradient takes them (odd output height, bands that do not divide the image).
+ODD_SHAPES = [(52, 76), (50, 72), (44, 88), (50, 96), (36, 80)]
 
 
 @pytest.mark.parametrize("h,w", ODD_SHAPES)
