@@ -38,6 +38,7 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 template <int NCW>  // compute waves: 4 or 8
 struct ConvDgradW0Shape {
   static constexpr int CI = 32, CO = 64, BQ = 32 * NCW, NBUF = 3, NLW = 4, THREADS = (NCW + NLW) * 64;
+  static constexpr int MAXD = 12, MAXI = 4, MAXM = 2;  // 1 KiB loads per loader wave and band: dY, image rows, mask words
   static int dyimg_bytes(int Wo, int TQ) { return (TQ + 1) * (Wo + 1) * 128; }
   static int img0_bytes(int W0, int C0, int TQ) { return (4 * TQ + 1) * W0 * C0 * 2; }
   static int mask_bytes(int W, int TQ) { return 2 * TQ * W * 4; }
@@ -47,8 +48,9 @@ struct ConvDgradW0Shape {
     return r > NCW * 2048 ? r : NCW * 2048;  // the final sums of the wave pairs reuse the ring
   }
   static int lds_bytes(int W, int Wo, int W0, int C0, int TQ) { return ring_bytes(W, Wo, W0, C0, TQ); }
-  static int loads_per_band(int W, int Wo, int W0, int C0, int TQ) {
-    return (TQ + 1) * ((Wo * 128 + 1023) / 1024) + (img0_bytes(W0, C0, TQ) + 1023) / 1024 + (mask_bytes(W, TQ) + 1023) / 1024;
+  static bool loads_fit(int W, int Wo, int W0, int C0, int TQ) {
+    return (TQ + 1) * ((Wo * 128 + 1023) / 1024) <= MAXD * NLW && (img0_bytes(W0, C0, TQ) + 1023) / 1024 <= MAXI * NLW &&
+           (mask_bytes(W, TQ) + 1023) / 1024 <= MAXM * NLW;
   }
 };
 
@@ -83,43 +85,83 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     const int lw = wave - NCW;
     const int rowbytes = Wo * 128, segs = (rowbytes + 1023) >> 10;
     const int n_dy = (TQ + 1) * segs, n_im = (img0_bytes + 1023) >> 10, n_mk = (mask_bytes + 1023) >> 10;
-    const int nl = n_dy + n_im + n_mk;
-    const int ni = nl > lw ? (nl - lw + S::NLW - 1) / S::NLW : 0;  // this wave's loads per band
+    // piece j of a kind (dY row parts, 1 KiB pieces of the image rows, of the mask words) belongs to loader j % 4
+    auto mine = [&](int n) { return n > lw ? (n - lw + S::NLW - 1) / S::NLW : 0; };
+    const int nd = mine(n_dy), nm_i = mine(n_im), nm_m = mine(n_mk);
+    const int ni = nd + nm_i + nm_m;  // this wave's loads per band
     const char* const zp = reinterpret_cast<const char*>(a.zpage) + lane * 16;
-    auto issue = [&](int q) __attribute__((always_inline)) {
-      const int t = blockIdx.x + q * gridDim.x;
-      const int img = t / a.NB, band = t - img * a.NB;
-      char* const slot = lds + (q % NBUF) * SLOT;
-      const int oy_lo = band * TQ, iy0 = 4 * band * TQ - 1, my0 = 2 * band * TQ;
-      const char* dsrc = reinterpret_cast<const char*>(a.dy.ptr_uniform(img)) + (int64_t)oy_lo * rowbytes;
-      const char* isrc = reinterpret_cast<const char*>(a.img0.ptr_uniform(img)) + (int64_t)iy0 * RB0;
-      const char* msrc = reinterpret_cast<const char*>(a.xbits + ((int64_t)img * a.H + my0) * W);
-      for (int i = lw; i < nl; i += S::NLW) {
-        if (i < n_dy) {
-          // a dY row; the 16-byte chunks of a pixel are permuted (dy_swz_bits) through the source address
-          const int row = i / segs, sg = i - row * segs;
-          const uint32_t phys = sg * 1024 + lane * 16, logi = phys ^ dy_swz_bits(phys);
-          const char* p = (oy_lo + row < a.Ho) ? dsrc + (int64_t)row * rowbytes + logi : zp;
-          if ((int)phys < rowbytes) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + row * RP + sg * 1024), 16, 0, 0);
-        } else if (i < n_dy + n_im) {
-          // image rows iy0 ... iy0 + 4*TQ: one contiguous span in memory and in LDS
-          const int j = i - n_dy, o = j * 1024 + lane * 16, iy = iy0 + (int)a.dv_rb0.div((uint32_t)o);
-          const char* p = (iy >= 0 && iy < a.H0) ? isrc + o : zp;
-          if (o < img0_bytes) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + OFF_IMG + j * 1024), 16, 0, 0);
-        } else {
-          // mask words of pixel rows my0 ... my0 + 2*TQ - 1, contiguous as well
-          const int j = i - n_dy - n_im, o = j * 1024 + lane * 16, my = my0 + (int)a.dv_mrow.div((uint32_t)o);
-          const char* p = (my < a.H) ? msrc + o : zp;
-          if (o < mask_bytes) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + OFF_MSK + j * 1024), 16, 0, 0);
-        }
-      }
+    // The pieces of a band are the same for every band; what differs is three base addresses and
+    // three row bounds.  Each piece is described once - LDS offset in the slot, this lane's source
+    // offset from the kind's base (-1: lane idle), the row it belongs to (for the test against the
+    // image's rows) - so that issuing a band is a short straight run per load.
+    constexpr int MAXD = S::MAXD, MAXI = S::MAXI, MAXM = S::MAXM;
+    int ddst[MAXD], drow[MAXD], dgo[MAXD], igo[MAXI], irow[MAXI], mgo[MAXM], mrow[MAXM];
+#pragma unroll
+    for (int k = 0; k < MAXD; ++k) {
+      // a dY row part; the 16-byte chunks of a pixel are permuted (dy_swz_bits) through the source address
+      const int i = lw + S::NLW * k, row = i / segs, sg = i - row * segs;
+      const uint32_t phys = sg * 1024 + lane * 16, logi = phys ^ dy_swz_bits(phys);
+      ddst[k] = row * RP + sg * 1024; drow[k] = row;
+      dgo[k] = (int)phys < rowbytes ? row * rowbytes + (int)logi : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < MAXI; ++k) {
+      const int o = (lw + S::NLW * k) * 1024 + lane * 16;
+      irow[k] = (int)a.dv_rb0.div((uint32_t)o); igo[k] = o < img0_bytes ? o : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < MAXM; ++k) {
+      const int o = (lw + S::NLW * k) * 1024 + lane * 16;
+      mrow[k] = (int)a.dv_mrow.div((uint32_t)o); mgo[k] = o < mask_bytes ? o : -1;
+    }
+    // tiles of this block in order: (img, band) advances by gridDim.x tiles without a division
+    const int step_img = (int)gridDim.x / a.NB, step_band = (int)gridDim.x - step_img * a.NB;
+    int n_img = (int)blockIdx.x / a.NB, n_band = (int)blockIdx.x - n_img * a.NB;
+    struct Band { const char* base[3]; int r0[3]; };
+    // base addresses and first rows of the next band to issue; formed one band ahead, so that the
+    // scalar load of the gather index is not waited for
+    auto prep = [&]() __attribute__((always_inline)) {
+      Band b;
+      const int img = n_img, band = n_band;
+      b.r0[0] = band * TQ; b.r0[1] = 4 * band * TQ - 1; b.r0[2] = 2 * band * TQ;
+      b.base[0] = reinterpret_cast<const char*>(a.dy.ptr_uniform(img)) + (int64_t)b.r0[0] * rowbytes;
+      b.base[1] = reinterpret_cast<const char*>(a.img0.ptr_uniform(img)) + (int64_t)b.r0[1] * RB0;
+      b.base[2] = reinterpret_cast<const char*>(a.xbits + ((int64_t)img * a.H + b.r0[2]) * W);
+      n_img += step_img; n_band += step_band;
+      if (n_band >= a.NB) { n_band -= a.NB; ++n_img; }
+      return b;
     };
-    if (nq > 0) issue(0);
-    if (nq > 1) issue(1);
+    Band nxt = prep();
+    auto issue = [&](int q) __attribute__((always_inline)) {  // called for q = 0, 1, 2, ... in order
+      const Band b = nxt;
+      if (q + 1 < nq) nxt = prep();
+      char* const slot = lds + (q % NBUF) * SLOT;
+#pragma unroll
+      for (int k = 0; k < MAXD; ++k)
+        if (k < nd) {
+          const char* p = (b.r0[0] + drow[k] < a.Ho) ? b.base[0] + dgo[k] : zp;  // rows outside the image: zeros
+          if (dgo[k] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + ddst[k]), 16, 0, 0);
+        }
+#pragma unroll
+      for (int k = 0; k < MAXI; ++k)
+        if (k < nm_i) {
+          const char* p = ((uint32_t)(b.r0[1] + irow[k]) < (uint32_t)a.H0) ? b.base[1] + igo[k] : zp;
+          if (igo[k] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + OFF_IMG + (lw + S::NLW * k) * 1024), 16, 0, 0);
+        }
+#pragma unroll
+      for (int k = 0; k < MAXM; ++k)
+        if (k < nm_m) {
+          const char* p = (b.r0[2] + mrow[k] < a.H) ? b.base[2] + mgo[k] : zp;
+          if (mgo[k] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + OFF_MSK + (lw + S::NLW * k) * 1024), 16, 0, 0);
+        }
+    };
     __builtin_amdgcn_s_barrier();
-    for (int q = 0; q < nq; ++q) {
-      vm_wait_dyn(q + 1 < nq ? ni : 0);  // band q has landed
-      __builtin_amdgcn_s_barrier();      // A(q); the compute waves have left band q - 1
+    // bands 0 and 1 are issued before the first wait: the loop starts two bands early
+    for (int q = -2; q < nq; ++q) {
+      if (q >= 0) {
+        vm_wait_dyn(q + 1 < nq ? ni : 0);  // band q has landed
+        __builtin_amdgcn_s_barrier();      // A(q); the compute waves have left band q - 1
+      }
       if (q + 2 < nq) issue(q + 2);
     }
     __builtin_amdgcn_s_barrier();        // C

@@ -70,18 +70,6 @@ __device__ __forceinline__ uint32_t tile_swz_bits(uint32_t off) {
   return (((t & 1u) << 2) | (t >> 1)) << 4;              // rotated, so neighbours differ in the top bit
 }
 
-// wait until at most n (wave-uniform, < 64) of this wave's vector-memory operations are outstanding
-__device__ __forceinline__ void vm_wait_dyn(int n) {
-  switch (n) {
-#define VMW(i) case i: vm_wait<i>(); break;
-#define VMW8(b) VMW(b) VMW(b + 1) VMW(b + 2) VMW(b + 3) VMW(b + 4) VMW(b + 5) VMW(b + 6) VMW(b + 7)
-    VMW8(0) VMW8(8) VMW8(16) VMW8(24) VMW8(32) VMW8(40) VMW8(48) VMW8(56)
-#undef VMW8
-#undef VMW
-    default: vm_wait<0>(); break;
-  }
-}
-
 template <int CIN>
 __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
   typedef ConvTileShape<CIN> S;

@@ -44,11 +44,23 @@ __device__ __forceinline__ void vm_wait() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// wait until at most n (wave-uniform, < 64) of this wave's vector-memory operations are outstanding
+__device__ __forceinline__ void vm_wait_dyn(int n) {
+  switch (n) {
+#define VMW(i) case i: vm_wait<i>(); break;
+#define VMW8(b) VMW(b) VMW(b + 1) VMW(b + 2) VMW(b + 3) VMW(b + 4) VMW(b + 5) VMW(b + 6) VMW(b + 7)
+    VMW8(0) VMW8(8) VMW8(16) VMW8(24) VMW8(32) VMW8(40) VMW8(48) VMW8(56)
+#undef VMW8
+#undef VMW
+    default: vm_wait<0>(); break;
+  }
+}
+
 template <int BM, int BN, int WGM, int WGN, int NST, class AL, class EP>
 __global__ __launch_bounds__(256) void k_gemm_dma(AL al, const bf16_t* __restrict__ Bm_, int64_t ldb_, int N, EP ep,
                                                   const bf16_t* __restrict__ zpage) {
   constexpr int TM = BM / (WGM * 32), TN = BN / (WGN * 32);
-  static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && NST >= 2 && NST <= 4, "tile shape");
+  static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && NST >= 2 && NST <= 8, "tile shape");
   constexpr int BK = 64;
   constexpr int AI = BM / 32, BI = BN / 32;  // loads per wave per stage (8 rows each)
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, ST_BYTES = A_BYTES + B_BYTES;
@@ -131,9 +143,7 @@ __global__ __launch_bounds__(256) void k_gemm_dma(AL al, const bf16_t* __restric
   int st = 0;
   for (int kt = 0; kt < nk; ++kt) {
     const int younger = min(D - 1, nk - 1 - kt);  // stages issued after stage kt
-    if (younger >= 2) vm_wait<(D >= 3 ? 2 : 0) * (AI + BI)>();
-    else if (younger == 1) vm_wait<(D >= 2 ? 1 : 0) * (AI + BI)>();
-    else vm_wait<0>();
+    vm_wait_dyn(younger * (AI + BI));
     __builtin_amdgcn_s_barrier();  // stage kt has landed for every wave; the stage read last step is free
     if (kt + D < nk) issue(st == 0 ? NST - 1 : st - 1, (kt + D) * BK);
     const uint32_t sA = st * ST_BYTES + offA, sB = st * ST_BYTES + offB;

@@ -285,15 +285,16 @@ int launch_gemm(Ctx* c, const AL& al_, int M, const bf16_t* Bm, int64_t ldb, int
   const char* what = name.c_str();
   ProfScope ps(c, name, flops >= 0.0 ? flops : 2.0 * M * (double)N * K, abytes);
   dim3 blk(256);
-  // Very deep reductions stream their operands through a three-stage LDS ring (two 64-wide k steps
-  // in flight per block); medium ones take 64-wide steps through registers, where the smaller LDS
+  // Very deep reductions stream their operands through an LDS ring of up to eight stages (128 KiB:
+  // the bytes in flight per CU, not the instruction rate, set the pace of such a stream); medium ones take 64-wide steps through registers, where the smaller LDS
   // footprint lets more blocks share a CU and hide the prologue and epilogue of their short loops.
 #define LAUNCH_GEMM(BM_, BN_, WM_, WN_, GX, GY)                                                                        \
   do {                                                                                                                   \
     dim3 grid(GX, GY, zdim);                                                                                             \
     if (K >= 1024) {                                                                                                     \
-      auto kfn = k_gemm_dma<BM_, BN_, WM_, WN_, 3, AL, EP>;                                                              \
-      constexpr int lds = 3 * (BM_ + BN_) * 128;                                                                         \
+      constexpr int nst = (BM_ + BN_) * 128 * 8 <= 128 * 1024 ? 8 : ((BM_ + BN_) * 128 * 5 <= 128 * 1024 ? 5 : 4);          \
+      auto kfn = k_gemm_dma<BM_, BN_, WM_, WN_, nst, AL, EP>;                                                            \
+      constexpr int lds = nst * (BM_ + BN_) * 128;                                                                       \
       static bool attr_set = false;                                                                                      \
       if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, lds)); attr_set = true; } \
       hipLaunchKernelGGL(kfn, grid, blk, lds, c->stream, al, Bm, ldb, N, ep, c->zpage);                                   \
@@ -554,7 +555,7 @@ int launch_conv_dgrad_wgrad0_reg_t(Ctx* c, ConvDgradArgs a, int nimg, const std:
   const int rb0 = a.W0 * C0 * 2;
   if (a.W % 8 || rb0 % 16 || a.Wo * 2 != a.W || a.Wo > S::BQ || a.H != (a.H0 + 1) / 2 || a.W * 2 != a.W0) return 1;
   auto fits = [&](int tq) {
-    return tq * a.Wo <= S::BQ && S::lds_bytes(a.W, a.Wo, a.W0, C0, tq) <= 158 * 1024 && cdiv(S::loads_per_band(a.W, a.Wo, a.W0, C0, tq), S::NLW) <= 63;
+    return tq * a.Wo <= S::BQ && S::lds_bytes(a.W, a.Wo, a.W0, C0, tq) <= 158 * 1024 && S::loads_fit(a.W, a.Wo, a.W0, C0, tq);
   };
   int TQ = S::BQ / a.Wo < a.Ho ? S::BQ / a.Wo : a.Ho;
   while (TQ > 1 && !fits(TQ)) --TQ;
