@@ -553,48 +553,15 @@ __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int
   }
 }
 
-// The same for partials stored transposed: dst[n*K + k] (+)= sum_s partial[s][k*N + n].
-__global__ __launch_bounds__(256) void k_reduce_partials_t(const float* __restrict__ partial, int splits, int N, int K,
-                                                           float* __restrict__ dst, int accumulate) {
-  __shared__ float red[8][33];
+// Sum over s of partial[s][i] for one output per lane: a block covers 32 outputs with 8 lanes of
+// splits each (lane j sums s = j, j+8, ... with four running sums, four loads in flight); the 8
+// lane sums are combined in a fixed order, so the result does not depend on scheduling.  Returns
+// the sum in the lanes with threadIdx.x < 32.
+__device__ __forceinline__ float reduce_partials_block(const float* __restrict__ partial, int splits, int64_t n, int64_t i, float (*red)[33]) {
   const int o = threadIdx.x & 31, sl = threadIdx.x >> 5;
-  const int64_t n_all = (int64_t)N * K, i = (int64_t)blockIdx.x * 32 + o;
-  float s0 = 0.f, s1 = 0.f;
-  if (i < n_all) {
-    int k = sl;
-    // four independent loads in flight per lane (the sums stay in a fixed order)
-    float s2 = 0.f, s3 = 0.f;
-    for (; k + 24 < splits; k += 32) {
-      const float v0 = partial[(int64_t)k * n_all + i], v1 = partial[(int64_t)(k + 8) * n_all + i];
-      const float v2 = partial[(int64_t)(k + 16) * n_all + i], v3 = partial[(int64_t)(k + 24) * n_all + i];
-      s0 += v0; s1 += v1; s2 += v2; s3 += v3;
-    }
-    s0 += s2; s1 += s3;
-    for (; k + 8 < splits; k += 16) { s0 += partial[(int64_t)k * n_all + i]; s1 += partial[(int64_t)(k + 8) * n_all + i]; }
-    if (k < splits) s0 += partial[(int64_t)k * n_all + i];
-  }
-  red[sl][o] = s0 + s1;
-  __syncthreads();
-  if (sl == 0 && i < n_all) {
-    const float s = ((red[0][o] + red[1][o]) + (red[2][o] + red[3][o])) + ((red[4][o] + red[5][o]) + (red[6][o] + red[7][o]));
-    const int kk = (int)(i / N), n = (int)(i - (int64_t)kk * N);
-    float* d = dst + (int64_t)n * K + kk;
-    *d = accumulate ? *d + s : s;
-  }
-}
-
-// dst[i] = (accumulate ? dst[i] : 0) + sum_s partial[s][i].  A block covers 32 outputs with 8
-// lanes of splits each (lane j sums s = j, j+8, ... with two running sums); the 8 lane sums are
-// combined in a fixed order, so the result does not depend on scheduling.
-__global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ partial, int splits, int64_t n,
-                                                         float* __restrict__ dst, int accumulate) {
-  __shared__ float red[8][33];
-  const int o = threadIdx.x & 31, sl = threadIdx.x >> 5;
-  const int64_t i = (int64_t)blockIdx.x * 32 + o;
   float s0 = 0.f, s1 = 0.f;
   if (i < n) {
     int k = sl;
-    // four independent loads in flight per lane (the sums stay in a fixed order)
     float s2 = 0.f, s3 = 0.f;
     for (; k + 24 < splits; k += 32) {
       const float v0 = partial[(int64_t)k * n + i], v1 = partial[(int64_t)(k + 8) * n + i];
@@ -607,8 +574,37 @@ __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict
   }
   red[sl][o] = s0 + s1;
   __syncthreads();
-  if (sl == 0 && i < n) {
-    float s = ((red[0][o] + red[1][o]) + (red[2][o] + red[3][o])) + ((red[4][o] + red[5][o]) + (red[6][o] + red[7][o]));
-    dst[i] = accumulate ? dst[i] + s : s;
+  return ((red[0][o] + red[1][o]) + (red[2][o] + red[3][o])) + ((red[4][o] + red[5][o]) + (red[6][o] + red[7][o]));
+}
+
+// dst[i] = (accumulate ? dst[i] : 0) + sum_s partial[s][i], and in the same launch (blocks past the
+// first ceil(n / 32)) the same for a second, small set of partials (the bias gradient), if given.
+__global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ partial, int splits, int64_t n,
+                                                         float* __restrict__ dst, int accumulate,
+                                                         const float* __restrict__ partial2, int64_t n2, float* __restrict__ dst2) {
+  __shared__ float red[8][33];
+  const int64_t main_blocks = (n + 31) / 32;
+  const bool second = (int64_t)blockIdx.x >= main_blocks;
+  const float* pp = second ? partial2 : partial;
+  const int64_t nn = second ? n2 : n, i = ((int64_t)blockIdx.x - (second ? main_blocks : 0)) * 32 + (threadIdx.x & 31);
+  float* dd = second ? dst2 : dst;
+  const float s = reduce_partials_block(pp, splits, nn, i, red);
+  if (threadIdx.x < 32 && i < nn) dd[i] = accumulate ? dd[i] + s : s;
+}
+
+// The same for main partials stored transposed: dst[n*K + k] (+)= sum_s partial[s][k*N + n].
+__global__ __launch_bounds__(256) void k_reduce_partials_t(const float* __restrict__ partial, int splits, int N, int K,
+                                                           float* __restrict__ dst, int accumulate,
+                                                           const float* __restrict__ partial2, int64_t n2, float* __restrict__ dst2) {
+  __shared__ float red[8][33];
+  const int64_t n_all = (int64_t)N * K, main_blocks = (n_all + 31) / 32;
+  const bool second = (int64_t)blockIdx.x >= main_blocks;
+  const int64_t nn = second ? n2 : n_all, i = ((int64_t)blockIdx.x - (second ? main_blocks : 0)) * 32 + (threadIdx.x & 31);
+  const float s = reduce_partials_block(second ? partial2 : partial, splits, nn, i, red);
+  if (threadIdx.x < 32 && i < nn) {
+    float* d;
+    if (second) d = dst2 + i;
+    else { const int kk = (int)(i / N), n = (int)(i - (int64_t)kk * N); d = dst + (int64_t)n * K + kk; }
+    *d = accumulate ? *d + s : s;
   }
 }

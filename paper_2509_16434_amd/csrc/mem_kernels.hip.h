@@ -531,17 +531,21 @@ struct DevStats { float pi_loss, v_loss, entropy, approx_kl, clip_frac, grad_nor
 __global__ void k_loss_finalize(int nblocks, int Bfull, int A, int distill, const float* __restrict__ stat_part,
                                 const float* __restrict__ dls_part, const float* __restrict__ logstd, float vf_coef,
                                 float ent_coef, DevStats* __restrict__ st, float* __restrict__ g_logstd) {
-  const int tid = threadIdx.x;
+  // 256 threads: column c (4 statistics, then the A log-std gradients) is summed by 8 lanes, lane j
+  // taking blocks j, j+8, ... in order; the 8 sums are combined in a fixed order
+  const int tid = threadIdx.x, l8 = tid & 7;
   __shared__ float tot[4];
-  if (tid < 4) {
+  const int ncol = 4 + (distill ? 0 : A);
+  for (int c0 = 0; c0 < ncol; c0 += 32) {
+    const int col = c0 + (tid >> 3);
     float s = 0.f;
-    for (int b = 0; b < nblocks; ++b) s += stat_part[(int64_t)b * LOSS_NSTAT + tid];
-    tot[tid] = s;
-  } else if (!distill && tid >= 32 && tid < 32 + A) {
-    int j = tid - 32;
-    float s = 0.f;
-    for (int b = 0; b < nblocks; ++b) s += dls_part[(int64_t)b * 32 + j];
-    g_logstd[j] = s - ent_coef;
+    if (col < ncol)
+      for (int b = l8; b < nblocks; b += 8) s += col < 4 ? stat_part[(int64_t)b * LOSS_NSTAT + col] : dls_part[(int64_t)b * 32 + (col - 4)];
+    s += __shfl_xor(s, 1); s += __shfl_xor(s, 2); s += __shfl_xor(s, 4);
+    if (l8 == 0 && col < ncol) {
+      if (col < 4) tot[col] = s;
+      else g_logstd[col - 4] = s - ent_coef;
+    }
   }
   __syncthreads();
   if (tid == 0) {
@@ -632,6 +636,36 @@ __global__ void k_pack_dgrad_taps(const bf16_t* __restrict__ w, int Cout, int Ci
   if (i >= (int64_t)9 * Cin * Cout) return;
   const int tap = (int)(i / ((int64_t)Cin * Cout)), rem = (int)(i - (int64_t)tap * Cin * Cout), ci = rem / Cout, co = rem - ci * Cout;
   dst[i] = w[(int64_t)co * 9 * Cin + tap * Cin + ci];
+}
+
+// All per-update re-packs in one launch: job j covers blocks [first[j], first[j+1]); kind 0 is
+// k_transpose_bf16's mapping (a = rows, b = cols, ld = leading dimension of dst), kind 1
+// k_pack_dgrad_taps's (a = Cout, b = Cin).
+struct RepackJobs {
+  static constexpr int MAXJ = 12;
+  int njobs;
+  int first[MAXJ + 1];
+  int kind[MAXJ], a[MAXJ], b[MAXJ], ld[MAXJ];
+  const bf16_t* src[MAXJ];
+  bf16_t* dst[MAXJ];
+};
+__global__ __launch_bounds__(256) void k_repack_all(RepackJobs jobs) {
+  int j = 0;
+  while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first[j + 1]) ++j;
+  const int64_t i = (int64_t)((int)blockIdx.x - jobs.first[j]) * 256 + threadIdx.x;
+  const bf16_t* __restrict__ src = jobs.src[j];
+  bf16_t* __restrict__ dst = jobs.dst[j];
+  if (jobs.kind[j] == 0) {
+    const int rows = jobs.a[j], cols = jobs.b[j], ld_dst = jobs.ld[j];
+    if (i >= (int64_t)cols * ld_dst) return;
+    const int c = (int)(i / ld_dst), r = (int)(i - (int64_t)c * ld_dst);
+    dst[i] = r < rows ? src[(int64_t)r * cols + c] : (bf16_t)0;
+  } else {
+    const int Cout = jobs.a[j], Cin = jobs.b[j];
+    if (i >= (int64_t)9 * Cin * Cout) return;
+    const int tap = (int)(i / ((int64_t)Cin * Cout)), rem = (int)(i - (int64_t)tap * Cin * Cout), ci = rem / Cout, co = rem - ci * Cout;
+    dst[i] = src[(int64_t)co * 9 * Cin + tap * Cin + ci];
+  }
 }
 
 // dst[px*Cin + ci][(tu*2 + dx)*Cout + co] = W[co][(u*3+v)*Cin + ci] with u = py ? 2*tu : 1 and the

@@ -352,12 +352,10 @@ int launch_wgrad(Ctx* c, const DL& dl_, const AL& al_, int Nn, int Kk, int M, fl
     LAUNCHCHK(c, what);
   }
   ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)splits + 1.0) * (double)per);
-  hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 32)), dim3(256), 0, c->stream, c->partial, splits, per, gw, accumulate ? 1 : 0);
+  // weight and bias partials in one launch
+  hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 32) + (gb ? cdiv(Nn, 32) : 0)), dim3(256), 0, c->stream, c->partial, splits, per, gw, accumulate ? 1 : 0,
+                     gb ? c->bias_partial : nullptr, (int64_t)(gb ? Nn : 0), gb);
   LAUNCHCHK(c, what);
-  if (gb) {
-    hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(Nn, 32)), dim3(256), 0, c->stream, c->bias_partial, splits, (int64_t)Nn, gb, accumulate ? 1 : 0);
-    LAUNCHCHK(c, what);
-  }
   return PPO_OK;
 }
 
@@ -379,15 +377,22 @@ int ensure_packed_dgrad_weights(Ctx* c, int l) {
 int repack_weights(Ctx* c) {
   c->wver += 1;
   ProfScope ps(c, "weight_repack", 0.0, 4.0 * (double)c->total);
-  for (int l = 1; l < c->nconv; ++l) {
-    int Co = c->cC[l + 1], Ci = c->cC[l];
-    hipLaunchKernelGGL(k_pack_dgrad_taps, dim3(cdiv((int64_t)9 * Ci * Co, 256)), dim3(256), 0, c->stream, c->shadow + c->convW[l], Co, Ci, c->wtap[l]);
-  }
-  for (int l = 0; l < c->nfc; ++l) {
-    int64_t n = (int64_t)c->fin[l] * c->fout[l];
-    hipLaunchKernelGGL(k_transpose_bf16, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->shadow + c->fcW[l], c->fout[l], c->fin[l], c->fcT[l], c->fout[l]);
-  }
-  hipLaunchKernelGGL(k_transpose_bf16, dim3(cdiv((int64_t)c->hid * HEAD_LD, 256)), dim3(256), 0, c->stream, c->shadow + c->headW, c->NH, c->hid, c->headT, HEAD_LD);
+  RepackJobs jobs;
+  int nj = 0, nblocks = 0;
+  auto add = [&](int kind, const bf16_t* src, bf16_t* dst, int a, int b, int ld, int64_t elems) {
+    jobs.first[nj] = nblocks; jobs.kind[nj] = kind; jobs.src[nj] = src; jobs.dst[nj] = dst; jobs.a[nj] = a; jobs.b[nj] = b; jobs.ld[nj] = ld;
+    nblocks += cdiv(elems, 256); ++nj;
+  };
+  if (c->nconv - 1 + c->nfc + 1 > RepackJobs::MAXJ) return fail(c, PPO_ESHAPE, "too many layers for one re-pack launch");
+  for (int l = 1; l < c->nconv; ++l)
+    add(1, c->shadow + c->convW[l], c->wtap[l], c->cC[l + 1], c->cC[l], 0, (int64_t)9 * c->cC[l] * c->cC[l + 1]);
+  for (int l = 0; l < c->nfc; ++l)
+    add(0, c->shadow + c->fcW[l], c->fcT[l], c->fout[l], c->fin[l], c->fout[l], (int64_t)c->fin[l] * c->fout[l]);
+  add(0, c->shadow + c->headW, c->headT, c->NH, c->hid, HEAD_LD, (int64_t)c->hid * HEAD_LD);
+  jobs.first[nj] = nblocks; jobs.njobs = nj;
+  for (int j = nj + 1; j <= RepackJobs::MAXJ; ++j) jobs.first[j] = nblocks;
+  for (int j = nj; j < RepackJobs::MAXJ; ++j) { jobs.kind[j] = 0; jobs.src[j] = nullptr; jobs.dst[j] = nullptr; jobs.a[j] = jobs.b[j] = jobs.ld[j] = 0; }
+  hipLaunchKernelGGL(k_repack_all, dim3(nblocks), dim3(256), 0, c->stream, jobs);
   LAUNCHCHK(c, "weight repack");
   return PPO_OK;
 }
@@ -472,9 +477,9 @@ int launch_conv_wgrad_tile_t(Ctx* c, ConvWgradArgs a, float* gw, float* gb, bool
     LAUNCHCHK(c, "k_conv_wgrad_tile");
   }
   ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)gx + 1.0) * (double)per);
-  hipLaunchKernelGGL(k_reduce_partials_t, dim3(cdiv(per, 32)), dim3(256), 0, c->stream, c->partial, gx, a.Cout, K, gw, accumulate ? 1 : 0);
-  if (gb) hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(a.Cout, 32)), dim3(256), 0, c->stream, c->bias_partial, gx, (int64_t)a.Cout, gb, accumulate ? 1 : 0);
-  LAUNCHCHK(c, "k_reduce_partials");
+  hipLaunchKernelGGL(k_reduce_partials_t, dim3(cdiv(per, 32) + (gb ? cdiv(a.Cout, 32) : 0)), dim3(256), 0, c->stream, c->partial, gx, a.Cout, K, gw, accumulate ? 1 : 0,
+                     gb ? c->bias_partial : nullptr, (int64_t)(gb ? a.Cout : 0), gb);
+  LAUNCHCHK(c, "k_reduce_partials_t");
   return PPO_OK;
 }
 int launch_conv_wgrad_tile(Ctx* c, const ImgAddr& dy, const AConvFwd& xl, int Cout, int nimg, float* gw, float* gb, bool accumulate,
@@ -844,7 +849,7 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
         rc = backward_chunk(c, idx + c0, n, c0 > 0);
         if (rc) return rc;
       }
-      hipLaunchKernelGGL(k_loss_finalize, dim3(1), dim3(64), 0, c->stream, nblocks, B, c->A, distill ? 1 : 0, c->stat_part, c->dls_part,
+      hipLaunchKernelGGL(k_loss_finalize, dim3(1), dim3(256), 0, c->stream, nblocks, B, c->A, distill ? 1 : 0, c->stat_part, c->dls_part,
                          distill ? nullptr : c->p + c->logstd, hp->vf_coef, hp->ent_coef, c->dstats + k, distill ? nullptr : c->g + c->logstd);
       LAUNCHCHK(c, "k_loss_finalize");
       c->step += 1;
