@@ -234,15 +234,18 @@ struct Ep {
 // lane%32, n = n0 + (wn*TN+j)*32 + g*8 + (lane/32)*4 + q.  bf16 results are packed four at a
 // time, staged through `stage` (BM x (BN+8) elements of LDS no longer in use) and leave as
 // 16-byte row segments; fp32 results are written directly.
-template <int BM, int BN, int TM, int TN, class EP, class MCLS>
+// NTHR threads take part (all of them reach the barrier inside); waves without accumulators
+// (has_acc false) only help to write the staged tile out.
+template <int BM, int BN, int TM, int TN, int NTHR = 256, class EP, class MCLS>
 __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[TM][TN], const EP& ep, const MCLS& mcls, int m0, int n0, int N, int wm, int wn,
-                                              bf16_t* stage, int64_t* rowoff, int* rowcols) {
+                                              bf16_t* stage, int64_t* rowoff, int* rowcols, bool has_acc = true) {
   constexpr int SP = BN + 8;
   const int tid = threadIdx.x, lane = tid & 63;
   // acc[i][j][g*4+q] = C[m][n] with m = m0 + (wm*TM+i)*32 + lane%32, n = n0 + (wn*TN+j)*32 + g*8 + (lane/32)*4 + q
   typedef typename EP::out_t OutT;
   if constexpr (sizeof(OutT) == 2) {
-    for (int r = tid; r < BM; r += 256) { rowoff[r] = ep.map.row_offset(m0 + r, mcls); rowcols[r] = ep.map.row_cols(m0 + r, mcls); }
+    for (int r = tid; r < BM; r += NTHR) { rowoff[r] = ep.map.row_offset(m0 + r, mcls); rowcols[r] = ep.map.row_cols(m0 + r, mcls); }
+    if (has_acc) {
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -258,10 +261,11 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[TM][TN], const EP&
           *reinterpret_cast<uint2*>(&stage[((wm * TM + i) * 32 + (lane & 31)) * SP + cl]) = o;
         }
       }
+    }
     __syncthreads();
     constexpr int CPR = BN / 8;  // 16-byte chunks per row
     bf16_t* out = reinterpret_cast<bf16_t*>(ep.out);
-    for (int ch = tid; ch < BM * CPR; ch += 256) {
+    for (int ch = tid; ch < BM * CPR; ch += NTHR) {
       const int rl = ch / CPR, cg = ch - rl * CPR, n = n0 + cg * 8;
       const int64_t off = rowoff[rl];
       if (off < 0 || n >= N || n >= rowcols[rl]) continue;
@@ -278,6 +282,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[TM][TN], const EP&
     }
   } else {
     float* out = reinterpret_cast<float*>(ep.out);
+    if (!has_acc) return;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int64_t off = ep.map.row_offset(m0 + (wm * TM + i) * 32 + (lane & 31), mcls);

@@ -285,13 +285,28 @@ int launch_gemm(Ctx* c, const AL& al_, int M, const bf16_t* Bm, int64_t ldb, int
   const char* what = name.c_str();
   ProfScope ps(c, name, flops >= 0.0 ? flops : 2.0 * M * (double)N * K, abytes);
   dim3 blk(256);
-  // Very deep reductions stream their operands through an LDS ring of up to eight stages (128 KiB:
-  // the bytes in flight per CU, not the instruction rate, set the pace of such a stream); medium ones take 64-wide steps through registers, where the smaller LDS
-  // footprint lets more blocks share a CU and hide the prologue and epilogue of their short loops.
+  // Very deep reductions stream their operands through an LDS ring of up to eight stages, filled by
+  // four loader waves while four or eight other waves compute (k_gemm_rs); medium ones take 64-wide
+  // steps through registers, where the smaller LDS footprint lets more blocks share a CU and hide
+  // the prologue and epilogue of their short loops.
+#define LAUNCH_GEMM_RS(BM_, BN_, WM_, WN_)                                                                              \
+  do {                                                                                                                   \
+    constexpr int ncw = WM_ * WN_;                                                                                       \
+    constexpr int nst = (BM_ + BN_) * 128 * 8 <= 128 * 1024 ? 8 : ((BM_ + BN_) * 128 * 4 <= 128 * 1024 ? 4 : 3);            \
+    auto kfn = k_gemm_rs<BM_, BN_, WM_, WN_, nst, AL, EP>;                                                               \
+    constexpr int lds = nst * (BM_ + BN_) * 128;                                                                         \
+    static bool attr_set = false;                                                                                        \
+    if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, lds)); attr_set = true; } \
+    hipLaunchKernelGGL(kfn, grid, dim3((ncw + 4) * 64), lds, c->stream, al, Bm, ldb, N, ep, c->zpage);                    \
+  } while (0)
 #define LAUNCH_GEMM(BM_, BN_, WM_, WN_, GX, GY)                                                                        \
   do {                                                                                                                   \
     dim3 grid(GX, GY, zdim);                                                                                             \
-    if (K >= 1024) {                                                                                                     \
+    if constexpr (WM_ * WN_ != 4) {                                                                                      \
+      LAUNCH_GEMM_RS(BM_, BN_, WM_, WN_);                                                                                \
+    } else if (K >= 1024 && sizeof(typename EP::out_t) == 2) {                                                           \
+      LAUNCH_GEMM_RS(BM_, BN_, WM_, WN_);                                                                                \
+    } else if (K >= 1024) {                                                                                              \
       constexpr int nst = (BM_ + BN_) * 128 * 8 <= 128 * 1024 ? 8 : ((BM_ + BN_) * 128 * 5 <= 128 * 1024 ? 5 : 4);          \
       auto kfn = k_gemm_dma<BM_, BN_, WM_, WN_, nst, AL, EP>;                                                            \
       constexpr int lds = nst * (BM_ + BN_) * 128;                                                                       \
@@ -302,7 +317,8 @@ int launch_gemm(Ctx* c, const AL& al_, int M, const bf16_t* Bm, int64_t ldb, int
     else hipLaunchKernelGGL((k_gemm<BM_, BN_, WM_, WN_, 32, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);        \
   } while (0)
   if (N > 64) {
-    if ((int64_t)cdiv(M, 128) * cdiv(N, 128) * zdim >= 256 || M <= 64) LAUNCH_GEMM(128, 128, 2, 2, cdiv(M, 128), cdiv(N, 128));
+    if (K >= 1024 && sizeof(typename EP::out_t) == 2 && (int64_t)cdiv(M, 256) * cdiv(N, 128) * zdim >= 256) LAUNCH_GEMM(256, 128, 4, 2, cdiv(M, 256), cdiv(N, 128));
+    else if ((int64_t)cdiv(M, 128) * cdiv(N, 128) * zdim >= 256 || M <= 64) LAUNCH_GEMM(128, 128, 2, 2, cdiv(M, 128), cdiv(N, 128));
     else LAUNCH_GEMM(64, 64, 2, 2, cdiv(M, 64), cdiv(N, 64));
   } else if (N > 32) {
     if ((int64_t)cdiv(M, 128) * zdim >= 256 || M <= 64) LAUNCH_GEMM(128, 64, 2, 2, cdiv(M, 128), 1);
@@ -311,6 +327,7 @@ int launch_gemm(Ctx* c, const AL& al_, int M, const bf16_t* Bm, int64_t ldb, int
     LAUNCH_GEMM(128, 32, 4, 1, cdiv(M, 128), 1);
   }
 #undef LAUNCH_GEMM
+#undef LAUNCH_GEMM_RS
   LAUNCHCHK(c, what);
   return PPO_OK;
 }
