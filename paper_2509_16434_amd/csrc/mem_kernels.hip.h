@@ -405,6 +405,7 @@ __global__ void k_gather_proprio(const bf16_t* __restrict__ proprio, const int32
 // ---------------------------------------------------------------- losses
 #define LOSS_NSTAT 8  // pi, v, kl, clipfrac sums; slots 4..7 unused
 #define HEAD_LD 32    // row stride of the head output / head gradient matrices
+#define LOSS_BLOCK 64  // samples (threads) per block of the loss kernels: one wave, so that a minibatch spreads over many CUs
 
 // Clipped-surrogate PPO loss on a chunk of `B` samples of a minibatch of `Bfull`:
 //   logp = sum_j [-z_j^2/2 - logstd_j - ln(2 pi)/2], z = (a - mu)/sigma; rho = exp(logp - logp_old)
@@ -422,7 +423,7 @@ __global__ __launch_bounds__(256) void k_ppo_loss(int B, int Bfull, int A, const
   const int tid = threadIdx.x;
   if (tid < A) { ls[tid] = logstd[tid]; sig_inv[tid] = __expf(-logstd[tid]); }
   __syncthreads();
-  const int b = blockIdx.x * 256 + tid;
+  const int b = blockIdx.x * blockDim.x + tid;
   const bool ok = b < B;
   float st[4] = {0.f, 0.f, 0.f, 0.f};
   float dlogp = 0.f;
@@ -436,15 +437,19 @@ __global__ __launch_bounds__(256) void k_ppo_loss(int B, int Bfull, int A, const
       const float4 v4 = *reinterpret_cast<const float4*>(out + (int64_t)b * HEAD_LD + 4 * q);
       o[4 * q] = v4.x; o[4 * q + 1] = v4.y; o[4 * q + 2] = v4.z; o[4 * q + 3] = v4.w;
     }
+    // every gather is issued before the first one is used (no branch between them): one memory latency, not A
+    float act[32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) act[j] = action[s * A + (j < A ? j : A - 1)];
+    const float lpo = logp_old[s], a = adv[s], r = ret[s], vo = v_old[s];
     float logp = 0.f;
 #pragma unroll
     for (int j = 0; j < 32; ++j) {
-      if (j < A) {
-        z[j] = (action[s * A + j] - o[j]) * sig_inv[j];
-        logp += -0.5f * z[j] * z[j] - ls[j] - 0.91893853320467274178f;
-      } else z[j] = 0.f;
+      const float zz = (act[j] - o[j]) * sig_inv[j < A ? j : 0];
+      z[j] = j < A ? zz : 0.f;
+      logp += j < A ? -0.5f * zz * zz - ls[j < A ? j : 0] - 0.91893853320467274178f : 0.f;
     }
-    const float lr = logp - logp_old[s], rho = expf(lr), a = adv[s];
+    const float lr = logp - lpo, rho = expf(lr);
     const float rc = fminf(fmaxf(rho, 1.f - clip_eps), 1.f + clip_eps);
     const float s1 = rho * a, s2 = rc * a;
     st[0] = -fminf(s1, s2);
@@ -454,10 +459,10 @@ __global__ __launch_bounds__(256) void k_ppo_loss(int B, int Bfull, int A, const
     float v = 0.f;
 #pragma unroll
     for (int j = 0; j < 32; ++j) v = (j == A) ? o[j] : v;  // the value head's column (register array: no dynamic index)
-    const float r = ret[s], err = v - r;
+    const float err = v - r;
     float dv;
     if (vclip_eps > 0.f) {
-      const float d = v - v_old[s], dc = fminf(fmaxf(d, -vclip_eps), vclip_eps), errc = v_old[s] + dc - r;
+      const float d = v - vo, dc = fminf(fmaxf(d, -vclip_eps), vclip_eps), errc = vo + dc - r;
       if (errc * errc > err * err) { st[1] = errc * errc; dv = (d >= -vclip_eps && d <= vclip_eps) ? 2.f * errc : 0.f; }
       else { st[1] = err * err; dv = 2.f * err; }
     } else { st[1] = err * err; dv = 2.f * err; }
@@ -476,17 +481,25 @@ __global__ __launch_bounds__(256) void k_ppo_loss(int B, int Bfull, int A, const
 #pragma unroll
     for (int q = 0; q < 4; ++q) d[q] = make_uint4(pk[4 * q], pk[4 * q + 1], pk[4 * q + 2], pk[4 * q + 3]);
   }
-  // block reductions in a fixed order: xor-butterfly inside each wave, then the four wave sums
+  // block reductions in a fixed order: xor-butterfly inside each wave (all 4 + A sums side by side,
+  // so that the steps of different sums overlap), then the four wave sums
   __shared__ float wred[4][36];
   const int lane = tid & 63, wave = tid >> 6;
-  auto wave_sum = [&](float v) -> float {
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return v;
-  };
-  for (int k = 0; k < 4; ++k) { float r = wave_sum(st[k]); if (lane == 0) wred[wave][k] = r; }
+  for (int i = tid; i < 4 * 36; i += blockDim.x) (&wred[0][0])[i] = 0.f;  // waves the block does not have contribute zero
+  __syncthreads();
+  float rv[36];
 #pragma unroll
-  for (int j = 0; j < 32; ++j) {
-    if (j < A) { float r = wave_sum(ok ? dlogp * (z[j] * z[j] - 1.f) : 0.f); if (lane == 0) wred[wave][4 + j] = r; }
+  for (int k = 0; k < 4; ++k) rv[k] = st[k];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) rv[4 + j] = (ok && j < A) ? dlogp * (z[j] * z[j] - 1.f) : 0.f;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+    for (int k = 0; k < 36; ++k) rv[k] += __shfl_xor(rv[k], off);  // sums beyond 4 + A are zeros
+  if (lane == 0) {
+#pragma unroll
+    for (int k = 0; k < 36; ++k)
+      if (k < 4 + A) wred[wave][k] = rv[k];
   }
   __syncthreads();
   if (tid < 4) stat_part[(int64_t)blockIdx.x * LOSS_NSTAT + tid] = (wred[0][tid] + wred[1][tid]) + (wred[2][tid] + wred[3][tid]);
@@ -501,7 +514,7 @@ __global__ __launch_bounds__(256) void k_mse_loss(int B, int Bfull, int A, const
                                                   const int32_t* __restrict__ idx, const float* __restrict__ teacher,
                                                   bf16_t* __restrict__ dout, float* __restrict__ stat_part) {
   __shared__ float red[256];
-  const int tid = threadIdx.x, b = blockIdx.x * 256 + tid;
+  const int tid = threadIdx.x, b = blockIdx.x * blockDim.x + tid;
   float l = 0.f;
   const float sc = 1.f / ((float)Bfull * (float)A);
   if (b < B) {
@@ -515,6 +528,7 @@ __global__ __launch_bounds__(256) void k_mse_loss(int B, int Bfull, int A, const
     }
   }
   red[tid] = l;
+  for (int i = tid + blockDim.x; i < 256; i += blockDim.x) red[i] = 0.f;
   __syncthreads();
   for (int s = 128; s > 0; s >>= 1) { if (tid < s) red[tid] += red[tid + s]; __syncthreads(); }
   if (tid == 0) {

@@ -838,7 +838,7 @@ int gen_permutation(Ctx* c, uint64_t seed, uint64_t update, uint64_t epoch) {
 int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool distill) {
   const int B = c->S / hp->minibatches;
   const int steps = hp->epochs * hp->minibatches;
-  const int blocks_per_chunk = cdiv(c->CH, 256);
+  const int blocks_per_chunk = cdiv(c->CH, LOSS_BLOCK);
   int k = 0;
   for (int e = 0; e < hp->epochs; ++e) {
     int rc = gen_permutation(c, hp->seed, (uint64_t)c->update_idx, (uint64_t)e);
@@ -855,14 +855,14 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
         {
         ProfScope ps(c, "loss", 0.0, (double)n * (HEAD_LD * 6.0 + 4.0 * c->A + 20.0));
         if (distill)
-          hipLaunchKernelGGL(k_mse_loss, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, n, B, c->A, c->headout, idx + c0, c->action, c->dhead, sp);
+          hipLaunchKernelGGL(k_mse_loss, dim3(cdiv(n, LOSS_BLOCK)), dim3(LOSS_BLOCK), 0, c->stream, n, B, c->A, c->headout, idx + c0, c->action, c->dhead, sp);
         else
-          hipLaunchKernelGGL(k_ppo_loss, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, n, B, c->A, c->headout, c->p + c->logstd, idx + c0, c->action,
+          hipLaunchKernelGGL(k_ppo_loss, dim3(cdiv(n, LOSS_BLOCK)), dim3(LOSS_BLOCK), 0, c->stream, n, B, c->A, c->headout, c->p + c->logstd, idx + c0, c->action,
                              c->logp, c->value, c->adv, c->ret, hp->clip_eps, hp->vclip_eps, hp->vf_coef, c->dhead, sp, dp);
         LAUNCHCHK(c, "loss kernel");
         }
         // partial slots of a ragged last chunk follow the full chunks contiguously
-        nblocks = ci * blocks_per_chunk + cdiv(n, 256);
+        nblocks = ci * blocks_per_chunk + cdiv(n, LOSS_BLOCK);
         rc = backward_chunk(c, idx + c0, n, c0 > 0);
         if (rc) return rc;
       }
@@ -957,7 +957,7 @@ int create_impl(Ctx* c) {
   DALLOC(c, c->zpage, 512);
   HIPCHK(c, hipMemsetAsync(c->zpage, 0, 1024, c->stream));
   // loss / Adam partials
-  c->max_loss_blocks = cdiv(S, CH) * cdiv(CH, 256) + 1;
+  c->max_loss_blocks = cdiv(S, CH) * cdiv(CH, LOSS_BLOCK) + 1;
   DALLOC(c, c->stat_part, (int64_t)c->max_loss_blocks * LOSS_NSTAT); DALLOC(c, c->dls_part, (int64_t)c->max_loss_blocks * 32);
   c->adam_blocks = cdiv(c->total, 1024); if (c->adam_blocks > 2048) c->adam_blocks = 2048;
   DALLOC(c, c->sq_part, c->adam_blocks);
