@@ -407,134 +407,150 @@ __global__ void k_gather_proprio(const bf16_t* __restrict__ proprio, const int32
 #define HEAD_LD 32    // row stride of the head output / head gradient matrices
 #define LOSS_BLOCK 64  // samples (threads) per block of the loss kernels: one wave, so that a minibatch spreads over many CUs
 
-// Clipped-surrogate PPO loss on a chunk of `B` samples of a minibatch of `Bfull`:
+// Per-sample inputs of the losses (rollout arrays indexed by the gathered sample number).
+struct LossData {
+  int Bfull, A;
+  const float* logstd;
+  const int32_t* idx;
+  const float *action, *logp_old, *v_old, *adv, *ret;
+  float clip_eps, vclip_eps, vf_coef;
+};
+
+// Clipped-surrogate PPO loss of one sample (number s of the rollout) of a minibatch of `Bfull`:
 //   logp = sum_j [-z_j^2/2 - logstd_j - ln(2 pi)/2], z = (a - mu)/sigma; rho = exp(logp - logp_old)
 //   L_pi = -mean min(rho A, clip(rho, 1-eps, 1+eps) A);  L_V = mean (V-R)^2 or its clipped max form
-// One thread per sample.  Writes the gradient rows dOut[b][0..A) = dL/dmu, dOut[b][A] = dL/dV (bf16,
-// zero padded to 32 columns) and per-block partial sums of the statistics and of dL/dlogstd.
-__global__ __launch_bounds__(256) void k_ppo_loss(int B, int Bfull, int A, const float* __restrict__ out,
-                                                  const float* __restrict__ logstd, const int32_t* __restrict__ idx,
-                                                  const float* __restrict__ action, const float* __restrict__ logp_old,
-                                                  const float* __restrict__ v_old, const float* __restrict__ adv,
-                                                  const float* __restrict__ ret, float clip_eps, float vclip_eps,
-                                                  float vf_coef, bf16_t* __restrict__ dout, float* __restrict__ stat_part,
-                                                  float* __restrict__ dls_part) {
-  __shared__ float sig_inv[32], ls[32];
-  const int tid = threadIdx.x;
-  if (tid < A) { ls[tid] = logstd[tid]; sig_inv[tid] = __expf(-logstd[tid]); }
-  __syncthreads();
-  const int b = blockIdx.x * blockDim.x + tid;
-  const bool ok = b < B;
-  float st[4] = {0.f, 0.f, 0.f, 0.f};
-  float dlogp = 0.f;
+// o: the head's output row (means, then the value).  Leaves the gradient row dL/dmu_0..A-1, dL/dV
+// (bf16 pairs, zero padded to 32 columns) in pk, this sample's terms of the four statistics in st and
+// of dL/dlogstd in dls.
+__device__ __forceinline__ void ppo_loss_sample(const LossData& L, const float* sig_inv, const float* ls, int64_t s, const float (&o)[HEAD_LD],
+                                                uint32_t (&pk)[16], float (&st)[4], float (&dls)[32]) {
+  const int A = L.A;
+  const float invB = 1.f / (float)L.Bfull;
+  // every gather is issued before the first one is used (no branch between them): one memory latency, not A
+  float act[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) act[j] = L.action[s * A + (j < A ? j : A - 1)];
+  const float lpo = L.logp_old[s], a = L.adv[s], r = L.ret[s], vo = L.v_old[s];
   float z[32];
-  const float invB = 1.f / (float)Bfull;
-  if (ok) {
-    const int64_t s = idx[b];
-    float o[HEAD_LD];  // the head's output row: eight 16-byte loads
+  float logp = 0.f;
 #pragma unroll
-    for (int q = 0; q < HEAD_LD / 4; ++q) {
-      const float4 v4 = *reinterpret_cast<const float4*>(out + (int64_t)b * HEAD_LD + 4 * q);
-      o[4 * q] = v4.x; o[4 * q + 1] = v4.y; o[4 * q + 2] = v4.z; o[4 * q + 3] = v4.w;
-    }
-    // every gather is issued before the first one is used (no branch between them): one memory latency, not A
-    float act[32];
-#pragma unroll
-    for (int j = 0; j < 32; ++j) act[j] = action[s * A + (j < A ? j : A - 1)];
-    const float lpo = logp_old[s], a = adv[s], r = ret[s], vo = v_old[s];
-    float logp = 0.f;
-#pragma unroll
-    for (int j = 0; j < 32; ++j) {
-      const float zz = (act[j] - o[j]) * sig_inv[j < A ? j : 0];
-      z[j] = j < A ? zz : 0.f;
-      logp += j < A ? -0.5f * zz * zz - ls[j < A ? j : 0] - 0.91893853320467274178f : 0.f;
-    }
-    const float lr = logp - lpo, rho = expf(lr);
-    const float rc = fminf(fmaxf(rho, 1.f - clip_eps), 1.f + clip_eps);
-    const float s1 = rho * a, s2 = rc * a;
-    st[0] = -fminf(s1, s2);
-    dlogp = (s1 <= s2) ? -invB * a * rho : 0.f;
-    st[2] = (rho - 1.f) - lr;
-    st[3] = fabsf(rho - 1.f) > clip_eps ? 1.f : 0.f;
-    float v = 0.f;
-#pragma unroll
-    for (int j = 0; j < 32; ++j) v = (j == A) ? o[j] : v;  // the value head's column (register array: no dynamic index)
-    const float err = v - r;
-    float dv;
-    if (vclip_eps > 0.f) {
-      const float d = v - vo, dc = fminf(fmaxf(d, -vclip_eps), vclip_eps), errc = vo + dc - r;
-      if (errc * errc > err * err) { st[1] = errc * errc; dv = (d >= -vclip_eps && d <= vclip_eps) ? 2.f * errc : 0.f; }
-      else { st[1] = err * err; dv = 2.f * err; }
-    } else { st[1] = err * err; dv = 2.f * err; }
-    // the row of 32 bf16 leaves as four 16-byte stores
-    uint32_t pk[16];
-#pragma unroll
-    for (int j = 0; j < 32; j += 2) {
-      float g0 = 0.f, g1 = 0.f;
-      if (j < A) g0 = dlogp * z[j] * sig_inv[j];
-      else if (j == A) g0 = vf_coef * invB * dv;
-      if (j + 1 < A) g1 = dlogp * z[j + 1] * sig_inv[j + 1];
-      else if (j + 1 == A) g1 = vf_coef * invB * dv;
-      pk[j >> 1] = pack2bf(g0, g1);
-    }
-    uint4* d = reinterpret_cast<uint4*>(dout + (int64_t)b * HEAD_LD);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) d[q] = make_uint4(pk[4 * q], pk[4 * q + 1], pk[4 * q + 2], pk[4 * q + 3]);
+  for (int j = 0; j < 32; ++j) {
+    const float zz = (act[j] - o[j]) * sig_inv[j < A ? j : 0];
+    z[j] = j < A ? zz : 0.f;
+    logp += j < A ? -0.5f * zz * zz - ls[j < A ? j : 0] - 0.91893853320467274178f : 0.f;
   }
-  // block reductions in a fixed order: xor-butterfly inside each wave (all 4 + A sums side by side,
-  // so that the steps of different sums overlap), then the four wave sums
-  __shared__ float wred[4][36];
-  const int lane = tid & 63, wave = tid >> 6;
+  const float lr = logp - lpo, rho = expf(lr);
+  const float rc = fminf(fmaxf(rho, 1.f - L.clip_eps), 1.f + L.clip_eps);
+  const float s1 = rho * a, s2 = rc * a;
+  st[0] = -fminf(s1, s2);
+  const float dlogp = (s1 <= s2) ? -invB * a * rho : 0.f;
+  st[2] = (rho - 1.f) - lr;
+  st[3] = fabsf(rho - 1.f) > L.clip_eps ? 1.f : 0.f;
+  float v = 0.f;
+#pragma unroll
+  for (int j = 0; j < 32; ++j) v = (j == A) ? o[j] : v;  // the value head's column (register array: no dynamic index)
+  const float err = v - r;
+  float dv;
+  if (L.vclip_eps > 0.f) {
+    const float d = v - vo, dc = fminf(fmaxf(d, -L.vclip_eps), L.vclip_eps), errc = vo + dc - r;
+    if (errc * errc > err * err) { st[1] = errc * errc; dv = (d >= -L.vclip_eps && d <= L.vclip_eps) ? 2.f * errc : 0.f; }
+    else { st[1] = err * err; dv = 2.f * err; }
+  } else { st[1] = err * err; dv = 2.f * err; }
+#pragma unroll
+  for (int j = 0; j < 32; j += 2) {
+    float g0 = 0.f, g1 = 0.f;
+    if (j < A) g0 = dlogp * z[j] * sig_inv[j];
+    else if (j == A) g0 = L.vf_coef * invB * dv;
+    if (j + 1 < A) g1 = dlogp * z[j + 1] * sig_inv[j + 1];
+    else if (j + 1 == A) g1 = L.vf_coef * invB * dv;
+    pk[j >> 1] = pack2bf(g0, g1);
+  }
+#pragma unroll
+  for (int j = 0; j < 32; ++j) dls[j] = j < A ? dlogp * (z[j] * z[j] - 1.f) : 0.f;
+}
+
+// Distillation loss of one sample: sum over the action dims of (pred - teacher)^2, scaled later.
+__device__ __forceinline__ void mse_loss_sample(const LossData& L, int64_t s, const float (&o)[HEAD_LD], uint32_t (&pk)[16], float (&st)[4]) {
+  const int A = L.A;
+  const float sc = 1.f / ((float)L.Bfull * (float)A);
+  float t[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) t[j] = L.action[s * A + (j < A ? j : A - 1)];
+  float l = 0.f, g[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) {
+    const float e = o[j] - t[j];
+    l += j < A ? e * e : 0.f;
+    g[j] = j < A ? 2.f * sc * e : 0.f;
+  }
+#pragma unroll
+  for (int j = 0; j < 32; j += 2) pk[j >> 1] = pack2bf(g[j], g[j + 1]);
+  st[0] = l; st[1] = 0.f; st[2] = 0.f; st[3] = 0.f;
+}
+
+// Sums of the four statistics and (if dls_part) of the A log-std terms over the block, in a fixed
+// order: xor-butterfly inside each wave (all sums side by side, so that their steps overlap), then
+// the wave sums.  Every thread of the block calls this (threads without a sample pass zeros);
+// wred: 4 x 36 floats of LDS.
+__device__ __forceinline__ void loss_block_sums(const float (&st)[4], const float (&dls)[32], int A, float (*wred)[36],
+                                                float* __restrict__ stat_part, float* __restrict__ dls_part) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int i = tid; i < 4 * 36; i += blockDim.x) (&wred[0][0])[i] = 0.f;  // waves the block does not have contribute zero
   __syncthreads();
   float rv[36];
 #pragma unroll
   for (int k = 0; k < 4; ++k) rv[k] = st[k];
 #pragma unroll
-  for (int j = 0; j < 32; ++j) rv[4 + j] = (ok && j < A) ? dlogp * (z[j] * z[j] - 1.f) : 0.f;
+  for (int j = 0; j < 32; ++j) rv[4 + j] = dls[j];
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1)
 #pragma unroll
     for (int k = 0; k < 36; ++k) rv[k] += __shfl_xor(rv[k], off);  // sums beyond 4 + A are zeros
-  if (lane == 0) {
+  if (lane == 0 && wave < 4) {
 #pragma unroll
     for (int k = 0; k < 36; ++k)
       if (k < 4 + A) wred[wave][k] = rv[k];
   }
   __syncthreads();
   if (tid < 4) stat_part[(int64_t)blockIdx.x * LOSS_NSTAT + tid] = (wred[0][tid] + wred[1][tid]) + (wred[2][tid] + wred[3][tid]);
-  else if (tid >= 32 && tid < 32 + A) {
+  else if (dls_part && tid >= 32 && tid < 32 + A) {
     const int j = tid - 32;
     dls_part[(int64_t)blockIdx.x * 32 + j] = (wred[0][4 + j] + wred[1][4 + j]) + (wred[2][4 + j] + wred[3][4 + j]);
   }
 }
 
-// Distillation loss: mean over batch and action dims of (pred - teacher)^2.
-__global__ __launch_bounds__(256) void k_mse_loss(int B, int Bfull, int A, const float* __restrict__ out,
-                                                  const int32_t* __restrict__ idx, const float* __restrict__ teacher,
-                                                  bf16_t* __restrict__ dout, float* __restrict__ stat_part) {
-  __shared__ float red[256];
-  const int tid = threadIdx.x, b = blockIdx.x * blockDim.x + tid;
-  float l = 0.f;
-  const float sc = 1.f / ((float)Bfull * (float)A);
-  if (b < B) {
-    const int64_t s = idx[b];
-    const float* o = out + (int64_t)b * HEAD_LD;
-    bf16_t* d = dout + (int64_t)b * HEAD_LD;
-    for (int j = 0; j < 32; ++j) {
-      float g = 0.f;
-      if (j < A) { float e = o[j] - teacher[s * A + j]; l += e * e; g = 2.f * sc * e; }
-      d[j] = f2bf(g);
-    }
-  }
-  red[tid] = l;
-  for (int i = tid + blockDim.x; i < 256; i += blockDim.x) red[i] = 0.f;
+// The losses on a chunk of `B` samples, one thread per sample (blocks of up to 256 threads): reads the
+// head outputs out[b][0..32), writes the gradient rows dout[b][0..32) (bf16) and per-block partial
+// sums of the statistics (and of dL/dlogstd for PPO).
+template <bool DISTILL>
+__global__ __launch_bounds__(256) void k_loss(int B, LossData L, const float* __restrict__ out, bf16_t* __restrict__ dout,
+                                              float* __restrict__ stat_part, float* __restrict__ dls_part) {
+  __shared__ float sig_inv[32], ls[32];
+  __shared__ float wred[4][36];
+  const int tid = threadIdx.x;
+  if (!DISTILL && tid < L.A) { ls[tid] = L.logstd[tid]; sig_inv[tid] = __expf(-L.logstd[tid]); }
   __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) { if (tid < s) red[tid] += red[tid + s]; __syncthreads(); }
-  if (tid == 0) {
-    float* sp = stat_part + (int64_t)blockIdx.x * LOSS_NSTAT;
-    sp[0] = red[0]; sp[1] = 0.f; sp[2] = 0.f; sp[3] = 0.f;
+  const int b = blockIdx.x * blockDim.x + tid;
+  float st[4] = {0.f, 0.f, 0.f, 0.f}, dls[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) dls[j] = 0.f;
+  if (b < B) {
+    const int64_t s = L.idx[b];
+    float o[HEAD_LD];  // the head's output row: eight 16-byte loads
+#pragma unroll
+    for (int q = 0; q < HEAD_LD / 4; ++q) {
+      const float4 v4 = *reinterpret_cast<const float4*>(out + (int64_t)b * HEAD_LD + 4 * q);
+      o[4 * q] = v4.x; o[4 * q + 1] = v4.y; o[4 * q + 2] = v4.z; o[4 * q + 3] = v4.w;
+    }
+    uint32_t pk[16];
+    if (DISTILL) mse_loss_sample(L, s, o, pk, st);
+    else ppo_loss_sample(L, sig_inv, ls, s, o, pk, st, dls);
+    // the row of 32 bf16 leaves as four 16-byte stores
+    uint4* d = reinterpret_cast<uint4*>(dout + (int64_t)b * HEAD_LD);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) d[q] = make_uint4(pk[4 * q], pk[4 * q + 1], pk[4 * q + 2], pk[4 * q + 3]);
   }
+  loss_block_sums(st, dls, DISTILL ? 0 : L.A, wred, stat_part, DISTILL ? nullptr : dls_part);
 }
 
 // Device-side record of one optimiser step (mirrors the host ppo_mb_stats layout).

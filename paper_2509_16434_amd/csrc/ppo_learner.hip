@@ -20,6 +20,7 @@
 #include "conv_dgrad_tile.hip.h"
 #include "conv_dgrad_wgrad0_tile.hip.h"
 #include "conv0_tile.hip.h"
+#include "head_loss.hip.h"
 
 static_assert(sizeof(DevStats) == sizeof(ppo_mb_stats), "device and host statistics records must match");
 
@@ -636,7 +637,7 @@ int launch_conv0_fwd_tile_t(Ctx* c, Conv0Args a, int nimg) {
 }
 
 // Forward of `n` samples selected by device indices idx (NULL = 0..n-1 offset by `first`).
-int forward_chunk(Ctx* c, const int32_t* idx, int n) {
+int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true) {
   const int V = c->V, nimg = n * V;
   {  // first convolution straight from the rollout buffer
     ImgAddr in; in.base = c->obs; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
@@ -688,7 +689,7 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n) {
     if (rc) return rc;
     x = c->fcact[l]; ldx = c->fout[l];
   }
-  {
+  if (with_head) {
     ARows al = plain_arows(x, ldx, n, c->hid);
     Ep<MapRows, float, true, false, false> ep;
     ep.map = plain_map(HEAD_LD, n); ep.out = c->headout; ep.bias = c->p + c->headB; ep.mask = nullptr; ep.N = c->NH;
@@ -700,11 +701,11 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n) {
 
 // Backward of the chunk whose forward activations are in the workspaces and whose head
 // gradient is in dhead.  Gradients land in c->g (overwritten, or added when `acc`).
-int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc) {
+int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc, bool with_head = true) {
   const int V = c->V, nimg = n * V;
   int cur = 0;
   const bf16_t* hlast = c->fcact[c->nfc - 1];
-  {  // heads
+  if (with_head) {  // heads (otherwise gbuf[0] already holds the gradient of the last hidden layer)
     ARows dl = plain_arows(c->dhead, HEAD_LD, n, HEAD_LD);
     ARows xl = plain_arows(hlast, c->hid, n, c->hid);
     int rc = launch_wgrad(c, dl, xl, c->NH, c->hid, n, c->g + c->headW, c->g + c->headB, acc, "head_wgrad", 2.0 * n * (c->hid + HEAD_LD));
@@ -835,6 +836,48 @@ int gen_permutation(Ctx* c, uint64_t seed, uint64_t update, uint64_t epoch) {
   return PPO_OK;
 }
 
+// Output layer forward, loss and output layer backward of a chunk in one kernel (head_loss.hip.h);
+// returns 1 when the width of the last hidden layer or the workspaces do not allow it.
+template <int HID>
+int launch_head_loss_t(Ctx* c, const LossData& L, int n, bool acc, bool distill, float* sp, float* dp) {
+  typedef HeadLossShape<HID> S;
+  const int nblk = cdiv(n, 64);
+  if ((int64_t)nblk * c->NH * HID > c->partial_elems || (int64_t)nblk * c->NH > c->bias_partial_elems) return 1;
+  HeadLossArgs a;
+  a.h = c->fcact[c->nfc - 1]; a.w = c->shadow + c->headW; a.wt = c->headT; a.bias = c->p + c->headB; a.dh = c->gbuf[0];
+  a.wpart = c->partial; a.bpart = c->bias_partial; a.stat_part = sp; a.dls_part = dp; a.n = n; a.NH = c->NH;
+  {
+    ProfScope ps(c, "head+loss", 6.0 * n * (double)HID * HEAD_LD, (double)n * (4.0 * HID + 4.0 * c->A + 20.0));
+    static bool attr_set[2] = {false, false};
+    if (distill) {
+      auto kfn = k_head_loss<HID, true>;
+      if (!attr_set[1]) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS_BYTES)); attr_set[1] = true; }
+      hipLaunchKernelGGL(kfn, dim3(nblk), dim3(256), S::LDS_BYTES, c->stream, a, L);
+    } else {
+      auto kfn = k_head_loss<HID, false>;
+      if (!attr_set[0]) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS_BYTES)); attr_set[0] = true; }
+      hipLaunchKernelGGL(kfn, dim3(nblk), dim3(256), S::LDS_BYTES, c->stream, a, L);
+    }
+    LAUNCHCHK(c, "k_head_loss");
+  }
+  const int64_t per = (int64_t)c->NH * HID;
+  ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)nblk + 1.0) * (double)per);
+  hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 32) + cdiv(c->NH, 32)), dim3(256), 0, c->stream, c->partial, nblk, per, c->g + c->headW, acc ? 1 : 0,
+                     c->bias_partial, (int64_t)c->NH, c->g + c->headB);
+  LAUNCHCHK(c, "k_reduce_partials");
+  return PPO_OK;
+}
+int launch_head_loss(Ctx* c, const LossData& L, int n, bool acc, bool distill, float* sp, float* dp) {
+  if (c->NH > HEAD_LD || c->nfc < 1) return 1;
+  switch (c->hid) {
+    case 32: return launch_head_loss_t<32>(c, L, n, acc, distill, sp, dp);
+    case 64: return launch_head_loss_t<64>(c, L, n, acc, distill, sp, dp);
+    case 128: return launch_head_loss_t<128>(c, L, n, acc, distill, sp, dp);
+    default: return 1;
+  }
+}
+bool head_loss_covers(const Ctx* c) { return c->NH <= HEAD_LD && c->nfc >= 1 && (c->hid == 32 || c->hid == 64 || c->hid == 128); }
+
 int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool distill) {
   const int B = c->S / hp->minibatches;
   const int steps = hp->epochs * hp->minibatches;
@@ -848,22 +891,36 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
       int nblocks = 0;
       for (int c0 = 0, ci = 0; c0 < B; c0 += c->CH, ++ci) {
         const int n = (B - c0 < c->CH) ? B - c0 : c->CH;
-        rc = forward_chunk(c, idx + c0, n);
+        const bool fused_head = head_loss_covers(c);
+        rc = forward_chunk(c, idx + c0, n, !fused_head);
         if (rc) return rc;
         float* sp = c->stat_part + (int64_t)ci * blocks_per_chunk * LOSS_NSTAT;
         float* dp = c->dls_part + (int64_t)ci * blocks_per_chunk * 32;
-        {
+        LossData L;
+        L.Bfull = B; L.A = c->A; L.logstd = distill ? nullptr : c->p + c->logstd; L.idx = idx + c0; L.action = c->action; L.logp_old = c->logp;
+        L.v_old = c->value; L.adv = c->adv; L.ret = c->ret; L.clip_eps = hp->clip_eps; L.vclip_eps = hp->vclip_eps; L.vf_coef = hp->vf_coef;
+        bool head_done = false;
+        if (fused_head) {
+          rc = launch_head_loss(c, L, n, c0 > 0, distill, sp, dp);
+          if (rc != PPO_OK && rc != 1) return rc;
+          head_done = rc == PPO_OK;
+          if (!head_done) {  // workspaces too small for the fused form: the output layer as a GEMM after all
+            ARows al = plain_arows(c->fcact[c->nfc - 1], c->hid, n, c->hid);
+            Ep<MapRows, float, true, false, false> ep;
+            ep.map = plain_map(HEAD_LD, n); ep.out = c->headout; ep.bias = c->p + c->headB; ep.mask = nullptr; ep.N = c->NH;
+            rc = launch_gemm(c, al, n, c->shadow + c->headW, c->hid, c->NH, c->hid, ep, "head_fwd", 2.0 * n * c->hid + 4.0 * n * c->NH);
+            if (rc) return rc;
+          }
+        }
+        if (!head_done) {
         ProfScope ps(c, "loss", 0.0, (double)n * (HEAD_LD * 6.0 + 4.0 * c->A + 20.0));
-        if (distill)
-          hipLaunchKernelGGL(k_mse_loss, dim3(cdiv(n, LOSS_BLOCK)), dim3(LOSS_BLOCK), 0, c->stream, n, B, c->A, c->headout, idx + c0, c->action, c->dhead, sp);
-        else
-          hipLaunchKernelGGL(k_ppo_loss, dim3(cdiv(n, LOSS_BLOCK)), dim3(LOSS_BLOCK), 0, c->stream, n, B, c->A, c->headout, c->p + c->logstd, idx + c0, c->action,
-                             c->logp, c->value, c->adv, c->ret, hp->clip_eps, hp->vclip_eps, hp->vf_coef, c->dhead, sp, dp);
+        if (distill) hipLaunchKernelGGL(k_loss<true>, dim3(cdiv(n, LOSS_BLOCK)), dim3(LOSS_BLOCK), 0, c->stream, n, L, c->headout, c->dhead, sp, dp);
+        else hipLaunchKernelGGL(k_loss<false>, dim3(cdiv(n, LOSS_BLOCK)), dim3(LOSS_BLOCK), 0, c->stream, n, L, c->headout, c->dhead, sp, dp);
         LAUNCHCHK(c, "loss kernel");
         }
         // partial slots of a ragged last chunk follow the full chunks contiguously
         nblocks = ci * blocks_per_chunk + cdiv(n, LOSS_BLOCK);
-        rc = backward_chunk(c, idx + c0, n, c0 > 0);
+        rc = backward_chunk(c, idx + c0, n, c0 > 0, !head_done);
         if (rc) return rc;
       }
       hipLaunchKernelGGL(k_loss_finalize, dim3(1), dim3(256), 0, c->stream, nblocks, B, c->A, distill ? 1 : 0, c->stat_part, c->dls_part,
