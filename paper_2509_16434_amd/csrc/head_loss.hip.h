@@ -59,6 +59,10 @@ __global__ __launch_bounds__(256) void k_head_loss(HeadLossArgs a, LossData L) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, h = lane >> 5;
   const int s0 = blockIdx.x * 64, ns = min(64, a.n - s0);  // this block's samples
 
+  // the loss's gathers from the rollout start now: their latency passes during steps 1 and 2
+  LossSample smp;
+  if (wave == 0 && lane < ns) smp = loss_gather(L, (int64_t)L.idx[s0 + lane], !DISTILL);
+
   // ---- 1. H rows (zeros beyond the chunk) in both pitches, W rows (zeros beyond NH)
   constexpr int CPR = HID / 8;  // 16-byte chunks per row
   for (int c = tid; c < 64 * CPR; c += 256) {
@@ -103,12 +107,11 @@ __global__ __launch_bounds__(256) void k_head_loss(HeadLossArgs a, LossData L) {
 #pragma unroll
     for (int q = 0; q < 16; ++q) pk[q] = 0u;
     if (lane < ns) {
-      const int64_t s = L.idx[s0 + lane];
       float o[HEAD_LD];
 #pragma unroll
       for (int j = 0; j < HEAD_LD; ++j) o[j] = Os[lane * 33 + j];
-      if (DISTILL) mse_loss_sample(L, s, o, pk, st);
-      else ppo_loss_sample(L, sgl, sgl + 32, s, o, pk, st, dls);
+      if (DISTILL) mse_loss_sample(L, smp, o, pk, st);
+      else ppo_loss_sample(L, sgl, sgl + 32, smp, o, pk, st, dls);
     }
     // the gradient row (zeros for lanes beyond the chunk) in both pitches
 #pragma unroll

@@ -422,15 +422,23 @@ struct LossData {
 // o: the head's output row (means, then the value).  Leaves the gradient row dL/dmu_0..A-1, dL/dV
 // (bf16 pairs, zero padded to 32 columns) in pk, this sample's terms of the four statistics in st and
 // of dL/dlogstd in dls.
-__device__ __forceinline__ void ppo_loss_sample(const LossData& L, const float* sig_inv, const float* ls, int64_t s, const float (&o)[HEAD_LD],
+// The rollout's values of one sample, gathered without a branch in between, so that every load is
+// issued before the first one is used: one memory latency, not A of them.
+struct LossSample { float act[32], lpo, adv, ret, vo; };
+__device__ __forceinline__ LossSample loss_gather(const LossData& L, int64_t s, bool ppo) {
+  LossSample g;
+  const int A = L.A;
+#pragma unroll
+  for (int j = 0; j < 32; ++j) g.act[j] = L.action[s * A + (j < A ? j : A - 1)];
+  g.lpo = ppo ? L.logp_old[s] : 0.f; g.adv = ppo ? L.adv[s] : 0.f; g.ret = ppo ? L.ret[s] : 0.f; g.vo = ppo ? L.v_old[s] : 0.f;
+  return g;
+}
+__device__ __forceinline__ void ppo_loss_sample(const LossData& L, const float* sig_inv, const float* ls, const LossSample& smp, const float (&o)[HEAD_LD],
                                                 uint32_t (&pk)[16], float (&st)[4], float (&dls)[32]) {
   const int A = L.A;
   const float invB = 1.f / (float)L.Bfull;
-  // every gather is issued before the first one is used (no branch between them): one memory latency, not A
-  float act[32];
-#pragma unroll
-  for (int j = 0; j < 32; ++j) act[j] = L.action[s * A + (j < A ? j : A - 1)];
-  const float lpo = L.logp_old[s], a = L.adv[s], r = L.ret[s], vo = L.v_old[s];
+  const float (&act)[32] = smp.act;
+  const float lpo = smp.lpo, a = smp.adv, r = smp.ret, vo = smp.vo;
   float z[32];
   float logp = 0.f;
 #pragma unroll
@@ -470,12 +478,10 @@ __device__ __forceinline__ void ppo_loss_sample(const LossData& L, const float* 
 }
 
 // Distillation loss of one sample: sum over the action dims of (pred - teacher)^2, scaled later.
-__device__ __forceinline__ void mse_loss_sample(const LossData& L, int64_t s, const float (&o)[HEAD_LD], uint32_t (&pk)[16], float (&st)[4]) {
+__device__ __forceinline__ void mse_loss_sample(const LossData& L, const LossSample& smp, const float (&o)[HEAD_LD], uint32_t (&pk)[16], float (&st)[4]) {
   const int A = L.A;
   const float sc = 1.f / ((float)L.Bfull * (float)A);
-  float t[32];
-#pragma unroll
-  for (int j = 0; j < 32; ++j) t[j] = L.action[s * A + (j < A ? j : A - 1)];
+  const float (&t)[32] = smp.act;
   float l = 0.f, g[32];
 #pragma unroll
   for (int j = 0; j < 32; ++j) {
@@ -543,8 +549,9 @@ __global__ __launch_bounds__(256) void k_loss(int B, LossData L, const float* __
       o[4 * q] = v4.x; o[4 * q + 1] = v4.y; o[4 * q + 2] = v4.z; o[4 * q + 3] = v4.w;
     }
     uint32_t pk[16];
-    if (DISTILL) mse_loss_sample(L, s, o, pk, st);
-    else ppo_loss_sample(L, sig_inv, ls, s, o, pk, st, dls);
+    const LossSample smp = loss_gather(L, s, !DISTILL);
+    if (DISTILL) mse_loss_sample(L, smp, o, pk, st);
+    else ppo_loss_sample(L, sig_inv, ls, smp, o, pk, st, dls);
     // the row of 32 bf16 leaves as four 16-byte stores
     uint4* d = reinterpret_cast<uint4*>(dout + (int64_t)b * HEAD_LD);
 #pragma unroll
