@@ -33,16 +33,16 @@ RIDGE_FLOP_PER_BYTE = PEAK_MFMA_BF16_TF * 1e12 / (PEAK_HBM_GBS * 1e9)  # 312.5
 
 # HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE and WRITE_SIZE in two runs of this
 # script, each scaled by what the same counter reads for the plain copy kernel of ppo_buffer_write in the
-# same run: x1.987 and x1.000).  The runs, the raw counter values and the commands are in
+# same run: x1.99 and x1.00).  The runs, the raw counter values and the commands are in
 # profiles/c1_medium_hbm_traffic.md; a kernel class or workload that was not measured reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("c1_medium", "conv_dgrad.1+wgrad.0"): 452.3e6,
-    ("c1_medium", "conv_wgrad.1"): 444.4e6,
-    ("c1_medium", "conv_fwd.0"): 302.6e6,
-    ("c1_medium", "conv_fwd.1"): 409.8e6,
-    ("c1_medium", "conv_dgrad.2"): 301.9e6,
-    ("c1_medium", "conv_wgrad.2"): 204.9e6,
-    ("c1_medium", "conv_fwd.2"): 167.7e6,
+    ("c1_medium", "conv_wgrad.1"): 428.4e6,
+    ("c1_medium", "conv_fwd.1"): 418.6e6,
+    ("c1_medium", "conv_fwd.0"): 319.1e6,
+    ("c1_medium", "conv_dgrad.1+wgrad.0"): 184.8e6,
+    ("c1_medium", "conv_dgrad.2"): 176.9e6,
+    ("c1_medium", "conv_wgrad.2"): 205.1e6,
+    ("c1_medium", "conv_fwd.2"): 167.9e6,
 }
 
 
