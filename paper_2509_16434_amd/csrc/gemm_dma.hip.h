@@ -1,6 +1,7 @@
-// C = A * B^T as in k_gemm, with the operand tiles brought from global memory straight into LDS
-// (global_load_lds_dwordx4: lane l's 16 bytes land at the wave's LDS base + 16*l, no registers in
-// between) through a ring of NST stages, so that NST-1 k-steps of 64 are in flight per block.
+// C = A * B^T as in k_gemm for deep reductions (K >= 1024), with the operand tiles brought from global
+// memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at the wave's LDS base
+// + 16*l, no registers in between) through a ring of NST stages, so that NST-1 k-steps of 64 are in
+// flight per block.
 //
 // Stage layout: A region [BM rows][8 chunks of 8 elements], B region [BN rows][8 chunks], rows 128
 // bytes apart with no padding.  One wave instruction fills 8 rows (lane = row*8 + position); the
@@ -8,35 +9,15 @@
 // operand reads (32 consecutive rows, one chunk) touch every LDS bank exactly once.  Rows beyond
 // the matrix, taps in the padding and k >= K are fetched from a page of zeros.
 //
-// The compiler orders every LDS access after all outstanding LDS-writing loads, which would drain
-// the ring at each step; the operand reads are therefore issued as inline ds_read_b128 and the
-// step is ordered by hand: s_waitcnt vmcnt(loads of the younger stages) ; s_barrier ; reads.
+// The compiler orders every LDS access of a wave after all of that wave's outstanding LDS-writing
+// loads, which would drain the ring at each step if one wave did both; here the loads belong to
+// loader waves, whose only waits are explicit (s_waitcnt vmcnt(loads of the younger stages)).
 #pragma once
 #include "gemm.hip.h"
 
 #define GLOBAL_AS(p) ((const void __attribute__((address_space(1)))*)(p))
 #define LDS_AS(p) ((void __attribute__((address_space(3)))*)(p))
 
-template <int OFF>
-__device__ __forceinline__ bf16x8_t lds_read16(uint32_t byte_addr) {
-  bf16x8_t v;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(byte_addr), "n"(OFF) : "memory");
-  return v;
-}
-// the values read by lds_read16 may be used after this
-template <int NA, int NB>
-__device__ __forceinline__ void lds_read_wait(bf16x8_t (&a)[NA], bf16x8_t (&b)[NB]) {
-  static_assert(NA <= 8 && NB <= 8, "operand count");
-  if constexpr (NA == 4 && NB == 4)
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]));
-  else if constexpr (NA == 8 && NB == 4)
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]),
-                 "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]));
-  else if constexpr (NA == 8 && NB == 8)
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]),
-                 "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]), "+v"(b[4]), "+v"(b[5]), "+v"(b[6]), "+v"(b[7]));
-  else static_assert(NA == 4 && NB == 4, "unsupported operand count");
-}
 // wait until at most N of this wave's vector-memory loads are outstanding (expcnt, lgkmcnt untouched)
 template <int N>
 __device__ __forceinline__ void vm_wait() {
@@ -56,127 +37,12 @@ __device__ __forceinline__ void vm_wait_dyn(int n) {
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int NST, class AL, class EP>
-__global__ __launch_bounds__(256) void k_gemm_dma(AL al, const bf16_t* __restrict__ Bm_, int64_t ldb_, int N, EP ep,
-                                                  const bf16_t* __restrict__ zpage) {
-  constexpr int TM = BM / (WGM * 32), TN = BN / (WGN * 32);
-  static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && NST >= 2 && NST <= 8, "tile shape");
-  constexpr int BK = 64;
-  constexpr int AI = BM / 32, BI = BN / 32;  // loads per wave per stage (8 rows each)
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, ST_BYTES = A_BYTES + B_BYTES;
-  constexpr int D = NST - 1;                 // stages in flight
-  static_assert(BM * (BN + 8) * 2 <= NST * ST_BYTES, "staging tile must fit in the ring");
-  static_assert(D * (AI + BI) < 64, "vmcnt range");
-  extern __shared__ __attribute__((aligned(16))) bf16_t ring[];
-  __shared__ int64_t rowoff[BM];
-  __shared__ int rowcols[BM];
-
-  const typename AL::Cls acls = al.cls(blockIdx.z);
-  const auto mcls = ep.map.cls(blockIdx.z);
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-  if (m0 >= acls.M) return;
-  const int K = acls.K;
-  const bf16_t* Bm = al.bmat(acls, Bm_);
-  const int64_t ldb = (Bm == Bm_) ? ldb_ : (int64_t)K;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WGN, wn = wave % WGN;
-  const int dr = lane >> 3, dpos = lane & 7;
-
-  // rows r = (wave*AI + j)*8 + dr: the swizzle (r >> 1) & 7 depends on j only through its parity
-  static_assert(AI % 2 == 0, "row groups per wave");
-  typename AL::Row arow[AI];
-#pragma unroll
-  for (int j = 0; j < AI; ++j) arow[j] = al.row(m0 + (wave * AI + j) * 8 + dr, acls);
-  typename AL::KCur acur[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) acur[j] = al.kcur((dpos ^ ((j * 4 + (dr >> 1)) & 7)) * 8, acls);
-  const bf16_t* brow[BI];
-  int b_k[BI];
-#pragma unroll
-  for (int j = 0; j < BI; ++j) {
-    const int r = (wave * BI + j) * 8 + dr, n = n0 + r;
-    brow[j] = (n < N) ? Bm + (int64_t)n * ldb : nullptr;
-    b_k[j] = (dpos ^ ((r >> 1) & 7)) * 8;
-  }
-  char* const ring_b = reinterpret_cast<char*>(ring);
-  // stages are issued in order of k, so the column cursors simply step along
-  auto issue = [&](int stage, int k0) {
-    char* sb = ring_b + stage * ST_BYTES;
-#pragma unroll
-    for (int j = 0; j < AI; ++j) {
-      const bf16_t* p = al.addr(arow[j], acur[j & 1], acls);
-      if (!p) p = zpage;
-      __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(sb + (wave * AI + j) * 1024), 16, 0, 0);
-    }
-#pragma unroll
-    for (int j = 0; j < BI; ++j) {
-      const int k = k0 + b_k[j];
-      const bf16_t* p = (brow[j] && k < K) ? brow[j] + k : zpage;
-      __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(sb + A_BYTES + (wave * BI + j) * 1024), 16, 0, 0);
-    }
-    al.kstep(acur[0], BK, acls);
-    al.kstep(acur[1], BK, acls);
-  };
-
-  f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  const int nk = (K + BK - 1) / BK;
-#pragma unroll
-  for (int s = 0; s < D; ++s)
-    if (s < nk) issue(s, s * BK);
-
-  // operand read addresses within a stage: row (tile*32 + lane%32), chunk (ks*2 + lane/32) ^ swizzle
-  const int l32 = lane & 31, h = lane >> 5, sw = (l32 >> 1) & 7;
-  const uint32_t lds0 = (uint32_t)(size_t)LDS_AS(ring_b);
-  uint32_t rd[4];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) rd[ks] = lds0 + l32 * 128 + (((ks * 2 + h) ^ sw) * 16);
-  const uint32_t offA = wm * TM * 4096, offB = A_BYTES + wn * TN * 4096;
-
-  int st = 0;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int younger = min(D - 1, nk - 1 - kt);  // stages issued after stage kt
-    vm_wait_dyn(younger * (AI + BI));
-    __builtin_amdgcn_s_barrier();  // stage kt has landed for every wave; the stage read last step is free
-    if (kt + D < nk) issue(st == 0 ? NST - 1 : st - 1, (kt + D) * BK);
-    const uint32_t sA = st * ST_BYTES + offA, sB = st * ST_BYTES + offB;
-    bf16x8_t a[TM * 4], b[TN * 4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      if constexpr (TM >= 1) a[ks * TM + 0] = lds_read16<0>(rd[ks] + sA);
-      if constexpr (TM >= 2) a[ks * TM + 1] = lds_read16<4096>(rd[ks] + sA);
-      if constexpr (TN >= 1) b[ks * TN + 0] = lds_read16<0>(rd[ks] + sB);
-      if constexpr (TN >= 2) b[ks * TN + 1] = lds_read16<4096>(rd[ks] + sB);
-    }
-    lds_read_wait(a, b);
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks * TN + j], a[ks * TM + i], acc[i][j], 0, 0, 0);
-    st = (st == NST - 1) ? 0 : st + 1;
-  }
-  __builtin_amdgcn_s_barrier();  // every wave is done reading; the ring becomes the staging tile
-  gemm_epilogue<BM, BN, TM, TN>(acc, ep, mcls, m0, n0, N, wm, wn, ring, rowoff, rowcols);
-}
-
-// The same product with the two jobs of a block given to different waves: WGM x WGN compute waves
-// (MFMAs on operands read from the ring with ordinary LDS reads) and four loader waves that do
-// nothing but keep NST-1 stages of LDS-writing loads in flight.  In k_gemm_dma every wave issues
-// its share of a stage (some hundred cycles during which it computes nothing), waits, and
-// computes; here the loaders' issue time and the compute waves' LDS and MFMA time overlap, and a
-// compute wave never has an LDS-writing load of its own in flight, so the compiler's ordering of
-// LDS reads after such loads costs nothing.  One barrier per k-step: the loaders arrive when their
-// part of stage kt has landed, the compute waves when they are done with stage kt-1 (whose slot
-// the loaders refill next).  Stage layout and chunk permutation as in k_gemm_dma.
+// The two jobs of a block belong to different waves: WGM x WGN compute waves (MFMAs on operands read
+// from the ring with ordinary LDS reads, all reads of a k-step before its first MFMA) and four loader
+// waves that do nothing but keep NST-1 stages of LDS-writing loads in flight.  A wave that did both
+// would spend some hundred cycles per stage issuing its loads, computing nothing meanwhile.  One
+// barrier per k-step: the loaders arrive when their part of stage kt has landed, the compute waves
+// when they are done with stage kt-1 (whose slot the loaders refill next).
 template <int BM, int BN, int WGM, int WGN, int NST, class AL, class EP>
 __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_gemm_rs(AL al, const bf16_t* __restrict__ Bm_, int64_t ldb_, int N, EP ep,
                                                                   const bf16_t* __restrict__ zpage) {

@@ -305,20 +305,13 @@ int launch_gemm(Ctx* c, const AL& al_, int M, const bf16_t* Bm, int64_t ldb, int
     dim3 grid(GX, GY, zdim);                                                                                             \
     if constexpr (WM_ * WN_ != 4) {                                                                                      \
       LAUNCH_GEMM_RS(BM_, BN_, WM_, WN_);                                                                                \
-    } else if (K >= 1024 && sizeof(typename EP::out_t) == 2) {                                                           \
-      LAUNCH_GEMM_RS(BM_, BN_, WM_, WN_);                                                                                \
     } else if (K >= 1024) {                                                                                              \
-      constexpr int nst = (BM_ + BN_) * 128 * 8 <= 128 * 1024 ? 8 : ((BM_ + BN_) * 128 * 5 <= 128 * 1024 ? 5 : 4);          \
-      auto kfn = k_gemm_dma<BM_, BN_, WM_, WN_, nst, AL, EP>;                                                            \
-      constexpr int lds = nst * (BM_ + BN_) * 128;                                                                       \
-      static bool attr_set = false;                                                                                      \
-      if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, lds)); attr_set = true; } \
-      hipLaunchKernelGGL(kfn, grid, blk, lds, c->stream, al, Bm, ldb, N, ep, c->zpage);                                   \
+      LAUNCH_GEMM_RS(BM_, BN_, WM_, WN_);                                                                                \
     } else if (K >= 128) hipLaunchKernelGGL((k_gemm<BM_, BN_, WM_, WN_, 64, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep); \
     else hipLaunchKernelGGL((k_gemm<BM_, BN_, WM_, WN_, 32, AL, EP>), grid, blk, 0, c->stream, al, Bm, ldb, N, ep);        \
   } while (0)
   if (N > 64) {
-    if (K >= 1024 && sizeof(typename EP::out_t) == 2 && (int64_t)cdiv(M, 256) * cdiv(N, 128) * zdim >= 256) LAUNCH_GEMM(256, 128, 4, 2, cdiv(M, 256), cdiv(N, 128));
+    if (K >= 1024 && (int64_t)cdiv(M, 256) * cdiv(N, 128) * zdim >= 256) LAUNCH_GEMM(256, 128, 4, 2, cdiv(M, 256), cdiv(N, 128));
     else if ((int64_t)cdiv(M, 128) * cdiv(N, 128) * zdim >= 256 || M <= 64) LAUNCH_GEMM(128, 128, 2, 2, cdiv(M, 128), cdiv(N, 128));
     else LAUNCH_GEMM(64, 64, 2, 2, cdiv(M, 64), cdiv(N, 64));
   } else if (N > 32) {

@@ -43,7 +43,8 @@ def _setup(L, cfg, max_chunk=0, seed=None):
 
 # ------------------------------------------------------------------ MFMA tile kernel
 @pytest.mark.parametrize("M,N,K", [(128, 128, 64), (200, 24, 72), (300, 64, 288), (129, 130, 8), (64, 512, 1056), (1, 1, 8),
-                                   (300, 40, 1032), (129, 20, 2048), (32773, 48, 1024)])
+                                   (300, 40, 1032), (129, 20, 2048), (32773, 48, 1024),
+                                   (32768 + 37, 250, 1096)])  # the last: 256 x 128 tiles, eight compute waves
 def test_mfma_gemm_tiles(L, M, N, K):
     rng = np.random.default_rng(M * 7 + N)
     a = synth.narrow_bf16(rng.standard_normal((M, K)).astype(np.float32))
