@@ -21,6 +21,7 @@
 #include "conv_dgrad_wgrad0_tile.hip.h"
 #include "conv0_tile.hip.h"
 #include "head_loss.hip.h"
+#include "wgrad_rs.hip.h"
 
 static_assert(sizeof(DevStats) == sizeof(ppo_mb_stats), "device and host statistics records must match");
 
@@ -332,10 +333,56 @@ ARows plain_arows(const bf16_t* base, int64_t ld, int M, int K) {
 }
 MapRows plain_map(int64_t ld, int M) { MapRows m; m.stride_b = ld; m.stride_v = 0; m.V = 1; m.HW = 1; m.C = 0; m.M = M; return m; }
 
+// Wide plain weight gradient through the LDS-ring kernel (wgrad_rs.hip.h); returns 1 when the shape is not covered.
+int launch_wgrad_rs(Ctx* c, const bf16_t* dy, int64_t ld_dy, const bf16_t* x, int64_t ld_x, int Nn, int Kk, int M, float* gw, float* gb, bool accumulate,
+                    const std::string& name, double abytes) {
+  typedef WgradRsShape S;
+  if (Nn < 128 || Kk < 1024 || Nn % 8 || Kk % 8 || ld_dy % 8 || ld_x % 8 || M < 128) return 1;
+  const int tiles = cdiv(Kk, S::TK) * cdiv(Nn, S::TN);
+  // few splits (their fp32 partials cost traffic), but enough blocks to fill the chip's 256 CUs in whole rounds
+  int splits = 1;
+  double best = 0.0;
+  for (int sp = 1; sp <= 8; ++sp) {
+    if (cdiv(M, sp) < 512 && sp > 1) break;
+    const int blocks = tiles * sp;
+    const double eff = (double)blocks / (double)(cdiv(blocks, 256) * 256) - 0.03 * (sp - 1);
+    if (eff > best + 1e-9) { best = eff; splits = sp; }
+  }
+  const int64_t per = (int64_t)Nn * Kk;
+  if (splits > 1 && ((int64_t)splits * per > c->partial_elems || (gb && (int64_t)splits * Nn > c->bias_partial_elems))) splits = 1;
+  int rows = cdiv(M, splits);
+  rows = (rows + S::ROWS - 1) / S::ROWS * S::ROWS;
+  splits = cdiv(M, rows);
+  WgradRsArgs a;
+  a.dy = dy; a.ld_dy = ld_dy; a.x = x; a.ld_x = ld_x; a.M = M; a.Nn = Nn; a.Kk = Kk; a.rows_per_split = rows; a.zpage = c->zpage;
+  a.direct = splits == 1 ? 1 : 0; a.accumulate = accumulate ? 1 : 0;
+  a.out = a.direct ? gw : c->partial; a.bias_out = gb ? (a.direct ? gb : c->bias_partial) : nullptr;
+  {
+    ProfScope ps(c, name, 2.0 * M * (double)Nn * Kk, abytes);
+    static bool attr_set = false;
+    if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)k_wgrad_rs, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS_BYTES)); attr_set = true; }
+    hipLaunchKernelGGL(k_wgrad_rs, dim3(cdiv(Kk, S::TK), cdiv(Nn, S::TN), splits), dim3(S::THREADS), S::LDS_BYTES, c->stream, a);
+    LAUNCHCHK(c, "k_wgrad_rs");
+  }
+  if (splits > 1) {
+    ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)splits + 1.0) * (double)per);
+    hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 32) + (gb ? cdiv(Nn, 32) : 0)), dim3(256), 0, c->stream, c->partial, splits, per, gw, accumulate ? 1 : 0,
+                       gb ? c->bias_partial : nullptr, (int64_t)(gb ? Nn : 0), gb);
+    LAUNCHCHK(c, "k_reduce_partials");
+  }
+  return PPO_OK;
+}
+
 // G[Nn][Kk] (+)= Dy^T * A over M rows, plus optional bias gradient gb[Nn].
 template <class DL, class AL>
 int launch_wgrad(Ctx* c, const DL& dl_, const AL& al_, int Nn, int Kk, int M, float* gw, float* gb, bool accumulate, const std::string& name, double abytes) {
   if (M <= 0) return PPO_OK;
+  if constexpr (std::is_same<DL, ARows>::value && std::is_same<AL, ARows>::value) {
+    if (dl_.plain && al_.plain) {
+      const int rc = launch_wgrad_rs(c, dl_.a.base, dl_.a.stride_b, al_.a.base, al_.a.stride_b, Nn, Kk, M, gw, gb, accumulate, name, abytes);
+      if (rc != 1) return rc;
+    }
+  }
   DL dl = dl_; AL al = al_;
   dl.prepare(); al.prepare();
   const char* what = name.c_str();
