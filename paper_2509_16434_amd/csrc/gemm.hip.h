@@ -558,58 +558,79 @@ __global__ __launch_bounds__(256) void k_wgrad(DL dl, AL al, int Nn, int Kk, int
   }
 }
 
-// Sum over s of partial[s][i] for one output per lane: a block covers 32 outputs with 8 lanes of
-// splits each (lane j sums s = j, j+8, ... with four running sums, four loads in flight); the 8
-// lane sums are combined in a fixed order, so the result does not depend on scheduling.  Returns
-// the sum in the lanes with threadIdx.x < 32.
-__device__ __forceinline__ float reduce_partials_block(const float* __restrict__ partial, int splits, int64_t n, int64_t i, float (*red)[33]) {
+// Sum over s of partial[s][i .. i+W-1] for W (1 or 4) consecutive outputs per lane: a block covers
+// 32*W outputs with 8 lanes of splits each (lane j sums s = j, j+8, ... with four running sums, four
+// loads in flight); the 8 lane sums are combined in a fixed order, so the result does not depend on
+// scheduling.  The sums are valid in the lanes with threadIdx.x < 32.
+template <int W>
+__device__ __forceinline__ void reduce_partials_block(const float* __restrict__ partial, int splits, int64_t n, int64_t i, float (*red)[33 * W], float (&out)[W]) {
+  typedef float vec_t __attribute__((ext_vector_type(W)));
   const int o = threadIdx.x & 31, sl = threadIdx.x >> 5;
-  float s0 = 0.f, s1 = 0.f;
+  vec_t s0 = 0.f, s1 = 0.f;
   if (i < n) {
+    auto ld = [&](int k) -> vec_t { return *reinterpret_cast<const vec_t*>(partial + (int64_t)k * n + i); };
     int k = sl;
-    float s2 = 0.f, s3 = 0.f;
+    vec_t s2 = 0.f, s3 = 0.f;
     for (; k + 24 < splits; k += 32) {
-      const float v0 = partial[(int64_t)k * n + i], v1 = partial[(int64_t)(k + 8) * n + i];
-      const float v2 = partial[(int64_t)(k + 16) * n + i], v3 = partial[(int64_t)(k + 24) * n + i];
+      const vec_t v0 = ld(k), v1 = ld(k + 8), v2 = ld(k + 16), v3 = ld(k + 24);
       s0 += v0; s1 += v1; s2 += v2; s3 += v3;
     }
     s0 += s2; s1 += s3;
-    for (; k + 8 < splits; k += 16) { s0 += partial[(int64_t)k * n + i]; s1 += partial[(int64_t)(k + 8) * n + i]; }
-    if (k < splits) s0 += partial[(int64_t)k * n + i];
+    for (; k + 8 < splits; k += 16) { s0 += ld(k); s1 += ld(k + 8); }
+    if (k < splits) s0 += ld(k);
   }
-  red[sl][o] = s0 + s1;
+  s0 += s1;
+#pragma unroll
+  for (int w = 0; w < W; ++w) red[sl][o * W + w] = s0[w];
   __syncthreads();
-  return ((red[0][o] + red[1][o]) + (red[2][o] + red[3][o])) + ((red[4][o] + red[5][o]) + (red[6][o] + red[7][o]));
-}
-
-// dst[i] = (accumulate ? dst[i] : 0) + sum_s partial[s][i], and in the same launch (blocks past the
-// first ceil(n / 32)) the same for a second, small set of partials (the bias gradient), if given.
-__global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ partial, int splits, int64_t n,
-                                                         float* __restrict__ dst, int accumulate,
-                                                         const float* __restrict__ partial2, int64_t n2, float* __restrict__ dst2) {
-  __shared__ float red[8][33];
-  const int64_t main_blocks = (n + 31) / 32;
-  const bool second = (int64_t)blockIdx.x >= main_blocks;
-  const float* pp = second ? partial2 : partial;
-  const int64_t nn = second ? n2 : n, i = ((int64_t)blockIdx.x - (second ? main_blocks : 0)) * 32 + (threadIdx.x & 31);
-  float* dd = second ? dst2 : dst;
-  const float s = reduce_partials_block(pp, splits, nn, i, red);
-  if (threadIdx.x < 32 && i < nn) dd[i] = accumulate ? dd[i] + s : s;
-}
-
-// The same for main partials stored transposed: dst[n*K + k] (+)= sum_s partial[s][k*N + n].
-__global__ __launch_bounds__(256) void k_reduce_partials_t(const float* __restrict__ partial, int splits, int N, int K,
-                                                           float* __restrict__ dst, int accumulate,
-                                                           const float* __restrict__ partial2, int64_t n2, float* __restrict__ dst2) {
-  __shared__ float red[8][33];
-  const int64_t n_all = (int64_t)N * K, main_blocks = (n_all + 31) / 32;
-  const bool second = (int64_t)blockIdx.x >= main_blocks;
-  const int64_t nn = second ? n2 : n_all, i = ((int64_t)blockIdx.x - (second ? main_blocks : 0)) * 32 + (threadIdx.x & 31);
-  const float s = reduce_partials_block(second ? partial2 : partial, splits, nn, i, red);
-  if (threadIdx.x < 32 && i < nn) {
-    float* d;
-    if (second) d = dst2 + i;
-    else { const int kk = (int)(i / N), n = (int)(i - (int64_t)kk * N); d = dst + (int64_t)n * K + kk; }
-    *d = accumulate ? *d + s : s;
+#pragma unroll
+  for (int w = 0; w < W; ++w) {
+    const int c = o * W + w;
+    out[w] = ((red[0][c] + red[1][c]) + (red[2][c] + red[3][c])) + ((red[4][c] + red[5][c]) + (red[6][c] + red[7][c]));
   }
 }
+
+// Every pending reduction of a backward pass in one launch: job j covers blocks [first[j], first[j+1]).
+// kind 0: dst[i] (+)= sum_s partial[s][i]; kind 1: partials stored transposed, dst[n*K + k] (+)=
+// sum_s partial[s][k*N + n]; kind 2: partial[s][co][K+1] of the first convolution, whose last column
+// is the bias gradient (dst2).  Jobs with vec set (n a multiple of 4, partials 16-byte aligned) take
+// four outputs per lane with 16-byte loads (128 outputs per block), the others one (32 per block).
+struct ReduceJobs {
+  static constexpr int MAXJ = 16;
+  int njobs;
+  int first[MAXJ + 1];
+  int kind[MAXJ], splits[MAXJ], N[MAXJ], K[MAXJ], accumulate[MAXJ], vec[MAXJ];
+  int64_t n[MAXJ];
+  const float* partial[MAXJ];
+  float* dst[MAXJ];
+  float* dst2[MAXJ];
+};
+__global__ __launch_bounds__(256) void k_reduce_batch(ReduceJobs jobs) {
+  __shared__ float red[8][33 * 4];
+  int j = 0;
+  while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first[j + 1]) ++j;
+  const int64_t nn = jobs.n[j];
+  const int kind = jobs.kind[j], blk = (int)blockIdx.x - jobs.first[j];
+  auto put = [&](int64_t i, float s) {
+    float* d;
+    if (kind == 0) d = jobs.dst[j] + i;
+    else if (kind == 1) { const int N = jobs.N[j], kk = (int)(i / N), n = (int)(i - (int64_t)kk * N); d = jobs.dst[j] + (int64_t)n * jobs.K[j] + kk; }
+    else { const int KP = jobs.K[j] + 1, co = (int)(i / KP), k = (int)(i - (int64_t)co * KP); d = k == jobs.K[j] ? jobs.dst2[j] + co : jobs.dst[j] + (int64_t)co * jobs.K[j] + k; }
+    *d = jobs.accumulate[j] ? *d + s : s;
+  };
+  if (jobs.vec[j]) {
+    const int64_t i = ((int64_t)blk * 32 + (threadIdx.x & 31)) * 4;
+    float s[4];
+    reduce_partials_block<4>(jobs.partial[j], jobs.splits[j], nn, i, red, s);
+    if (threadIdx.x < 32 && i < nn) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) put(i + w, s[w]);
+    }
+  } else {
+    const int64_t i = (int64_t)blk * 32 + (threadIdx.x & 31);
+    float s[1];
+    reduce_partials_block<1>(jobs.partial[j], jobs.splits[j], nn, i, reinterpret_cast<float (*)[33]>(&red[0][0]), s);
+    if (threadIdx.x < 32 && i < nn) put(i, s[0]);
+  }
+}
+

@@ -373,23 +373,6 @@ __global__ __launch_bounds__(256) void k_conv1_wgrad(ImgAddr in, int n_img, int 
     P[i] = (wsum[0][s] + wsum[1][s]) + (wsum[2][s] + wsum[3][s]);
   }
 }
-// Sum conv1 partials: partial[nb][Cout][K+1] -> gw[Cout][K], gb[Cout].  One block per output
-// element; strided partial sums, then a fixed-order tree.
-__global__ __launch_bounds__(256) void k_conv1_wgrad_reduce(const float* __restrict__ partial, int nb, int Cout, int K,
-                                                            float* __restrict__ gw, float* __restrict__ gb, int accumulate) {
-  __shared__ float red[256];
-  const int pr = blockIdx.x, KP = K + 1, npair = Cout * KP, tid = threadIdx.x;
-  float s = 0.f;
-  for (int b = tid; b < nb; b += 256) s += partial[(int64_t)b * npair + pr];
-  red[tid] = s;
-  __syncthreads();
-  for (int w = 128; w > 0; w >>= 1) { if (tid < w) red[tid] += red[tid + w]; __syncthreads(); }
-  if (tid == 0) {
-    const int co = pr / KP, k = pr - co * KP;
-    float* dst = (k == K) ? gb + co : gw + co * K + k;
-    *dst = (accumulate ? *dst : 0.f) + red[0];
-  }
-}
 
 // ---------------------------------------------------------------- gather of small per-sample data
 // proprio (bf16 in the buffer) -> columns [col0, col0+P) of the feature matrix.

@@ -71,7 +71,14 @@ struct Ctx {
   bf16_t* gbuf[2] = {nullptr, nullptr};
   float *partial = nullptr, *bias_partial = nullptr;
   bf16_t* zpage = nullptr;  // 1 KiB of zeros: source of out-of-range operand fetches
+  // partial / bias_partial are cursors into the two workspaces and *_elems what is left behind them:
+  // every weight-gradient kernel of a backward pass takes its partials from the cursor and queues its
+  // reduction (defer_reduce); flush_reduces sums them all in one launch and rewinds the cursors
   int64_t partial_elems = 0, bias_partial_elems = 0;
+  float *partial_base = nullptr, *bias_partial_base = nullptr;
+  int64_t partial_cap = 0, bias_partial_cap = 0;
+  ReduceJobs rjobs;
+  int rjob_blocks = 0;
   float *stat_part = nullptr, *dls_part = nullptr, *sq_part = nullptr;
   int max_loss_blocks = 0, adam_blocks = 0;
   DevStats* dstats = nullptr;
@@ -333,6 +340,47 @@ ARows plain_arows(const bf16_t* base, int64_t ld, int M, int K) {
 }
 MapRows plain_map(int64_t ld, int M) { MapRows m; m.stride_b = ld; m.stride_v = 0; m.V = 1; m.HW = 1; m.C = 0; m.M = M; return m; }
 
+// All queued partial-sum reductions in one launch; the partial workspaces are free again afterwards.
+int flush_reduces(Ctx* c) {
+  ReduceJobs& J = c->rjobs;
+  if (J.njobs > 0) {
+    double bytes = 0.0;
+    for (int j = 0; j < J.njobs; ++j) bytes += 4.0 * ((double)J.splits[j] + 1.0) * (double)J.n[j];
+    ProfScope ps(c, "wgrad_reduce", 0.0, bytes);
+    J.first[J.njobs] = c->rjob_blocks;
+    for (int j = J.njobs + 1; j <= ReduceJobs::MAXJ; ++j) J.first[j] = c->rjob_blocks;
+    hipLaunchKernelGGL(k_reduce_batch, dim3(c->rjob_blocks), dim3(256), 0, c->stream, J);
+    LAUNCHCHK(c, "k_reduce_batch");
+  }
+  J.njobs = 0; c->rjob_blocks = 0;
+  c->partial = c->partial_base; c->partial_elems = c->partial_cap;
+  c->bias_partial = c->bias_partial_base; c->bias_partial_elems = c->bias_partial_cap;
+  return PPO_OK;
+}
+// Make room for a kernel that would like `need` partial and `bneed` bias-partial elements.
+int ensure_partial(Ctx* c, int64_t need, int64_t bneed) {
+  if (need > c->partial_elems || bneed > c->bias_partial_elems || c->rjobs.njobs + 2 > ReduceJobs::MAXJ) return flush_reduces(c);
+  return PPO_OK;
+}
+// Queue the reduction of `splits` partials of n elements that start at the cursor (kind as in ReduceJobs) and
+// move the cursor behind them; with bias: the same for `splits` bias partials of nb elements (plain sums).
+void defer_reduce(Ctx* c, int kind, int splits, int64_t n, int N, int K, float* dst, float* dst2, bool accumulate, bool with_bias, int64_t nb, float* bdst) {
+  ReduceJobs& J = c->rjobs;
+  auto add = [&](int kd, const float* part, int64_t nn, float* d, float* d2) {
+    const int j = J.njobs++;
+    J.first[j] = c->rjob_blocks; J.kind[j] = kd; J.splits[j] = splits; J.N[j] = N; J.K[j] = K; J.accumulate[j] = accumulate ? 1 : 0;
+    J.n[j] = nn; J.partial[j] = part; J.dst[j] = d; J.dst2[j] = d2;
+    J.vec[j] = (nn % 4 == 0 && (reinterpret_cast<uintptr_t>(part) & 15) == 0) ? 1 : 0;
+    c->rjob_blocks += cdiv(nn, J.vec[j] ? 128 : 32);
+  };
+  add(kind, c->partial, n, dst, dst2);
+  c->partial += (int64_t)splits * n; c->partial_elems -= (int64_t)splits * n;
+  if (with_bias) {
+    add(0, c->bias_partial, nb, bdst, nullptr);
+    c->bias_partial += (int64_t)splits * nb; c->bias_partial_elems -= (int64_t)splits * nb;
+  }
+}
+
 // Wide plain weight gradient through the LDS-ring kernel (wgrad_rs.hip.h); returns 1 when the shape is not covered.
 int launch_wgrad_rs(Ctx* c, const bf16_t* dy, int64_t ld_dy, const bf16_t* x, int64_t ld_x, int Nn, int Kk, int M, float* gw, float* gb, bool accumulate,
                     const std::string& name, double abytes) {
@@ -349,6 +397,7 @@ int launch_wgrad_rs(Ctx* c, const bf16_t* dy, int64_t ld_dy, const bf16_t* x, in
     if (eff > best + 1e-9) { best = eff; splits = sp; }
   }
   const int64_t per = (int64_t)Nn * Kk;
+  if (splits > 1) { const int erc = ensure_partial(c, (int64_t)splits * per, gb ? (int64_t)splits * Nn : 0); if (erc) return erc; }
   if (splits > 1 && ((int64_t)splits * per > c->partial_elems || (gb && (int64_t)splits * Nn > c->bias_partial_elems))) splits = 1;
   int rows = cdiv(M, splits);
   rows = (rows + S::ROWS - 1) / S::ROWS * S::ROWS;
@@ -364,12 +413,7 @@ int launch_wgrad_rs(Ctx* c, const bf16_t* dy, int64_t ld_dy, const bf16_t* x, in
     hipLaunchKernelGGL(k_wgrad_rs, dim3(cdiv(Kk, S::TK), cdiv(Nn, S::TN), splits), dim3(S::THREADS), S::LDS_BYTES, c->stream, a);
     LAUNCHCHK(c, "k_wgrad_rs");
   }
-  if (splits > 1) {
-    ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)splits + 1.0) * (double)per);
-    hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 32) + (gb ? cdiv(Nn, 32) : 0)), dim3(256), 0, c->stream, c->partial, splits, per, gw, accumulate ? 1 : 0,
-                       gb ? c->bias_partial : nullptr, (int64_t)(gb ? Nn : 0), gb);
-    LAUNCHCHK(c, "k_reduce_partials");
-  }
+  if (splits > 1) defer_reduce(c, 0, splits, per, 0, 0, gw, nullptr, accumulate, gb != nullptr, Nn, gb);
   return PPO_OK;
 }
 
@@ -394,6 +438,7 @@ int launch_wgrad(Ctx* c, const DL& dl_, const AL& al_, int Nn, int Kk, int M, fl
   const int max_by_rows = cdiv(M, 128);
   if (splits > max_by_rows) splits = max_by_rows;
   const int64_t per = (int64_t)Nn * Kk;
+  { const int erc = ensure_partial(c, (int64_t)splits * per, (int64_t)splits * Nn); if (erc) return erc; }
   if ((int64_t)splits * per > c->partial_elems) splits = (int)(c->partial_elems / per);
   if ((int64_t)splits * Nn > c->bias_partial_elems) splits = (int)(c->bias_partial_elems / Nn);
   if (splits < 1) return fail(c, PPO_ENOMEM, "weight-gradient workspace too small for %s", what);
@@ -409,11 +454,7 @@ int launch_wgrad(Ctx* c, const DL& dl_, const AL& al_, int Nn, int Kk, int M, fl
     else hipLaunchKernelGGL((k_wgrad<3, DL, AL>), grid, dim3(256), 0, c->stream, dl, al, Nn, Kk, M, rows, c->partial, bp);
     LAUNCHCHK(c, what);
   }
-  ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)splits + 1.0) * (double)per);
-  // weight and bias partials in one launch
-  hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 32) + (gb ? cdiv(Nn, 32) : 0)), dim3(256), 0, c->stream, c->partial, splits, per, gw, accumulate ? 1 : 0,
-                     gb ? c->bias_partial : nullptr, (int64_t)(gb ? Nn : 0), gb);
-  LAUNCHCHK(c, what);
+  defer_reduce(c, 0, splits, per, 0, 0, gw, nullptr, accumulate, gb != nullptr, Nn, gb);
   return PPO_OK;
 }
 
@@ -521,6 +562,7 @@ int launch_conv_wgrad_tile_t(Ctx* c, ConvWgradArgs a, float* gw, float* gb, bool
   const int gy = cdiv(a.Cout, 64), K = 9 * CIN;
   int gx = 256 / gy; if (gx > a.ntiles) gx = a.ntiles; if (gx < 1) gx = 1;
   const int64_t per = (int64_t)a.Cout * K;
+  { const int erc = ensure_partial(c, (int64_t)gx * per, gb ? (int64_t)gx * a.Cout : 0); if (erc) return erc; }
   if ((int64_t)gx * per > c->partial_elems) gx = (int)(c->partial_elems / per);
   if (gb && (int64_t)gx * a.Cout > c->bias_partial_elems) gx = (int)(c->bias_partial_elems / a.Cout);
   if (gx < 1) return 1;
@@ -534,10 +576,7 @@ int launch_conv_wgrad_tile_t(Ctx* c, ConvWgradArgs a, float* gw, float* gb, bool
     hipLaunchKernelGGL(kfn, dim3(gx, gy), dim3(S::THREADS), lds, c->stream, a);
     LAUNCHCHK(c, "k_conv_wgrad_tile");
   }
-  ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)gx + 1.0) * (double)per);
-  hipLaunchKernelGGL(k_reduce_partials_t, dim3(cdiv(per, 32) + (gb ? cdiv(a.Cout, 32) : 0)), dim3(256), 0, c->stream, c->partial, gx, a.Cout, K, gw, accumulate ? 1 : 0,
-                     gb ? c->bias_partial : nullptr, (int64_t)(gb ? a.Cout : 0), gb);
-  LAUNCHCHK(c, "k_reduce_partials_t");
+  defer_reduce(c, 1, gx, per, a.Cout, K, gw, nullptr, accumulate, gb != nullptr, a.Cout, gb);
   return PPO_OK;
 }
 int launch_conv_wgrad_tile(Ctx* c, const ImgAddr& dy, const AConvFwd& xl, int Cout, int nimg, float* gw, float* gb, bool accumulate,
@@ -583,6 +622,7 @@ int launch_conv_dgrad_tile_t(Ctx* c, ConvDgradArgs a, int nimg, const std::strin
   int gx = a.ntiles < 256 ? a.ntiles : 256;
   if (C0 > 0) {
     const int64_t npair = (int64_t)CI * (9 * C0 + 1);
+    { const int erc = ensure_partial(c, gx * npair, 0); if (erc) return erc; }
     if (gx * npair > c->partial_elems) gx = (int)(c->partial_elems / npair);
     if (gx < 1) return 1;
     a.partial0 = c->partial;
@@ -627,6 +667,7 @@ int launch_conv_dgrad_wgrad0_reg_t(Ctx* c, ConvDgradArgs a, int nimg, const std:
   a.dv_rb0 = make_fastdiv(rb0); a.dv_mrow = make_fastdiv(a.W * 4);
   int gx = a.ntiles < 256 ? a.ntiles : 256;
   const int64_t npair = (int64_t)S::CI * (9 * C0 + 1);
+  { const int erc = ensure_partial(c, gx * npair, 0); if (erc) return erc; }
   if (gx * npair > c->partial_elems) gx = (int)(c->partial_elems / npair);
   if (gx < 1) return 1;
   a.partial0 = c->partial;
@@ -798,6 +839,7 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc, bool with_head =
       in.prepare(); al.prepare(); ep.map.prepare();
       const int K0 = 9 * c->cC[0], npair = Ci * (K0 + 1), tpp = cdiv(M0, 128);
       int grid = 2 * tpp < 512 ? 2 * tpp : 512;
+      { const int erc = ensure_partial(c, (int64_t)grid * npair, 0); if (erc) return erc; }
       if ((int64_t)grid * npair > c->partial_elems) grid = (int)(c->partial_elems / npair);
       const double fflops = 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co + 2.0 * pix * Ci * (K0 + 1);
       // the ReLU mask is one bit per element when the forward kernel left its sign-bit words, else the stored activation
@@ -826,9 +868,8 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc, bool with_head =
 #undef LAUNCH_FUSED
         LAUNCHCHK(c, "k_dgrad1_wgrad0");
       }
-      hipLaunchKernelGGL(k_conv1_wgrad_reduce, dim3(npair), dim3(256), 0, c->stream, c->partial, grid, Ci, K0, c->g + c->convW[0], c->g + c->convB[0], acc ? 1 : 0);
-      LAUNCHCHK(c, "k_conv1_wgrad_reduce");
-      return PPO_OK;
+      defer_reduce(c, 2, grid, npair, Ci, K0, c->g + c->convW[0], c->g + c->convB[0], acc, false, 0, nullptr);
+      return flush_reduces(c);
     }
     double ab = 2.0 * ((double)nimg * Ho * Wo * Co + pix * Ci + 9.0 * Ci * Co) + (c->abits_ok[l - 1] && Co == 64 ? pix * Ci / 8.0 : 2.0 * pix * Ci);
     const double dflops = 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co;
@@ -846,6 +887,7 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc, bool with_head =
     const int Co = c->cC[1], Ho = c->cH[1], Wo = c->cW[1], K = 9 * c->cC[0];
     int64_t M = (int64_t)nimg * Ho * Wo;
     const int npair = Co * (K + 1);
+    { const int erc = ensure_partial(c, (int64_t)2048 * npair, 0); if (erc) return erc; }
     int64_t max_blocks = c->partial_elems / npair;
     if (max_blocks > 2048) max_blocks = 2048;
     int64_t ppb = (M + max_blocks - 1) / max_blocks;
@@ -857,10 +899,9 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc, bool with_head =
     else
       hipLaunchKernelGGL((k_conv1_wgrad<3>), dim3(nblk), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->gbuf[cur], (int)ppb, c->partial);
     LAUNCHCHK(c, "k_conv1_wgrad");
-    hipLaunchKernelGGL(k_conv1_wgrad_reduce, dim3(npair), dim3(256), 0, c->stream, c->partial, nblk, Co, K, c->g + c->convW[0], c->g + c->convB[0], acc ? 1 : 0);
-    LAUNCHCHK(c, "k_conv1_wgrad_reduce");
+    defer_reduce(c, 2, nblk, npair, Co, K, c->g + c->convW[0], c->g + c->convB[0], acc, false, 0, nullptr);
   }
-  return PPO_OK;
+  return flush_reduces(c);
 }
 
 int gen_permutation(Ctx* c, uint64_t seed, uint64_t update, uint64_t epoch) {
@@ -882,6 +923,7 @@ template <int HID>
 int launch_head_loss_t(Ctx* c, const LossData& L, int n, bool acc, bool distill, float* sp, float* dp) {
   typedef HeadLossShape<HID> S;
   const int nblk = cdiv(n, 64);
+  { const int erc = ensure_partial(c, (int64_t)nblk * c->NH * HID, (int64_t)nblk * c->NH); if (erc) return erc; }
   if ((int64_t)nblk * c->NH * HID > c->partial_elems || (int64_t)nblk * c->NH > c->bias_partial_elems) return 1;
   HeadLossArgs a;
   a.h = c->fcact[c->nfc - 1]; a.w = c->shadow + c->headW; a.wt = c->headT; a.bias = c->p + c->headB; a.dh = c->gbuf[0];
@@ -900,11 +942,7 @@ int launch_head_loss_t(Ctx* c, const LossData& L, int n, bool acc, bool distill,
     }
     LAUNCHCHK(c, "k_head_loss");
   }
-  const int64_t per = (int64_t)c->NH * HID;
-  ProfScope ps2(c, "wgrad_reduce", 0.0, 4.0 * ((double)nblk + 1.0) * (double)per);
-  hipLaunchKernelGGL(k_reduce_partials, dim3(cdiv(per, 32) + cdiv(c->NH, 32)), dim3(256), 0, c->stream, c->partial, nblk, per, c->g + c->headW, acc ? 1 : 0,
-                     c->bias_partial, (int64_t)c->NH, c->g + c->headB);
-  LAUNCHCHK(c, "k_reduce_partials");
+  defer_reduce(c, 0, nblk, (int64_t)c->NH * HID, 0, 0, c->g + c->headW, nullptr, acc, true, c->NH, c->g + c->headB);
   return PPO_OK;
 }
 int launch_head_loss(Ctx* c, const LossData& L, int n, bool acc, bool distill, float* sp, float* dp) {
@@ -1030,27 +1068,47 @@ int create_impl(Ctx* c) {
   for (int l = 0; l < c->nfc; ++l) { DALLOC(c, c->fcact[l], (int64_t)CH * c->fout[l]); if ((int64_t)CH * c->fout[l] > gmax) gmax = (int64_t)CH * c->fout[l]; }
   DALLOC(c, c->headout, (int64_t)CH * HEAD_LD); DALLOC(c, c->dhead, (int64_t)CH * HEAD_LD);
   DALLOC(c, c->gbuf[0], gmax); DALLOC(c, c->gbuf[1], gmax);
-  // weight-gradient partials: room for every layer at its preferred split count
-  int64_t pe = 2048LL * c->cC[1] * (9 * c->cC[0] + 1), bpe = 0;
-  auto want = [&](int Nn, int Kk, int64_t M) {
+  // weight-gradient partials: room for every layer at its preferred split count, all layers of a backward
+  // pass side by side (their sums are taken in one launch at the end of the pass)
+  int64_t pe_sum = 2048LL * c->cC[1] * (9 * c->cC[0] + 1), bpe_sum = 0;
+  auto want = [&](int Nn, int Kk, int64_t M, int64_t& need, int64_t& bneed) {  // k_wgrad
     int ktw = Kk <= 128 ? 1 : (Kk <= 256 ? 2 : 3);
     int tiles = cdiv(Kk, 128 * ktw) * cdiv(Nn, 64);
     int splits = cdiv(768, tiles), mr = cdiv(M, 128);
     if (splits > mr) splits = mr;
     if (splits < 1) splits = 1;
-    if ((int64_t)splits * Nn * Kk > pe) pe = (int64_t)splits * Nn * Kk;
-    if ((int64_t)splits * Nn > bpe) bpe = (int64_t)splits * Nn;
+    need = (int64_t)splits * Nn * Kk; bneed = (int64_t)splits * Nn;
   };
-  for (int l = 1; l < c->nconv; ++l) want(c->cC[l + 1], 9 * c->cC[l], (int64_t)CH * V * c->cH[l + 1] * c->cW[l + 1]);
-  for (int l = 1; l < c->nconv; ++l) {  // one partial per block of the LDS-image weight-gradient kernel
+  for (int l = 1; l < c->nconv; ++l) {
+    int64_t need, bneed;
+    want(c->cC[l + 1], 9 * c->cC[l], (int64_t)CH * V * c->cH[l + 1] * c->cW[l + 1], need, bneed);
+    // or one partial per block of the LDS-image weight-gradient kernel
     const int64_t gy = cdiv(c->cC[l + 1], 64), gx = 256 / gy > 0 ? 256 / gy : 1, per = (int64_t)c->cC[l + 1] * 9 * c->cC[l];
-    if (gx * per > pe) pe = gx * per;
-    if (gx * c->cC[l + 1] > bpe) bpe = gx * c->cC[l + 1];
+    if (gx * per > need) need = gx * per;
+    if (gx * c->cC[l + 1] > bneed) bneed = gx * c->cC[l + 1];
+    pe_sum += need; bpe_sum += bneed;
   }
-  for (int l = 0; l < c->nfc; ++l) want(c->fout[l], c->fin[l], CH);
-  want(c->NH, c->hid, CH);
-  c->partial_elems = pe; c->bias_partial_elems = bpe;
-  DALLOC(c, c->partial, pe); DALLOC(c, c->bias_partial, bpe);
+  for (int l = 0; l < c->nfc; ++l) {
+    int64_t need, bneed;
+    want(c->fout[l], c->fin[l], CH, need, bneed);
+    const int64_t per = (int64_t)c->fout[l] * c->fin[l];  // k_wgrad_rs: up to four splits are worth their partials
+    if (4 * per > need) need = 4 * per;
+    if (4 * (int64_t)c->fout[l] > bneed) bneed = 4 * (int64_t)c->fout[l];
+    pe_sum += need; bpe_sum += bneed;
+  }
+  {
+    int64_t need, bneed;
+    want(c->NH, c->hid, CH, need, bneed);
+    const int64_t nblk = cdiv(CH, 64);  // fused output-layer kernel: one partial per 64 samples
+    if (nblk * c->NH * c->hid > need) need = nblk * c->NH * c->hid;
+    if (nblk * c->NH > bneed) bneed = nblk * c->NH;
+    pe_sum += need; bpe_sum += bneed;
+  }
+  c->partial_cap = pe_sum; c->bias_partial_cap = bpe_sum > 0 ? bpe_sum : 1;
+  DALLOC(c, c->partial_base, c->partial_cap); DALLOC(c, c->bias_partial_base, c->bias_partial_cap);
+  c->partial = c->partial_base; c->partial_elems = c->partial_cap;
+  c->bias_partial = c->bias_partial_base; c->bias_partial_elems = c->bias_partial_cap;
+  c->rjobs.njobs = 0; c->rjob_blocks = 0;
   DALLOC(c, c->zpage, 512);
   HIPCHK(c, hipMemsetAsync(c->zpage, 0, 1024, c->stream));
   // loss / Adam partials
