@@ -4,12 +4,37 @@
 #pragma once
 #include "common.hip.h"
 
+// The per-step scalars of a rollout slab: proprio (-> bf16), action, log-prob, value, reward, done.
+struct ScalarWrite {
+  int N, P, A;
+  const float *proprio, *action, *logp, *value, *reward;
+  const uint8_t* done;
+  bf16_t* o_proprio;
+  float *o_action, *o_logp, *o_value, *o_reward;
+  uint8_t* o_done;
+};
+__device__ __forceinline__ void write_scalars(int64_t i, const ScalarWrite& w) {
+  if (i < (int64_t)w.N * w.P) w.o_proprio[i] = f2bf(w.proprio[i]);
+  if (i < (int64_t)w.N * w.A) w.o_action[i] = w.action[i];
+  if (i < w.N) {
+    if (w.logp) w.o_logp[i] = w.logp[i];
+    if (w.value) w.o_value[i] = w.value[i];
+    if (w.reward) w.o_reward[i] = w.reward[i];
+    if (w.done) w.o_done[i] = w.done[i];
+  }
+}
+
 // ---------------------------------------------------------------- buffer append
 // One step's images [N][V][C][HW] (fp32 or bf16) -> bf16 channel-last [N][V][HW][C] at the
-// step's slab.  Each thread converts 8 consecutive pixels of one (n, v) image.
+// step's slab.  Each thread converts 8 consecutive pixels of one (n, v) image; the blocks behind
+// the last image block write the slab's scalars (one launch per rollout step).
 template <typename InT>
-__global__ void k_write_obs(const InT* __restrict__ src, bf16_t* __restrict__ dst, int64_t n_img, int C, int HW) {
+__global__ void k_write_obs(const InT* __restrict__ src, bf16_t* __restrict__ dst, int64_t n_img, int C, int HW, int obs_blocks, ScalarWrite sw) {
   const int groups = (HW + 7) / 8;
+  if ((int)blockIdx.x >= obs_blocks) {  // the blocks behind the images write the slab's scalars
+    write_scalars((int64_t)((int)blockIdx.x - obs_blocks) * blockDim.x + threadIdx.x, sw);
+    return;
+  }
   int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= n_img * groups) return;
   int64_t img = gid / groups;
@@ -72,22 +97,6 @@ __global__ void k_read_obs(const bf16_t* __restrict__ src, bf16_t* __restrict__ 
   dst[i] = src[img * per + (int64_t)p * C + c];
 }
 
-// Per-step scalars: proprio -> bf16, action/logp/value/reward fp32, done u8.
-__global__ void k_write_scalars(int N, int P, int A, const float* __restrict__ proprio, const float* __restrict__ action,
-                                const float* __restrict__ logp, const float* __restrict__ value,
-                                const float* __restrict__ reward, const uint8_t* __restrict__ done,
-                                bf16_t* __restrict__ o_proprio, float* __restrict__ o_action, float* __restrict__ o_logp,
-                                float* __restrict__ o_value, float* __restrict__ o_reward, uint8_t* __restrict__ o_done) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < (int64_t)N * P) o_proprio[i] = f2bf(proprio[i]);
-  if (i < (int64_t)N * A) o_action[i] = action[i];
-  if (i < N) {
-    if (logp) o_logp[i] = logp[i];
-    if (value) o_value[i] = value[i];
-    if (reward) o_reward[i] = reward[i];
-    if (done) o_done[i] = done[i];
-  }
-}
 
 // ---------------------------------------------------------------- GAE
 // One thread per environment, reverse scan over time held in registers; at every t the

@@ -1244,16 +1244,19 @@ int ppo_buffer_write(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_pr
   const int64_t nimg = (int64_t)N * V, groups = (HW + 7) / 8;
   bf16_t* dst = c->obs + (int64_t)t * N * V * c->img_elems;
   ProfScope ps(c, "buffer_write", 0.0, (double)nimg * c->img_elems * (c->d.obs_dtype == 0 ? 6.0 : 4.0) + (double)N * (6.0 * c->P + 8.0 * c->A + 26.0));
-  if (c->d.obs_dtype == 0)
-    hipLaunchKernelGGL((k_write_obs<float>), dim3(cdiv(nimg * groups, 256)), dim3(256), 0, c->stream, (const float*)d_obs, dst, nimg, C, HW);
-  else
-    hipLaunchKernelGGL((k_write_obs<bf16_t>), dim3(cdiv(nimg * groups, 256)), dim3(256), 0, c->stream, (const bf16_t*)d_obs, dst, nimg, C, HW);
-  LAUNCHCHK(c, "k_write_obs");
   const int64_t off = (int64_t)t * N;
   const int mx = c->P > c->A ? c->P : c->A;
-  hipLaunchKernelGGL(k_write_scalars, dim3(cdiv((int64_t)N * mx, 256)), dim3(256), 0, c->stream, N, c->P, c->A, d_proprio, d_action, d_logp, d_value,
-                     d_reward, d_done, c->proprio + off * c->P, c->action + off * c->A, c->logp + off, c->value + off, c->reward + off, c->done + off);
-  LAUNCHCHK(c, "k_write_scalars");
+  ScalarWrite sw;
+  sw.N = N; sw.P = c->P; sw.A = c->A; sw.proprio = d_proprio; sw.action = d_action; sw.logp = d_logp; sw.value = d_value; sw.reward = d_reward; sw.done = d_done;
+  sw.o_proprio = c->proprio + off * c->P; sw.o_action = c->action + off * c->A; sw.o_logp = c->logp + off; sw.o_value = c->value + off;
+  sw.o_reward = c->reward + off; sw.o_done = c->done + off;
+  // images and scalars of the slab in one launch
+  const int obs_blocks = cdiv(nimg * groups, 256), sc_blocks = cdiv((int64_t)N * mx, 256);
+  if (c->d.obs_dtype == 0)
+    hipLaunchKernelGGL((k_write_obs<float>), dim3(obs_blocks + sc_blocks), dim3(256), 0, c->stream, (const float*)d_obs, dst, nimg, C, HW, obs_blocks, sw);
+  else
+    hipLaunchKernelGGL((k_write_obs<bf16_t>), dim3(obs_blocks + sc_blocks), dim3(256), 0, c->stream, (const bf16_t*)d_obs, dst, nimg, C, HW, obs_blocks, sw);
+  LAUNCHCHK(c, "k_write_obs");
   if (t == 0) { c->written.assign((size_t)c->T, 0); }
   c->written[(size_t)t] = 1;
   c->gae_done = false;
