@@ -651,25 +651,11 @@ __global__ void k_cast_bf16(const float* __restrict__ src, bf16_t* __restrict__ 
 }
 
 // ---------------------------------------------------------------- weight re-packing for the backward GEMMs
-// dst[c][r] = src[r][c] for r < rows, zero for rows <= r < ld_dst.
-__global__ void k_transpose_bf16(const bf16_t* __restrict__ src, int rows, int cols, bf16_t* __restrict__ dst, int ld_dst) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)cols * ld_dst) return;
-  int c = (int)(i / ld_dst), r = (int)(i - (int64_t)c * ld_dst);
-  dst[i] = r < rows ? src[(int64_t)r * cols + c] : (bf16_t)0;
-}
-// Transposed-convolution weights of row parity py for pixel-pair rows:
-// Per-tap transpose for the quad-organised transposed convolution: dst[(tap*Cin + ci)*Cout + co] = W[co][tap*Cin + ci].
-__global__ void k_pack_dgrad_taps(const bf16_t* __restrict__ w, int Cout, int Cin, bf16_t* __restrict__ dst) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)9 * Cin * Cout) return;
-  const int tap = (int)(i / ((int64_t)Cin * Cout)), rem = (int)(i - (int64_t)tap * Cin * Cout), ci = rem / Cout, co = rem - ci * Cout;
-  dst[i] = w[(int64_t)co * 9 * Cin + tap * Cin + ci];
-}
-
-// All per-update re-packs in one launch: job j covers blocks [first[j], first[j+1]); kind 0 is
-// k_transpose_bf16's mapping (a = rows, b = cols, ld = leading dimension of dst), kind 1
-// k_pack_dgrad_taps's (a = Cout, b = Cin).
+// All per-update re-packs in one launch: job j covers blocks [first[j], first[j+1]).
+// kind 0, transpose with zero padding (a = rows, b = cols, ld = leading dimension of dst):
+//   dst[c][r] = src[r][c] for r < rows, zero for rows <= r < ld;
+// kind 1, per-tap transpose for the quad-organised transposed convolution (a = Cout, b = Cin):
+//   dst[(tap*Cin + ci)*Cout + co] = W[co][tap*Cin + ci].
 struct RepackJobs {
   static constexpr int MAXJ = 12;
   int njobs;
