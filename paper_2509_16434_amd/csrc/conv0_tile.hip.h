@@ -63,7 +63,6 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
     };
     if (nq > 0) issue(0);
     if (nq > 1) issue(1);
-    __builtin_amdgcn_s_barrier();
     for (int q = 0; q < nq; ++q) {
       vm_wait_dyn(q + 1 < nq ? ni : 0);  // band q has landed
       __builtin_amdgcn_s_barrier();
@@ -98,7 +97,6 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
   const int npix = TR * Wo, ngroups = (npix + 31) >> 5;
   const int cpr = Cout >> 3;  // 16-byte chunks per pixel
 
-  __builtin_amdgcn_s_barrier();
   for (int q = 0; q < nq; ++q) {
     const int t = blockIdx.x + q * gridDim.x;
     const int img = t / a.NB, band = t - img * a.NB;

@@ -157,7 +157,6 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     };
     if (nq > 0) issue(0);
     if (nq > 1) issue(1);
-    __builtin_amdgcn_s_barrier();
     for (int q = 0; q < nq; ++q) {
       vm_wait_dyn(q + 1 < nq ? ni : 0);  // band q has landed
       __builtin_amdgcn_s_barrier();      // A(q)
@@ -332,7 +331,6 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       if (nq > 0) load_mask(0, set0());
       if (nq > 1) load_mask(1, set1());
     }
-    __builtin_amdgcn_s_barrier();
     for (int q = 0; q < nq; q += 2) {
       step(q, set0());
       if (q + 1 < nq) step(q + 1, set1());
@@ -372,7 +370,6 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     for (int cc = 0; cc < CC; ++cc)
       wr[s][cc] = *reinterpret_cast<const bf16x8_t*>(a.wt + ((int64_t)s * CI + wn * 32 + l32) * CO + cc * 16 + h * 8);
 
-  __builtin_amdgcn_s_barrier();
   for (int q = 0; q < nq; ++q) {
     const int t = blockIdx.x + q * gridDim.x;
     const int band = t % a.NB;

@@ -155,7 +155,6 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
           if (mgo[k] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + OFF_MSK + (lw + S::NLW * k) * 1024), 16, 0, 0);
         }
     };
-    __builtin_amdgcn_s_barrier();
     // bands 0 and 1 are issued before the first wait: the loop starts two bands early
     for (int q = -2; q < nq; ++q) {
       if (q >= 0) {
@@ -298,9 +297,8 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     }
   };
 
-  __builtin_amdgcn_s_barrier();
   for (int q = 0; q < nq; ++q) {
-    __builtin_amdgcn_s_barrier();  // A(q): band q is in LDS
+    __builtin_amdgcn_s_barrier();  // A(q): band q is in LDS (the first one also orders the zero pads)
     const char* slot = lds + (q % NBUF) * SLOT;
     // the first product of M-tile m + 1 is independent of the second product of M-tile m
     f32x4_t acc[2][4];

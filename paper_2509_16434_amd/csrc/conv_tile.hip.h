@@ -120,7 +120,6 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
     };
     if (nq > 0) issue(0);
     if (nq > 1) issue(1);
-    __builtin_amdgcn_s_barrier();  // pad fill done (matches the compute waves' first barrier)
     for (int q = 0; q < nq; ++q) {
       vm_wait_dyn(q + 1 < nq ? ni : 0);  // band q has landed; band q+1 may still be in flight
       __builtin_amdgcn_s_barrier();
@@ -157,7 +156,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
 #pragma unroll
   for (int v = 0; v < 3; ++v) hx[v] = (uint32_t)(h * 16) ^ tile_swz_bits<CIN>((uint32_t)((2 * ox + v) * PIX));
 
-  __builtin_amdgcn_s_barrier();  // pad fill and bias table done
+  // the first tile's barrier also orders the pad fill and the bias table before their first use
   for (int q = 0; q < nq; ++q) {
     const int t = blockIdx.x + q * gridDim.x;
     __builtin_amdgcn_s_barrier();  // band q is in LDS
@@ -327,7 +326,6 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
     };
     if (nq > 0) issue(0);
     if (nq > 1) issue(1);
-    __builtin_amdgcn_s_barrier();
     for (int q = 0; q < nq; ++q) {
       vm_wait_dyn(q + 1 < nq ? ni : 0);
       __builtin_amdgcn_s_barrier();
@@ -373,9 +371,8 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
     tapc[t] = (uint32_t)((u * WP + v) * PIX); tapv2[t] = v == 2; taphi[t] = (CIN == 64) && (kt & 1);
   }
 
-  __builtin_amdgcn_s_barrier();  // pad fill done
   for (int q = 0; q < nq; ++q) {
-    __builtin_amdgcn_s_barrier();  // band q is in LDS
+    __builtin_amdgcn_s_barrier();  // band q is in LDS (the first one also orders the pad fill)
     const char* buf = lds + (q % NBUF) * buf_bytes;
 #pragma unroll
     for (int s = 0; s < MAXSTEP; ++s) {
