@@ -23,7 +23,9 @@
  * against fp64 automatic differentiation and central finite differences;
  * loss closed forms at ratio=1; Adam against closed forms and a library
  * optimiser; permutation bijection / brute force / published SplitMix64
- * vectors.  The composed multi-minibatch update (orc_ppo_update,
+ * vectors; the policy step against a library normal density, the closed
+ * form at zero noise and the ratio-1 property of the loss on its own
+ * output.  The composed multi-minibatch update (orc_ppo_update,
  * orc_distill_update) is pinned only transitively through those parts:
  * parity unpinned by the paper for the composed loop.
  *
@@ -409,6 +411,40 @@ void orc_forward(const orc_net *n, const double *params_in, int64_t B, const flo
     acts_free(n, &a);
   }
   free(params);
+}
+
+/* ------------------------------------------------------------------ */
+/* Policy step of the collection loop (Algorithm 2: the policy maps the */
+/* stacked observations to actions, and the record is appended after    */
+/* the simulators have stepped).  Diagonal Gaussian policy:             */
+/*   a_j   = mu_j + exp(logsigma_j) * xi_j,   xi given by the caller    */
+/*   logp  = sum_j [-((a_j-mu_j)/sigma_j)^2/2 - logsigma_j - ln(2pi)/2] */
+/*   value = V(obs)                                                     */
+/* logp is evaluated at the action, the way the loss evaluates it       */
+/* later, so that the first pass over fresh data sees ratio 1.          */
+/* Outputs: action [B][A], logp [B], value [B].                         */
+/* ------------------------------------------------------------------ */
+void orc_act(const orc_net *n, const double *params, int64_t B, const float *obs,
+             const double *proprio, const double *noise, double *action, double *logp,
+             double *value) {
+  const double LN2PI = 1.8378770664093454835606594728112;
+  geom g; make_geom(n, &g);
+  const int A = n->act_dim;
+  const double *logstd = params + g.logstd;
+  double *mu = (double *)malloc(sizeof(double) * (size_t)B * A);
+  orc_forward(n, params, B, obs, proprio, mu, value);
+  for (int64_t s = 0; s < B; ++s) {
+    double lp = 0;
+    for (int j = 0; j < A; ++j) {
+      double sg = exp(logstd[j]);
+      double a = mu[s * A + j] + sg * noise[s * A + j];
+      double z = (a - mu[s * A + j]) / sg;
+      action[s * A + j] = a;
+      lp += -0.5 * z * z - logstd[j] - 0.5 * LN2PI;
+    }
+    logp[s] = lp;
+  }
+  free(mu);
 }
 
 /* ------------------------------------------------------------------ */

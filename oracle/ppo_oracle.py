@@ -162,6 +162,20 @@ def forward(net, params, obs, proprio):
     return mu, v
 
 
+def act(net, params, obs, proprio, noise):
+    """Policy step -> action [B][A], logp [B], value [B] (actor-critic nets only)."""
+    assert net.get("has_value_head", 1)
+    n = _net(net)
+    proprio, noise = _d(proprio), _d(noise)
+    B = proprio.shape[0]
+    obs, params = _obs(net, obs, B), _d(params)
+    assert params.size == param_count(net) and noise.shape == (B, net["act_dim"])
+    action, logp, value = np.empty((B, net["act_dim"])), np.empty(B), np.empty(B)
+    lib().orc_act(C.byref(n), _p(params), C.c_int64(B), _p(obs, C.c_float), _p(proprio), _p(noise), _p(action),
+                  _p(logp), _p(value))
+    return action, logp, value
+
+
 def _stats(a):
     return dict(zip(ST_NAMES, (float(x) for x in a)))
 

@@ -252,6 +252,46 @@ def test_value_clipping_limits():
     assert tight["v_loss"] >= base["v_loss"]
 
 
+# ----------------------------------------------------------------- policy step
+def _act_setup(seed, B=6):
+    p = _params(TINY, seed)
+    sl = synth.param_slices(TINY)["logstd"]
+    p[sl[0]:sl[1]] = np.array([math.log(2.0), -0.7])
+    b = _batch(TINY, B, seed + 1)
+    noise = np.random.default_rng(seed + 2).standard_normal((B, TINY["act_dim"]))
+    return p, b, noise, np.exp(p[sl[0]:sl[1]])
+
+
+def test_act_zero_noise_is_the_mean_with_closed_form_logp():
+    p, b, _, sigma = _act_setup(40)
+    mu, v = orc.forward(TINY, p, b["obs"], b["proprio"])
+    a, logp, val = orc.act(TINY, p, b["obs"], b["proprio"], np.zeros_like(mu))
+    np.testing.assert_array_equal(a, mu)
+    np.testing.assert_array_equal(val, v)
+    want = -np.log(sigma).sum() - 0.5 * TINY["act_dim"] * math.log(2 * math.pi)
+    np.testing.assert_allclose(logp, np.full(len(logp), want), rtol=0, atol=1e-13)
+
+
+def test_act_offset_is_sigma_times_noise_and_logp_is_library_density():
+    from scipy.stats import norm
+    p, b, noise, sigma = _act_setup(41)
+    mu, _ = orc.forward(TINY, p, b["obs"], b["proprio"])
+    a, logp, _ = orc.act(TINY, p, b["obs"], b["proprio"], noise)
+    # sigma_0 = 2 exactly: the offset of the first action component is twice its noise, sign included
+    np.testing.assert_allclose(a[:, 0] - mu[:, 0], 2.0 * noise[:, 0], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(a[:, 1] - mu[:, 1], sigma[1] * noise[:, 1], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(logp, norm.logpdf(a, loc=mu, scale=sigma).sum(1), rtol=0, atol=1e-12)
+
+
+def test_act_output_gives_ratio_one_in_the_loss():
+    p, b, noise, _ = _act_setup(42, B=9)
+    a, logp, val = orc.act(TINY, p, b["obs"], b["proprio"], noise)
+    st, _ = orc.ppo_loss_grad(TINY, p, b["obs"], b["proprio"], a, logp, val, b["adv"], b["ret"])
+    assert abs(st["approx_kl"]) < 1e-13 and st["clip_frac"] == 0.0
+    assert abs(st["pi_loss"] + b["adv"].mean()) < 1e-13
+    assert abs(st["v_loss"] - ((val - b["ret"]) ** 2).mean()) < 1e-13
+
+
 def test_mse_closed_forms():
     rng = np.random.default_rng(7)
     a = rng.standard_normal((6, 23))
