@@ -117,6 +117,23 @@ int ppo_get_opt_state(ppo_ctx* ctx, float* h_m, float* h_v, int64_t n, int64_t* 
 int ppo_buffer_write(ppo_ctx* ctx, int32_t t, const void* d_obs, const float* d_proprio, const float* d_action,
                      const float* d_logp, const float* d_value, const float* d_reward, const uint8_t* d_done);
 
+/* Policy step of the collection loop (Algorithm 2: the policy maps the stacked observations of all
+ * environments to actions; the record is appended once the simulators have stepped).  Stores the
+ * step-t observations like ppo_buffer_write, runs the network forward on them with the current
+ * parameters and samples the diagonal-Gaussian policy,
+ *   a = mu + exp(logstd) * xi,   logp = sum_j [-((a_j-mu_j)/sigma_j)^2/2 - logstd_j - ln(2 pi)/2],
+ * with the standard-normal draws xi supplied by the caller (d_noise [N][A] fp32, device).  Action,
+ * log-prob and value go into the step-t slab and, where the pointers are not NULL, to the DEVICE
+ * arrays d_action [N][A], d_logp [N], d_value [N] (fp32).  The step counts as written only after
+ * ppo_buffer_write_outcome(t).  Actor-critic contexts only (else PPO_ESTATE); t = 0 starts a new rollout. */
+int ppo_act(ppo_ctx* ctx, int32_t t, const void* d_obs, const float* d_proprio, const float* d_noise, float* d_action,
+            float* d_logp, float* d_value);
+/* Reward and termination flag of step t (device, [N] fp32 / uint8), known only after the
+ * simulators have stepped (Algorithm 2: obs, rew, done <- step(actions)); completes a record
+ * begun by ppo_act, or replaces these two fields of a record written by ppo_buffer_write.
+ * PPO_ESTATE when step t holds no record. */
+int ppo_buffer_write_outcome(ppo_ctx* ctx, int32_t t, const float* d_reward, const uint8_t* d_done);
+
 /* Read back the step-t images as stored (bf16) into a DEVICE array in the caller's layout
  * [N][n_views][in_c][in_h][in_w] (bf16).  Test hook for the write path. */
 int ppo_buffer_read_obs(ppo_ctx* ctx, int32_t t, void* d_obs_bf16);

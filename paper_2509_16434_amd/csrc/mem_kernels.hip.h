@@ -15,7 +15,7 @@ struct ScalarWrite {
 };
 __device__ __forceinline__ void write_scalars(int64_t i, const ScalarWrite& w) {
   if (i < (int64_t)w.N * w.P) w.o_proprio[i] = f2bf(w.proprio[i]);
-  if (i < (int64_t)w.N * w.A) w.o_action[i] = w.action[i];
+  if (w.action && i < (int64_t)w.N * w.A) w.o_action[i] = w.action[i];
   if (i < w.N) {
     if (w.logp) w.o_logp[i] = w.logp[i];
     if (w.value) w.o_value[i] = w.value[i];
@@ -398,6 +398,41 @@ __global__ void k_gather_proprio(const bf16_t* __restrict__ proprio, const int32
 #define LOSS_NSTAT 8  // pi, v, kl, clipfrac sums; slots 4..7 unused
 #define HEAD_LD 32    // row stride of the head output / head gradient matrices
 #define LOSS_BLOCK 64  // samples (threads) per block of the loss kernels: one wave, so that a minibatch spreads over many CUs
+
+// Reward and termination flag of one step, which arrive after the simulators have stepped.
+__global__ void k_write_outcome(int N, const float* __restrict__ reward, const uint8_t* __restrict__ done, float* __restrict__ o_reward,
+                                uint8_t* __restrict__ o_done) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < N) { o_reward[i] = reward[i]; o_done[i] = done[i]; }
+}
+
+// ---------------------------------------------------------------- policy step
+// Sampling of the collection loop's action (Algorithm 2: actions from the stacked observations)
+// from the head outputs of n samples (row: A means, then the value):
+//   a_j = mu_j + exp(logstd_j) * xi_j,  logp = sum_j [-z_j^2/2 - logstd_j - ln(2 pi)/2],  z = (a - mu)/sigma
+// z is formed from the rounded action, with the arithmetic of the loss kernels, so that the loss
+// sees ratio 1 on fresh data.  One thread per sample; results go to the rollout slab (o_*) and,
+// where given, to the caller's arrays (c_*).
+__global__ void k_act_sample(int n, int A, const float* __restrict__ headout, const float* __restrict__ logstd, const float* __restrict__ noise,
+                             float* __restrict__ o_action, float* __restrict__ o_logp, float* __restrict__ o_value,
+                             float* __restrict__ c_action, float* __restrict__ c_logp, float* __restrict__ c_value) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= n) return;
+  const float* o = headout + (int64_t)s * HEAD_LD;
+  float logp = 0.f;
+  for (int j = 0; j < A; ++j) {
+    const float ls = logstd[j], sg = expf(ls), sig_inv = __expf(-ls), mu = o[j];
+    const float a = mu + sg * noise[(int64_t)s * A + j];
+    const float zz = (a - mu) * sig_inv;
+    logp += -0.5f * zz * zz - ls - 0.91893853320467274178f;
+    o_action[(int64_t)s * A + j] = a;
+    if (c_action) c_action[(int64_t)s * A + j] = a;
+  }
+  const float v = o[A];
+  o_logp[s] = logp; o_value[s] = v;
+  if (c_logp) c_logp[s] = logp;
+  if (c_value) c_value[s] = v;
+}
 
 // Per-sample inputs of the losses (rollout arrays indexed by the gathered sample number).
 struct LossData {

@@ -1233,6 +1233,9 @@ int ppo_get_opt_state(ppo_ctx* c, float* hm, float* hv, int64_t n, int64_t* step
   return PPO_OK;
 }
 
+static int write_slab(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, const float* d_action, const float* d_logp,
+                      const float* d_value, const float* d_reward, const uint8_t* d_done);
+
 int ppo_buffer_write(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, const float* d_action, const float* d_logp,
                      const float* d_value, const float* d_reward, const uint8_t* d_done) {
   if (!c) return PPO_EINVAL;
@@ -1240,23 +1243,8 @@ int ppo_buffer_write(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_pr
   if (!d_obs || !d_proprio || !d_action) return fail(c, PPO_EINVAL, "d_obs, d_proprio and d_action must not be NULL");
   if (c->d.has_value_head && (!d_logp || !d_value || !d_reward || !d_done))
     return fail(c, PPO_EINVAL, "an actor-critic buffer needs d_logp, d_value, d_reward and d_done");
-  const int N = c->N, V = c->V, HW = c->d.in_h * c->d.in_w, C = c->d.in_c;
-  const int64_t nimg = (int64_t)N * V, groups = (HW + 7) / 8;
-  bf16_t* dst = c->obs + (int64_t)t * N * V * c->img_elems;
-  ProfScope ps(c, "buffer_write", 0.0, (double)nimg * c->img_elems * (c->d.obs_dtype == 0 ? 6.0 : 4.0) + (double)N * (6.0 * c->P + 8.0 * c->A + 26.0));
-  const int64_t off = (int64_t)t * N;
-  const int mx = c->P > c->A ? c->P : c->A;
-  ScalarWrite sw;
-  sw.N = N; sw.P = c->P; sw.A = c->A; sw.proprio = d_proprio; sw.action = d_action; sw.logp = d_logp; sw.value = d_value; sw.reward = d_reward; sw.done = d_done;
-  sw.o_proprio = c->proprio + off * c->P; sw.o_action = c->action + off * c->A; sw.o_logp = c->logp + off; sw.o_value = c->value + off;
-  sw.o_reward = c->reward + off; sw.o_done = c->done + off;
-  // images and scalars of the slab in one launch
-  const int obs_blocks = cdiv(nimg * groups, 256), sc_blocks = cdiv((int64_t)N * mx, 256);
-  if (c->d.obs_dtype == 0)
-    hipLaunchKernelGGL((k_write_obs<float>), dim3(obs_blocks + sc_blocks), dim3(256), 0, c->stream, (const float*)d_obs, dst, nimg, C, HW, obs_blocks, sw);
-  else
-    hipLaunchKernelGGL((k_write_obs<bf16_t>), dim3(obs_blocks + sc_blocks), dim3(256), 0, c->stream, (const bf16_t*)d_obs, dst, nimg, C, HW, obs_blocks, sw);
-  LAUNCHCHK(c, "k_write_obs");
+  const int rc = write_slab(c, t, d_obs, d_proprio, d_action, d_logp, d_value, d_reward, d_done);
+  if (rc) return rc;
   if (t == 0) { c->written.assign((size_t)c->T, 0); }
   c->written[(size_t)t] = 1;
   c->gae_done = false;
@@ -1276,8 +1264,30 @@ int ppo_buffer_read_obs(ppo_ctx* c, int32_t t, void* d_obs_bf16) {
 }
 
 static int all_written(ppo_ctx* c) {
-  for (char w : c->written) if (!w) return 0;
+  for (char w : c->written) if (w != 1) return 0;  // 2: acted, outcome still missing
   return 1;
+}
+
+// Images, proprioception and (where given) the other fields of step t into the slab: one launch.
+static int write_slab(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, const float* d_action, const float* d_logp,
+                      const float* d_value, const float* d_reward, const uint8_t* d_done) {
+  const int N = c->N, V = c->V, HW = c->d.in_h * c->d.in_w, C = c->d.in_c;
+  const int64_t nimg = (int64_t)N * V, groups = (HW + 7) / 8;
+  bf16_t* dst = c->obs + (int64_t)t * N * V * c->img_elems;
+  ProfScope ps(c, "buffer_write", 0.0, (double)nimg * c->img_elems * (c->d.obs_dtype == 0 ? 6.0 : 4.0) + (double)N * (6.0 * c->P + 8.0 * c->A + 26.0));
+  const int64_t off = (int64_t)t * N;
+  const int mx = c->P > c->A ? c->P : c->A;
+  ScalarWrite sw;
+  sw.N = N; sw.P = c->P; sw.A = c->A; sw.proprio = d_proprio; sw.action = d_action; sw.logp = d_logp; sw.value = d_value; sw.reward = d_reward; sw.done = d_done;
+  sw.o_proprio = c->proprio + off * c->P; sw.o_action = c->action + off * c->A; sw.o_logp = c->logp + off; sw.o_value = c->value + off;
+  sw.o_reward = c->reward + off; sw.o_done = c->done + off;
+  const int obs_blocks = cdiv(nimg * groups, 256), sc_blocks = cdiv((int64_t)N * mx, 256);
+  if (c->d.obs_dtype == 0)
+    hipLaunchKernelGGL((k_write_obs<float>), dim3(obs_blocks + sc_blocks), dim3(256), 0, c->stream, (const float*)d_obs, dst, nimg, C, HW, obs_blocks, sw);
+  else
+    hipLaunchKernelGGL((k_write_obs<bf16_t>), dim3(obs_blocks + sc_blocks), dim3(256), 0, c->stream, (const bf16_t*)d_obs, dst, nimg, C, HW, obs_blocks, sw);
+  LAUNCHCHK(c, "k_write_obs");
+  return PPO_OK;
 }
 
 int ppo_gae(ppo_ctx* c, const float* d_last_value, float gamma, float lambda) {
@@ -1358,6 +1368,47 @@ int ppo_forward(ppo_ctx* c, const int32_t* d_idx, int64_t count, float* d_mu, fl
                        d_mu + c0 * c->A, d_v ? d_v + c0 : nullptr);
     LAUNCHCHK(c, "k_copy_heads");
   }
+  return PPO_OK;
+}
+
+int ppo_act(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, const float* d_noise, float* d_action, float* d_logp,
+            float* d_value) {
+  if (!c) return PPO_EINVAL;
+  if (!c->d.has_value_head) return fail(c, PPO_ESTATE, "ppo_act needs an actor-critic context (has_value_head = 1)");
+  if (t < 0 || t >= c->T) return fail(c, PPO_EINVAL, "t = %d outside [0, %d)", t, c->T);
+  if (!d_obs || !d_proprio || !d_noise) return fail(c, PPO_EINVAL, "d_obs, d_proprio and d_noise must not be NULL");
+  int rc = write_slab(c, t, d_obs, d_proprio, nullptr, nullptr, nullptr, nullptr, nullptr);
+  if (rc) return rc;
+  if (t == 0) { c->written.assign((size_t)c->T, 0); }
+  c->written[(size_t)t] = 2;
+  c->gae_done = false;
+  const int64_t first = (int64_t)t * c->N;
+  for (int64_t c0 = 0; c0 < c->N; c0 += c->CH) {
+    const int n = (int)((c->N - c0 < c->CH) ? c->N - c0 : c->CH);
+    hipLaunchKernelGGL(k_iota_i32, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->ptmp, n, (int32_t)(first + c0));
+    LAUNCHCHK(c, "k_iota_i32");
+    rc = forward_chunk(c, c->ptmp, n);
+    if (rc) return rc;
+    ProfScope ps(c, "act_sample", 0.0, (double)n * (4.0 * HEAD_LD + 12.0 * c->A + 8.0));
+    const int64_t s0 = first + c0;
+    hipLaunchKernelGGL(k_act_sample, dim3(cdiv(n, 64)), dim3(64), 0, c->stream, n, c->A, c->headout, c->p + c->logstd, d_noise + c0 * c->A,
+                       c->action + s0 * c->A, c->logp + s0, c->value + s0, d_action ? d_action + c0 * c->A : nullptr,
+                       d_logp ? d_logp + c0 : nullptr, d_value ? d_value + c0 : nullptr);
+    LAUNCHCHK(c, "k_act_sample");
+  }
+  return PPO_OK;
+}
+
+int ppo_buffer_write_outcome(ppo_ctx* c, int32_t t, const float* d_reward, const uint8_t* d_done) {
+  if (!c) return PPO_EINVAL;
+  if (t < 0 || t >= c->T) return fail(c, PPO_EINVAL, "t = %d outside [0, %d)", t, c->T);
+  if (!d_reward || !d_done) return fail(c, PPO_EINVAL, "d_reward and d_done must not be NULL");
+  if (!c->written[(size_t)t]) return fail(c, PPO_ESTATE, "step %d holds no record yet (ppo_act or ppo_buffer_write first)", t);
+  hipLaunchKernelGGL(k_write_outcome, dim3(cdiv(c->N, 256)), dim3(256), 0, c->stream, c->N, d_reward, d_done, c->reward + (int64_t)t * c->N,
+                     c->done + (int64_t)t * c->N);
+  LAUNCHCHK(c, "k_write_outcome");
+  c->written[(size_t)t] = 1;
+  c->gae_done = false;
   return PPO_OK;
 }
 

@@ -68,6 +68,8 @@ def load_library():
         "ppo_set_opt_state": (C.c_int, [vp, fp, fp, i64, i64, i64]),
         "ppo_get_opt_state": (C.c_int, [vp, fp, fp, i64, C.POINTER(i64), C.POINTER(i64)]),
         "ppo_buffer_write": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "ppo_act": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp]),
+        "ppo_buffer_write_outcome": (C.c_int, [vp, i32, vp, vp]),
         "ppo_buffer_read_obs": (C.c_int, [vp, i32, vp]),
         "ppo_gae": (C.c_int, [vp, vp, C.c_float, C.c_float]),
         "ppo_get_adv_ret": (C.c_int, [vp, vp, vp]),
@@ -88,7 +90,7 @@ def load_library():
 _lib = load_library()
 EXPORTS = ("ppo_create", "ppo_destroy", "ppo_last_error", "ppo_param_count", "ppo_buffer_image_bytes",
            "ppo_set_params", "ppo_get_params", "ppo_get_grads", "ppo_set_opt_state", "ppo_get_opt_state",
-           "ppo_buffer_write", "ppo_buffer_read_obs", "ppo_gae", "ppo_get_adv_ret", "ppo_permutation", "ppo_update", "distill_update",
+           "ppo_buffer_write", "ppo_act", "ppo_buffer_write_outcome", "ppo_buffer_read_obs", "ppo_gae", "ppo_get_adv_ret", "ppo_permutation", "ppo_update", "distill_update",
            "ppo_forward", "ppo_profile", "ppo_profile_report", "ppo_diag_gemm")
 
 
@@ -224,6 +226,23 @@ class Learner:
             self._h, t, _dev(obs, odt, n_obs), _dev(proprio, torch.float32, self.N * net["proprio_dim"]),
             _dev(action, torch.float32, self.N * net["act_dim"]), _dev(logp, torch.float32, self.N),
             _dev(value, torch.float32, self.N), _dev(reward, torch.float32, self.N), _dev(done, torch.uint8, self.N)))
+
+    def act(self, t, obs, proprio, noise):
+        """Policy step on the step-t observations -> (action [N][A], logp [N], value [N]) device tensors."""
+        torch, net = self._torch, self.net
+        n_obs = self.N * net.get("n_views", 1) * net["in_c"] * net["in_h"] * net["in_w"]
+        odt = torch.float32 if self.obs_dtype == "fp32" else torch.bfloat16
+        action = torch.empty(self.N, net["act_dim"], dtype=torch.float32, device="cuda")
+        logp = torch.empty(self.N, dtype=torch.float32, device="cuda")
+        value = torch.empty(self.N, dtype=torch.float32, device="cuda")
+        self._chk(_lib.ppo_act(
+            self._h, t, _dev(obs, odt, n_obs), _dev(proprio, torch.float32, self.N * net["proprio_dim"]),
+            _dev(noise, torch.float32, self.N * net["act_dim"]), _dev(action), _dev(logp), _dev(value)))
+        return action, logp, value
+
+    def buffer_write_outcome(self, t, reward, done):
+        torch = self._torch
+        self._chk(_lib.ppo_buffer_write_outcome(self._h, t, _dev(reward, torch.float32, self.N), _dev(done, torch.uint8, self.N)))
 
     def buffer_read_obs(self, t):
         torch, net = self._torch, self.net

@@ -138,6 +138,81 @@ def test_forward_matches_oracle(L, ci, N, T):
         assert rel_l2(v.cpu().numpy(), qv) <= 5e-3
 
 
+# ------------------------------------------------------------------ policy step of the collection loop
+ACT_CASES = [(0, 64, 3), (1, 200, 2), (1, 1024, 2), (2, 24, 2)]  # (1, 1024, .) is the benchmark's shape
+
+
+@pytest.mark.parametrize("ci,N,T", ACT_CASES)
+def test_act_matches_oracle_and_fills_the_buffer(L, ci, N, T):
+    torch = _torch()
+    cfg = configs.get_config(ci, num_envs=N, horizon=T)
+    net, A = cfg["net"], cfg["net"]["act_dim"]
+    ro = synth.rollout(cfg)
+    params = synth.init_params(net, cfg["seed"])
+    a0, a1, _ = synth.param_slices(net)["logstd"]
+    rng = np.random.default_rng(99)
+    params[a0:a1] = rng.uniform(-1.0, 0.5, A).astype(np.float32)
+    sigma = np.exp(params[a0:a1].astype(np.float64))
+    lrn = L.Learner(net, N, T, cfg["obs_dtype"])
+    lrn.set_params(params)
+    odt = torch.float32 if cfg["obs_dtype"] == "fp32" else torch.bfloat16
+    noise = rng.standard_normal((T, N, A)).astype(np.float32)
+    acted = []
+    for t in range(T):
+        obs = torch.from_numpy(ro["obs"][t]).cuda().to(odt).contiguous()
+        pr = torch.from_numpy(ro["proprio"][t]).cuda().contiguous()
+        a, lp, v = lrn.act(t, obs, pr, torch.from_numpy(noise[t]).cuda())
+        lrn.synchronize()
+        a, lp, v = a.cpu().numpy(), lp.cpu().numpy(), v.cpu().numpy()
+        acted.append((a, lp, v))
+        oa, olp, ov = orc.act(net, params, ro["obs"][t], ro["proprio"][t], noise[t])
+        omu = oa - sigma * noise[t]
+        # the sampled offset is common to both sides: the error is measured against the mean's norm
+        assert np.linalg.norm(a - oa) / np.linalg.norm(omu) <= TOL_BF16
+        assert rel_l2(v, ov) <= TOL_BF16
+        assert np.max(np.abs(lp - olp)) <= 1e-3
+        with orc.quant(1):
+            qa, _, qv = orc.act(net, params, ro["obs"][t], ro["proprio"][t], noise[t])
+        assert np.linalg.norm(a - qa) / np.linalg.norm(omu) <= 5e-3 and rel_l2(v, qv) <= 5e-3
+    # gae is refused until every step has its outcome
+    lv = torch.from_numpy(ro["last_value"]).cuda()
+    with pytest.raises(L.LearnerError) as e:
+        lrn.gae(lv, 0.99, 0.95)
+    assert e.value.code == L.PPO_ESTATE
+    for t in range(T):
+        lrn.buffer_write_outcome(t, torch.from_numpy(ro["reward"][t]).cuda(), torch.from_numpy(ro["done"][t]).cuda())
+    lrn.gae(lv, cfg["hp"]["gamma"], cfg["hp"]["lam"])
+    # the slab holds what act returned: GAE from the returned values equals the oracle's
+    vals = np.stack([x[2] for x in acted])
+    adv, ret = lrn.get_adv_ret()
+    oadv, oret = orc.gae(ro["reward"], ro["done"], vals, ro["last_value"], cfg["hp"]["gamma"], cfg["hp"]["lam"])
+    assert np.max(np.abs(adv.cpu().numpy() - oadv) / np.maximum(1, np.abs(oadv))) <= TOL_GAE
+    # and the stored actions and log-probs give ratio 1 on the first optimiser step
+    if (N * T) % 2 == 0:
+        st = lrn.update(dict(cfg["hp"], epochs=1, minibatches=2))
+        assert abs(st[0]["approx_kl"]) <= 1e-6 and st[0]["clip_frac"] == 0.0
+        B = N * T // 2
+        perm = orc.permutation(cfg["hp"].get("seed", 0), 0, 0, N * T)[:B]
+        assert abs(st[0]["pi_loss"] + oadv.reshape(-1)[perm].mean()) <= 1e-4 * max(1.0, np.abs(oadv).max())
+
+
+def test_act_call_order_errors(L):
+    torch = _torch()
+    cfg = configs.get_config(0, num_envs=8, horizon=2)
+    lrn = L.Learner(cfg["net"], 8, 2, "fp32")
+    z = torch.zeros(8, device="cuda")
+    with pytest.raises(L.LearnerError) as e:
+        lrn.buffer_write_outcome(0, z, z.to(torch.uint8))
+    assert e.value.code == L.PPO_ESTATE
+    scfg = _stereo_cfg(8, 2)
+    stu = L.Learner(scfg["net"], 8, 2, scfg["obs_dtype"])
+    sn = scfg["net"]
+    with pytest.raises(L.LearnerError) as e:
+        stu.act(0, torch.zeros(8, sn["n_views"], sn["in_c"], sn["in_h"], sn["in_w"], device="cuda", dtype=torch.bfloat16),
+                torch.zeros(8, sn["proprio_dim"], device="cuda"), torch.zeros(8, sn["act_dim"], device="cuda"))
+    assert e.value.code == L.PPO_ESTATE
+
+
 # ------------------------------------------------------------------ one minibatch: loss and gradients
 def _oracle_inputs(cfg, ro, lrn):
     fr = flat_rollout(ro)
