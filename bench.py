@@ -6,7 +6,10 @@ resident in HBM: T x ppo_buffer_write, ppo_gae, ppo_update (all epochs x minibat
 distillation workload T x ppo_buffer_write + distill_update.  The metric is learner
 env-steps/s = N*T / time per step.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline] [--phase learn|act]
+
+--phase act times the step in front of the path instead: T x (ppo_act + ppo_buffer_write_outcome), the policy
+step of the collection loop on the same observations (metric: policy env-steps/s).
 
 Prints one JSON line.  `roofline` describes the kernel class with the largest share of the step,
 timed with HIP events on the library's stream in a second, instrumented pass over the same K steps;
@@ -63,6 +66,7 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into the benchmark config list (default 1: medium)")
     ap.add_argument("--num-envs", type=int, default=None, help="override the config's env count (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--phase", choices=["learn", "act"], default="learn", help="learn: the learner path (default); act: the policy step")
     ap.add_argument("--profile-table", action="store_true", help="also print the per-kernel-class table to stderr")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -80,6 +84,10 @@ def main():
     cfg = configs.get_config(args.config, num_envs=args.num_envs)
     net, N, T, hp = cfg["net"], cfg["num_envs"], cfg["horizon"], dict(cfg["hp"], seed=cfg["seed"])
     distill = cfg["kind"] == "distill"
+    act = args.phase == "act"
+    if act and distill:
+        print("bench.py: --phase act needs an actor-critic workload", file=sys.stderr)
+        sys.exit(2)
     S = N * T
 
     # ---- synthetic rollout, drawn per step on the GPU (seeded) and kept resident in HBM
@@ -97,9 +105,15 @@ def main():
             host_steps.append({k: v.float().cpu().numpy() if v.dtype != torch.uint8 else v.cpu().numpy() for k, v in d.items()})
         steps_dev.append(d)
     last_value = torch.randn(N, generator=gen, device="cuda")
+    noise = [torch.randn(N, net["act_dim"], generator=gen, device="cuda") for _ in range(T)] if act else None
     torch.cuda.synchronize()
 
     def one_step():
+        if act:
+            for t, d in enumerate(steps_dev):
+                lrn.act(t, d["obs"], d["proprio"], noise[t])
+                lrn.buffer_write_outcome(t, d["reward"], d["done"])
+            return
         for t, d in enumerate(steps_dev):
             if distill:
                 lrn.buffer_write(t, d["obs"], d["proprio"], d["action"])
@@ -140,10 +154,10 @@ def main():
         ach, peak, unit = r["bytes"] / r["launches"] / avg_s / 1e9, PEAK_HBM_GBS, "GB/s"
     roofline = dict(bound=kernel_bound(r), kernel=dom, intensity_flop_per_byte=round(r["flops"] / max(r["bytes"], 1.0), 1), achieved=round(ach, 3), peak=peak, unit=unit,
                     frac=round(ach / peak, 5),
-                    traffic=MEASURED_TRAFFIC_BYTES.get((cfg["name"], dom)) if args.num_envs is None else None,
+                    traffic=MEASURED_TRAFFIC_BYTES.get((cfg["name"], dom)) if args.num_envs is None and not act else None,
                     algorithmic_bytes_per_launch=round(r["bytes"] / r["launches"], 1), avg_launch_us=round(avg_s * 1e6, 2),
                     launches_per_step=r["launches"] / args.steps, share_of_kernel_time=round(r["ms"] / tot_ms, 4))
-    step_flops = fl["fwd_bwd"] * S * hp["epochs"]
+    step_flops = fl["fwd"] * S if act else fl["fwd_bwd"] * S * hp["epochs"]
     if args.profile_table:
         print(f"{'class':<16}{'launches':>9}{'ms/step':>10}{'share':>8}{'TFLOP/s':>10}{'GB/s':>10}", file=sys.stderr)
         for k in sorted(rep, key=lambda k: -rep[k]["ms"]):
@@ -161,28 +175,37 @@ def main():
         sub = {k: np.concatenate([h[k] for h in host_steps])[:n_sub] for k in host_steps[0]}
         p = synth.init_params(net, cfg["seed"])
         t1 = time.perf_counter()
-        if distill:
+        if act:
+            n_sub = min(n_sub * 3, len(host_steps) * N)  # forward only: a third of the work per sample
+            sub = {k: v[:n_sub] for k, v in {k: np.concatenate([h[k] for h in host_steps]) for k in host_steps[0]}.items()}
+            orc.act(net, p, sub["obs"], sub["proprio"], np.zeros((n_sub, net["act_dim"])))
+        elif distill:
             orc.distill_loss_grad(net, p, sub["obs"], sub["proprio"], sub["action"])
         else:
             orc.ppo_loss_grad(net, p, sub["obs"], sub["proprio"], sub["action"], sub["logp_old"], sub["value"],
                               np.zeros(n_sub), np.zeros(n_sub), clip_eps=hp["clip_eps"], vclip_eps=hp["vclip_eps"],
                               vf_coef=hp["vf_coef"], ent_coef=hp["ent_coef"])
         t_mb = time.perf_counter() - t1
+        if act:
+            cpu = dict(value=round(n_sub / t_mb, 3), unit="env-steps/s", cores=orc.num_threads(), kind="oracle",
+                       sample=f"policy step of {n_sub} of the {S} observations timed ({t_mb:.1f} s)")
         # GAE and the permutations at full size (cheap), then extrapolate the network part linearly in samples
         t2 = time.perf_counter()
-        if not distill:
+        if not distill and not act:
             z = np.zeros((T, N))
             orc.gae(z, np.zeros((T, N), np.uint8), z, np.zeros(N), hp["gamma"], hp["lam"])
-        for e in range(hp["epochs"]):
+        for e in range(0 if act else hp["epochs"]):
             orc.permutation(hp["seed"], 0, e, S)
         t_small = time.perf_counter() - t2
         t_full = t_mb / n_sub * S * hp["epochs"] + t_small
-        cpu = dict(value=round(S / t_full, 3), unit="env-steps/s", cores=orc.num_threads(), kind="oracle",
-                   sample=f"forward+loss+backward of {n_sub} of the {S} samples timed ({t_mb:.1f} s), extrapolated "
-                          f"linearly to {hp['epochs']} epochs; GAE and permutations timed at full size")
+        if not act:
+          cpu = dict(value=round(S / t_full, 3), unit="env-steps/s", cores=orc.num_threads(), kind="oracle",
+                     sample=f"forward+loss+backward of {n_sub} of the {S} samples timed ({t_mb:.1f} s), extrapolated "
+                            f"linearly to {hp['epochs']} epochs; GAE and permutations timed at full size")
 
     out = {
-        "metric": "learner env-steps/sec (GAE + PPO epochs)" if not distill else "learner env-steps/sec (distillation update)",
+        "metric": "policy env-steps/sec (act + buffer append)" if act else
+                  "learner env-steps/sec (GAE + PPO epochs)" if not distill else "learner env-steps/sec (distillation update)",
         "value": round(value, 1), "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",

@@ -63,6 +63,7 @@ typedef struct {
 
 typedef struct {
   double lr, beta1, beta2, eps;
+  double max_grad_norm; /* <= 0: no clipping */
 } orc_adam_cfg;
 
 /* stats slots */
@@ -595,10 +596,38 @@ void orc_adam_step(int64_t n, double *params, double *m, double *v, const double
   }
 }
 
+/* Global gradient-norm clipping (Pascanu et al. 2013, as the common deep-learning
+ * libraries implement it): with n = ||g||_2 over ALL parameters, g <- g * min(1, c / (n + 1e-6)).
+ * Returns n, the norm before clipping.  max_norm <= 0: g untouched. */
+double orc_clip_grad_norm(int64_t n, double *grads, double max_norm) {
+  double sq = 0;
+  for (int64_t i = 0; i < n; ++i) sq += grads[i] * grads[i];
+  double norm = sqrt(sq);
+  if (max_norm > 0) {
+    double coef = max_norm / (norm + 1e-6);
+    if (coef < 1.0)
+      for (int64_t i = 0; i < n; ++i) grads[i] *= coef;
+  }
+  return norm;
+}
+
+/* Advantage normalisation over the whole rollout (all S = N*T samples, once per update):
+ *   out = (adv - mean) / (std + 1e-8),  std = population standard deviation. */
+void orc_normalize_adv(int64_t S, const double *adv, double *out) {
+  double mean = 0, var = 0;
+  for (int64_t i = 0; i < S; ++i) mean += adv[i];
+  mean /= (double)S;
+  for (int64_t i = 0; i < S; ++i) var += (adv[i] - mean) * (adv[i] - mean);
+  double sd = sqrt(var / (double)S);
+  for (int64_t i = 0; i < S; ++i) out[i] = (adv[i] - mean) / (sd + 1e-8);
+}
+
 /* One learner update over a buffer of S = N*T samples: for each epoch draw a
  * fresh permutation, split it into `minibatches` contiguous chunks, and for
  * each chunk: forward, loss, backward, one Adam step.  adv/ret/logp_old/v_old
  * stay fixed for the whole update.  *step is the Adam step counter (in/out).
+ * With ac->max_grad_norm > 0 the gradient is clipped to that global norm before the Adam step
+ * (the grad-norm statistic stays the norm before clipping).
  * stats: [epochs*minibatches][ST_N]; grads_last: gradients of the last minibatch. */
 static void update_loop(const orc_net *n, double *params, double *m, double *v, int64_t *step,
                         int64_t S, const float *obs, const double *proprio, const double *action,
@@ -630,10 +659,13 @@ static void update_loop(const orc_net *n, double *params, double *m, double *v, 
       double *st = stats + ((int64_t)e * minibatches + mb) * ST_N;
       minibatch_grad(n, params, B, mobs, mpro, mact, mlp, mvo, mad, mre, lc, distill, grads, st);
       *step += 1;
+      /* the gradient reported for the last minibatch is the one before clipping */
+      if (grads_last && e == epochs - 1 && mb == minibatches - 1)
+        memcpy(grads_last, grads, sizeof(double) * (size_t)g.total);
+      orc_clip_grad_norm(g.total, grads, ac->max_grad_norm);
       orc_adam_step(g.total, params, m, v, grads, *step, ac);
     }
   }
-  if (grads_last) memcpy(grads_last, grads, sizeof(double) * (size_t)g.total);
   free(perm); free(mobs); free(mpro); free(mact); free(mlp); free(mvo); free(mad); free(mre); free(grads);
 }
 

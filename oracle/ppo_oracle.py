@@ -45,7 +45,8 @@ class _LossCfg(C.Structure):
 
 
 class _AdamCfg(C.Structure):
-    _fields_ = [("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double)]
+    _fields_ = [("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
+                ("max_grad_norm", C.c_double)]
 
 
 _lib = None
@@ -235,8 +236,25 @@ def adam_step(params, m, v, grads, k, lr=3e-4, beta1=0.9, beta2=0.999, eps=1e-8)
     for a in (params, m, v):
         assert a.dtype == np.float64 and a.flags.c_contiguous
     grads = _d(grads)
-    cfg = _AdamCfg(lr, beta1, beta2, eps)
+    cfg = _AdamCfg(lr, beta1, beta2, eps, 0.0)
     lib().orc_adam_step(C.c_int64(params.size), _p(params), _p(m), _p(v), _p(grads), C.c_int64(k), C.byref(cfg))
+
+
+def clip_grad_norm(grads, max_norm):
+    """-> (clipped copy of grads, norm before clipping)."""
+    g = _d(grads).copy()
+    f = lib().orc_clip_grad_norm
+    f.restype = C.c_double
+    norm = f(C.c_int64(g.size), _p(g), C.c_double(max_norm))
+    return g, float(norm)
+
+
+def normalize_adv(adv):
+    """(adv - mean) / (population std + 1e-8) over all samples."""
+    a = _d(adv)
+    out = np.empty_like(a)
+    lib().orc_normalize_adv(C.c_int64(a.size), _p(a), _p(out))
+    return out
 
 
 def _update(fn_name, net, params, m, v, step, obs, proprio, action, extra, hp, update_idx):
@@ -250,7 +268,8 @@ def _update(fn_name, net, params, m, v, step, obs, proprio, action, extra, hp, u
     st = np.zeros((E * M, ST_N))
     gl = np.zeros(params.size)
     stp = C.c_int64(step)
-    ac = _AdamCfg(hp.get("lr", 3e-4), hp.get("beta1", 0.9), hp.get("beta2", 0.999), hp.get("adam_eps", 1e-8))
+    ac = _AdamCfg(hp.get("lr", 3e-4), hp.get("beta1", 0.9), hp.get("beta2", 0.999), hp.get("adam_eps", 1e-8),
+                  hp.get("max_grad_norm", 0.0))
     if fn_name == "ppo":
         logp_old, v_old, adv, ret = (_d(x) for x in extra)
         lc = _LossCfg(hp.get("clip_eps", 0.2), hp.get("vclip_eps", 0.0), hp.get("vf_coef", 0.5),
@@ -268,7 +287,11 @@ def _update(fn_name, net, params, m, v, step, obs, proprio, action, extra, hp, u
 
 
 def ppo_update(net, params, m, v, step, obs, proprio, action, logp_old, v_old, adv, ret, hp, update_idx=0):
-    """Whole PPO update over flat samples s = t*N + n.  Returns new params/m/v/step, stats, last grads."""
+    """Whole PPO update over flat samples s = t*N + n.  Returns new params/m/v/step, stats, last grads.
+    hp["norm_adv"]: advantages normalised over the whole rollout first; hp["max_grad_norm"] > 0: global
+    gradient-norm clipping before every Adam step."""
+    if hp.get("norm_adv", 0):
+        adv = normalize_adv(adv)
     return _update("ppo", net, params, m, v, step, obs, proprio, action, (logp_old, v_old, adv, ret), hp,
                    update_idx)
 

@@ -435,18 +435,56 @@ def test_adam_matches_library_optimiser():
 
 
 # ----------------------------------------------------------------- composed update
-def test_update_loop_against_library_recomposition():
-    """The epochs x minibatches loop, re-composed from library pieces (autograd + optim.Adam)
-    around the oracle's own permutation."""
+def test_grad_norm_clipping_closed_forms_and_library():
+    rng = np.random.default_rng(50)
+    g = rng.standard_normal(1000)
+    n0 = np.linalg.norm(g)
+    c, n = orc.clip_grad_norm(g, 0.5 * n0)
+    assert abs(n - n0) < 1e-12
+    np.testing.assert_allclose(np.linalg.norm(c), 0.5 * n0 * n0 / (n0 + 1e-6), rtol=1e-12)
+    np.testing.assert_allclose(c / np.linalg.norm(c), g / n0, rtol=0, atol=1e-14)   # direction kept
+    for mx in (2.0 * n0, 0.0, -1.0):                                                # above the norm / off: untouched
+        c, n = orc.clip_grad_norm(g, mx)
+        np.testing.assert_array_equal(c, g)
+        assert abs(n - n0) < 1e-12
+    # the library's routine over several tensors: one global norm
+    parts = [torch.tensor(g[:300].copy(), requires_grad=True), torch.tensor(g[300:].copy(), requires_grad=True)]
+    for t, sl in zip(parts, (slice(0, 300), slice(300, 1000))):
+        t.grad = torch.tensor(g[sl].copy())
+    tn = torch.nn.utils.clip_grad_norm_(parts, 3.0)
+    c, n = orc.clip_grad_norm(g, 3.0)
+    assert abs(float(tn) - n) < 1e-10
+    np.testing.assert_allclose(c, np.concatenate([t.grad.numpy() for t in parts]), rtol=1e-12, atol=0)
+
+
+def test_advantage_normalisation_closed_forms():
+    out = orc.normalize_adv(np.array([1.0, 2.0, 3.0]))
+    np.testing.assert_allclose(out, np.array([-1.0, 0.0, 1.0]) / (math.sqrt(2.0 / 3.0) + 1e-8), rtol=1e-14)
+    a = np.random.default_rng(51).standard_normal(5000) * 3.0 + 7.0
+    out = orc.normalize_adv(a)
+    assert abs(out.mean()) < 1e-12 and abs(out.std() - 1.0) < 1e-7          # population std
+    np.testing.assert_allclose(out, (a - a.mean()) / (a.std(ddof=0) + 1e-8), rtol=1e-12, atol=1e-12)
+    np.testing.assert_array_equal(orc.normalize_adv(np.full(7, 4.25)), np.zeros(7))   # constant input: zero, not NaN
+    # affine invariance: a positive rescaling and a shift of the advantages change nothing
+    np.testing.assert_allclose(orc.normalize_adv(5.0 * a - 2.0), out, rtol=0, atol=1e-7)
+
+
+@pytest.mark.parametrize("extras", [dict(), dict(max_grad_norm=0.05, norm_adv=1)])
+def test_update_loop_against_library_recomposition(extras):
+    """The epochs x minibatches loop, re-composed from library pieces (autograd + optim.Adam, and with the
+    options on: clip_grad_norm_ and a numpy normalisation) around the oracle's own permutation."""
     net = TINY
     N, T, E, M = 6, 4, 2, 3
     S = N * T
     b, params = _batch(net, S, 40), _params(net, 41)
-    hp = dict(epochs=E, minibatches=M, clip_eps=0.2, vclip_eps=0.3, vf_coef=0.5, ent_coef=0.01, lr=1e-3, seed=99)
+    hp = dict(epochs=E, minibatches=M, clip_eps=0.2, vclip_eps=0.3, vf_coef=0.5, ent_coef=0.01, lr=1e-3, seed=99, **extras)
     out = orc.ppo_update(net, params, np.zeros_like(params), np.zeros_like(params), 0, b["obs"], b["proprio"],
                          b["action"], b["logp_old"], b["v_old"], b["adv"], b["ret"], hp, update_idx=2)
     p, sl = torch_ref.unpack(net, params)
     opt = torch.optim.Adam([p], lr=1e-3)
+    adv = b["adv"]
+    if extras.get("norm_adv"):
+        adv = (adv - adv.mean()) / (adv.std() + 1e-8)
     k = 0
     for e in range(E):
         perm = orc.permutation(99, 2, e, S)
@@ -455,9 +493,13 @@ def test_update_loop_against_library_recomposition():
             opt.zero_grad()
             mu, v, ls = torch_ref.forward(net, p, sl, b["obs"][idx], b["proprio"][idx])
             loss, _ = torch_ref.ppo_loss(mu, v, ls, b["action"][idx], b["logp_old"][idx], b["v_old"][idx],
-                                         b["adv"][idx], b["ret"][idx], 0.2, 0.3, 0.5, 0.01)
+                                         adv[idx], b["ret"][idx], 0.2, 0.3, 0.5, 0.01)
             loss.backward()
             assert abs(out["stats"][k]["total"] - loss.item()) < 1e-10
+            if extras.get("max_grad_norm"):
+                tn = torch.nn.utils.clip_grad_norm_([p], extras["max_grad_norm"])
+                assert float(tn) > extras["max_grad_norm"]          # the clip is active in this test
+                assert abs(out["stats"][k]["grad_norm"] - float(tn)) < 1e-10
             opt.step()
             k += 1
     assert out["step"] == E * M
