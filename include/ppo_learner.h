@@ -73,9 +73,10 @@ typedef struct {
   float vclip_eps;              /* <= 0: value clipping off */
   float vf_coef, ent_coef;
   float lr, beta1, beta2, adam_eps;
-  float max_grad_norm;          /* must be <= 0 (gradient clipping is not implemented) */
+  float max_grad_norm;          /* > 0: global gradient-norm clipping, g *= min(1, c / (||g|| + 1e-6)), before every Adam step; <= 0: off */
   int32_t epochs, minibatches;  /* num_envs*horizon must be divisible by minibatches */
-  int32_t norm_adv;             /* must be 0 */
+  int32_t norm_adv;             /* 1: advantages normalised once per update over the whole rollout,
+                                   (A - mean) / (population std + 1e-8); 0: raw advantages */
   uint64_t seed;                /* permutation stream seed */
 } ppo_hparams;
 

@@ -630,13 +630,17 @@ __global__ void k_loss_finalize(int nblocks, int Bfull, int A, int distill, cons
 // ---------------------------------------------------------------- Adam
 // m = b1 m + (1-b1) g; v = b2 v + (1-b2) g^2; p -= lr (m/c1) / (sqrt(v/c2) + eps), c1 = 1-b1^k,
 // c2 = 1-b2^k passed in.  Also refreshes the bf16 copy of the parameters and leaves per-block sums
-// of g^2 for the gradient-norm statistic.
+// of g^2 for the gradient-norm statistic.  With gradient-norm clipping the gradient enters as
+// g * *clip_coef (the coefficient min(1, c / (||g|| + 1e-6)) left by k_gnorm_finalize); the sums
+// of g^2 are of the gradient before clipping either way.
 __global__ __launch_bounds__(256) void k_adam(int64_t n, float* __restrict__ p, float* __restrict__ m,
                                               float* __restrict__ v, const float* __restrict__ g,
                                               bf16_t* __restrict__ shadow, float lr, float b1, float b2, float eps,
-                                              float inv_c1, float inv_c2, float* __restrict__ sq_part) {
+                                              float inv_c1, float inv_c2, float* __restrict__ sq_part,
+                                              const float* __restrict__ clip_coef) {
   __shared__ float red[256];
   const int tid = threadIdx.x;
+  const float coef = clip_coef ? *clip_coef : 1.f;
   float sq = 0.f;
   for (int64_t i = ((int64_t)blockIdx.x * 256 + tid) * 4; i < n; i += (int64_t)gridDim.x * 1024) {
     if (i + 4 <= n) {
@@ -645,20 +649,21 @@ __global__ __launch_bounds__(256) void k_adam(int64_t n, float* __restrict__ p, 
       float* gp = &g4.x; float* mp = &m4.x; float* vp = &v4.x; float* pp = &p4.x;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        mp[j] = b1 * mp[j] + (1.f - b1) * gp[j];
-        vp[j] = b2 * vp[j] + (1.f - b2) * gp[j] * gp[j];
-        pp[j] -= lr * (mp[j] * inv_c1) / (sqrtf(vp[j] * inv_c2) + eps);
         sq += gp[j] * gp[j];
+        const float gc = gp[j] * coef;
+        mp[j] = b1 * mp[j] + (1.f - b1) * gc;
+        vp[j] = b2 * vp[j] + (1.f - b2) * gc * gc;
+        pp[j] -= lr * (mp[j] * inv_c1) / (sqrtf(vp[j] * inv_c2) + eps);
       }
       *reinterpret_cast<float4*>(m + i) = m4; *reinterpret_cast<float4*>(v + i) = v4; *reinterpret_cast<float4*>(p + i) = p4;
       uint2 s2; s2.x = pack2bf(p4.x, p4.y); s2.y = pack2bf(p4.z, p4.w);
       *reinterpret_cast<uint2*>(shadow + i) = s2;
     } else {
       for (int64_t q = i; q < n; ++q) {
-        float gq = g[q];
+        const float gr = g[q], gq = gr * coef;
         float mq = b1 * m[q] + (1.f - b1) * gq, vq = b2 * v[q] + (1.f - b2) * gq * gq;
         float pq = p[q] - lr * (mq * inv_c1) / (sqrtf(vq * inv_c2) + eps);
-        m[q] = mq; v[q] = vq; p[q] = pq; shadow[q] = f2bf(pq); sq += gq * gq;
+        m[q] = mq; v[q] = vq; p[q] = pq; shadow[q] = f2bf(pq); sq += gr * gr;
       }
     }
   }
@@ -667,7 +672,29 @@ __global__ __launch_bounds__(256) void k_adam(int64_t n, float* __restrict__ p, 
   for (int s = 128; s > 0; s >>= 1) { if (tid < s) red[tid] += red[tid + s]; __syncthreads(); }
   if (tid == 0) sq_part[blockIdx.x] = red[0];
 }
-__global__ __launch_bounds__(256) void k_gnorm_finalize(const float* __restrict__ sq_part, int nb, DevStats* __restrict__ st) {
+// Per-block sums of g^2 with the blocking of k_adam (the same partial sums, so the norm used for
+// clipping is bit-identical to the statistic reported without clipping).
+__global__ __launch_bounds__(256) void k_gnorm_partial(int64_t n, const float* __restrict__ g, float* __restrict__ sq_part) {
+  __shared__ float red[256];
+  const int tid = threadIdx.x;
+  float sq = 0.f;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + tid) * 4; i < n; i += (int64_t)gridDim.x * 1024) {
+    if (i + 4 <= n) {
+      const float4 g4 = *reinterpret_cast<const float4*>(g + i);
+      sq += g4.x * g4.x; sq += g4.y * g4.y; sq += g4.z * g4.z; sq += g4.w * g4.w;
+    } else {
+      for (int64_t q = i; q < n; ++q) sq += g[q] * g[q];
+    }
+  }
+  red[tid] = sq;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) { if (tid < s) red[tid] += red[tid + s]; __syncthreads(); }
+  if (tid == 0) sq_part[blockIdx.x] = red[0];
+}
+// Gradient norm from the per-block sums; with max_norm > 0 also the clipping coefficient
+// min(1, max_norm / (norm + 1e-6)) for k_adam.
+__global__ __launch_bounds__(256) void k_gnorm_finalize(const float* __restrict__ sq_part, int nb, DevStats* __restrict__ st, float max_norm,
+                                                        float* __restrict__ clip_coef) {
   __shared__ float red[256];
   const int tid = threadIdx.x;
   float s = 0.f;
@@ -676,9 +703,39 @@ __global__ __launch_bounds__(256) void k_gnorm_finalize(const float* __restrict_
   __syncthreads();
   for (int w = 128; w > 0; w >>= 1) { if (tid < w) red[tid] += red[tid + w]; __syncthreads(); }
   if (tid == 0) {
-    st->grad_norm = sqrtf(red[0]);
+    const float norm = sqrtf(red[0]);
+    st->grad_norm = norm;
     if (!isfinite(red[0])) st->nonfinite = 1;
+    if (clip_coef) *clip_coef = max_norm > 0.f ? fminf(1.f, max_norm / (norm + 1e-6f)) : 1.f;
   }
+}
+
+// ---------------------------------------------------------------- advantage normalisation
+// out = (adv - mean) / (std + 1e-8) over all S samples of the rollout, std the population standard
+// deviation.  One block of 1024 threads, sums in a fixed order (the result does not depend on the
+// launch); S is at most a few hundred thousand, once per update.
+__global__ __launch_bounds__(1024) void k_adv_normalize(int S, const float* __restrict__ adv, float* __restrict__ out) {
+  __shared__ float red[1024];
+  __shared__ float bc[2];
+  const int tid = threadIdx.x;
+  float s = 0.f;
+  for (int i = tid; i < S; i += 1024) s += adv[i];
+  red[tid] = s;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) { if (tid < w) red[tid] += red[tid + w]; __syncthreads(); }
+  if (tid == 0) bc[0] = red[0] / (float)S;
+  __syncthreads();
+  const float mean = bc[0];
+  float q = 0.f;
+  for (int i = tid; i < S; i += 1024) { const float d = adv[i] - mean; q += d * d; }
+  __syncthreads();
+  red[tid] = q;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) { if (tid < w) red[tid] += red[tid + w]; __syncthreads(); }
+  if (tid == 0) bc[1] = 1.f / (sqrtf(red[0] / (float)S) + 1e-8f);
+  __syncthreads();
+  const float inv = bc[1];
+  for (int i = tid; i < S; i += 1024) out[i] = (adv[i] - mean) * inv;
 }
 __global__ void k_cast_bf16(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

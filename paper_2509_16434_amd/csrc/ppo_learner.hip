@@ -79,7 +79,8 @@ struct Ctx {
   int64_t partial_cap = 0, bias_partial_cap = 0;
   ReduceJobs rjobs;
   int rjob_blocks = 0;
-  float *stat_part = nullptr, *dls_part = nullptr, *sq_part = nullptr;
+  float *stat_part = nullptr, *dls_part = nullptr, *sq_part = nullptr, *clip_coef = nullptr;
+  float* adv_n = nullptr;  // advantages normalised over the rollout (norm_adv)
   int max_loss_blocks = 0, adam_blocks = 0;
   DevStats* dstats = nullptr;
   int max_steps = 4096;
@@ -192,8 +193,7 @@ int validate_hp(Ctx* c, const ppo_hparams* hp, bool distill) {
   if (!distill && !(hp->clip_eps > 0.f)) return fail(c, PPO_EINVAL, "clip_eps must be > 0");
   if (!(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) || !(hp->adam_eps > 0.f))
     return fail(c, PPO_EINVAL, "Adam hyper-parameters out of range");
-  if (hp->max_grad_norm > 0.f) return fail(c, PPO_EINVAL, "gradient-norm clipping is not implemented (max_grad_norm must be <= 0)");
-  if (hp->norm_adv != 0) return fail(c, PPO_EINVAL, "advantage normalisation is not implemented (norm_adv must be 0)");
+  if (hp->norm_adv != 0 && hp->norm_adv != 1) return fail(c, PPO_EINVAL, "norm_adv must be 0 or 1");
   if (hp->epochs < 1 || hp->minibatches < 1) return fail(c, PPO_EINVAL, "epochs and minibatches must be >= 1");
   if (c->S % hp->minibatches) return fail(c, PPO_ESHAPE, "num_envs*horizon = %d is not divisible by minibatches = %d", c->S, hp->minibatches);
   if ((int64_t)hp->epochs * hp->minibatches > c->max_steps) return fail(c, PPO_ESHAPE, "epochs*minibatches exceeds %d", c->max_steps);
@@ -961,6 +961,11 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
   const int steps = hp->epochs * hp->minibatches;
   const int blocks_per_chunk = cdiv(c->CH, LOSS_BLOCK);
   int k = 0;
+  if (!distill && hp->norm_adv) {
+    ProfScope ps(c, "adv_normalize", 0.0, 12.0 * c->S);
+    hipLaunchKernelGGL(k_adv_normalize, dim3(1), dim3(1024), 0, c->stream, c->S, c->adv, c->adv_n);
+    LAUNCHCHK(c, "k_adv_normalize");
+  }
   for (int e = 0; e < hp->epochs; ++e) {
     int rc = gen_permutation(c, hp->seed, (uint64_t)c->update_idx, (uint64_t)e);
     if (rc) return rc;
@@ -976,7 +981,7 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
         float* dp = c->dls_part + (int64_t)ci * blocks_per_chunk * 32;
         LossData L;
         L.Bfull = B; L.A = c->A; L.logstd = distill ? nullptr : c->p + c->logstd; L.idx = idx + c0; L.action = c->action; L.logp_old = c->logp;
-        L.v_old = c->value; L.adv = c->adv; L.ret = c->ret; L.clip_eps = hp->clip_eps; L.vclip_eps = hp->vclip_eps; L.vf_coef = hp->vf_coef;
+        L.v_old = c->value; L.adv = hp->norm_adv ? c->adv_n : c->adv; L.ret = c->ret; L.clip_eps = hp->clip_eps; L.vclip_eps = hp->vclip_eps; L.vf_coef = hp->vf_coef;
         bool head_done = false;
         if (fused_head) {
           rc = launch_head_loss(c, L, n, c0 > 0, distill, sp, dp);
@@ -1008,11 +1013,20 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
       {
       ProfScope ps(c, "adam", 0.0, 30.0 * (double)c->total);
       const double c1 = 1.0 - pow((double)hp->beta1, (double)c->step), c2 = 1.0 - pow((double)hp->beta2, (double)c->step);
+      const bool clip = hp->max_grad_norm > 0.f;
+      if (clip) {  // the norm has to be known before the step: one more pass over the gradient
+        hipLaunchKernelGGL(k_gnorm_partial, dim3(c->adam_blocks), dim3(256), 0, c->stream, c->total, c->g, c->sq_part);
+        LAUNCHCHK(c, "k_gnorm_partial");
+        hipLaunchKernelGGL(k_gnorm_finalize, dim3(1), dim3(256), 0, c->stream, c->sq_part, c->adam_blocks, c->dstats + k, hp->max_grad_norm, c->clip_coef);
+        LAUNCHCHK(c, "k_gnorm_finalize");
+      }
       hipLaunchKernelGGL(k_adam, dim3(c->adam_blocks), dim3(256), 0, c->stream, c->total, c->p, c->m, c->v, c->g, c->shadow, hp->lr, hp->beta1, hp->beta2,
-                         hp->adam_eps, (float)(1.0 / c1), (float)(1.0 / c2), c->sq_part);
+                         hp->adam_eps, (float)(1.0 / c1), (float)(1.0 / c2), c->sq_part, clip ? c->clip_coef : nullptr);
       LAUNCHCHK(c, "k_adam");
-      hipLaunchKernelGGL(k_gnorm_finalize, dim3(1), dim3(256), 0, c->stream, c->sq_part, c->adam_blocks, c->dstats + k);
-      LAUNCHCHK(c, "k_gnorm_finalize");
+      if (!clip) {
+        hipLaunchKernelGGL(k_gnorm_finalize, dim3(1), dim3(256), 0, c->stream, c->sq_part, c->adam_blocks, c->dstats + k, 0.f, nullptr);
+        LAUNCHCHK(c, "k_gnorm_finalize");
+      }
       }
       rc = repack_weights(c);
       if (rc) return rc;
@@ -1049,7 +1063,7 @@ int create_impl(Ctx* c) {
   // rollout buffer
   DALLOC(c, c->obs, S * V * c->img_elems);
   DALLOC(c, c->proprio, S * c->P); DALLOC(c, c->action, S * c->A);
-  DALLOC(c, c->logp, S); DALLOC(c, c->value, S); DALLOC(c, c->reward, S); DALLOC(c, c->adv, S); DALLOC(c, c->ret, S); DALLOC(c, c->done, S);
+  DALLOC(c, c->logp, S); DALLOC(c, c->value, S); DALLOC(c, c->reward, S); DALLOC(c, c->adv, S); DALLOC(c, c->adv_n, S); DALLOC(c, c->ret, S); DALLOC(c, c->done, S);
   // permutation: about 32 keys per bucket
   int nb = 1, lg = 0;
   while ((int64_t)nb * 32 < S && nb < (1 << 20)) { nb <<= 1; ++lg; }
@@ -1116,6 +1130,7 @@ int create_impl(Ctx* c) {
   DALLOC(c, c->stat_part, (int64_t)c->max_loss_blocks * LOSS_NSTAT); DALLOC(c, c->dls_part, (int64_t)c->max_loss_blocks * 32);
   c->adam_blocks = cdiv(c->total, 1024); if (c->adam_blocks > 2048) c->adam_blocks = 2048;
   DALLOC(c, c->sq_part, c->adam_blocks);
+  DALLOC(c, c->clip_coef, 1);
   DALLOC(c, c->dstats, c->max_steps);
   HIPCHK(c, hipMemsetAsync(c->p, 0, sizeof(float) * (size_t)c->total, c->stream));
   HIPCHK(c, hipMemsetAsync(c->m, 0, sizeof(float) * (size_t)c->total, c->stream));

@@ -332,6 +332,56 @@ def test_adam_steps_replayed_exactly(L, ci, N, T):
         m, v = gm.astype(np.float64), gv.astype(np.float64)
 
 
+# ------------------------------------------------------------------ optional PPO features
+def test_advantage_normalisation_and_grad_clipping(L):
+    """One minibatch over the whole rollout with both options on: statistics and gradient against the oracle fed
+    with its own normalised advantages; the clipped Adam step replayed exactly from the gradient the library
+    reports; a clip threshold above the norm changes nothing, bit for bit."""
+    torch = _torch()
+    cfg = configs.get_config(0, num_envs=64, horizon=16)
+    base = dict(cfg["hp"], epochs=1, minibatches=1, seed=3, norm_adv=1)
+    fr = adv = ret = None
+    results = {}
+    for name, mx in (("off", 0.0), ("loose", 1e6), ("tight", None)):
+        lrn, ro, params = _setup(L, cfg)
+        lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), base["gamma"], base["lam"])
+        if mx is None:
+            mx = 0.3 * results["off"][0]["grad_norm"]
+        st = lrn.update(dict(base, max_grad_norm=mx))[0]
+        results[name] = (st, lrn.get_grads(), lrn.get_params(), lrn.get_opt_state(), mx)
+        if fr is None:
+            fr, adv, ret = _oracle_inputs(cfg, ro, lrn)
+    st, g, p_off, _, _ = results["off"]
+    nadv = orc.normalize_adv(adv)
+    with orc.quant(1):
+        qst, qg = orc.ppo_loss_grad(cfg["net"], params, fr["obs"], fr["proprio"], fr["action"], fr["logp_old"], fr["value"], nadv, ret,
+                                    clip_eps=base["clip_eps"], vclip_eps=base["vclip_eps"], vf_coef=base["vf_coef"], ent_coef=base["ent_coef"])
+    for k_gpu, k_or in (("pi_loss", "pi_loss"), ("v_loss", "v_loss"), ("approx_kl", "approx_kl"), ("clip_frac", "clip_frac"), ("total_loss", "total")):
+        assert abs(st[k_gpu] - qst[k_or]) <= TOL_BF16 * max(abs(qst[k_or]), 1e-3), (k_gpu, st[k_gpu], qst[k_or])
+    errs = per_tensor_errors(cfg["net"], g, qg)
+    assert max(errs.values()) <= TOL_BF16, errs
+    # the raw advantages would give a different policy loss: the option is really on
+    with orc.quant(1):
+        rst, _ = orc.ppo_loss_grad(cfg["net"], params, fr["obs"], fr["proprio"], fr["action"], fr["logp_old"], fr["value"], adv, ret,
+                                   clip_eps=base["clip_eps"], vclip_eps=base["vclip_eps"], vf_coef=base["vf_coef"], ent_coef=base["ent_coef"])
+    assert abs(rst["pi_loss"] - qst["pi_loss"]) > 10 * TOL_BF16 * max(abs(qst["pi_loss"]), 1e-3)
+    # a threshold above the norm: identical to no clipping
+    np.testing.assert_array_equal(results["loose"][2], p_off)
+    # an active threshold: same gradient and reported (pre-clip) norm, Adam step of the clipped gradient
+    stt, gt, pt, (gm, gv, step, _), mx = results["tight"]
+    np.testing.assert_array_equal(gt, g)
+    assert stt["grad_norm"] == st["grad_norm"] and abs(stt["grad_norm"] - np.linalg.norm(g.astype(np.float64))) <= 1e-5 * stt["grad_norm"]
+    clipped, n = orc.clip_grad_norm(g.astype(np.float64), mx)
+    assert n > mx
+    p = params.astype(np.float64)
+    m, v = np.zeros_like(p), np.zeros_like(p)
+    orc.adam_step(p, m, v, clipped, 1, lr=base["lr"], beta1=base["beta1"], beta2=base["beta2"], eps=base["adam_eps"])
+    assert step == 1
+    assert np.abs(pt.astype(np.float64) - p).max() <= 1e-6 * max(1.0, np.abs(p).max()) + 2e-3 * base["lr"]
+    assert rel_l2(gm, m) <= 1e-5 and rel_l2(gv, v) <= 5e-5
+    assert rel_l2(gm, 0.3 * results["off"][3][0] * (st["grad_norm"] / (st["grad_norm"] + 1e-6))) <= 1e-5   # m scales with the coefficient
+
+
 # ------------------------------------------------------------------ whole update
 def _compare_update(L, cfg, lrn, ro, params, out, stats, lr):
     """Loss statistics of every optimiser step, and the parameters after the whole update.  From the second
@@ -354,12 +404,12 @@ def _compare_update(L, cfg, lrn, ro, params, out, stats, lr):
     assert cos > 0.95, cos
 
 
-@pytest.mark.parametrize("ci,N,T", [(0, 64, 16), (1, 256, 4)])
-def test_ppo_update_matches_oracle(L, ci, N, T):
+@pytest.mark.parametrize("ci,N,T,extras", [(0, 64, 16, {}), (1, 256, 4, {}), (0, 64, 16, dict(norm_adv=1, max_grad_norm=0.5))])
+def test_ppo_update_matches_oracle(L, ci, N, T, extras):
     torch = _torch()
     cfg = configs.get_config(ci, num_envs=N, horizon=T)
     lrn, ro, params = _setup(L, cfg)
-    hp = dict(cfg["hp"], seed=11)
+    hp = dict(cfg["hp"], seed=11, **extras)
     lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
     stats = lrn.update(hp)
     fr, adv, ret = _oracle_inputs(cfg, ro, lrn)
