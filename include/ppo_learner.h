@@ -118,6 +118,16 @@ int ppo_get_opt_state(ppo_ctx* ctx, float* h_m, float* h_v, int64_t n, int64_t* 
 int ppo_buffer_write(ppo_ctx* ctx, int32_t t, const void* d_obs, const float* d_proprio, const float* d_action,
                      const float* d_logp, const float* d_value, const float* d_reward, const uint8_t* d_done);
 
+/* ppo_buffer_write for the environments [env_offset, env_offset + count) of step t only; every array
+ * holds `count` rows.  This is the landing call for observations that arrive from several producers
+ * (the simulator GPUs of Fig. 2b each own a range of environments and send their slice once per
+ * step): the ranges may come in any order; step t counts as written once the ranges received for it
+ * cover [0, N), and a write into a complete step starts that step afresh.  count = 0 is a no-op;
+ * a range outside [0, N) is PPO_EINVAL. */
+int ppo_buffer_write_range(ppo_ctx* ctx, int32_t t, int32_t env_offset, int32_t count, const void* d_obs, const float* d_proprio,
+                           const float* d_action, const float* d_logp, const float* d_value, const float* d_reward,
+                           const uint8_t* d_done);
+
 /* Policy step of the collection loop (Algorithm 2: the policy maps the stacked observations of all
  * environments to actions; the record is appended once the simulators have stepped).  Stores the
  * step-t observations like ppo_buffer_write, runs the network forward on them with the current

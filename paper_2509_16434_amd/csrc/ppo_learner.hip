@@ -8,8 +8,10 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <map>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "gemm.hip.h"
@@ -85,7 +87,8 @@ struct Ctx {
   DevStats* dstats = nullptr;
   int max_steps = 4096;
   // state
-  std::vector<char> written;
+  std::vector<char> written;                               // per step: 0 incomplete, 1 complete, 2 acted (outcome missing)
+  std::vector<std::vector<std::pair<int, int>>> cover;     // per step: merged environment ranges of partial writes
   bool gae_done = false;
   int64_t step = 0, update_idx = 0;
   std::vector<void*> allocs;
@@ -1141,6 +1144,7 @@ int create_impl(Ctx* c) {
   if (rc) return rc;
   HIPCHK(c, hipStreamSynchronize(c->stream));
   c->written.assign((size_t)c->T, 0);
+  c->cover.assign((size_t)c->T, {});
   return PPO_OK;
 }
 
@@ -1248,8 +1252,8 @@ int ppo_get_opt_state(ppo_ctx* c, float* hm, float* hv, int64_t n, int64_t* step
   return PPO_OK;
 }
 
-static int write_slab(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, const float* d_action, const float* d_logp,
-                      const float* d_value, const float* d_reward, const uint8_t* d_done);
+static int write_slab(ppo_ctx* c, int32_t t, int32_t n0, int32_t cnt, const void* d_obs, const float* d_proprio, const float* d_action,
+                      const float* d_logp, const float* d_value, const float* d_reward, const uint8_t* d_done);
 
 int ppo_buffer_write(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, const float* d_action, const float* d_logp,
                      const float* d_value, const float* d_reward, const uint8_t* d_done) {
@@ -1258,10 +1262,41 @@ int ppo_buffer_write(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_pr
   if (!d_obs || !d_proprio || !d_action) return fail(c, PPO_EINVAL, "d_obs, d_proprio and d_action must not be NULL");
   if (c->d.has_value_head && (!d_logp || !d_value || !d_reward || !d_done))
     return fail(c, PPO_EINVAL, "an actor-critic buffer needs d_logp, d_value, d_reward and d_done");
-  const int rc = write_slab(c, t, d_obs, d_proprio, d_action, d_logp, d_value, d_reward, d_done);
+  const int rc = write_slab(c, t, 0, c->N, d_obs, d_proprio, d_action, d_logp, d_value, d_reward, d_done);
   if (rc) return rc;
-  if (t == 0) { c->written.assign((size_t)c->T, 0); }
+  if (t == 0) { c->written.assign((size_t)c->T, 0); c->cover.assign((size_t)c->T, {}); }
   c->written[(size_t)t] = 1;
+  c->cover[(size_t)t].clear();
+  c->gae_done = false;
+  return PPO_OK;
+}
+
+int ppo_buffer_write_range(ppo_ctx* c, int32_t t, int32_t env_offset, int32_t count, const void* d_obs, const float* d_proprio,
+                           const float* d_action, const float* d_logp, const float* d_value, const float* d_reward, const uint8_t* d_done) {
+  if (!c) return PPO_EINVAL;
+  if (t < 0 || t >= c->T) return fail(c, PPO_EINVAL, "t = %d outside [0, %d)", t, c->T);
+  if (env_offset < 0 || count < 0 || (int64_t)env_offset + count > c->N)
+    return fail(c, PPO_EINVAL, "environments [%d, %d + %d) outside [0, %d)", env_offset, env_offset, count, c->N);
+  if (count == 0) return PPO_OK;
+  if (!d_obs || !d_proprio || !d_action) return fail(c, PPO_EINVAL, "d_obs, d_proprio and d_action must not be NULL");
+  if (c->d.has_value_head && (!d_logp || !d_value || !d_reward || !d_done))
+    return fail(c, PPO_EINVAL, "an actor-critic buffer needs d_logp, d_value, d_reward and d_done");
+  const int rc = write_slab(c, t, env_offset, count, d_obs, d_proprio, d_action, d_logp, d_value, d_reward, d_done);
+  if (rc) return rc;
+  // a write into a complete step starts the step afresh; the step is complete again once the ranges cover [0, N)
+  auto& cv = c->cover[(size_t)t];
+  if (c->written[(size_t)t] == 1) cv.clear();
+  cv.push_back({env_offset, env_offset + count});
+  std::sort(cv.begin(), cv.end());
+  std::vector<std::pair<int, int>> merged;
+  for (const auto& r : cv) {
+    if (!merged.empty() && r.first <= merged.back().second) merged.back().second = std::max(merged.back().second, r.second);
+    else merged.push_back(r);
+  }
+  cv.swap(merged);
+  const bool complete = cv.size() == 1 && cv[0].first == 0 && cv[0].second == c->N;
+  c->written[(size_t)t] = complete ? 1 : 0;
+  if (complete) cv.clear();
   c->gae_done = false;
   return PPO_OK;
 }
@@ -1284,13 +1319,14 @@ static int all_written(ppo_ctx* c) {
 }
 
 // Images, proprioception and (where given) the other fields of step t into the slab: one launch.
-static int write_slab(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, const float* d_action, const float* d_logp,
-                      const float* d_value, const float* d_reward, const uint8_t* d_done) {
-  const int N = c->N, V = c->V, HW = c->d.in_h * c->d.in_w, C = c->d.in_c;
+// Environments [n0, n0 + cnt) of the step; the caller's arrays hold cnt rows.
+static int write_slab(ppo_ctx* c, int32_t t, int32_t n0, int32_t cnt, const void* d_obs, const float* d_proprio, const float* d_action,
+                      const float* d_logp, const float* d_value, const float* d_reward, const uint8_t* d_done) {
+  const int N = cnt, V = c->V, HW = c->d.in_h * c->d.in_w, C = c->d.in_c;
   const int64_t nimg = (int64_t)N * V, groups = (HW + 7) / 8;
-  bf16_t* dst = c->obs + (int64_t)t * N * V * c->img_elems;
+  const int64_t off = (int64_t)t * c->N + n0;
+  bf16_t* dst = c->obs + off * V * c->img_elems;
   ProfScope ps(c, "buffer_write", 0.0, (double)nimg * c->img_elems * (c->d.obs_dtype == 0 ? 6.0 : 4.0) + (double)N * (6.0 * c->P + 8.0 * c->A + 26.0));
-  const int64_t off = (int64_t)t * N;
   const int mx = c->P > c->A ? c->P : c->A;
   ScalarWrite sw;
   sw.N = N; sw.P = c->P; sw.A = c->A; sw.proprio = d_proprio; sw.action = d_action; sw.logp = d_logp; sw.value = d_value; sw.reward = d_reward; sw.done = d_done;
@@ -1392,10 +1428,11 @@ int ppo_act(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, co
   if (!c->d.has_value_head) return fail(c, PPO_ESTATE, "ppo_act needs an actor-critic context (has_value_head = 1)");
   if (t < 0 || t >= c->T) return fail(c, PPO_EINVAL, "t = %d outside [0, %d)", t, c->T);
   if (!d_obs || !d_proprio || !d_noise) return fail(c, PPO_EINVAL, "d_obs, d_proprio and d_noise must not be NULL");
-  int rc = write_slab(c, t, d_obs, d_proprio, nullptr, nullptr, nullptr, nullptr, nullptr);
+  int rc = write_slab(c, t, 0, c->N, d_obs, d_proprio, nullptr, nullptr, nullptr, nullptr, nullptr);
   if (rc) return rc;
-  if (t == 0) { c->written.assign((size_t)c->T, 0); }
+  if (t == 0) { c->written.assign((size_t)c->T, 0); c->cover.assign((size_t)c->T, {}); }
   c->written[(size_t)t] = 2;
+  c->cover[(size_t)t].clear();
   c->gae_done = false;
   const int64_t first = (int64_t)t * c->N;
   for (int64_t c0 = 0; c0 < c->N; c0 += c->CH) {

@@ -68,6 +68,7 @@ def load_library():
         "ppo_set_opt_state": (C.c_int, [vp, fp, fp, i64, i64, i64]),
         "ppo_get_opt_state": (C.c_int, [vp, fp, fp, i64, C.POINTER(i64), C.POINTER(i64)]),
         "ppo_buffer_write": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp, vp]),
+        "ppo_buffer_write_range": (C.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
         "ppo_act": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp]),
         "ppo_buffer_write_outcome": (C.c_int, [vp, i32, vp, vp]),
         "ppo_buffer_read_obs": (C.c_int, [vp, i32, vp]),
@@ -90,7 +91,7 @@ def load_library():
 _lib = load_library()
 EXPORTS = ("ppo_create", "ppo_destroy", "ppo_last_error", "ppo_param_count", "ppo_buffer_image_bytes",
            "ppo_set_params", "ppo_get_params", "ppo_get_grads", "ppo_set_opt_state", "ppo_get_opt_state",
-           "ppo_buffer_write", "ppo_act", "ppo_buffer_write_outcome", "ppo_buffer_read_obs", "ppo_gae", "ppo_get_adv_ret", "ppo_permutation", "ppo_update", "distill_update",
+           "ppo_buffer_write", "ppo_buffer_write_range", "ppo_act", "ppo_buffer_write_outcome", "ppo_buffer_read_obs", "ppo_gae", "ppo_get_adv_ret", "ppo_permutation", "ppo_update", "distill_update",
            "ppo_forward", "ppo_profile", "ppo_profile_report", "ppo_diag_gemm")
 
 
@@ -226,6 +227,17 @@ class Learner:
             self._h, t, _dev(obs, odt, n_obs), _dev(proprio, torch.float32, self.N * net["proprio_dim"]),
             _dev(action, torch.float32, self.N * net["act_dim"]), _dev(logp, torch.float32, self.N),
             _dev(value, torch.float32, self.N), _dev(reward, torch.float32, self.N), _dev(done, torch.uint8, self.N)))
+
+    def buffer_write_range(self, t, env_offset, obs, proprio, action, logp=None, value=None, reward=None, done=None):
+        """Rows [env_offset, env_offset + len(proprio)) of step t."""
+        torch, net = self._torch, self.net
+        cnt = int(proprio.shape[0])
+        n_obs = cnt * net.get("n_views", 1) * net["in_c"] * net["in_h"] * net["in_w"]
+        odt = torch.float32 if self.obs_dtype == "fp32" else torch.bfloat16
+        self._chk(_lib.ppo_buffer_write_range(
+            self._h, t, env_offset, cnt, _dev(obs, odt, n_obs), _dev(proprio, torch.float32, cnt * net["proprio_dim"]),
+            _dev(action, torch.float32, cnt * net["act_dim"]), _dev(logp, torch.float32, cnt),
+            _dev(value, torch.float32, cnt), _dev(reward, torch.float32, cnt), _dev(done, torch.uint8, cnt)))
 
     def act(self, t, obs, proprio, noise):
         """Policy step on the step-t observations -> (action [N][A], logp [N], value [N]) device tensors."""

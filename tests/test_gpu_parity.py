@@ -78,6 +78,45 @@ def test_buffer_write_odd_image_size(L):
     np.testing.assert_array_equal(got, want)
 
 
+def test_buffer_write_by_environment_ranges(L):
+    """Slabs filled by several producers (ragged, out-of-order environment ranges) hold exactly what one full
+    write leaves: stored images bit for bit, and a whole update from them bit-identical parameters."""
+    torch = _torch()
+    cfg = configs.get_config(0, num_envs=50, horizon=4)
+    cfg["net"].update(in_h=9, in_w=11)      # 99-element images: slices start at odd element offsets
+    hp = dict(cfg["hp"], epochs=1, minibatches=2, seed=5)
+    full, ro, params = _setup(L, cfg)
+    part = L.Learner(cfg["net"], 50, 4, cfg["obs_dtype"])
+    part.set_params(params)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    bounds = [(37, 50), (0, 1), (8, 37), (1, 8)]
+    lv = dev(ro["last_value"])
+    for t in range(4):
+        for i, (a, b) in enumerate(bounds):
+            if i == len(bounds) - 1:    # one range still missing: the rollout is not complete
+                with pytest.raises(L.LearnerError) as e:
+                    part.gae(lv, hp["gamma"], hp["lam"])
+                assert e.value.code == L.PPO_ESTATE
+            part.buffer_write_range(t, a, dev(ro["obs"][t][a:b]), *[dev(ro[k][t][a:b]) for k in
+                                    ("proprio", "action", "logp_old", "value", "reward", "done")])
+    for t in range(4):
+        assert torch.equal(part.buffer_read_obs(t), full.buffer_read_obs(t))
+    for x in (full, part):
+        x.gae(lv, hp["gamma"], hp["lam"])
+        x.update(hp)
+    np.testing.assert_array_equal(part.get_params(), full.get_params())
+    with pytest.raises(L.LearnerError) as e:
+        part.buffer_write_range(0, 40, dev(ro["obs"][0][:11]), *[dev(ro[k][0][:11]) for k in
+                                ("proprio", "action", "logp_old", "value", "reward", "done")])
+    assert e.value.code == L.PPO_EINVAL
+    # a partial write into a complete step makes it incomplete again
+    part.buffer_write_range(2, 0, dev(ro["obs"][2][:5]), *[dev(ro[k][2][:5]) for k in
+                            ("proprio", "action", "logp_old", "value", "reward", "done")])
+    with pytest.raises(L.LearnerError) as e:
+        part.gae(lv, hp["gamma"], hp["lam"])
+    assert e.value.code == L.PPO_ESTATE
+
+
 # ------------------------------------------------------------------ GAE
 @pytest.mark.parametrize("N,T", [(64, 16), (1000, 16), (16384, 32), (1, 1), (3, 7)])
 def test_gae_matches_oracle(L, N, T):
