@@ -1,11 +1,13 @@
-"""Workload registry: the five benchmark configurations as plain data.
+"""Workload registry: the five benchmark configurations, and the paper's second resolution, as plain data.
 
 Holds no arithmetic of the method; both the HIP binding and the test oracle
 read their network geometry and hyper-parameters from here.  Index = position
 in the benchmark's config list (0 tiny, 1 medium, 2 full, 3 stereo
 distillation, 4 large batch).  Horizon 16 and the 7+16 = 23-d action space
 follow the paper (Sec. III-B sizing example; Sec. III-C robot description);
-resolution 160x120 is the paper's Table I row 1.
+resolution 160x120 is the paper's Table I row 1.  Index 5 is Table I row 2: 320x240 depth at the
+2100 environments the disaggregated set-up reaches there, with the network and hyper-parameters of
+the full configuration.
 """
 from __future__ import annotations
 
@@ -37,6 +39,9 @@ CONFIGS = [
     dict(name="c4_large", kind="ppo", num_envs=16384, horizon=32, obs_dtype="bf16", seed=1238,
          net=_net(1, 1, 120, 160, 64, 23, (32, 64, 64, 128), (512, 256, 128)),
          hp=dict(_PPO_HP, epochs=5, minibatches=8, ent_coef=0.01, vclip_eps=0.2)),
+    dict(name="c5_hires", kind="ppo", num_envs=2100, horizon=16, obs_dtype="bf16", seed=1239,
+         net=_net(1, 1, 240, 320, 64, 23, (32, 64, 64, 128), (512, 256, 128)),
+         hp=dict(_PPO_HP, epochs=5, minibatches=4, ent_coef=0.01, vclip_eps=0.2)),
 ]
 
 

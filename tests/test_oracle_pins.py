@@ -507,7 +507,7 @@ def test_update_loop_against_library_recomposition(extras):
 
 
 def test_param_counts_of_the_workloads():
-    want = [69_753, 1_156_975, 5_573_103, 10_786_455, 5_573_103]
+    want = [69_753, 1_156_975, 5_573_103, 10_786_455, 5_573_103, 19_991_023]   # hand count per layer
     for c, w in zip(configs.CONFIGS, want):
         assert orc.param_count(c["net"]) == w == configs.param_count(c["net"])
         assert sum(int(np.prod(s)) for _, s, _ in synth.param_layout(c["net"])) == w
