@@ -4,8 +4,9 @@
 // per 32 pixels, and the vector-memory instruction rate of a wave, not bandwidth, sets the pace.
 // Here one loader wave copies each band's image rows (a few KiB, 1 KiB per load) into an LDS ring
 // with LDS-writing 16-byte loads, seven compute waves take the band's pixels in groups of 32 (lane =
-// pixel), gather the window from LDS with 2-byte reads, apply the weights with one or two MFMAs
-// (K = 9*C0 padded to 16 or 32), add bias, clamp, round to bf16, stage the 32 pixels in a private
+// pixel), gather the window from LDS (one channel: two dwords per window row; three: 2-byte reads), apply
+// the weights with one or two MFMAs (K = 9*C0 padded to 16 or 32) whose accumulator starts at the
+// bias, round to bf16, clamp, stage the 32 pixels in a private
 // LDS strip and write them as 16-byte segments of the band's contiguous output span.  The images
 // are addressed through the minibatch's gather list.
 #pragma once
@@ -20,6 +21,7 @@ struct Conv0Args {
   uint32_t* bits;             // optional sign-bit words of the output (layout as in ConvTileArgs)
   int H, W, Ho, Wo, Cout;
   int TR, NB, ntiles;         // output rows per band, bands per image, nimg * NB
+  FastDiv dv_wo;              // division by Wo
 };
 
 template <int C0>
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
   const int NJ = (Cout + 31) / 32;
   // weights (MFMA first operand: row co = jn*32 + l32, 8 k at ks*16 + h*8) and bias per accumulator element
   bf16x8_t bw[2][KS];
-  float bs[2][16];
+  f32x16_t bs[2];
 #pragma unroll
   for (int jn = 0; jn < 2; ++jn) {
     const int co = jn * 32 + l32;
@@ -96,6 +98,8 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
   }
   const int npix = TR * Wo, ngroups = (npix + 31) >> 5;
   const int cpr = Cout >> 3;  // 16-byte chunks per pixel
+  const int cshift = (cpr & (cpr - 1)) == 0 ? 31 - __builtin_clz(cpr) : -1;  // log2 of it when it is a power of two
+  const FastDiv dv_wo = a.dv_wo;
 
   for (int q = 0; q < nq; ++q) {
     const int t = blockIdx.x + q * gridDim.x;
@@ -106,45 +110,60 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
     const char* im = lds + (q % NBUF) * image_bytes;
     for (int gi = wave; gi < ngroups; gi += NCW) {
       const int p = gi * 32 + l32, pc = p < npix ? p : 0;
-      const int oyl = pc / Wo, ox = pc - oyl * Wo;
-      const char* pb = im + (2 * oyl) * RB + (2 * ox - 1) * C0 * 2;  // window corner (column -1 for ox = 0)
-      const bool cok[3] = {ox > 0, true, 2 * ox + 1 < W};
+      const int oyl = (int)dv_wo.div((uint32_t)pc), ox = pc - oyl * Wo;
       bf16x8_t av[KS];
+      if constexpr (C0 == 1) {
+        // three rows of the window as two dwords each: columns (2x-2, 2x-1) and (2x, 2x+1); W is even here (rows are
+        // multiples of 16 bytes), so only the left edge needs a mask.  k = 3*u + v: half 0 takes taps 0..7, half 1 tap 8.
+        const char* rowp = im + (2 * oyl) * RB + 4 * ox;
+        const uint32_t lm = ox > 0 ? 0xffffffffu : 0u;
+        uint32_t d0[3], d1[3];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        uint32_t x4[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          // the two halves' k are compile-time; pick by h
-          const int k0 = ks * 16 + j, k1 = ks * 16 + 8 + j;
-          const int t0 = k0 / C0, c0 = k0 - t0 * C0, u0 = t0 / 3, v0 = t0 - 3 * u0;
-          const int t1 = k1 / C0, c1 = k1 - t1 * C0, u1 = t1 / 3, v1 = t1 - 3 * u1;
-          const bool in0 = k0 < K, in1 = k1 < K;
-          const bool ok = h ? (in1 && cok[in1 ? v1 : 1]) : (in0 && cok[in0 ? v0 : 1]);
-          const int off = h ? (in1 ? u1 * RB + (v1 * C0 + c1) * 2 : 0) : (in0 ? u0 * RB + (v0 * C0 + c0) * 2 : 0);
-          const char* src = ok ? pb + off : zero16;
-          x4[j >> 1] |= (uint32_t)*reinterpret_cast<const unsigned short*>(src) << (16 * (j & 1));
+        for (int u = 0; u < 3; ++u) {
+          d1[u] = *reinterpret_cast<const uint32_t*>(rowp + u * RB);
+          d0[u] = *reinterpret_cast<const uint32_t*>(rowp + u * RB + (ox > 0 ? -4 : 0)) & lm;
         }
-        av[ks] = __builtin_bit_cast(bf16x8_t, make_uint4(x4[0], x4[1], x4[2], x4[3]));
+        const uint32_t w0 = __builtin_amdgcn_alignbit(d1[0], d0[0], 16);       // (row 0: col -1, col 0)
+        const uint32_t w1 = __builtin_amdgcn_perm(d0[1], d1[0], 0x07060302u);  // (row 0: col +1, row 1: col -1)
+        const uint32_t w3 = __builtin_amdgcn_alignbit(d1[2], d0[2], 16);       // (row 2: col -1, col 0)
+        av[0] = __builtin_bit_cast(bf16x8_t, h ? make_uint4(d1[2] >> 16, 0u, 0u, 0u) : make_uint4(w0, w1, d1[1], w3));
+      } else {
+        const char* pb = im + (2 * oyl) * RB + (2 * ox - 1) * C0 * 2;  // window corner (column -1 for ox = 0)
+        const bool cok[3] = {ox > 0, true, 2 * ox + 1 < W};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          uint32_t x4[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            // the two halves' k are compile-time; pick by h
+            const int k0 = ks * 16 + j, k1 = ks * 16 + 8 + j;
+            const int t0 = k0 / C0, c0 = k0 - t0 * C0, u0 = t0 / 3, v0 = t0 - 3 * u0;
+            const int t1 = k1 / C0, c1 = k1 - t1 * C0, u1 = t1 / 3, v1 = t1 - 3 * u1;
+            const bool in0 = k0 < K, in1 = k1 < K;
+            const bool ok = h ? (in1 && cok[in1 ? v1 : 1]) : (in0 && cok[in0 ? v0 : 1]);
+            const int off = h ? (in1 ? u1 * RB + (v1 * C0 + c1) * 2 : 0) : (in0 ? u0 * RB + (v0 * C0 + c0) * 2 : 0);
+            const char* src = ok ? pb + off : zero16;
+            x4[j >> 1] |= (uint32_t)*reinterpret_cast<const unsigned short*>(src) << (16 * (j & 1));
+          }
+          av[ks] = __builtin_bit_cast(bf16x8_t, make_uint4(x4[0], x4[1], x4[2], x4[3]));
+        }
       }
       uint32_t pw[2] = {0u, 0u};
 #pragma unroll
       for (int jn = 0; jn < 2; ++jn) {
         if (jn < NJ) {
-          f32x16_t acc;
+          f32x16_t acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw[jn][0], av[0], bs[jn], 0, 0, 0);  // the bias enters as the accumulator
 #pragma unroll
-          for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw[jn][ks], av[ks], acc, 0, 0, 0);
+          for (int ks = 1; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw[jn][ks], av[ks], acc, 0, 0, 0);
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             const int cl = jn * 32 + g * 8 + h * 4;
             if (cl < Cout) {
               uint2 o;
-              o.x = pack2bf(fmaxf(acc[g * 4] + bs[jn][g * 4], 0.f), fmaxf(acc[g * 4 + 1] + bs[jn][g * 4 + 1], 0.f));
-              o.y = pack2bf(fmaxf(acc[g * 4 + 2] + bs[jn][g * 4 + 2], 0.f), fmaxf(acc[g * 4 + 3] + bs[jn][g * 4 + 3], 0.f));
+              o.x = relu_pack2bf(acc[g * 4], acc[g * 4 + 1]);
+              o.y = relu_pack2bf(acc[g * 4 + 2], acc[g * 4 + 3]);
               *reinterpret_cast<uint2*>(&stage[l32 * SP + cl]) = o;
-              pw[jn] |= nonzero4(o.x, o.y) << (g * 8 + h * 4);
+              pw[jn] |= (nonzero2(o.x) | (nonzero2(o.y) << 2)) << (g * 8 + h * 4);
             }
           }
         }
@@ -160,7 +179,7 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
       }
       // the group's 32 pixels are contiguous in the output: 16-byte segments, lane after lane
       for (int ch = lane; ch < 32 * cpr; ch += 64) {
-        const int r = ch / cpr, cg = ch - r * cpr;
+        const int r = cshift >= 0 ? ch >> cshift : ch / cpr, cg = ch - r * cpr;
         if (gi * 32 + r < plim)
           *reinterpret_cast<uint4*>(dst + (int64_t)(gi * 32 + r) * Cout + cg * 8) = *reinterpret_cast<const uint4*>(&stage[r * SP + cg * 8]);
       }

@@ -43,6 +43,21 @@ __device__ __forceinline__ uint32_t nonzero4(uint32_t lo, uint32_t hi) {
   return ((lo & 0xffffu) ? 1u : 0u) | ((lo >> 16) ? 2u : 0u) | ((hi & 0xffffu) ? 4u : 0u) | ((hi >> 16) ? 8u : 0u);
 }
 
+// bf16 pair of (max(lo, 0), max(hi, 0)): rounded first, then clamped as 16-bit integers (a negative bf16 is a
+// negative int16, and rounding keeps the sign, so the order of rounding and clamping does not matter)
+__device__ __forceinline__ uint32_t relu_pack2bf(float lo, float hi) {
+  typedef short s16x2_t __attribute__((ext_vector_type(2)));
+  const s16x2_t z = {0, 0};
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2_t, pack2bf(lo, hi)), z));
+}
+// bit 0: low half of x non-zero, bit 1: high half non-zero
+__device__ __forceinline__ uint32_t nonzero2(uint32_t x) {
+  typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
+  const u16x2_t one = {1, 1};
+  const uint32_t t = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2_t, x), one));
+  return (t | (t >> 15)) & 3u;
+}
+
 template <int CIN>
 struct ConvTileShape {
   static constexpr int NW = (CIN == 32) ? 64 : 32;   // output columns per wave (18432 weights per wave)

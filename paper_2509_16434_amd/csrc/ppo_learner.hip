@@ -711,6 +711,7 @@ int launch_conv0_fwd_tile_t(Ctx* c, Conv0Args a, int nimg) {
     if (cdiv((2 * tr + 1) * rb, 1024) <= 63 && tr * a.Wo <= 1024 && S::lds_bytes(a.W, tr, a.Cout) <= 64 * 1024) { TR = tr; break; }
   if (TR == 0) return 1;
   a.NB = cdiv(a.Ho, TR); a.TR = cdiv(a.Ho, a.NB); a.ntiles = nimg * a.NB;
+  a.dv_wo = make_fastdiv(a.Wo);
   int gx = a.ntiles < 512 ? a.ntiles : 512;
   auto kfn = k_conv0_fwd_tile<C0>;
   static bool attr_set = false;
