@@ -38,11 +38,6 @@ struct ConvTileArgs {
   int TR, NB, ntiles;         // output rows per band, bands per image, nimg * NB
 };
 
-// bits of the four bf16 packed in (lo, hi) that are non-zero (the values are >= +0 after the clamp)
-__device__ __forceinline__ uint32_t nonzero4(uint32_t lo, uint32_t hi) {
-  return ((lo & 0xffffu) ? 1u : 0u) | ((lo >> 16) ? 2u : 0u) | ((hi & 0xffffu) ? 4u : 0u) | ((hi >> 16) ? 8u : 0u);
-}
-
 // bf16 pair of (max(lo, 0), max(hi, 0)): rounded first, then clamped as 16-bit integers (a negative bf16 is a
 // negative int16, and rounding keeps the sign, so the order of rounding and clamping does not matter)
 __device__ __forceinline__ uint32_t relu_pack2bf(float lo, float hi) {
@@ -177,11 +172,14 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
     __builtin_amdgcn_s_barrier();  // band q is in LDS
     const char* img_s = lds + (q % NBUF) * image_bytes;
 
-    f32x16_t acc[TN];
+    f32x16_t acc[TN];  // starts at the bias of the lane's columns j*32 + g*8 + h*4 + 0..3
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+      for (int g = 0; g < 4; ++g) {
+        const float4 bv = *reinterpret_cast<const float4*>(bias_s + wn * NW + j * 32 + g * 8 + h * 4);
+        acc[j][g * 4] = bv.x; acc[j][g * 4 + 1] = bv.y; acc[j][g * 4 + 2] = bv.z; acc[j][g * 4 + 3] = bv.w;
+      }
 #pragma unroll
     for (int u = 0; u < 3; ++u)
 #pragma unroll
@@ -195,7 +193,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
           for (int j = 0; j < TN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[(u * 3 + v) * KC + cc][j], av, acc[j], 0, 0, 0);
         }
       }
-    // ---- epilogue: bias, ReLU, bf16; lane holds pixel l32 of the wave, columns j*32 + g*8 + h*4 + 0..3
+    // ---- epilogue: bf16, ReLU; lane holds pixel l32 of the wave, columns j*32 + g*8 + h*4 + 0..3
     uint32_t pw[TN];  // this lane's 16 sign bits of the pixel's 32-column group j
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -203,12 +201,11 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int cl = j * 32 + g * 8 + h * 4;
-        const float4 bv = *reinterpret_cast<const float4*>(bias_s + wn * NW + cl);
         uint2 o;
-        o.x = pack2bf(fmaxf(acc[j][g * 4] + bv.x, 0.f), fmaxf(acc[j][g * 4 + 1] + bv.y, 0.f));
-        o.y = pack2bf(fmaxf(acc[j][g * 4 + 2] + bv.z, 0.f), fmaxf(acc[j][g * 4 + 3] + bv.w, 0.f));
+        o.x = relu_pack2bf(acc[j][g * 4], acc[j][g * 4 + 1]);
+        o.y = relu_pack2bf(acc[j][g * 4 + 2], acc[j][g * 4 + 3]);
         *reinterpret_cast<uint2*>(stage + (l32 * SP + cl) * 2) = o;
-        pw[j] |= nonzero4(o.x, o.y) << (g * 8 + h * 4);
+        pw[j] |= (nonzero2(o.x) | (nonzero2(o.y) << 2)) << (g * 8 + h * 4);
       }
     }
     {
