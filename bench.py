@@ -39,12 +39,12 @@ RIDGE_FLOP_PER_BYTE = PEAK_MFMA_BF16_TF * 1e12 / (PEAK_HBM_GBS * 1e9)  # 312.5
 # same run: x1.99 and x1.00).  The runs, the raw counter values and the commands are in
 # profiles/c1_medium_hbm_traffic.md; a kernel class or workload that was not measured reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("c1_medium", "conv_wgrad.1"): 427.5e6,
-    ("c1_medium", "conv_fwd.1"): 418.1e6,
+    ("c1_medium", "conv_wgrad.1"): 427.4e6,
+    ("c1_medium", "conv_fwd.1"): 418.0e6,
     ("c1_medium", "conv_fwd.0"): 319.0e6,
-    ("c1_medium", "conv_dgrad.1+wgrad.0"): 184.5e6,
+    ("c1_medium", "conv_dgrad.1+wgrad.0"): 184.4e6,
     ("c1_medium", "conv_dgrad.2"): 176.8e6,
-    ("c1_medium", "conv_wgrad.2"): 204.8e6,
+    ("c1_medium", "conv_wgrad.2"): 204.7e6,
     ("c1_medium", "conv_fwd.2"): 167.6e6,
 }
 
