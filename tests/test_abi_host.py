@@ -1,0 +1,86 @@
+"""The C-ABI library on a host without a GPU: it loads, exports every function the header declares, and its
+argument validation (which runs before any HIP call) returns the documented codes.  No compute calls."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2509_16434_amd import configs, learner as L
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ppo_learner.h")
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"^(?:int|int64_t|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
+
+
+def test_library_exports_every_declared_function():
+    names = _declared()
+    assert len(names) >= 20 and len(set(names)) == len(names)
+    lib = C.CDLL(L.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    # the binding marshals exactly the declared functions
+    assert sorted(L.EXPORTS) == sorted(names)
+
+
+def test_the_four_path_entry_points_are_declared():
+    names = set(_declared())
+    assert {"ppo_buffer_write", "ppo_gae", "ppo_update", "distill_update"} <= names
+
+
+def test_header_is_plain_c():
+    text = open(HEADER).read()
+    assert 'extern "C"' in text and "torch" not in text and "std::" not in text
+
+
+@pytest.mark.parametrize("change,code", [
+    (dict(conv_k=5), L.PPO_ESHAPE), (dict(conv_stride=1), L.PPO_ESHAPE), (dict(conv_pad=0), L.PPO_ESHAPE),
+    (dict(proprio_dim=3), L.PPO_ESHAPE), (dict(act_dim=40), L.PPO_ESHAPE), (dict(act_dim=0), L.PPO_ESHAPE),
+    (dict(fc_dim=[12]), L.PPO_ESHAPE), (dict(fc_dim=[]), L.PPO_ESHAPE), (dict(conv_ch=[12]), L.PPO_ESHAPE),
+    (dict(in_h=0), L.PPO_ESHAPE), (dict(has_value_head=2), L.PPO_EINVAL),
+])
+def test_create_rejects_bad_geometry_before_touching_the_gpu(change, code):
+    net = dict(configs.get_config(0)["net"], **change)
+    with pytest.raises(L.LearnerError) as e:
+        L.Learner(net, 8, 2, "fp32")
+    assert e.value.code == code, str(e.value)
+    assert len(str(e.value)) > 10
+
+
+def test_create_rejects_bad_sizes():
+    net = configs.get_config(0)["net"]
+    for n, t in ((0, 2), (8, 0), (-1, 2)):
+        with pytest.raises(L.LearnerError) as e:
+            L.Learner(net, n, t, "fp32")
+        assert e.value.code in (L.PPO_ESHAPE, L.PPO_EINVAL)
+    with pytest.raises(L.LearnerError) as e:
+        L.Learner(net, 8, 2, "fp32", max_chunk=-5)
+    assert e.value.code == L.PPO_EINVAL
+
+
+def test_null_handles_are_einval_not_a_crash():
+    lib = L._lib
+    assert lib.ppo_create(None, None, None) == L.PPO_EINVAL
+    assert lib.ppo_destroy(None) == L.PPO_EINVAL
+    assert lib.ppo_gae(None, None, C.c_float(0.9), C.c_float(0.9)) == L.PPO_EINVAL
+    assert lib.ppo_update(None, None, None) == L.PPO_EINVAL
+    assert lib.distill_update(None, None, None) == L.PPO_EINVAL
+    assert lib.ppo_buffer_write(None, 0, None, None, None, None, None, None, None) == L.PPO_EINVAL
+    assert lib.ppo_buffer_write_range(None, 0, 0, 1, None, None, None, None, None, None, None) == L.PPO_EINVAL
+    assert lib.ppo_act(None, 0, None, None, None, None, None, None) == L.PPO_EINVAL
+    assert lib.ppo_buffer_write_outcome(None, 0, None, None) == L.PPO_EINVAL
+    assert lib.ppo_param_count(None) < 0
+    assert lib.ppo_diag_gemm(4, 4, 7, None, None, None) == L.PPO_EINVAL
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        L._dev(torch.zeros(4))
+    with pytest.raises(ValueError):
+        L._dev(torch.zeros(4, device="meta") if False else torch.zeros(2, 2).t())
