@@ -235,6 +235,27 @@ def test_act_matches_oracle_and_fills_the_buffer(L, ci, N, T):
         assert abs(st[0]["pi_loss"] + oadv.reshape(-1)[perm].mean()) <= 1e-4 * max(1.0, np.abs(oadv).max())
 
 
+def test_act_in_chunks_equals_one_pass(L):
+    """More environments than the chunk of the forward workspaces: the chunk loop of ppo_act gives the same
+    actions, log-probs and values, bit for bit, as one pass."""
+    torch = _torch()
+    cfg = configs.get_config(1, num_envs=150, horizon=1)
+    ro = synth.rollout(cfg)
+    params = synth.init_params(cfg["net"], cfg["seed"])
+    obs = torch.from_numpy(ro["obs"][0]).cuda().to(torch.bfloat16).contiguous()
+    pr = torch.from_numpy(ro["proprio"][0]).cuda().contiguous()
+    noise = torch.randn(150, cfg["net"]["act_dim"], device="cuda", generator=torch.Generator(device="cuda").manual_seed(3))
+    outs = []
+    for chunk in (0, 64):
+        lrn = L.Learner(cfg["net"], 150, 1, cfg["obs_dtype"], max_chunk=chunk)
+        lrn.set_params(params)
+        a, lp, v = lrn.act(0, obs, pr, noise)
+        lrn.synchronize()
+        outs.append((a.cpu().numpy(), lp.cpu().numpy(), v.cpu().numpy()))
+    for x, y in zip(*outs):
+        np.testing.assert_array_equal(x, y)
+
+
 def test_act_call_order_errors(L):
     torch = _torch()
     cfg = configs.get_config(0, num_envs=8, horizon=2)
