@@ -37,7 +37,8 @@ RIDGE_FLOP_PER_BYTE = PEAK_MFMA_BF16_TF * 1e12 / (PEAK_HBM_GBS * 1e9)  # 312.5
 # HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE and WRITE_SIZE in two runs of this
 # script, each scaled by what the same counter reads for the plain copy kernel of ppo_buffer_write in the
 # same run: x1.99 and x1.00).  The runs, the raw counter values and the commands are in
-# profiles/c1_medium_hbm_traffic.md; a kernel class or workload that was not measured reports null.
+# profiles/c1_medium_hbm_traffic.md and profiles/c2_full_hbm_traffic.md; a kernel class or workload that was not
+# measured reports null.
 MEASURED_TRAFFIC_BYTES = {
     ("c1_medium", "conv_wgrad.1"): 427.4e6,
     ("c1_medium", "conv_fwd.1"): 418.0e6,
@@ -46,6 +47,11 @@ MEASURED_TRAFFIC_BYTES = {
     ("c1_medium", "conv_dgrad.2"): 176.8e6,
     ("c1_medium", "conv_wgrad.2"): 204.7e6,
     ("c1_medium", "conv_fwd.2"): 167.6e6,
+    ("c2_full", "conv_fwd.1"): 8460.3e6,
+    ("c2_full", "conv_wgrad.1"): 8320.7e6,
+    ("c2_full", "conv_fwd.0"): 6003.6e6,
+    ("c2_full", "conv_dgrad.1+wgrad.0"): 3821.4e6,
+    ("c2_full", "conv_dgrad.2"): 3471.3e6,
 }
 
 
