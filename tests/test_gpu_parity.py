@@ -492,9 +492,12 @@ def _stereo_cfg(N, T):
     return cfg
 
 
-@pytest.mark.parametrize("chunk", [0, 200])
-def test_distill_single_minibatch_gradients(L, chunk):
+# act_dim 26 = 23 action components + a 3-d auxiliary target (the deployed student's object-position output, Sec. IV-C):
+# more outputs of the same linear head under the same mean-squared error
+@pytest.mark.parametrize("chunk,act_dim", [(0, 23), (200, 23), (0, 26)])
+def test_distill_single_minibatch_gradients(L, chunk, act_dim):
     cfg = _stereo_cfg(128, 4)
+    cfg["net"]["act_dim"] = act_dim
     lrn, ro, params = _setup(L, cfg, max_chunk=chunk)
     hp = dict(cfg["hp"], minibatches=1, seed=5)
     st = lrn.distill_update(hp)[0]
