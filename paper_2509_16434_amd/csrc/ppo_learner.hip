@@ -738,12 +738,13 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true) {
     int trc = c->cC[0] == 1 ? launch_conv0_fwd_tile_t<1>(c, ca, nimg) : (c->cC[0] == 3 ? launch_conv0_fwd_tile_t<3>(c, ca, nimg) : 1);
     if (trc != PPO_OK && trc != 1) return trc;
     c->abits_ok[0] = trc == PPO_OK && c->nconv > 1;
-    if (trc == PPO_OK) {}
-    else if (c->cC[0] == 1)
-      hipLaunchKernelGGL((k_conv1_fwd<1, TPW>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->shadow + c->convW[0], c->p + c->convB[0], c->act[0]);
-    else
-      hipLaunchKernelGGL((k_conv1_fwd<3, TPW>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->shadow + c->convW[0], c->p + c->convB[0], c->act[0]);
-    LAUNCHCHK(c, "k_conv1_fwd");
+    if (trc != PPO_OK) {  // shapes the LDS-ring kernel does not cover
+      if (c->cC[0] == 1)
+        hipLaunchKernelGGL((k_conv1_fwd<1, TPW>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->shadow + c->convW[0], c->p + c->convB[0], c->act[0]);
+      else
+        hipLaunchKernelGGL((k_conv1_fwd<3, TPW>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->shadow + c->convW[0], c->p + c->convB[0], c->act[0]);
+      LAUNCHCHK(c, "k_conv1_fwd");
+    }
   }
   for (int l = 1; l < c->nconv; ++l) {
     AConvFwd al;
