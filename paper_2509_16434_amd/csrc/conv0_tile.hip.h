@@ -181,7 +181,7 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
       for (int ch = lane; ch < 32 * cpr; ch += 64) {
         const int r = cshift >= 0 ? ch >> cshift : ch / cpr, cg = ch - r * cpr;
         if (gi * 32 + r < plim)
-          *reinterpret_cast<uint4*>(dst + (int64_t)(gi * 32 + r) * Cout + cg * 8) = *reinterpret_cast<const uint4*>(&stage[r * SP + cg * 8]);
+          store_stream16(dst + (int64_t)(gi * 32 + r) * Cout + cg * 8, *reinterpret_cast<const uint4*>(&stage[r * SP + cg * 8]));
       }
     }
   }

@@ -261,7 +261,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
           else {
             uint32_t off = L;
             asm volatile("" : "+v"(off));
-            *reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.dx + band_off[SET]) + off) = v;
+            store_stream16(reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(a.dx + band_off[SET]) + off), v);
           }
         }
       }
