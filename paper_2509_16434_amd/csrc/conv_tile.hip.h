@@ -88,7 +88,8 @@ __device__ __forceinline__ uint32_t tile_swz_bits(uint32_t off) {
   return (((t & 1u) << 2) | (t >> 1)) << 4;              // rotated, so neighbours differ in the top bit
 }
 
-template <int CIN>
+// AUX: cache policy of the band loads (LOAD_NT where a band shares few rows with its neighbours)
+template <int CIN, int AUX>
 __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
   typedef ConvTileShape<CIN> S;
   constexpr int NW = S::NW, WGN = S::WGN, TN = NW / 32, PIX = S::PIX, SP = S::SP, NBUF = S::NBUF;
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
         for (int sg = 0; sg < S::MAXSEG; ++sg)
           if (sg < segs) {
             const char* p = inside ? src + (int64_t)row * rowbytes + goff[sg] : reinterpret_cast<const char*>(a.zpage) + lane * 16;
-            if (goff[sg] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + row * WP * PIX + sg * 1024), 16, 0, 0);
+            if (goff[sg] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + row * WP * PIX + sg * 1024), 16, 0, AUX);
           }
       }
     };
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
         for (int sg = 0; sg < S::MAXSEG; ++sg)
           if (sg < segs) {
             const char* p = inside ? xsrc + (int64_t)row * rowbytes + xgoff[sg] : zp;
-            if (xgoff[sg] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(buf + row * WP * PIX + PIX + sg * 1024), 16, 0, 0);
+            if (xgoff[sg] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(buf + row * WP * PIX + PIX + sg * 1024), 16, 0, LOAD_NT);
           }
       }
       for (int j = lw; j < nstep * 2; j += 4) {  // 1 KiB = 8 pixels of 128 bytes
@@ -341,7 +342,7 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
         const int p_ = (int)(logi >> 7), cb = (int)(logi & 127u);
         const bool ok = p_ < plim && nb0 + (cb >> 1) < a.Cout;
         const char* p = ok ? reinterpret_cast<const char*>(dsrc + (int64_t)p_ * a.Cout) + cb : zp;
-        __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(buf + image_bytes + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(buf + image_bytes + j * 1024), 16, 0, LOAD_NT);
       }
     };
     if (nq > 0) issue(0);

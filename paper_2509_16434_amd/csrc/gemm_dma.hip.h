@@ -15,6 +15,8 @@
 #pragma once
 #include "gemm.hip.h"
 
+// cache-policy operand of an LDS-writing load: non-temporal, for data that is read once per launch
+#define LOAD_NT 2
 #define GLOBAL_AS(p) ((const void __attribute__((address_space(1)))*)(p))
 #define LDS_AS(p) ((void __attribute__((address_space(3)))*)(p))
 

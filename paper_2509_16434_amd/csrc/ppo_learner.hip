@@ -523,9 +523,11 @@ int launch_conv_fwd_tile_t(Ctx* c, const ConvTileArgs& a, const std::string& nam
   if (segs > S::MAXSEG || ni > 63 || lds > 160 * 1024) return 1;
   const int gy = cdiv(a.Cout, S::BN);
   int gx = 256 / gy; if (gx > a.ntiles) gx = a.ntiles; if (gx < 1) gx = 1;
-  auto kfn = k_conv_fwd_tile<CIN>;
-  static bool attr_set = false;
-  if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_set = true; }
+  // bands of four or more output rows share at most an eighth of their input rows with a neighbour: read once, non-temporal
+  const bool nt = a.TR >= 4;
+  auto kfn = nt ? k_conv_fwd_tile<CIN, LOAD_NT> : k_conv_fwd_tile<CIN, 0>;
+  static bool attr_set[2] = {false, false};
+  if (!attr_set[nt]) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_set[nt] = true; }
   ProfScope ps(c, name, flops, abytes);
   hipLaunchKernelGGL(kfn, dim3(gx, gy), dim3(S::THREADS), lds, c->stream, a);
   LAUNCHCHK(c, "k_conv_fwd_tile");
