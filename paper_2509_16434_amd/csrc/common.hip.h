@@ -23,6 +23,14 @@ __device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));  // one v_cvt_pk_bf16_f32
 }
 
+// 16-byte store of data that is not read again soon (an activation written for a later kernel): non-temporal,
+// so that it does not displace the inputs in the caches
+__device__ __forceinline__ void store_stream16(bf16_t* p, const uint4& v) {
+  typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+  const u32x4_t w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t*>(p));
+}
+
 // Division of n < 2^31 by a launch constant d >= 1 without a divide: with 2^sh < d <= 2^(sh+1)
 // and mul = floor(2^(32+sh) / d) + 1, floor(n / d) = (n * mul) >> (32 + sh) exactly (the error
 // term n * (mul*d - 2^(32+sh)) stays below 2^(32+sh)).  d == 0 marks "not prepared".

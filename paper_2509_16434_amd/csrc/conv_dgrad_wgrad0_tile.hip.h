@@ -140,7 +140,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
       for (int k = 0; k < MAXD; ++k)
         if (k < nd) {
           const char* p = (b.r0[0] + drow[k] < a.Ho) ? b.base[0] + dgo[k] : zp;  // rows outside the image: zeros
-          if (dgo[k] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + ddst[k]), 16, 0, 0);
+          if (dgo[k] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + ddst[k]), 16, 0, LOAD_NT);
         }
 #pragma unroll
       for (int k = 0; k < MAXI; ++k)
@@ -152,7 +152,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
       for (int k = 0; k < MAXM; ++k)
         if (k < nm_m) {
           const char* p = (b.r0[2] + mrow[k] < a.H) ? b.base[2] + mgo[k] : zp;
-          if (mgo[k] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + OFF_MSK + (lw + S::NLW * k) * 1024), 16, 0, 0);
+          if (mgo[k] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + OFF_MSK + (lw + S::NLW * k) * 1024), 16, 0, LOAD_NT);
         }
     };
     // bands 0 and 1 are issued before the first wait: the loop starts two bands early

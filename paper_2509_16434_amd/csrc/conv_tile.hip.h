@@ -53,14 +53,6 @@ __device__ __forceinline__ uint32_t nonzero2(uint32_t x) {
   return (t | (t >> 15)) & 3u;
 }
 
-// 16-byte store of data that is not read again soon (an activation written for a later kernel): non-temporal,
-// so that it does not displace the inputs in the caches
-__device__ __forceinline__ void store_stream16(bf16_t* p, const uint4& v) {
-  typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-  const u32x4_t w = {v.x, v.y, v.z, v.w};
-  __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t*>(p));
-}
-
 template <int CIN>
 struct ConvTileShape {
   static constexpr int NW = (CIN == 32) ? 64 : 32;   // output columns per wave (18432 weights per wave)

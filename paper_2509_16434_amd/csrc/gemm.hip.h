@@ -278,7 +278,8 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[TM][TN], const EP&
         };
         v.x &= keep(mk.x); v.y &= keep(mk.y); v.z &= keep(mk.z); v.w &= keep(mk.w);
       }
-      *reinterpret_cast<uint4*>(out + off + n) = v;
+      if (EP::kMask) store_stream16(out + off + n, v);  // an activation gradient: large, read once by the layer below
+      else *reinterpret_cast<uint4*>(out + off + n) = v;
     }
   } else {
     float* out = reinterpret_cast<float*>(ep.out);
