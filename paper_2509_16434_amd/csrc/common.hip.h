@@ -50,6 +50,12 @@ inline FastDiv make_fastdiv(int32_t d) {
   return f;
 }
 
+// Blocks are dealt to the eight XCDs (each with its own L2) round-robin: block b runs on XCD b % 8.  xcd_block
+// renumbers the blocks so that those of one XCD get consecutive numbers; the tile kernels deal their tiles by
+// that number, so that neighbouring bands of an image, which share input rows, are worked on at the same time
+// by CUs behind the same L2.  A permutation when nb is a multiple of 8, else the identity.
+__device__ __forceinline__ int xcd_block(int b, int nb) { return (nb & 7) == 0 ? (b & 7) * (nb >> 3) + (b >> 3) : b; }
+
 // Address of image `img` (= sample*V + view) inside a tensor whose samples may be gathered
 // through an index list and whose views sit at a fixed stride inside a sample row.
 struct ImgAddr {

@@ -43,7 +43,8 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
   const int RB = W * C0 * 2, nrows = 2 * TR + 1, image_bytes = nrows * RB;
   char* const zero16 = lds + NBUF * image_bytes;
   const int SP = Cout + 8;  // staging pitch (elements)
-  const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
+  const int vb = xcd_block((int)blockIdx.x, (int)gridDim.x);  // this block's number in the dealing of tiles
+  const int nq = (a.ntiles > vb) ? (a.ntiles - 1 - vb) / (int)gridDim.x + 1 : 0;
   if (tid < 4) reinterpret_cast<uint32_t*>(zero16)[tid] = 0u;
 
   if (wave == 7) {
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
     // the band's rows follow each other in memory and in LDS: 1 KiB per load whatever the row length
     const int ni = (image_bytes + 1023) >> 10;
     auto issue = [&](int q) {
-      const int t = blockIdx.x + q * gridDim.x;
+      const int t = vb + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int iy_lo = 2 * band * TR - 1;
       const char* src = reinterpret_cast<const char*>(a.in.ptr_uniform(img)) + (int64_t)iy_lo * RB;
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
   const FastDiv dv_wo = a.dv_wo;
 
   for (int q = 0; q < nq; ++q) {
-    const int t = blockIdx.x + q * gridDim.x;
+    const int t = vb + q * gridDim.x;
     const int img = t / a.NB, band = t - img * a.NB;
     const int plim = min(TR, a.Ho - band * TR) * Wo;  // pixels of the band that exist
     bf16_t* dst = a.out + ((int64_t)img * a.Ho + (int64_t)band * TR) * Wo * Cout;

@@ -106,7 +106,8 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       reinterpret_cast<uint32_t*>(patch0 + (w * hp16 + half) * KP * 2)[r] = 0u;
     }
   }
-  const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
+  const int vb = xcd_block((int)blockIdx.x, (int)gridDim.x);  // this block's number in the dealing of tiles
+  const int nq = (a.ntiles > vb) ? (a.ntiles - 1 - vb) / (int)gridDim.x + 1 : 0;
 
   // zero the right pad slot of every dY image row once
   for (int i = tid; i < NBUF * (TQ + 1) * 8; i += S::THREADS) {
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       goff[sg] = (sg < segs && (int)phys < rowbytes) ? (int)logi : -1;
     }
     auto issue = [&](int q) __attribute__((always_inline)) {
-      const int t = blockIdx.x + q * gridDim.x;
+      const int t = vb + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int oy_lo = band * TQ;
       const char* src = reinterpret_cast<const char*>(a.dy.ptr_uniform(img)) + (int64_t)oy_lo * rowbytes;
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
     int nvalid[2] = {0, 0};        // its chunks that lie inside the image
     auto load_mask = [&](int q, auto setc) __attribute__((always_inline)) {
       constexpr int SET = decltype(setc)::value;
-      const int t = blockIdx.x + q * gridDim.x;
+      const int t = vb + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int b = img / a.V, vw = img - b * a.V;
       const int rows = min(2 * TQ, a.H - 2 * band * TQ);
@@ -371,7 +372,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
       wr[s][cc] = *reinterpret_cast<const bf16x8_t*>(a.wt + ((int64_t)s * CI + wn * 32 + l32) * CO + cc * 16 + h * 8);
 
   for (int q = 0; q < nq; ++q) {
-    const int t = blockIdx.x + q * gridDim.x;
+    const int t = vb + q * gridDim.x;
     const int band = t % a.NB;
     __builtin_amdgcn_s_barrier();  // A(q): band q is in LDS, staging buffer q&1 is free
     char* st = stage0 + (q & 1) * stage_bytes;

@@ -68,7 +68,8 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
   const int MRB = W * 4, mask_bytes = 2 * TQ * MRB;
   // slot: dY image | image rows | 16 zero bytes | mask words | 32 zero bytes
   const int OFF_IMG = dyimg_bytes, OFF_MSK = OFF_IMG + img0_bytes + 16, OFF_Z = OFF_MSK + mask_bytes, SLOT = OFF_Z + 32;
-  const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
+  const int vb = xcd_block((int)blockIdx.x, (int)gridDim.x);  // this block's number in the dealing of tiles
+  const int nq = (a.ntiles > vb) ? (a.ntiles - 1 - vb) / (int)gridDim.x + 1 : 0;
 
   // ---- once: the zero pads no load ever writes
   for (int i = tid; i < NBUF * (TQ + 1) * 8; i += S::THREADS) {
@@ -116,7 +117,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     }
     // tiles of this block in order: (img, band) advances by gridDim.x tiles without a division
     const int step_img = (int)gridDim.x / a.NB, step_band = (int)gridDim.x - step_img * a.NB;
-    int n_img = (int)blockIdx.x / a.NB, n_band = (int)blockIdx.x - n_img * a.NB;
+    int n_img = vb / a.NB, n_band = vb - n_img * a.NB;
     struct Band { const char* base[3]; int r0[3]; };
     // base addresses and first rows of the next band to issue; formed one band ahead, so that the
     // scalar load of the gather index is not waited for

@@ -92,8 +92,9 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
   const int W = a.W, WP = W + 2, TR = a.TR, Wo = a.Wo;
   const int nrows = 2 * TR + 1, rowbytes = W * PIX, segs = (rowbytes + 1023) >> 10;
   const int image_bytes = nrows * WP * PIX;
-  // tiles of this block: blockIdx.x, + gridDim.x, ...
-  const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
+  // tiles of this block: vb, vb + gridDim.x, ...
+  const int vb = xcd_block((int)blockIdx.x, (int)gridDim.x);  // this block's number in the dealing of tiles
+  const int nq = (a.ntiles > vb) ? (a.ntiles - 1 - vb) / (int)gridDim.x + 1 : 0;
 
   // zero the pad pixels of all ring images once
   for (int i = tid; i < NBUF * nrows * 2 * CPP; i += S::THREADS) {
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
       goff[sg] = (sg < segs && (int)phys < (W + 1) * PIX) ? (int)logi - PIX : -1;
     }
     auto issue = [&](int q) {
-      const int t = blockIdx.x + q * gridDim.x;
+      const int t = vb + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int iy_lo = 2 * band * TR - 1;
       const char* src = reinterpret_cast<const char*>(a.in.ptr_uniform(img)) + (int64_t)iy_lo * rowbytes;
@@ -169,7 +170,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
 
   // the first tile's barrier also orders the pad fill and the bias table before their first use
   for (int q = 0; q < nq; ++q) {
-    const int t = blockIdx.x + q * gridDim.x;
+    const int t = vb + q * gridDim.x;
     __builtin_amdgcn_s_barrier();  // band q is in LDS
     const char* img_s = lds + (q % NBUF) * image_bytes;
 
@@ -289,7 +290,8 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
   const int W = a.W, WP = W + 2, TR = a.TR, Wo = a.Wo, nstep = a.nstep;
   const int nrows = 2 * TR + 1, rowbytes = W * PIX, segs = (rowbytes + 1023) >> 10;
   const int image_bytes = nrows * WP * PIX, dy_bytes = nstep * 16 * 128, buf_bytes = image_bytes + dy_bytes;
-  const int nq = (a.ntiles > (int)blockIdx.x) ? (a.ntiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0;
+  const int vb = xcd_block((int)blockIdx.x, (int)gridDim.x);  // this block's number in the dealing of tiles
+  const int nq = (a.ntiles > vb) ? (a.ntiles - 1 - vb) / (int)gridDim.x + 1 : 0;
   const int nb0 = blockIdx.y * 64;
 
   // zero the pad pixels of all ring images once
@@ -311,7 +313,7 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
       xgoff[sg] = (sg < segs && (int)phys < (W + 1) * PIX) ? (int)logi - PIX : -1;
     }
     auto issue = [&](int q) {
-      const int t = blockIdx.x + q * gridDim.x;
+      const int t = vb + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int iy_lo = 2 * band * TR - 1;
       const char* xsrc = reinterpret_cast<const char*>(a.in.ptr_uniform(img)) + (int64_t)iy_lo * rowbytes;
