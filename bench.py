@@ -73,6 +73,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=1, help="index into the benchmark config list (default 1: medium)")
     ap.add_argument("--num-envs", type=int, default=None, help="override the config's env count (debugging only)")
+    ap.add_argument("--max-chunk", type=int, default=0, help="samples per forward/backward pass inside a minibatch (0: the library's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--phase", choices=["learn", "act"], default="learn", help="learn: the learner path (default); act: the policy step")
     ap.add_argument("--profile-table", action="store_true", help="also print the per-kernel-class table to stderr")
@@ -100,7 +101,7 @@ def main():
 
     # ---- synthetic rollout, drawn per step on the GPU (seeded) and kept resident in HBM
     stream = torch.cuda.Stream()
-    lrn = learner.Learner(net, N, T, cfg["obs_dtype"], stream=stream)
+    lrn = learner.Learner(net, N, T, cfg["obs_dtype"], max_chunk=args.max_chunk, stream=stream)
     lrn.set_params(synth.init_params(net, cfg["seed"]))
     gen = torch.Generator(device="cuda")
     gen.manual_seed(cfg["seed"])

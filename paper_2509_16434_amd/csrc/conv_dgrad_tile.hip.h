@@ -139,7 +139,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
         for (int sg = 0; sg < S::MAXSEG; ++sg)
           if (sg < segs) {
             const char* p = inside ? src + (int64_t)row * rowbytes + goff[sg] : reinterpret_cast<const char*>(a.zpage) + lane * 16;
-            if (goff[sg] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + row * RP + sg * 1024), 16, 0, LOAD_NT);
+            if (goff[sg] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + row * RP + sg * 1024), 16, 0, 0);
           }
       }
       if constexpr (C0 > 0) {
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(512) void k_conv_dgrad_tile(ConvDgradArgs a) {
           const int o = j * 1024 + lane * 16, iy = iy0 + o / RB0;
           const bool inside = iy >= 0 && iy < a.H0;
           const char* p = inside ? isrc + o : reinterpret_cast<const char*>(a.zpage) + lane * 16;
-          if (o < img0_bytes) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(idst + j * 1024), 16, 0, LOAD_NT);
+          if (o < img0_bytes) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(idst + j * 1024), 16, 0, 0);
         }
       }
     };
