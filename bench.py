@@ -40,20 +40,20 @@ RIDGE_FLOP_PER_BYTE = PEAK_MFMA_BF16_TF * 1e12 / (PEAK_HBM_GBS * 1e9)  # 312.5
 # profiles/c1_medium_hbm_traffic.md and profiles/c2_full_hbm_traffic.md; a kernel class or workload that was not
 # measured reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("c1_medium", "conv_wgrad.1"): 428.4e6,
-    ("c1_medium", "conv_fwd.1"): 418.7e6,
-    ("c1_medium", "conv_fwd.0"): 319.1e6,
-    ("c1_medium", "conv_dgrad.1+wgrad.0"): 184.9e6,
-    ("c1_medium", "conv_dgrad.2"): 176.9e6,
-    ("c1_medium", "conv_wgrad.2"): 205.1e6,
-    ("c1_medium", "conv_fwd.2"): 169.7e6,
-    ("c2_full", "conv_fwd.1"): 8461.0e6,
-    ("c2_full", "conv_wgrad.1"): 8321.8e6,
-    ("c2_full", "conv_fwd.0"): 6003.4e6,
-    ("c2_full", "conv_dgrad.1+wgrad.0"): 3823.2e6,
-    ("c2_full", "conv_dgrad.2"): 3472.2e6,
-    ("c2_full", "conv_fwd.2"): 3613.4e6,
-    ("c2_full", "conv_fwd.3"): 1208.3e6,
+    ("c1_medium", "conv_wgrad.1"): 425.3e6,
+    ("c1_medium", "conv_fwd.1"): 414.1e6,
+    ("c1_medium", "conv_fwd.0"): 318.8e6,
+    ("c1_medium", "conv_dgrad.1+wgrad.0"): 184.2e6,
+    ("c1_medium", "conv_dgrad.2"): 176.8e6,
+    ("c1_medium", "conv_wgrad.2"): 204.7e6,
+    ("c1_medium", "conv_fwd.2"): 169.1e6,
+    ("c2_full", "conv_fwd.1"): 7889.0e6,
+    ("c2_full", "conv_wgrad.1"): 8006.6e6,
+    ("c2_full", "conv_fwd.0"): 5978.0e6,
+    ("c2_full", "conv_dgrad.1+wgrad.0"): 3642.8e6,
+    ("c2_full", "conv_dgrad.2"): 3308.9e6,
+    ("c2_full", "conv_fwd.2"): 3290.7e6,
+    ("c2_full", "conv_fwd.3"): 1222.2e6,
 }
 
 
