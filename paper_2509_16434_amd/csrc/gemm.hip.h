@@ -590,48 +590,3 @@ __device__ __forceinline__ void reduce_partials_block(const float* __restrict__ 
     out[w] = ((red[0][c] + red[1][c]) + (red[2][c] + red[3][c])) + ((red[4][c] + red[5][c]) + (red[6][c] + red[7][c]));
   }
 }
-
-// Every pending reduction of a backward pass in one launch: job j covers blocks [first[j], first[j+1]).
-// kind 0: dst[i] (+)= sum_s partial[s][i]; kind 1: partials stored transposed, dst[n*K + k] (+)=
-// sum_s partial[s][k*N + n]; kind 2: partial[s][co][K+1] of the first convolution, whose last column
-// is the bias gradient (dst2).  Jobs with vec set (n a multiple of 4, partials 16-byte aligned) take
-// four outputs per lane with 16-byte loads (128 outputs per block), the others one (32 per block).
-struct ReduceJobs {
-  static constexpr int MAXJ = 16;
-  int njobs;
-  int first[MAXJ + 1];
-  int kind[MAXJ], splits[MAXJ], N[MAXJ], K[MAXJ], accumulate[MAXJ], vec[MAXJ];
-  int64_t n[MAXJ];
-  const float* partial[MAXJ];
-  float* dst[MAXJ];
-  float* dst2[MAXJ];
-};
-__global__ __launch_bounds__(256) void k_reduce_batch(ReduceJobs jobs) {
-  __shared__ float red[8][33 * 4];
-  int j = 0;
-  while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first[j + 1]) ++j;
-  const int64_t nn = jobs.n[j];
-  const int kind = jobs.kind[j], blk = (int)blockIdx.x - jobs.first[j];
-  auto put = [&](int64_t i, float s) {
-    float* d;
-    if (kind == 0) d = jobs.dst[j] + i;
-    else if (kind == 1) { const int N = jobs.N[j], kk = (int)(i / N), n = (int)(i - (int64_t)kk * N); d = jobs.dst[j] + (int64_t)n * jobs.K[j] + kk; }
-    else { const int KP = jobs.K[j] + 1, co = (int)(i / KP), k = (int)(i - (int64_t)co * KP); d = k == jobs.K[j] ? jobs.dst2[j] + co : jobs.dst[j] + (int64_t)co * jobs.K[j] + k; }
-    *d = jobs.accumulate[j] ? *d + s : s;
-  };
-  if (jobs.vec[j]) {
-    const int64_t i = ((int64_t)blk * 32 + (threadIdx.x & 31)) * 4;
-    float s[4];
-    reduce_partials_block<4>(jobs.partial[j], jobs.splits[j], nn, i, red, s);
-    if (threadIdx.x < 32 && i < nn) {
-#pragma unroll
-      for (int w = 0; w < 4; ++w) put(i + w, s[w]);
-    }
-  } else {
-    const int64_t i = (int64_t)blk * 32 + (threadIdx.x & 31);
-    float s[1];
-    reduce_partials_block<1>(jobs.partial[j], jobs.splits[j], nn, i, reinterpret_cast<float (*)[33]>(&red[0][0]), s);
-    if (threadIdx.x < 32 && i < nn) put(i, s[0]);
-  }
-}
-

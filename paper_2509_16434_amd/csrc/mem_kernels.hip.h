@@ -3,6 +3,7 @@
 // weight re-packing.
 #pragma once
 #include "common.hip.h"
+#include "gemm.hip.h"
 
 // The per-step scalars of a rollout slab: proprio (-> bf16), action, log-prob, value, reward, done.
 struct ScalarWrite {
@@ -591,41 +592,95 @@ __global__ __launch_bounds__(256) void k_loss(int B, LossData L, const float* __
 struct DevStats { float pi_loss, v_loss, entropy, approx_kl, clip_frac, grad_norm, total_loss; int32_t nonfinite; };
 
 // Sum the per-block partials of one minibatch (all chunks) in block order; write the loss
-// statistics and the log-std gradient (which also carries the entropy bonus).
-__global__ void k_loss_finalize(int nblocks, int Bfull, int A, int distill, const float* __restrict__ stat_part,
-                                const float* __restrict__ dls_part, const float* __restrict__ logstd, float vf_coef,
-                                float ent_coef, DevStats* __restrict__ st, float* __restrict__ g_logstd) {
-  // 256 threads: column c (4 statistics, then the A log-std gradients) is summed by 8 lanes, lane j
-  // taking blocks j, j+8, ... in order; the 8 sums are combined in a fixed order
+// statistics and the log-std gradient (which also carries the entropy bonus).  The work of one
+// block of 256 threads; it rides along as the last block of the backward pass's reduction launch.
+struct LossFinalize {
+  int on, nblocks, Bfull, A, distill;
+  const float *stat_part, *dls_part, *logstd;
+  float vf_coef, ent_coef;
+  DevStats* st;
+  float* g_logstd;
+};
+__device__ __forceinline__ void loss_finalize_block(const LossFinalize& f) {
+  // column c (4 statistics, then the A log-std gradients) is summed by 8 lanes, lane j taking
+  // blocks j, j+8, ... in order; the 8 sums are combined in a fixed order
   const int tid = threadIdx.x, l8 = tid & 7;
   __shared__ float tot[4];
-  const int ncol = 4 + (distill ? 0 : A);
+  const int ncol = 4 + (f.distill ? 0 : f.A);
   for (int c0 = 0; c0 < ncol; c0 += 32) {
     const int col = c0 + (tid >> 3);
     float s = 0.f;
     if (col < ncol)
-      for (int b = l8; b < nblocks; b += 8) s += col < 4 ? stat_part[(int64_t)b * LOSS_NSTAT + col] : dls_part[(int64_t)b * 32 + (col - 4)];
+      for (int b = l8; b < f.nblocks; b += 8) s += col < 4 ? f.stat_part[(int64_t)b * LOSS_NSTAT + col] : f.dls_part[(int64_t)b * 32 + (col - 4)];
     s += __shfl_xor(s, 1); s += __shfl_xor(s, 2); s += __shfl_xor(s, 4);
     if (l8 == 0 && col < ncol) {
       if (col < 4) tot[col] = s;
-      else g_logstd[col - 4] = s - ent_coef;
+      else f.g_logstd[col - 4] = s - f.ent_coef;
     }
   }
   __syncthreads();
   if (tid == 0) {
-    if (distill) {
-      float l = tot[0] / ((float)Bfull * (float)A);
+    DevStats* st = f.st;
+    if (f.distill) {
+      float l = tot[0] / ((float)f.Bfull * (float)f.A);
       st->pi_loss = l; st->v_loss = 0.f; st->entropy = 0.f; st->approx_kl = 0.f; st->clip_frac = 0.f; st->total_loss = l;
     } else {
-      float invB = 1.f / (float)Bfull, ent = 0.f;
-      for (int j = 0; j < A; ++j) ent += logstd[j] + 1.4189385332046727418f;
+      float invB = 1.f / (float)f.Bfull, ent = 0.f;
+      for (int j = 0; j < f.A; ++j) ent += f.logstd[j] + 1.4189385332046727418f;
       st->pi_loss = tot[0] * invB; st->v_loss = tot[1] * invB; st->entropy = ent;
       st->approx_kl = tot[2] * invB; st->clip_frac = tot[3] * invB;
-      st->total_loss = st->pi_loss + vf_coef * st->v_loss - ent_coef * ent;
+      st->total_loss = st->pi_loss + f.vf_coef * st->v_loss - f.ent_coef * ent;
     }
     st->nonfinite = isfinite(st->total_loss) ? 0 : 1;
   }
 }
+
+// ---------------------------------------------------------------- partial sums of a backward pass
+// Every pending reduction of a backward pass in one launch: job j covers blocks [first[j], first[j+1]).
+// kind 0: dst[i] (+)= sum_s partial[s][i]; kind 1: partials stored transposed, dst[n*K + k] (+)=
+// sum_s partial[s][k*N + n]; kind 2: partial[s][co][K+1] of the first convolution, whose last column
+// is the bias gradient (dst2).  Jobs with vec set (n a multiple of 4, partials 16-byte aligned) take
+// four outputs per lane with 16-byte loads (128 outputs per block), the others one (32 per block).
+struct ReduceJobs {
+  static constexpr int MAXJ = 16;
+  int njobs;
+  int first[MAXJ + 1];
+  int kind[MAXJ], splits[MAXJ], N[MAXJ], K[MAXJ], accumulate[MAXJ], vec[MAXJ];
+  int64_t n[MAXJ];
+  const float* partial[MAXJ];
+  float* dst[MAXJ];
+  float* dst2[MAXJ];
+};
+__global__ __launch_bounds__(256) void k_reduce_batch(ReduceJobs jobs, LossFinalize fin) {
+  if (fin.on && blockIdx.x + 1 == gridDim.x) { loss_finalize_block(fin); return; }  // the block behind the last job
+  __shared__ float red[8][33 * 4];
+  int j = 0;
+  while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first[j + 1]) ++j;
+  const int64_t nn = jobs.n[j];
+  const int kind = jobs.kind[j], blk = (int)blockIdx.x - jobs.first[j];
+  auto put = [&](int64_t i, float s) {
+    float* d;
+    if (kind == 0) d = jobs.dst[j] + i;
+    else if (kind == 1) { const int N = jobs.N[j], kk = (int)(i / N), n = (int)(i - (int64_t)kk * N); d = jobs.dst[j] + (int64_t)n * jobs.K[j] + kk; }
+    else { const int KP = jobs.K[j] + 1, co = (int)(i / KP), k = (int)(i - (int64_t)co * KP); d = k == jobs.K[j] ? jobs.dst2[j] + co : jobs.dst[j] + (int64_t)co * jobs.K[j] + k; }
+    *d = jobs.accumulate[j] ? *d + s : s;
+  };
+  if (jobs.vec[j]) {
+    const int64_t i = ((int64_t)blk * 32 + (threadIdx.x & 31)) * 4;
+    float s[4];
+    reduce_partials_block<4>(jobs.partial[j], jobs.splits[j], nn, i, red, s);
+    if (threadIdx.x < 32 && i < nn) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) put(i + w, s[w]);
+    }
+  } else {
+    const int64_t i = (int64_t)blk * 32 + (threadIdx.x & 31);
+    float s[1];
+    reduce_partials_block<1>(jobs.partial[j], jobs.splits[j], nn, i, reinterpret_cast<float (*)[33]>(&red[0][0]), s);
+    if (threadIdx.x < 32 && i < nn) put(i, s[0]);
+  }
+}
+
 
 // ---------------------------------------------------------------- Adam
 // m = b1 m + (1-b1) g; v = b2 v + (1-b2) g^2; p -= lr (m/c1) / (sqrt(v/c2) + eps), c1 = 1-b1^k,
@@ -692,23 +747,24 @@ __global__ __launch_bounds__(256) void k_gnorm_partial(int64_t n, const float* _
   if (tid == 0) sq_part[blockIdx.x] = red[0];
 }
 // Gradient norm from the per-block sums; with max_norm > 0 also the clipping coefficient
-// min(1, max_norm / (norm + 1e-6)) for k_adam.
-__global__ __launch_bounds__(256) void k_gnorm_finalize(const float* __restrict__ sq_part, int nb, DevStats* __restrict__ st, float max_norm,
-                                                        float* __restrict__ clip_coef) {
+// min(1, max_norm / (norm + 1e-6)) for k_adam.  The work of one block of 256 threads.
+struct GnormFinalize { int on, nb; const float* sq_part; DevStats* st; float max_norm; float* clip_coef; };
+__device__ __forceinline__ void gnorm_finalize_block(const GnormFinalize& f) {
   __shared__ float red[256];
   const int tid = threadIdx.x;
   float s = 0.f;
-  for (int b = tid; b < nb; b += 256) s += sq_part[b];
+  for (int b = tid; b < f.nb; b += 256) s += f.sq_part[b];
   red[tid] = s;
   __syncthreads();
   for (int w = 128; w > 0; w >>= 1) { if (tid < w) red[tid] += red[tid + w]; __syncthreads(); }
   if (tid == 0) {
     const float norm = sqrtf(red[0]);
-    st->grad_norm = norm;
-    if (!isfinite(red[0])) st->nonfinite = 1;
-    if (clip_coef) *clip_coef = max_norm > 0.f ? fminf(1.f, max_norm / (norm + 1e-6f)) : 1.f;
+    f.st->grad_norm = norm;
+    if (!isfinite(red[0])) f.st->nonfinite = 1;
+    if (f.clip_coef) *f.clip_coef = f.max_norm > 0.f ? fminf(1.f, f.max_norm / (norm + 1e-6f)) : 1.f;
   }
 }
+__global__ __launch_bounds__(256) void k_gnorm_finalize(GnormFinalize f) { gnorm_finalize_block(f); }
 
 // ---------------------------------------------------------------- advantage normalisation
 // out = (adv - mean) / (std + 1e-8) over all S samples of the rollout, std the population standard
@@ -756,7 +812,8 @@ struct RepackJobs {
   const bf16_t* src[MAXJ];
   bf16_t* dst[MAXJ];
 };
-__global__ __launch_bounds__(256) void k_repack_all(RepackJobs jobs) {
+__global__ __launch_bounds__(256) void k_repack_all(RepackJobs jobs, GnormFinalize gn) {
+  if (gn.on && blockIdx.x + 1 == gridDim.x) { gnorm_finalize_block(gn); return; }  // the block behind the last job: the step's gradient norm
   int j = 0;
   while (j + 1 < jobs.njobs && (int)blockIdx.x >= jobs.first[j + 1]) ++j;
   const int64_t i = (int64_t)((int)blockIdx.x - jobs.first[j]) * 256 + threadIdx.x;

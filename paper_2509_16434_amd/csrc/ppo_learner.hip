@@ -80,6 +80,8 @@ struct Ctx {
   float *partial_base = nullptr, *bias_partial_base = nullptr;
   int64_t partial_cap = 0, bias_partial_cap = 0;
   ReduceJobs rjobs;
+  LossFinalize lossfin = {};    // pending: rides as the last block of the next reduction launch
+  GnormFinalize gnfin = {}; // pending: rides as the last block of the next re-pack launch
   int rjob_blocks = 0;
   float *stat_part = nullptr, *dls_part = nullptr, *sq_part = nullptr, *clip_coef = nullptr;
   float* adv_n = nullptr;  // advantages normalised over the rollout (norm_adv)
@@ -346,14 +348,14 @@ MapRows plain_map(int64_t ld, int M) { MapRows m; m.stride_b = ld; m.stride_v = 
 // All queued partial-sum reductions in one launch; the partial workspaces are free again afterwards.
 int flush_reduces(Ctx* c) {
   ReduceJobs& J = c->rjobs;
-  if (J.njobs > 0) {
+  if (J.njobs > 0 || c->lossfin.on) {
     double bytes = 0.0;
     for (int j = 0; j < J.njobs; ++j) bytes += 4.0 * ((double)J.splits[j] + 1.0) * (double)J.n[j];
     ProfScope ps(c, "wgrad_reduce", 0.0, bytes);
-    J.first[J.njobs] = c->rjob_blocks;
-    for (int j = J.njobs + 1; j <= ReduceJobs::MAXJ; ++j) J.first[j] = c->rjob_blocks;
-    hipLaunchKernelGGL(k_reduce_batch, dim3(c->rjob_blocks), dim3(256), 0, c->stream, J);
+    for (int j = J.njobs; j <= ReduceJobs::MAXJ; ++j) J.first[j] = c->rjob_blocks;
+    hipLaunchKernelGGL(k_reduce_batch, dim3(c->rjob_blocks + (c->lossfin.on ? 1 : 0)), dim3(256), 0, c->stream, J, c->lossfin);
     LAUNCHCHK(c, "k_reduce_batch");
+    c->lossfin.on = 0;
   }
   J.njobs = 0; c->rjob_blocks = 0;
   c->partial = c->partial_base; c->partial_elems = c->partial_cap;
@@ -494,8 +496,9 @@ int repack_weights(Ctx* c) {
   jobs.first[nj] = nblocks; jobs.njobs = nj;
   for (int j = nj + 1; j <= RepackJobs::MAXJ; ++j) jobs.first[j] = nblocks;
   for (int j = nj; j < RepackJobs::MAXJ; ++j) { jobs.kind[j] = 0; jobs.src[j] = nullptr; jobs.dst[j] = nullptr; jobs.a[j] = jobs.b[j] = jobs.ld[j] = 0; }
-  hipLaunchKernelGGL(k_repack_all, dim3(nblocks), dim3(256), 0, c->stream, jobs);
+  hipLaunchKernelGGL(k_repack_all, dim3(nblocks + (c->gnfin.on ? 1 : 0)), dim3(256), 0, c->stream, jobs, c->gnfin);
   LAUNCHCHK(c, "weight repack");
+  c->gnfin.on = 0;
   return PPO_OK;
 }
 
@@ -1010,12 +1013,18 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
         }
         // partial slots of a ragged last chunk follow the full chunks contiguously
         nblocks = ci * blocks_per_chunk + cdiv(n, LOSS_BLOCK);
+        if (c0 + c->CH >= B) {
+          // last chunk: every loss partial of the minibatch exists; their sums (statistics, log-std gradient)
+          // are taken by one more block of the backward pass's reduction launch
+          LossFinalize& f = c->lossfin;
+          f.on = 1; f.nblocks = nblocks; f.Bfull = B; f.A = c->A; f.distill = distill ? 1 : 0; f.stat_part = c->stat_part; f.dls_part = c->dls_part;
+          f.logstd = distill ? nullptr : c->p + c->logstd; f.vf_coef = hp->vf_coef; f.ent_coef = hp->ent_coef; f.st = c->dstats + k;
+          f.g_logstd = distill ? nullptr : c->g + c->logstd;
+        }
         rc = backward_chunk(c, idx + c0, n, c0 > 0, !head_done);
         if (rc) return rc;
       }
-      hipLaunchKernelGGL(k_loss_finalize, dim3(1), dim3(256), 0, c->stream, nblocks, B, c->A, distill ? 1 : 0, c->stat_part, c->dls_part,
-                         distill ? nullptr : c->p + c->logstd, hp->vf_coef, hp->ent_coef, c->dstats + k, distill ? nullptr : c->g + c->logstd);
-      LAUNCHCHK(c, "k_loss_finalize");
+      if (c->lossfin.on) { rc = flush_reduces(c); if (rc) return rc; }  // (a backward pass always ends with a flush; kept for safety)
       c->step += 1;
       {
       ProfScope ps(c, "adam", 0.0, 30.0 * (double)c->total);
@@ -1024,15 +1033,16 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
       if (clip) {  // the norm has to be known before the step: one more pass over the gradient
         hipLaunchKernelGGL(k_gnorm_partial, dim3(c->adam_blocks), dim3(256), 0, c->stream, c->total, c->g, c->sq_part);
         LAUNCHCHK(c, "k_gnorm_partial");
-        hipLaunchKernelGGL(k_gnorm_finalize, dim3(1), dim3(256), 0, c->stream, c->sq_part, c->adam_blocks, c->dstats + k, hp->max_grad_norm, c->clip_coef);
+        GnormFinalize gf; gf.on = 1; gf.nb = c->adam_blocks; gf.sq_part = c->sq_part; gf.st = c->dstats + k; gf.max_norm = hp->max_grad_norm; gf.clip_coef = c->clip_coef;
+        hipLaunchKernelGGL(k_gnorm_finalize, dim3(1), dim3(256), 0, c->stream, gf);
         LAUNCHCHK(c, "k_gnorm_finalize");
       }
       hipLaunchKernelGGL(k_adam, dim3(c->adam_blocks), dim3(256), 0, c->stream, c->total, c->p, c->m, c->v, c->g, c->shadow, hp->lr, hp->beta1, hp->beta2,
                          hp->adam_eps, (float)(1.0 / c1), (float)(1.0 / c2), c->sq_part, clip ? c->clip_coef : nullptr);
       LAUNCHCHK(c, "k_adam");
-      if (!clip) {
-        hipLaunchKernelGGL(k_gnorm_finalize, dim3(1), dim3(256), 0, c->stream, c->sq_part, c->adam_blocks, c->dstats + k, 0.f, nullptr);
-        LAUNCHCHK(c, "k_gnorm_finalize");
+      if (!clip) {  // the step's gradient norm: one more block of the re-pack launch that follows
+        GnormFinalize& gf = c->gnfin;
+        gf.on = 1; gf.nb = c->adam_blocks; gf.sq_part = c->sq_part; gf.st = c->dstats + k; gf.max_norm = 0.f; gf.clip_coef = nullptr;
       }
       }
       rc = repack_weights(c);
