@@ -22,6 +22,12 @@ struct Conv0Args {
   int H, W, Ho, Wo, Cout;
   int TR, NB, ntiles;         // output rows per band, bands per image, nimg * NB
   FastDiv dv_wo;              // division by Wo
+  // the blocks behind the tile_blocks tile blocks copy the samples' proprioception (bf16 in the rollout
+  // buffer, gathered through in.idx) into columns [pcol0, pcol0 + P) of the feature matrix (gather_blocks = 0: none)
+  int tile_blocks, gather_blocks, pB, P, pcol0;
+  const bf16_t* proprio;
+  bf16_t* feat;
+  int64_t feat_ld;
 };
 
 template <int C0>
@@ -43,8 +49,18 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
   const int RB = W * C0 * 2, nrows = 2 * TR + 1, image_bytes = nrows * RB;
   char* const zero16 = lds + NBUF * image_bytes;
   const int SP = Cout + 8;  // staging pitch (elements)
-  const int vb = xcd_block((int)blockIdx.x, (int)gridDim.x);  // this block's number in the dealing of tiles
-  const int nq = (a.ntiles > vb) ? (a.ntiles - 1 - vb) / (int)gridDim.x + 1 : 0;
+  if ((int)blockIdx.x >= a.tile_blocks) {
+    const int64_t n = (int64_t)a.pB * a.P;
+    for (int64_t i = (int64_t)((int)blockIdx.x - a.tile_blocks) * 512 + tid; i < n; i += (int64_t)a.gather_blocks * 512) {
+      const int b = (int)(i / a.P), j = (int)(i - (int64_t)b * a.P);
+      const int64_t s = a.in.idx ? a.in.idx[b] : b;
+      a.feat[(int64_t)b * a.feat_ld + a.pcol0 + j] = a.proprio[s * a.P + j];
+    }
+    return;
+  }
+  const int nblk = a.tile_blocks;
+  const int vb = xcd_block((int)blockIdx.x, nblk);  // this block's number in the dealing of tiles
+  const int nq = (a.ntiles > vb) ? (a.ntiles - 1 - vb) / nblk + 1 : 0;
   if (tid < 4) reinterpret_cast<uint32_t*>(zero16)[tid] = 0u;
 
   if (wave == 7) {
@@ -52,7 +68,7 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
     // the band's rows follow each other in memory and in LDS: 1 KiB per load whatever the row length
     const int ni = (image_bytes + 1023) >> 10;
     auto issue = [&](int q) {
-      const int t = vb + q * gridDim.x;
+      const int t = vb + q * nblk;
       const int img = t / a.NB, band = t - img * a.NB;
       const int iy_lo = 2 * band * TR - 1;
       const char* src = reinterpret_cast<const char*>(a.in.ptr_uniform(img)) + (int64_t)iy_lo * RB;
@@ -103,7 +119,7 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
   const FastDiv dv_wo = a.dv_wo;
 
   for (int q = 0; q < nq; ++q) {
-    const int t = vb + q * gridDim.x;
+    const int t = vb + q * nblk;
     const int img = t / a.NB, band = t - img * a.NB;
     const int plim = min(TR, a.Ho - band * TR) * Wo;  // pixels of the band that exist
     bf16_t* dst = a.out + ((int64_t)img * a.Ho + (int64_t)band * TR) * Wo * Cout;

@@ -718,10 +718,12 @@ int launch_conv0_fwd_tile_t(Ctx* c, Conv0Args a, int nimg) {
   a.NB = cdiv(a.Ho, TR); a.TR = cdiv(a.Ho, a.NB); a.ntiles = nimg * a.NB;
   a.dv_wo = make_fastdiv(a.Wo);
   int gx = a.ntiles < 512 ? a.ntiles : 512;
+  a.tile_blocks = gx;
+  if (a.gather_blocks > 0) a.gather_blocks = (int)std::min<int64_t>(32, cdiv((int64_t)a.pB * a.P, 512));
   auto kfn = k_conv0_fwd_tile<C0>;
   static bool attr_set = false;
   if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024)); attr_set = true; }
-  hipLaunchKernelGGL(kfn, dim3(gx), dim3(S::THREADS), S::lds_bytes(a.W, a.TR, a.Cout), c->stream, a);
+  hipLaunchKernelGGL(kfn, dim3(gx + a.gather_blocks), dim3(S::THREADS), S::lds_bytes(a.W, a.TR, a.Cout), c->stream, a);
   LAUNCHCHK(c, "k_conv0_fwd_tile");
   return PPO_OK;
 }
@@ -729,6 +731,7 @@ int launch_conv0_fwd_tile_t(Ctx* c, Conv0Args a, int nimg) {
 // Forward of `n` samples selected by device indices idx (NULL = 0..n-1 offset by `first`).
 int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true) {
   const int V = c->V, nimg = n * V;
+  bool proprio_done = false;
   {  // first convolution straight from the rollout buffer
     ImgAddr in; in.base = c->obs; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
     int Co = c->cC[1], Ho = c->cH[1], Wo = c->cW[1];
@@ -740,9 +743,11 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true) {
     ca.in = in; ca.in.prepare(); ca.out = c->act[0]; ca.w = c->shadow + c->convW[0]; ca.bias = c->p + c->convB[0]; ca.zpage = c->zpage;
     ca.bits = c->nconv > 1 ? c->abits[0] : nullptr;
     ca.H = c->cH[0]; ca.W = c->cW[0]; ca.Ho = Ho; ca.Wo = Wo; ca.Cout = Co; ca.TR = 0; ca.NB = 0; ca.ntiles = 0;
+    ca.tile_blocks = 0; ca.gather_blocks = 1; ca.pB = n; ca.P = c->P; ca.pcol0 = V * c->flat; ca.proprio = c->proprio; ca.feat = c->feat; ca.feat_ld = c->feat_ld;
     int trc = c->cC[0] == 1 ? launch_conv0_fwd_tile_t<1>(c, ca, nimg) : (c->cC[0] == 3 ? launch_conv0_fwd_tile_t<3>(c, ca, nimg) : 1);
     if (trc != PPO_OK && trc != 1) return trc;
     c->abits_ok[0] = trc == PPO_OK && c->nconv > 1;
+    proprio_done = trc == PPO_OK;
     if (trc != PPO_OK) {  // shapes the LDS-ring kernel does not cover
       if (c->cC[0] == 1)
         hipLaunchKernelGGL((k_conv1_fwd<1, TPW>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, c->shadow + c->convW[0], c->p + c->convB[0], c->act[0]);
@@ -768,8 +773,10 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true) {
     if (rc == PPO_OK + 1) rc = launch_gemm(c, al, al.M, c->shadow + c->convW[l], al.K, c->cC[l + 1], al.K, ep, "conv_fwd." + std::to_string(l), ab);
     if (rc) return rc;
   }
-  hipLaunchKernelGGL(k_gather_proprio, dim3(cdiv((int64_t)n * c->P, 256)), dim3(256), 0, c->stream, c->proprio, idx, n, c->P, c->feat, (int64_t)c->feat_ld, V * c->flat);
-  LAUNCHCHK(c, "k_gather_proprio");
+  if (!proprio_done) {  // (the first convolution's kernel copies the proprioception when it is the LDS-ring form)
+    hipLaunchKernelGGL(k_gather_proprio, dim3(cdiv((int64_t)n * c->P, 256)), dim3(256), 0, c->stream, c->proprio, idx, n, c->P, c->feat, (int64_t)c->feat_ld, V * c->flat);
+    LAUNCHCHK(c, "k_gather_proprio");
+  }
   const bf16_t* x = c->feat; int64_t ldx = c->feat_ld;
   for (int l = 0; l < c->nfc; ++l) {
     ARows al = plain_arows(x, ldx, n, c->fin[l]);
