@@ -142,10 +142,6 @@ __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
 }
-__global__ void k_iota_i32(int32_t* p, int n, int32_t first) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = first + i;
-}
 __global__ void k_perm_hist(uint64_t stream, int S, int shift, int32_t* __restrict__ hist) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= S) return;

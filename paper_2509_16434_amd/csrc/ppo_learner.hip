@@ -728,12 +728,14 @@ int launch_conv0_fwd_tile_t(Ctx* c, Conv0Args a, int nimg) {
   return PPO_OK;
 }
 
-// Forward of `n` samples selected by device indices idx (NULL = 0..n-1 offset by `first`).
-int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true) {
+// Forward of `n` samples selected by device indices idx (NULL: samples first .. first + n - 1 of the buffer).
+int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true, int64_t first = 0) {
   const int V = c->V, nimg = n * V;
   bool proprio_done = false;
+  if (idx) first = 0;
+  const bf16_t* const proprio = c->proprio + first * c->P;
   {  // first convolution straight from the rollout buffer
-    ImgAddr in; in.base = c->obs; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
+    ImgAddr in; in.base = c->obs + first * c->img_elems * V; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
     int Co = c->cC[1], Ho = c->cH[1], Wo = c->cW[1];
     int64_t M = (int64_t)nimg * Ho * Wo;
     ProfScope ps(c, "conv_fwd.0", 2.0 * (double)M * Co * 9 * c->cC[0], 2.0 * ((double)nimg * c->img_elems + (double)M * Co));
@@ -743,7 +745,7 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true) {
     ca.in = in; ca.in.prepare(); ca.out = c->act[0]; ca.w = c->shadow + c->convW[0]; ca.bias = c->p + c->convB[0]; ca.zpage = c->zpage;
     ca.bits = c->nconv > 1 ? c->abits[0] : nullptr;
     ca.H = c->cH[0]; ca.W = c->cW[0]; ca.Ho = Ho; ca.Wo = Wo; ca.Cout = Co; ca.TR = 0; ca.NB = 0; ca.ntiles = 0;
-    ca.tile_blocks = 0; ca.gather_blocks = 1; ca.pB = n; ca.P = c->P; ca.pcol0 = V * c->flat; ca.proprio = c->proprio; ca.feat = c->feat; ca.feat_ld = c->feat_ld;
+    ca.tile_blocks = 0; ca.gather_blocks = 1; ca.pB = n; ca.P = c->P; ca.pcol0 = V * c->flat; ca.proprio = proprio; ca.feat = c->feat; ca.feat_ld = c->feat_ld;
     int trc = c->cC[0] == 1 ? launch_conv0_fwd_tile_t<1>(c, ca, nimg) : (c->cC[0] == 3 ? launch_conv0_fwd_tile_t<3>(c, ca, nimg) : 1);
     if (trc != PPO_OK && trc != 1) return trc;
     c->abits_ok[0] = trc == PPO_OK && c->nconv > 1;
@@ -774,7 +776,7 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true) {
     if (rc) return rc;
   }
   if (!proprio_done) {  // (the first convolution's kernel copies the proprioception when it is the LDS-ring form)
-    hipLaunchKernelGGL(k_gather_proprio, dim3(cdiv((int64_t)n * c->P, 256)), dim3(256), 0, c->stream, c->proprio, idx, n, c->P, c->feat, (int64_t)c->feat_ld, V * c->flat);
+    hipLaunchKernelGGL(k_gather_proprio, dim3(cdiv((int64_t)n * c->P, 256)), dim3(256), 0, c->stream, proprio, idx, n, c->P, c->feat, (int64_t)c->feat_ld, V * c->flat);
     LAUNCHCHK(c, "k_gather_proprio");
   }
   const bf16_t* x = c->feat; int64_t ldx = c->feat_ld;
@@ -1428,13 +1430,7 @@ int ppo_forward(ppo_ctx* c, const int32_t* d_idx, int64_t count, float* d_mu, fl
   for (int64_t c0 = 0; c0 < count; c0 += c->CH) {
     int n = (int)((count - c0 < c->CH) ? count - c0 : c->CH);
     const int32_t* idx = d_idx ? d_idx + c0 : nullptr;
-    if (!d_idx) {
-      // identity indices: reuse the permutation scratch
-      hipLaunchKernelGGL(k_iota_i32, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->ptmp, n, (int32_t)c0);
-      LAUNCHCHK(c, "k_iota_i32");
-      idx = c->ptmp;
-    }
-    int rc = forward_chunk(c, idx, n);
+    int rc = forward_chunk(c, idx, n, true, c0);  // without indices: samples c0 .. c0 + n - 1
     if (rc) return rc;
     hipLaunchKernelGGL(k_copy_heads, dim3(cdiv((int64_t)n * HEAD_LD, 256)), dim3(256), 0, c->stream, n, c->A, c->d.has_value_head, c->headout,
                        d_mu + c0 * c->A, d_v ? d_v + c0 : nullptr);
@@ -1458,9 +1454,7 @@ int ppo_act(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, co
   const int64_t first = (int64_t)t * c->N;
   for (int64_t c0 = 0; c0 < c->N; c0 += c->CH) {
     const int n = (int)((c->N - c0 < c->CH) ? c->N - c0 : c->CH);
-    hipLaunchKernelGGL(k_iota_i32, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, c->ptmp, n, (int32_t)(first + c0));
-    LAUNCHCHK(c, "k_iota_i32");
-    rc = forward_chunk(c, c->ptmp, n);
+    rc = forward_chunk(c, nullptr, n, true, first + c0);
     if (rc) return rc;
     ProfScope ps(c, "act_sample", 0.0, (double)n * (4.0 * HEAD_LD + 12.0 * c->A + 8.0));
     const int64_t s0 = first + c0;
