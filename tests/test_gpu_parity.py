@@ -295,7 +295,9 @@ def test_ppo_single_minibatch_gradients(L, ci, N, T, chunk):
 # image, an image height whose first-layer output is odd.
 # (50, 96) and (36, 80) have a first-layer output width that is a multiple of 8: the register-fused
 # first-layer weight gradient takes them (odd output height, bands that do not divide the image).
-ODD_SHAPES = [(52, 76), (50, 72), (44, 88), (50, 96), (36, 80)]
+ODD_SHAPES = [(52, 76), (50, 72), (44, 88), (50, 96), (36, 80),
+              # small and tall images, an odd height, several bands per image, rows of 13 to 15 sixteen-byte pieces
+              (24, 40), (70, 56), (33, 64), (16, 16), (90, 120), (28, 104)]
 
 
 @pytest.mark.parametrize("h,w", ODD_SHAPES)
