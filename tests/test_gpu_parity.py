@@ -587,6 +587,24 @@ def test_distill_single_minibatch_gradients(L, chunk, act_dim):
     assert max(per_tensor_errors(cfg["net"], lrn.get_grads(), og).values()) <= 0.15
 
 
+@pytest.mark.parametrize("h,w", [(44, 72), (52, 100), (30, 48)])
+def test_distill_gradients_odd_image_shapes(L, h, w):
+    """RGB views whose rows are and are not multiples of 16 bytes (the register-fused, the LDS-fused and the
+    implicit-GEMM form of the second layer's backward) and bands that do not divide the image."""
+    cfg = configs.get_config(3, num_envs=128, horizon=4)
+    cfg["net"].update(in_h=h, in_w=w)
+    lrn, ro, params = _setup(L, cfg)
+    hp = dict(cfg["hp"], minibatches=1, seed=5)
+    st = lrn.distill_update(hp)[0]
+    fr = flat_rollout(ro)
+    with orc.quant(1):
+        qst, qg = orc.distill_loss_grad(cfg["net"], params, fr["obs"], fr["proprio"], fr["action"])
+    assert abs(st["total_loss"] - qst["total"]) <= TOL_BF16 * abs(qst["total"])
+    assert abs(st["grad_norm"] - qst["grad_norm"]) <= TOL_BF16 * qst["grad_norm"]
+    errs = per_tensor_errors(cfg["net"], lrn.get_grads(), qg)
+    assert max(errs.values()) <= TOL_BF16, errs
+
+
 def test_distill_update_matches_oracle(L):
     cfg = _stereo_cfg(64, 4)
     lrn, ro, params = _setup(L, cfg)
