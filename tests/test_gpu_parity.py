@@ -555,6 +555,27 @@ def test_ppo_update_matches_oracle(L, ci, N, T, extras):
     assert step == out["step"] == hp["epochs"] * hp["minibatches"] and upd == 1
 
 
+@pytest.mark.parametrize("ci,N,T,M", [(0, 2, 2, 4), (0, 3, 1, 1), (1, 1, 1, 1), (1, 5, 3, 3)])
+def test_tiny_batches(L, ci, N, T, M):
+    """Degenerate sizes: minibatches of one to five samples.  Loss statistics of the first step against the oracle."""
+    torch = _torch()
+    cfg = configs.get_config(ci, num_envs=N, horizon=T)
+    lrn, ro, params = _setup(L, cfg)
+    hp = dict(cfg["hp"], epochs=1, minibatches=M, seed=2)
+    lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
+    stats = lrn.update(hp)
+    assert len(stats) == M and all(s["nonfinite"] == 0 for s in stats)
+    fr, adv, ret = _oracle_inputs(cfg, ro, lrn)
+    B = N * T // M
+    sel = orc.permutation(hp["seed"], 0, 0, N * T)[:B]
+    with orc.quant(1):
+        qst, _ = orc.ppo_loss_grad(cfg["net"], params, fr["obs"][sel], fr["proprio"][sel], fr["action"][sel], fr["logp_old"][sel],
+                                   fr["value"][sel], adv[sel], ret[sel], clip_eps=hp["clip_eps"], vclip_eps=hp["vclip_eps"],
+                                   vf_coef=hp["vf_coef"], ent_coef=hp["ent_coef"])
+    for k_gpu, k_or in (("pi_loss", "pi_loss"), ("v_loss", "v_loss"), ("total_loss", "total")):
+        assert abs(stats[0][k_gpu] - qst[k_or]) <= TOL_BF16 * max(abs(qst[k_or]), 1e-2), (k_gpu, stats[0][k_gpu], qst[k_or])
+
+
 def _stereo_cfg(N, T):
     """The stereo student of config 3 at half resolution (60x80 per view), so that the oracle can
     afford minibatches large enough for a meaningful gradient comparison (two bf16-operand
