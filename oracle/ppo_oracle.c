@@ -64,10 +64,12 @@ typedef struct {
 typedef struct {
   double lr, beta1, beta2, eps;
   double max_grad_norm; /* <= 0: no clipping */
+  double desired_kl;    /* > 0: KL-adaptive learning rate (PPO only), see update_loop */
+  double lr_min, lr_max;
 } orc_adam_cfg;
 
 /* stats slots */
-enum { ST_PI = 0, ST_V, ST_ENT, ST_KL, ST_CLIPFRAC, ST_GNORM, ST_TOTAL, ST_N };
+enum { ST_PI = 0, ST_V, ST_ENT, ST_KL, ST_CLIPFRAC, ST_GNORM, ST_TOTAL, ST_LR, ST_N };
 
 /* ------------------------------------------------------------------ */
 /* geometry                                                            */
@@ -628,6 +630,13 @@ void orc_normalize_adv(int64_t S, const double *adv, double *out) {
  * stay fixed for the whole update.  *step is the Adam step counter (in/out).
  * With ac->max_grad_norm > 0 the gradient is clipped to that global norm before the Adam step
  * (the grad-norm statistic stays the norm before clipping).
+ * With ac->desired_kl > 0 (PPO only) the learning rate follows the divergence between the behaviour
+ * policy and the current one, measured on each minibatch before its step by the sample estimate
+ * kl = mean((rho - 1) - log rho) the loss already reports: kl > 2 desired_kl divides the rate by 1.5
+ * (not below lr_min), kl < desired_kl / 2 multiplies it by 1.5 (not above lr_max); the new rate is the
+ * one this minibatch's Adam step uses and the next minibatch starts from.  The paper names no
+ * schedule; this is the usual one of on-policy robot-learning code, with the sampled estimate in
+ * place of the closed-form Gaussian divergence.  stats[.][ST_LR] is the rate each step used.
  * stats: [epochs*minibatches][ST_N]; grads_last: gradients of the last minibatch. */
 static void update_loop(const orc_net *n, double *params, double *m, double *v, int64_t *step,
                         int64_t S, const float *obs, const double *proprio, const double *action,
@@ -646,6 +655,7 @@ static void update_loop(const orc_net *n, double *params, double *m, double *v, 
   double *mlp = (double *)calloc((size_t)B, sizeof(double)), *mvo = (double *)calloc((size_t)B, sizeof(double));
   double *mad = (double *)calloc((size_t)B, sizeof(double)), *mre = (double *)calloc((size_t)B, sizeof(double));
   double *grads = (double *)malloc(sizeof(double) * (size_t)g.total);
+  orc_adam_cfg cur = *ac;
   for (int e = 0; e < epochs; ++e) {
     orc_permutation(seed, update_idx, (uint64_t)e, S, perm);
     for (int mb = 0; mb < minibatches; ++mb) {
@@ -662,8 +672,14 @@ static void update_loop(const orc_net *n, double *params, double *m, double *v, 
       /* the gradient reported for the last minibatch is the one before clipping */
       if (grads_last && e == epochs - 1 && mb == minibatches - 1)
         memcpy(grads_last, grads, sizeof(double) * (size_t)g.total);
+      if (!distill && ac->desired_kl > 0) {
+        double kl = st[ST_KL];
+        if (kl > 2.0 * ac->desired_kl) cur.lr = fmax(ac->lr_min, cur.lr / 1.5);
+        else if (kl < 0.5 * ac->desired_kl) cur.lr = fmin(ac->lr_max, cur.lr * 1.5);
+      }
+      st[ST_LR] = cur.lr;
       orc_clip_grad_norm(g.total, grads, ac->max_grad_norm);
-      orc_adam_step(g.total, params, m, v, grads, *step, ac);
+      orc_adam_step(g.total, params, m, v, grads, *step, &cur);
     }
   }
   free(perm); free(mobs); free(mpro); free(mact); free(mlp); free(mvo); free(mad); free(mre); free(grads);

@@ -18,7 +18,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ppo_oracle.c")
 _LIB = os.path.join(_HERE, "libppo_oracle.so")
-ST_NAMES = ("pi_loss", "v_loss", "entropy", "approx_kl", "clip_frac", "grad_norm", "total")
+ST_NAMES = ("pi_loss", "v_loss", "entropy", "approx_kl", "clip_frac", "grad_norm", "total", "lr")
 ST_N = len(ST_NAMES)
 MAXL = 8
 
@@ -46,7 +46,8 @@ class _LossCfg(C.Structure):
 
 class _AdamCfg(C.Structure):
     _fields_ = [("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
-                ("max_grad_norm", C.c_double)]
+                ("max_grad_norm", C.c_double), ("desired_kl", C.c_double), ("lr_min", C.c_double),
+                ("lr_max", C.c_double)]
 
 
 _lib = None
@@ -269,7 +270,8 @@ def _update(fn_name, net, params, m, v, step, obs, proprio, action, extra, hp, u
     gl = np.zeros(params.size)
     stp = C.c_int64(step)
     ac = _AdamCfg(hp.get("lr", 3e-4), hp.get("beta1", 0.9), hp.get("beta2", 0.999), hp.get("adam_eps", 1e-8),
-                  hp.get("max_grad_norm", 0.0))
+                  hp.get("max_grad_norm", 0.0), hp.get("desired_kl", 0.0), hp.get("lr_min", 1e-5),
+                  hp.get("lr_max", 1e-2))
     if fn_name == "ppo":
         logp_old, v_old, adv, ret = (_d(x) for x in extra)
         lc = _LossCfg(hp.get("clip_eps", 0.2), hp.get("vclip_eps", 0.0), hp.get("vf_coef", 0.5),
@@ -289,7 +291,8 @@ def _update(fn_name, net, params, m, v, step, obs, proprio, action, extra, hp, u
 def ppo_update(net, params, m, v, step, obs, proprio, action, logp_old, v_old, adv, ret, hp, update_idx=0):
     """Whole PPO update over flat samples s = t*N + n.  Returns new params/m/v/step, stats, last grads.
     hp["norm_adv"]: advantages normalised over the whole rollout first; hp["max_grad_norm"] > 0: global
-    gradient-norm clipping before every Adam step."""
+    gradient-norm clipping before every Adam step; hp["desired_kl"] > 0: KL-adaptive learning rate between
+    hp["lr_min"] and hp["lr_max"], starting from hp["lr"] (stats[i]["lr"] is the rate step i used)."""
     if hp.get("norm_adv", 0):
         adv = normalize_adv(adv)
     return _update("ppo", net, params, m, v, step, obs, proprio, action, (logp_old, v_old, adv, ret), hp,

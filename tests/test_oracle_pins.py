@@ -5,6 +5,7 @@ import math
 import numpy as np
 import pytest
 import torch
+from scipy.stats import norm
 
 from oracle import ppo_oracle as orc
 from paper_2509_16434_amd import configs, synth
@@ -273,7 +274,7 @@ def test_act_zero_noise_is_the_mean_with_closed_form_logp():
 
 
 def test_act_offset_is_sigma_times_noise_and_logp_is_library_density():
-    from scipy.stats import norm
+
     p, b, noise, sigma = _act_setup(41)
     mu, _ = orc.forward(TINY, p, b["obs"], b["proprio"])
     a, logp, _ = orc.act(TINY, p, b["obs"], b["proprio"], noise)
@@ -504,6 +505,95 @@ def test_update_loop_against_library_recomposition(extras):
             k += 1
     assert out["step"] == E * M
     np.testing.assert_allclose(out["params"], p.detach().numpy(), rtol=1e-9, atol=1e-12)
+
+
+def _torch_kl_estimate(mu, ls, action, logp_old):
+    logp = torch.distributions.Normal(mu, ls.exp()).log_prob(torch.as_tensor(action)).sum(-1)
+    d = logp - torch.as_tensor(logp_old)
+    return float(((d.exp() - 1.0) - d).mean())
+
+
+def test_adaptive_learning_rate_against_library_recomposition():
+    """KL-adaptive learning rate: the loop re-composed from autograd + optim.Adam with the rate of the
+    parameter group moved by the rule, the divergence estimated on the library side from
+    torch.distributions log-probabilities.  The target is chosen so that the rate moves both ways."""
+    net = TINY
+    N, T, E, M = 6, 4, 3, 4
+    S = N * T
+    b, params = _batch(net, S, 60), _params(net, 61)
+    lp = orc.act(net, params, b["obs"], b["proprio"], np.zeros_like(b["action"]))[1]   # start on-policy: kl = 0
+    b["logp_old"] = lp + 0.0
+    b["action"] = orc.forward(net, params, b["obs"], b["proprio"])[0]                  # the means: zero noise
+    hp = dict(epochs=E, minibatches=M, clip_eps=0.2, vclip_eps=0.0, vf_coef=0.5, ent_coef=0.0, lr=2e-3, seed=5,
+              desired_kl=2e-5, lr_min=5e-4, lr_max=4e-3)
+    out = orc.ppo_update(net, params, np.zeros_like(params), np.zeros_like(params), 0, b["obs"], b["proprio"],
+                         b["action"], b["logp_old"], b["v_old"], b["adv"], b["ret"], hp, update_idx=1)
+    p, sl = torch_ref.unpack(net, params)
+    opt = torch.optim.Adam([p], lr=hp["lr"])
+    lr, k, moves = hp["lr"], 0, []
+    for e in range(E):
+        perm = orc.permutation(5, 1, e, S)
+        for mb in range(M):
+            idx = perm[mb * (S // M):(mb + 1) * (S // M)]
+            opt.zero_grad()
+            mu, v, ls = torch_ref.forward(net, p, sl, b["obs"][idx], b["proprio"][idx])
+            loss, _ = torch_ref.ppo_loss(mu, v, ls, b["action"][idx], b["logp_old"][idx], b["v_old"][idx],
+                                         b["adv"][idx], b["ret"][idx], 0.2, 0.0, 0.5, 0.0)
+            loss.backward()
+            kl = _torch_kl_estimate(mu.detach(), ls.detach(), b["action"][idx], b["logp_old"][idx])
+            assert abs(kl - out["stats"][k]["approx_kl"]) < 1e-12
+            assert min(abs(kl / (2 * hp["desired_kl"]) - 1), abs(kl / (0.5 * hp["desired_kl"]) - 1)) > 1e-6  # no tie
+            old = lr
+            if kl > 2 * hp["desired_kl"]:
+                lr = max(hp["lr_min"], lr / 1.5)
+            elif kl < 0.5 * hp["desired_kl"]:
+                lr = min(hp["lr_max"], lr * 1.5)
+            moves.append(np.sign(lr - old))
+            for gr in opt.param_groups:
+                gr["lr"] = lr
+            assert out["stats"][k]["lr"] == pytest.approx(lr, rel=1e-14)
+            opt.step()
+            k += 1
+    assert moves[0] == 1 and -1 in moves and 0 in moves   # first step: kl = 0, the rate goes up; later it holds and falls
+    np.testing.assert_allclose(out["params"], p.detach().numpy(), rtol=1e-9, atol=1e-12)
+
+
+def test_adaptive_learning_rate_bounds_and_off():
+    net = TINY
+    S = 12
+    b, params = _batch(net, S, 62), _params(net, 63)
+    z = np.zeros_like(params)
+    base = dict(epochs=4, minibatches=2, clip_eps=0.2, vf_coef=0.5, lr=1e-3, seed=1, lr_min=4e-4, lr_max=3e-3)
+    run = lambda **kw: orc.ppo_update(net, params, z, z, 0, b["obs"], b["proprio"], b["action"], b["logp_old"],
+                                      b["v_old"], b["adv"], b["ret"], dict(base, **kw))
+    up = [s["lr"] for s in run(desired_kl=1e9)["stats"]]        # always far below the target: x1.5 up to the cap
+    assert up == pytest.approx([min(3e-3, 1e-3 * 1.5 ** (k + 1)) for k in range(8)], rel=1e-14)
+    down = [s["lr"] for s in run(desired_kl=1e-12)["stats"]]    # always above: /1.5 down to the floor
+    assert down == pytest.approx([max(4e-4, 1e-3 / 1.5 ** (k + 1)) for k in range(8)], rel=1e-14)
+    off, off2 = run(desired_kl=0.0), run()
+    assert [s["lr"] for s in off["stats"]] == [1e-3] * 8
+    np.testing.assert_array_equal(off["params"], off2["params"])
+    # distillation ignores the option
+    d = orc.distill_update(net, params, z, z, 0, b["obs"], b["proprio"], b["action"], dict(base, desired_kl=1e9))
+    assert [s["lr"] for s in d["stats"]] == [1e-3] * 8
+
+
+def test_sampled_kl_estimate_is_the_gaussian_divergence():
+    """What the schedule reacts to: mean((rho - 1) - log rho) over actions drawn from the behaviour policy
+    estimates KL(old || new); checked against the closed form of the library for two diagonal Gaussians."""
+    rng = np.random.default_rng(64)
+    B, A = 400_000, 5
+    mu_o, ls_o = rng.standard_normal(A) * 0.3, rng.standard_normal(A) * 0.1 - 0.5
+    mu_n, ls_n = mu_o + rng.standard_normal(A) * 0.08, ls_o + rng.standard_normal(A) * 0.05
+    act = mu_o + np.exp(ls_o) * rng.standard_normal((B, A))
+    lpo = norm.logpdf(act, mu_o, np.exp(ls_o)).sum(-1)
+    st = orc.ppo_loss(np.tile(mu_n, (B, 1)), np.zeros(B), ls_n, act, lpo, np.zeros(B), np.zeros(B), np.zeros(B),
+                      want_grads=False)[0]
+    D = torch.distributions
+    want = float(D.kl_divergence(D.Normal(torch.tensor(mu_o), torch.tensor(ls_o).exp()),
+                                 D.Normal(torch.tensor(mu_n), torch.tensor(ls_n).exp())).sum())
+    assert want > 0.01
+    assert abs(st["approx_kl"] - want) < 0.02 * want
 
 
 def test_param_counts_of_the_workloads():
