@@ -74,9 +74,19 @@ typedef struct {
   float vf_coef, ent_coef;
   float lr, beta1, beta2, adam_eps;
   float max_grad_norm;          /* > 0: global gradient-norm clipping, g *= min(1, c / (||g|| + 1e-6)), before every Adam step; <= 0: off */
+  float desired_kl;             /* > 0 (ppo_update only): KL-adaptive learning rate.  Before each Adam step the rate
+                                   follows the minibatch's approx_kl = mean((rho-1) - log rho), the sampled estimate of
+                                   KL(behaviour policy || current policy): approx_kl > 2 desired_kl divides it by 1.5
+                                   (not below lr_min), approx_kl < desired_kl / 2 multiplies it by 1.5 (not above
+                                   lr_max).  The rate starts from `lr` and lives on the device (no host round trip);
+                                   ppo_mb_stats.lr reports what each step used.  <= 0: off, every step uses `lr`.
+                                   The paper gives no schedule (Sec. III-C); this is the common one of on-policy code. */
+  float lr_min, lr_max;         /* bounds of the adaptive rate; 0 < lr_min <= lr_max when desired_kl > 0 */
   int32_t epochs, minibatches;  /* num_envs*horizon must be divisible by minibatches */
   int32_t norm_adv;             /* 1: advantages normalised once per update over the whole rollout,
                                    (A - mean) / (population std + 1e-8); 0: raw advantages */
+  int32_t lr_carry;             /* with desired_kl > 0: 1 = start from the rate the previous adaptive update of this
+                                   context ended with (if there was one; else from `lr`), 0 = start from `lr` */
   uint64_t seed;                /* permutation stream seed */
 } ppo_hparams;
 
@@ -84,6 +94,7 @@ typedef struct {
 typedef struct {
   float pi_loss, v_loss, entropy, approx_kl, clip_frac, grad_norm, total_loss;
   int32_t nonfinite; /* 1 if the total loss was not finite */
+  float lr;          /* learning rate this step's Adam update used */
 } ppo_mb_stats;
 
 /* Create a learner for `desc` on the current HIP device; all device memory is

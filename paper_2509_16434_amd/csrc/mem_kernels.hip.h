@@ -585,17 +585,24 @@ __global__ __launch_bounds__(256) void k_loss(int B, LossData L, const float* __
 }
 
 // Device-side record of one optimiser step (mirrors the host ppo_mb_stats layout).
-struct DevStats { float pi_loss, v_loss, entropy, approx_kl, clip_frac, grad_norm, total_loss; int32_t nonfinite; };
+struct DevStats { float pi_loss, v_loss, entropy, approx_kl, clip_frac, grad_norm, total_loss; int32_t nonfinite; float lr; };
 
 // Sum the per-block partials of one minibatch (all chunks) in block order; write the loss
 // statistics and the log-std gradient (which also carries the entropy bonus).  The work of one
 // block of 256 threads; it rides along as the last block of the backward pass's reduction launch.
+// With desired_kl > 0 it also moves the learning rate kept in *lr_dev by the minibatch's approx_kl
+// (above 2 desired_kl: / 1.5, not below lr_min; below desired_kl / 2: x 1.5, not above lr_max); the
+// Adam step that follows reads the rate from there.  lr_reset: the rate starts from lr_init
+// instead of the stored one (first step of an update).
 struct LossFinalize {
   int on, nblocks, Bfull, A, distill;
   const float *stat_part, *dls_part, *logstd;
   float vf_coef, ent_coef;
   DevStats* st;
   float* g_logstd;
+  float desired_kl, lr_min, lr_max, lr_init;
+  int lr_reset;
+  float* lr_dev;
 };
 __device__ __forceinline__ void loss_finalize_block(const LossFinalize& f) {
   // column c (4 statistics, then the A log-std gradients) is summed by 8 lanes, lane j taking
@@ -627,6 +634,15 @@ __device__ __forceinline__ void loss_finalize_block(const LossFinalize& f) {
       st->approx_kl = tot[2] * invB; st->clip_frac = tot[3] * invB;
       st->total_loss = st->pi_loss + f.vf_coef * st->v_loss - f.ent_coef * ent;
     }
+    float lr = f.lr_init;
+    if (!f.distill && f.desired_kl > 0.f) {
+      if (!f.lr_reset) lr = *f.lr_dev;
+      const float kl = st->approx_kl;
+      if (kl > 2.f * f.desired_kl) lr = fmaxf(f.lr_min, lr / 1.5f);
+      else if (kl < 0.5f * f.desired_kl) lr = fminf(f.lr_max, lr * 1.5f);
+      *f.lr_dev = lr;
+    }
+    st->lr = lr;
     st->nonfinite = isfinite(st->total_loss) ? 0 : 1;
   }
 }
@@ -683,14 +699,16 @@ __global__ __launch_bounds__(256) void k_reduce_batch(ReduceJobs jobs, LossFinal
 // c2 = 1-b2^k passed in.  Also refreshes the bf16 copy of the parameters and leaves per-block sums
 // of g^2 for the gradient-norm statistic.  With gradient-norm clipping the gradient enters as
 // g * *clip_coef (the coefficient min(1, c / (||g|| + 1e-6)) left by k_gnorm_finalize); the sums
-// of g^2 are of the gradient before clipping either way.
+// of g^2 are of the gradient before clipping either way.  lr_dev (if not null) holds the rate
+// instead of the argument: the KL-adaptive schedule keeps it on the device.
 __global__ __launch_bounds__(256) void k_adam(int64_t n, float* __restrict__ p, float* __restrict__ m,
                                               float* __restrict__ v, const float* __restrict__ g,
                                               bf16_t* __restrict__ shadow, float lr, float b1, float b2, float eps,
                                               float inv_c1, float inv_c2, float* __restrict__ sq_part,
-                                              const float* __restrict__ clip_coef) {
+                                              const float* __restrict__ clip_coef, const float* __restrict__ lr_dev) {
   __shared__ float red[256];
   const int tid = threadIdx.x;
+  if (lr_dev) lr = *lr_dev;
   const float coef = clip_coef ? *clip_coef : 1.f;
   float sq = 0.f;
   for (int64_t i = ((int64_t)blockIdx.x * 256 + tid) * 4; i < n; i += (int64_t)gridDim.x * 1024) {

@@ -84,6 +84,8 @@ struct Ctx {
   GnormFinalize gnfin = {}; // pending: rides as the last block of the next re-pack launch
   int rjob_blocks = 0;
   float *stat_part = nullptr, *dls_part = nullptr, *sq_part = nullptr, *clip_coef = nullptr;
+  float* lr_dev = nullptr;  // the KL-adaptive learning rate (desired_kl > 0); lr_live: an adaptive update has left a rate there
+  bool lr_live = false;
   float* adv_n = nullptr;  // advantages normalised over the rollout (norm_adv)
   int max_loss_blocks = 0, adam_blocks = 0;
   DevStats* dstats = nullptr;
@@ -193,12 +195,15 @@ int validate_desc(const ppo_net_desc* d) {
 
 int validate_hp(Ctx* c, const ppo_hparams* hp, bool distill) {
   if (!hp) return fail(c, PPO_EINVAL, "hparams is NULL");
-  const float f[] = {hp->clip_eps, hp->vclip_eps, hp->vf_coef, hp->ent_coef, hp->lr, hp->beta1, hp->beta2, hp->adam_eps, hp->max_grad_norm};
+  const float f[] = {hp->clip_eps, hp->vclip_eps, hp->vf_coef, hp->ent_coef, hp->lr, hp->beta1, hp->beta2, hp->adam_eps, hp->max_grad_norm, hp->desired_kl};
   for (float x : f) if (!isfinite(x)) return fail(c, PPO_EINVAL, "non-finite hyper-parameter");
   if (!distill && !(hp->clip_eps > 0.f)) return fail(c, PPO_EINVAL, "clip_eps must be > 0");
   if (!(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) || !(hp->adam_eps > 0.f))
     return fail(c, PPO_EINVAL, "Adam hyper-parameters out of range");
   if (hp->norm_adv != 0 && hp->norm_adv != 1) return fail(c, PPO_EINVAL, "norm_adv must be 0 or 1");
+  if (hp->lr_carry != 0 && hp->lr_carry != 1) return fail(c, PPO_EINVAL, "lr_carry must be 0 or 1");
+  if (!distill && hp->desired_kl > 0.f && !(isfinite(hp->lr_min) && isfinite(hp->lr_max) && hp->lr_min > 0.f && hp->lr_min <= hp->lr_max))
+    return fail(c, PPO_EINVAL, "desired_kl > 0 needs 0 < lr_min <= lr_max");
   if (hp->epochs < 1 || hp->minibatches < 1) return fail(c, PPO_EINVAL, "epochs and minibatches must be >= 1");
   if (c->S % hp->minibatches) return fail(c, PPO_ESHAPE, "num_envs*horizon = %d is not divisible by minibatches = %d", c->S, hp->minibatches);
   if ((int64_t)hp->epochs * hp->minibatches > c->max_steps) return fail(c, PPO_ESHAPE, "epochs*minibatches exceeds %d", c->max_steps);
@@ -980,6 +985,7 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
   const int steps = hp->epochs * hp->minibatches;
   const int blocks_per_chunk = cdiv(c->CH, LOSS_BLOCK);
   int k = 0;
+  const bool adaptive = !distill && hp->desired_kl > 0.f;  // the learning rate lives on the device and follows approx_kl
   if (!distill && hp->norm_adv) {
     ProfScope ps(c, "adv_normalize", 0.0, 12.0 * c->S);
     hipLaunchKernelGGL(k_adv_normalize, dim3(1), dim3(1024), 0, c->stream, c->S, c->adv, c->adv_n);
@@ -1029,6 +1035,8 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
           f.on = 1; f.nblocks = nblocks; f.Bfull = B; f.A = c->A; f.distill = distill ? 1 : 0; f.stat_part = c->stat_part; f.dls_part = c->dls_part;
           f.logstd = distill ? nullptr : c->p + c->logstd; f.vf_coef = hp->vf_coef; f.ent_coef = hp->ent_coef; f.st = c->dstats + k;
           f.g_logstd = distill ? nullptr : c->g + c->logstd;
+          f.desired_kl = adaptive ? hp->desired_kl : 0.f; f.lr_min = hp->lr_min; f.lr_max = hp->lr_max; f.lr_init = hp->lr; f.lr_dev = c->lr_dev;
+          f.lr_reset = (k == 0 && !(hp->lr_carry && c->lr_live)) ? 1 : 0;
         }
         rc = backward_chunk(c, idx + c0, n, c0 > 0, !head_done);
         if (rc) return rc;
@@ -1047,7 +1055,8 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
         LAUNCHCHK(c, "k_gnorm_finalize");
       }
       hipLaunchKernelGGL(k_adam, dim3(c->adam_blocks), dim3(256), 0, c->stream, c->total, c->p, c->m, c->v, c->g, c->shadow, hp->lr, hp->beta1, hp->beta2,
-                         hp->adam_eps, (float)(1.0 / c1), (float)(1.0 / c2), c->sq_part, clip ? c->clip_coef : nullptr);
+                         hp->adam_eps, (float)(1.0 / c1), (float)(1.0 / c2), c->sq_part, clip ? c->clip_coef : nullptr,
+                         adaptive ? c->lr_dev : nullptr);
       LAUNCHCHK(c, "k_adam");
       if (!clip) {  // the step's gradient norm: one more block of the re-pack launch that follows
         GnormFinalize& gf = c->gnfin;
@@ -1059,6 +1068,7 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
     }
   }
   c->update_idx += 1;
+  if (adaptive) c->lr_live = true;
   if (host_stats) {
     HIPCHK(c, hipMemcpyAsync(host_stats, c->dstats, sizeof(DevStats) * (size_t)steps, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -1156,7 +1166,7 @@ int create_impl(Ctx* c) {
   DALLOC(c, c->stat_part, (int64_t)c->max_loss_blocks * LOSS_NSTAT); DALLOC(c, c->dls_part, (int64_t)c->max_loss_blocks * 32);
   c->adam_blocks = cdiv(c->total, 1024); if (c->adam_blocks > 2048) c->adam_blocks = 2048;
   DALLOC(c, c->sq_part, c->adam_blocks);
-  DALLOC(c, c->clip_coef, 1);
+  DALLOC(c, c->clip_coef, 1); DALLOC(c, c->lr_dev, 1);
   DALLOC(c, c->dstats, c->max_steps);
   HIPCHK(c, hipMemsetAsync(c->p, 0, sizeof(float) * (size_t)c->total, c->stream));
   HIPCHK(c, hipMemsetAsync(c->m, 0, sizeof(float) * (size_t)c->total, c->stream));

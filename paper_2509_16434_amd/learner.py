@@ -36,11 +36,13 @@ class HParams(C.Structure):
     _fields_ = [("gamma", C.c_float), ("lam", C.c_float), ("clip_eps", C.c_float), ("vclip_eps", C.c_float),
                 ("vf_coef", C.c_float), ("ent_coef", C.c_float), ("lr", C.c_float), ("beta1", C.c_float),
                 ("beta2", C.c_float), ("adam_eps", C.c_float), ("max_grad_norm", C.c_float),
-                ("epochs", C.c_int32), ("minibatches", C.c_int32), ("norm_adv", C.c_int32), ("seed", C.c_uint64)]
+                ("desired_kl", C.c_float), ("lr_min", C.c_float), ("lr_max", C.c_float),
+                ("epochs", C.c_int32), ("minibatches", C.c_int32), ("norm_adv", C.c_int32), ("lr_carry", C.c_int32),
+                ("seed", C.c_uint64)]
 
 
 class MbStats(C.Structure):
-    _fields_ = [(f, C.c_float) for f in STAT_FIELDS] + [("nonfinite", C.c_int32)]
+    _fields_ = [(f, C.c_float) for f in STAT_FIELDS] + [("nonfinite", C.c_int32), ("lr", C.c_float)]
 
 
 class LearnerError(RuntimeError):
@@ -120,6 +122,8 @@ def make_hparams(hp: dict) -> HParams:
     h.vf_coef, h.ent_coef = hp.get("vf_coef", 0.5), hp.get("ent_coef", 0.0)
     h.lr, h.beta1, h.beta2, h.adam_eps = hp.get("lr", 3e-4), hp.get("beta1", 0.9), hp.get("beta2", 0.999), hp.get("adam_eps", 1e-8)
     h.max_grad_norm = hp.get("max_grad_norm", 0.0)
+    h.desired_kl, h.lr_min, h.lr_max = hp.get("desired_kl", 0.0), hp.get("lr_min", 1e-5), hp.get("lr_max", 1e-2)
+    h.lr_carry = hp.get("lr_carry", 0)
     h.epochs, h.minibatches, h.norm_adv = hp["epochs"], hp["minibatches"], hp.get("norm_adv", 0)
     h.seed = hp.get("seed", 0)
     return h
@@ -288,7 +292,7 @@ class Learner:
         n = hp["epochs"] * hp["minibatches"]
         st = (MbStats * n)()
         self._chk(fn(self._h, C.byref(h), st))
-        return [dict({f: float(getattr(s, f)) for f in STAT_FIELDS}, nonfinite=int(s.nonfinite)) for s in st]
+        return [dict({f: float(getattr(s, f)) for f in STAT_FIELDS}, nonfinite=int(s.nonfinite), lr=float(s.lr)) for s in st]
 
     def update(self, hp: dict, want_stats: bool = True):
         return self._run(_lib.ppo_update, hp, want_stats)

@@ -33,6 +33,17 @@ def test_the_four_path_entry_points_are_declared():
     assert {"ppo_buffer_write", "ppo_gae", "ppo_update", "distill_update"} <= names
 
 
+def test_struct_sizes_match_the_header_layout():
+    # ppo_hparams: 14 floats, 4 int32, one uint64; ppo_mb_stats: 7 floats, int32, float
+    assert C.sizeof(L.HParams) == 14 * 4 + 4 * 4 + 8 and L.HParams.seed.offset == 72
+    assert C.sizeof(L.MbStats) == 36 and L.MbStats.lr.offset == 32
+    text = open(HEADER).read()
+    body = text[text.index("float gamma, lambda;"):text.index("} ppo_hparams;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = re.findall(r"(\w+)\s*[,;]", body)
+    assert names == [("lambda" if f == "lam" else f) for f, _ in L.HParams._fields_]
+
+
 def test_header_is_plain_c():
     text = open(HEADER).read()
     assert 'extern "C"' in text and "torch" not in text and "std::" not in text

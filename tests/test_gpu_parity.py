@@ -555,6 +555,117 @@ def test_ppo_update_matches_oracle(L, ci, N, T, extras):
     assert step == out["step"] == hp["epochs"] * hp["minibatches"] and upd == 1
 
 
+def _rule32(lr, kl, d, lo, hi):
+    """The schedule in the kernel's precision."""
+    f = np.float32
+    lr, kl, d = f(lr), f(kl), f(d)
+    if kl > f(2.0) * d:
+        return max(f(lo), lr / f(1.5))
+    if kl < f(0.5) * d:
+        return min(f(hi), lr * f(1.5))
+    return lr
+
+
+def test_kl_adaptive_learning_rate(L):
+    """The device-resident learning rate: bounds and switch-off exactly; the rule applied to the library's own
+    approx_kl reproduces the reported rates; the Adam step really uses the reported rate; the rates agree with
+    the oracle's on a target its divergences stay clear of; lr_carry continues where the last update stopped."""
+    torch = _torch()
+    cfg = configs.get_config(0, num_envs=64, horizon=16)
+    base = dict(cfg["hp"], epochs=3, seed=21, lr_min=1e-4, lr_max=1.5e-3)
+    lr0, n = base["lr"], base["epochs"] * base["minibatches"]
+
+    def run(**kw):
+        lrn, ro, params = _setup(L, cfg)
+        lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), base["gamma"], base["lam"])
+        return lrn, ro, params, lrn.update(dict(base, **kw))
+
+    lrn_off, ro, params, st_off = run()
+    assert [s["lr"] for s in st_off] == [float(np.float32(lr0))] * n
+    _, _, _, st0 = run(desired_kl=0.0, lr_carry=1)
+    assert st0 == st_off                                                       # off: the other fields do nothing
+    up = [s["lr"] for s in run(desired_kl=1e9)[3]]
+    np.testing.assert_allclose(up, [min(1.5e-3, lr0 * 1.5 ** (k + 1)) for k in range(n)], rtol=1e-6)
+    down = [s["lr"] for s in run(desired_kl=1e-12)[3]]
+    np.testing.assert_allclose(down, [max(1e-4, lr0 / 1.5 ** (k + 1)) for k in range(n)], rtol=1e-6)
+
+    def own_rule(st, d):
+        lr, seq = lr0, []
+        for k, s in enumerate(st):                                              # the rule on the library's own numbers, exactly
+            lr = _rule32(lr, s["approx_kl"], d, base["lr_min"], base["lr_max"])
+            assert s["lr"] == float(lr), (k, s["lr"], lr)
+            seq.append(float(lr))
+        return seq
+
+    # thresholds inside the spread of the minibatch divergences: the rate moves on some steps and holds on others
+    kls = sorted(s["approx_kl"] for s in st_off)
+    med = 0.5 * (kls[n // 2 - 1] + kls[n // 2])
+    seq_a = own_rule(run(desired_kl=0.5 * med)[3], 0.5 * med)                   # upper threshold 2d at the median
+    seq_b = own_rule(run(desired_kl=2.0 * med)[3], 2.0 * med)                   # lower threshold d/2 at the median
+    assert len(set(seq_a)) >= 2 and len(set(seq_b)) >= 2
+    assert any(x == y for x, y in zip(seq_a, [lr0] + seq_a)) or any(x == y for x, y in zip(seq_b, [lr0] + seq_b))   # a hold
+
+    # against the oracle: a target (picked deterministically) that keeps the oracle's divergences clear of both thresholds
+    fr, adv, ret = _oracle_inputs(cfg, ro, lrn_off)
+    z = np.zeros_like(params, dtype=np.float64)
+    for d in (0.25 * med, 0.2 * med, 0.15 * med, 4.0 * med, 5.0 * med):
+        hp = dict(base, desired_kl=float(d))
+        with orc.quant(1):
+            out = orc.ppo_update(cfg["net"], params, z, z, 0, fr["obs"], fr["proprio"], fr["action"], fr["logp_old"], fr["value"],
+                                 adv, ret, hp, update_idx=0)
+        margin = min(min(abs(o["approx_kl"] / (2 * d) - 1), abs(o["approx_kl"] / (0.5 * d) - 1)) for o in out["stats"])
+        if margin > 0.15:
+            break
+    else:
+        pytest.fail("no target keeps the oracle's divergences clear of the thresholds")
+    lrn, _, _, st = run(desired_kl=float(d))
+    own_rule(st, d)
+    np.testing.assert_allclose([s["lr"] for s in st], [o["lr"] for o in out["stats"]], rtol=1e-6)
+    for s, o in zip(st, out["stats"]):
+        assert abs(s["approx_kl"] - o["approx_kl"]) <= 0.1 * o["approx_kl"] + 1e-6
+    _compare_update(L, cfg, lrn, ro, params, out, st, max(o["lr"] for o in out["stats"]))
+
+    # lr_carry: the next update goes on from the stored rate, or restarts from hp.lr
+    last = st[-1]["lr"]
+    st2 = lrn.update(dict(base, desired_kl=float(d), lr_carry=1))
+    assert st2[0]["lr"] == float(_rule32(last, st2[0]["approx_kl"], d, base["lr_min"], base["lr_max"]))
+    st3 = lrn.update(dict(base, desired_kl=float(d), lr_carry=0))
+    assert st3[0]["lr"] == float(_rule32(lr0, st3[0]["approx_kl"], d, base["lr_min"], base["lr_max"]))
+
+
+def test_kl_adaptive_rate_is_the_one_adam_uses(L):
+    """Single-minibatch updates with a target far above any divergence: each step's rate is 1.5 x the last, and the
+    oracle's Adam with the reported rate, applied to the reported gradient, reproduces the parameters."""
+    torch = _torch()
+    cfg = configs.get_config(0, num_envs=64, horizon=16)
+    lrn, ro, params = _setup(L, cfg)
+    hp = dict(cfg["hp"], epochs=1, minibatches=1, seed=3, desired_kl=1e9, lr_min=1e-5, lr_max=1.0, lr_carry=1)
+    lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
+    p = params.astype(np.float64)
+    m, v = np.zeros_like(p), np.zeros_like(p)
+    for k in (1, 2, 3):
+        st = lrn.update(hp)[0]
+        assert abs(st["lr"] / (hp["lr"] * 1.5 ** k) - 1) < 1e-6
+        g = lrn.get_grads().astype(np.float64)
+        orc.adam_step(p, m, v, g, k, lr=st["lr"], beta1=hp["beta1"], beta2=hp["beta2"], eps=hp["adam_eps"])
+        got = lrn.get_params().astype(np.float64)
+        assert np.abs(got - p).max() <= 1e-6 * max(1.0, np.abs(p).max()) + 2e-3 * st["lr"]
+        gm, gv, _, _ = lrn.get_opt_state()
+        p, m, v = got.copy(), gm.astype(np.float64), gv.astype(np.float64)
+
+
+def test_kl_adaptive_argument_errors(L):
+    cfg = configs.get_config(0, num_envs=8, horizon=2)
+    torch = _torch()
+    lrn, ro, params = _setup(L, cfg)
+    lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), 0.99, 0.95)
+    for bad in (dict(desired_kl=0.01, lr_min=0.0, lr_max=1e-2), dict(desired_kl=0.01, lr_min=1e-2, lr_max=1e-3),
+                dict(desired_kl=float("nan")), dict(lr_carry=2), dict(desired_kl=0.01, lr_min=1e-4, lr_max=float("inf"))):
+        with pytest.raises(L.LearnerError) as e:
+            lrn.update(dict(cfg["hp"], **bad))
+        assert e.value.code == L.PPO_EINVAL, bad
+
+
 @pytest.mark.parametrize("ci,N,T,M", [(0, 2, 2, 4), (0, 3, 1, 1), (1, 1, 1, 1), (1, 5, 3, 3)])
 def test_tiny_batches(L, ci, N, T, M):
     """Degenerate sizes: minibatches of one to five samples.  Loss statistics of the first step against the oracle."""
