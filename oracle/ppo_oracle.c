@@ -59,6 +59,8 @@ typedef struct {
 
 typedef struct {
   double clip_eps, vclip_eps /* <=0: off */, vf_coef, ent_coef;
+  double aux_coef;  /* distillation: weight of the auxiliary columns' error */
+  int32_t aux_dim;  /* distillation: the last aux_dim head columns are the auxiliary output; 0: none */
 } orc_loss_cfg;
 
 typedef struct {
@@ -509,17 +511,26 @@ void orc_ppo_loss(int64_t B, int32_t A, const double *mu, const double *v, const
   stats[ST_TOTAL] = stats[ST_PI] + cfg->vf_coef * stats[ST_V] - cfg->ent_coef * ent;
 }
 
-/* Distillation loss: mean over batch and action dims of (pred - teacher)^2. */
-void orc_mse_loss(int64_t B, int32_t A, const double *pred, const double *target, double *stats,
-                  double *dpred) {
-  double l = 0, sc = 1.0 / ((double)B * A);
-  for (int64_t i = 0; i < B * A; ++i) {
-    double d = pred[i] - target[i];
-    l += d * d;
-    if (dpred) dpred[i] = 2.0 * sc * d;
-  }
+/* Distillation loss.  Without auxiliary columns: mean over batch and action dims of
+ * (pred - teacher)^2.  With the last X = aux_dim columns an auxiliary output (the deployed
+ * student's object position, Sec. IV-C; the paper gives no weighting):
+ *   L = mean_b [ 1/(A-X) sum_{j<A-X} e_bj^2 ] + aux_coef * mean_b [ 1/X sum_{j>=A-X} e_bj^2 ],
+ * the two means reported as stats[ST_PI] and stats[ST_V]. */
+void orc_mse_loss(int64_t B, int32_t A, int32_t aux_dim, double aux_coef, const double *pred,
+                  const double *target, double *stats, double *dpred) {
+  int Aa = A - aux_dim;
+  double la = 0, lx = 0;
+  double sa = 1.0 / ((double)B * Aa), sx = aux_dim > 0 ? aux_coef / ((double)B * aux_dim) : 0.0;
+  for (int64_t b = 0; b < B; ++b)
+    for (int j = 0; j < A; ++j) {
+      double d = pred[b * A + j] - target[b * A + j];
+      if (j < Aa) la += d * d; else lx += d * d;
+      if (dpred) dpred[b * A + j] = 2.0 * (j < Aa ? sa : sx) * d;
+    }
   for (int i = 0; i < ST_N; ++i) stats[i] = 0;
-  stats[ST_TOTAL] = l * sc; stats[ST_PI] = l * sc;
+  stats[ST_PI] = la * sa;
+  stats[ST_V] = aux_dim > 0 ? lx / ((double)B * aux_dim) : 0.0;
+  stats[ST_TOTAL] = stats[ST_PI] + (aux_dim > 0 ? aux_coef * stats[ST_V] : 0.0);
 }
 
 /* forward all samples, evaluate loss on the outputs, backward all samples */
@@ -537,7 +548,7 @@ static void minibatch_grad(const orc_net *n, const double *params_in, int64_t B,
   double *params = operand_params(n, &g, params_in);
   orc_forward(n, params_in, B, obs, proprio, mu, v);
   memset(grads, 0, sizeof(double) * (size_t)g.total);
-  if (distill) orc_mse_loss(B, A, mu, action, stats, dmu);
+  if (distill) orc_mse_loss(B, A, cfg ? cfg->aux_dim : 0, cfg ? cfg->aux_coef : 0.0, mu, action, stats, dmu);
   else
     orc_ppo_loss(B, A, mu, v, params + g.logstd, action, logp_old, v_old, adv, ret, cfg, stats,
                  dmu, dv, grads + g.logstd);
@@ -580,9 +591,10 @@ void orc_ppo_loss_grad(const orc_net *n, const double *params, int64_t B, const 
   minibatch_grad(n, params, B, obs, proprio, action, logp_old, v_old, adv, ret, cfg, 0, grads, stats);
 }
 void orc_distill_loss_grad(const orc_net *n, const double *params, int64_t B, const float *obs,
-                           const double *proprio, const double *teacher, double *grads,
-                           double *stats) {
-  minibatch_grad(n, params, B, obs, proprio, teacher, NULL, NULL, NULL, NULL, NULL, 1, grads, stats);
+                           const double *proprio, const double *teacher, int32_t aux_dim,
+                           double aux_coef, double *grads, double *stats) {
+  orc_loss_cfg lc; memset(&lc, 0, sizeof lc); lc.aux_dim = aux_dim; lc.aux_coef = aux_coef;
+  minibatch_grad(n, params, B, obs, proprio, teacher, NULL, NULL, NULL, NULL, &lc, 1, grads, stats);
 }
 
 /* Adam (Kingma & Ba 2015, Algorithm 1), epsilon added to the bias-corrected
@@ -696,9 +708,11 @@ void orc_ppo_update(const orc_net *n, double *params, double *m, double *v, int6
 }
 void orc_distill_update(const orc_net *n, double *params, double *m, double *v, int64_t *step,
                         int64_t S, const float *obs, const double *proprio, const double *teacher,
+                        int32_t aux_dim, double aux_coef,
                         const orc_adam_cfg *ac, int32_t epochs, int32_t minibatches, uint64_t seed,
                         uint64_t update_idx, double *stats, double *grads_last) {
-  update_loop(n, params, m, v, step, S, obs, proprio, teacher, NULL, NULL, NULL, NULL, NULL, ac,
+  orc_loss_cfg lc; memset(&lc, 0, sizeof lc); lc.aux_dim = aux_dim; lc.aux_coef = aux_coef;
+  update_loop(n, params, m, v, step, S, obs, proprio, teacher, NULL, NULL, NULL, NULL, &lc, ac,
               epochs, minibatches, seed, update_idx, 1, stats, grads_last);
 }
 

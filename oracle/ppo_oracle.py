@@ -41,7 +41,7 @@ class _Net(C.Structure):
 
 class _LossCfg(C.Structure):
     _fields_ = [("clip_eps", C.c_double), ("vclip_eps", C.c_double), ("vf_coef", C.c_double),
-                ("ent_coef", C.c_double)]
+                ("ent_coef", C.c_double), ("aux_coef", C.c_double), ("aux_dim", C.c_int32)]
 
 
 class _AdamCfg(C.Structure):
@@ -198,11 +198,15 @@ def ppo_loss(mu, v, logstd, action, logp_old, v_old, adv, ret, clip_eps=0.2, vcl
     return _stats(st), dmu, dv, dls
 
 
-def mse_loss(pred, target):
+def mse_loss(pred, target, aux_dim=0, aux_coef=1.0):
+    """Distillation loss -> (stats, dpred).  aux_dim > 0: the last aux_dim columns are an auxiliary output whose
+    mean squared error (stats["v_loss"]) enters with weight aux_coef beside that of the others (stats["pi_loss"])."""
     pred, target = _d(pred), _d(target)
     B, A = pred.shape
+    assert 0 <= aux_dim < A
     st, dp = np.zeros(ST_N), np.zeros((B, A))
-    lib().orc_mse_loss(C.c_int64(B), C.c_int32(A), _p(pred), _p(target), _p(st), _p(dp))
+    lib().orc_mse_loss(C.c_int64(B), C.c_int32(A), C.c_int32(aux_dim), C.c_double(aux_coef), _p(pred), _p(target),
+                       _p(st), _p(dp))
     return _stats(st), dp
 
 
@@ -221,14 +225,14 @@ def ppo_loss_grad(net, params, obs, proprio, action, logp_old, v_old, adv, ret, 
     return _stats(st), grads
 
 
-def distill_loss_grad(net, params, obs, proprio, teacher):
+def distill_loss_grad(net, params, obs, proprio, teacher, aux_dim=0, aux_coef=1.0):
     n = _net(net)
     params, proprio, teacher = _d(params), _d(proprio), _d(teacher)
     B = proprio.shape[0]
     obs = _obs(net, obs, B)
     grads, st = np.zeros(params.size), np.zeros(ST_N)
     lib().orc_distill_loss_grad(C.byref(n), _p(params), C.c_int64(B), _p(obs, C.c_float), _p(proprio),
-                                _p(teacher), _p(grads), _p(st))
+                                _p(teacher), C.c_int32(aux_dim), C.c_double(aux_coef), _p(grads), _p(st))
     return _stats(st), grads
 
 
@@ -282,7 +286,8 @@ def _update(fn_name, net, params, m, v, step, obs, proprio, action, extra, hp, u
                              C.c_uint64(hp.get("seed", 0)), C.c_uint64(update_idx), _p(st), _p(gl))
     else:
         lib().orc_distill_update(C.byref(n), _p(params), _p(m), _p(v), C.byref(stp), C.c_int64(S),
-                                 _p(obs, C.c_float), _p(proprio), _p(action), C.byref(ac), C.c_int32(E),
+                                 _p(obs, C.c_float), _p(proprio), _p(action), C.c_int32(hp.get("aux_dim", 0)),
+                                 C.c_double(hp.get("aux_coef", 1.0)), C.byref(ac), C.c_int32(E),
                                  C.c_int32(M), C.c_uint64(hp.get("seed", 0)), C.c_uint64(update_idx),
                                  _p(st), _p(gl))
     return dict(params=params, m=m, v=v, step=int(stp.value), stats=[_stats(r) for r in st], grads_last=gl)

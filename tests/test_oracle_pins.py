@@ -305,6 +305,56 @@ def test_mse_closed_forms():
     assert abs(d[2, 5] - 2 * 3.0 / (6 * 23)) < 1e-15 and np.count_nonzero(d) == 1
 
 
+def test_mse_with_weighted_auxiliary_columns():
+    rng = np.random.default_rng(8)
+    B, A, X = 7, 26, 3
+    pred, tgt = rng.standard_normal((B, A)), rng.standard_normal((B, A))
+    tp = torch.tensor(pred, requires_grad=True)
+    F = torch.nn.functional
+    for coef in (0.25, 1.0, 3.0):
+        st, d = orc.mse_loss(pred, tgt, aux_dim=X, aux_coef=coef)
+        la, lx = F.mse_loss(tp[:, :A - X], torch.tensor(tgt[:, :A - X])), F.mse_loss(tp[:, A - X:], torch.tensor(tgt[:, A - X:]))
+        loss = la + coef * lx
+        tp.grad = None
+        loss.backward()
+        assert abs(st["pi_loss"] - la.item()) < 1e-14 and abs(st["v_loss"] - lx.item()) < 1e-14
+        assert abs(st["total"] - loss.item()) < 1e-14
+        np.testing.assert_allclose(d, tp.grad.numpy(), rtol=1e-13, atol=1e-16)
+    # weight X/(A-X): every column counts alike, the plain mean scaled by A/(A-X)
+    st, d = orc.mse_loss(pred, tgt, aux_dim=X, aux_coef=X / (A - X))
+    st0, d0 = orc.mse_loss(pred, tgt)
+    assert abs(st["total"] - st0["total"] * A / (A - X)) < 1e-14
+    np.testing.assert_allclose(d, d0 * A / (A - X), rtol=1e-13)
+    # one wrong auxiliary element: its own closed form
+    b = tgt.copy()
+    b[4, A - 2] += 2.0
+    st, d = orc.mse_loss(b, tgt, aux_dim=X, aux_coef=0.5)
+    assert st["pi_loss"] == 0 and abs(st["v_loss"] - 4.0 / (B * X)) < 1e-15 and abs(st["total"] - 2.0 / (B * X)) < 1e-15
+    assert abs(d[4, A - 2] - 2 * 0.5 * 2.0 / (B * X)) < 1e-15 and np.count_nonzero(d) == 1
+
+
+def test_distill_gradients_with_auxiliary_columns_match_autograd():
+    net, B, X, coef = dict(TINY_STEREO), 9, 2, 0.7
+    b, params = _batch(net, B, 14), _params(net, 15)
+    A = net["act_dim"]
+    st, g = orc.distill_loss_grad(net, params, b["obs"], b["proprio"], b["action"], aux_dim=X, aux_coef=coef)
+    p, sl = torch_ref.unpack(net, params)
+    mu, _, _ = torch_ref.forward(net, p, sl, b["obs"], b["proprio"])
+    e2 = (mu - torch.as_tensor(b["action"])) ** 2
+    loss = e2[:, :A - X].mean() + coef * e2[:, A - X:].mean()
+    loss.backward()
+    np.testing.assert_allclose(g, p.grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert abs(st["total"] - loss.item()) < 1e-12
+    # and through the update loop: one step equals Adam on that gradient
+    z = np.zeros_like(params)
+    out = orc.distill_update(net, params, z, z, 0, b["obs"], b["proprio"], b["action"],
+                             dict(epochs=1, minibatches=1, lr=1e-3, seed=0, aux_dim=X, aux_coef=coef))
+    pp, m, v = params.astype(np.float64).copy(), z.copy(), z.copy()
+    orc.adam_step(pp, m, v, g, 1, lr=1e-3)
+    np.testing.assert_allclose(out["params"], pp, rtol=1e-12, atol=1e-15)
+    assert abs(out["stats"][0]["total"] - loss.item()) < 1e-12
+
+
 # ----------------------------------------------------------------- gradients
 @pytest.mark.parametrize("vclip,ent", [(0.0, 0.0), (0.3, 0.01)])
 def test_ppo_gradients_match_autograd(vclip, ent):
