@@ -82,11 +82,14 @@ typedef struct {
                                    ppo_mb_stats.lr reports what each step used.  <= 0: off, every step uses `lr`.
                                    The paper gives no schedule (Sec. III-C); this is the common one of on-policy code. */
   float lr_min, lr_max;         /* bounds of the adaptive rate; 0 < lr_min <= lr_max when desired_kl > 0 */
+  float aux_coef;               /* distill_update with aux_dim > 0: weight of the auxiliary columns' error (>= 0) */
   int32_t epochs, minibatches;  /* num_envs*horizon must be divisible by minibatches */
   int32_t norm_adv;             /* 1: advantages normalised once per update over the whole rollout,
                                    (A - mean) / (population std + 1e-8); 0: raw advantages */
   int32_t lr_carry;             /* with desired_kl > 0: 1 = start from the rate the previous adaptive update of this
                                    context ended with (if there was one; else from `lr`), 0 = start from `lr` */
+  int32_t aux_dim;              /* distill_update: the last aux_dim (< act_dim) head columns are an auxiliary output,
+                                   0 = none; see distill_update */
   uint64_t seed;                /* permutation stream seed */
 } ppo_hparams;
 
@@ -177,7 +180,12 @@ int ppo_permutation(ppo_ctx* ctx, uint64_t seed, uint64_t update_idx, uint64_t e
 int ppo_update(ppo_ctx* ctx, const ppo_hparams* hp, ppo_mb_stats* host_stats);
 
 /* Distillation update of a student (has_value_head = 0): MSE between the student's
- * action and the teacher action stored in the buffer's action slot; no GAE needed. */
+ * action and the teacher action stored in the buffer's action slot; no GAE needed.
+ * With hp->aux_dim = X > 0 the last X head columns are an auxiliary regression output (the deployed
+ * student's object-position output, Sec. IV-C) whose target sits in the same columns of the action
+ * slot; the paper gives no weighting, the loss taken is
+ *   L = mean_b[ 1/(A-X) sum_{j<A-X} e_bj^2 ] + aux_coef * mean_b[ 1/X sum_{j>=A-X} e_bj^2 ],
+ * and the two means are reported as pi_loss and v_loss.  X = 0: the mean over batch and all A columns. */
 int distill_update(ppo_ctx* ctx, const ppo_hparams* hp, ppo_mb_stats* host_stats);
 
 /* Forward only, on `count` buffer samples given by DEVICE int32 indices d_idx (NULL = samples

@@ -438,6 +438,8 @@ struct LossData {
   const int32_t* idx;
   const float *action, *logp_old, *v_old, *adv, *ret;
   float clip_eps, vclip_eps, vf_coef;
+  int aux_dim;      // distillation: the last aux_dim columns are the auxiliary output (0: none)
+  float aux_coef;   // and their error's weight
 };
 
 // Clipped-surrogate PPO loss of one sample (number s of the rollout) of a minibatch of `Bfull`:
@@ -501,21 +503,23 @@ __device__ __forceinline__ void ppo_loss_sample(const LossData& L, const float* 
   for (int j = 0; j < 32; ++j) dls[j] = j < A ? dlogp * (z[j] * z[j] - 1.f) : 0.f;
 }
 
-// Distillation loss of one sample: sum over the action dims of (pred - teacher)^2, scaled later.
+// Distillation loss of one sample: sums over the action columns (st[0]) and over the auxiliary columns (st[1]) of
+// (pred - teacher)^2, scaled later; the gradient carries the scales 1/(B (A-X)) and aux_coef/(B X).
 __device__ __forceinline__ void mse_loss_sample(const LossData& L, const LossSample& smp, const float (&o)[HEAD_LD], uint32_t (&pk)[16], float (&st)[4]) {
-  const int A = L.A;
-  const float sc = 1.f / ((float)L.Bfull * (float)A);
+  const int A = L.A, Aa = A - L.aux_dim;
+  const float sa = 1.f / ((float)L.Bfull * (float)Aa), sx = L.aux_dim > 0 ? L.aux_coef / ((float)L.Bfull * (float)L.aux_dim) : 0.f;
   const float (&t)[32] = smp.act;
-  float l = 0.f, g[32];
+  float la = 0.f, lx = 0.f, g[32];
 #pragma unroll
   for (int j = 0; j < 32; ++j) {
     const float e = o[j] - t[j];
-    l += j < A ? e * e : 0.f;
-    g[j] = j < A ? 2.f * sc * e : 0.f;
+    la += j < Aa ? e * e : 0.f;
+    lx += (j >= Aa && j < A) ? e * e : 0.f;
+    g[j] = j < Aa ? 2.f * sa * e : (j < A ? 2.f * sx * e : 0.f);
   }
 #pragma unroll
   for (int j = 0; j < 32; j += 2) pk[j >> 1] = pack2bf(g[j], g[j + 1]);
-  st[0] = l; st[1] = 0.f; st[2] = 0.f; st[3] = 0.f;
+  st[0] = la; st[1] = lx; st[2] = 0.f; st[3] = 0.f;
 }
 
 // Sums of the four statistics and (if dls_part) of the A log-std terms over the block, in a fixed
@@ -603,6 +607,8 @@ struct LossFinalize {
   float desired_kl, lr_min, lr_max, lr_init;
   int lr_reset;
   float* lr_dev;
+  int aux_dim;     // distillation: auxiliary columns and their weight
+  float aux_coef;
 };
 __device__ __forceinline__ void loss_finalize_block(const LossFinalize& f) {
   // column c (4 statistics, then the A log-std gradients) is summed by 8 lanes, lane j taking
@@ -625,8 +631,10 @@ __device__ __forceinline__ void loss_finalize_block(const LossFinalize& f) {
   if (tid == 0) {
     DevStats* st = f.st;
     if (f.distill) {
-      float l = tot[0] / ((float)f.Bfull * (float)f.A);
-      st->pi_loss = l; st->v_loss = 0.f; st->entropy = 0.f; st->approx_kl = 0.f; st->clip_frac = 0.f; st->total_loss = l;
+      const float la = tot[0] / ((float)f.Bfull * (float)(f.A - f.aux_dim));
+      const float lx = f.aux_dim > 0 ? tot[1] / ((float)f.Bfull * (float)f.aux_dim) : 0.f;
+      st->pi_loss = la; st->v_loss = lx; st->entropy = 0.f; st->approx_kl = 0.f; st->clip_frac = 0.f;
+      st->total_loss = f.aux_dim > 0 ? la + f.aux_coef * lx : la;
     } else {
       float invB = 1.f / (float)f.Bfull, ent = 0.f;
       for (int j = 0; j < f.A; ++j) ent += f.logstd[j] + 1.4189385332046727418f;

@@ -195,13 +195,15 @@ int validate_desc(const ppo_net_desc* d) {
 
 int validate_hp(Ctx* c, const ppo_hparams* hp, bool distill) {
   if (!hp) return fail(c, PPO_EINVAL, "hparams is NULL");
-  const float f[] = {hp->clip_eps, hp->vclip_eps, hp->vf_coef, hp->ent_coef, hp->lr, hp->beta1, hp->beta2, hp->adam_eps, hp->max_grad_norm, hp->desired_kl};
+  const float f[] = {hp->clip_eps, hp->vclip_eps, hp->vf_coef, hp->ent_coef, hp->lr, hp->beta1, hp->beta2, hp->adam_eps, hp->max_grad_norm, hp->desired_kl, hp->aux_coef};
   for (float x : f) if (!isfinite(x)) return fail(c, PPO_EINVAL, "non-finite hyper-parameter");
   if (!distill && !(hp->clip_eps > 0.f)) return fail(c, PPO_EINVAL, "clip_eps must be > 0");
   if (!(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) || !(hp->adam_eps > 0.f))
     return fail(c, PPO_EINVAL, "Adam hyper-parameters out of range");
   if (hp->norm_adv != 0 && hp->norm_adv != 1) return fail(c, PPO_EINVAL, "norm_adv must be 0 or 1");
   if (hp->lr_carry != 0 && hp->lr_carry != 1) return fail(c, PPO_EINVAL, "lr_carry must be 0 or 1");
+  if (distill && (hp->aux_dim < 0 || hp->aux_dim >= c->A)) return fail(c, PPO_EINVAL, "aux_dim must be in [0, act_dim)");
+  if (distill && hp->aux_dim > 0 && !(hp->aux_coef >= 0.f)) return fail(c, PPO_EINVAL, "aux_coef must be >= 0");
   if (!distill && hp->desired_kl > 0.f && !(isfinite(hp->lr_min) && isfinite(hp->lr_max) && hp->lr_min > 0.f && hp->lr_min <= hp->lr_max))
     return fail(c, PPO_EINVAL, "desired_kl > 0 needs 0 < lr_min <= lr_max");
   if (hp->epochs < 1 || hp->minibatches < 1) return fail(c, PPO_EINVAL, "epochs and minibatches must be >= 1");
@@ -1007,6 +1009,7 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
         LossData L;
         L.Bfull = B; L.A = c->A; L.logstd = distill ? nullptr : c->p + c->logstd; L.idx = idx + c0; L.action = c->action; L.logp_old = c->logp;
         L.v_old = c->value; L.adv = hp->norm_adv ? c->adv_n : c->adv; L.ret = c->ret; L.clip_eps = hp->clip_eps; L.vclip_eps = hp->vclip_eps; L.vf_coef = hp->vf_coef;
+        L.aux_dim = distill ? hp->aux_dim : 0; L.aux_coef = hp->aux_coef;
         bool head_done = false;
         if (fused_head) {
           rc = launch_head_loss(c, L, n, c0 > 0, distill, sp, dp);
@@ -1037,6 +1040,7 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
           f.g_logstd = distill ? nullptr : c->g + c->logstd;
           f.desired_kl = adaptive ? hp->desired_kl : 0.f; f.lr_min = hp->lr_min; f.lr_max = hp->lr_max; f.lr_init = hp->lr; f.lr_dev = c->lr_dev;
           f.lr_reset = (k == 0 && !(hp->lr_carry && c->lr_live)) ? 1 : 0;
+          f.aux_dim = distill ? hp->aux_dim : 0; f.aux_coef = hp->aux_coef;
         }
         rc = backward_chunk(c, idx + c0, n, c0 > 0, !head_done);
         if (rc) return rc;

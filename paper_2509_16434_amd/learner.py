@@ -37,8 +37,9 @@ class HParams(C.Structure):
                 ("vf_coef", C.c_float), ("ent_coef", C.c_float), ("lr", C.c_float), ("beta1", C.c_float),
                 ("beta2", C.c_float), ("adam_eps", C.c_float), ("max_grad_norm", C.c_float),
                 ("desired_kl", C.c_float), ("lr_min", C.c_float), ("lr_max", C.c_float),
+                ("aux_coef", C.c_float),
                 ("epochs", C.c_int32), ("minibatches", C.c_int32), ("norm_adv", C.c_int32), ("lr_carry", C.c_int32),
-                ("seed", C.c_uint64)]
+                ("aux_dim", C.c_int32), ("seed", C.c_uint64)]
 
 
 class MbStats(C.Structure):
@@ -124,6 +125,7 @@ def make_hparams(hp: dict) -> HParams:
     h.max_grad_norm = hp.get("max_grad_norm", 0.0)
     h.desired_kl, h.lr_min, h.lr_max = hp.get("desired_kl", 0.0), hp.get("lr_min", 1e-5), hp.get("lr_max", 1e-2)
     h.lr_carry = hp.get("lr_carry", 0)
+    h.aux_dim, h.aux_coef = hp.get("aux_dim", 0), hp.get("aux_coef", 1.0)
     h.epochs, h.minibatches, h.norm_adv = hp["epochs"], hp["minibatches"], hp.get("norm_adv", 0)
     h.seed = hp.get("seed", 0)
     return h

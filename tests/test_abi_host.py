@@ -34,8 +34,8 @@ def test_the_four_path_entry_points_are_declared():
 
 
 def test_struct_sizes_match_the_header_layout():
-    # ppo_hparams: 14 floats, 4 int32, one uint64; ppo_mb_stats: 7 floats, int32, float
-    assert C.sizeof(L.HParams) == 14 * 4 + 4 * 4 + 8 and L.HParams.seed.offset == 72
+    # ppo_hparams: 15 floats, 5 int32, one uint64; ppo_mb_stats: 7 floats, int32, float
+    assert C.sizeof(L.HParams) == 15 * 4 + 5 * 4 + 8 and L.HParams.seed.offset == 80
     assert C.sizeof(L.MbStats) == 36 and L.MbStats.lr.offset == 32
     text = open(HEADER).read()
     body = text[text.index("float gamma, lambda;"):text.index("} ppo_hparams;")]

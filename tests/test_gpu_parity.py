@@ -719,6 +719,51 @@ def test_distill_single_minibatch_gradients(L, chunk, act_dim):
     assert max(per_tensor_errors(cfg["net"], lrn.get_grads(), og).values()) <= 0.15
 
 
+@pytest.mark.parametrize("chunk,aux_dim,aux_coef", [(0, 3, 0.3), (200, 3, 2.0), (0, 1, 0.0)])
+def test_distill_weighted_auxiliary_output(L, chunk, aux_dim, aux_coef):
+    """The student's auxiliary regression output (last aux_dim head columns, own weight): loss parts and gradient of
+    one minibatch against the oracle; a multi-step update; weight 0 leaves the auxiliary columns' head rows without
+    gradient; bad arguments."""
+    cfg = _stereo_cfg(128, 4)
+    cfg["net"]["act_dim"] = 26
+    lrn, ro, params = _setup(L, cfg, max_chunk=chunk)
+    hp = dict(cfg["hp"], minibatches=1, seed=5, aux_dim=aux_dim, aux_coef=aux_coef)
+    st = lrn.distill_update(hp)[0]
+    fr = flat_rollout(ro)
+    with orc.quant(1):
+        qst, qg = orc.distill_loss_grad(cfg["net"], params, fr["obs"], fr["proprio"], fr["action"], aux_dim=aux_dim, aux_coef=aux_coef)
+    for k_gpu, k_or in (("pi_loss", "pi_loss"), ("v_loss", "v_loss"), ("total_loss", "total")):
+        assert abs(st[k_gpu] - qst[k_or]) <= TOL_BF16 * abs(qst[k_or]), (k_gpu, st[k_gpu], qst[k_or])
+    assert abs(st["total_loss"] - (st["pi_loss"] + aux_coef * st["v_loss"])) <= 1e-5 * st["total_loss"]
+    assert abs(st["grad_norm"] - qst["grad_norm"]) <= TOL_BF16 * qst["grad_norm"]
+    g = lrn.get_grads()
+    errs = per_tensor_errors(cfg["net"], g, qg)
+    assert max(errs.values()) <= TOL_BF16, errs
+    # the plain mean over all columns is a different loss: the option is really on
+    with orc.quant(1):
+        pst, _ = orc.distill_loss_grad(cfg["net"], params, fr["obs"], fr["proprio"], fr["action"])
+    assert abs(pst["total"] - qst["total"]) > 10 * TOL_BF16 * abs(qst["total"]) or aux_coef == 0.0
+    if aux_coef == 0.0:
+        a, b, shape = synth.param_slices(cfg["net"])["mu.w"]
+        hw = g[a:b].reshape(shape)
+        assert np.all(hw[26 - aux_dim:] == 0) and np.any(hw[:26 - aux_dim] != 0)
+        for bad in (dict(aux_dim=26), dict(aux_dim=-1), dict(aux_dim=2, aux_coef=-1.0), dict(aux_dim=2, aux_coef=float("nan"))):
+            with pytest.raises(L.LearnerError) as e:
+                lrn.distill_update(dict(hp, **bad))
+            assert e.value.code == L.PPO_EINVAL, bad
+    else:
+        lrn2, _, _ = _setup(L, cfg, max_chunk=chunk)
+        hp2 = dict(cfg["hp"], seed=5, aux_dim=aux_dim, aux_coef=aux_coef)
+        stats = lrn2.distill_update(hp2)
+        z = np.zeros_like(params, dtype=np.float64)
+        with orc.quant(1):
+            out = orc.distill_update(cfg["net"], params, z, z, 0, fr["obs"], fr["proprio"], fr["action"], hp2, update_idx=0)
+        for s, o in zip(stats, out["stats"]):
+            assert abs(s["total_loss"] - o["total"]) <= TOL_BF16 * abs(o["total"])
+            assert abs(s["v_loss"] - o["v_loss"]) <= TOL_BF16 * abs(o["v_loss"])
+        assert rel_l2(lrn2.get_params(), out["params"]) <= TOL_BF16
+
+
 @pytest.mark.parametrize("h,w", [(44, 72), (52, 100), (30, 48)])
 def test_distill_gradients_odd_image_shapes(L, h, w):
     """RGB views whose rows are and are not multiples of 16 bytes (the register-fused, the LDS-fused and the
