@@ -117,6 +117,7 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
   const int cpr = Cout >> 3;  // 16-byte chunks per pixel
   const int cshift = (cpr & (cpr - 1)) == 0 ? 31 - __builtin_clz(cpr) : -1;  // log2 of it when it is a power of two
   const FastDiv dv_wo = a.dv_wo;
+  const uint32_t negw = nonzero_weights(h);
 
   for (int q = 0; q < nq; ++q) {
     const int t = vb + q * nblk;
@@ -174,31 +175,33 @@ __global__ __launch_bounds__(512) void k_conv0_fwd_tile(Conv0Args a) {
           for (int ks = 1; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bw[jn][ks], av[ks], acc, 0, 0, 0);
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
-            const int cl = jn * 32 + g * 8 + h * 4;
-            if (cl < Cout) {
+            // Cout is a multiple of 8: the eight columns of (jn, g) exist together, for both lane halves
+            if (jn * 32 + g * 8 < Cout) {
               uint2 o;
               o.x = relu_pack2bf(acc[g * 4], acc[g * 4 + 1]);
               o.y = relu_pack2bf(acc[g * 4 + 2], acc[g * 4 + 3]);
-              *reinterpret_cast<uint2*>(&stage[l32 * SP + cl]) = o;
-              pw[jn] |= (nonzero2(o.x) | (nonzero2(o.y) << 2)) << (g * 8 + h * 4);
+              *reinterpret_cast<uint2*>(&stage[l32 * SP + jn * 32 + g * 8 + h * 4]) = o;
+              pw[jn] |= nonzero4(o.x, o.y, negw) << (g * 8);
             }
           }
         }
       }
       if (a.bits) {
         const int wpp = (Cout + 31) >> 5;
+        uint32_t* const bw0 = a.bits + ((int64_t)img * a.Ho * Wo + (int64_t)band * TR * Wo) * wpp;  // the band's words
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn) {
-          const uint32_t word = pw[jn] | (uint32_t)__shfl_xor((int)pw[jn], 32);
-          if (h == 0 && jn < wpp && p < plim)
-            a.bits[((int64_t)img * a.Ho * Wo + (int64_t)band * TR * Wo + p) * wpp + jn] = word;
+          const uint32_t word = or_with_lane_xor32(pw[jn]);
+          if (h == 0 && jn < wpp && p < plim) bw0[(uint32_t)(p * wpp + jn)] = word;
         }
       }
-      // the group's 32 pixels are contiguous in the output: 16-byte segments, lane after lane
+      // the group's 32 pixels are contiguous in the output: chunk ch of the group is its bytes [16 ch, 16 ch + 16)
+      bf16_t* const dst_g = dst + (int64_t)gi * 32 * Cout;
+      const int plim_g = plim - gi * 32;
       for (int ch = lane; ch < 32 * cpr; ch += 64) {
         const int r = cshift >= 0 ? ch >> cshift : ch / cpr, cg = ch - r * cpr;
-        if (gi * 32 + r < plim)
-          store_stream16(dst + (int64_t)(gi * 32 + r) * Cout + cg * 8, *reinterpret_cast<const uint4*>(&stage[r * SP + cg * 8]));
+        if (r < plim_g)
+          store_stream16(dst_g + (uint32_t)ch * 8u, *reinterpret_cast<const uint4*>(&stage[r * SP + cg * 8]));
       }
     }
   }

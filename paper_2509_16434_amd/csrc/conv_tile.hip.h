@@ -45,12 +45,22 @@ __device__ __forceinline__ uint32_t relu_pack2bf(float lo, float hi) {
   const s16x2_t z = {0, 0};
   return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2_t, pack2bf(lo, hi)), z));
 }
-// bit 0: low half of x non-zero, bit 1: high half non-zero
-__device__ __forceinline__ uint32_t nonzero2(uint32_t x) {
-  typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
-  const u16x2_t one = {1, 1};
-  const uint32_t t = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2_t, x), one));
-  return (t | (t >> 15)) & 3u;
+// Which of the four non-negative bf16 of the pairs (x, y) are non-zero, as bits 0..3 times the weight the caller's
+// negw encodes (nonzero_weights: 1, or 16 for the upper nibble of a byte), added to acc.  A half is at most 0x7fff, so
+// x + 0x7fff7fff carries "non-zero" into each half's top bit without a carry between the halves; the byte permute's
+// sign selectors spread the four top bits to bytes 0x00 / 0xff (= -1), and the signed 4-byte dot product with the
+// weights -1, -2, -4, -8 (or -16 .. -128) sums them.
+// x of this lane OR x of the lane 32 away (one half-wave swap instead of a permute through LDS): either returned half
+// holds the own value and the other the partner's, so the OR of both is independent of which is which
+__device__ __forceinline__ uint32_t or_with_lane_xor32(uint32_t x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+  return r[0] | r[1];
+}
+__device__ __forceinline__ uint32_t nonzero_weights(int upper) { return upper ? 0x80c0e0f0u : 0xf8fcfeffu; }
+__device__ __forceinline__ uint32_t nonzero4(uint32_t x, uint32_t y, uint32_t negw) {
+  const uint32_t tx = x + 0x7fff7fffu, ty = y + 0x7fff7fffu;
+  const uint32_t s = __builtin_amdgcn_perm(ty, tx, 0x0b0a0908u);
+  return (uint32_t)__builtin_amdgcn_sdot4((int)s, (int)negw, 0, false);
 }
 
 template <int CIN>
@@ -197,6 +207,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
       }
     // ---- epilogue: bf16, ReLU; lane holds pixel l32 of the wave, columns j*32 + g*8 + h*4 + 0..3
     uint32_t pw[TN];  // this lane's 16 sign bits of the pixel's 32-column group j
+    const uint32_t negw = nonzero_weights(h);
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       pw[j] = 0u;
@@ -207,7 +218,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
         o.x = relu_pack2bf(acc[j][g * 4], acc[j][g * 4 + 1]);
         o.y = relu_pack2bf(acc[j][g * 4 + 2], acc[j][g * 4 + 3]);
         *reinterpret_cast<uint2*>(stage + (l32 * SP + cl) * 2) = o;
-        pw[j] |= (nonzero2(o.x) | (nonzero2(o.y) << 2)) << (g * 8 + h * 4);
+        pw[j] |= nonzero4(o.x, o.y, negw) << (g * 8);
       }
     }
     {
@@ -220,7 +231,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
         const int wpp = (a.Cout + 31) >> 5, p = wm * 32 + l32;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          const uint32_t word = pw[j] | (uint32_t)__shfl_xor((int)pw[j], 32);
+          const uint32_t word = or_with_lane_xor32(pw[j]);
           const int wi = (n0 >> 5) + j;
           if (h == 0 && p < plim && wi < wpp)
             a.bits[((int64_t)img * a.Ho * Wo + (int64_t)band * TR * Wo + p) * wpp + wi] = word;
