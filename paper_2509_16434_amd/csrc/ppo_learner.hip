@@ -405,7 +405,7 @@ int launch_wgrad_rs(Ctx* c, const bf16_t* dy, int64_t ld_dy, const bf16_t* x, in
   for (int sp = 1; sp <= 8; ++sp) {
     if (cdiv(M, sp) < 512 && sp > 1) break;
     const int blocks = tiles * sp;
-    const double eff = (double)blocks / (double)(cdiv(blocks, 256) * 256) - 0.03 * (sp - 1);
+    const double eff = (double)blocks / (double)(cdiv(blocks, 256) * 256) - 0.06 * (sp - 1);
     if (eff > best + 1e-9) { best = eff; splits = sp; }
   }
   const int64_t per = (int64_t)Nn * Kk;
