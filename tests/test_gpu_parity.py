@@ -633,6 +633,33 @@ def test_kl_adaptive_learning_rate(L):
     assert st3[0]["lr"] == float(_rule32(lr0, st3[0]["approx_kl"], d, base["lr_min"], base["lr_max"]))
 
 
+def test_kl_adaptive_rate_at_the_benchmark_size(L):
+    """The schedule in the launch configuration bench.py times (1024 envs x 16 steps, 2 epochs x 4 minibatches of 4096):
+    every reported rate follows from the library's own approx_kl by the rule in fp32, the rates stay inside the bounds,
+    and the statistics of the first step equal those of the run without the schedule (the loss does not depend on the rate)."""
+    torch = _torch()
+    cfg = configs.get_config(1)
+    lrn, ro, params = _setup(L, cfg)
+    hp = dict(cfg["hp"], seed=11)
+    lrn.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
+    st_off = lrn.update(hp)
+    kls = sorted(s["approx_kl"] for s in st_off)
+    d = float(kls[len(kls) // 2])                       # upper threshold above, lower threshold below every divergence but the rate still moves
+    lrn2, _, _ = _setup(L, cfg)
+    lrn2.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
+    hp2 = dict(hp, desired_kl=0.5 * d, lr_min=1e-5, lr_max=1e-2)
+    st = lrn2.update(hp2)
+    lr = hp["lr"]
+    for k, s in enumerate(st):
+        lr = _rule32(lr, s["approx_kl"], 0.5 * d, 1e-5, 1e-2)
+        assert s["lr"] == float(lr), (k, s["lr"], lr)
+        assert 1e-5 <= s["lr"] <= 1e-2 and s["nonfinite"] == 0
+    for f in ("pi_loss", "v_loss", "approx_kl", "total_loss", "grad_norm"):
+        assert st[0][f] == st_off[0][f], f
+    assert len({s["lr"] for s in st}) >= 2
+    assert np.isfinite(lrn2.get_params()).all()
+
+
 def test_kl_adaptive_rate_is_the_one_adam_uses(L):
     """Single-minibatch updates with a target far above any divergence: each step's rate is 1.5 x the last, and the
     oracle's Adam with the reported rate, applied to the reported gradient, reproduces the parameters."""
