@@ -142,15 +142,23 @@ __global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
 }
-__global__ void k_perm_hist(uint64_t stream, int S, int shift, int32_t* __restrict__ hist) {
+// The kernels below work on up to PERM_BATCH permutations (the epochs of one update) at once: blockIdx.y is the slot,
+// with its own generator state, histogram + cursor (2*nb words), bucket starts (nb), scratch and result (S each).
+#define PERM_BATCH 8
+struct PermStreams { uint64_t s[PERM_BATCH]; };
+__global__ void k_perm_hist(PermStreams ps, int S, int shift, int nb, int32_t* __restrict__ hist_all) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= S) return;
+  const uint64_t stream = ps.s[blockIdx.y];
+  int32_t* hist = hist_all + (int64_t)blockIdx.y * 2 * nb;
   int b = shift >= 64 ? 0 : (int)(perm_key(stream, (uint64_t)i) >> shift);
   atomicAdd(&hist[b], 1);
 }
-// exclusive scan of hist[nb] into start[nb]; one block of 1024 threads
-__global__ void k_perm_scan(const int32_t* __restrict__ hist, int32_t* __restrict__ start, int nb) {
+// exclusive scan of hist[nb] into start[nb]; one block of 1024 threads per slot
+__global__ void k_perm_scan(const int32_t* __restrict__ hist_all, int32_t* __restrict__ start_all, int nb) {
   __shared__ int32_t part[1024];
+  const int32_t* hist = hist_all + (int64_t)blockIdx.y * 2 * nb;
+  int32_t* start = start_all + (int64_t)blockIdx.y * nb;
   int tid = threadIdx.x, per = (nb + 1023) / 1024, b0 = tid * per, s = 0;
   for (int j = 0; j < per; ++j) if (b0 + j < nb) s += hist[b0 + j];
   part[tid] = s;
@@ -160,18 +168,27 @@ __global__ void k_perm_scan(const int32_t* __restrict__ hist, int32_t* __restric
   int run = part[tid];
   for (int j = 0; j < per; ++j) if (b0 + j < nb) { start[b0 + j] = run; run += hist[b0 + j]; }
 }
-__global__ void k_perm_scatter(uint64_t stream, int S, int shift, const int32_t* __restrict__ start,
-                               int32_t* __restrict__ cursor, int32_t* __restrict__ tmp) {
+__global__ void k_perm_scatter(PermStreams ps, int S, int shift, int nb, const int32_t* __restrict__ start_all,
+                               int32_t* __restrict__ hist_all, int32_t* __restrict__ tmp_all) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= S) return;
+  const uint64_t stream = ps.s[blockIdx.y];
+  const int32_t* start = start_all + (int64_t)blockIdx.y * nb;
+  int32_t* cursor = hist_all + (int64_t)blockIdx.y * 2 * nb + nb;
+  int32_t* tmp = tmp_all + (int64_t)blockIdx.y * S;
   int b = shift >= 64 ? 0 : (int)(perm_key(stream, (uint64_t)i) >> shift);
   int pos = start[b] + atomicAdd(&cursor[b], 1);
   tmp[pos] = i;
 }
-__global__ void k_perm_rank(uint64_t stream, int S, int shift, const int32_t* __restrict__ start,
-                            const int32_t* __restrict__ hist, const int32_t* __restrict__ tmp, int32_t* __restrict__ perm) {
+__global__ void k_perm_rank(PermStreams ps, int S, int shift, int nb, const int32_t* __restrict__ start_all,
+                            const int32_t* __restrict__ hist_all, const int32_t* __restrict__ tmp_all, int32_t* __restrict__ perm_all) {
   int p = blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= S) return;
+  const uint64_t stream = ps.s[blockIdx.y];
+  const int32_t* start = start_all + (int64_t)blockIdx.y * nb;
+  const int32_t* hist = hist_all + (int64_t)blockIdx.y * 2 * nb;
+  const int32_t* tmp = tmp_all + (int64_t)blockIdx.y * S;
+  int32_t* perm = perm_all + (int64_t)blockIdx.y * S;
   int i = tmp[p];
   uint64_t key = perm_key(stream, (uint64_t)i);
   int b = shift >= 64 ? 0 : (int)(key >> shift);

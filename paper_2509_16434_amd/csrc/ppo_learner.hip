@@ -61,7 +61,7 @@ struct Ctx {
   float *action = nullptr, *logp = nullptr, *value = nullptr, *reward = nullptr, *adv = nullptr, *ret = nullptr;
   uint8_t* done = nullptr;
   // device: permutation
-  int32_t *perm = nullptr, *ptmp = nullptr, *phist = nullptr, *pstart = nullptr, *pcursor = nullptr;
+  int32_t *perm = nullptr, *ptmp = nullptr, *phist = nullptr, *pstart = nullptr;
   int nb = 1, shift = 64;
   // device: workspaces for one chunk of CH samples
   int CH = 0;
@@ -930,18 +930,22 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc, bool with_head =
   return flush_reduces(c);
 }
 
-int gen_permutation(Ctx* c, uint64_t seed, uint64_t update, uint64_t epoch) {
-  const uint64_t stream = perm_stream(seed, update, epoch);
-  const int S = c->S, g = cdiv(S, 256);
-  ProfScope ps(c, "permutation", 0.0, 4.0 * S);
-  hipLaunchKernelGGL(k_fill_i32, dim3(cdiv(2 * c->nb, 256)), dim3(256), 0, c->stream, c->phist, (int64_t)2 * c->nb, 0);  // hist + cursor
-  hipLaunchKernelGGL(k_perm_hist, dim3(g), dim3(256), 0, c->stream, stream, S, c->shift, c->phist);
-  hipLaunchKernelGGL(k_perm_scan, dim3(1), dim3(1024), 0, c->stream, c->phist, c->pstart, c->nb);
-  hipLaunchKernelGGL(k_perm_scatter, dim3(g), dim3(256), 0, c->stream, stream, S, c->shift, c->pstart, c->pcursor, c->ptmp);
-  hipLaunchKernelGGL(k_perm_rank, dim3(g), dim3(256), 0, c->stream, stream, S, c->shift, c->pstart, c->phist, c->ptmp, c->perm);
+// The permutations of epochs epoch0 .. epoch0 + count - 1 (count <= PERM_BATCH) of (seed, update) into the slots
+// 0 .. count - 1 of c->perm ([PERM_BATCH][S]): five launches whatever the count.
+int gen_permutations(Ctx* c, uint64_t seed, uint64_t update, uint64_t epoch0, int count) {
+  PermStreams ps;
+  for (int e = 0; e < PERM_BATCH; ++e) ps.s[e] = perm_stream(seed, update, epoch0 + (uint64_t)(e < count ? e : 0));
+  const int S = c->S, g = cdiv(S, 256), nb = c->nb;
+  ProfScope pscope(c, "permutation", 0.0, 4.0 * S * count);
+  hipLaunchKernelGGL(k_fill_i32, dim3(cdiv((int64_t)count * 2 * nb, 256)), dim3(256), 0, c->stream, c->phist, (int64_t)count * 2 * nb, 0);  // hist + cursor
+  hipLaunchKernelGGL(k_perm_hist, dim3(g, count), dim3(256), 0, c->stream, ps, S, c->shift, nb, c->phist);
+  hipLaunchKernelGGL(k_perm_scan, dim3(1, count), dim3(1024), 0, c->stream, c->phist, c->pstart, nb);
+  hipLaunchKernelGGL(k_perm_scatter, dim3(g, count), dim3(256), 0, c->stream, ps, S, c->shift, nb, c->pstart, c->phist, c->ptmp);
+  hipLaunchKernelGGL(k_perm_rank, dim3(g, count), dim3(256), 0, c->stream, ps, S, c->shift, nb, c->pstart, c->phist, c->ptmp, c->perm);
   LAUNCHCHK(c, "permutation kernels");
   return PPO_OK;
 }
+int gen_permutation(Ctx* c, uint64_t seed, uint64_t update, uint64_t epoch) { return gen_permutations(c, seed, update, epoch, 1); }
 
 // Output layer forward, loss and output layer backward of a chunk in one kernel (head_loss.hip.h);
 // returns 1 when the width of the last hidden layer or the workspaces do not allow it.
@@ -994,10 +998,12 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
     LAUNCHCHK(c, "k_adv_normalize");
   }
   for (int e = 0; e < hp->epochs; ++e) {
-    int rc = gen_permutation(c, hp->seed, (uint64_t)c->update_idx, (uint64_t)e);
+    int rc = PPO_OK;
+    // the permutations of the next PERM_BATCH epochs in one set of launches (those of the last set are no longer read)
+    if (e % PERM_BATCH == 0) rc = gen_permutations(c, hp->seed, (uint64_t)c->update_idx, (uint64_t)e, hp->epochs - e < PERM_BATCH ? hp->epochs - e : PERM_BATCH);
     if (rc) return rc;
     for (int mb = 0; mb < hp->minibatches; ++mb, ++k) {
-      const int32_t* idx = c->perm + (int64_t)mb * B;
+      const int32_t* idx = c->perm + (int64_t)(e % PERM_BATCH) * c->S + (int64_t)mb * B;
       int nblocks = 0;
       for (int c0 = 0, ci = 0; c0 < B; c0 += c->CH, ++ci) {
         const int n = (B - c0 < c->CH) ? B - c0 : c->CH;
@@ -1108,8 +1114,8 @@ int create_impl(Ctx* c) {
   int nb = 1, lg = 0;
   while ((int64_t)nb * 32 < S && nb < (1 << 20)) { nb <<= 1; ++lg; }
   c->nb = nb; c->shift = 64 - lg;
-  DALLOC(c, c->perm, S); DALLOC(c, c->ptmp, S); DALLOC(c, c->phist, 2 * (int64_t)nb); DALLOC(c, c->pstart, nb);
-  c->pcursor = c->phist + nb;
+  DALLOC(c, c->perm, (int64_t)PERM_BATCH * S); DALLOC(c, c->ptmp, (int64_t)PERM_BATCH * S);  // one slot per epoch of a batch
+  DALLOC(c, c->phist, (int64_t)PERM_BATCH * 2 * nb); DALLOC(c, c->pstart, (int64_t)PERM_BATCH * nb);
   // workspaces
   int64_t gmax = (int64_t)CH * c->feat_ld;
   for (int l = 0; l < c->nconv - 1; ++l) {
