@@ -40,13 +40,13 @@ RIDGE_FLOP_PER_BYTE = PEAK_MFMA_BF16_TF * 1e12 / (PEAK_HBM_GBS * 1e9)  # 312.5
 # profiles/c1_medium_hbm_traffic.md and profiles/c2_full_hbm_traffic.md; a kernel class or workload that was not
 # measured reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("c1_medium", "conv_wgrad.1"): 425.2e6,
-    ("c1_medium", "conv_fwd.1"): 413.6e6,
-    ("c1_medium", "conv_fwd.0"): 319.9e6,
-    ("c1_medium", "conv_dgrad.1+wgrad.0"): 184.2e6,
-    ("c1_medium", "conv_dgrad.2"): 176.8e6,
-    ("c1_medium", "conv_wgrad.2"): 204.7e6,
-    ("c1_medium", "conv_fwd.2"): 169.6e6,
+    ("c1_medium", "conv_wgrad.1"): 425.9e6,
+    ("c1_medium", "conv_fwd.1"): 414.0e6,
+    ("c1_medium", "conv_fwd.0"): 320.0e6,
+    ("c1_medium", "conv_dgrad.1+wgrad.0"): 184.5e6,
+    ("c1_medium", "conv_dgrad.2"): 176.9e6,
+    ("c1_medium", "conv_wgrad.2"): 205.0e6,
+    ("c1_medium", "conv_fwd.2"): 169.8e6,
     ("c2_full", "conv_fwd.1"): 7900.0e6,
     ("c2_full", "conv_wgrad.1"): 7979.8e6,
     ("c2_full", "conv_fwd.0"): 5982.5e6,
