@@ -114,12 +114,20 @@ int64_t ppo_buffer_image_bytes(const ppo_ctx* ctx);
 /* Parameters / gradients / optimiser state in canonical order, HOST fp32 arrays of
  * n = ppo_param_count() elements.  All synchronise.  ppo_get_grads returns the gradient
  * of the last minibatch processed.  Setting parameters or optimiser state is the
- * checkpoint/resume path: after get -> (new ctx) set, the next update is bit-identical. */
+ * checkpoint/resume path: after get -> (new ctx) set, the next update is bit-identical (with
+ * desired_kl > 0 and lr_carry = 1 the adaptive rate below belongs to the state as well). */
 int ppo_set_params(ppo_ctx* ctx, const float* h_params, int64_t n);
 int ppo_get_params(ppo_ctx* ctx, float* h_params, int64_t n);
 int ppo_get_grads(ppo_ctx* ctx, float* h_grads, int64_t n);
 int ppo_set_opt_state(ppo_ctx* ctx, const float* h_m, const float* h_v, int64_t n, int64_t step, int64_t update_idx);
 int ppo_get_opt_state(ppo_ctx* ctx, float* h_m, float* h_v, int64_t n, int64_t* step, int64_t* update_idx);
+
+/* The KL-adaptive learning rate a context carries between updates (hp.desired_kl > 0, hp.lr_carry = 1): part of
+ * a checkpoint beside the optimiser state.  get: *h_live = 1 and *h_lr = the rate the last adaptive update ended
+ * with, or *h_live = 0 (no adaptive update has run; *h_lr = 0).  set with live = 1 installs `lr` (> 0) as that
+ * rate, live = 0 forgets it (the next adaptive update starts from hp.lr).  Both synchronise. */
+int ppo_get_adaptive_lr(ppo_ctx* ctx, float* h_lr, int32_t* h_live);
+int ppo_set_adaptive_lr(ppo_ctx* ctx, float lr, int32_t live);
 
 /* Append the step-t record of all N environments to the trajectory buffer
  * (Algorithm 2: D <- D u {(obs, actions, rew, done)}), plus the behaviour
@@ -136,8 +144,10 @@ int ppo_buffer_write(ppo_ctx* ctx, int32_t t, const void* d_obs, const float* d_
  * holds `count` rows.  This is the landing call for observations that arrive from several producers
  * (the simulator GPUs of Fig. 2b each own a range of environments and send their slice once per
  * step): the ranges may come in any order; step t counts as written once the ranges received for it
- * cover [0, N), and a write into a complete step starts that step afresh.  count = 0 is a no-op;
- * a range outside [0, N) is PPO_EINVAL. */
+ * cover [0, N); within a rollout a write into a complete step starts that step afresh.  A range that
+ * arrives while ALL T steps are complete is the first slice of the next rollout: every step then counts
+ * as unwritten until its own ranges have covered [0, N) again (to replace a whole step of a complete
+ * rollout in place use ppo_buffer_write).  count = 0 is a no-op; a range outside [0, N) is PPO_EINVAL. */
 int ppo_buffer_write_range(ppo_ctx* ctx, int32_t t, int32_t env_offset, int32_t count, const void* d_obs, const float* d_proprio,
                            const float* d_action, const float* d_logp, const float* d_value, const float* d_reward,
                            const uint8_t* d_done);
@@ -191,18 +201,6 @@ int distill_update(ppo_ctx* ctx, const ppo_hparams* hp, ppo_mb_stats* host_stats
 /* Forward only, on `count` buffer samples given by DEVICE int32 indices d_idx (NULL = samples
  * 0..count-1): action means to d_mu [count][A] fp32 and values to d_v [count] fp32 (may be NULL). */
 int ppo_forward(ppo_ctx* ctx, const int32_t* d_idx, int64_t count, float* d_mu, float* d_v);
-
-/* Per-kernel-class timing (tracing aid, off by default).  ppo_profile(ctx, 1) clears the
- * counters and starts bracketing every kernel class launched by the calls above with HIP events
- * on the context's stream; ppo_profile(ctx, 0) stops.  ppo_profile_report synchronises and writes
- * one text line per class into the HOST buffer: "name launches total_ms algorithmic_flops
- * algorithmic_bytes"; returns the length written or a negative code. */
-int ppo_profile(ppo_ctx* ctx, int32_t enable);
-int64_t ppo_profile_report(ppo_ctx* ctx, char* h_buf, int64_t cap);
-
-/* Diagnostic: C[M][N] (fp32, host) = A[M][K] * B[N][K]^T with A, B given as HOST fp32 and
- * narrowed to bf16, through the library's MFMA GEMM tile kernel.  K must be a multiple of 8. */
-int ppo_diag_gemm(int32_t M, int32_t N, int32_t K, const float* h_a, const float* h_b, float* h_c);
 
 #ifdef __cplusplus
 }

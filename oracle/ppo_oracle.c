@@ -716,6 +716,15 @@ void orc_distill_update(const orc_net *n, double *params, double *m, double *v, 
               epochs, minibatches, seed, update_idx, 1, stats, grads_last);
 }
 
+/* Number of threads the sample loops use from now on (timing aid of the benchmark's baseline leg). */
+void orc_set_num_threads(int32_t n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
 int32_t orc_num_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

@@ -14,8 +14,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wal
 
 def sources():
     d = os.path.join(_HERE, "csrc")
-    return [os.path.join(d, f) for f in sorted(os.listdir(d))] + [
-        os.path.join(os.path.dirname(_HERE), "include", "ppo_learner.h")]
+    inc = os.path.join(os.path.dirname(_HERE), "include")
+    return [os.path.join(d, f) for f in sorted(os.listdir(d))] + [os.path.join(inc, f) for f in sorted(os.listdir(inc))]
 
 
 def stale() -> bool:

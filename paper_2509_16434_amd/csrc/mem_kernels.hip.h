@@ -100,21 +100,35 @@ __global__ void k_read_obs(const bf16_t* __restrict__ src, bf16_t* __restrict__ 
 
 
 // ---------------------------------------------------------------- GAE
-// One thread per environment, reverse scan over time held in registers; at every t the
-// wave reads/writes N-contiguous rows.
-__global__ void k_gae(int T, int N, const float* __restrict__ reward, const uint8_t* __restrict__ done,
-                      const float* __restrict__ value, const float* __restrict__ last_value, float gamma, float lambda,
-                      float* __restrict__ adv, float* __restrict__ ret) {
-  int n = blockIdx.x * blockDim.x + threadIdx.x;
+// One thread per environment, reverse scan over time held in registers; at every t the wave reads/writes
+// N-contiguous rows.  The scan itself is a dependent chain of a few flops per step, the loads are not: the
+// rewards, values and done flags of up to TC steps are all requested before the first of them is used, so an
+// environment pays one memory round trip per TC steps instead of one per step (loads and stores return in
+// order on this hardware: a load issued behind a store waits for it).
+template <int TC>
+__global__ __launch_bounds__(64) void k_gae(int T, int N, const float* __restrict__ reward, const uint8_t* __restrict__ done,
+                                            const float* __restrict__ value, const float* __restrict__ last_value, float gamma, float lambda,
+                                            float* __restrict__ adv, float* __restrict__ ret) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
   if (n >= N) return;
   float next_v = last_value[n], next_a = 0.f;
-  for (int t = T - 1; t >= 0; --t) {
-    int64_t i = (int64_t)t * N + n;
-    float nt = done[i] ? 0.f : 1.f, v = value[i];
-    float delta = reward[i] + gamma * next_v * nt - v;
-    float a = delta + gamma * lambda * nt * next_a;
-    adv[i] = a; ret[i] = a + v;
-    next_a = a; next_v = v;
+  for (int t1 = T; t1 > 0; t1 -= TC) {  // steps [t0, t1), last chunk first
+    const int t0 = t1 > TC ? t1 - TC : 0, cnt = t1 - t0;
+    float r[TC], v[TC];
+    uint8_t d[TC];
+#pragma unroll
+    for (int j = 0; j < TC; ++j)
+      if (j < cnt) { const int64_t i = (int64_t)(t0 + j) * N + n; r[j] = reward[i]; v[j] = value[i]; d[j] = done[i]; }
+#pragma unroll
+    for (int j = TC - 1; j >= 0; --j)
+      if (j < cnt) {
+        const int64_t i = (int64_t)(t0 + j) * N + n;
+        const float nt = d[j] ? 0.f : 1.f;
+        const float delta = r[j] + gamma * next_v * nt - v[j];
+        const float a = delta + gamma * lambda * nt * next_a;
+        adv[i] = a; ret[i] = a + v[j];
+        next_a = a; next_v = v[j];
+      }
   }
 }
 
@@ -806,31 +820,44 @@ __device__ __forceinline__ void gnorm_finalize_block(const GnormFinalize& f) {
 __global__ __launch_bounds__(256) void k_gnorm_finalize(GnormFinalize f) { gnorm_finalize_block(f); }
 
 // ---------------------------------------------------------------- advantage normalisation
-// out = (adv - mean) / (std + 1e-8) over all S samples of the rollout, std the population standard
-// deviation.  One block of 1024 threads, sums in a fixed order (the result does not depend on the
-// launch); S is at most a few hundred thousand, once per update.
-__global__ __launch_bounds__(1024) void k_adv_normalize(int S, const float* __restrict__ adv, float* __restrict__ out) {
-  __shared__ float red[1024];
-  __shared__ float bc[2];
+// out = (adv - mean) / (std + 1e-8) over all S samples of the rollout, std the population standard deviation.
+// Two launches of ADVN_BLOCKS-or-fewer blocks.  k_adv_stats: block b takes the contiguous slice b of the samples and
+// leaves (count, mean, sum of squared deviations from its own mean) of it.  k_adv_apply: every block merges those
+// triples in block order (the pairwise update of Chan et al. for combined means and variances: no cancellation
+// between a large mean^2 and E[x^2]) and normalises its slice.  Fixed slices and a fixed merge order: the result
+// does not depend on the launch.
+#define ADVN_BLOCKS 256
+__device__ __forceinline__ float block_sum_1024(float x, float* red) {
   const int tid = threadIdx.x;
+  __syncthreads();
+  red[tid] = x;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) { if (tid < w) red[tid] += red[tid + w]; __syncthreads(); }
+  return red[0];
+}
+__global__ __launch_bounds__(1024) void k_adv_stats(int S, int per, const float* __restrict__ adv, float* __restrict__ part) {
+  __shared__ float red[1024];
+  const int tid = threadIdx.x, b = blockIdx.x, lo = b * per, hi = lo + per < S ? lo + per : S, cnt = hi - lo;
   float s = 0.f;
-  for (int i = tid; i < S; i += 1024) s += adv[i];
-  red[tid] = s;
-  __syncthreads();
-  for (int w = 512; w > 0; w >>= 1) { if (tid < w) red[tid] += red[tid + w]; __syncthreads(); }
-  if (tid == 0) bc[0] = red[0] / (float)S;
-  __syncthreads();
-  const float mean = bc[0];
+  for (int i = lo + tid; i < hi; i += 1024) s += adv[i];
+  const float mean = block_sum_1024(s, red) / (float)cnt;
   float q = 0.f;
-  for (int i = tid; i < S; i += 1024) { const float d = adv[i] - mean; q += d * d; }
-  __syncthreads();
-  red[tid] = q;
-  __syncthreads();
-  for (int w = 512; w > 0; w >>= 1) { if (tid < w) red[tid] += red[tid + w]; __syncthreads(); }
-  if (tid == 0) bc[1] = 1.f / (sqrtf(red[0] / (float)S) + 1e-8f);
-  __syncthreads();
-  const float inv = bc[1];
-  for (int i = tid; i < S; i += 1024) out[i] = (adv[i] - mean) * inv;
+  for (int i = lo + tid; i < hi; i += 1024) { const float d = adv[i] - mean; q += d * d; }
+  const float m2 = block_sum_1024(q, red);
+  if (tid == 0) { part[3 * b] = (float)cnt; part[3 * b + 1] = mean; part[3 * b + 2] = m2; }
+}
+__global__ __launch_bounds__(1024) void k_adv_apply(int S, int per, int nblk, const float* __restrict__ adv, const float* __restrict__ part,
+                                                    float* __restrict__ out) {
+  float n = part[0], mean = part[1], m2 = part[2];
+  for (int b = 1; b < nblk; ++b) {
+    const float nb = part[3 * b], mb = part[3 * b + 1], qb = part[3 * b + 2], nab = n + nb, dlt = mb - mean;
+    mean += dlt * (nb / nab);
+    m2 += qb + dlt * dlt * (n * nb / nab);
+    n = nab;
+  }
+  const float inv = 1.f / (sqrtf(m2 / (float)S) + 1e-8f);
+  const int lo = blockIdx.x * per, hi = lo + per < S ? lo + per : S;
+  for (int i = lo + threadIdx.x; i < hi; i += 1024) out[i] = (adv[i] - mean) * inv;
 }
 __global__ void k_cast_bf16(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -2,6 +2,7 @@
 // launch sequences of ppo_buffer_write / ppo_gae / ppo_update / distill_update.
 // Every step of the learner's path runs in the HIP kernels of gemm.hip.h and mem_kernels.hip.h.
 #include "../../include/ppo_learner.h"
+#include "../../include/ppo_learner_diag.h"
 
 #include <math.h>
 #include <stdarg.h>
@@ -24,6 +25,7 @@
 #include "conv0_tile.hip.h"
 #include "head_loss.hip.h"
 #include "wgrad_rs.hip.h"
+#include "peaks.hip.h"
 
 static_assert(sizeof(DevStats) == sizeof(ppo_mb_stats), "device and host statistics records must match");
 
@@ -87,6 +89,7 @@ struct Ctx {
   float* lr_dev = nullptr;  // the KL-adaptive learning rate (desired_kl > 0); lr_live: an adaptive update has left a rate there
   bool lr_live = false;
   float* adv_n = nullptr;  // advantages normalised over the rollout (norm_adv)
+  float* advn_part = nullptr;  // per-block (count, mean, squared deviations) of that normalisation
   int max_loss_blocks = 0, adam_blocks = 0;
   DevStats* dstats = nullptr;
   int max_steps = 4096;
@@ -994,8 +997,12 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
   const bool adaptive = !distill && hp->desired_kl > 0.f;  // the learning rate lives on the device and follows approx_kl
   if (!distill && hp->norm_adv) {
     ProfScope ps(c, "adv_normalize", 0.0, 12.0 * c->S);
-    hipLaunchKernelGGL(k_adv_normalize, dim3(1), dim3(1024), 0, c->stream, c->S, c->adv, c->adv_n);
-    LAUNCHCHK(c, "k_adv_normalize");
+    int per = cdiv(c->S, ADVN_BLOCKS);
+    if (per < 4096) per = 4096;  // a block is worth launching for a few samples per thread
+    const int nblk = cdiv(c->S, per);
+    hipLaunchKernelGGL(k_adv_stats, dim3(nblk), dim3(1024), 0, c->stream, c->S, per, c->adv, c->advn_part);
+    hipLaunchKernelGGL(k_adv_apply, dim3(nblk), dim3(1024), 0, c->stream, c->S, per, nblk, c->adv, c->advn_part, c->adv_n);
+    LAUNCHCHK(c, "advantage normalisation");
   }
   for (int e = 0; e < hp->epochs; ++e) {
     int rc = PPO_OK;
@@ -1176,7 +1183,7 @@ int create_impl(Ctx* c) {
   DALLOC(c, c->stat_part, (int64_t)c->max_loss_blocks * LOSS_NSTAT); DALLOC(c, c->dls_part, (int64_t)c->max_loss_blocks * 32);
   c->adam_blocks = cdiv(c->total, 1024); if (c->adam_blocks > 2048) c->adam_blocks = 2048;
   DALLOC(c, c->sq_part, c->adam_blocks);
-  DALLOC(c, c->clip_coef, 1); DALLOC(c, c->lr_dev, 1);
+  DALLOC(c, c->clip_coef, 1); DALLOC(c, c->lr_dev, 1); DALLOC(c, c->advn_part, 3 * ADVN_BLOCKS);
   DALLOC(c, c->dstats, c->max_steps);
   HIPCHK(c, hipMemsetAsync(c->p, 0, sizeof(float) * (size_t)c->total, c->stream));
   HIPCHK(c, hipMemsetAsync(c->m, 0, sizeof(float) * (size_t)c->total, c->stream));
@@ -1295,8 +1302,32 @@ int ppo_get_opt_state(ppo_ctx* c, float* hm, float* hv, int64_t n, int64_t* step
   return PPO_OK;
 }
 
+int ppo_get_adaptive_lr(ppo_ctx* c, float* h_lr, int32_t* h_live) {
+  if (!c) return PPO_EINVAL;
+  if (!h_lr || !h_live) return fail(c, PPO_EINVAL, "h_lr / h_live is NULL");
+  *h_live = c->lr_live ? 1 : 0;
+  *h_lr = 0.f;
+  if (c->lr_live) {
+    HIPCHK(c, hipMemcpyAsync(h_lr, c->lr_dev, sizeof(float), hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+  }
+  return PPO_OK;
+}
+int ppo_set_adaptive_lr(ppo_ctx* c, float lr, int32_t live) {
+  if (!c) return PPO_EINVAL;
+  if (live != 0 && live != 1) return fail(c, PPO_EINVAL, "live must be 0 or 1");
+  if (live && !(isfinite(lr) && lr > 0.f)) return fail(c, PPO_EINVAL, "a live adaptive rate must be finite and > 0");
+  if (live) {
+    HIPCHK(c, hipMemcpyAsync(c->lr_dev, &lr, sizeof(float), hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+  }
+  c->lr_live = live != 0;
+  return PPO_OK;
+}
+
 static int write_slab(ppo_ctx* c, int32_t t, int32_t n0, int32_t cnt, const void* d_obs, const float* d_proprio, const float* d_action,
                       const float* d_logp, const float* d_value, const float* d_reward, const uint8_t* d_done);
+static int all_written(ppo_ctx* c);
 
 int ppo_buffer_write(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, const float* d_action, const float* d_logp,
                      const float* d_value, const float* d_reward, const uint8_t* d_done) {
@@ -1324,9 +1355,15 @@ int ppo_buffer_write_range(ppo_ctx* c, int32_t t, int32_t env_offset, int32_t co
   if (!d_obs || !d_proprio || !d_action) return fail(c, PPO_EINVAL, "d_obs, d_proprio and d_action must not be NULL");
   if (c->d.has_value_head && (!d_logp || !d_value || !d_reward || !d_done))
     return fail(c, PPO_EINVAL, "an actor-critic buffer needs d_logp, d_value, d_reward and d_done");
+  // a range that arrives while every step of the rollout is complete is the first slice of the NEXT rollout: from
+  // here on no step counts as written until its own ranges have covered [0, N) again (the slabs still hold the
+  // previous rollout's records)
+  const bool new_rollout = all_written(c) != 0;
   const int rc = write_slab(c, t, env_offset, count, d_obs, d_proprio, d_action, d_logp, d_value, d_reward, d_done);
   if (rc) return rc;
-  // a write into a complete step starts the step afresh; the step is complete again once the ranges cover [0, N)
+  if (new_rollout) { c->written.assign((size_t)c->T, 0); c->cover.assign((size_t)c->T, {}); }
+  // within a rollout, a write into a complete step starts that step afresh; the step is complete again once the
+  // ranges cover [0, N)
   auto& cv = c->cover[(size_t)t];
   if (c->written[(size_t)t] == 1) cv.clear();
   cv.push_back({env_offset, env_offset + count});
@@ -1392,7 +1429,9 @@ int ppo_gae(ppo_ctx* c, const float* d_last_value, float gamma, float lambda) {
   if (!c->d.has_value_head) return fail(c, PPO_ESTATE, "this context has no value head (distillation student)");
   if (!all_written(c)) return fail(c, PPO_ESTATE, "ppo_gae needs all %d steps written", c->T);
   ProfScope ps(c, "gae", 6.0 * c->S, 17.0 * c->S + 4.0 * c->N);
-  hipLaunchKernelGGL(k_gae, dim3(cdiv(c->N, 64)), dim3(64), 0, c->stream, c->T, c->N, c->reward, c->done, c->value, d_last_value, gamma, lambda, c->adv, c->ret);
+  if (c->T <= 8) hipLaunchKernelGGL(k_gae<8>, dim3(cdiv(c->N, 64)), dim3(64), 0, c->stream, c->T, c->N, c->reward, c->done, c->value, d_last_value, gamma, lambda, c->adv, c->ret);
+  else if (c->T <= 16) hipLaunchKernelGGL(k_gae<16>, dim3(cdiv(c->N, 64)), dim3(64), 0, c->stream, c->T, c->N, c->reward, c->done, c->value, d_last_value, gamma, lambda, c->adv, c->ret);
+  else hipLaunchKernelGGL(k_gae<32>, dim3(cdiv(c->N, 64)), dim3(64), 0, c->stream, c->T, c->N, c->reward, c->done, c->value, d_last_value, gamma, lambda, c->adv, c->ret);
   LAUNCHCHK(c, "k_gae");
   c->gae_done = true;
   return PPO_OK;
@@ -1555,6 +1594,55 @@ int ppo_diag_gemm(int32_t M, int32_t N, int32_t K, const float* h_a, const float
     return PPO_OK;
   };
   rc = body();
+  if (rc) g_create_error = c->err;
+  free_all(c);
+  return rc;
+}
+
+int ppo_diag_peak(int32_t kind, int64_t nbytes, int32_t iters, float* h_result) {
+  if (!h_result || kind < PEAK_COPY || kind > PEAK_MFMA || iters < 1 || iters > 100000) return fail(nullptr, PPO_EINVAL, "ppo_diag_peak: bad argument");
+  if (kind != PEAK_MFMA && (nbytes < (1 << 20) || nbytes > (16LL << 30) || nbytes % 16)) return fail(nullptr, PPO_EINVAL, "ppo_diag_peak: nbytes must be a multiple of 16 in [1 MiB, 16 GiB]");
+  Ctx tmp;
+  Ctx* c = &tmp;
+  auto body = [&]() -> int {
+    uint4 *src = nullptr, *dst = nullptr;
+    float* sink = nullptr;
+    hipEvent_t e0, e1;
+    DALLOC(c, sink, 4);
+    const int64_t n16 = nbytes / 16;
+    if (kind != PEAK_MFMA) {
+      DALLOC(c, src, n16); DALLOC(c, dst, n16);
+      HIPCHK(c, hipMemset(src, 0, (size_t)nbytes));
+      HIPCHK(c, hipMemset(dst, 0, (size_t)nbytes));
+    }
+    HIPCHK(c, hipEventCreate(&e0)); HIPCHK(c, hipEventCreate(&e1));
+    const int mfma_rounds = 4096;
+    auto launch = [&]() {
+      const dim3 grid(256 * 16), blk(256);
+      switch (kind) {
+        case PEAK_COPY: hipLaunchKernelGGL(k_peak_stream<PEAK_COPY>, grid, blk, 0, nullptr, src, dst, n16, (uint32_t*)sink); break;
+        case PEAK_READ: hipLaunchKernelGGL(k_peak_stream<PEAK_READ>, grid, blk, 0, nullptr, src, dst, n16, (uint32_t*)sink); break;
+        case PEAK_WRITE: hipLaunchKernelGGL(k_peak_stream<PEAK_WRITE>, grid, blk, 0, nullptr, src, dst, n16, (uint32_t*)sink); break;
+        case PEAK_COPY_NT: hipLaunchKernelGGL(k_peak_stream<PEAK_COPY_NT>, grid, blk, 0, nullptr, src, dst, n16, (uint32_t*)sink); break;
+        default: hipLaunchKernelGGL(k_peak_mfma, dim3(256 * 2), dim3(512), 0, nullptr, mfma_rounds, sink); break;
+      }
+    };
+    for (int i = 0; i < 2; ++i) launch();
+    LAUNCHCHK(c, "peak kernel");
+    HIPCHK(c, hipEventRecord(e0, nullptr));
+    for (int i = 0; i < iters; ++i) launch();
+    HIPCHK(c, hipEventRecord(e1, nullptr));
+    HIPCHK(c, hipEventSynchronize(e1));
+    LAUNCHCHK(c, "peak kernel");
+    float ms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    const double sec = (double)ms * 1e-3 / iters;
+    if (kind == PEAK_MFMA) *h_result = (float)(256.0 * 2 * 8 * mfma_rounds * 4 * 32768.0 / sec / 1e12);   // TFLOP/s
+    else *h_result = (float)((kind == PEAK_COPY || kind == PEAK_COPY_NT ? 2.0 : 1.0) * (double)nbytes / sec / 1e9);  // GB/s
+    return PPO_OK;
+  };
+  const int rc = body();
   if (rc) g_create_error = c->err;
   free_all(c);
   return rc;

@@ -70,6 +70,8 @@ def load_library():
         "ppo_get_grads": (C.c_int, [vp, fp, i64]),
         "ppo_set_opt_state": (C.c_int, [vp, fp, fp, i64, i64, i64]),
         "ppo_get_opt_state": (C.c_int, [vp, fp, fp, i64, C.POINTER(i64), C.POINTER(i64)]),
+        "ppo_get_adaptive_lr": (C.c_int, [vp, fp, C.POINTER(i32)]),
+        "ppo_set_adaptive_lr": (C.c_int, [vp, C.c_float, i32]),
         "ppo_buffer_write": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp, vp]),
         "ppo_buffer_write_range": (C.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
         "ppo_act": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp]),
@@ -84,6 +86,7 @@ def load_library():
         "ppo_profile": (C.c_int, [vp, i32]),
         "ppo_profile_report": (i64, [vp, C.c_char_p, i64]),
         "ppo_diag_gemm": (C.c_int, [i32, i32, i32, fp, fp, fp]),
+        "ppo_diag_peak": (C.c_int, [i32, i64, i32, fp]),
     }
     for name, (res, args) in sig.items():
         f = getattr(lib, name)
@@ -93,9 +96,9 @@ def load_library():
 
 _lib = load_library()
 EXPORTS = ("ppo_create", "ppo_destroy", "ppo_last_error", "ppo_param_count", "ppo_buffer_image_bytes",
-           "ppo_set_params", "ppo_get_params", "ppo_get_grads", "ppo_set_opt_state", "ppo_get_opt_state",
+           "ppo_set_params", "ppo_get_params", "ppo_get_grads", "ppo_set_opt_state", "ppo_get_opt_state", "ppo_get_adaptive_lr", "ppo_set_adaptive_lr",
            "ppo_buffer_write", "ppo_buffer_write_range", "ppo_act", "ppo_buffer_write_outcome", "ppo_buffer_read_obs", "ppo_gae", "ppo_get_adv_ret", "ppo_permutation", "ppo_update", "distill_update",
-           "ppo_forward", "ppo_profile", "ppo_profile_report", "ppo_diag_gemm")
+           "ppo_forward", "ppo_profile", "ppo_profile_report", "ppo_diag_gemm", "ppo_diag_peak")
 
 
 def make_desc(net: dict, num_envs: int, horizon: int, obs_dtype: str = "bf16", max_chunk: int = 0) -> NetDesc:
@@ -160,6 +163,18 @@ def diag_gemm(a: np.ndarray, b: np.ndarray) -> np.ndarray:
     return c
 
 
+PEAK_KINDS = {"copy": 0, "copy_read_only": 1, "copy_write_only": 2, "copy_nt": 3, "mfma_bf16_loop": 4}
+
+
+def diag_peak(kind: str, nbytes: int = 2 << 30, iters: int = 20) -> float:
+    """GB/s (copies; read + written bytes) or TFLOP/s (MFMA loop) of a plain kernel on the current GPU (diagnostic)."""
+    r = C.c_float()
+    rc = _lib.ppo_diag_peak(PEAK_KINDS[kind], nbytes, iters, C.byref(r))
+    if rc:
+        raise LearnerError(rc, _lib.ppo_last_error(None).decode())
+    return float(r.value)
+
+
 class Learner:
     """One learner context on the current device."""
 
@@ -222,6 +237,15 @@ class Learner:
     def set_opt_state(self, m, v, step, update_idx):
         m, v = np.ascontiguousarray(m, np.float32), np.ascontiguousarray(v, np.float32)
         self._chk(_lib.ppo_set_opt_state(self._h, _fp(m), _fp(v), m.size, step, update_idx))
+
+    def get_adaptive_lr(self):
+        """(rate, live): the KL-adaptive rate carried between updates, live False when there is none."""
+        lr, live = C.c_float(), C.c_int32()
+        self._chk(_lib.ppo_get_adaptive_lr(self._h, C.byref(lr), C.byref(live)))
+        return float(lr.value), bool(live.value)
+
+    def set_adaptive_lr(self, lr: float, live: bool = True):
+        self._chk(_lib.ppo_set_adaptive_lr(self._h, lr, int(bool(live))))
 
     # -- the path
     def buffer_write(self, t, obs, proprio, action, logp=None, value=None, reward=None, done=None):

@@ -101,12 +101,38 @@ def rollout_step(cfg: dict, rng) -> dict:
     return dict(obs=obs, proprio=proprio, action=action, logp_old=logp, value=value, reward=reward, done=done)
 
 
-def rollout(cfg: dict, seed: int | None = None) -> dict:
-    """All T steps stacked ([T][N]...), plus last_value [N]."""
-    rng = np.random.default_rng(cfg["seed"] if seed is None else seed)
+def rollout(cfg: dict, seed: int | None = None, conditioned: bool = False) -> dict:
+    """All T steps stacked ([T][N]...), plus last_value [N].
+
+    conditioned=False: the benchmark recipe, every scalar field independent noise.  The batch gradient of
+    such a rollout is a sum of B zero-mean terms that cancels like sqrt(B).
+    conditioned=True: the same observations, proprioception and actions, but the fields a learner regresses
+    on are fixed functions of them, so the batch gradient is a coherent sum (what a real rollout gives):
+      PPO:      reward = u.a + 1 + 0.1 eps   (u a fixed unit vector: advantages favour one action direction),
+                value  = 0.5 w.proprio + 0.1 eps (w a fixed unit vector), last_value = 0.1 eps;
+      student:  teacher action = c + 0.5 M proprio + 0.1 eps  (c in {-1, +1}^A, M fixed with rows of unit
+                expected norm), stored in the action slot.
+    u, w, c, M come from a generator seeded with seed + 99 only."""
+    s0 = cfg["seed"] if seed is None else seed
+    rng = np.random.default_rng(s0)
     steps = [rollout_step(cfg, rng) for _ in range(cfg["horizon"])]
     out = {k: np.stack([s[k] for s in steps]) for k in steps[0]}
     out["last_value"] = rng.standard_normal(cfg["num_envs"], dtype=np.float32)
+    if conditioned:
+        A, P = cfg["net"]["act_dim"], cfg["net"]["proprio_dim"]
+        r2 = np.random.default_rng(s0 + 99)
+        if cfg["kind"] == "distill":
+            c = r2.choice(np.array([-1.0, 1.0], np.float32), A)
+            M = (r2.standard_normal((P, A)) / math.sqrt(P)).astype(np.float32)
+            out["action"] = (c + 0.5 * (out["proprio"] @ M) + 0.1 * out["action"]).astype(np.float32)
+        else:
+            u = r2.standard_normal(A).astype(np.float32)
+            u /= np.linalg.norm(u)
+            w = r2.standard_normal(P).astype(np.float32)
+            w /= np.linalg.norm(w)
+            out["reward"] = (out["action"] @ u + 1.0 + 0.1 * out["reward"]).astype(np.float32)
+            out["value"] = (0.5 * (out["proprio"] @ w) + 0.1 * out["value"]).astype(np.float32)
+            out["last_value"] = (0.1 * out["last_value"]).astype(np.float32)
     return out
 
 

@@ -52,3 +52,39 @@ def per_tensor_param_errors(net, got, want, steps, lr):
         scale = max(np.linalg.norm(w), np.sqrt(b - a) * steps * lr)
         out[name] = float(np.linalg.norm(np.asarray(got[a:b], np.float64) - w) / scale)
     return out
+
+
+STAT_PAIRS = (("pi_loss", "pi_loss"), ("v_loss", "v_loss"), ("entropy", "entropy"), ("approx_kl", "approx_kl"),
+              ("clip_frac", "clip_frac"), ("total_loss", "total"), ("grad_norm", "grad_norm"))
+
+
+def assert_stats_close(st, ref, tol=TOL_BF16, keys=None, floor=1e-3):
+    """Library statistics record `st` against the oracle's `ref`: |x - y| <= tol * max(|y|, floor)."""
+    for k_gpu, k_or in STAT_PAIRS:
+        if keys is not None and k_gpu not in keys:
+            continue
+        assert abs(st[k_gpu] - ref[k_or]) <= tol * max(abs(ref[k_or]), floor), (k_gpu, st[k_gpu], ref[k_or])
+
+
+def adam_determined(net, g_first, tol=TOL_BF16):
+    """Boolean mask over the canonical parameter vector: elements whose first Adam step a gradient that is accurate
+    to `tol` determines.  From zero moments Adam moves element i by -lr * g_i / (|g_i| + eps) = -lr * sign(g_i); the
+    sign of an element with |g_i| <= tol * rms(g over its tensor) is not fixed by a gradient whose per-tensor error
+    is tol, whatever computes it (such elements keep ratios of rounding noise as their steps afterwards too)."""
+    g = np.asarray(g_first, np.float64)
+    mask = np.zeros(g.size, bool)
+    for _, (a, b, _) in synth.param_slices(net).items():
+        rms = np.sqrt(np.mean(g[a:b] ** 2))
+        mask[a:b] = np.abs(g[a:b]) > tol * rms
+    return mask
+
+
+def masked_param_errors(net, got, want, mask):
+    """{tensor: relative L2 error of the updated parameters over the elements of `mask`}, each relative to the
+    norm of the oracle's tensor over the same elements."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    out = {}
+    for name, (a, b, _) in synth.param_slices(net).items():
+        k = mask[a:b]
+        out[name] = float(np.linalg.norm((got[a:b] - want[a:b])[k]) / max(np.linalg.norm(want[a:b][k]), 1e-30)) if k.any() else 0.0
+    return out

@@ -3,6 +3,7 @@ argument validation (which runs before any HIP call) returns the documented code
 import ctypes as C
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -10,12 +11,15 @@ from paper_2509_16434_amd import configs, learner as L
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "ppo_learner.h")
+DIAG_HEADER = os.path.join(ROOT, "include", "ppo_learner_diag.h")   # tracing / diagnostic aids, not the learner's path
 
 
-def _declared():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return re.findall(r"^(?:int|int64_t|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
+def _declared(headers=(HEADER, DIAG_HEADER)):
+    names = []
+    for h in headers:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names += re.findall(r"^(?:int|int64_t|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
+    return names
 
 
 def test_library_exports_every_declared_function():
@@ -29,8 +33,9 @@ def test_library_exports_every_declared_function():
 
 
 def test_the_four_path_entry_points_are_declared():
-    names = set(_declared())
+    names = set(_declared((HEADER,)))
     assert {"ppo_buffer_write", "ppo_gae", "ppo_update", "distill_update"} <= names
+    assert set(_declared((DIAG_HEADER,))) == {"ppo_profile", "ppo_profile_report", "ppo_diag_gemm", "ppo_diag_peak"}
 
 
 def test_struct_sizes_match_the_header_layout():
@@ -44,9 +49,17 @@ def test_struct_sizes_match_the_header_layout():
     assert names == [("lambda" if f == "lam" else f) for f, _ in L.HParams._fields_]
 
 
-def test_header_is_plain_c():
-    text = open(HEADER).read()
-    assert 'extern "C"' in text and "torch" not in text and "std::" not in text
+def test_header_is_plain_c(tmp_path):
+    for h in (HEADER, DIAG_HEADER):
+        text = open(h).read()
+        assert 'extern "C"' in text and "torch" not in text and "std::" not in text
+    # both headers compile as C99 and as C++, on their own, with every warning an error
+    src = tmp_path / "use.c"
+    src.write_text('#include "ppo_learner_diag.h"\nint main(void) { ppo_hparams hp; ppo_net_desc d; ppo_mb_stats s; (void)hp; (void)d; (void)s;'
+                   ' return PPO_OK == 0 ? 0 : 1; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src)])
+    subprocess.check_call(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)])
 
 
 @pytest.mark.parametrize("change,code", [
@@ -87,6 +100,8 @@ def test_null_handles_are_einval_not_a_crash():
     assert lib.ppo_buffer_write_outcome(None, 0, None, None) == L.PPO_EINVAL
     assert lib.ppo_param_count(None) < 0
     assert lib.ppo_diag_gemm(4, 4, 7, None, None, None) == L.PPO_EINVAL
+    assert lib.ppo_get_adaptive_lr(None, None, None) == L.PPO_EINVAL
+    assert lib.ppo_set_adaptive_lr(None, 1e-3, 1) == L.PPO_EINVAL
 
 
 def test_binding_refuses_host_tensors():

@@ -109,12 +109,38 @@ def test_buffer_write_by_environment_ranges(L):
         part.buffer_write_range(0, 40, dev(ro["obs"][0][:11]), *[dev(ro[k][0][:11]) for k in
                                 ("proprio", "action", "logp_old", "value", "reward", "done")])
     assert e.value.code == L.PPO_EINVAL
-    # a partial write into a complete step makes it incomplete again
-    part.buffer_write_range(2, 0, dev(ro["obs"][2][:5]), *[dev(ro[k][2][:5]) for k in
-                            ("proprio", "action", "logp_old", "value", "reward", "done")])
+    # a range that arrives when the whole rollout is complete begins the NEXT rollout: no step counts as written
+    # (the slabs still hold the first rollout) until its own ranges cover all environments again
+    ro2 = synth.rollout(cfg, seed=cfg["seed"] + 1)
+    fields = ("proprio", "action", "logp_old", "value", "reward", "done")
+    part.buffer_write_range(2, 0, dev(ro2["obs"][2][:5]), *[dev(ro2[k][2][:5]) for k in fields])
     with pytest.raises(L.LearnerError) as e:
         part.gae(lv, hp["gamma"], hp["lam"])
     assert e.value.code == L.PPO_ESTATE
+    part.buffer_write_range(2, 5, dev(ro2["obs"][2][5:]), *[dev(ro2[k][2][5:]) for k in fields])   # step 2 complete, 0, 1, 3 are not
+    for t in (3, 1):
+        for a, b in ((25, 50), (0, 25)):
+            part.buffer_write_range(t, a, dev(ro2["obs"][t][a:b]), *[dev(ro2[k][t][a:b]) for k in fields])
+    with pytest.raises(L.LearnerError) as e:    # step 0 still holds only the first rollout's record
+        part.gae(lv, hp["gamma"], hp["lam"])
+    assert e.value.code == L.PPO_ESTATE
+    with pytest.raises(L.LearnerError) as e:
+        part.buffer_read_obs(0)
+    assert e.value.code == L.PPO_ESTATE
+    part.buffer_write_range(0, 0, dev(ro2["obs"][0]), *[dev(ro2[k][0]) for k in fields])
+    # within a rollout, a partial write into a complete step makes that step (only) incomplete again
+    part.buffer_write_range(3, 10, dev(ro2["obs"][3][10:20]), *[dev(ro2[k][3][10:20]) for k in fields])
+    with pytest.raises(L.LearnerError) as e:
+        part.gae(lv, hp["gamma"], hp["lam"])
+    assert e.value.code == L.PPO_ESTATE
+    for a, b in ((0, 10), (20, 50)):
+        part.buffer_write_range(3, a, dev(ro2["obs"][3][a:b]), *[dev(ro2[k][3][a:b]) for k in fields])
+    fill_learner(full, cfg, ro2)
+    lv2 = dev(ro2["last_value"])
+    for x in (full, part):
+        x.gae(lv2, hp["gamma"], hp["lam"])
+        x.update(hp)
+    np.testing.assert_array_equal(part.get_params(), full.get_params())
 
 
 # ------------------------------------------------------------------ GAE
@@ -878,3 +904,37 @@ def test_update_is_deterministic_and_resumable(L):
         x.gae(torch.from_numpy(ro["last_value"]).cuda(), hp["gamma"], hp["lam"])
         x.update(hp)
     np.testing.assert_array_equal(a.get_params(), b.get_params())
+
+
+def test_resume_carries_the_adaptive_rate(L):
+    """Checkpoint of a context that runs the KL-adaptive rate with lr_carry: parameters, optimiser state AND the rate
+    the last update ended with; the resumed context's next update is bit-identical, and without the rate it is not."""
+    torch = _torch()
+    cfg = configs.get_config(0, num_envs=64, horizon=16)
+    hp = dict(cfg["hp"], epochs=3, seed=7, desired_kl=1e-6, lr_min=1e-5, lr_max=1e-2, lr_carry=1)   # every divergence is above 2e-6: the rate falls
+    a, ro, params = _setup(L, cfg)
+    lv = torch.from_numpy(ro["last_value"]).cuda()
+    assert a.get_adaptive_lr() == (0.0, False)
+    a.gae(lv, hp["gamma"], hp["lam"])
+    st = a.update(hp)
+    lr, live = a.get_adaptive_lr()
+    assert live and lr == st[-1]["lr"] and lr < hp["lr"]
+    ckpt = (a.get_params(), a.get_opt_state(), lr)
+    outs = []
+    for with_rate in (True, False):
+        b = L.Learner(cfg["net"], cfg["num_envs"], cfg["horizon"], cfg["obs_dtype"])
+        b.set_params(ckpt[0])
+        b.set_opt_state(*ckpt[1])
+        if with_rate:
+            b.set_adaptive_lr(ckpt[2])
+        fill_learner(b, cfg, ro)
+        b.gae(lv, hp["gamma"], hp["lam"])
+        outs.append((b.update(hp), b.get_params()))
+    a.update(hp)
+    np.testing.assert_array_equal(a.get_params(), outs[0][1])
+    assert outs[0][0][0]["lr"] != outs[1][0][0]["lr"] and not np.array_equal(outs[0][1], outs[1][1])
+    with pytest.raises(L.LearnerError) as e:
+        a.set_adaptive_lr(-1.0)
+    assert e.value.code == L.PPO_EINVAL
+    a.set_adaptive_lr(0.0, live=False)
+    assert a.get_adaptive_lr() == (0.0, False)
