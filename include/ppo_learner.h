@@ -184,6 +184,18 @@ int ppo_get_adv_ret(ppo_ctx* ctx, float* d_adv, float* d_ret);
  * HOST int32[N*T]); minibatch m is entries [m*B, (m+1)*B). */
 int ppo_permutation(ppo_ctx* ctx, uint64_t seed, uint64_t update_idx, uint64_t epoch, int32_t* h_perm);
 
+/* ppo_permutation for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): needs no context and calls no hipMalloc / hipFree or any allocating
+ * routine.  The same kernels write the permutation of 0..S-1 for (seed, update_idx, epoch) into the DEVICE array
+ * d_perm [S] (int32, caller-owned), enqueued on hip_stream (a hipStream_t, may be NULL); nothing synchronises.
+ * Their scratch (histogram, bucket starts, bucket-ordered indices) lives in a static device array of the
+ * library, 4.4 MiB per GPU the library is used on, resolved once per device on the first call there (or by
+ * ppo_create).  S <= PPO_STATIC_PERM_MAX (else PPO_ESHAPE); S = 0 is a no-op.  All calls on one GPU share that
+ * array: two calls whose work overlaps in time on one GPU (different streams, or different threads) race;
+ * calls on one stream are ordered and safe.  Errors are reported through ppo_last_error(NULL). */
+#define PPO_STATIC_PERM_MAX (1 << 20)
+int ppo_permutation_static(int64_t S, uint64_t seed, uint64_t update_idx, uint64_t epoch, int32_t* d_perm, void* hip_stream);
+
 /* TrainPPO (Algorithm 2): epochs x minibatches of forward, clipped-surrogate + value +
  * entropy loss, backward and one Adam step each.  Needs ppo_gae (else PPO_ESTATE).
  * host_stats: HOST array [epochs*minibatches] or NULL (NULL = fully asynchronous). */

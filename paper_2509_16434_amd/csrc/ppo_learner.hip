@@ -11,6 +11,7 @@
 
 #include <algorithm>
 #include <map>
+#include <mutex>
 #include <string>
 #include <utility>
 #include <vector>
@@ -29,9 +30,39 @@
 
 static_assert(sizeof(DevStats) == sizeof(ppo_mb_stats), "device and host statistics records must match");
 
+// Scratch of ppo_permutation_static: bucket histogram + cursors [2*nb], bucket starts [nb], bucket-ordered
+// indices [S], for up to STATIC_PERM_MAX_S samples (nb <= STATIC_PERM_MAX_NB buckets of about 32 keys).  Every GPU
+// the library runs on holds its own copy of this array until the process ends (4.4 MiB).
+constexpr int64_t STATIC_PERM_MAX_S = 1 << 20;
+constexpr int STATIC_PERM_MAX_NB = 1 << 15;
+constexpr int STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) int32_t scratch[3 * STATIC_PERM_MAX_NB + STATIC_PERM_MAX_S];
+
 namespace {
 
 thread_local std::string g_create_error;
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a stand-in for the
+// symbol, not an address a kernel can use: the address is asked for once per device (with that device current)
+// and kept; host code passes this pointer, never the name, to kernels.
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[STATIC_MAX_DEVICES] = {};
+hipError_t static_scratch(int32_t** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = (int32_t*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 struct Ctx {
   ppo_net_desc d;
@@ -1095,6 +1126,7 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
 
 int create_impl(Ctx* c) {
   build_geometry(c);
+  { int32_t* ws = nullptr; HIPCHK(c, static_scratch(&ws)); }  // the static scratch of ppo_permutation_static on this device
   const int V = c->V;
   int CH = c->d.max_chunk > 0 ? c->d.max_chunk : 16384 / V;
   if (CH > c->S) CH = c->S;
@@ -1452,6 +1484,40 @@ int ppo_permutation(ppo_ctx* c, uint64_t seed, uint64_t update_idx, uint64_t epo
   if (rc) return rc;
   HIPCHK(c, hipMemcpyAsync(h_perm, c->perm, sizeof(int32_t) * (size_t)c->S, hipMemcpyDeviceToHost, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
+  return PPO_OK;
+}
+
+int ppo_permutation_static(int64_t S, uint64_t seed, uint64_t update_idx, uint64_t epoch, int32_t* d_perm, void* hip_stream) {
+  if (S < 0) return fail(nullptr, PPO_EINVAL, "S must be >= 0");
+  if (S > STATIC_PERM_MAX_S)
+    return fail(nullptr, PPO_ESHAPE, "ppo_permutation_static handles at most %lld samples (got %lld); use a context's ppo_permutation",
+                (long long)STATIC_PERM_MAX_S, (long long)S);
+  if (S == 0) return PPO_OK;
+  if (!d_perm) return fail(nullptr, PPO_EINVAL, "d_perm is NULL");
+  int32_t* ws = nullptr;
+  {
+    const hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return fail(nullptr, PPO_EHIP, "address of the static scratch array: %s", hipGetErrorString(e));
+  }
+  // the bucket count of ppo_create (about 32 keys per bucket), so both entry points run the same kernels on the same grids
+  int nb = 1, lg = 0;
+  while ((int64_t)nb * 32 < S && nb < STATIC_PERM_MAX_NB) { nb <<= 1; ++lg; }
+  const int shift = 64 - lg;
+  int32_t* hist = ws;                  // [2 * nb]: counts, then scatter cursors
+  int32_t* start = ws + 2 * (int64_t)STATIC_PERM_MAX_NB;  // [nb]
+  int32_t* tmp = ws + 3 * (int64_t)STATIC_PERM_MAX_NB;    // [S]
+  hipStream_t st = (hipStream_t)hip_stream;
+  PermStreams ps;
+  for (int e = 0; e < PERM_BATCH; ++e) ps.s[e] = perm_stream(seed, update_idx, epoch);
+  const int g = cdiv(S, 256), Si = (int)S;
+  // the array keeps the last call's contents: counts and cursors must start at zero (a fill kernel, so that a
+  // caller may record this call into a graph); start and tmp are fully overwritten before they are read
+  hipLaunchKernelGGL(k_fill_i32, dim3(cdiv((int64_t)2 * nb, 256)), dim3(256), 0, st, hist, (int64_t)2 * nb, 0);
+  hipLaunchKernelGGL(k_perm_hist, dim3(g, 1), dim3(256), 0, st, ps, Si, shift, nb, hist);
+  hipLaunchKernelGGL(k_perm_scan, dim3(1, 1), dim3(1024), 0, st, hist, start, nb);
+  hipLaunchKernelGGL(k_perm_scatter, dim3(g, 1), dim3(256), 0, st, ps, Si, shift, nb, start, hist, tmp);
+  hipLaunchKernelGGL(k_perm_rank, dim3(g, 1), dim3(256), 0, st, ps, Si, shift, nb, start, hist, tmp, d_perm);
+  LAUNCHCHK(nullptr, "permutation kernels");
   return PPO_OK;
 }
 

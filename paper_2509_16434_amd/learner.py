@@ -80,6 +80,7 @@ def load_library():
         "ppo_gae": (C.c_int, [vp, vp, C.c_float, C.c_float]),
         "ppo_get_adv_ret": (C.c_int, [vp, vp, vp]),
         "ppo_permutation": (C.c_int, [vp, u64, u64, u64, C.POINTER(i32)]),
+        "ppo_permutation_static": (C.c_int, [i64, u64, u64, u64, vp, vp]),
         "ppo_update": (C.c_int, [vp, C.POINTER(HParams), C.POINTER(MbStats)]),
         "distill_update": (C.c_int, [vp, C.POINTER(HParams), C.POINTER(MbStats)]),
         "ppo_forward": (C.c_int, [vp, vp, i64, vp, vp]),
@@ -97,7 +98,7 @@ def load_library():
 _lib = load_library()
 EXPORTS = ("ppo_create", "ppo_destroy", "ppo_last_error", "ppo_param_count", "ppo_buffer_image_bytes",
            "ppo_set_params", "ppo_get_params", "ppo_get_grads", "ppo_set_opt_state", "ppo_get_opt_state", "ppo_get_adaptive_lr", "ppo_set_adaptive_lr",
-           "ppo_buffer_write", "ppo_buffer_write_range", "ppo_act", "ppo_buffer_write_outcome", "ppo_buffer_read_obs", "ppo_gae", "ppo_get_adv_ret", "ppo_permutation", "ppo_update", "distill_update",
+           "ppo_buffer_write", "ppo_buffer_write_range", "ppo_act", "ppo_buffer_write_outcome", "ppo_buffer_read_obs", "ppo_gae", "ppo_get_adv_ret", "ppo_permutation", "ppo_permutation_static", "ppo_update", "distill_update",
            "ppo_forward", "ppo_profile", "ppo_profile_report", "ppo_diag_gemm", "ppo_diag_peak")
 
 
@@ -173,6 +174,22 @@ def diag_peak(kind: str, nbytes: int = 2 << 30, iters: int = 20) -> float:
     if rc:
         raise LearnerError(rc, _lib.ppo_last_error(None).decode())
     return float(r.value)
+
+
+STATIC_PERM_MAX = 1 << 20
+
+
+def permutation_static(S: int, seed: int, update_idx: int, epoch: int, out=None, stream=None):
+    """ppo_permutation_static: the permutation of 0..S-1 into the int32 CUDA tensor `out` (allocated here when
+    None; the library itself allocates nothing), enqueued on `stream` (None: the default stream)."""
+    import torch
+    if out is None:
+        out = torch.empty(max(S, 0), dtype=torch.int32, device="cuda")
+    sp = C.c_void_p(stream.cuda_stream) if stream is not None else None
+    rc = _lib.ppo_permutation_static(S, seed, update_idx, epoch, _dev(out, torch.int32) if S > 0 else None, sp)
+    if rc:
+        raise LearnerError(rc, _lib.ppo_last_error(None).decode())
+    return out
 
 
 class Learner:

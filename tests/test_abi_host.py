@@ -56,10 +56,21 @@ def test_header_is_plain_c(tmp_path):
     # both headers compile as C99 and as C++, on their own, with every warning an error
     src = tmp_path / "use.c"
     src.write_text('#include "ppo_learner_diag.h"\nint main(void) { ppo_hparams hp; ppo_net_desc d; ppo_mb_stats s; (void)hp; (void)d; (void)s;'
-                   ' return PPO_OK == 0 ? 0 : 1; }\n')
+                   ' return PPO_STATIC_PERM_MAX > 0 && PPO_OK == 0 ? 0 : 1; }\n')
     inc = os.path.join(ROOT, "include")
     subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src)])
     subprocess.check_call(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)])
+
+
+def test_static_permutation_validates_before_touching_the_gpu():
+    lib = L._lib
+    assert lib.ppo_permutation_static(-1, 1, 1, 1, None, None) == L.PPO_EINVAL
+    assert lib.ppo_permutation_static(L.STATIC_PERM_MAX + 1, 1, 1, 1, None, None) == L.PPO_ESHAPE
+    assert b"at most" in lib.ppo_last_error(None)
+    assert lib.ppo_permutation_static(0, 1, 1, 1, None, None) == L.PPO_OK
+    assert lib.ppo_permutation_static(16, 1, 1, 1, None, None) == L.PPO_EINVAL   # d_perm is NULL
+    text = open(HEADER).read()
+    assert "#define PPO_STATIC_PERM_MAX (1 << 20)" in text and L.STATIC_PERM_MAX == 1 << 20
 
 
 @pytest.mark.parametrize("change,code", [
