@@ -38,6 +38,14 @@
  *                                                 flat in (c,h,w) order)
  *       head:  W_mu[A][h], b_mu[A]
  *       if has_value_head: w_v[h], b_v, logstd[A]
+ *   (the full order with the optional layer-norm, embedding, LSTM and auxiliary-head
+ *    parameters is given at make_geom)
+ *
+ * Pins of the recurrent teacher's parts and of the auxiliary MLP head (tests/test_oracle_pins.py):
+ * layer normalisation against a library group normalisation, the LSTM against a library LSTM module
+ * (forward, final state, gradients through time), state resets at done flags against a sequence cut
+ * by hand, the whole recurrent forward/loss/backward against fp64 automatic differentiation and
+ * central finite differences, the auxiliary head against automatic differentiation.
  */
 #include <math.h>
 #include <stdint.h>
@@ -55,6 +63,14 @@ typedef struct {
   int32_t n_conv, conv_ch[ORC_MAX_LAYERS], conv_k, conv_stride, conv_pad;
   int32_t n_fc, fc_dim[ORC_MAX_LAYERS];
   int32_t has_value_head;
+  /* the deployed student's extra MLP head (Sec. IV-C): with aux_hidden > 0 the last aux_dim output
+   * columns come from  W_a2 relu(W_a1 h + b_a1) + b_a2  on the last hidden layer h instead of the
+   * linear mean head (which then has act_dim - aux_dim rows) */
+  int32_t aux_hidden, aux_dim;
+  /* the paper's own teacher (Sec. III-C, Fig. 3): layer normalisation after every convolution,
+   * a linear embedding of each view's flattened features, LSTM layers between the concatenation
+   * with the proprioception and the MLP */
+  int32_t layer_norm, embed_dim, lstm_layers, lstm_units;
 } orc_net;
 
 typedef struct {
@@ -78,18 +94,25 @@ enum { ST_PI = 0, ST_V, ST_ENT, ST_KL, ST_CLIPFRAC, ST_GNORM, ST_TOTAL, ST_LR, S
 /* ------------------------------------------------------------------ */
 static int conv_out(int in, int k, int s, int p) { return (in + 2 * p - k) / s + 1; }
 
+#define ORC_MAX_LSTM 4
 typedef struct {
-  int n_conv, n_fc;
+  int n_conv, n_fc, nl, H;
   int c[ORC_MAX_LAYERS + 1], h[ORC_MAX_LAYERS + 1], w[ORC_MAX_LAYERS + 1];
   int fc_in[ORC_MAX_LAYERS + 1], fc_out[ORC_MAX_LAYERS + 1];
-  int64_t convW[ORC_MAX_LAYERS], convB[ORC_MAX_LAYERS];
+  int lstm_in[ORC_MAX_LSTM];
+  int64_t convW[ORC_MAX_LAYERS], convB[ORC_MAX_LAYERS], lnG[ORC_MAX_LAYERS], lnB[ORC_MAX_LAYERS];
+  int64_t embW, embB;
+  int64_t lstmWih[ORC_MAX_LSTM], lstmWhh[ORC_MAX_LSTM], lstmB[ORC_MAX_LSTM];
   int64_t fcW[ORC_MAX_LAYERS], fcB[ORC_MAX_LAYERS];
-  int64_t muW, muB, vW, vB, logstd, total;
-  int flat, feat, hid;
+  int64_t muW, muB, vW, vB, logstd, a1W, a1B, a2W, a2B, total;
+  int flat, enc, feat, trunk_in, hid, A_main;
 } geom;
 
+/* Canonical parameter order: for each conv l: W, b, [LN gain[Co], LN shift[Co]]; [embedding W[E][flat], b[E]];
+ * for each LSTM layer: W_ih[4H][in], W_hh[4H][H], b[4H] (gate order i, f, g, o); for each hidden layer W, b;
+ * mean head W[A_main][h], b; [value head w[h], b; logstd[A]]; [aux head W_a1[X][h], b_a1, W_a2[aux_dim][X], b_a2]. */
 static void make_geom(const orc_net *n, geom *g) {
-  g->n_conv = n->n_conv; g->n_fc = n->n_fc;
+  g->n_conv = n->n_conv; g->n_fc = n->n_fc; g->nl = n->lstm_layers; g->H = n->lstm_units;
   g->c[0] = n->in_c; g->h[0] = n->in_h; g->w[0] = n->in_w;
   int64_t off = 0;
   for (int l = 0; l < n->n_conv; ++l) {
@@ -98,10 +121,22 @@ static void make_geom(const orc_net *n, geom *g) {
     g->w[l + 1] = conv_out(g->w[l], n->conv_k, n->conv_stride, n->conv_pad);
     g->convW[l] = off; off += (int64_t)g->c[l + 1] * g->c[l] * n->conv_k * n->conv_k;
     g->convB[l] = off; off += g->c[l + 1];
+    g->lnG[l] = g->lnB[l] = -1;
+    if (n->layer_norm) { g->lnG[l] = off; off += g->c[l + 1]; g->lnB[l] = off; off += g->c[l + 1]; }
   }
   g->flat = g->c[n->n_conv] * g->h[n->n_conv] * g->w[n->n_conv];
-  int in = n->n_views * g->flat + n->proprio_dim;
+  g->embW = g->embB = -1; g->enc = g->flat;
+  if (n->embed_dim > 0) { g->enc = n->embed_dim; g->embW = off; off += (int64_t)n->embed_dim * g->flat; g->embB = off; off += n->embed_dim; }
+  int in = n->n_views * g->enc + n->proprio_dim;
   g->feat = in;
+  for (int l = 0; l < g->nl; ++l) {
+    g->lstm_in[l] = in;
+    g->lstmWih[l] = off; off += (int64_t)4 * g->H * in;
+    g->lstmWhh[l] = off; off += (int64_t)4 * g->H * g->H;
+    g->lstmB[l] = off; off += 4 * g->H;
+    in = g->H;
+  }
+  g->trunk_in = in;
   for (int l = 0; l < n->n_fc; ++l) {
     g->fc_in[l] = in; g->fc_out[l] = n->fc_dim[l];
     g->fcW[l] = off; off += (int64_t)in * n->fc_dim[l];
@@ -109,13 +144,21 @@ static void make_geom(const orc_net *n, geom *g) {
     in = n->fc_dim[l];
   }
   g->hid = in;
-  g->muW = off; off += (int64_t)n->act_dim * in;
-  g->muB = off; off += n->act_dim;
+  g->A_main = n->act_dim - (n->aux_hidden > 0 ? n->aux_dim : 0);
+  g->muW = off; off += (int64_t)g->A_main * in;
+  g->muB = off; off += g->A_main;
   g->vW = g->vB = g->logstd = -1;
   if (n->has_value_head) {
     g->vW = off; off += in;
     g->vB = off; off += 1;
     g->logstd = off; off += n->act_dim;
+  }
+  g->a1W = g->a1B = g->a2W = g->a2B = -1;
+  if (n->aux_hidden > 0) {
+    g->a1W = off; off += (int64_t)n->aux_hidden * in;
+    g->a1B = off; off += n->aux_hidden;
+    g->a2W = off; off += (int64_t)n->aux_dim * n->aux_hidden;
+    g->a2B = off; off += n->aux_dim;
   }
   g->total = off;
 }
@@ -284,138 +327,355 @@ static void lin_bwd(const double *x, int in, const double *w, int out, const dou
   }
 }
 
-/* per-sample activation storage */
+/* ------------------------------------------------------------------ */
+/* Layer normalisation of one convolution output (Ba, Kiros, Hinton     */
+/* 2016), statistics over all C*H*W values of one sample, gain and      */
+/* shift per channel:                                                   */
+/*   mean = avg(x), var = avg((x-mean)^2)  (population variance)        */
+/*   xhat = (x - mean) / sqrt(var + 1e-5),  y[c][.] = g[c] xhat + b[c]  */
+/* ------------------------------------------------------------------ */
+#define ORC_LN_EPS 1e-5
+static void ln_fwd(const double *x, int C, int HW, const double *gain, const double *shift, double *xhat,
+                   double *rstd_out, double *y) {
+  int64_t m = (int64_t)C * HW;
+  double mean = 0, var = 0;
+  for (int64_t i = 0; i < m; ++i) mean += x[i];
+  mean /= (double)m;
+  for (int64_t i = 0; i < m; ++i) var += (x[i] - mean) * (x[i] - mean);
+  var /= (double)m;
+  double rstd = 1.0 / sqrt(var + ORC_LN_EPS);
+  for (int c = 0; c < C; ++c)
+    for (int k = 0; k < HW; ++k) {
+      int64_t i = (int64_t)c * HW + k;
+      xhat[i] = (x[i] - mean) * rstd;
+      y[i] = gain[c] * xhat[i] + shift[c];
+    }
+  *rstd_out = rstd;
+}
+/* adjoint of ln_fwd: dgain, dshift accumulate; dx = rstd (dxhat - avg(dxhat) - xhat avg(dxhat xhat)) */
+static void ln_bwd(const double *dy, const double *xhat, double rstd, int C, int HW, const double *gain,
+                   double *dgain, double *dshift, double *dx) {
+  int64_t m = (int64_t)C * HW;
+  double s1 = 0, s2 = 0;
+  for (int c = 0; c < C; ++c)
+    for (int k = 0; k < HW; ++k) {
+      int64_t i = (int64_t)c * HW + k;
+      dgain[c] += dy[i] * xhat[i];
+      dshift[c] += dy[i];
+      double dxh = dy[i] * gain[c];
+      s1 += dxh; s2 += dxh * xhat[i];
+    }
+  s1 /= (double)m; s2 /= (double)m;
+  for (int c = 0; c < C; ++c)
+    for (int k = 0; k < HW; ++k) {
+      int64_t i = (int64_t)c * HW + k;
+      dx[i] = rstd * (dy[i] * gain[c] - s1 - xhat[i] * s2);
+    }
+}
+
+static double sigmoid(double x) { return 1.0 / (1.0 + exp(-x)); }
+
+/* activations of ONE time step of one environment */
 typedef struct {
-  /* conv activations per view: act[v][l] for l = 0..n_conv (0 = input image), post-ReLU */
-  double *conv[4][ORC_MAX_LAYERS + 1];
-  double *feat;                       /* fc0 input: [views*flat + P] */
-  double *fc[ORC_MAX_LAYERS];         /* post-ReLU hidden activations */
-  double *mu; double v;
-  /* gradient scratch */
-  double *dconv[ORC_MAX_LAYERS + 1];
-  double *dfeat; double *dfc[ORC_MAX_LAYERS];
+  double *conv[4][ORC_MAX_LAYERS + 1];  /* per view: input image (l = 0), then each layer's output after ReLU */
+  double *xhat[4][ORC_MAX_LAYERS + 1];  /* with layer_norm: normalised conv output of layer l-1 at index l */
+  double rstd[4][ORC_MAX_LAYERS + 1];
+  double *feat;                         /* [views*enc + P]: encoder outputs, then proprioception */
+  double *gate[ORC_MAX_LSTM];           /* [4H]: i, f, g, o after their nonlinearities */
+  double *cell[ORC_MAX_LSTM], *hid[ORC_MAX_LSTM], *tcell[ORC_MAX_LSTM];  /* c_t, h_t, tanh(c_t) */
+  double *cin[ORC_MAX_LSTM], *hin[ORC_MAX_LSTM];                         /* the state that entered the step */
+  double *fc[ORC_MAX_LAYERS];           /* hidden activations after ReLU */
+  double *aux;                          /* [aux_hidden] after ReLU */
+  double *mu; double v;                 /* outputs: [A] (aux head's columns last), value */
 } acts;
 
+typedef struct {  /* gradient scratch of one environment (reused by every step) */
+  double *dconv[ORC_MAX_LAYERS + 1], *dpre;
+  double *dfeat, *dfc[ORC_MAX_LAYERS], *daux, *dtrunk;
+  double *dx[ORC_MAX_LSTM + 1];  /* gradient w.r.t. the input of LSTM layer l; [nl] = w.r.t. the top output */
+  double *da;                    /* [4H] gate pre-activation gradients */
+  double *dh_next[ORC_MAX_LSTM], *dc_next[ORC_MAX_LSTM];  /* from step t+1 into (h_t, c_t) */
+  double *tmp;                   /* conv scratch */
+} grads_ws;
+
+static double *dalloc(int64_t n) { return (double *)calloc((size_t)(n > 0 ? n : 1), sizeof(double)); }
+
 static void acts_alloc(const orc_net *n, const geom *g, acts *a) {
+  memset(a, 0, sizeof *a);
   for (int v = 0; v < n->n_views; ++v)
-    for (int l = 0; l <= n->n_conv; ++l)
-      a->conv[v][l] = (double *)malloc(sizeof(double) * (size_t)g->c[l] * g->h[l] * g->w[l]);
-  for (int l = 0; l <= n->n_conv; ++l)
-    a->dconv[l] = (double *)malloc(sizeof(double) * (size_t)g->c[l] * g->h[l] * g->w[l]);
-  a->feat = (double *)malloc(sizeof(double) * (size_t)g->feat);
-  a->dfeat = (double *)malloc(sizeof(double) * (size_t)g->feat);
-  for (int l = 0; l < n->n_fc; ++l) {
-    a->fc[l] = (double *)malloc(sizeof(double) * (size_t)g->fc_out[l]);
-    a->dfc[l] = (double *)malloc(sizeof(double) * (size_t)g->fc_out[l]);
+    for (int l = 0; l <= n->n_conv; ++l) {
+      a->conv[v][l] = dalloc((int64_t)g->c[l] * g->h[l] * g->w[l]);
+      if (n->layer_norm && l > 0) a->xhat[v][l] = dalloc((int64_t)g->c[l] * g->h[l] * g->w[l]);
+    }
+  a->feat = dalloc(g->feat);
+  for (int l = 0; l < g->nl; ++l) {
+    a->gate[l] = dalloc(4 * g->H); a->cell[l] = dalloc(g->H); a->hid[l] = dalloc(g->H); a->tcell[l] = dalloc(g->H);
+    a->cin[l] = dalloc(g->H); a->hin[l] = dalloc(g->H);
   }
-  a->mu = (double *)malloc(sizeof(double) * (size_t)n->act_dim);
+  for (int l = 0; l < n->n_fc; ++l) a->fc[l] = dalloc(g->fc_out[l]);
+  a->aux = dalloc(n->aux_hidden);
+  a->mu = dalloc(n->act_dim);
 }
-static void acts_free(const orc_net *n, acts *a) {
+static void acts_free(const orc_net *n, const geom *g, acts *a) {
   for (int v = 0; v < n->n_views; ++v)
-    for (int l = 0; l <= n->n_conv; ++l) free(a->conv[v][l]);
-  for (int l = 0; l <= n->n_conv; ++l) free(a->dconv[l]);
-  free(a->feat); free(a->dfeat);
-  for (int l = 0; l < n->n_fc; ++l) { free(a->fc[l]); free(a->dfc[l]); }
-  free(a->mu);
+    for (int l = 0; l <= n->n_conv; ++l) { free(a->conv[v][l]); free(a->xhat[v][l]); }
+  free(a->feat);
+  for (int l = 0; l < g->nl; ++l) { free(a->gate[l]); free(a->cell[l]); free(a->hid[l]); free(a->tcell[l]); free(a->cin[l]); free(a->hin[l]); }
+  for (int l = 0; l < n->n_fc; ++l) free(a->fc[l]);
+  free(a->aux); free(a->mu);
+}
+static void ws_alloc(const orc_net *n, const geom *g, grads_ws *w) {
+  memset(w, 0, sizeof *w);
+  int64_t mx = 0;
+  for (int l = 0; l <= n->n_conv; ++l) {
+    int64_t m = (int64_t)g->c[l] * g->h[l] * g->w[l];
+    w->dconv[l] = dalloc(m);
+    if (m > mx) mx = m;
+  }
+  w->dpre = dalloc(mx); w->tmp = dalloc(mx);
+  w->dfeat = dalloc(g->feat); w->dtrunk = dalloc(g->trunk_in); w->daux = dalloc(n->aux_hidden);
+  for (int l = 0; l < n->n_fc; ++l) w->dfc[l] = dalloc(g->fc_out[l]);
+  for (int l = 0; l <= g->nl; ++l) w->dx[l] = dalloc(l < g->nl ? g->lstm_in[l] : g->H);
+  w->da = dalloc(4 * g->H);
+  for (int l = 0; l < g->nl; ++l) { w->dh_next[l] = dalloc(g->H); w->dc_next[l] = dalloc(g->H); }
+}
+static void ws_free(const orc_net *n, const geom *g, grads_ws *w) {
+  for (int l = 0; l <= n->n_conv; ++l) free(w->dconv[l]);
+  free(w->dpre); free(w->tmp); free(w->dfeat); free(w->dtrunk); free(w->daux);
+  for (int l = 0; l < n->n_fc; ++l) free(w->dfc[l]);
+  for (int l = 0; l <= g->nl; ++l) free(w->dx[l]);
+  free(w->da);
+  for (int l = 0; l < g->nl; ++l) { free(w->dh_next[l]); free(w->dc_next[l]); }
 }
 
-/* Forward of one sample: conv stack (+bias, ReLU) on each view with shared
- * weights, flatten in (c,h,w) order, views side by side, append proprio,
- * hidden layers (+bias, ReLU), linear heads (no squashing). */
-static void sample_forward(const orc_net *n, const geom *g, const double *P, const float *obs,
-                           const double *proprio, acts *a) {
+/* Forward of one time step of one environment.
+ *   encoder, per view with shared weights: conv (+bias) [-> layer norm] -> ReLU, ..., flatten in (c,h,w)
+ *     order [-> linear embedding, no activation];
+ *   features = [encoder(view 0), encoder(view 1), ..., proprioception];
+ *   LSTM layers (Hochreiter & Schmidhuber; gate order i, f, g, o):
+ *     a = W_ih x + W_hh h_in + b;  i, f, o = sigmoid(a_i, a_f, a_o);  g = tanh(a_g);
+ *     c = f c_in + i g;  h = o tanh(c);   (h_in, c_in) given by the caller in a->hin / a->cin;
+ *   hidden layers (+bias, ReLU); linear mean head (no squashing), scalar value head; with aux_hidden > 0 the
+ *   last aux_dim outputs are W_a2 relu(W_a1 h + b_a1) + b_a2. */
+static void step_forward(const orc_net *n, const geom *g, const double *P, const float *obs,
+                         const double *proprio, acts *a) {
   for (int v = 0; v < n->n_views; ++v) {
     int64_t px = (int64_t)g->c[0] * g->h[0] * g->w[0];
     for (int64_t i = 0; i < px; ++i) a->conv[v][0][i] = q((double)obs[v * px + i]);  /* the stored image */
     for (int l = 0; l < n->n_conv; ++l) {
+      double *y = a->conv[v][l + 1];
       conv_fwd(a->conv[v][l], g->c[l], g->h[l], g->w[l], P + g->convW[l], P + g->convB[l],
-               g->c[l + 1], n->conv_k, n->conv_stride, n->conv_pad, a->conv[v][l + 1], g->h[l + 1],
-               g->w[l + 1]);
+               g->c[l + 1], n->conv_k, n->conv_stride, n->conv_pad, y, g->h[l + 1], g->w[l + 1]);
       int64_t m = (int64_t)g->c[l + 1] * g->h[l + 1] * g->w[l + 1];
-      for (int64_t i = 0; i < m; ++i)
-        a->conv[v][l + 1][i] = (a->conv[v][l + 1][i] > 0.0) ? q(a->conv[v][l + 1][i]) : 0.0;
+      if (n->layer_norm) {
+        for (int64_t i = 0; i < m; ++i) y[i] = q(y[i]);  /* the stored convolution output */
+        ln_fwd(y, g->c[l + 1], g->h[l + 1] * g->w[l + 1], P + g->lnG[l], P + g->lnB[l], a->xhat[v][l + 1],
+               &a->rstd[v][l + 1], y);
+      }
+      for (int64_t i = 0; i < m; ++i) y[i] = (y[i] > 0.0) ? q(y[i]) : 0.0;
     }
-    memcpy(a->feat + (size_t)v * g->flat, a->conv[v][n->n_conv], sizeof(double) * (size_t)g->flat);
+    if (n->embed_dim > 0) {
+      double *e = a->feat + (size_t)v * g->enc;
+      lin_fwd(a->conv[v][n->n_conv], g->flat, P + g->embW, P + g->embB, g->enc, e);
+      for (int i = 0; i < g->enc; ++i) e[i] = q(e[i]);
+    } else {
+      memcpy(a->feat + (size_t)v * g->flat, a->conv[v][n->n_conv], sizeof(double) * (size_t)g->flat);
+    }
   }
-  for (int i = 0; i < n->proprio_dim; ++i) a->feat[n->n_views * g->flat + i] = q(proprio[i]);
+  for (int i = 0; i < n->proprio_dim; ++i) a->feat[n->n_views * g->enc + i] = q(proprio[i]);
   const double *x = a->feat;
+  const int H = g->H;
+  for (int l = 0; l < g->nl; ++l) {
+    double *ga = a->gate[l];
+    lin_fwd(x, g->lstm_in[l], P + g->lstmWih[l], P + g->lstmB[l], 4 * H, ga);
+    for (int r = 0; r < 4 * H; ++r) {
+      double acc = 0;
+      for (int k = 0; k < H; ++k) acc += P[g->lstmWhh[l] + (int64_t)r * H + k] * a->hin[l][k];
+      ga[r] += acc;
+    }
+    for (int k = 0; k < H; ++k) {
+      double ig = sigmoid(ga[k]), fg = sigmoid(ga[H + k]), gg = tanh(ga[2 * H + k]), og = sigmoid(ga[3 * H + k]);
+      ga[k] = ig; ga[H + k] = fg; ga[2 * H + k] = gg; ga[3 * H + k] = og;
+      a->cell[l][k] = fg * a->cin[l][k] + ig * gg;
+      a->tcell[l][k] = tanh(a->cell[l][k]);
+      a->hid[l][k] = q(og * a->tcell[l][k]);
+    }
+    x = a->hid[l];
+  }
   for (int l = 0; l < n->n_fc; ++l) {
     lin_fwd(x, g->fc_in[l], P + g->fcW[l], P + g->fcB[l], g->fc_out[l], a->fc[l]);
     for (int i = 0; i < g->fc_out[l]; ++i) a->fc[l][i] = (a->fc[l][i] > 0.0) ? q(a->fc[l][i]) : 0.0;
     x = a->fc[l];
   }
-  lin_fwd(x, g->hid, P + g->muW, P + g->muB, n->act_dim, a->mu);
+  lin_fwd(x, g->hid, P + g->muW, P + g->muB, g->A_main, a->mu);
   a->v = 0.0;
   if (n->has_value_head) lin_fwd(x, g->hid, P + g->vW, P + g->vB, 1, &a->v);
+  if (n->aux_hidden > 0) {
+    lin_fwd(x, g->hid, P + g->a1W, P + g->a1B, n->aux_hidden, a->aux);
+    for (int i = 0; i < n->aux_hidden; ++i) a->aux[i] = (a->aux[i] > 0.0) ? q(a->aux[i]) : 0.0;
+    lin_fwd(a->aux, n->aux_hidden, P + g->a2W, P + g->a2B, n->aux_dim, a->mu + g->A_main);
+  }
 }
 
-/* Backward of one sample from dmu[A], dv; accumulates into G (param layout).
- * ReLU passes gradient where the stored activation is > 0. */
-static void sample_backward(const orc_net *n, const geom *g, const double *P, acts *a,
-                            const double *dmu, double dv, double *G) {
-  const double *x = n->n_fc ? a->fc[n->n_fc - 1] : a->feat;
-  double *dx = n->n_fc ? a->dfc[n->n_fc - 1] : a->dfeat;
+/* Backward of one time step from dmu[A], dv and (recurrent nets) the gradients w->dh_next / w->dc_next that
+ * step t+1 sent into this step's (h, c); accumulates into G (parameter layout) and leaves in w->dh_next /
+ * w->dc_next the gradients w.r.t. the state that ENTERED this step.  ReLU passes gradient where the stored
+ * activation is > 0. */
+static void step_backward(const orc_net *n, const geom *g, const double *P, acts *a, grads_ws *w,
+                          const double *dmu, double dv, double *G) {
+  const double *x = n->n_fc ? a->fc[n->n_fc - 1] : (g->nl ? a->hid[g->nl - 1] : a->feat);
+  double *dx = n->n_fc ? w->dfc[n->n_fc - 1] : w->dtrunk;
   memset(dx, 0, sizeof(double) * (size_t)g->hid);
-  lin_bwd(x, g->hid, P + g->muW, n->act_dim, dmu, G + g->muW, G + g->muB, dx);
+  lin_bwd(x, g->hid, P + g->muW, g->A_main, dmu, G + g->muW, G + g->muB, dx);
   if (n->has_value_head) lin_bwd(x, g->hid, P + g->vW, 1, &dv, G + g->vW, G + g->vB, dx);
+  if (n->aux_hidden > 0) {
+    memset(w->daux, 0, sizeof(double) * (size_t)n->aux_hidden);
+    lin_bwd(a->aux, n->aux_hidden, P + g->a2W, n->aux_dim, dmu + g->A_main, G + g->a2W, G + g->a2B, w->daux);
+    for (int i = 0; i < n->aux_hidden; ++i) w->daux[i] = (a->aux[i] > 0.0) ? q(w->daux[i]) : 0.0;
+    lin_bwd(x, g->hid, P + g->a1W, n->aux_hidden, w->daux, G + g->a1W, G + g->a1B, dx);
+  }
   for (int l = n->n_fc - 1; l >= 0; --l) {
-    double *dy = a->dfc[l];
+    double *dy = w->dfc[l];
     for (int i = 0; i < g->fc_out[l]; ++i) dy[i] = (a->fc[l][i] > 0.0) ? q(dy[i]) : 0.0;
-    const double *xin = l ? a->fc[l - 1] : a->feat;
-    double *dxin = l ? a->dfc[l - 1] : a->dfeat;
+    const double *xin = l ? a->fc[l - 1] : (g->nl ? a->hid[g->nl - 1] : a->feat);
+    double *dxin = l ? w->dfc[l - 1] : w->dtrunk;
     memset(dxin, 0, sizeof(double) * (size_t)g->fc_in[l]);
     lin_bwd(xin, g->fc_in[l], P + g->fcW[l], g->fc_out[l], dy, G + g->fcW[l], G + g->fcB[l], dxin);
   }
+  /* w->dtrunk = gradient w.r.t. the trunk's input: the features, or the top LSTM layer's h */
+  double *dfeat = w->dtrunk;
+  if (g->nl > 0) {
+    const int H = g->H;
+    memcpy(w->dx[g->nl], w->dtrunk, sizeof(double) * (size_t)H);
+    for (int l = g->nl - 1; l >= 0; --l) {
+      const double *ga = a->gate[l];
+      const double *xin = l ? a->hid[l - 1] : a->feat;
+      for (int k = 0; k < H; ++k) {
+        double dh = q(w->dx[l + 1][k] + w->dh_next[l][k]);  /* the stored gradient w.r.t. h_t */
+        double ig = ga[k], fg = ga[H + k], gg = ga[2 * H + k], og = ga[3 * H + k], tc = a->tcell[l][k];
+        double dc = dh * og * (1.0 - tc * tc) + w->dc_next[l][k];
+        w->da[k] = dc * gg * ig * (1.0 - ig);
+        w->da[H + k] = dc * a->cin[l][k] * fg * (1.0 - fg);
+        w->da[2 * H + k] = dc * ig * (1.0 - gg * gg);
+        w->da[3 * H + k] = dh * tc * og * (1.0 - og);
+        w->dc_next[l][k] = dc * fg;
+      }
+      for (int r = 0; r < 4 * H; ++r) w->da[r] = q(w->da[r]);
+      memset(w->dx[l], 0, sizeof(double) * (size_t)g->lstm_in[l]);
+      lin_bwd(xin, g->lstm_in[l], P + g->lstmWih[l], 4 * H, w->da, G + g->lstmWih[l], G + g->lstmB[l], w->dx[l]);
+      memset(w->dh_next[l], 0, sizeof(double) * (size_t)H);
+      lin_bwd(a->hin[l], H, P + g->lstmWhh[l], 4 * H, w->da, G + g->lstmWhh[l], NULL, w->dh_next[l]);
+    }
+    dfeat = w->dx[0];
+  }
   for (int v = 0; v < n->n_views; ++v) {
     int L = n->n_conv;
-    memcpy(a->dconv[L], a->dfeat + (size_t)v * g->flat, sizeof(double) * (size_t)g->flat);
+    if (n->embed_dim > 0) {
+      double *de = dfeat + (size_t)v * g->enc;
+      for (int i = 0; i < g->enc; ++i) de[i] = q(de[i]);
+      memset(w->dconv[L], 0, sizeof(double) * (size_t)g->flat);
+      lin_bwd(a->conv[v][L], g->flat, P + g->embW, g->enc, de, G + g->embW, G + g->embB, w->dconv[L]);
+    } else {
+      memcpy(w->dconv[L], dfeat + (size_t)v * g->flat, sizeof(double) * (size_t)g->flat);
+    }
     for (int l = L - 1; l >= 0; --l) {
       int64_t m = (int64_t)g->c[l + 1] * g->h[l + 1] * g->w[l + 1];
-      for (int64_t i = 0; i < m; ++i)
-        a->dconv[l + 1][i] = (a->conv[v][l + 1][i] > 0.0) ? q(a->dconv[l + 1][i]) : 0.0;
-      double *dxl = l ? a->dconv[l] : NULL;
+      double *dy = w->dconv[l + 1];
+      for (int64_t i = 0; i < m; ++i) dy[i] = (a->conv[v][l + 1][i] > 0.0) ? q(dy[i]) : 0.0;
+      if (n->layer_norm) {
+        ln_bwd(dy, a->xhat[v][l + 1], a->rstd[v][l + 1], g->c[l + 1], g->h[l + 1] * g->w[l + 1], P + g->lnG[l],
+               G + g->lnG[l], G + g->lnB[l], w->dpre);
+        for (int64_t i = 0; i < m; ++i) w->dpre[i] = q(w->dpre[i]);  /* the stored gradient w.r.t. the convolution output */
+        dy = w->dpre;
+      }
+      double *dxl = l ? w->dconv[l] : NULL;
       if (dxl) memset(dxl, 0, sizeof(double) * (size_t)g->c[l] * g->h[l] * g->w[l]);
       conv_bwd(a->conv[v][l], g->c[l], g->h[l], g->w[l], P + g->convW[l], g->c[l + 1], n->conv_k,
-               n->conv_stride, n->conv_pad, a->dconv[l + 1], g->h[l + 1], g->w[l + 1],
+               n->conv_stride, n->conv_pad, dy, g->h[l + 1], g->w[l + 1],
                G + g->convW[l], G + g->convB[l], dxl);
     }
   }
 }
 
 /* Copy of the parameters as the layers use them: in bf16-operand mode the weight matrices of
- * every layer are rounded to bf16; everything else is unchanged. */
+ * every layer are rounded to bf16; everything else (biases, log-std, layer-norm gain and shift) is unchanged. */
 static double *operand_params(const orc_net *n, const geom *g, const double *params) {
   double *P = (double *)malloc(sizeof(double) * (size_t)g->total);
   memcpy(P, params, sizeof(double) * (size_t)g->total);
   if (!g_quant) return P;
   for (int l = 0; l < n->n_conv; ++l)
     for (int64_t i = g->convW[l]; i < g->convB[l]; ++i) P[i] = q(P[i]);
+  if (n->embed_dim > 0) for (int64_t i = g->embW; i < g->embB; ++i) P[i] = q(P[i]);
+  for (int l = 0; l < g->nl; ++l)
+    for (int64_t i = g->lstmWih[l]; i < g->lstmB[l]; ++i) P[i] = q(P[i]);
   for (int l = 0; l < n->n_fc; ++l)
     for (int64_t i = g->fcW[l]; i < g->fcB[l]; ++i) P[i] = q(P[i]);
   for (int64_t i = g->muW; i < g->muB; ++i) P[i] = q(P[i]);
   if (n->has_value_head)
     for (int64_t i = g->vW; i < g->vB; ++i) P[i] = q(P[i]);
+  if (n->aux_hidden > 0) {
+    for (int64_t i = g->a1W; i < g->a1B; ++i) P[i] = q(P[i]);
+    for (int64_t i = g->a2W; i < g->a2B; ++i) P[i] = q(P[i]);
+  }
   return P;
 }
 
-/* Network outputs for B samples: mu [B][A], v [B] (v untouched without a value head). */
-void orc_forward(const orc_net *n, const double *params_in, int64_t B, const float *obs,
-                 const double *proprio, double *mu, double *v) {
+/* The state that enters step t of environment b: the given initial state at t = 0 (zero when none is given),
+ * else the state step t-1 left, or zero when that step ended the episode (its done flag is set: Algorithm 1
+ * returns obs, rew, dones from one Env.Step, so done_{t-1} says that the observation of step t starts a new
+ * episode). */
+static void enter_state(const geom *g, int64_t Benv, int64_t b, int t, const uint8_t *done, const double *h0,
+                        const double *c0, const acts *prev, acts *cur) {
+  for (int l = 0; l < g->nl; ++l)
+    for (int k = 0; k < g->H; ++k) {
+      double h = 0, c = 0;
+      if (t == 0) {
+        if (h0) h = h0[((int64_t)l * Benv + b) * g->H + k];
+        if (c0) c = c0[((int64_t)l * Benv + b) * g->H + k];
+      } else if (!(done && done[(int64_t)(t - 1) * Benv + b])) { h = prev->hid[l][k]; c = prev->cell[l][k]; }
+      cur->hin[l][k] = h; cur->cin[l][k] = c;
+    }
+}
+
+/* Network outputs for Benv environments x L steps, arrays time-major ([L][Benv]...): mu [L][Benv][A], v [L][Benv]
+ * (v untouched without a value head).  Feed-forward nets (lstm_layers = 0) treat every (t, b) independently;
+ * recurrent nets carry (h, c) along t from (h0, c0) [layers][Benv][H] (NULL: zeros) with resets at done flags
+ * (done [L][Benv], NULL: none) and return the final state in hT, cT when those are not NULL. */
+void orc_seq_forward(const orc_net *n, const double *params_in, int64_t Benv, int32_t L, const float *obs,
+                     const double *proprio, const uint8_t *done, const double *h0, const double *c0,
+                     double *mu, double *v, double *hT, double *cT) {
   geom g; make_geom(n, &g);
   double *params = operand_params(n, &g, params_in);
   int64_t obs_sz = (int64_t)n->n_views * g.c[0] * g.h[0] * g.w[0];
 #pragma omp parallel
   {
-    acts a; acts_alloc(n, &g, &a);
+    acts a[2]; acts_alloc(n, &g, &a[0]); acts_alloc(n, &g, &a[1]);
 #pragma omp for schedule(static)
-    for (int64_t s = 0; s < B; ++s) {
-      sample_forward(n, &g, params, obs + s * obs_sz, proprio + s * n->proprio_dim, &a);
-      memcpy(mu + s * n->act_dim, a.mu, sizeof(double) * (size_t)n->act_dim);
-      if (n->has_value_head) v[s] = a.v;
+    for (int64_t b = 0; b < Benv; ++b) {
+      for (int t = 0; t < L; ++t) {
+        acts *cur = &a[t & 1], *prev = &a[(t & 1) ^ 1];
+        int64_t s = (int64_t)t * Benv + b;
+        enter_state(&g, Benv, b, t, done, h0, c0, prev, cur);
+        step_forward(n, &g, params, obs + s * obs_sz, proprio + s * n->proprio_dim, cur);
+        memcpy(mu + s * n->act_dim, cur->mu, sizeof(double) * (size_t)n->act_dim);
+        if (n->has_value_head) v[s] = cur->v;
+      }
+      const acts *last = &a[(L - 1) & 1];
+      for (int l = 0; l < g.nl; ++l)
+        for (int k = 0; k < g.H; ++k) {
+          if (hT) hT[((int64_t)l * Benv + b) * g.H + k] = last->hid[l][k];
+          if (cT) cT[((int64_t)l * Benv + b) * g.H + k] = last->cell[l][k];
+        }
     }
-    acts_free(n, &a);
+    acts_free(n, &g, &a[0]); acts_free(n, &g, &a[1]);
   }
   free(params);
+}
+
+/* Network outputs for B independent samples: mu [B][A], v [B]. */
+void orc_forward(const orc_net *n, const double *params_in, int64_t B, const float *obs,
+                 const double *proprio, double *mu, double *v) {
+  orc_seq_forward(n, params_in, B, 1, obs, proprio, NULL, NULL, NULL, mu, v, NULL, NULL);
 }
 
 /* ------------------------------------------------------------------ */
@@ -533,20 +793,25 @@ void orc_mse_loss(int64_t B, int32_t A, int32_t aux_dim, double aux_coef, const 
   stats[ST_TOTAL] = stats[ST_PI] + (aux_dim > 0 ? aux_coef * stats[ST_V] : 0.0);
 }
 
-/* forward all samples, evaluate loss on the outputs, backward all samples */
-static void minibatch_grad(const orc_net *n, const double *params_in, int64_t B, const float *obs,
+/* One minibatch of Benv environments x L steps (time-major arrays; L = 1 for feed-forward nets, where an
+ * "environment" is just a sample): forward everything, evaluate the loss on all Benv*L outputs (its means
+ * run over all of them), backward everything.  Recurrent nets: back-propagation through time over the L steps
+ * of each environment, the state gradient cut where a done flag reset the state. */
+static void minibatch_grad(const orc_net *n, const double *params_in, int64_t Benv, int32_t L, const float *obs,
                            const double *proprio, const double *action, const double *logp_old,
-                           const double *v_old, const double *adv, const double *ret,
+                           const double *v_old, const double *adv, const double *ret, const uint8_t *done,
+                           const double *h0, const double *c0,
                            const orc_loss_cfg *cfg, int distill, double *grads, double *stats) {
   geom g; make_geom(n, &g);
   int A = n->act_dim;
+  int64_t B = Benv * L;
   int64_t obs_sz = (int64_t)n->n_views * g.c[0] * g.h[0] * g.w[0];
   double *mu = (double *)malloc(sizeof(double) * (size_t)B * A);
   double *v = (double *)calloc((size_t)B, sizeof(double));
   double *dmu = (double *)malloc(sizeof(double) * (size_t)B * A);
   double *dv = (double *)calloc((size_t)B, sizeof(double));
   double *params = operand_params(n, &g, params_in);
-  orc_forward(n, params_in, B, obs, proprio, mu, v);
+  orc_seq_forward(n, params_in, Benv, L, obs, proprio, done, h0, c0, mu, v, NULL, NULL);
   memset(grads, 0, sizeof(double) * (size_t)g.total);
   if (distill) orc_mse_loss(B, A, cfg ? cfg->aux_dim : 0, cfg ? cfg->aux_coef : 0.0, mu, action, stats, dmu);
   else
@@ -566,14 +831,35 @@ static void minibatch_grad(const orc_net *n, const double *params_in, int64_t B,
 #ifdef _OPENMP
     tid = omp_get_thread_num();
 #endif
-    acts a; acts_alloc(n, &g, &a);
+    acts *a = (acts *)malloc(sizeof(acts) * (size_t)L);
+    for (int t = 0; t < L; ++t) acts_alloc(n, &g, &a[t]);
+    grads_ws w; ws_alloc(n, &g, &w);
     double *G = tg + (size_t)tid * (size_t)g.total;
 #pragma omp for schedule(static)
-    for (int64_t s = 0; s < B; ++s) {
-      sample_forward(n, &g, params, obs + s * obs_sz, proprio + s * n->proprio_dim, &a);
-      sample_backward(n, &g, params, &a, dmu + s * A, dv[s], G);
+    for (int64_t b = 0; b < Benv; ++b) {
+      for (int t = 0; t < L; ++t) {
+        int64_t s = (int64_t)t * Benv + b;
+        enter_state(&g, Benv, b, t, done, h0, c0, t ? &a[t - 1] : NULL, &a[t]);
+        step_forward(n, &g, params, obs + s * obs_sz, proprio + s * n->proprio_dim, &a[t]);
+      }
+      for (int l = 0; l < g.nl; ++l) {
+        memset(w.dh_next[l], 0, sizeof(double) * (size_t)g.H);
+        memset(w.dc_next[l], 0, sizeof(double) * (size_t)g.H);
+      }
+      for (int t = L - 1; t >= 0; --t) {
+        int64_t s = (int64_t)t * Benv + b;
+        step_backward(n, &g, params, &a[t], &w, dmu + s * A, dv[s], G);
+        /* what is left in dh_next / dc_next goes to step t-1, unless step t started a new episode */
+        if (t > 0 && done && done[(int64_t)(t - 1) * Benv + b])
+          for (int l = 0; l < g.nl; ++l) {
+            memset(w.dh_next[l], 0, sizeof(double) * (size_t)g.H);
+            memset(w.dc_next[l], 0, sizeof(double) * (size_t)g.H);
+          }
+      }
     }
-    acts_free(n, &a);
+    for (int t = 0; t < L; ++t) acts_free(n, &g, &a[t]);
+    free(a);
+    ws_free(n, &g, &w);
   }
   for (int t = 0; t < nth; ++t)
     for (int64_t i = 0; i < g.total; ++i) grads[i] += tg[(size_t)t * (size_t)g.total + i];
@@ -583,18 +869,26 @@ static void minibatch_grad(const orc_net *n, const double *params_in, int64_t B,
   free(tg); free(mu); free(v); free(dmu); free(dv); free(params);
 }
 
-/* Loss, stats and parameter gradients of the PPO objective on one minibatch. */
+/* Loss, stats and parameter gradients of the PPO objective on one minibatch of B independent samples. */
 void orc_ppo_loss_grad(const orc_net *n, const double *params, int64_t B, const float *obs,
                        const double *proprio, const double *action, const double *logp_old,
                        const double *v_old, const double *adv, const double *ret,
                        const orc_loss_cfg *cfg, double *grads, double *stats) {
-  minibatch_grad(n, params, B, obs, proprio, action, logp_old, v_old, adv, ret, cfg, 0, grads, stats);
+  minibatch_grad(n, params, B, 1, obs, proprio, action, logp_old, v_old, adv, ret, NULL, NULL, NULL, cfg, 0, grads, stats);
+}
+/* The same on a minibatch of Benv whole sequences of L steps (time-major arrays), for recurrent nets. */
+void orc_seq_ppo_loss_grad(const orc_net *n, const double *params, int64_t Benv, int32_t L, const float *obs,
+                           const double *proprio, const double *action, const double *logp_old,
+                           const double *v_old, const double *adv, const double *ret, const uint8_t *done,
+                           const double *h0, const double *c0, const orc_loss_cfg *cfg, double *grads,
+                           double *stats) {
+  minibatch_grad(n, params, Benv, L, obs, proprio, action, logp_old, v_old, adv, ret, done, h0, c0, cfg, 0, grads, stats);
 }
 void orc_distill_loss_grad(const orc_net *n, const double *params, int64_t B, const float *obs,
                            const double *proprio, const double *teacher, int32_t aux_dim,
                            double aux_coef, double *grads, double *stats) {
   orc_loss_cfg lc; memset(&lc, 0, sizeof lc); lc.aux_dim = aux_dim; lc.aux_coef = aux_coef;
-  minibatch_grad(n, params, B, obs, proprio, teacher, NULL, NULL, NULL, NULL, &lc, 1, grads, stats);
+  minibatch_grad(n, params, B, 1, obs, proprio, teacher, NULL, NULL, NULL, NULL, NULL, NULL, NULL, &lc, 1, grads, stats);
 }
 
 /* Adam (Kingma & Ba 2015, Algorithm 1), epsilon added to the bias-corrected
@@ -636,10 +930,14 @@ void orc_normalize_adv(int64_t S, const double *adv, double *out) {
   for (int64_t i = 0; i < S; ++i) out[i] = (adv[i] - mean) / (sd + 1e-8);
 }
 
-/* One learner update over a buffer of S = N*T samples: for each epoch draw a
- * fresh permutation, split it into `minibatches` contiguous chunks, and for
- * each chunk: forward, loss, backward, one Adam step.  adv/ret/logp_old/v_old
- * stay fixed for the whole update.  *step is the Adam step counter (in/out).
+/* One learner update over a rollout of N environments x T steps (arrays [T][N]..., flat sample s = t*N + n).
+ * Feed-forward nets: for each epoch draw a fresh permutation of the S = N*T samples, split it into
+ * `minibatches` contiguous chunks, and for each chunk: forward, loss, backward, one Adam step.
+ * Recurrent nets (lstm_layers > 0): the unit of a minibatch is a whole environment (the LSTM is unrolled over
+ * the T steps of the horizon, Sec. III-B/III-C), so the permutation is over the N environments, a minibatch is
+ * N/minibatches environments x all T steps, the initial state of each environment is (h0, c0)
+ * [layers][N][H] (NULL: zeros), and done flags reset the state (see enter_state).
+ * adv/ret/logp_old/v_old stay fixed for the whole update.  *step is the Adam step counter (in/out).
  * With ac->max_grad_norm > 0 the gradient is clipped to that global norm before the Adam step
  * (the grad-norm statistic stays the norm before clipping).
  * With ac->desired_kl > 0 (PPO only) the learning rate follows the divergence between the behaviour
@@ -651,35 +949,54 @@ void orc_normalize_adv(int64_t S, const double *adv, double *out) {
  * place of the closed-form Gaussian divergence.  stats[.][ST_LR] is the rate each step used.
  * stats: [epochs*minibatches][ST_N]; grads_last: gradients of the last minibatch. */
 static void update_loop(const orc_net *n, double *params, double *m, double *v, int64_t *step,
-                        int64_t S, const float *obs, const double *proprio, const double *action,
+                        int64_t N, int32_t T, const float *obs, const double *proprio, const double *action,
                         const double *logp_old, const double *v_old, const double *adv,
-                        const double *ret, const orc_loss_cfg *lc, const orc_adam_cfg *ac,
+                        const double *ret, const uint8_t *done, const double *h0, const double *c0,
+                        const orc_loss_cfg *lc, const orc_adam_cfg *ac,
                         int32_t epochs, int32_t minibatches, uint64_t seed, uint64_t update_idx,
                         int distill, double *stats, double *grads_last) {
   geom g; make_geom(n, &g);
   int A = n->act_dim, P = n->proprio_dim;
+  const int recurrent = g.nl > 0;
+  const int64_t S = N * T;
+  const int64_t U = recurrent ? N : S;   /* units the permutation shuffles */
+  const int32_t L = recurrent ? T : 1;   /* steps per unit */
   int64_t obs_sz = (int64_t)n->n_views * g.c[0] * g.h[0] * g.w[0];
-  int64_t B = S / minibatches;
-  int32_t *perm = (int32_t *)malloc(sizeof(int32_t) * (size_t)S);
+  int64_t Bu = U / minibatches, B = Bu * L;
+  int32_t *perm = (int32_t *)malloc(sizeof(int32_t) * (size_t)U);
   float *mobs = (float *)malloc(sizeof(float) * (size_t)B * (size_t)obs_sz);
   double *mpro = (double *)malloc(sizeof(double) * (size_t)B * P);
   double *mact = (double *)malloc(sizeof(double) * (size_t)B * A);
   double *mlp = (double *)calloc((size_t)B, sizeof(double)), *mvo = (double *)calloc((size_t)B, sizeof(double));
   double *mad = (double *)calloc((size_t)B, sizeof(double)), *mre = (double *)calloc((size_t)B, sizeof(double));
+  uint8_t *mdo = (uint8_t *)calloc((size_t)B, 1);
+  double *mh0 = (double *)calloc((size_t)(g.nl * Bu * g.H + 1), sizeof(double));
+  double *mc0 = (double *)calloc((size_t)(g.nl * Bu * g.H + 1), sizeof(double));
   double *grads = (double *)malloc(sizeof(double) * (size_t)g.total);
   orc_adam_cfg cur = *ac;
   for (int e = 0; e < epochs; ++e) {
-    orc_permutation(seed, update_idx, (uint64_t)e, S, perm);
+    orc_permutation(seed, update_idx, (uint64_t)e, U, perm);
     for (int mb = 0; mb < minibatches; ++mb) {
-      for (int64_t b = 0; b < B; ++b) {
-        int64_t s = perm[(int64_t)mb * B + b];
-        memcpy(mobs + b * obs_sz, obs + s * obs_sz, sizeof(float) * (size_t)obs_sz);
-        memcpy(mpro + b * P, proprio + s * P, sizeof(double) * (size_t)P);
-        memcpy(mact + b * A, action + s * A, sizeof(double) * (size_t)A);
-        if (!distill) { mlp[b] = logp_old[s]; mvo[b] = v_old[s]; mad[b] = adv[s]; mre[b] = ret[s]; }
+      for (int64_t b = 0; b < Bu; ++b) {
+        int64_t u = perm[(int64_t)mb * Bu + b];
+        for (int t = 0; t < L; ++t) {
+          int64_t s = recurrent ? (int64_t)t * N + u : u;  /* source sample */
+          int64_t d = (int64_t)t * Bu + b;                  /* slot in the time-major minibatch */
+          memcpy(mobs + d * obs_sz, obs + s * obs_sz, sizeof(float) * (size_t)obs_sz);
+          memcpy(mpro + d * P, proprio + s * P, sizeof(double) * (size_t)P);
+          memcpy(mact + d * A, action + s * A, sizeof(double) * (size_t)A);
+          if (!distill) { mlp[d] = logp_old[s]; mvo[d] = v_old[s]; mad[d] = adv[s]; mre[d] = ret[s]; }
+          if (recurrent) mdo[d] = done ? done[s] : 0;
+        }
+        for (int l = 0; l < g.nl; ++l)
+          for (int k = 0; k < g.H; ++k) {
+            mh0[((int64_t)l * Bu + b) * g.H + k] = h0 ? h0[((int64_t)l * N + u) * g.H + k] : 0.0;
+            mc0[((int64_t)l * Bu + b) * g.H + k] = c0 ? c0[((int64_t)l * N + u) * g.H + k] : 0.0;
+          }
       }
       double *st = stats + ((int64_t)e * minibatches + mb) * ST_N;
-      minibatch_grad(n, params, B, mobs, mpro, mact, mlp, mvo, mad, mre, lc, distill, grads, st);
+      minibatch_grad(n, params, Bu, L, mobs, mpro, mact, mlp, mvo, mad, mre, recurrent ? mdo : NULL,
+                     recurrent ? mh0 : NULL, recurrent ? mc0 : NULL, lc, distill, grads, st);
       *step += 1;
       /* the gradient reported for the last minibatch is the one before clipping */
       if (grads_last && e == epochs - 1 && mb == minibatches - 1)
@@ -694,16 +1011,29 @@ static void update_loop(const orc_net *n, double *params, double *m, double *v, 
       orc_adam_step(g.total, params, m, v, grads, *step, &cur);
     }
   }
-  free(perm); free(mobs); free(mpro); free(mact); free(mlp); free(mvo); free(mad); free(mre); free(grads);
+  free(perm); free(mobs); free(mpro); free(mact); free(mlp); free(mvo); free(mad); free(mre); free(mdo);
+  free(mh0); free(mc0); free(grads);
 }
 
+/* Feed-forward nets: S flat samples (the rollout's [T][N] arrays flattened). */
 void orc_ppo_update(const orc_net *n, double *params, double *m, double *v, int64_t *step, int64_t S,
                     const float *obs, const double *proprio, const double *action,
                     const double *logp_old, const double *v_old, const double *adv,
                     const double *ret, const orc_loss_cfg *lc, const orc_adam_cfg *ac,
                     int32_t epochs, int32_t minibatches, uint64_t seed, uint64_t update_idx,
                     double *stats, double *grads_last) {
-  update_loop(n, params, m, v, step, S, obs, proprio, action, logp_old, v_old, adv, ret, lc, ac,
+  update_loop(n, params, m, v, step, S, 1, obs, proprio, action, logp_old, v_old, adv, ret, NULL, NULL, NULL, lc, ac,
+              epochs, minibatches, seed, update_idx, 0, stats, grads_last);
+}
+/* Any net, rollout given as [T][N] arrays; recurrent nets need this form. */
+void orc_seq_ppo_update(const orc_net *n, double *params, double *m, double *v, int64_t *step, int64_t N, int32_t T,
+                        const float *obs, const double *proprio, const double *action,
+                        const double *logp_old, const double *v_old, const double *adv,
+                        const double *ret, const uint8_t *done, const double *h0, const double *c0,
+                        const orc_loss_cfg *lc, const orc_adam_cfg *ac,
+                        int32_t epochs, int32_t minibatches, uint64_t seed, uint64_t update_idx,
+                        double *stats, double *grads_last) {
+  update_loop(n, params, m, v, step, N, T, obs, proprio, action, logp_old, v_old, adv, ret, done, h0, c0, lc, ac,
               epochs, minibatches, seed, update_idx, 0, stats, grads_last);
 }
 void orc_distill_update(const orc_net *n, double *params, double *m, double *v, int64_t *step,
@@ -712,7 +1042,7 @@ void orc_distill_update(const orc_net *n, double *params, double *m, double *v, 
                         const orc_adam_cfg *ac, int32_t epochs, int32_t minibatches, uint64_t seed,
                         uint64_t update_idx, double *stats, double *grads_last) {
   orc_loss_cfg lc; memset(&lc, 0, sizeof lc); lc.aux_dim = aux_dim; lc.aux_coef = aux_coef;
-  update_loop(n, params, m, v, step, S, obs, proprio, teacher, NULL, NULL, NULL, NULL, &lc, ac,
+  update_loop(n, params, m, v, step, S, 1, obs, proprio, teacher, NULL, NULL, NULL, NULL, NULL, NULL, NULL, &lc, ac,
               epochs, minibatches, seed, update_idx, 1, stats, grads_last);
 }
 

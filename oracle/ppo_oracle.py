@@ -36,7 +36,9 @@ class _Net(C.Structure):
                 ("proprio_dim", C.c_int32), ("act_dim", C.c_int32),
                 ("n_conv", C.c_int32), ("conv_ch", C.c_int32 * MAXL), ("conv_k", C.c_int32),
                 ("conv_stride", C.c_int32), ("conv_pad", C.c_int32),
-                ("n_fc", C.c_int32), ("fc_dim", C.c_int32 * MAXL), ("has_value_head", C.c_int32)]
+                ("n_fc", C.c_int32), ("fc_dim", C.c_int32 * MAXL), ("has_value_head", C.c_int32),
+                ("aux_hidden", C.c_int32), ("aux_dim", C.c_int32),
+                ("layer_norm", C.c_int32), ("embed_dim", C.c_int32), ("lstm_layers", C.c_int32), ("lstm_units", C.c_int32)]
 
 
 class _LossCfg(C.Structure):
@@ -84,6 +86,9 @@ def _net(net: dict) -> _Net:
     for i, c in enumerate(net["fc_dim"]):
         n.fc_dim[i] = c
     n.has_value_head = int(net.get("has_value_head", 1))
+    n.aux_hidden, n.aux_dim = net.get("aux_hidden", 0), net.get("aux_dim", 0) if net.get("aux_hidden", 0) else 0
+    n.layer_norm, n.embed_dim = int(net.get("layer_norm", 0)), net.get("embed_dim", 0)
+    n.lstm_layers, n.lstm_units = net.get("lstm_layers", 0), net.get("lstm_units", 0) if net.get("lstm_layers", 0) else 0
     return n
 
 
@@ -164,9 +169,81 @@ def forward(net, params, obs, proprio):
     return mu, v
 
 
+def _seq_args(net, proprio, done, h0, c0):
+    """Checks the time-major sequence arrays of a recurrent net and returns (L, Benv, done, h0, c0) as C-ready arrays."""
+    L, Benv = proprio.shape[0], proprio.shape[1]
+    nl, H = net.get("lstm_layers", 0), net.get("lstm_units", 0)
+    if done is not None:
+        done = np.ascontiguousarray(done, dtype=np.uint8)
+        assert done.shape == (L, Benv)
+    if h0 is not None:
+        h0 = _d(h0)
+        assert h0.shape == (nl, Benv, H)
+    if c0 is not None:
+        c0 = _d(c0)
+        assert c0.shape == (nl, Benv, H)
+    return L, Benv, done, h0, c0
+
+
+def seq_forward(net, params, obs, proprio, done=None, h0=None, c0=None):
+    """Time-major sequences: obs [L][Benv]..., proprio [L][Benv][P], done [L][Benv], h0/c0 [layers][Benv][H]
+    -> mu [L][Benv][A], v [L][Benv], hT, cT [layers][Benv][H]."""
+    n = _net(net)
+    proprio = _d(proprio)
+    L, Benv, done, h0, c0 = _seq_args(net, proprio, done, h0, c0)
+    obs, params = _obs(net, obs, L * Benv), _d(params)
+    assert params.size == param_count(net)
+    nl, H = net.get("lstm_layers", 0), net.get("lstm_units", 0)
+    mu, v = np.empty((L, Benv, net["act_dim"])), np.zeros((L, Benv))
+    hT, cT = np.zeros((nl, Benv, H)), np.zeros((nl, Benv, H))
+    lib().orc_seq_forward(C.byref(n), _p(params), C.c_int64(Benv), C.c_int32(L), _p(obs, C.c_float), _p(proprio),
+                          _p(done, C.c_uint8), _p(h0), _p(c0), _p(mu), _p(v), _p(hT), _p(cT))
+    return mu, v, hT, cT
+
+
+def seq_ppo_loss_grad(net, params, obs, proprio, action, logp_old, v_old, adv, ret, done=None, h0=None, c0=None,
+                      clip_eps=0.2, vclip_eps=0.0, vf_coef=0.5, ent_coef=0.0):
+    """One minibatch of whole sequences (time-major [L][Benv]... arrays) -> (stats, grads)."""
+    n = _net(net)
+    params, proprio, action = _d(params), _d(proprio), _d(action)
+    logp_old, v_old, adv, ret = _d(logp_old), _d(v_old), _d(adv), _d(ret)
+    L, Benv, done, h0, c0 = _seq_args(net, proprio, done, h0, c0)
+    obs = _obs(net, obs, L * Benv)
+    cfg = _LossCfg(clip_eps, vclip_eps, vf_coef, ent_coef)
+    grads, st = np.zeros(params.size), np.zeros(ST_N)
+    lib().orc_seq_ppo_loss_grad(C.byref(n), _p(params), C.c_int64(Benv), C.c_int32(L), _p(obs, C.c_float), _p(proprio),
+                                _p(action), _p(logp_old), _p(v_old), _p(adv), _p(ret), _p(done, C.c_uint8), _p(h0), _p(c0),
+                                C.byref(cfg), _p(grads), _p(st))
+    return _stats(st), grads
+
+
+def seq_ppo_update(net, params, m, v, step, obs, proprio, action, logp_old, v_old, adv, ret, hp, done=None, h0=None,
+                   c0=None, update_idx=0):
+    """Whole PPO update on a rollout given as [T][N] arrays; for a recurrent net the minibatches are whole
+    environments (h0/c0 [layers][N][H] are the states at the rollout's start, done flags reset the state)."""
+    n = _net(net)
+    params, m, v = _d(params).copy(), _d(m).copy(), _d(v).copy()
+    proprio, action = _d(proprio), _d(action)
+    logp_old, v_old, ret = _d(logp_old), _d(v_old), _d(ret)
+    adv = normalize_adv(adv) if hp.get("norm_adv", 0) else _d(adv)
+    T, N, done, h0, c0 = _seq_args(net, proprio, done, h0, c0)
+    obs = _obs(net, obs, T * N)
+    E, M = hp["epochs"], hp["minibatches"]
+    assert (N if net.get("lstm_layers", 0) else N * T) % M == 0
+    st, gl, stp = np.zeros((E * M, ST_N)), np.zeros(params.size), C.c_int64(step)
+    ac = _AdamCfg(hp.get("lr", 3e-4), hp.get("beta1", 0.9), hp.get("beta2", 0.999), hp.get("adam_eps", 1e-8),
+                  hp.get("max_grad_norm", 0.0), hp.get("desired_kl", 0.0), hp.get("lr_min", 1e-5), hp.get("lr_max", 1e-2))
+    lc = _LossCfg(hp.get("clip_eps", 0.2), hp.get("vclip_eps", 0.0), hp.get("vf_coef", 0.5), hp.get("ent_coef", 0.0))
+    lib().orc_seq_ppo_update(C.byref(n), _p(params), _p(m), _p(v), C.byref(stp), C.c_int64(N), C.c_int32(T), _p(obs, C.c_float),
+                             _p(proprio), _p(action), _p(logp_old), _p(v_old), _p(adv), _p(ret), _p(done, C.c_uint8), _p(h0),
+                             _p(c0), C.byref(lc), C.byref(ac), C.c_int32(E), C.c_int32(M), C.c_uint64(hp.get("seed", 0)),
+                             C.c_uint64(update_idx), _p(st), _p(gl))
+    return dict(params=params, m=m, v=v, step=int(stp.value), stats=[_stats(r) for r in st], grads_last=gl)
+
+
 def act(net, params, obs, proprio, noise):
-    """Policy step -> action [B][A], logp [B], value [B] (actor-critic nets only)."""
-    assert net.get("has_value_head", 1)
+    """Policy step -> action [B][A], logp [B], value [B] (feed-forward actor-critic nets only)."""
+    assert net.get("has_value_head", 1) and not net.get("lstm_layers", 0)
     n = _net(net)
     proprio, noise = _d(proprio), _d(noise)
     B = proprio.shape[0]

@@ -73,15 +73,26 @@ def param_count(net: dict) -> int:
     shp = layer_shapes(net)
     n = 0
     for (ci, _, _), (co, _, _) in zip(shp[:-1], shp[1:]):
-        n += co * ci * net["conv_k"] ** 2 + co
+        n += co * ci * net["conv_k"] ** 2 + co + (2 * co if net.get("layer_norm", 0) else 0)
     c, h, w = shp[-1]
-    fin = net["n_views"] * c * h * w + net["proprio_dim"]
+    enc = c * h * w
+    if net.get("embed_dim", 0):
+        n += net["embed_dim"] * enc + net["embed_dim"]
+        enc = net["embed_dim"]
+    fin = net["n_views"] * enc + net["proprio_dim"]
+    for _ in range(net.get("lstm_layers", 0)):
+        H = net["lstm_units"]
+        n += 4 * H * (fin + H + 1)
+        fin = H
     for f in net["fc_dim"]:
         n += fin * f + f
         fin = f
-    n += net["act_dim"] * fin + net["act_dim"]
+    X, xh = (net.get("aux_dim", 0), net.get("aux_hidden", 0)) if net.get("aux_hidden", 0) else (0, 0)
+    n += (net["act_dim"] - X) * (fin + 1)
     if net["has_value_head"]:
         n += fin + 1 + net["act_dim"]
+    if xh:
+        n += xh * (fin + 1) + X * (xh + 1)
     return n
 
 

@@ -137,21 +137,36 @@ def rollout(cfg: dict, seed: int | None = None, conditioned: bool = False) -> di
 
 
 def param_layout(net: dict):
-    """[(name, shape, fan_in)] in canonical order: conv W/b ..., fc W/b ..., mu W/b, [v w/b, logstd]."""
+    """[(name, shape, fan_in)] in canonical order: per conv layer W, b, [layer-norm gain, shift]; [embedding W, b];
+    per LSTM layer W_ih, W_hh, b (gates i, f, g, o); per hidden layer W, b; mu W, b; [v w, b, logstd];
+    [auxiliary MLP head W1, b1, W2, b2]."""
     shp = layer_shapes(net)
     k = net["conv_k"]
     items = []
     for i, ((ci, _, _), (co, _, _)) in enumerate(zip(shp[:-1], shp[1:])):
         items += [(f"conv{i}.w", (co, ci, k, k), ci * k * k), (f"conv{i}.b", (co,), ci * k * k)]
+        if net.get("layer_norm", 0):
+            items += [(f"ln{i}.g", (co,), 0), (f"ln{i}.b", (co,), 0)]
     c, h, w = shp[-1]
-    fin = net["n_views"] * c * h * w + net["proprio_dim"]
+    enc = c * h * w
+    if net.get("embed_dim", 0):
+        items += [("emb.w", (net["embed_dim"], enc), enc), ("emb.b", (net["embed_dim"],), enc)]
+        enc = net["embed_dim"]
+    fin = net["n_views"] * enc + net["proprio_dim"]
+    H = net.get("lstm_units", 0)
+    for i in range(net.get("lstm_layers", 0)):
+        items += [(f"lstm{i}.wih", (4 * H, fin), H), (f"lstm{i}.whh", (4 * H, H), H), (f"lstm{i}.b", (4 * H,), H)]
+        fin = H
     for i, f in enumerate(net["fc_dim"]):
         items += [(f"fc{i}.w", (f, fin), fin), (f"fc{i}.b", (f,), fin)]
         fin = f
     A = net["act_dim"]
-    items += [("mu.w", (A, fin), fin), ("mu.b", (A,), fin)]
+    X, xh = (net.get("aux_dim", 0), net.get("aux_hidden", 0)) if net.get("aux_hidden", 0) else (0, 0)
+    items += [("mu.w", (A - X, fin), fin), ("mu.b", (A - X,), fin)]
     if net["has_value_head"]:
         items += [("v.w", (fin,), fin), ("v.b", (1,), fin), ("logstd", (A,), 0)]
+    if xh:
+        items += [("aux1.w", (xh, fin), fin), ("aux1.b", (xh,), fin), ("aux2.w", (X, xh), xh), ("aux2.b", (X,), xh)]
     return items
 
 
@@ -172,6 +187,9 @@ def init_params(net: dict, seed: int) -> np.ndarray:
     for name, shape, fan_in in param_layout(net):
         if name == "logstd":
             parts.append(np.zeros(shape, np.float32))
+            continue
+        if name.startswith("ln"):   # gains around 1, small shifts (exactly 1 and 0 would hide a swapped pair)
+            parts.append((rng.uniform(0.5, 1.5, size=shape) if name.endswith(".g") else rng.uniform(-0.1, 0.1, size=shape)).astype(np.float32))
             continue
         bound = 1.0 / math.sqrt(fan_in)
         x = rng.uniform(-bound, bound, size=shape).astype(np.float32)
