@@ -651,3 +651,245 @@ def test_param_counts_of_the_workloads():
     for c, w in zip(configs.CONFIGS, want):
         assert orc.param_count(c["net"]) == w == configs.param_count(c["net"])
         assert sum(int(np.prod(s)) for _, s, _ in synth.param_layout(c["net"])) == w
+
+
+# ----------------------------------------------------------------- the paper's teacher: layer norm, embedding, LSTM
+# (Sec. III-C: 4-layer CNN with layer normalisation and ReLU -> fully connected 32-d embedding -> concatenated with the
+# proprioception -> two LSTM layers -> fully connected layers -> heads), at toy sizes
+TINY_LN = dict(TINY, layer_norm=1)
+TINY_REC = dict(n_views=1, in_c=1, in_h=9, in_w=11, proprio_dim=3, act_dim=2, conv_ch=[3, 4], conv_k=3, conv_stride=2,
+                conv_pad=1, fc_dim=[7, 5], has_value_head=1, layer_norm=1, embed_dim=6, lstm_layers=2, lstm_units=5)
+
+
+def _seq_batch(net, L, B, seed, p_done=0.0):
+    rng = np.random.default_rng(seed)
+    obs = rng.standard_normal((L, B, net["n_views"], net["in_c"], net["in_h"], net["in_w"])).astype(np.float32)
+    nl, H = net["lstm_layers"], net["lstm_units"]
+    return dict(obs=obs, proprio=rng.standard_normal((L, B, net["proprio_dim"])), action=rng.standard_normal((L, B, net["act_dim"])),
+                logp_old=-0.5 * net["act_dim"] * math.log(2 * math.pi) - rng.uniform(0.5, 2.5, (L, B)),
+                v_old=rng.standard_normal((L, B)), adv=rng.standard_normal((L, B)), ret=rng.standard_normal((L, B)),
+                done=(rng.random((L, B)) < p_done).astype(np.uint8), h0=0.5 * rng.standard_normal((nl, B, H)),
+                c0=0.5 * rng.standard_normal((nl, B, H)))
+
+
+def _rec_params(net, seed):
+    """Random parameters with layer-norm gains around 1 (a gain near 0 would hide the normalised values)."""
+    p = _params(net, seed)
+    for name, (a, b, _) in synth.param_slices(net).items():
+        if name.startswith("ln") and name.endswith(".g"):
+            p[a:b] = 1.0 + 0.3 * p[a:b]
+    return p
+
+
+def test_param_layout_of_the_recurrent_teacher():
+    net = TINY_REC
+    sl = synth.param_slices(net)
+    assert list(sl)[:6] == ["conv0.w", "conv0.b", "ln0.g", "ln0.b", "conv1.w", "conv1.b"]
+    assert sl["emb.w"][2] == (6, orc.flat_dim(net)) and sl["lstm0.wih"][2] == (20, 6 + 3) and sl["lstm1.wih"][2] == (20, 5)
+    assert sl["fc0.w"][2] == (7, 5)
+    n = list(sl.values())[-1][1]
+    assert n == orc.param_count(net) == configs.param_count(net)
+    # the paper's sizes: CNN [16, 32, 64, 128], 32-d embedding, two LSTM layers of 1024 units, MLP [512, 512, 256]
+    paper = dict(n_views=1, in_c=1, in_h=120, in_w=160, proprio_dim=64, act_dim=23, conv_ch=[16, 32, 64, 128], conv_k=3, conv_stride=2,
+                 conv_pad=1, fc_dim=[512, 512, 256], has_value_head=1, layer_norm=1, embed_dim=32, lstm_layers=2, lstm_units=1024)
+    lstm = 4 * 1024 * (32 + 64 + 1024 + 1) + 4 * 1024 * (1024 + 1024 + 1)
+    assert orc.param_count(paper) == configs.param_count(paper)
+    assert orc.param_count(paper) - orc.param_count(dict(paper, lstm_layers=0)) == lstm + 512 * (1024 - 96)  # and fc0 reads 1024 instead of 96 inputs
+
+
+def test_layer_norm_forward_and_gradients_match_library_group_norm():
+    net, B = TINY_LN, 10
+    b, params = _batch(net, B, 30), _rec_params(net, 31)
+    st, g = orc.ppo_loss_grad(net, params, b["obs"], b["proprio"], b["action"], b["logp_old"], b["v_old"], b["adv"], b["ret"],
+                              clip_eps=0.2, vclip_eps=0.3, vf_coef=0.5, ent_coef=0.01)
+    p, sl = torch_ref.unpack(net, params)
+    mu, v, ls = torch_ref.forward(net, p, sl, b["obs"], b["proprio"])
+    omu, ov = orc.forward(net, params, b["obs"], b["proprio"])
+    np.testing.assert_allclose(omu, mu.detach().numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(ov, v.detach().numpy(), rtol=1e-10, atol=1e-12)
+    loss, _ = torch_ref.ppo_loss(mu, v, ls, b["action"], b["logp_old"], b["v_old"], b["adv"], b["ret"], 0.2, 0.3, 0.5, 0.01)
+    loss.backward()
+    np.testing.assert_allclose(g, p.grad.numpy(), rtol=1e-8, atol=1e-11)
+    a0, a1, _ = sl["ln0.g"]
+    assert np.abs(g[a0:a1]).min() > 0   # the gains do receive gradient
+
+
+def test_layer_norm_closed_forms():
+    """A constant image gives every convolution output channel a constant interior; with all-zero weights the layer-norm
+    input is the bias per channel: normalised values are ((b_c - mean b) / sqrt(var b + 1e-5)) and the network output no
+    longer depends on the image at all."""
+    net = dict(TINY_LN, conv_ch=[3])
+    params = _rec_params(net, 32)
+    sl = synth.param_slices(net)
+    a, e, _ = sl["conv0.w"]
+    params[a:e] = 0.0
+    rng = np.random.default_rng(33)
+    pro = rng.standard_normal((1, 3))
+    o1 = rng.standard_normal((1, 1, 1, 9, 11)).astype(np.float32)
+    m1, v1 = orc.forward(net, params, o1, pro)
+    m2, v2 = orc.forward(net, params, 5.0 * o1 + 1.0, pro)
+    np.testing.assert_allclose(m1, m2, rtol=0, atol=1e-14)
+    # the flattened features are relu(g_c * xhat_c + s_c), constant over pixels: re-state the head by hand
+    bias = params[sl["conv0.b"][0]:sl["conv0.b"][1]]
+    g, s = params[sl["ln0.g"][0]:sl["ln0.g"][1]], params[sl["ln0.b"][0]:sl["ln0.b"][1]]
+    xhat = (bias - bias.mean()) / np.sqrt(bias.var() + 1e-5)
+    feat = np.concatenate([np.repeat(np.maximum(g * xhat + s, 0.0), 5 * 6), pro[0]])
+    x = feat
+    for i in range(2):
+        w = params[sl[f"fc{i}.w"][0]:sl[f"fc{i}.w"][1]].reshape(sl[f"fc{i}.w"][2])
+        x = np.maximum(w @ x + params[sl[f"fc{i}.b"][0]:sl[f"fc{i}.b"][1]], 0.0)
+    mu = params[sl["mu.w"][0]:sl["mu.w"][1]].reshape(sl["mu.w"][2]) @ x + params[sl["mu.b"][0]:sl["mu.b"][1]]
+    np.testing.assert_allclose(m1[0], mu, rtol=1e-12, atol=1e-14)
+
+
+def test_recurrent_forward_matches_library_lstm():
+    net, L, B = TINY_REC, 6, 4
+    b, params = _seq_batch(net, L, B, 40), _rec_params(net, 41)
+    mu, v, hT, cT = orc.seq_forward(net, params, b["obs"], b["proprio"], None, b["h0"], b["c0"])
+    p, sl = torch_ref.unpack(net, params)
+    rmu, rv, _, (rh, rc) = torch_ref.seq_forward(net, p, sl, b["obs"], b["proprio"], b["h0"], b["c0"])
+    np.testing.assert_allclose(mu, rmu.detach().numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(v, rv.detach().numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(hT, rh.detach().numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(cT, rc.detach().numpy(), rtol=1e-10, atol=1e-12)
+    # zero initial state when none is given; the outputs do depend on the state
+    mu0, _, _, _ = orc.seq_forward(net, params, b["obs"], b["proprio"])
+    muz, _, _, _ = orc.seq_forward(net, params, b["obs"], b["proprio"], None, np.zeros_like(b["h0"]), np.zeros_like(b["c0"]))
+    np.testing.assert_array_equal(mu0, muz)
+    assert np.abs(mu0 - mu).max() > 1e-3
+    # a sequence of one step is the flat forward with zero state
+    fmu, fv = orc.forward(net, params, b["obs"][0], b["proprio"][0])
+    np.testing.assert_allclose(fmu, mu0[0], rtol=1e-13, atol=1e-15)
+
+
+@pytest.mark.parametrize("vclip,ent", [(0.0, 0.0), (0.3, 0.01)])
+def test_recurrent_gradients_match_autograd_through_library_lstm(vclip, ent):
+    """Back-propagation through time over the whole sequence: the PPO loss over all L*B outputs, differentiated by the
+    library through its own LSTM, convolutions, group norm and linear layers."""
+    net, L, B = TINY_REC, 5, 3
+    b, params = _seq_batch(net, L, B, 42), _rec_params(net, 43)
+    st, g = orc.seq_ppo_loss_grad(net, params, b["obs"], b["proprio"], b["action"], b["logp_old"], b["v_old"], b["adv"], b["ret"],
+                                  None, b["h0"], b["c0"], clip_eps=0.2, vclip_eps=vclip, vf_coef=0.5, ent_coef=ent)
+    p, sl = torch_ref.unpack(net, params)
+    mu, v, ls, _ = torch_ref.seq_forward(net, p, sl, b["obs"], b["proprio"], b["h0"], b["c0"])
+    fl = lambda x: np.asarray(x).reshape((L * B,) + np.asarray(x).shape[2:])
+    loss, tst = torch_ref.ppo_loss(mu.reshape(L * B, -1), v.reshape(L * B), ls, fl(b["action"]), fl(b["logp_old"]), fl(b["v_old"]),
+                                   fl(b["adv"]), fl(b["ret"]), 0.2, vclip, 0.5, ent)
+    loss.backward()
+    np.testing.assert_allclose(g, p.grad.numpy(), rtol=1e-8, atol=1e-11)
+    assert abs(st["total"] - loss.item()) < 1e-12
+    for name in ("lstm0.whh", "lstm1.wih", "emb.w", "ln1.g", "conv0.w"):
+        a0, a1, _ = sl[name]
+        assert np.abs(g[a0:a1]).max() > 0, name
+
+
+def test_done_flags_cut_the_sequence():
+    """A done flag at step k-1 means step k starts a new episode: outputs and gradients equal those of two separate
+    sequences, [0, k) from the given state and [k, L) from the zero state."""
+    net, L, B, k = TINY_REC, 6, 2, 4
+    b, params = _seq_batch(net, L, B, 44), _rec_params(net, 45)
+    done = np.zeros((L, B), np.uint8)
+    done[k - 1, :] = 1
+    done[L - 1, 0] = 1      # a flag at the last step resets nothing inside the sequence
+    mu, v, hT, cT = orc.seq_forward(net, params, b["obs"], b["proprio"], done, b["h0"], b["c0"])
+    mu_a, v_a, _, _ = orc.seq_forward(net, params, b["obs"][:k], b["proprio"][:k], None, b["h0"], b["c0"])
+    mu_b, v_b, hb, cb = orc.seq_forward(net, params, b["obs"][k:], b["proprio"][k:])
+    np.testing.assert_allclose(mu, np.concatenate([mu_a, mu_b]), rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(v, np.concatenate([v_a, v_b]), rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(hT, hb, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(cT, cb, rtol=1e-13, atol=1e-15)
+    # gradients: the loss is a mean over all L*B samples, so the whole equals the sample-weighted sum of the parts
+    kw = dict(clip_eps=0.2, vclip_eps=0.3, vf_coef=0.5, ent_coef=0.0)
+    f = ("action", "logp_old", "v_old", "adv", "ret")
+    _, g = orc.seq_ppo_loss_grad(net, params, b["obs"], b["proprio"], *[b[x] for x in f], done, b["h0"], b["c0"], **kw)
+    _, ga = orc.seq_ppo_loss_grad(net, params, b["obs"][:k], b["proprio"][:k], *[b[x][:k] for x in f], None, b["h0"], b["c0"], **kw)
+    _, gb = orc.seq_ppo_loss_grad(net, params, b["obs"][k:], b["proprio"][k:], *[b[x][k:] for x in f], **kw)
+    np.testing.assert_allclose(g, (k * ga + (L - k) * gb) / L, rtol=1e-9, atol=1e-13)
+    # and without the flag the two halves are coupled
+    _, g0 = orc.seq_ppo_loss_grad(net, params, b["obs"], b["proprio"], *[b[x] for x in f], None, b["h0"], b["c0"], **kw)
+    assert np.abs(g0 - g).max() > 1e-6
+
+
+def test_recurrent_gradients_central_finite_differences():
+    net, L, B = TINY_REC, 4, 3
+    b, params = _seq_batch(net, L, B, 46, p_done=0.25), _rec_params(net, 47)
+    assert b["done"][:-1].any()
+    args = (b["obs"], b["proprio"], b["action"], b["logp_old"], b["v_old"], b["adv"], b["ret"], b["done"], b["h0"], b["c0"])
+    kw = dict(clip_eps=0.2, vclip_eps=0.3, vf_coef=0.5, ent_coef=0.01)
+    _, g = orc.seq_ppo_loss_grad(net, params, *args, **kw)
+    rng = np.random.default_rng(48)
+    sl = synth.param_slices(net)
+    idx = list(rng.choice(params.size, 50, replace=False))
+    for name in ("ln0.g", "ln1.b", "emb.w", "lstm0.wih", "lstm0.whh", "lstm0.b", "lstm1.whh"):   # every new parameter kind
+        idx.append(int(rng.integers(sl[name][0], sl[name][1])))
+    h, bad = 1e-6, 0
+    for i in idx:
+        pp, pm = params.copy(), params.copy()
+        pp[i] += h
+        pm[i] -= h
+        fd = (orc.seq_ppo_loss_grad(net, pp, *args, **kw)[0]["total"] - orc.seq_ppo_loss_grad(net, pm, *args, **kw)[0]["total"]) / (2 * h)
+        if abs(fd - g[i]) > 1e-6 * max(1.0, abs(g[i])):
+            bad += 1
+    assert bad <= 1
+
+
+def test_recurrent_update_loop_shuffles_whole_environments():
+    """The recurrent update: minibatches are whole environments drawn through the permutation of the N environments;
+    re-composed here from the pinned parts (permutation, sequence gradient, Adam) on hand-gathered environments."""
+    net, T, N = TINY_REC, 4, 6
+    b, params = _seq_batch(net, T, N, 50, p_done=0.2), _rec_params(net, 51)
+    hp = dict(epochs=2, minibatches=3, lr=1e-3, seed=9, clip_eps=0.2, vclip_eps=0.3, vf_coef=0.5, ent_coef=0.01)
+    z = np.zeros_like(params)
+    out = orc.seq_ppo_update(net, params, z, z, 0, b["obs"], b["proprio"], b["action"], b["logp_old"], b["v_old"], b["adv"], b["ret"], hp,
+                             done=b["done"], h0=b["h0"], c0=b["c0"], update_idx=4)
+    p, m, v, k = params.astype(np.float64).copy(), z.copy(), z.copy(), 0
+    kw = dict(clip_eps=0.2, vclip_eps=0.3, vf_coef=0.5, ent_coef=0.01)
+    for e in range(2):
+        perm = orc.permutation(9, 4, e, N)
+        for mb in range(3):
+            env = perm[mb * 2:(mb + 1) * 2]
+            st, g = orc.seq_ppo_loss_grad(net, p, b["obs"][:, env], b["proprio"][:, env], b["action"][:, env], b["logp_old"][:, env],
+                                          b["v_old"][:, env], b["adv"][:, env], b["ret"][:, env], b["done"][:, env], b["h0"][:, env],
+                                          b["c0"][:, env], **kw)
+            k += 1
+            orc.adam_step(p, m, v, g, k, lr=1e-3)
+            assert abs(st["total"] - out["stats"][e * 3 + mb]["total"]) < 1e-12
+    np.testing.assert_allclose(out["params"], p, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(out["grads_last"], g, rtol=1e-10, atol=1e-14)
+    assert out["step"] == 6
+    # a feed-forward net through the same entry point is the flat update (samples, not environments, are shuffled)
+    ff = TINY
+    bf, pf = _seq_batch(dict(ff, lstm_layers=0, lstm_units=0), T, N, 52), _params(ff, 53)
+    hp2 = dict(hp, minibatches=4)
+    zf = np.zeros_like(pf)
+    o1 = orc.seq_ppo_update(ff, pf, zf, zf, 0, bf["obs"], bf["proprio"], bf["action"], bf["logp_old"], bf["v_old"], bf["adv"], bf["ret"], hp2)
+    fl = lambda x: x.reshape((T * N,) + x.shape[2:])
+    o2 = orc.ppo_update(ff, pf, zf, zf, 0, fl(bf["obs"]), fl(bf["proprio"]), fl(bf["action"]), fl(bf["logp_old"]), fl(bf["v_old"]),
+                        fl(bf["adv"]), fl(bf["ret"]), hp2)
+    np.testing.assert_array_equal(o1["params"], o2["params"])
+
+
+# ----------------------------------------------------------------- the deployed student's extra MLP head (Sec. IV-C)
+def test_auxiliary_mlp_head_gradients_match_autograd():
+    net, B, X, coef = dict(TINY_STEREO, act_dim=5, aux_hidden=4, aux_dim=2), 9, 2, 0.7
+    b, params = _batch(net, B, 60), _params(net, 61)
+    sl = synth.param_slices(net)
+    assert sl["mu.w"][2] == (3, 6) and sl["aux1.w"][2] == (4, 6) and sl["aux2.w"][2] == (2, 4)
+    assert list(sl)[-4:] == ["aux1.w", "aux1.b", "aux2.w", "aux2.b"] and list(sl.values())[-1][1] == orc.param_count(net) == configs.param_count(net)
+    st, g = orc.distill_loss_grad(net, params, b["obs"], b["proprio"], b["action"], aux_dim=X, aux_coef=coef)
+    p, s2 = torch_ref.unpack(net, params)
+    mu, _, _ = torch_ref.forward(net, p, s2, b["obs"], b["proprio"])
+    omu, _ = orc.forward(net, params, b["obs"], b["proprio"])
+    np.testing.assert_allclose(omu, mu.detach().numpy(), rtol=1e-11, atol=1e-13)
+    e2 = (mu - torch.as_tensor(b["action"])) ** 2
+    la, lx = e2[:, :3].mean(), e2[:, 3:].mean()
+    (la + coef * lx).backward()
+    np.testing.assert_allclose(g, p.grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert abs(st["pi_loss"] - la.item()) < 1e-12 and abs(st["v_loss"] - lx.item()) < 1e-12
+    for name in ("aux1.w", "aux1.b", "aux2.w", "aux2.b"):
+        assert np.abs(g[sl[name][0]:sl[name][1]]).max() > 0
+    # weight 0: the auxiliary head gets no gradient and sends none into the trunk
+    _, g0 = orc.distill_loss_grad(net, params, b["obs"], b["proprio"], b["action"], aux_dim=X, aux_coef=0.0)
+    assert np.abs(g0[sl["aux1.w"][0]:]).max() == 0.0
+    _, gm = orc.distill_loss_grad(dict(net, aux_hidden=0, aux_dim=0, act_dim=3), params[:sl["aux1.w"][0]], b["obs"], b["proprio"], b["action"][:, :3])
+    np.testing.assert_allclose(g0[:sl["aux1.w"][0]], gm, rtol=1e-12, atol=1e-15)

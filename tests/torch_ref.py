@@ -14,6 +14,33 @@ def unpack(net, params):
     return p, {k: (a, b, s) for k, (a, b, s) in param_slices(net).items()}
 
 
+def _encode(net, get, x, B):
+    """Conv stack of one view [B][C][H][W] -> [B][enc]: conv [-> group norm with one group = layer norm over (C,H,W)
+    with per-channel gain and shift] -> ReLU, flatten, [linear embedding]."""
+    for i in range(len(net["conv_ch"])):
+        x = F.conv2d(x, get(f"conv{i}.w"), get(f"conv{i}.b"), stride=net["conv_stride"], padding=net["conv_pad"])
+        if net.get("layer_norm", 0):
+            x = F.group_norm(x, 1, get(f"ln{i}.g"), get(f"ln{i}.b"), eps=1e-5)
+        x = F.relu(x)
+    x = x.reshape(B, -1)
+    if net.get("embed_dim", 0):
+        x = F.linear(x, get("emb.w"), get("emb.b"))
+    return x
+
+
+def _heads(net, get, x):
+    for i in range(len(net["fc_dim"])):
+        x = F.relu(F.linear(x, get(f"fc{i}.w"), get(f"fc{i}.b")))
+    mu = F.linear(x, get("mu.w"), get("mu.b"))
+    if net.get("aux_hidden", 0):
+        a = F.relu(F.linear(x, get("aux1.w"), get("aux1.b")))
+        mu = torch.cat([mu, F.linear(a, get("aux2.w"), get("aux2.b"))], dim=-1)
+    if net["has_value_head"]:
+        v = x @ get("v.w") + get("v.b")
+        return mu, v, get("logstd")
+    return mu, None, None
+
+
 def forward(net, p, sl, obs, proprio):
     def get(name):
         a, b, s = sl[name]
@@ -21,21 +48,32 @@ def forward(net, p, sl, obs, proprio):
     obs = torch.as_tensor(np.asarray(obs, np.float64))
     B = proprio.shape[0]
     obs = obs.reshape(B, net["n_views"], net["in_c"], net["in_h"], net["in_w"])
-    feats = []
-    for v in range(net["n_views"]):
-        x = obs[:, v]
-        for i in range(len(net["conv_ch"])):
-            x = F.relu(F.conv2d(x, get(f"conv{i}.w"), get(f"conv{i}.b"), stride=net["conv_stride"],
-                                padding=net["conv_pad"]))
-        feats.append(x.reshape(B, -1))
+    feats = [_encode(net, get, obs[:, v], B) for v in range(net["n_views"])]
     x = torch.cat(feats + [torch.as_tensor(np.asarray(proprio, np.float64))], dim=1)
-    for i in range(len(net["fc_dim"])):
-        x = F.relu(F.linear(x, get(f"fc{i}.w"), get(f"fc{i}.b")))
-    mu = F.linear(x, get("mu.w"), get("mu.b"))
-    if net["has_value_head"]:
-        v = x @ get("v.w") + get("v.b")
-        return mu, v, get("logstd")
-    return mu, None, None
+    return _heads(net, get, x)
+
+
+def seq_forward(net, p, sl, obs, proprio, h0=None, c0=None):
+    """Recurrent net on time-major sequences WITHOUT done flags, the recurrent core being the library's LSTM module
+    (torch.nn.LSTM, its second bias vector zero): obs [L][B]..., proprio [L][B][P] -> mu [L][B][A], v [L][B], logstd,
+    (hT, cT) [layers][B][H]."""
+    def get(name):
+        a, b, s = sl[name]
+        return p[a:b].reshape(s)
+    L, B = proprio.shape[0], proprio.shape[1]
+    obs = torch.as_tensor(np.asarray(obs, np.float64)).reshape(L * B, net["n_views"], net["in_c"], net["in_h"], net["in_w"])
+    feats = [_encode(net, get, obs[:, v], L * B) for v in range(net["n_views"])]
+    x = torch.cat(feats + [torch.as_tensor(np.asarray(proprio, np.float64)).reshape(L * B, -1)], dim=1).reshape(L, B, -1)
+    nl, H = net["lstm_layers"], net["lstm_units"]
+    lstm = torch.nn.LSTM(x.shape[-1], H, num_layers=nl).double()
+    flat = []
+    for l in range(nl):
+        flat += [get(f"lstm{l}.wih"), get(f"lstm{l}.whh"), get(f"lstm{l}.b"), torch.zeros(4 * H, dtype=torch.float64)]
+    z = torch.zeros(nl, B, H, dtype=torch.float64)
+    state = (z if h0 is None else torch.as_tensor(np.asarray(h0, np.float64)), z if c0 is None else torch.as_tensor(np.asarray(c0, np.float64)))
+    y, (hT, cT) = torch.func.functional_call(lstm, {n_: w for (n_, _), w in zip(lstm.named_parameters(), flat)}, (x, state))
+    mu, v, logstd = _heads(net, get, y.reshape(L * B, H))
+    return mu.reshape(L, B, -1), None if v is None else v.reshape(L, B), logstd, (hT, cT)
 
 
 def ppo_loss(mu, v, logstd, action, logp_old, v_old, adv, ret, clip_eps, vclip_eps, vf_coef, ent_coef):
