@@ -65,6 +65,23 @@ typedef struct {
   int32_t n_fc, fc_dim[PPO_MAX_LAYERS];    /* hidden widths, each a multiple of 8, n_fc >= 1 */
   int32_t has_value_head;            /* 1 actor-critic (PPO), 0 distillation student */
   int32_t max_chunk;                 /* samples per forward/backward pass inside a minibatch; 0 = default */
+  /* The deployed student's extra MLP head (Sec. IV-C: "an extra MLP head that predicts the position of the
+   * object"): with aux_hidden > 0 (a multiple of 8; students only) the last aux_dim (1 .. act_dim-1) output
+   * columns are  W_a2 relu(W_a1 h + b_a1) + b_a2  on the last hidden layer h, and the linear head has
+   * act_dim - aux_dim rows.  The targets stay in the last aux_dim columns of the action slot; ppo_hparams.aux_dim
+   * must equal this aux_dim and aux_coef weighs their error.  Canonical order: W_a1[aux_hidden][h], b_a1,
+   * W_a2[aux_dim][aux_hidden], b_a2 after everything else.  0: no such head. */
+  int32_t aux_hidden, aux_dim;
+  /* The paper's own teacher (Sec. III-C, Fig. 3): layer normalisation after every convolution (over the C*H*W
+   * values of a sample, eps 1e-5, gain and shift per channel, before the ReLU; canonical: g[Co], s[Co] after each
+   * conv bias), embed_dim > 0: a linear layer flatten -> embed_dim per view (no activation; canonical W[E][flat],
+   * b[E] after the convolutions) whose output is concatenated with the proprioception, and lstm_layers LSTM
+   * layers of lstm_units units (gate order i, f, g, o; canonical per layer W_ih[4H][in], W_hh[4H][H], b[4H])
+   * between that concatenation and the hidden layers.  With lstm_layers > 0 ppo_update trains on minibatches
+   * of whole environments (back-propagation through the T steps of the horizon, the state reset where a done
+   * flag is set, initial state from ppo_buffer_write_state) and num_envs must be divisible by
+   * hp.minibatches.  All zero: the feed-forward network of the benchmark configurations. */
+  int32_t layer_norm, embed_dim, lstm_layers, lstm_units;
 } ppo_net_desc;
 
 typedef struct {

@@ -422,6 +422,25 @@ __global__ void k_gather_proprio(const bf16_t* __restrict__ proprio, const int32
   feat[(int64_t)b * ld + col0 + j] = proprio[s * P + j];
 }
 
+// The auxiliary MLP head's slice of the loss gradient: columns [col0, col0 + X) of the head-gradient rows
+// dhead [B][32] move to columns [0, X) of daux [B][32], the rest of a daux row is zero.
+__global__ void k_aux_cols(int B, int col0, int X, const bf16_t* __restrict__ dhead, bf16_t* __restrict__ daux) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)B * 32) return;
+  const int j = (int)(i & 31);
+  daux[i] = j < X ? dhead[(i - j) + col0 + j] : (bf16_t)0;
+}
+// a[i] = bf16(a[i] + b[i]): two gradient contributions to one stored activation (eight elements per thread)
+__global__ void k_add_bf16(int64_t n8, bf16_t* __restrict__ a, const bf16_t* __restrict__ b) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n8) return;
+  uint4 x = reinterpret_cast<const uint4*>(a)[i];
+  const uint4 y = reinterpret_cast<const uint4*>(b)[i];
+  auto add2 = [](uint32_t u, uint32_t v) { return pack2bf(bf2f((bf16_t)(u & 0xffffu)) + bf2f((bf16_t)(v & 0xffffu)), bf2f((bf16_t)(u >> 16)) + bf2f((bf16_t)(v >> 16))); };
+  x.x = add2(x.x, y.x); x.y = add2(x.y, y.y); x.z = add2(x.z, y.z); x.w = add2(x.w, y.w);
+  reinterpret_cast<uint4*>(a)[i] = x;
+}
+
 // ---------------------------------------------------------------- losses
 #define LOSS_NSTAT 8  // pi, v, kl, clipfrac sums; slots 4..7 unused
 #define HEAD_LD 32    // row stride of the head output / head gradient matrices

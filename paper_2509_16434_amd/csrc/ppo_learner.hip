@@ -77,6 +77,15 @@ struct Ctx {
   // internal parameter layout (fp32 master, bf16 shadow share the offsets)
   int64_t convW[PPO_MAX_LAYERS], convB[PPO_MAX_LAYERS], fcW[PPO_MAX_LAYERS], fcB[PPO_MAX_LAYERS];
   int64_t headW = 0, headB = 0, logstd = -1, total = 0;
+  // optional parts of the network
+  int XH = 0, X = 0, A_main = 0;            // auxiliary MLP head: hidden width, outputs; rows of the linear mean head
+  int64_t aux1W = -1, aux1B = -1, aux2W = -1, aux2B = -1;
+  bool ln = false;                          // layer normalisation after every convolution
+  int64_t lnG[PPO_MAX_LAYERS], lnB[PPO_MAX_LAYERS];
+  int E = 0, enc = 0;                       // embedding width (0: none); encoder output width per view
+  int64_t embW = -1, embB = -1;
+  int nl = 0, H = 0, lin[4] = {0, 0, 0, 0};  // LSTM layers, units, input width per layer
+  int64_t lstmW[4], lstmB[4];               // per layer [4H][lin + H] (input and recurrent weights side by side), bias [4H]
   std::vector<int32_t> i2c;  // internal index -> canonical index
   // device: parameters
   float *p = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
@@ -89,6 +98,8 @@ struct Ctx {
   int64_t wd_ver[PPO_MAX_LAYERS] = {};   // weight version that wd[l] holds (0: none); packed on demand
   bf16_t* fcT[PPO_MAX_LAYERS];    // [in][out]
   bf16_t* headT = nullptr;        // [hid][32]
+  bf16_t *aux1T = nullptr, *aux2T = nullptr;  // auxiliary head: [hid][XH], [XH][32]
+  bf16_t *auxact = nullptr, *dauxact = nullptr, *daux = nullptr;  // its hidden activation [CH][XH], that layer's gradient, its output gradient [CH][32]
   // device: rollout buffer (SoA)
   bf16_t *obs = nullptr, *proprio = nullptr;
   float *action = nullptr, *logp = nullptr, *value = nullptr, *reward = nullptr, *adv = nullptr, *ret = nullptr;
@@ -224,6 +235,16 @@ int validate_desc(const ppo_net_desc* d) {
     if (d->fc_dim[i] < 8 || d->fc_dim[i] % 8 || d->fc_dim[i] > 16384) return fail(nullptr, PPO_ESHAPE, "fc_dim[%d] must be a multiple of 8 in 8..16384", i);
   if (d->has_value_head != 0 && d->has_value_head != 1) return fail(nullptr, PPO_EINVAL, "has_value_head must be 0 or 1");
   if (d->max_chunk < 0) return fail(nullptr, PPO_EINVAL, "max_chunk must be >= 0");
+  if (d->aux_hidden < 0 || d->aux_hidden % 8 || d->aux_hidden > 4096) return fail(nullptr, PPO_ESHAPE, "aux_hidden must be a multiple of 8 in 0..4096");
+  if (d->aux_hidden > 0 && d->has_value_head) return fail(nullptr, PPO_ESHAPE, "the auxiliary MLP head belongs to a distillation student (has_value_head = 0)");
+  if (d->aux_hidden > 0 && (d->aux_dim < 1 || d->aux_dim >= d->act_dim)) return fail(nullptr, PPO_ESHAPE, "aux_dim must be in 1..act_dim-1 when aux_hidden > 0");
+  if (d->aux_hidden == 0 && d->aux_dim != 0) return fail(nullptr, PPO_ESHAPE, "aux_dim without aux_hidden (for auxiliary columns of the linear head use ppo_hparams.aux_dim)");
+  if (d->layer_norm != 0 && d->layer_norm != 1) return fail(nullptr, PPO_EINVAL, "layer_norm must be 0 or 1");
+  if (d->embed_dim < 0 || d->embed_dim % 8 || d->embed_dim > 4096) return fail(nullptr, PPO_ESHAPE, "embed_dim must be a multiple of 8 in 0..4096");
+  if (d->lstm_layers < 0 || d->lstm_layers > 4) return fail(nullptr, PPO_ESHAPE, "lstm_layers must be 0..4");
+  if (d->lstm_layers > 0 && (d->lstm_units < 8 || d->lstm_units % 8 || d->lstm_units > 4096)) return fail(nullptr, PPO_ESHAPE, "lstm_units must be a multiple of 8 in 8..4096");
+  if (d->lstm_layers == 0 && d->lstm_units != 0) return fail(nullptr, PPO_ESHAPE, "lstm_units without lstm_layers");
+  if (d->lstm_layers > 0 && !d->has_value_head) return fail(nullptr, PPO_ESHAPE, "recurrent layers are built for the actor-critic teacher (has_value_head = 1)");
   return PPO_OK;
 }
 
@@ -238,6 +259,7 @@ int validate_hp(Ctx* c, const ppo_hparams* hp, bool distill) {
   if (hp->lr_carry != 0 && hp->lr_carry != 1) return fail(c, PPO_EINVAL, "lr_carry must be 0 or 1");
   if (distill && (hp->aux_dim < 0 || hp->aux_dim >= c->A)) return fail(c, PPO_EINVAL, "aux_dim must be in [0, act_dim)");
   if (distill && hp->aux_dim > 0 && !(hp->aux_coef >= 0.f)) return fail(c, PPO_EINVAL, "aux_coef must be >= 0");
+  if (distill && c->XH > 0 && hp->aux_dim != c->X) return fail(c, PPO_EINVAL, "this student has an auxiliary MLP head for %d outputs: hparams.aux_dim must be %d", c->X, c->X);
   if (!distill && hp->desired_kl > 0.f && !(isfinite(hp->lr_min) && isfinite(hp->lr_max) && hp->lr_min > 0.f && hp->lr_min <= hp->lr_max))
     return fail(c, PPO_EINVAL, "desired_kl > 0 needs 0 < lr_min <= lr_max");
   if (hp->epochs < 1 || hp->minibatches < 1) return fail(c, PPO_EINVAL, "epochs and minibatches must be >= 1");
@@ -250,7 +272,9 @@ int validate_hp(Ctx* c, const ppo_hparams* hp, bool distill) {
 void build_geometry(Ctx* c) {
   const ppo_net_desc& d = c->d;
   c->N = d.num_envs; c->T = d.horizon; c->S = c->N * c->T; c->V = d.n_views; c->A = d.act_dim; c->P = d.proprio_dim;
-  c->NH = d.act_dim + (d.has_value_head ? 1 : 0);
+  c->XH = d.aux_hidden; c->X = d.aux_hidden > 0 ? d.aux_dim : 0; c->A_main = c->A - c->X;
+  c->ln = d.layer_norm != 0; c->E = d.embed_dim; c->nl = d.lstm_layers; c->H = d.lstm_layers > 0 ? d.lstm_units : 0;
+  c->NH = c->A_main + (d.has_value_head ? 1 : 0);
   c->nconv = d.n_conv; c->nfc = d.n_fc;
   c->cC[0] = d.in_c; c->cH[0] = d.in_h; c->cW[0] = d.in_w;
   for (int l = 0; l < c->nconv; ++l) {
@@ -260,25 +284,45 @@ void build_geometry(Ctx* c) {
   }
   c->img_elems = (int64_t)d.in_c * d.in_h * d.in_w;
   c->flat = c->cC[c->nconv] * c->cH[c->nconv] * c->cW[c->nconv];
-  c->feat_ld = c->V * c->flat + c->P;
+  c->enc = c->E > 0 ? c->E : c->flat;
+  c->feat_ld = c->V * c->enc + c->P;
   int in = c->feat_ld;
+  for (int l = 0; l < c->nl; ++l) { c->lin[l] = in; in = c->H; }
   for (int l = 0; l < c->nfc; ++l) { c->fin[l] = in; c->fout[l] = d.fc_dim[l]; in = d.fc_dim[l]; }
   c->hid = in;
 
-  // canonical offsets
-  std::vector<int64_t> cConvW(c->nconv), cConvB(c->nconv), cFcW(c->nfc), cFcB(c->nfc);
+  // canonical offsets: per conv W, b, [gain, shift]; [embedding W, b]; per LSTM layer W_ih, W_hh, b; per hidden
+  // layer W, b; mean head W, b; [value head w, b; logstd]; [auxiliary head W1, b1, W2, b2]
+  std::vector<int64_t> cConvW(c->nconv), cConvB(c->nconv), cLnG(c->nconv), cLnB(c->nconv), cFcW(c->nfc), cFcB(c->nfc);
+  int64_t cWih[4], cWhh[4], cLb[4], cEmbW = -1, cEmbB = -1;
   int64_t off = 0;
-  for (int l = 0; l < c->nconv; ++l) { cConvW[l] = off; off += (int64_t)c->cC[l + 1] * c->cC[l] * 9; cConvB[l] = off; off += c->cC[l + 1]; }
+  for (int l = 0; l < c->nconv; ++l) {
+    cConvW[l] = off; off += (int64_t)c->cC[l + 1] * c->cC[l] * 9; cConvB[l] = off; off += c->cC[l + 1];
+    if (c->ln) { cLnG[l] = off; off += c->cC[l + 1]; cLnB[l] = off; off += c->cC[l + 1]; }
+  }
+  if (c->E > 0) { cEmbW = off; off += (int64_t)c->E * c->flat; cEmbB = off; off += c->E; }
+  for (int l = 0; l < c->nl; ++l) {
+    cWih[l] = off; off += (int64_t)4 * c->H * c->lin[l]; cWhh[l] = off; off += (int64_t)4 * c->H * c->H; cLb[l] = off; off += 4 * c->H;
+  }
   for (int l = 0; l < c->nfc; ++l) { cFcW[l] = off; off += (int64_t)c->fin[l] * c->fout[l]; cFcB[l] = off; off += c->fout[l]; }
-  int64_t cMuW = off; off += (int64_t)c->A * c->hid;
-  int64_t cMuB = off; off += c->A;
+  int64_t cMuW = off; off += (int64_t)c->A_main * c->hid;
+  int64_t cMuB = off; off += c->A_main;
   int64_t cVW = -1, cVB = -1, cLs = -1;
   if (d.has_value_head) { cVW = off; off += c->hid; cVB = off; off += 1; cLs = off; off += c->A; }
+  int64_t cA1W = -1, cA1B = -1, cA2W = -1, cA2B = -1;
+  if (c->XH > 0) {
+    cA1W = off; off += (int64_t)c->XH * c->hid; cA1B = off; off += c->XH;
+    cA2W = off; off += (int64_t)c->X * c->XH; cA2B = off; off += c->X;
+  }
   c->total = off;
   c->i2c.assign((size_t)off, 0);
+  auto same = [&](int64_t io, int64_t co, int64_t n) { for (int64_t i = 0; i < n; ++i) c->i2c[(size_t)(io + i)] = (int32_t)(co + i); };
 
-  // internal layout: conv W as [Co][(u*3+v)*Ci + ci]; first hidden layer's columns follow the
-  // channel-last flatten (view, pixel, channel); heads stacked as one [NH][hid] matrix.
+  // internal layout: conv W as [Co][(u*3+v)*Ci + ci]; the first layer behind the convolutions reads the
+  // channel-last flatten (view, pixel, channel); LSTM input and recurrent weights side by side per gate row;
+  // heads stacked as one [NH][hid] matrix.  Every matrix starts at a multiple of 8 elements (16-byte operand
+  // loads from the bf16 shadow) and every bias a bf16-output epilogue reads at a multiple of 4: the vectors of
+  // odd length (head biases, log-std, the auxiliary output bias) come last.
   int64_t io = 0;
   for (int l = 0; l < c->nconv; ++l) {
     int Co = c->cC[l + 1], Ci = c->cC[l];
@@ -289,40 +333,58 @@ void build_geometry(Ctx* c) {
           for (int ci = 0; ci < Ci; ++ci)
             c->i2c[(size_t)(io + (int64_t)co * 9 * Ci + (u * 3 + v) * Ci + ci)] = (int32_t)(cConvW[l] + (((int64_t)co * Ci + ci) * 3 + u) * 3 + v);
     io += (int64_t)Co * 9 * Ci;
-    c->convB[l] = io;
-    for (int co = 0; co < Co; ++co) c->i2c[(size_t)(io + co)] = (int32_t)(cConvB[l] + co);
-    io += Co;
+    c->convB[l] = io; same(io, cConvB[l], Co); io += Co;
+    c->lnG[l] = c->lnB[l] = -1;
+    if (c->ln) { c->lnG[l] = io; same(io, cLnG[l], Co); io += Co; c->lnB[l] = io; same(io, cLnB[l], Co); io += Co; }
   }
   const int CL = c->cC[c->nconv], HWL = c->cH[c->nconv] * c->cW[c->nconv];
+  // column j of a matrix that reads the channel-last flatten of one view <-> canonical (c,h,w) column
+  auto flat_col = [&](int r) { const int pix = r / CL, ch = r - pix * CL; return ch * HWL + pix; };
+  if (c->E > 0) {
+    c->embW = io;
+    for (int o = 0; o < c->E; ++o)
+      for (int j = 0; j < c->flat; ++j) c->i2c[(size_t)(io + (int64_t)o * c->flat + j)] = (int32_t)(cEmbW + (int64_t)o * c->flat + flat_col(j));
+    io += (int64_t)c->E * c->flat;
+    c->embB = io; same(io, cEmbB, c->E); io += c->E;
+  }
+  // the first layer behind the concatenation [encoder(view 0), ..., proprioception]
+  auto feat_col = [&](int j) {
+    if (c->E > 0 || j >= c->V * c->flat) return j;
+    const int v = j / c->flat;
+    return v * c->flat + flat_col(j - v * c->flat);
+  };
+  for (int l = 0; l < c->nl; ++l) {
+    const int K = c->lin[l] + c->H;
+    c->lstmW[l] = io;
+    for (int r = 0; r < 4 * c->H; ++r) {
+      for (int j = 0; j < c->lin[l]; ++j)
+        c->i2c[(size_t)(io + (int64_t)r * K + j)] = (int32_t)(cWih[l] + (int64_t)r * c->lin[l] + (l == 0 ? feat_col(j) : j));
+      for (int j = 0; j < c->H; ++j) c->i2c[(size_t)(io + (int64_t)r * K + c->lin[l] + j)] = (int32_t)(cWhh[l] + (int64_t)r * c->H + j);
+    }
+    io += (int64_t)4 * c->H * K;
+    c->lstmB[l] = io; same(io, cLb[l], 4 * c->H); io += 4 * c->H;
+  }
   for (int l = 0; l < c->nfc; ++l) {
     c->fcW[l] = io;
     for (int o = 0; o < c->fout[l]; ++o)
-      for (int j = 0; j < c->fin[l]; ++j) {
-        int cj = j;
-        if (l == 0 && j < c->V * c->flat) {
-          int v = j / c->flat, r = j - v * c->flat, pix = r / CL, ch = r - pix * CL;
-          cj = v * c->flat + ch * HWL + pix;
-        }
-        c->i2c[(size_t)(io + (int64_t)o * c->fin[l] + j)] = (int32_t)(cFcW[l] + (int64_t)o * c->fin[l] + cj);
-      }
+      for (int j = 0; j < c->fin[l]; ++j)
+        c->i2c[(size_t)(io + (int64_t)o * c->fin[l] + j)] = (int32_t)(cFcW[l] + (int64_t)o * c->fin[l] + ((l == 0 && c->nl == 0) ? feat_col(j) : j));
     io += (int64_t)c->fin[l] * c->fout[l];
-    c->fcB[l] = io;
-    for (int o = 0; o < c->fout[l]; ++o) c->i2c[(size_t)(io + o)] = (int32_t)(cFcB[l] + o);
-    io += c->fout[l];
+    c->fcB[l] = io; same(io, cFcB[l], c->fout[l]); io += c->fout[l];
   }
-  c->headW = io;
-  for (int64_t i = 0; i < (int64_t)c->A * c->hid; ++i) c->i2c[(size_t)(io + i)] = (int32_t)(cMuW + i);
-  io += (int64_t)c->A * c->hid;
-  if (d.has_value_head) { for (int i = 0; i < c->hid; ++i) c->i2c[(size_t)(io + i)] = (int32_t)(cVW + i); io += c->hid; }
-  c->headB = io;
-  for (int i = 0; i < c->A; ++i) c->i2c[(size_t)(io + i)] = (int32_t)(cMuB + i);
-  io += c->A;
+  if (c->XH > 0) {
+    c->aux1W = io; same(io, cA1W, (int64_t)c->XH * c->hid); io += (int64_t)c->XH * c->hid;
+    c->aux1B = io; same(io, cA1B, c->XH); io += c->XH;
+    c->aux2W = io; same(io, cA2W, (int64_t)c->X * c->XH); io += (int64_t)c->X * c->XH;
+  }
+  c->headW = io; same(io, cMuW, (int64_t)c->A_main * c->hid); io += (int64_t)c->A_main * c->hid;
+  if (d.has_value_head) { same(io, cVW, c->hid); io += c->hid; }
+  c->headB = io; same(io, cMuB, c->A_main); io += c->A_main;
   if (d.has_value_head) {
     c->i2c[(size_t)io] = (int32_t)cVB; io += 1;
-    c->logstd = io;
-    for (int i = 0; i < c->A; ++i) c->i2c[(size_t)(io + i)] = (int32_t)(cLs + i);
-    io += c->A;
+    c->logstd = io; same(io, cLs, c->A); io += c->A;
   }
+  if (c->XH > 0) { c->aux2B = io; same(io, cA2B, c->X); io += c->X; }
 }
 
 // number of input pixels of parity `par` along an axis of length n
@@ -528,12 +590,16 @@ int repack_weights(Ctx* c) {
     jobs.first[nj] = nblocks; jobs.kind[nj] = kind; jobs.src[nj] = src; jobs.dst[nj] = dst; jobs.a[nj] = a; jobs.b[nj] = b; jobs.ld[nj] = ld;
     nblocks += cdiv(elems, 256); ++nj;
   };
-  if (c->nconv - 1 + c->nfc + 1 > RepackJobs::MAXJ) return fail(c, PPO_ESHAPE, "too many layers for one re-pack launch");
+  if (c->nconv - 1 + c->nfc + 1 + (c->XH > 0 ? 2 : 0) > RepackJobs::MAXJ) return fail(c, PPO_ESHAPE, "too many layers for one re-pack launch");
   for (int l = 1; l < c->nconv; ++l)
     add(1, c->shadow + c->convW[l], c->wtap[l], c->cC[l + 1], c->cC[l], 0, (int64_t)9 * c->cC[l] * c->cC[l + 1]);
   for (int l = 0; l < c->nfc; ++l)
     add(0, c->shadow + c->fcW[l], c->fcT[l], c->fout[l], c->fin[l], c->fout[l], (int64_t)c->fin[l] * c->fout[l]);
   add(0, c->shadow + c->headW, c->headT, c->NH, c->hid, HEAD_LD, (int64_t)c->hid * HEAD_LD);
+  if (c->XH > 0) {
+    add(0, c->shadow + c->aux1W, c->aux1T, c->XH, c->hid, c->XH, (int64_t)c->hid * c->XH);
+    add(0, c->shadow + c->aux2W, c->aux2T, c->X, c->XH, HEAD_LD, (int64_t)c->XH * HEAD_LD);
+  }
   jobs.first[nj] = nblocks; jobs.njobs = nj;
   for (int j = nj + 1; j <= RepackJobs::MAXJ; ++j) jobs.first[j] = nblocks;
   for (int j = nj; j < RepackJobs::MAXJ; ++j) { jobs.kind[j] = 0; jobs.src[j] = nullptr; jobs.dst[j] = nullptr; jobs.a[j] = jobs.b[j] = jobs.ld[j] = 0; }
@@ -769,6 +835,48 @@ int launch_conv0_fwd_tile_t(Ctx* c, Conv0Args a, int nimg) {
   return PPO_OK;
 }
 
+// The student's auxiliary MLP head on the last hidden layer x [n][hid]: hidden layer (bias, ReLU) into auxact, its
+// X outputs into the columns [A_main, A) of the head-output rows, behind the linear head's.
+int aux_head_forward(Ctx* c, const bf16_t* x, int64_t ldx, int n) {
+  if (c->XH <= 0) return PPO_OK;
+  ARows al = plain_arows(x, ldx, n, c->hid);
+  Ep<MapRows, bf16_t, true, true, false> e1;
+  e1.map = plain_map(c->XH, n); e1.out = c->auxact; e1.bias = c->p + c->aux1B; e1.mask = nullptr; e1.N = c->XH;
+  int rc = launch_gemm(c, al, n, c->shadow + c->aux1W, c->hid, c->XH, c->hid, e1, "aux_fwd.0", 2.0 * n * ((double)c->hid + c->XH) + 2.0 * c->hid * c->XH);
+  if (rc) return rc;
+  ARows a2 = plain_arows(c->auxact, c->XH, n, c->XH);
+  Ep<MapRows, float, true, false, false> e2;
+  e2.map = plain_map(HEAD_LD, n); e2.out = c->headout + c->A_main; e2.bias = c->p + c->aux2B; e2.mask = nullptr; e2.N = c->X;
+  return launch_gemm(c, a2, n, c->shadow + c->aux2W, c->XH, c->X, c->XH, e2, "aux_fwd.1", 2.0 * n * c->XH + 4.0 * n * c->X);
+}
+// Its backward from the loss gradient rows dhead [n][32]: weight and bias gradients of both layers, and the
+// gradient it sends into the last hidden layer h, added to what the linear head left in dh [n][hid]
+// (scratch: another [n][hid] buffer).
+int aux_head_backward(Ctx* c, const bf16_t* h, int n, bool acc, bf16_t* dh, bf16_t* scratch) {
+  if (c->XH <= 0) return PPO_OK;
+  hipLaunchKernelGGL(k_aux_cols, dim3(cdiv((int64_t)n * 32, 256)), dim3(256), 0, c->stream, n, c->A_main, c->X, c->dhead, c->daux);
+  LAUNCHCHK(c, "k_aux_cols");
+  ARows dl2 = plain_arows(c->daux, HEAD_LD, n, HEAD_LD);
+  ARows x2 = plain_arows(c->auxact, c->XH, n, c->XH);
+  int rc = launch_wgrad(c, dl2, x2, c->X, c->XH, n, c->g + c->aux2W, c->g + c->aux2B, acc, "aux_wgrad.1", 2.0 * n * (c->XH + HEAD_LD));
+  if (rc) return rc;
+  Ep<MapRows, bf16_t, false, false, true> e2;
+  e2.map = plain_map(c->XH, n); e2.out = c->dauxact; e2.bias = nullptr; e2.mask = c->auxact; e2.N = c->XH;
+  rc = launch_gemm(c, dl2, n, c->aux2T, HEAD_LD, c->XH, HEAD_LD, e2, "aux_dgrad.1", 2.0 * n * (2.0 * c->XH + HEAD_LD));
+  if (rc) return rc;
+  ARows dl1 = plain_arows(c->dauxact, c->XH, n, c->XH);
+  ARows x1 = plain_arows(h, c->hid, n, c->hid);
+  rc = launch_wgrad(c, dl1, x1, c->XH, c->hid, n, c->g + c->aux1W, c->g + c->aux1B, acc, "aux_wgrad.0", 2.0 * n * ((double)c->hid + c->XH));
+  if (rc) return rc;
+  Ep<MapRows, bf16_t, false, false, true> e1;
+  e1.map = plain_map(c->hid, n); e1.out = scratch; e1.bias = nullptr; e1.mask = h; e1.N = c->hid;
+  rc = launch_gemm(c, dl1, n, c->aux1T, c->XH, c->hid, c->XH, e1, "aux_dgrad.0", 2.0 * n * (2.0 * c->hid + c->XH));
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_add_bf16, dim3(cdiv((int64_t)n * c->hid / 8, 256)), dim3(256), 0, c->stream, (int64_t)n * c->hid / 8, dh, scratch);
+  LAUNCHCHK(c, "k_add_bf16");
+  return PPO_OK;
+}
+
 // Forward of `n` samples selected by device indices idx (NULL: samples first .. first + n - 1 of the buffer).
 int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true, int64_t first = 0) {
   const int V = c->V, nimg = n * V;
@@ -836,6 +944,8 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true, int6
     ep.map = plain_map(HEAD_LD, n); ep.out = c->headout; ep.bias = c->p + c->headB; ep.mask = nullptr; ep.N = c->NH;
     int rc = launch_gemm(c, al, n, c->shadow + c->headW, c->hid, c->NH, c->hid, ep, "head_fwd", 2.0 * n * c->hid + 4.0 * n * c->NH);
     if (rc) return rc;
+    rc = aux_head_forward(c, x, ldx, n);
+    if (rc) return rc;
   }
   return PPO_OK;
 }
@@ -854,6 +964,8 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc, bool with_head =
     Ep<MapRows, bf16_t, false, false, true> ep;
     ep.map = plain_map(c->hid, n); ep.out = c->gbuf[cur]; ep.bias = nullptr; ep.mask = hlast; ep.N = c->hid;
     rc = launch_gemm(c, dl, n, c->headT, HEAD_LD, c->hid, HEAD_LD, ep, "head_dgrad", 2.0 * n * (2.0 * c->hid + HEAD_LD));
+    if (rc) return rc;
+    rc = aux_head_backward(c, hlast, n, acc, c->gbuf[cur], c->gbuf[cur ^ 1]);
     if (rc) return rc;
   }
   for (int l = c->nfc - 1; l >= 0; --l) {
@@ -1018,7 +1130,7 @@ int launch_head_loss(Ctx* c, const LossData& L, int n, bool acc, bool distill, f
     default: return 1;
   }
 }
-bool head_loss_covers(const Ctx* c) { return c->NH <= HEAD_LD && c->nfc >= 1 && (c->hid == 32 || c->hid == 64 || c->hid == 128); }
+bool head_loss_covers(const Ctx* c) { return c->XH == 0 && c->NH <= HEAD_LD && c->nfc >= 1 && (c->hid == 32 || c->hid == 64 || c->hid == 128); }
 
 int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool distill) {
   const int B = c->S / hp->minibatches;
@@ -1145,6 +1257,7 @@ int create_impl(Ctx* c) {
   }
   for (int l = 0; l < c->nfc; ++l) DALLOC(c, c->fcT[l], (int64_t)c->fin[l] * c->fout[l]);
   DALLOC(c, c->headT, (int64_t)c->hid * HEAD_LD);
+  if (c->XH > 0) { DALLOC(c, c->aux1T, (int64_t)c->hid * c->XH); DALLOC(c, c->aux2T, (int64_t)c->XH * HEAD_LD); }
   // rollout buffer
   DALLOC(c, c->obs, S * V * c->img_elems);
   DALLOC(c, c->proprio, S * c->P); DALLOC(c, c->action, S * c->A);
@@ -1166,6 +1279,10 @@ int create_impl(Ctx* c) {
   DALLOC(c, c->feat, (int64_t)CH * c->feat_ld);
   for (int l = 0; l < c->nfc; ++l) { DALLOC(c, c->fcact[l], (int64_t)CH * c->fout[l]); if ((int64_t)CH * c->fout[l] > gmax) gmax = (int64_t)CH * c->fout[l]; }
   DALLOC(c, c->headout, (int64_t)CH * HEAD_LD); DALLOC(c, c->dhead, (int64_t)CH * HEAD_LD);
+  if (c->XH > 0) {
+    DALLOC(c, c->auxact, (int64_t)CH * c->XH); DALLOC(c, c->dauxact, (int64_t)CH * c->XH); DALLOC(c, c->daux, (int64_t)CH * HEAD_LD);
+    HIPCHK(c, hipMemsetAsync(c->headout, 0, sizeof(float) * (size_t)CH * HEAD_LD, c->stream));
+  }
   DALLOC(c, c->gbuf[0], gmax); DALLOC(c, c->gbuf[1], gmax);
   // weight-gradient partials: room for every layer at its preferred split count, all layers of a backward
   // pass side by side (their sums are taken in one launch at the end of the pass)
@@ -1202,6 +1319,11 @@ int create_impl(Ctx* c) {
     if (nblk * c->NH * c->hid > need) need = nblk * c->NH * c->hid;
     if (nblk * c->NH > bneed) bneed = nblk * c->NH;
     pe_sum += need; bpe_sum += bneed;
+  }
+  if (c->XH > 0) {
+    int64_t need, bneed;
+    want(c->XH, c->hid, CH, need, bneed); pe_sum += need; bpe_sum += bneed;
+    want(c->X, c->XH, CH, need, bneed); pe_sum += need; bpe_sum += bneed;
   }
   c->partial_cap = pe_sum; c->bias_partial_cap = bpe_sum > 0 ? bpe_sum : 1;
   DALLOC(c, c->partial_base, c->partial_cap); DALLOC(c, c->bias_partial_base, c->bias_partial_cap);

@@ -29,7 +29,9 @@ class NetDesc(C.Structure):
                 ("n_conv", C.c_int32), ("conv_ch", C.c_int32 * MAXL),
                 ("conv_k", C.c_int32), ("conv_stride", C.c_int32), ("conv_pad", C.c_int32),
                 ("n_fc", C.c_int32), ("fc_dim", C.c_int32 * MAXL),
-                ("has_value_head", C.c_int32), ("max_chunk", C.c_int32)]
+                ("has_value_head", C.c_int32), ("max_chunk", C.c_int32),
+                ("aux_hidden", C.c_int32), ("aux_dim", C.c_int32),
+                ("layer_norm", C.c_int32), ("embed_dim", C.c_int32), ("lstm_layers", C.c_int32), ("lstm_units", C.c_int32)]
 
 
 class HParams(C.Structure):
@@ -117,6 +119,11 @@ def make_desc(net: dict, num_envs: int, horizon: int, obs_dtype: str = "bf16", m
         d.fc_dim[i] = c
     d.has_value_head = int(net.get("has_value_head", 1))
     d.max_chunk = max_chunk
+    d.aux_hidden = net.get("aux_hidden", 0)
+    d.aux_dim = net.get("aux_dim", 0) if d.aux_hidden else 0
+    d.layer_norm, d.embed_dim = int(net.get("layer_norm", 0)), net.get("embed_dim", 0)
+    d.lstm_layers = net.get("lstm_layers", 0)
+    d.lstm_units = net.get("lstm_units", 0) if d.lstm_layers else 0
     return d
 
 

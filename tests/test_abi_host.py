@@ -38,10 +38,20 @@ def test_the_four_path_entry_points_are_declared():
     assert set(_declared((DIAG_HEADER,))) == {"ppo_profile", "ppo_profile_report", "ppo_diag_gemm", "ppo_diag_peak"}
 
 
+def text_of_desc():
+    text = open(HEADER).read()
+    return text[text.index("int32_t num_envs, horizon;"):text.index("} ppo_net_desc;")]
+
+
 def test_struct_sizes_match_the_header_layout():
     # ppo_hparams: 15 floats, 5 int32, one uint64; ppo_mb_stats: 7 floats, int32, float
     assert C.sizeof(L.HParams) == 15 * 4 + 5 * 4 + 8 and L.HParams.seed.offset == 80
     assert C.sizeof(L.MbStats) == 36 and L.MbStats.lr.offset == 32
+    # ppo_net_desc: 9 + 1 + 8 + 3 + 1 + 8 + 2 + 6 int32 fields, in the header's order
+    assert C.sizeof(L.NetDesc) == 4 * (9 + 1 + 8 + 3 + 1 + 8 + 2 + 6)
+    dbody = re.sub(r"/\*.*?\*/", "", text_of_desc(), flags=re.S)
+    dnames = [n for n in re.findall(r"(\w+)(?:\[\w+\])?\s*[,;]", dbody)]
+    assert dnames == [f for f, _ in L.NetDesc._fields_]
     text = open(HEADER).read()
     body = text[text.index("float gamma, lambda;"):text.index("} ppo_hparams;")]
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
@@ -78,6 +88,10 @@ def test_static_permutation_validates_before_touching_the_gpu():
     (dict(proprio_dim=3), L.PPO_ESHAPE), (dict(act_dim=40), L.PPO_ESHAPE), (dict(act_dim=0), L.PPO_ESHAPE),
     (dict(fc_dim=[12]), L.PPO_ESHAPE), (dict(fc_dim=[]), L.PPO_ESHAPE), (dict(conv_ch=[12]), L.PPO_ESHAPE),
     (dict(in_h=0), L.PPO_ESHAPE), (dict(has_value_head=2), L.PPO_EINVAL),
+    (dict(aux_hidden=12, aux_dim=2), L.PPO_ESHAPE), (dict(aux_hidden=16, aux_dim=2), L.PPO_ESHAPE),   # the second: an actor-critic
+    (dict(has_value_head=0, aux_hidden=16, aux_dim=12), L.PPO_ESHAPE), (dict(has_value_head=0, aux_hidden=16, aux_dim=0), L.PPO_ESHAPE),
+    (dict(layer_norm=2), L.PPO_EINVAL), (dict(embed_dim=12), L.PPO_ESHAPE), (dict(lstm_layers=5, lstm_units=16), L.PPO_ESHAPE),
+    (dict(lstm_layers=1, lstm_units=12), L.PPO_ESHAPE), (dict(has_value_head=0, lstm_layers=1, lstm_units=16), L.PPO_ESHAPE),
 ])
 def test_create_rejects_bad_geometry_before_touching_the_gpu(change, code):
     net = dict(configs.get_config(0)["net"], **change)

@@ -179,7 +179,7 @@ def _step_through(L, cfg, ro, E, M, distill):
                 st = lrn.update(hp1)[0]
             ost = out["stats"][0]
             assert st["nonfinite"] == 0
-            assert_stats_close(st, ost, keys=("pi_loss", "total_loss", "grad_norm") if distill else None)
+            assert_stats_close(st, ost, keys=("pi_loss", "v_loss", "total_loss", "grad_norm") if distill else None)
             gerr = per_tensor_errors(net, lrn.get_grads(), out["grads_last"])
             assert max(gerr.values()) <= TOL_BF16, (k, gerr)
             # parameters after the step; only a step from zero moments is a pure sign step
@@ -259,3 +259,58 @@ def test_whole_update_conditioned_vs_exact_oracle(L, ci, N, T, epochs):
     assert float(d_gpu @ d_or / (np.linalg.norm(d_gpu) * np.linalg.norm(d_or))) > 0.99
     assert rel_l2(got, out["params"]) <= TOL_BF16
     lrn.close()
+
+
+# ------------------------------------------------------------------ the student's auxiliary MLP head (object position)
+def _aux_student_cfg(N, T):
+    """The stereo student at half resolution with the deployed student's extra MLP head: 23 action outputs from the
+    linear head, a 3-d object position from a 64-unit hidden layer on the last hidden layer; the 26 targets sit in
+    the action slot."""
+    cfg = configs.get_config(3, num_envs=N, horizon=T)
+    cfg["net"].update(in_h=60, in_w=80, act_dim=26, aux_hidden=64, aux_dim=3)
+    cfg["hp"].update(aux_dim=3, aux_coef=0.5)
+    return cfg
+
+
+def test_auxiliary_mlp_head_forward_and_gradients(L):
+    torch = _torch()
+    cfg = _aux_student_cfg(128, 4)
+    net = cfg["net"]
+    ro = synth.rollout(cfg, conditioned=True)
+    params = synth.init_params(net, cfg["seed"])
+    assert params.size == orc.param_count(net)
+    hp = dict(cfg["hp"], minibatches=1, seed=5)
+    fr = flat_rollout(ro)
+    ost, og = orc.distill_loss_grad(net, params, fr["obs"], fr["proprio"], fr["action"], aux_dim=3, aux_coef=0.5)
+    omu, _ = orc.forward(net, params, fr["obs"][:64], fr["proprio"][:64])
+    sl = synth.param_slices(net)
+    for chunk in (0, 200):
+        lrn = _learner(L, cfg, ro, params, chunk)
+        assert lrn.n_params == params.size
+        mu, _ = lrn.forward(count=64)
+        mu = mu.cpu().numpy()
+        assert mu.shape == (64, 26)
+        assert rel_l2(mu[:, :23], omu[:, :23]) <= TOL_BF16 and rel_l2(mu[:, 23:], omu[:, 23:]) <= TOL_BF16
+        st = lrn.distill_update(hp)[0]
+        assert_stats_close(st, ost, keys=("pi_loss", "v_loss", "total_loss", "grad_norm"))
+        errs = per_tensor_errors(net, lrn.get_grads(), og)
+        print("aux head", chunk, {k: round(v, 4) for k, v in errs.items()})
+        assert max(errs.values()) <= TOL_BF16, errs
+        lrn.close()
+    # weight 0: the auxiliary head gets no gradient and sends none into the trunk
+    lrn = _learner(L, cfg, ro, params)
+    lrn.distill_update(dict(hp, aux_coef=0.0))
+    g0 = lrn.get_grads()
+    assert np.abs(g0[sl["aux1.w"][0]:]).max() == 0.0
+    _, og0 = orc.distill_loss_grad(net, params, fr["obs"], fr["proprio"], fr["action"], aux_dim=3, aux_coef=0.0)
+    assert max(per_tensor_errors(net, g0[:sl["aux1.w"][0]], og0[:sl["aux1.w"][0]]).values()) <= TOL_BF16
+    # the head's width is part of the network: the update's aux_dim has to agree with it
+    with pytest.raises(L.LearnerError) as e:
+        lrn.distill_update(dict(hp, aux_dim=2))
+    assert e.value.code == L.PPO_EINVAL
+    lrn.close()
+
+
+def test_auxiliary_mlp_head_update_every_step_from_oracle_state(L):
+    cfg = _aux_student_cfg(256, 16)
+    _step_through(L, cfg, synth.rollout(cfg, conditioned=True), E=1, M=4, distill=True)
