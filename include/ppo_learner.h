@@ -186,6 +186,11 @@ int ppo_act(ppo_ctx* ctx, int32_t t, const void* d_obs, const float* d_proprio, 
  * PPO_ESTATE when step t holds no record. */
 int ppo_buffer_write_outcome(ppo_ctx* ctx, int32_t t, const float* d_reward, const uint8_t* d_done);
 
+/* Recurrent nets (lstm_layers > 0): the LSTM state of every environment at the START of the rollout in the
+ * buffer (the state the acting policy had when it took step 0), DEVICE fp32 arrays [lstm_layers][N][lstm_units];
+ * NULL = zeros.  Kept until the next call; a new context starts from zeros.  PPO_ESTATE for a feed-forward net. */
+int ppo_buffer_write_state(ppo_ctx* ctx, const float* d_h0, const float* d_c0);
+
 /* Read back the step-t images as stored (bf16) into a DEVICE array in the caller's layout
  * [N][n_views][in_c][in_h][in_w] (bf16).  Test hook for the write path. */
 int ppo_buffer_read_obs(ppo_ctx* ctx, int32_t t, void* d_obs_bf16);
@@ -198,7 +203,8 @@ int ppo_gae(ppo_ctx* ctx, const float* d_last_value, float gamma, float lambda);
 int ppo_get_adv_ret(ppo_ctx* ctx, float* d_adv, float* d_ret);
 
 /* The permutation the next update will use for `epoch` (device kernel, result copied to
- * HOST int32[N*T]); minibatch m is entries [m*B, (m+1)*B). */
+ * HOST int32[N*T]); minibatch m is entries [m*B, (m+1)*B).  A recurrent net shuffles whole environments:
+ * the first N entries are then a permutation of 0..N-1 and the rest of h_perm is left untouched. */
 int ppo_permutation(ppo_ctx* ctx, uint64_t seed, uint64_t update_idx, uint64_t epoch, int32_t* h_perm);
 
 /* ppo_permutation for callers that cannot allocate device memory (code under HIP graph capture, tight serving

@@ -248,7 +248,7 @@ __device__ __forceinline__ bf16x8_t pack8(const bf16_t (&x)[8]) {
 // [co][k] first (lane: co = lane%32, k = (lane/32)*8..+7), patches second (lane: pixel = lane%32),
 // so a lane ends up with 4 groups of 4 consecutive channels of ONE pixel; bias + ReLU, pack, stage
 // in wave-private LDS, and leave as 16-byte pieces of the contiguous [pixel][Cout] output.
-template <int CIN, int TPW>
+template <int CIN, int TPW, bool RELU = true>
 __global__ __launch_bounds__(256) void k_conv1_fwd(ImgAddr in, int n_img, int H, int W, int Ho, int Wo, int Cout,
                                                    const bf16_t* __restrict__ Wb, const float* __restrict__ bias,
                                                    bf16_t* __restrict__ out) {
@@ -319,8 +319,9 @@ __global__ __launch_bounds__(256) void k_conv1_fwd(ImgAddr in, int n_img, int H,
         const int cl = jn * 32 + g * 8 + h * 4;
         if (cl < Cout) {
           uint2 o;
-          o.x = pack2bf(fmaxf(acc[g * 4] + bs[jn][g * 4], 0.f), fmaxf(acc[g * 4 + 1] + bs[jn][g * 4 + 1], 0.f));
-          o.y = pack2bf(fmaxf(acc[g * 4 + 2] + bs[jn][g * 4 + 2], 0.f), fmaxf(acc[g * 4 + 3] + bs[jn][g * 4 + 3], 0.f));
+          const float lo = RELU ? 0.f : -3.0e38f;  // without the ReLU (a layer normalisation follows) the sums pass as they are
+          o.x = pack2bf(fmaxf(acc[g * 4] + bs[jn][g * 4], lo), fmaxf(acc[g * 4 + 1] + bs[jn][g * 4 + 1], lo));
+          o.y = pack2bf(fmaxf(acc[g * 4 + 2] + bs[jn][g * 4 + 2], lo), fmaxf(acc[g * 4 + 3] + bs[jn][g * 4 + 3], lo));
           *reinterpret_cast<uint2*>(&stage[wave][l32 * SP + cl]) = o;
         }
       }

@@ -27,6 +27,7 @@
 #include "head_loss.hip.h"
 #include "wgrad_rs.hip.h"
 #include "peaks.hip.h"
+#include "recurrent.hip.h"
 
 static_assert(sizeof(DevStats) == sizeof(ppo_mb_stats), "device and host statistics records must match");
 
@@ -86,6 +87,25 @@ struct Ctx {
   int64_t embW = -1, embB = -1;
   int nl = 0, H = 0, lin[4] = {0, 0, 0, 0};  // LSTM layers, units, input width per layer
   int64_t lstmW[4], lstmB[4];               // per layer [4H][lin + H] (input and recurrent weights side by side), bias [4H]
+  int feat_cols = 0;                        // V*enc + P: the feature columns of a row of the feature matrix
+  // workspaces of the generic encoder (layer norm and / or embedding) and of the recurrent core
+  bf16_t* pre[PPO_MAX_LAYERS] = {};         // conv outputs before the layer normalisation [CH*V][Ho*Wo*Co]
+  float2* lnstat[PPO_MAX_LAYERS] = {};      // (mean, rstd) per image
+  bf16_t* dpre = nullptr;                   // gradient w.r.t. one convolution's output (largest layer)
+  bf16_t* embT = nullptr;                   // [flat][E]
+  bf16_t* lstmWT[4] = {};                   // [lin + H][4H]
+  bf16_t* xh[4] = {};                       // LSTM layer inputs [CH][lin + H]: x_t, then the h entering step t (xh[0] is the feature matrix)
+  bf16_t* dxh[4] = {};                      // their gradients
+  float* gates[4] = {};                     // [CH][4H] gate activations
+  float* c_enter[4] = {};                   // [CH][H] cell state entering each step
+  float* lstm_pre = nullptr;                // [CHe][4H] gate pre-activations of one step
+  bf16_t* da = nullptr;                     // [CH][4H] gate pre-activation gradients of one layer
+  float* dc_carry = nullptr;                // [CHe][H]
+  bf16_t* htop = nullptr;                   // [CH][H] top layer's h: the trunk's input
+  int32_t* seqidx = nullptr;                // [CH] rollout sample of each row of a sequence chunk
+  float *h0 = nullptr, *c0 = nullptr;       // [nl][N][H] state of every environment at the start of the rollout
+  int PU = 0;                               // units the minibatch permutation shuffles: N environments (recurrent) or S samples
+  int CHe = 0;                              // environments per sequence chunk
   std::vector<int32_t> i2c;  // internal index -> canonical index
   // device: parameters
   float *p = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
@@ -263,7 +283,9 @@ int validate_hp(Ctx* c, const ppo_hparams* hp, bool distill) {
   if (!distill && hp->desired_kl > 0.f && !(isfinite(hp->lr_min) && isfinite(hp->lr_max) && hp->lr_min > 0.f && hp->lr_min <= hp->lr_max))
     return fail(c, PPO_EINVAL, "desired_kl > 0 needs 0 < lr_min <= lr_max");
   if (hp->epochs < 1 || hp->minibatches < 1) return fail(c, PPO_EINVAL, "epochs and minibatches must be >= 1");
-  if (c->S % hp->minibatches) return fail(c, PPO_ESHAPE, "num_envs*horizon = %d is not divisible by minibatches = %d", c->S, hp->minibatches);
+  if (c->PU % hp->minibatches)
+    return fail(c, PPO_ESHAPE, "%s = %d is not divisible by minibatches = %d", c->nl > 0 ? "num_envs (a recurrent net's minibatches are whole environments)" : "num_envs*horizon",
+                c->PU, hp->minibatches);
   if ((int64_t)hp->epochs * hp->minibatches > c->max_steps) return fail(c, PPO_ESHAPE, "epochs*minibatches exceeds %d", c->max_steps);
   return PPO_OK;
 }
@@ -285,8 +307,11 @@ void build_geometry(Ctx* c) {
   c->img_elems = (int64_t)d.in_c * d.in_h * d.in_w;
   c->flat = c->cC[c->nconv] * c->cH[c->nconv] * c->cW[c->nconv];
   c->enc = c->E > 0 ? c->E : c->flat;
-  c->feat_ld = c->V * c->enc + c->P;
-  int in = c->feat_ld;
+  c->feat_cols = c->V * c->enc + c->P;
+  // recurrent nets: a feature row is followed by the h that enters the first LSTM layer at that step (the two
+  // halves of that layer's GEMM operand side by side)
+  c->feat_ld = c->feat_cols + (c->nl > 0 ? c->H : 0);
+  int in = c->feat_cols;
   for (int l = 0; l < c->nl; ++l) { c->lin[l] = in; in = c->H; }
   for (int l = 0; l < c->nfc; ++l) { c->fin[l] = in; c->fout[l] = d.fc_dim[l]; in = d.fc_dim[l]; }
   c->hid = in;
@@ -590,7 +615,7 @@ int repack_weights(Ctx* c) {
     jobs.first[nj] = nblocks; jobs.kind[nj] = kind; jobs.src[nj] = src; jobs.dst[nj] = dst; jobs.a[nj] = a; jobs.b[nj] = b; jobs.ld[nj] = ld;
     nblocks += cdiv(elems, 256); ++nj;
   };
-  if (c->nconv - 1 + c->nfc + 1 + (c->XH > 0 ? 2 : 0) > RepackJobs::MAXJ) return fail(c, PPO_ESHAPE, "too many layers for one re-pack launch");
+  if (c->nconv - 1 + c->nfc + 1 + (c->XH > 0 ? 2 : 0) + (c->E > 0 ? 1 : 0) + c->nl > RepackJobs::MAXJ) return fail(c, PPO_ESHAPE, "too many layers for one re-pack launch");
   for (int l = 1; l < c->nconv; ++l)
     add(1, c->shadow + c->convW[l], c->wtap[l], c->cC[l + 1], c->cC[l], 0, (int64_t)9 * c->cC[l] * c->cC[l + 1]);
   for (int l = 0; l < c->nfc; ++l)
@@ -600,6 +625,9 @@ int repack_weights(Ctx* c) {
     add(0, c->shadow + c->aux1W, c->aux1T, c->XH, c->hid, c->XH, (int64_t)c->hid * c->XH);
     add(0, c->shadow + c->aux2W, c->aux2T, c->X, c->XH, HEAD_LD, (int64_t)c->XH * HEAD_LD);
   }
+  if (c->E > 0) add(0, c->shadow + c->embW, c->embT, c->E, c->flat, c->E, (int64_t)c->flat * c->E);
+  for (int l = 0; l < c->nl; ++l)
+    add(0, c->shadow + c->lstmW[l], c->lstmWT[l], 4 * c->H, c->lin[l] + c->H, 4 * c->H, (int64_t)(c->lin[l] + c->H) * 4 * c->H);
   jobs.first[nj] = nblocks; jobs.njobs = nj;
   for (int j = nj + 1; j <= RepackJobs::MAXJ; ++j) jobs.first[j] = nblocks;
   for (int j = nj; j < RepackJobs::MAXJ; ++j) { jobs.kind[j] = 0; jobs.src[j] = nullptr; jobs.dst[j] = nullptr; jobs.a[j] = jobs.b[j] = jobs.ld[j] = 0; }
@@ -877,8 +905,10 @@ int aux_head_backward(Ctx* c, const bf16_t* h, int n, bool acc, bf16_t* dh, bf16
   return PPO_OK;
 }
 
-// Forward of `n` samples selected by device indices idx (NULL: samples first .. first + n - 1 of the buffer).
-int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true, int64_t first = 0) {
+// Encoder of the feed-forward configurations: convolutions with fused bias + ReLU, the last one writing into the
+// feature matrix, whose tail columns receive the proprioception.  `n` samples selected by device indices idx
+// (NULL: samples first .. first + n - 1 of the buffer).
+int encoder_forward_ff(Ctx* c, const int32_t* idx, int n, int64_t first) {
   const int V = c->V, nimg = n * V;
   bool proprio_done = false;
   if (idx) first = 0;
@@ -928,7 +958,11 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true, int6
     hipLaunchKernelGGL(k_gather_proprio, dim3(cdiv((int64_t)n * c->P, 256)), dim3(256), 0, c->stream, proprio, idx, n, c->P, c->feat, (int64_t)c->feat_ld, V * c->flat);
     LAUNCHCHK(c, "k_gather_proprio");
   }
-  const bf16_t* x = c->feat; int64_t ldx = c->feat_ld;
+  return PPO_OK;
+}
+
+// Hidden layers (bias, ReLU) on the trunk's input x [n][fin0] (row stride ldx), then the heads.
+int trunk_forward(Ctx* c, const bf16_t* x, int64_t ldx, int n, bool with_head) {
   for (int l = 0; l < c->nfc; ++l) {
     ARows al = plain_arows(x, ldx, n, c->fin[l]);
     Ep<MapRows, bf16_t, true, true, false> ep;
@@ -950,10 +984,21 @@ int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true, int6
   return PPO_OK;
 }
 
-// Backward of the chunk whose forward activations are in the workspaces and whose head
-// gradient is in dhead.  Gradients land in c->g (overwritten, or added when `acc`).
-int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc, bool with_head = true) {
-  const int V = c->V, nimg = n * V;
+int encoder_forward_generic(Ctx* c, const int32_t* idx, int n, int64_t first);
+
+// Forward of `n` samples of a feed-forward network selected by device indices idx (NULL: samples first ..
+// first + n - 1 of the buffer).
+int forward_chunk(Ctx* c, const int32_t* idx, int n, bool with_head = true, int64_t first = 0) {
+  const int rc = (c->ln || c->E > 0) ? encoder_forward_generic(c, idx, n, first) : encoder_forward_ff(c, idx, n, first);
+  if (rc) return rc;
+  return trunk_forward(c, c->feat, c->feat_ld, n, with_head);
+}
+
+// Backward of heads and hidden layers of a chunk whose forward activations are in the workspaces and whose
+// head gradient is in dhead; xin [n][fin0] (row stride ldin) is the trunk's input.  Gradients land in c->g
+// (overwritten, or added when `acc`); the gradient w.r.t. the trunk's input is left in gbuf[*cur_out] as
+// [n][fin0], masked by xin > 0 when `mask_in` (xin is then a ReLU output).
+int trunk_backward(Ctx* c, const bf16_t* xin, int64_t ldin, bool mask_in, int n, bool acc, bool with_head, int* cur_out) {
   int cur = 0;
   const bf16_t* hlast = c->fcact[c->nfc - 1];
   if (with_head) {  // heads (otherwise gbuf[0] already holds the gradient of the last hidden layer)
@@ -969,20 +1014,34 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc, bool with_head =
     if (rc) return rc;
   }
   for (int l = c->nfc - 1; l >= 0; --l) {
-    const bf16_t* x = l ? c->fcact[l - 1] : c->feat;
+    const bf16_t* x = l ? c->fcact[l - 1] : xin;
+    const int64_t ldx = l ? c->fin[l] : ldin;
     ARows dl = plain_arows(c->gbuf[cur], c->fout[l], n, c->fout[l]);
-    ARows xl = plain_arows(x, c->fin[l], n, c->fin[l]);
+    ARows xl = plain_arows(x, ldx, n, c->fin[l]);
     int rc = launch_wgrad(c, dl, xl, c->fout[l], c->fin[l], n, c->g + c->fcW[l], c->g + c->fcB[l], acc, "fc_wgrad." + std::to_string(l),
                           2.0 * n * ((double)c->fin[l] + c->fout[l]) + 4.0 * (double)c->fin[l] * c->fout[l]);
     if (rc) return rc;
-    Ep<MapRows, bf16_t, false, false, true> ep;
-    ep.map = plain_map(c->fin[l], n); ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = x; ep.N = c->fin[l];
-    rc = launch_gemm(c, dl, n, c->fcT[l], c->fout[l], c->fin[l], c->fout[l], ep, "fc_dgrad." + std::to_string(l),
-                     2.0 * ((double)n * c->fout[l] + 2.0 * n * c->fin[l] + (double)c->fin[l] * c->fout[l]));
+    const double ab = 2.0 * ((double)n * c->fout[l] + 2.0 * n * c->fin[l] + (double)c->fin[l] * c->fout[l]);
+    if (l > 0 || mask_in) {
+      Ep<MapRows, bf16_t, false, false, true> ep;
+      ep.map = plain_map(c->fin[l], n); ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = x; ep.N = c->fin[l];
+      rc = launch_gemm(c, dl, n, c->fcT[l], c->fout[l], c->fin[l], c->fout[l], ep, "fc_dgrad." + std::to_string(l), ab);
+    } else {  // the trunk's input is not a ReLU output (an embedding, an LSTM's h): nothing to mask
+      Ep<MapRows, bf16_t, false, false, false> ep;
+      ep.map = plain_map(c->fin[l], n); ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = nullptr; ep.N = c->fin[l];
+      rc = launch_gemm(c, dl, n, c->fcT[l], c->fout[l], c->fin[l], c->fout[l], ep, "fc_dgrad." + std::to_string(l), ab);
+    }
     if (rc) return rc;
     cur ^= 1;
   }
-  // gbuf[cur] now holds d(feat) [n][feat_ld], already masked by the last conv layer's ReLU
+  *cur_out = cur;
+  return PPO_OK;
+}
+
+// Backward of the feed-forward configurations' convolutions from d(feat) in gbuf[cur] ([n][feat_ld], already masked
+// by the last conv layer's ReLU).
+int encoder_backward_ff(Ctx* c, const int32_t* idx, int n, bool acc, int cur) {
+  const int V = c->V, nimg = n * V;
   for (int l = c->nconv - 1; l >= 1; --l) {
     const int Co = c->cC[l + 1], Ci = c->cC[l], Ho = c->cH[l + 1], Wo = c->cW[l + 1], H = c->cH[l], W = c->cW[l];
     ImgAddr dy = conv_out_addr(c, l, c->gbuf[cur], c->gbuf[cur]);
@@ -1076,12 +1135,272 @@ int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc, bool with_head =
   return flush_reduces(c);
 }
 
+int encoder_backward_generic(Ctx* c, const int32_t* idx, int n, bool acc, int cur);
+int encoder_forward_generic(Ctx* c, const int32_t* idx, int n, int64_t first);
+
+// Backward of a feed-forward chunk whose forward activations are in the workspaces and whose head gradient is
+// in dhead.  Gradients land in c->g (overwritten, or added when `acc`).
+int backward_chunk(Ctx* c, const int32_t* idx, int n, bool acc, bool with_head = true) {
+  int cur = 0;
+  const bool generic = c->ln || c->E > 0;
+  int rc = trunk_backward(c, c->feat, c->feat_ld, c->E == 0, n, acc, with_head, &cur);
+  if (rc) return rc;
+  return generic ? encoder_backward_generic(c, idx, n, acc, cur) : encoder_backward_ff(c, idx, n, acc, cur);
+}
+
+// ---------------------------------------------------------------- encoder with layer normalisation and / or embedding
+// Every convolution through the implicit-GEMM kernels without the fused ReLU; with layer_norm the convolution
+// output is stored (pre), normalised per image and rectified by k_ln_fwd; without it the ReLU stays in the
+// convolution's epilogue.  The last layer's activation goes into the feature matrix, or (embed_dim > 0) into a
+// buffer of its own that the embedding GEMM reads, view by view.
+static ImgAddrW as_w(const ImgAddr& a) { ImgAddrW w; w.base = const_cast<bf16_t*>(a.base); w.stride_b = a.stride_b; w.stride_v = a.stride_v; w.V = a.V; return w; }
+static ImgAddr contiguous_imgs(const bf16_t* base, int64_t e, int V) { ImgAddr a; a.base = base; a.idx = nullptr; a.stride_b = e * V; a.stride_v = e; a.V = V; return a; }
+// where the output activation of conv layer l lives for a chunk
+static ImgAddr act_addr(Ctx* c, int l) {
+  const int64_t e = (int64_t)c->cC[l + 1] * c->cH[l + 1] * c->cW[l + 1];
+  if (l == c->nconv - 1 && c->E == 0) { ImgAddr a; a.base = c->feat; a.idx = nullptr; a.stride_b = c->feat_ld; a.stride_v = c->flat; a.V = c->V; return a; }
+  return contiguous_imgs(c->act[l], e, c->V);
+}
+
+int encoder_forward_generic(Ctx* c, const int32_t* idx, int n, int64_t first) {
+  const int V = c->V, nimg = n * V;
+  if (idx) first = 0;
+  for (int l = 0; l < c->nconv; ++l) {
+    const int Co = c->cC[l + 1], Ho = c->cH[l + 1], Wo = c->cW[l + 1], Ci = c->cC[l];
+    const int64_t e = (int64_t)Co * Ho * Wo, M = (int64_t)nimg * Ho * Wo;
+    const ImgAddr oa = act_addr(c, l);
+    const ImgAddr conv_to = c->ln ? contiguous_imgs(c->pre[l], e, V) : oa;
+    const std::string name = "conv_fwd." + std::to_string(l);
+    if (l == 0) {
+      ImgAddr in; in.base = c->obs + first * c->img_elems * V; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
+      in.prepare();
+      if (conv_to.stride_v != e || conv_to.stride_b != e * V) return fail(c, PPO_ESHAPE, "the first convolution needs a contiguous output (n_conv >= 2 or an embedding)");
+      ProfScope ps(c, name, 2.0 * (double)M * Co * 9 * Ci, 2.0 * ((double)nimg * c->img_elems + (double)M * Co));
+      constexpr int TPW = 4;
+      const int grid = cdiv(M, 32 * 4 * TPW);
+      bf16_t* out = const_cast<bf16_t*>(conv_to.base);
+      const bf16_t* w = c->shadow + c->convW[0];
+      const float* b = c->p + c->convB[0];
+#define LAUNCH_C1(CIN_, RELU_) hipLaunchKernelGGL((k_conv1_fwd<CIN_, TPW, RELU_>), dim3(grid), dim3(256), 0, c->stream, in, nimg, c->cH[0], c->cW[0], Ho, Wo, Co, w, b, out)
+      if (Ci == 1) { if (c->ln) LAUNCH_C1(1, false); else LAUNCH_C1(1, true); }
+      else { if (c->ln) LAUNCH_C1(3, false); else LAUNCH_C1(3, true); }
+#undef LAUNCH_C1
+      LAUNCHCHK(c, "k_conv1_fwd");
+    } else {
+      AConvFwd al;
+      al.in = act_addr(c, l - 1);
+      al.H = c->cH[l]; al.W = c->cW[l]; al.Cin = Ci; al.lc = ilog2(Ci); al.Ho = Ho; al.Wo = Wo; al.M = (int)M; al.K = 9 * Ci;
+      const double ab = 2.0 * ((double)nimg * al.H * al.W * Ci + (double)M * Co + (double)al.K * Co);
+      int rc;
+      if (c->ln) {
+        Ep<MapRows, bf16_t, true, false, false> ep;
+        ep.map.stride_b = conv_to.stride_b; ep.map.stride_v = conv_to.stride_v; ep.map.V = V; ep.map.HW = Ho * Wo; ep.map.C = Co; ep.map.M = (int)M;
+        ep.out = const_cast<bf16_t*>(conv_to.base); ep.bias = c->p + c->convB[l]; ep.mask = nullptr; ep.N = Co;
+        rc = launch_gemm(c, al, (int)M, c->shadow + c->convW[l], al.K, Co, al.K, ep, name, ab);
+      } else {
+        Ep<MapRows, bf16_t, true, true, false> ep;
+        ep.map.stride_b = conv_to.stride_b; ep.map.stride_v = conv_to.stride_v; ep.map.V = V; ep.map.HW = Ho * Wo; ep.map.C = Co; ep.map.M = (int)M;
+        ep.out = const_cast<bf16_t*>(conv_to.base); ep.bias = c->p + c->convB[l]; ep.mask = nullptr; ep.N = Co;
+        rc = launch_gemm(c, al, (int)M, c->shadow + c->convW[l], al.K, Co, al.K, ep, name, ab);
+      }
+      if (rc) return rc;
+    }
+    c->abits_ok[l] = false;
+    if (c->ln) {
+      ProfScope ps(c, "layer_norm_fwd", 8.0 * (double)nimg * e, 4.0 * (double)nimg * e);
+      hipLaunchKernelGGL(k_ln_fwd, dim3(nimg), dim3(LN_THREADS), 0, c->stream, c->pre[l], (int)e, Co, c->p + c->lnG[l], c->p + c->lnB[l], as_w(oa), c->lnstat[l]);
+      LAUNCHCHK(c, "k_ln_fwd");
+    }
+  }
+  if (c->E > 0) {  // embedding of each view's flattened features: a linear layer, no activation
+    for (int v = 0; v < V; ++v) {
+      ARows al = plain_arows(c->act[c->nconv - 1] + (int64_t)v * c->flat, (int64_t)V * c->flat, n, c->flat);
+      Ep<MapRows, bf16_t, true, false, false> ep;
+      ep.map = plain_map(c->feat_ld, n); ep.out = c->feat + (int64_t)v * c->E; ep.bias = c->p + c->embB; ep.mask = nullptr; ep.N = c->E;
+      const int rc = launch_gemm(c, al, n, c->shadow + c->embW, c->flat, c->E, c->flat, ep, "embed_fwd", 2.0 * ((double)n * c->flat + (double)n * c->E + (double)c->flat * c->E));
+      if (rc) return rc;
+    }
+  }
+  hipLaunchKernelGGL(k_gather_proprio, dim3(cdiv((int64_t)n * c->P, 256)), dim3(256), 0, c->stream, c->proprio + first * c->P, idx, n, c->P, c->feat,
+                     (int64_t)c->feat_ld, V * c->enc);
+  LAUNCHCHK(c, "k_gather_proprio");
+  return PPO_OK;
+}
+
+// Its backward from d(features) in `dfeat` (row stride ld_df; with an embedding its columns [v*E, (v+1)*E) are the
+// gradient of view v's embedding, without one the masked gradient of the last convolution's activation).
+int encoder_backward_seq(Ctx* c, const int32_t* idx, int n, bool acc, const bf16_t* dfeat, int64_t ld_df, int cur) {
+  const int V = c->V, nimg = n * V, L = c->nconv;
+  // gradient w.r.t. the last convolution's activation, masked by its ReLU
+  ImgAddr dy;
+  if (c->E > 0) {
+    bf16_t* dst = c->gbuf[cur ^ 1];
+    for (int v = 0; v < V; ++v) {
+      ARows dl = plain_arows(dfeat + (int64_t)v * c->E, ld_df, n, c->E);
+      ARows xl = plain_arows(c->act[L - 1] + (int64_t)v * c->flat, (int64_t)V * c->flat, n, c->flat);
+      int rc = launch_wgrad(c, dl, xl, c->E, c->flat, n, c->g + c->embW, c->g + c->embB, acc || v > 0, "embed_wgrad", 2.0 * n * ((double)c->flat + c->E));
+      if (rc) return rc;
+      Ep<MapRows, bf16_t, false, false, true> ep;
+      ep.map = plain_map((int64_t)V * c->flat, n); ep.out = dst + (int64_t)v * c->flat; ep.bias = nullptr; ep.mask = c->act[L - 1] + (int64_t)v * c->flat; ep.N = c->flat;
+      rc = launch_gemm(c, dl, n, c->embT, c->E, c->flat, c->E, ep, "embed_dgrad", 2.0 * n * (2.0 * c->flat + c->E));
+      if (rc) return rc;
+    }
+    cur ^= 1;
+    dy = contiguous_imgs(c->gbuf[cur], c->flat, V);
+  } else {
+    if (c->nl > 0 && !c->ln) {  // the LSTM's GEMM left this gradient unmasked, and no layer-norm backward will mask it
+      hipLaunchKernelGGL(k_mask_rows, dim3(cdiv((int64_t)n * (V * c->flat / 8), 256)), dim3(256), 0, c->stream, (int64_t)n, V * c->flat, const_cast<bf16_t*>(dfeat), ld_df,
+                         c->feat, (int64_t)c->feat_ld);
+      LAUNCHCHK(c, "k_mask_rows");
+    }
+    dy.base = dfeat; dy.idx = nullptr; dy.stride_b = ld_df; dy.stride_v = c->flat; dy.V = V;
+  }
+  for (int l = L - 1; l >= 0; --l) {
+    const int Co = c->cC[l + 1], Ci = c->cC[l], Ho = c->cH[l + 1], Wo = c->cW[l + 1], H = c->cH[l], W = c->cW[l];
+    const int64_t e = (int64_t)Co * Ho * Wo;
+    ImgAddr dconv = dy;  // gradient w.r.t. the convolution's output
+    if (c->ln) {
+      int grid = nimg < 1024 ? nimg : 1024;
+      { const int erc = ensure_partial(c, (int64_t)grid * 2 * Co, 0); if (erc) return erc; }
+      if ((int64_t)grid * 2 * Co > c->partial_elems) grid = (int)(c->partial_elems / (2 * Co));
+      if (grid < 1) return fail(c, PPO_ENOMEM, "weight-gradient workspace too small for the layer-norm gradients");
+      {
+        ProfScope ps(c, "layer_norm_bwd", 14.0 * (double)nimg * e, 6.0 * (double)nimg * e);
+        dy.prepare();
+        hipLaunchKernelGGL(k_ln_bwd, dim3(grid), dim3(LN_THREADS), 0, c->stream, dy, c->pre[l], c->lnstat[l], nimg, (int)e, Co, c->p + c->lnG[l], c->p + c->lnB[l], c->dpre, c->partial);
+        LAUNCHCHK(c, "k_ln_bwd");
+      }
+      defer_reduce(c, 0, grid, 2 * Co, 0, 0, c->g + c->lnG[l], nullptr, acc, false, 0, nullptr);  // gain and shift gradients are adjacent
+      dconv = contiguous_imgs(c->dpre, e, V);
+    }
+    if (l == 0) {
+      ImgAddr in; in.base = c->obs; in.idx = idx; in.stride_b = c->img_elems * V; in.stride_v = c->img_elems; in.V = V;
+      if (dconv.stride_v != e || dconv.stride_b != e * V) return fail(c, PPO_ESHAPE, "the first convolution's gradient needs a contiguous layout");
+      const int K = 9 * Ci;
+      int64_t M = (int64_t)nimg * Ho * Wo;
+      const int npair = Co * (K + 1);
+      { const int erc = ensure_partial(c, (int64_t)2048 * npair, 0); if (erc) return erc; }
+      int64_t max_blocks = c->partial_elems / npair;
+      if (max_blocks > 2048) max_blocks = 2048;
+      if (max_blocks < 1) return fail(c, PPO_ENOMEM, "weight-gradient workspace too small for the first convolution");
+      int64_t ppb = (M + max_blocks - 1) / max_blocks;
+      ppb = (ppb + 63) / 64 * 64;
+      const int nblk = cdiv(M, ppb);
+      ProfScope ps(c, "conv_wgrad.0", 2.0 * (double)M * Co * (K + 1), 2.0 * ((double)M * Co + (double)nimg * c->img_elems));
+      if (Ci == 1) hipLaunchKernelGGL((k_conv1_wgrad<1>), dim3(nblk), dim3(256), 0, c->stream, in, nimg, H, W, Ho, Wo, Co, dconv.base, (int)ppb, c->partial);
+      else hipLaunchKernelGGL((k_conv1_wgrad<3>), dim3(nblk), dim3(256), 0, c->stream, in, nimg, H, W, Ho, Wo, Co, dconv.base, (int)ppb, c->partial);
+      LAUNCHCHK(c, "k_conv1_wgrad");
+      defer_reduce(c, 2, nblk, npair, Co, K, c->g + c->convW[0], c->g + c->convB[0], acc, false, 0, nullptr);
+      break;
+    }
+    ARows dl; dl.a = dconv; dl.HW = Ho * Wo; dl.C = Co; dl.M = nimg * Ho * Wo; dl.K = Co; dl.plain = false;
+    AConvFwd xl; xl.in = act_addr(c, l - 1);
+    xl.H = H; xl.W = W; xl.Cin = Ci; xl.lc = ilog2(Ci); xl.Ho = Ho; xl.Wo = Wo; xl.M = dl.M; xl.K = 9 * Ci;
+    const double wab = 2.0 * ((double)dl.M * Co + (double)nimg * H * W * Ci) + 4.0 * 9.0 * Ci * Co;
+    int rc = launch_wgrad(c, dl, xl, Co, 9 * Ci, dl.M, c->g + c->convW[l], c->g + c->convB[l], acc, "conv_wgrad." + std::to_string(l), wab);
+    if (rc) return rc;
+    AConvDgrad al; al.dy = dconv; al.Ho = Ho; al.Wo = Wo; al.Cout = Co; al.lco = ilog2(Co); al.H = H; al.W = W; al.dy_imgs = nimg;
+    rc = ensure_packed_dgrad_weights(c, l);
+    if (rc) return rc;
+    al.w0 = c->wd[l][0]; al.w1 = c->wd[l][1];
+    const int M0 = nimg * class_len(H, 0) * class_len(W, 0);
+    const ImgAddr xa = act_addr(c, l - 1);
+    Ep<MapDgrad, bf16_t, false, false, true> ep;
+    ep.map.stride_b = xa.stride_b; ep.map.stride_v = xa.stride_v; ep.map.V = V; ep.map.H = H; ep.map.W = W; ep.map.Cin = Ci; ep.map.imgs = nimg;
+    ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = xa.base; ep.N = 2 * Ci;
+    const double pix = (double)nimg * H * W;
+    rc = launch_gemm(c, al, M0, nullptr, 0, 2 * Ci, 4 * Co, ep, "conv_dgrad." + std::to_string(l),
+                     2.0 * ((double)nimg * Ho * Wo * Co + 2.0 * pix * Ci + 9.0 * Ci * Co), 2, 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co);
+    if (rc) return rc;
+    cur ^= 1;
+    dy = contiguous_imgs(c->gbuf[cur], (int64_t)Ci * H * W, V);
+  }
+  return flush_reduces(c);
+}
+int encoder_backward_generic(Ctx* c, const int32_t* idx, int n, bool acc, int cur) {
+  return encoder_backward_seq(c, idx, n, acc, c->gbuf[cur], c->fin[0], cur);
+}
+
+// ---------------------------------------------------------------- recurrent core
+// Forward of a chunk of `ne` whole environments (device list env) x T steps, rows time-major.  Encoder on all
+// ne*T rows at once, then per LSTM layer and step one GEMM (the operand row [x_t, h_enter] against the layer's
+// [W_ih, W_hh]) and one cell kernel, then hidden layers and heads on all rows.
+int forward_seq_chunk(Ctx* c, const int32_t* env, int ne, bool with_head) {
+  const int T = c->T, n = ne * T, H = c->H;
+  hipLaunchKernelGGL(k_seq_index, dim3(cdiv(n, 256)), dim3(256), 0, c->stream, env, ne, T, c->N, c->seqidx);
+  LAUNCHCHK(c, "k_seq_index");
+  int rc = (c->ln || c->E > 0) ? encoder_forward_generic(c, c->seqidx, n, 0) : encoder_forward_ff(c, c->seqidx, n, 0);
+  if (rc) return rc;
+  for (int l = 0; l < c->nl; ++l) {
+    const int K = c->lin[l] + H;
+    hipLaunchKernelGGL(k_lstm_init, dim3(cdiv(ne * H, 256)), dim3(256), 0, c->stream, env, ne, H, c->h0 + (int64_t)l * c->N * H, c->c0 + (int64_t)l * c->N * H,
+                       c->xh[l], (int64_t)K, c->lin[l], c->c_enter[l]);
+    LAUNCHCHK(c, "k_lstm_init");
+    const bool top = l == c->nl - 1;
+    bf16_t* outm = top ? c->htop : c->xh[l + 1];
+    const int64_t ld_out = top ? H : c->lin[l + 1] + H;
+    for (int t = 0; t < T; ++t) {
+      const int64_t r0 = (int64_t)t * ne;
+      ARows al = plain_arows(c->xh[l] + r0 * K, K, ne, K);
+      Ep<MapRows, float, true, false, false> ep;
+      ep.map = plain_map(4 * H, ne); ep.out = c->lstm_pre; ep.bias = c->p + c->lstmB[l]; ep.mask = nullptr; ep.N = 4 * H;
+      rc = launch_gemm(c, al, ne, c->shadow + c->lstmW[l], K, 4 * H, K, ep, "lstm_fwd." + std::to_string(l), 2.0 * ((double)ne * K + (double)K * 4 * H) + 16.0 * ne * H);
+      if (rc) return rc;
+      ProfScope ps(c, "lstm_cell_fwd", 30.0 * ne * H, (double)ne * H * (16.0 + 16.0 + 8.0 + 4.0));
+      const bool last = t == T - 1;
+      hipLaunchKernelGGL(k_lstm_cell_fwd, dim3(cdiv(ne * H, 256)), dim3(256), 0, c->stream, ne, H, c->lstm_pre, c->c_enter[l] + r0 * H, c->done, c->seqidx + r0,
+                         c->gates[l] + r0 * 4 * H, outm + r0 * ld_out, ld_out, last ? nullptr : c->xh[l] + (r0 + ne) * K + c->lin[l], (int64_t)K,
+                         last ? nullptr : c->c_enter[l] + (r0 + ne) * H);
+      LAUNCHCHK(c, "k_lstm_cell_fwd");
+    }
+  }
+  return trunk_forward(c, c->nl > 0 ? c->htop : c->feat, c->nl > 0 ? (int64_t)H : c->feat_ld, n, with_head);
+}
+
+// Its backward: heads and hidden layers on all rows, then back-propagation through time per LSTM layer (top
+// first): per step the cell's backward kernel and one GEMM that turns the gate gradients into the gradient of
+// the operand row [x_t, h_enter] - its h half is what step t-1 receives -; the layer's weight gradient is one
+// contraction over all rows afterwards.  Then the encoder's backward on all rows.
+int backward_seq_chunk(Ctx* c, int ne, bool acc, bool with_head) {
+  const int T = c->T, n = ne * T, H = c->H;
+  int cur = 0;
+  int rc = trunk_backward(c, c->htop, H, false, n, acc, with_head, &cur);
+  if (rc) return rc;
+  const bf16_t* dabove = c->gbuf[cur];
+  int64_t ld_above = H;
+  for (int l = c->nl - 1; l >= 0; --l) {
+    const int K = c->lin[l] + H;
+    for (int t = T - 1; t >= 0; --t) {
+      const int64_t r0 = (int64_t)t * ne;
+      const bool last = t == T - 1;
+      {
+        ProfScope ps(c, "lstm_cell_bwd", 40.0 * ne * H, (double)ne * H * (16.0 + 4.0 + 4.0 + 8.0 + 8.0));
+        hipLaunchKernelGGL(k_lstm_cell_bwd, dim3(cdiv(ne * H, 256)), dim3(256), 0, c->stream, ne, H, c->gates[l] + r0 * 4 * H, c->c_enter[l] + r0 * H, c->done,
+                           c->seqidx + r0, dabove + r0 * ld_above, ld_above, last ? nullptr : c->dxh[l] + (r0 + ne) * K + c->lin[l], (int64_t)K, c->dc_carry,
+                           last ? 1 : 0, c->da + r0 * 4 * H);
+        LAUNCHCHK(c, "k_lstm_cell_bwd");
+      }
+      ARows dl = plain_arows(c->da + r0 * 4 * H, 4 * H, ne, 4 * H);
+      Ep<MapRows, bf16_t, false, false, false> ep;
+      ep.map = plain_map(K, ne); ep.out = c->dxh[l] + r0 * K; ep.bias = nullptr; ep.mask = nullptr; ep.N = K;
+      rc = launch_gemm(c, dl, ne, c->lstmWT[l], 4 * H, K, 4 * H, ep, "lstm_dgrad." + std::to_string(l), 2.0 * ((double)ne * 4 * H + (double)ne * K + (double)K * 4 * H));
+      if (rc) return rc;
+    }
+    ARows dl = plain_arows(c->da, 4 * H, n, 4 * H);
+    ARows xl = plain_arows(c->xh[l], K, n, K);
+    rc = launch_wgrad(c, dl, xl, 4 * H, K, n, c->g + c->lstmW[l], c->g + c->lstmB[l], acc, "lstm_wgrad." + std::to_string(l), 2.0 * n * ((double)K + 4 * H) + 4.0 * (double)K * 4 * H);
+    if (rc) return rc;
+    dabove = c->dxh[l]; ld_above = K;   // the x half of this layer's operand gradient is the layer below's dh
+  }
+  return encoder_backward_seq(c, c->seqidx, n, acc, c->dxh[0], c->lin[0] + H, cur);
+}
+
 // The permutations of epochs epoch0 .. epoch0 + count - 1 (count <= PERM_BATCH) of (seed, update) into the slots
 // 0 .. count - 1 of c->perm ([PERM_BATCH][S]): five launches whatever the count.
 int gen_permutations(Ctx* c, uint64_t seed, uint64_t update, uint64_t epoch0, int count) {
   PermStreams ps;
   for (int e = 0; e < PERM_BATCH; ++e) ps.s[e] = perm_stream(seed, update, epoch0 + (uint64_t)(e < count ? e : 0));
-  const int S = c->S, g = cdiv(S, 256), nb = c->nb;
+  const int S = c->PU, g = cdiv(S, 256), nb = c->nb;  // the units a minibatch is made of: samples, or whole environments
   ProfScope pscope(c, "permutation", 0.0, 4.0 * S * count);
   hipLaunchKernelGGL(k_fill_i32, dim3(cdiv((int64_t)count * 2 * nb, 256)), dim3(256), 0, c->stream, c->phist, (int64_t)count * 2 * nb, 0);  // hist + cursor
   hipLaunchKernelGGL(k_perm_hist, dim3(g, count), dim3(256), 0, c->stream, ps, S, c->shift, nb, c->phist);
@@ -1133,9 +1452,12 @@ int launch_head_loss(Ctx* c, const LossData& L, int n, bool acc, bool distill, f
 bool head_loss_covers(const Ctx* c) { return c->XH == 0 && c->NH <= HEAD_LD && c->nfc >= 1 && (c->hid == 32 || c->hid == 64 || c->hid == 128); }
 
 int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool distill) {
-  const int B = c->S / hp->minibatches;
+  // a minibatch is Bu units of L rows each: samples (L = 1), or whole environments of T steps (recurrent nets)
+  const bool recurrent = c->nl > 0;
+  const int L = recurrent ? c->T : 1, Bu = c->PU / hp->minibatches, CU = recurrent ? c->CHe : c->CH;
+  const int B = Bu * L;
   const int steps = hp->epochs * hp->minibatches;
-  const int blocks_per_chunk = cdiv(c->CH, LOSS_BLOCK);
+  const int blocks_per_chunk = cdiv(CU * L, LOSS_BLOCK);
   int k = 0;
   const bool adaptive = !distill && hp->desired_kl > 0.f;  // the learning rate lives on the device and follows approx_kl
   if (!distill && hp->norm_adv) {
@@ -1153,17 +1475,20 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
     if (e % PERM_BATCH == 0) rc = gen_permutations(c, hp->seed, (uint64_t)c->update_idx, (uint64_t)e, hp->epochs - e < PERM_BATCH ? hp->epochs - e : PERM_BATCH);
     if (rc) return rc;
     for (int mb = 0; mb < hp->minibatches; ++mb, ++k) {
-      const int32_t* idx = c->perm + (int64_t)(e % PERM_BATCH) * c->S + (int64_t)mb * B;
+      const int32_t* units = c->perm + (int64_t)(e % PERM_BATCH) * c->PU + (int64_t)mb * Bu;
       int nblocks = 0;
-      for (int c0 = 0, ci = 0; c0 < B; c0 += c->CH, ++ci) {
-        const int n = (B - c0 < c->CH) ? B - c0 : c->CH;
+      for (int c0 = 0, ci = 0; c0 < Bu; c0 += CU, ++ci) {
+        const int nu = (Bu - c0 < CU) ? Bu - c0 : CU, n = nu * L;
         const bool fused_head = head_loss_covers(c);
-        rc = forward_chunk(c, idx + c0, n, !fused_head);
+        // the rollout samples of the chunk's rows: the permutation's entries themselves, or the index list that
+        // forward_seq_chunk builds from the chunk's environments
+        const int32_t* rows = recurrent ? c->seqidx : units + c0;
+        rc = recurrent ? forward_seq_chunk(c, units + c0, nu, !fused_head) : forward_chunk(c, rows, n, !fused_head);
         if (rc) return rc;
         float* sp = c->stat_part + (int64_t)ci * blocks_per_chunk * LOSS_NSTAT;
         float* dp = c->dls_part + (int64_t)ci * blocks_per_chunk * 32;
         LossData L;
-        L.Bfull = B; L.A = c->A; L.logstd = distill ? nullptr : c->p + c->logstd; L.idx = idx + c0; L.action = c->action; L.logp_old = c->logp;
+        L.Bfull = B; L.A = c->A; L.logstd = distill ? nullptr : c->p + c->logstd; L.idx = rows; L.action = c->action; L.logp_old = c->logp;
         L.v_old = c->value; L.adv = hp->norm_adv ? c->adv_n : c->adv; L.ret = c->ret; L.clip_eps = hp->clip_eps; L.vclip_eps = hp->vclip_eps; L.vf_coef = hp->vf_coef;
         L.aux_dim = distill ? hp->aux_dim : 0; L.aux_coef = hp->aux_coef;
         bool head_done = false;
@@ -1187,7 +1512,7 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
         }
         // partial slots of a ragged last chunk follow the full chunks contiguously
         nblocks = ci * blocks_per_chunk + cdiv(n, LOSS_BLOCK);
-        if (c0 + c->CH >= B) {
+        if (c0 + CU >= Bu) {
           // last chunk: every loss partial of the minibatch exists; their sums (statistics, log-std gradient)
           // are taken by one more block of the backward pass's reduction launch
           LossFinalize& f = c->lossfin;
@@ -1198,7 +1523,7 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
           f.lr_reset = (k == 0 && !(hp->lr_carry && c->lr_live)) ? 1 : 0;
           f.aux_dim = distill ? hp->aux_dim : 0; f.aux_coef = hp->aux_coef;
         }
-        rc = backward_chunk(c, idx + c0, n, c0 > 0, !head_done);
+        rc = recurrent ? backward_seq_chunk(c, nu, c0 > 0, !head_done) : backward_chunk(c, rows, n, c0 > 0, !head_done);
         if (rc) return rc;
       }
       if (c->lossfin.on) { rc = flush_reduces(c); if (rc) return rc; }  // (a backward pass always ends with a flush; kept for safety)
@@ -1248,6 +1573,10 @@ int create_impl(Ctx* c) {
   if ((int64_t)CH * V * c->cH[1] * c->cW[1] >= (1LL << 31) || (int64_t)CH * c->feat_ld >= (1LL << 40))
     return fail(c, PPO_ESHAPE, "chunk of %d samples is too large for 32-bit row indices; lower max_chunk", CH);
   const int64_t S = c->S;
+  c->PU = c->nl > 0 ? c->N : c->S;
+  c->CHe = CH / c->T < 1 ? 1 : CH / c->T;
+  if (c->CHe > c->N) c->CHe = c->N;
+  if (c->nl > 0 && (int64_t)c->CHe * c->T > CH) return fail(c, PPO_ESHAPE, "max_chunk = %d holds no whole environment of %d steps", CH, c->T);
   // parameters
   DALLOC(c, c->p, c->total); DALLOC(c, c->m, c->total); DALLOC(c, c->v, c->total); DALLOC(c, c->g, c->total);
   DALLOC(c, c->shadow, c->total + 8);
@@ -1262,11 +1591,11 @@ int create_impl(Ctx* c) {
   DALLOC(c, c->obs, S * V * c->img_elems);
   DALLOC(c, c->proprio, S * c->P); DALLOC(c, c->action, S * c->A);
   DALLOC(c, c->logp, S); DALLOC(c, c->value, S); DALLOC(c, c->reward, S); DALLOC(c, c->adv, S); DALLOC(c, c->adv_n, S); DALLOC(c, c->ret, S); DALLOC(c, c->done, S);
-  // permutation: about 32 keys per bucket
+  // permutation of the PU units a minibatch is drawn from: about 32 keys per bucket
   int nb = 1, lg = 0;
-  while ((int64_t)nb * 32 < S && nb < (1 << 20)) { nb <<= 1; ++lg; }
+  while ((int64_t)nb * 32 < c->PU && nb < (1 << 20)) { nb <<= 1; ++lg; }
   c->nb = nb; c->shift = 64 - lg;
-  DALLOC(c, c->perm, (int64_t)PERM_BATCH * S); DALLOC(c, c->ptmp, (int64_t)PERM_BATCH * S);  // one slot per epoch of a batch
+  DALLOC(c, c->perm, (int64_t)PERM_BATCH * c->PU); DALLOC(c, c->ptmp, (int64_t)PERM_BATCH * c->PU);  // one slot per epoch of a batch
   DALLOC(c, c->phist, (int64_t)PERM_BATCH * 2 * nb); DALLOC(c, c->pstart, (int64_t)PERM_BATCH * nb);
   // workspaces
   int64_t gmax = (int64_t)CH * c->feat_ld;
@@ -1277,6 +1606,40 @@ int create_impl(Ctx* c) {
     if (e > gmax) gmax = e;
   }
   DALLOC(c, c->feat, (int64_t)CH * c->feat_ld);
+  if ((int64_t)CH * c->fin[0] > gmax) gmax = (int64_t)CH * c->fin[0];
+  if (c->E > 0) {  // the last convolution's activation has a buffer of its own, read by the embedding
+    const int l = c->nconv - 1;
+    DALLOC(c, c->act[l], (int64_t)CH * V * c->flat);
+    DALLOC(c, c->embT, (int64_t)c->flat * c->E);
+    if ((int64_t)CH * V * c->flat > gmax) gmax = (int64_t)CH * V * c->flat;
+  }
+  if (c->ln) {
+    int64_t emax = 0;
+    for (int l = 0; l < c->nconv; ++l) {
+      const int64_t e = (int64_t)CH * V * c->cC[l + 1] * c->cH[l + 1] * c->cW[l + 1];
+      DALLOC(c, c->pre[l], e); DALLOC(c, c->lnstat[l], (int64_t)CH * V);
+      if (e > emax) emax = e;
+    }
+    DALLOC(c, c->dpre, emax);
+    if (emax > gmax) gmax = emax;
+  }
+  if (c->nl > 0) {
+    const int H = c->H;
+    c->xh[0] = c->feat;
+    for (int l = 0; l < c->nl; ++l) {
+      const int64_t K = c->lin[l] + H;
+      DALLOC(c, c->lstmWT[l], K * 4 * H);
+      if (l > 0) DALLOC(c, c->xh[l], (int64_t)CH * K);
+      DALLOC(c, c->dxh[l], (int64_t)CH * K);
+      DALLOC(c, c->gates[l], (int64_t)CH * 4 * H); DALLOC(c, c->c_enter[l], (int64_t)CH * H);
+    }
+    DALLOC(c, c->lstm_pre, (int64_t)c->CHe * 4 * H); DALLOC(c, c->da, (int64_t)CH * 4 * H); DALLOC(c, c->dc_carry, (int64_t)c->CHe * H);
+    DALLOC(c, c->htop, (int64_t)CH * H); DALLOC(c, c->seqidx, CH);
+    DALLOC(c, c->h0, (int64_t)c->nl * c->N * H); DALLOC(c, c->c0, (int64_t)c->nl * c->N * H);
+    HIPCHK(c, hipMemsetAsync(c->h0, 0, sizeof(float) * (size_t)c->nl * c->N * H, c->stream));
+    HIPCHK(c, hipMemsetAsync(c->c0, 0, sizeof(float) * (size_t)c->nl * c->N * H, c->stream));
+    if ((int64_t)CH * H > gmax) gmax = (int64_t)CH * H;
+  }
   for (int l = 0; l < c->nfc; ++l) { DALLOC(c, c->fcact[l], (int64_t)CH * c->fout[l]); if ((int64_t)CH * c->fout[l] > gmax) gmax = (int64_t)CH * c->fout[l]; }
   DALLOC(c, c->headout, (int64_t)CH * HEAD_LD); DALLOC(c, c->dhead, (int64_t)CH * HEAD_LD);
   if (c->XH > 0) {
@@ -1320,6 +1683,16 @@ int create_impl(Ctx* c) {
     if (nblk * c->NH > bneed) bneed = nblk * c->NH;
     pe_sum += need; bpe_sum += bneed;
   }
+  if (c->E > 0) { int64_t need, bneed; want(c->E, c->flat, CH, need, bneed); pe_sum += need; bpe_sum += bneed; }
+  for (int l = 0; l < c->nl; ++l) {
+    int64_t need, bneed;
+    want(4 * c->H, c->lin[l] + c->H, CH, need, bneed);
+    const int64_t per = (int64_t)4 * c->H * (c->lin[l] + c->H);
+    if (4 * per > need) need = 4 * per;
+    if (16 * (int64_t)c->H > bneed) bneed = 16 * (int64_t)c->H;
+    pe_sum += need; bpe_sum += bneed;
+  }
+  if (c->ln) pe_sum += 1024LL * 2 * 1024;  // layer-norm gain / shift partials: one per block of k_ln_bwd
   if (c->XH > 0) {
     int64_t need, bneed;
     want(c->XH, c->hid, CH, need, bneed); pe_sum += need; bpe_sum += bneed;
@@ -1333,7 +1706,10 @@ int create_impl(Ctx* c) {
   DALLOC(c, c->zpage, 512);
   HIPCHK(c, hipMemsetAsync(c->zpage, 0, 1024, c->stream));
   // loss / Adam partials
-  c->max_loss_blocks = cdiv(S, CH) * cdiv(CH, LOSS_BLOCK) + 1;
+  {
+    const int CU = c->nl > 0 ? c->CHe : CH, Lr = c->nl > 0 ? c->T : 1;
+    c->max_loss_blocks = (cdiv(c->PU, CU) + 1) * cdiv((int64_t)CU * Lr, LOSS_BLOCK) + 1;
+  }
   DALLOC(c, c->stat_part, (int64_t)c->max_loss_blocks * LOSS_NSTAT); DALLOC(c, c->dls_part, (int64_t)c->max_loss_blocks * 32);
   c->adam_blocks = cdiv(c->total, 1024); if (c->adam_blocks > 2048) c->adam_blocks = 2048;
   DALLOC(c, c->sq_part, c->adam_blocks);
@@ -1535,6 +1911,17 @@ int ppo_buffer_write_range(ppo_ctx* c, int32_t t, int32_t env_offset, int32_t co
   return PPO_OK;
 }
 
+int ppo_buffer_write_state(ppo_ctx* c, const float* d_h0, const float* d_c0) {
+  if (!c) return PPO_EINVAL;
+  if (c->nl <= 0) return fail(c, PPO_ESTATE, "this network has no recurrent layers");
+  const size_t bytes = sizeof(float) * (size_t)c->nl * c->N * c->H;
+  if (d_h0) HIPCHK(c, hipMemcpyAsync(c->h0, d_h0, bytes, hipMemcpyDeviceToDevice, c->stream));
+  else HIPCHK(c, hipMemsetAsync(c->h0, 0, bytes, c->stream));
+  if (d_c0) HIPCHK(c, hipMemcpyAsync(c->c0, d_c0, bytes, hipMemcpyDeviceToDevice, c->stream));
+  else HIPCHK(c, hipMemsetAsync(c->c0, 0, bytes, c->stream));
+  return PPO_OK;
+}
+
 int ppo_buffer_read_obs(ppo_ctx* c, int32_t t, void* d_obs_bf16) {
   if (!c) return PPO_EINVAL;
   if (t < 0 || t >= c->T) return fail(c, PPO_EINVAL, "t = %d outside [0, %d)", t, c->T);
@@ -1604,7 +1991,7 @@ int ppo_permutation(ppo_ctx* c, uint64_t seed, uint64_t update_idx, uint64_t epo
   if (!h_perm) return fail(c, PPO_EINVAL, "h_perm is NULL");
   int rc = gen_permutation(c, seed, update_idx, epoch);
   if (rc) return rc;
-  HIPCHK(c, hipMemcpyAsync(h_perm, c->perm, sizeof(int32_t) * (size_t)c->S, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipMemcpyAsync(h_perm, c->perm, sizeof(int32_t) * (size_t)c->PU, hipMemcpyDeviceToHost, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   return PPO_OK;
 }
@@ -1673,6 +2060,7 @@ int ppo_forward(ppo_ctx* c, const int32_t* d_idx, int64_t count, float* d_mu, fl
   if (!c) return PPO_EINVAL;
   if (!d_mu) return fail(c, PPO_EINVAL, "d_mu is NULL");
   if (count < 0 || (!d_idx && count > c->S)) return fail(c, PPO_EINVAL, "count out of range");
+  if (c->nl > 0) return fail(c, PPO_ESTATE, "ppo_forward treats samples independently: not available for a recurrent net");
   if (!all_written(c)) return fail(c, PPO_ESTATE, "ppo_forward needs all %d steps written", c->T);
   for (int64_t c0 = 0; c0 < count; c0 += c->CH) {
     int n = (int)((count - c0 < c->CH) ? count - c0 : c->CH);
@@ -1690,6 +2078,7 @@ int ppo_act(ppo_ctx* c, int32_t t, const void* d_obs, const float* d_proprio, co
             float* d_value) {
   if (!c) return PPO_EINVAL;
   if (!c->d.has_value_head) return fail(c, PPO_ESTATE, "ppo_act needs an actor-critic context (has_value_head = 1)");
+  if (c->nl > 0) return fail(c, PPO_ESTATE, "ppo_act keeps no recurrent state between calls: not available for a recurrent net");
   if (t < 0 || t >= c->T) return fail(c, PPO_EINVAL, "t = %d outside [0, %d)", t, c->T);
   if (!d_obs || !d_proprio || !d_noise) return fail(c, PPO_EINVAL, "d_obs, d_proprio and d_noise must not be NULL");
   int rc = write_slab(c, t, 0, c->N, d_obs, d_proprio, nullptr, nullptr, nullptr, nullptr, nullptr);

@@ -73,20 +73,22 @@ __global__ __launch_bounds__(LN_THREADS) void k_ln_fwd(const bf16_t* __restrict_
   }
 }
 
-// Backward of the layer normalisation.  dy: gradient w.r.t. the normalised (and ReLU-masked) output, addressed
-// like the forward's output; x, stats: the forward's input and statistics.  With xhat = (x - mean) rstd and
-// dxhat = dy * gain[c]:  dx = rstd (dxhat - avg(dxhat) - xhat avg(dxhat xhat)),  dgain[c] = sum dy xhat,
+// Backward of the layer normalisation and of the ReLU behind it.  dy: gradient w.r.t. the rectified output,
+// addressed like the forward's output; x, stats: the forward's input and statistics.  The ReLU passes gradient
+// where gain[c] xhat + shift[c] > 0 (recomputed here exactly as the forward formed it, so dy may or may not have
+// been masked already).  With xhat = (x - mean) rstd and dxhat = dy * gain[c]:  dx = rstd (dxhat - avg(dxhat) - xhat avg(dxhat xhat)),  dgain[c] = sum dy xhat,
 // dshift[c] = sum dy.  Block b takes images b, b + gridDim.x, ... and leaves ONE partial [2C] (gain gradients,
 // then shift gradients), summed later in block order; all sums in fixed orders.
 __global__ __launch_bounds__(LN_THREADS) void k_ln_bwd(ImgAddr dy, const bf16_t* __restrict__ x, const float2* __restrict__ stats, int nimg, int m,
-                                                       int C, const float* __restrict__ gain, bf16_t* __restrict__ dx, float* __restrict__ partial) {
+                                                       int C, const float* __restrict__ gain, const float* __restrict__ shift, bf16_t* __restrict__ dx,
+                                                       float* __restrict__ partial) {
   __shared__ float red[LN_THREADS / 64 + 1];
   __shared__ float acc[LN_THREADS][17];  // per-thread channel sums (padded rows: conflict-free column walks)
   const int tid = threadIdx.x, nch = m >> 3;
   const int c0 = (tid * 8) & (C - 1);
-  float g[8], dg[8], db[8];
+  float g[8], sh[8], dg[8], db[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) { g[j] = gain[c0 + j]; dg[j] = 0.f; db[j] = 0.f; }
+  for (int j = 0; j < 8; ++j) { g[j] = gain[c0 + j]; sh[j] = shift[c0 + j]; dg[j] = 0.f; db[j] = 0.f; }
   for (int img = blockIdx.x; img < nimg; img += gridDim.x) {
     const uint4* xi = reinterpret_cast<const uint4*>(x + (int64_t)img * m);
     const uint4* di = reinterpret_cast<const uint4*>(dy.ptr(img));
@@ -98,9 +100,11 @@ __global__ __launch_bounds__(LN_THREADS) void k_ln_bwd(ImgAddr dy, const bf16_t*
       float f[8], d[8]; unpack8(xi[k], f); unpack8(di[k], d);
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const float xh = (f[j] - mean) * rstd, dxh = d[j] * g[j];
+        const float gr = g[j] * rstd, br = sh[j] - mean * gr;   // the forward's y = x * gr + br
+        const float dj = (f[j] * gr + br > 0.f) ? d[j] : 0.f;
+        const float xh = (f[j] - mean) * rstd, dxh = dj * g[j];
         s1 += dxh; s2 += dxh * xh;
-        dg[j] += d[j] * xh; db[j] += d[j];
+        dg[j] += dj * xh; db[j] += dj;
       }
     }
     const float a1 = ln_block_sum(s1, red) / (float)m;
@@ -109,7 +113,12 @@ __global__ __launch_bounds__(LN_THREADS) void k_ln_bwd(ImgAddr dy, const bf16_t*
       float f[8], d[8]; unpack8(xi[k], f); unpack8(di[k], d);
       float o[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { const float xh = (f[j] - mean) * rstd; o[j] = rstd * (d[j] * g[j] - a1 - xh * a2); }
+      for (int j = 0; j < 8; ++j) {
+        const float gr = g[j] * rstd, br = sh[j] - mean * gr;
+        const float dj = (f[j] * gr + br > 0.f) ? d[j] : 0.f;
+        const float xh = (f[j] - mean) * rstd;
+        o[j] = rstd * (dj * g[j] - a1 - xh * a2);
+      }
       dxo[k] = make_uint4(pack2bf(o[0], o[1]), pack2bf(o[2], o[3]), pack2bf(o[4], o[5]), pack2bf(o[6], o[7]));
     }
   }
@@ -194,4 +203,19 @@ __global__ void k_lstm_cell_bwd(int ne, int H, const float* __restrict__ gates, 
   d[2 * H + k] = f2bf(dc * ig * (1.f - gg * gg));
   d[3 * H + k] = f2bf(dh * tc * og * (1.f - og));
   dc_carry[i] = dc * fg;
+}
+
+// d[r][0..cols) = 0 where x[r][0..cols) <= 0 (rows of stride ld_d / ld_x): the ReLU mask of a stored activation
+// applied to its gradient when the kernel that produced the gradient could not (eight elements per thread).
+__global__ void k_mask_rows(int64_t rows, int cols, bf16_t* __restrict__ d, int64_t ld_d, const bf16_t* __restrict__ x, int64_t ld_x) {
+  const int cpr = cols >> 3;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * cpr) return;
+  const int64_t r = i / cpr;
+  const int k = (int)(i - r * cpr) * 8;
+  uint4 v = *reinterpret_cast<const uint4*>(d + r * ld_d + k);
+  const uint4 m = *reinterpret_cast<const uint4*>(x + r * ld_x + k);
+  auto keep = [](uint32_t w) -> uint32_t { return (((short)(w & 0xffffu) > 0) ? 0x0000ffffu : 0u) | (((short)(w >> 16) > 0) ? 0xffff0000u : 0u); };
+  v.x &= keep(m.x); v.y &= keep(m.y); v.z &= keep(m.z); v.w &= keep(m.w);
+  *reinterpret_cast<uint4*>(d + r * ld_d + k) = v;
 }

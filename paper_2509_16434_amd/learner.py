@@ -78,6 +78,7 @@ def load_library():
         "ppo_buffer_write_range": (C.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
         "ppo_act": (C.c_int, [vp, i32, vp, vp, vp, vp, vp, vp]),
         "ppo_buffer_write_outcome": (C.c_int, [vp, i32, vp, vp]),
+        "ppo_buffer_write_state": (C.c_int, [vp, vp, vp]),
         "ppo_buffer_read_obs": (C.c_int, [vp, i32, vp]),
         "ppo_gae": (C.c_int, [vp, vp, C.c_float, C.c_float]),
         "ppo_get_adv_ret": (C.c_int, [vp, vp, vp]),
@@ -100,7 +101,7 @@ def load_library():
 _lib = load_library()
 EXPORTS = ("ppo_create", "ppo_destroy", "ppo_last_error", "ppo_param_count", "ppo_buffer_image_bytes",
            "ppo_set_params", "ppo_get_params", "ppo_get_grads", "ppo_set_opt_state", "ppo_get_opt_state", "ppo_get_adaptive_lr", "ppo_set_adaptive_lr",
-           "ppo_buffer_write", "ppo_buffer_write_range", "ppo_act", "ppo_buffer_write_outcome", "ppo_buffer_read_obs", "ppo_gae", "ppo_get_adv_ret", "ppo_permutation", "ppo_permutation_static", "ppo_update", "distill_update",
+           "ppo_buffer_write", "ppo_buffer_write_range", "ppo_act", "ppo_buffer_write_outcome", "ppo_buffer_write_state", "ppo_buffer_read_obs", "ppo_gae", "ppo_get_adv_ret", "ppo_permutation", "ppo_permutation_static", "ppo_update", "distill_update",
            "ppo_forward", "ppo_profile", "ppo_profile_report", "ppo_diag_gemm", "ppo_diag_peak")
 
 
@@ -310,6 +311,12 @@ class Learner:
         torch = self._torch
         self._chk(_lib.ppo_buffer_write_outcome(self._h, t, _dev(reward, torch.float32, self.N), _dev(done, torch.uint8, self.N)))
 
+    def buffer_write_state(self, h0=None, c0=None):
+        """Recurrent nets: LSTM state of every environment at the start of the rollout, [layers][N][units] fp32 (None: zeros)."""
+        torch, net = self._torch, self.net
+        n = net.get("lstm_layers", 0) * self.N * net.get("lstm_units", 0)
+        self._chk(_lib.ppo_buffer_write_state(self._h, _dev(h0, torch.float32, n), _dev(c0, torch.float32, n)))
+
     def buffer_read_obs(self, t):
         torch, net = self._torch, self.net
         out = torch.empty(self.N, net.get("n_views", 1), net["in_c"], net["in_h"], net["in_w"], dtype=torch.bfloat16,
@@ -332,7 +339,7 @@ class Learner:
     def permutation(self, seed, update_idx, epoch) -> np.ndarray:
         out = np.empty(self.N * self.T, np.int32)
         self._chk(_lib.ppo_permutation(self._h, seed, update_idx, epoch, out.ctypes.data_as(C.POINTER(C.c_int32))))
-        return out
+        return out[:self.N] if self.net.get("lstm_layers", 0) else out   # a recurrent net shuffles whole environments
 
     def _run(self, fn, hp: dict, want_stats: bool):
         h = make_hparams(hp)
