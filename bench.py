@@ -44,7 +44,7 @@ PEAK_FP32_VALU_TF = 157.3   # fp32 vector, published
 
 RIDGE_FLOP_PER_BYTE = PEAK_MFMA_BF16_TF * 1e12 / (PEAK_HBM_GBS * 1e9)  # 312.5
 HBM_SIDE_CLASSES = ("buffer_write", "gae", "adam", "permutation", "adv_normalize", "wgrad_reduce", "weight_repack")
-PER_CONFIG_STEPS = {0: 20, 1: 20, 2: 4, 3: 4, 4: 3, 5: 2}
+PER_CONFIG_STEPS = {0: 20, 1: 20, 2: 4, 3: 4, 4: 3, 5: 2, 6: 3}
 
 
 def kernel_bound(rec: dict) -> str:

@@ -7,7 +7,9 @@ distillation, 4 large batch).  Horizon 16 and the 7+16 = 23-d action space
 follow the paper (Sec. III-B sizing example; Sec. III-C robot description);
 resolution 160x120 is the paper's Table I row 1.  Index 5 is Table I row 2: 320x240 depth at the
 2100 environments the disaggregated set-up reaches there, with the network and hyper-parameters of
-the full configuration.
+the full configuration.  Index 6 is the paper's own teacher (Sec. III-C, Fig. 3: 4-layer CNN [16, 32, 64, 128] with
+layer normalisation, 32-d embedding, two LSTM layers of 1024 units, MLP [512, 512, 256]) at the 1024 environments one
+GPU of the data-parallel set-up holds at 160x120 (Table I), trained on minibatches of whole environments.
 """
 from __future__ import annotations
 
@@ -17,10 +19,10 @@ _PPO_HP = dict(gamma=0.99, lam=0.95, clip_eps=0.2, vclip_eps=0.0, vf_coef=0.5, e
                lr=3e-4, beta1=0.9, beta2=0.999, adam_eps=1e-8)
 
 
-def _net(n_views, c, h, w, P, A, conv, fc, value=1):
+def _net(n_views, c, h, w, P, A, conv, fc, value=1, **extra):
     return dict(n_views=n_views, in_c=c, in_h=h, in_w=w, proprio_dim=P, act_dim=A,
                 conv_ch=list(conv), conv_k=3, conv_stride=2, conv_pad=1, fc_dim=list(fc),
-                has_value_head=value)
+                has_value_head=value, **extra)
 
 
 CONFIGS = [
@@ -41,6 +43,9 @@ CONFIGS = [
          hp=dict(_PPO_HP, epochs=5, minibatches=8, ent_coef=0.01, vclip_eps=0.2)),
     dict(name="c5_hires", kind="ppo", num_envs=2100, horizon=16, obs_dtype="bf16", seed=1239,
          net=_net(1, 1, 240, 320, 64, 23, (32, 64, 64, 128), (512, 256, 128)),
+         hp=dict(_PPO_HP, epochs=5, minibatches=4, ent_coef=0.01, vclip_eps=0.2)),
+    dict(name="c6_paper_teacher", kind="ppo", num_envs=1024, horizon=16, obs_dtype="bf16", seed=1240,
+         net=_net(1, 1, 120, 160, 64, 23, (16, 32, 64, 128), (512, 512, 256), layer_norm=1, embed_dim=32, lstm_layers=2, lstm_units=1024),
          hp=dict(_PPO_HP, epochs=5, minibatches=4, ent_coef=0.01, vclip_eps=0.2)),
 ]
 
@@ -107,9 +112,18 @@ def flops_per_sample(net: dict) -> dict:
         if i == 0:
             first = f
     c, h, w = shp[-1]
-    fin = net["n_views"] * c * h * w + net["proprio_dim"]
+    enc = c * h * w
+    if net.get("embed_dim", 0):
+        fwd += 2 * net["n_views"] * enc * net["embed_dim"]
+        enc = net["embed_dim"]
+    fin = net["n_views"] * enc + net["proprio_dim"]
+    for _ in range(net.get("lstm_layers", 0)):
+        fwd += 2 * 4 * net["lstm_units"] * (fin + net["lstm_units"])
+        fin = net["lstm_units"]
     for fo in net["fc_dim"]:
         fwd += 2 * fin * fo
         fin = fo
     fwd += 2 * fin * (net["act_dim"] + (1 if net["has_value_head"] else 0))
+    if net.get("aux_hidden", 0):
+        fwd += 2 * net["aux_hidden"] * (fin + net["aux_dim"])
     return dict(fwd=fwd, fwd_bwd=3 * fwd - first)

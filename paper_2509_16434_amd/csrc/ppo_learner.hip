@@ -68,6 +68,7 @@ hipError_t static_scratch(int32_t** out) {
 struct Ctx {
   ppo_net_desc d;
   hipStream_t stream = nullptr;
+  int dev = 0;  // the HIP device the context lives on (kernel attributes are set once per device)
   std::string err;
   // geometry
   int N = 0, T = 0, S = 0, V = 1, A = 0, P = 0, NH = 0, nconv = 0, nfc = 0;
@@ -437,8 +438,8 @@ int launch_gemm(Ctx* c, const AL& al_, int M, const bf16_t* Bm, int64_t ldb, int
     constexpr int nst = (BM_ + BN_) * 128 * 8 <= 128 * 1024 ? 8 : ((BM_ + BN_) * 128 * 4 <= 128 * 1024 ? 4 : 3);            \
     auto kfn = k_gemm_rs<BM_, BN_, WM_, WN_, nst, AL, EP>;                                                               \
     constexpr int lds = nst * (BM_ + BN_) * 128;                                                                         \
-    static bool attr_set = false;                                                                                        \
-    if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, lds)); attr_set = true; } \
+    static uint64_t attr_devs = 0;  /* bit d: set on device d */                                                                                        \
+    if (!((attr_devs >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, lds)); attr_devs |= 1ull << c->dev; } \
     hipLaunchKernelGGL(kfn, grid, dim3((ncw + 4) * 64), lds, c->stream, al, Bm, ldb, N, ep, c->zpage);                    \
   } while (0)
 #define LAUNCH_GEMM(BM_, BN_, WM_, WN_, GX, GY)                                                                        \
@@ -541,8 +542,8 @@ int launch_wgrad_rs(Ctx* c, const bf16_t* dy, int64_t ld_dy, const bf16_t* x, in
   a.out = a.direct ? gw : c->partial; a.bias_out = gb ? (a.direct ? gb : c->bias_partial) : nullptr;
   {
     ProfScope ps(c, name, 2.0 * M * (double)Nn * Kk, abytes);
-    static bool attr_set = false;
-    if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)k_wgrad_rs, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS_BYTES)); attr_set = true; }
+    static uint64_t attr_devs = 0;  /* bit d: set on device d */
+    if (!((attr_devs >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)k_wgrad_rs, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS_BYTES)); attr_devs |= 1ull << c->dev; }
     hipLaunchKernelGGL(k_wgrad_rs, dim3(cdiv(Kk, S::TK), cdiv(Nn, S::TN), splits), dim3(S::THREADS), S::LDS_BYTES, c->stream, a);
     LAUNCHCHK(c, "k_wgrad_rs");
   }
@@ -664,8 +665,8 @@ int launch_conv_fwd_tile_t(Ctx* c, const ConvTileArgs& a, const std::string& nam
   // bands of four or more output rows share at most an eighth of their input rows with a neighbour: read once, non-temporal
   const bool nt = a.TR >= 4;
   auto kfn = nt ? k_conv_fwd_tile<CIN, LOAD_NT> : k_conv_fwd_tile<CIN, 0>;
-  static bool attr_set[2] = {false, false};
-  if (!attr_set[nt]) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_set[nt] = true; }
+  static uint64_t attr_devs[2] = {0, 0};  // bit d: set on device d
+  if (!((attr_devs[nt] >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_devs[nt] |= 1ull << c->dev; }
   ProfScope ps(c, name, flops, abytes);
   hipLaunchKernelGGL(kfn, dim3(gx, gy), dim3(S::THREADS), lds, c->stream, a);
   LAUNCHCHK(c, "k_conv_fwd_tile");
@@ -712,8 +713,8 @@ int launch_conv_wgrad_tile_t(Ctx* c, ConvWgradArgs a, float* gw, float* gb, bool
   a.partial = c->partial; a.bias_partial = gb ? c->bias_partial : nullptr;
   const int lds = S::lds_bytes(a.W, a.TR, a.nstep);
   auto kfn = k_conv_wgrad_tile<CIN>;
-  static bool attr_set = false;
-  if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_set = true; }
+  static uint64_t attr_devs = 0;  /* bit d: set on device d */
+  if (!((attr_devs >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_devs |= 1ull << c->dev; }
   {
     ProfScope ps(c, name, flops, abytes);
     hipLaunchKernelGGL(kfn, dim3(gx, gy), dim3(S::THREADS), lds, c->stream, a);
@@ -772,8 +773,8 @@ int launch_conv_dgrad_tile_t(Ctx* c, ConvDgradArgs a, int nimg, const std::strin
     *grid_out = gx;
   }
   auto kfn = k_conv_dgrad_tile<CI, C0>;
-  static bool attr_set = false;
-  if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_set = true; }
+  static uint64_t attr_devs = 0;  /* bit d: set on device d */
+  if (!((attr_devs >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_devs |= 1ull << c->dev; }
   ProfScope ps(c, name, flops, abytes);
   hipLaunchKernelGGL(kfn, dim3(gx), dim3(S::THREADS), lds_of(a.TQ), c->stream, a);
   LAUNCHCHK(c, "k_conv_dgrad_tile");
@@ -816,8 +817,8 @@ int launch_conv_dgrad_wgrad0_reg_t(Ctx* c, ConvDgradArgs a, int nimg, const std:
   a.partial0 = c->partial;
   *grid_out = gx;
   auto kfn = k_conv_dgrad_wgrad0_tile<C0, NCW>;
-  static bool attr_set = false;
-  if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_set = true; }
+  static uint64_t attr_devs = 0;  /* bit d: set on device d */
+  if (!((attr_devs >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_devs |= 1ull << c->dev; }
   ProfScope ps(c, name, flops, abytes);
   hipLaunchKernelGGL(kfn, dim3(gx), dim3(S::THREADS), S::lds_bytes(a.W, a.Wo, a.W0, C0, a.TQ), c->stream, a);
   LAUNCHCHK(c, "k_conv_dgrad_wgrad0_tile");
@@ -856,8 +857,8 @@ int launch_conv0_fwd_tile_t(Ctx* c, Conv0Args a, int nimg) {
   a.tile_blocks = gx;
   if (a.gather_blocks > 0) a.gather_blocks = (int)std::min<int64_t>(32, cdiv((int64_t)a.pB * a.P, 512));
   auto kfn = k_conv0_fwd_tile<C0>;
-  static bool attr_set = false;
-  if (!attr_set) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024)); attr_set = true; }
+  static uint64_t attr_devs = 0;  /* bit d: set on device d */
+  if (!((attr_devs >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024)); attr_devs |= 1ull << c->dev; }
   hipLaunchKernelGGL(kfn, dim3(gx + a.gather_blocks), dim3(S::THREADS), S::lds_bytes(a.W, a.TR, a.Cout), c->stream, a);
   LAUNCHCHK(c, "k_conv0_fwd_tile");
   return PPO_OK;
@@ -1425,14 +1426,14 @@ int launch_head_loss_t(Ctx* c, const LossData& L, int n, bool acc, bool distill,
   a.wpart = c->partial; a.bpart = c->bias_partial; a.stat_part = sp; a.dls_part = dp; a.n = n; a.NH = c->NH;
   {
     ProfScope ps(c, "head+loss", 6.0 * n * (double)HID * HEAD_LD, (double)n * (4.0 * HID + 4.0 * c->A + 20.0));
-    static bool attr_set[2] = {false, false};
+    static uint64_t attr_devs[2] = {0, 0};  // bit d: set on device d
     if (distill) {
       auto kfn = k_head_loss<HID, true>;
-      if (!attr_set[1]) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS_BYTES)); attr_set[1] = true; }
+      if (!((attr_devs[1] >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS_BYTES)); attr_devs[1] |= 1ull << c->dev; }
       hipLaunchKernelGGL(kfn, dim3(nblk), dim3(256), S::LDS_BYTES, c->stream, a, L);
     } else {
       auto kfn = k_head_loss<HID, false>;
-      if (!attr_set[0]) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS_BYTES)); attr_set[0] = true; }
+      if (!((attr_devs[0] >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS_BYTES)); attr_devs[0] |= 1ull << c->dev; }
       hipLaunchKernelGGL(kfn, dim3(nblk), dim3(256), S::LDS_BYTES, c->stream, a, L);
     }
     LAUNCHCHK(c, "k_head_loss");
@@ -1563,6 +1564,8 @@ int run_update(Ctx* c, const ppo_hparams* hp, ppo_mb_stats* host_stats, bool dis
 
 int create_impl(Ctx* c) {
   build_geometry(c);
+  HIPCHK(c, hipGetDevice(&c->dev));
+  if (c->dev < 0 || c->dev >= 64) return fail(c, PPO_EHIP, "device number %d out of range", c->dev);
   { int32_t* ws = nullptr; HIPCHK(c, static_scratch(&ws)); }  // the static scratch of ppo_permutation_static on this device
   const int V = c->V;
   int CH = c->d.max_chunk > 0 ? c->d.max_chunk : 16384 / V;
@@ -2148,6 +2151,7 @@ int ppo_diag_gemm(int32_t M, int32_t N, int32_t K, const float* h_a, const float
   if (!h_a || !h_b || !h_c || M < 1 || N < 1 || K < 8 || K % 8) return PPO_EINVAL;
   Ctx tmp;
   Ctx* c = &tmp;
+  if (hipGetDevice(&c->dev) != hipSuccess || c->dev < 0 || c->dev >= 64) return fail(nullptr, PPO_EHIP, "no usable HIP device");
   float *da = nullptr, *db = nullptr, *dc = nullptr;
   bf16_t *ba = nullptr, *bb = nullptr;
   int rc = PPO_OK;

@@ -127,14 +127,15 @@ def test_buffer_write_by_environment_ranges(L):
     with pytest.raises(L.LearnerError) as e:
         part.buffer_read_obs(0)
     assert e.value.code == L.PPO_ESTATE
-    part.buffer_write_range(0, 0, dev(ro2["obs"][0]), *[dev(ro2[k][0]) for k in fields])
-    # within a rollout, a partial write into a complete step makes that step (only) incomplete again
+    # within a rollout (step 0 is still missing), a partial write into a complete step makes that step incomplete again
     part.buffer_write_range(3, 10, dev(ro2["obs"][3][10:20]), *[dev(ro2[k][3][10:20]) for k in fields])
     with pytest.raises(L.LearnerError) as e:
-        part.gae(lv, hp["gamma"], hp["lam"])
+        part.buffer_read_obs(3)
     assert e.value.code == L.PPO_ESTATE
     for a, b in ((0, 10), (20, 50)):
         part.buffer_write_range(3, a, dev(ro2["obs"][3][a:b]), *[dev(ro2[k][3][a:b]) for k in fields])
+    assert torch.equal(part.buffer_read_obs(3), dev(ro2["obs"][3]).to(torch.bfloat16))
+    part.buffer_write_range(0, 0, dev(ro2["obs"][0]), *[dev(ro2[k][0]) for k in fields])
     fill_learner(full, cfg, ro2)
     lv2 = dev(ro2["last_value"])
     for x in (full, part):

@@ -647,7 +647,7 @@ def test_sampled_kl_estimate_is_the_gaussian_divergence():
 
 
 def test_param_counts_of_the_workloads():
-    want = [69_753, 1_156_975, 5_573_103, 10_786_455, 5_573_103, 19_991_023]   # hand count per layer
+    want = [69_753, 1_156_975, 5_573_103, 10_786_455, 5_573_103, 19_991_023, 14_334_639]   # hand count per layer
     for c, w in zip(configs.CONFIGS, want):
         assert orc.param_count(c["net"]) == w == configs.param_count(c["net"])
         assert sum(int(np.prod(s)) for _, s, _ in synth.param_layout(c["net"])) == w
