@@ -114,21 +114,28 @@ __global__ __launch_bounds__(64) void k_gae(int T, int N, const float* __restric
   float next_v = last_value[n], next_a = 0.f;
   for (int t1 = T; t1 > 0; t1 -= TC) {  // steps [t0, t1), last chunk first
     const int t0 = t1 > TC ? t1 - TC : 0, cnt = t1 - t0;
+    // No branch between the loads (a slot beyond the chunk re-reads the chunk's last step): the compiler
+    // drains every outstanding load at a branch target, which would put the round trips back in a row.
     float r[TC], v[TC];
     uint8_t d[TC];
 #pragma unroll
-    for (int j = 0; j < TC; ++j)
-      if (j < cnt) { const int64_t i = (int64_t)(t0 + j) * N + n; r[j] = reward[i]; v[j] = value[i]; d[j] = done[i]; }
+    for (int j = 0; j < TC; ++j) {
+      const int64_t i = (int64_t)(t0 + (j < cnt ? j : cnt - 1)) * N + n;
+      r[j] = reward[i]; v[j] = value[i]; d[j] = done[i];
+    }
+    asm volatile("" ::: "memory");  // every load above is issued before the first store below (the scheduler would sink them to their uses)
+    // Slots beyond the chunk come first in this order; they leave the running pair untouched and write the
+    // chunk's last step, which that step's own turn then overwrites (same thread, same address: in order).
 #pragma unroll
-    for (int j = TC - 1; j >= 0; --j)
-      if (j < cnt) {
-        const int64_t i = (int64_t)(t0 + j) * N + n;
-        const float nt = d[j] ? 0.f : 1.f;
-        const float delta = r[j] + gamma * next_v * nt - v[j];
-        const float a = delta + gamma * lambda * nt * next_a;
-        adv[i] = a; ret[i] = a + v[j];
-        next_a = a; next_v = v[j];
-      }
+    for (int j = TC - 1; j >= 0; --j) {
+      const bool live = j < cnt;
+      const int64_t i = (int64_t)(t0 + (live ? j : cnt - 1)) * N + n;
+      const float nt = d[j] ? 0.f : 1.f;
+      const float delta = r[j] + gamma * next_v * nt - v[j];
+      const float a = delta + gamma * lambda * nt * next_a;
+      adv[i] = a; ret[i] = a + v[j];
+      next_a = live ? a : next_a; next_v = live ? v[j] : next_v;
+    }
   }
 }
 
