@@ -7,8 +7,9 @@
 //    an LDS image; the im2col gather happens at LDS-read time, where a tap is a constant byte
 //    offset from the lane's window corner.  Every input byte crosses the memory path once per block.
 //  * The copy is done by four extra waves with loads that write LDS directly (global_load_lds_dwordx4,
-//    lane l's 16 bytes land at the instruction's LDS base + 16*l), into a ring of three images:
-//    two bands are in flight while one is computed.  (One wave alone sustains only about one such
+//    lane l's 16 bytes land at the instruction's LDS base + 16*l), into a ring of nbuf images
+//    (three for the large layers, as many as fit up to MAXBUF for small ones, whose bands are too few bytes to
+//    cover the memory latency two at a time): nbuf - 1 bands are in flight while one is computed.  (One wave alone sustains only about one such
 //    load per 190 cycles.)  A loader's own vmcnt counts only these loads, so "band q has landed" is an exact wait; one barrier per tile hands the image over and
 //    returns the ring slot consumed one tile earlier.
 //  * Each image row has a zero pixel to its left and right (written once), rows outside the image
@@ -36,6 +37,7 @@ struct ConvTileArgs {
                               // bits[(i*Ho*Wo + p) * ceil(Cout/32) + w]; read by the transposed convolution as ReLU mask
   int V, H, W, Ho, Wo, Cout;
   int TR, NB, ntiles;         // output rows per band, bands per image, nimg * NB
+  int nbuf;                   // ring images (3 .. MAXBUF)
 };
 
 // bf16 pair of (max(lo, 0), max(hi, 0)): rounded first, then clamped as 16-bit integers (a negative bf16 is a
@@ -63,19 +65,22 @@ __device__ __forceinline__ uint32_t nonzero4(uint32_t x, uint32_t y, uint32_t ne
   return (uint32_t)__builtin_amdgcn_sdot4((int)s, (int)negw, 0, false);
 }
 
-template <int CIN>
+template <int CIN, int WIDE = 0>
 struct ConvTileShape {
+  static_assert(!WIDE || CIN == 64, "the wide form is for 64 input channels");
   static constexpr int NW = (CIN == 32) ? 64 : 32;   // output columns per wave (18432 weights per wave)
-  static constexpr int WGM = (CIN == 32) ? 4 : 2, WGN = 4 / WGM;
-  static constexpr int BM = WGM * 32, BN = WGN * NW;  // 128 x 64 or 64 x 64
+  // WIDE: the four waves stand side by side (128 columns) and each takes both 32-pixel halves of the band, so that a
+  // layer with more than 64 output channels loads its input once instead of once per 64 columns
+  static constexpr int WGM = WIDE ? 1 : (CIN == 32) ? 4 : 2, WGN = 4 / WGM, TM = WIDE ? 2 : 1;
+  static constexpr int BM = WGM * TM * 32, BN = WGN * NW;  // 128 x 64, 64 x 64 or 64 x 128
   static constexpr int PIX = CIN * 2;                 // bytes per pixel
   static constexpr int MAXSEG = 6;                    // 1 KiB load instructions per image row
-  static constexpr int NBUF = 3;
+  static constexpr int MAXBUF = 6;
   static constexpr int SP = NW + 8;                   // staging pitch (elements)
   static constexpr int STAGE_BYTES = 4 * 32 * SP * 2;
   static constexpr int THREADS = 512;                 // four compute waves + four loader waves
   static int image_bytes(int W, int TR) { return (2 * TR + 1) * (W + 2) * PIX; }
-  static int lds_bytes(int W, int TR) { return NBUF * image_bytes(W, TR) + STAGE_BYTES + BN * 4; }
+  static int lds_bytes(int W, int TR, int nbuf) { return nbuf * image_bytes(W, TR) + STAGE_BYTES + BN * 4; }
 };
 
 // LDS image rows hold pixel slots of CIN*2 bytes (slot 0 and slot W+1 are zero pads).  A byte at
@@ -90,16 +95,28 @@ __device__ __forceinline__ uint32_t tile_swz_bits(uint32_t off) {
   return (((t & 1u) << 2) | (t >> 1)) << 4;              // rotated, so neighbours differ in the top bit
 }
 
+// The forward kernel's form for 64 channels.  A b128 operand read is served eight lanes at a time, and eight lanes
+// run at full rate when their 16-byte chunks sit at eight different positions of the 128-byte pixel.  Consecutive
+// lanes are consecutive output pixels, row after row of the band, so the key that permutes a pixel's chunks counts
+// pixels the same way: slot pair + Wo * (image row / 2), i.e. lane number plus a constant for every tap.  (The
+// in-row key alone repeats where a short output row wraps inside a group of eight lanes: 16 instead of 8 cycles
+// per read at Wo = 10.)  `rowkey` = Wo * (row >> 1) of the LDS image row the byte belongs to.
+template <int CIN>
+__device__ __forceinline__ uint32_t fwd_swz_bits(uint32_t off, uint32_t rowkey) {
+  if (CIN == 32) return tile_swz_bits<32>(off);
+  return (((off >> 8) + rowkey) & 7u) << 4;
+}
+
 // AUX: cache policy of the band loads (LOAD_NT where a band shares few rows with its neighbours)
-template <int CIN, int AUX>
+template <int CIN, int AUX, int WIDE = 0>
 __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
-  typedef ConvTileShape<CIN> S;
-  constexpr int NW = S::NW, WGN = S::WGN, TN = NW / 32, PIX = S::PIX, SP = S::SP, NBUF = S::NBUF;
+  typedef ConvTileShape<CIN, WIDE> S;
+  constexpr int NW = S::NW, WGN = S::WGN, TN = NW / 32, TM = S::TM, PIX = S::PIX, SP = S::SP;
   constexpr int KC = CIN / 16;  // MFMA k-steps per tap
   constexpr int CPP = CIN / 8;  // 16-byte chunks per pixel
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, h = lane >> 5;
-  const int W = a.W, WP = W + 2, TR = a.TR, Wo = a.Wo;
+  const int W = a.W, WP = W + 2, TR = a.TR, Wo = a.Wo, NBUF = a.nbuf;
   const int nrows = 2 * TR + 1, rowbytes = W * PIX, segs = (rowbytes + 1023) >> 10;
   const int image_bytes = nrows * WP * PIX;
   // tiles of this block: vb, vb + gridDim.x, ...
@@ -116,36 +133,41 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
     // ------------------------------------------------------------------ loaders: span row r belongs to loader r % 4
     const int lw = wave - 4;
     const int ni = ((nrows - lw + 3) >> 2) * segs;  // this wave's loads per band
-    int goff[S::MAXSEG];  // byte offset within an image row of the chunk this lane fetches, -1 = none
+    // this lane's 16 bytes land at in-row offset PIX + sg*1024 + lane*16: it fetches what belongs there
+    // (byte offset within the image row; depends on the row for 64 channels)
+    auto src_off = [&](int sg, int row) {
+      const uint32_t phys = PIX + sg * 1024 + lane * 16, logi = phys ^ fwd_swz_bits<CIN>(phys, (uint32_t)(Wo * (row >> 1)));
+      return (sg < segs && (int)phys < (W + 1) * PIX) ? (int)logi - PIX : -1;  // -1 = none
+    };
+    int goff[S::MAXSEG];
 #pragma unroll
-    for (int sg = 0; sg < S::MAXSEG; ++sg) {
-      // this lane's 16 bytes land at in-row offset PIX + sg*1024 + lane*16: fetch what belongs there
-      const uint32_t phys = PIX + sg * 1024 + lane * 16, logi = phys ^ tile_swz_bits<CIN>(phys);
-      goff[sg] = (sg < segs && (int)phys < (W + 1) * PIX) ? (int)logi - PIX : -1;
-    }
+    for (int sg = 0; sg < S::MAXSEG; ++sg) goff[sg] = src_off(sg, 0);
+    int slot = 0;  // ring image the next issued band goes to
     auto issue = [&](int q) {
       const int t = vb + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
       const int iy_lo = 2 * band * TR - 1;
       const char* src = reinterpret_cast<const char*>(a.in.ptr_uniform(img)) + (int64_t)iy_lo * rowbytes;
-      char* dst = lds + (q % NBUF) * image_bytes + PIX;  // skip the left pad
+      char* dst = lds + slot * image_bytes + PIX;  // skip the left pad
+      slot = slot + 1 == NBUF ? 0 : slot + 1;
       for (int row = lw; row < nrows; row += 4) {
         const int iy = iy_lo + row;
         const bool inside = iy >= 0 && iy < a.H;
 #pragma unroll
         for (int sg = 0; sg < S::MAXSEG; ++sg)
           if (sg < segs) {
-            const char* p = inside ? src + (int64_t)row * rowbytes + goff[sg] : reinterpret_cast<const char*>(a.zpage) + lane * 16;
-            if (goff[sg] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + row * WP * PIX + sg * 1024), 16, 0, AUX);
+            const int go = (CIN == 32) ? goff[sg] : src_off(sg, row);
+            const char* p = inside ? src + (int64_t)row * rowbytes + go : reinterpret_cast<const char*>(a.zpage) + lane * 16;
+            if (go >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + row * WP * PIX + sg * 1024), 16, 0, AUX);
           }
       }
     };
-    if (nq > 0) issue(0);
-    if (nq > 1) issue(1);
+    const int D = NBUF - 1;  // bands in flight
+    for (int q = 0; q < D && q < nq; ++q) issue(q);
     for (int q = 0; q < nq; ++q) {
-      vm_wait_dyn(q + 1 < nq ? ni : 0);  // band q has landed; band q+1 may still be in flight
+      vm_wait_dyn(min(D - 1, nq - 1 - q) * ni);  // band q has landed; the bands issued after it may still be in flight
       __builtin_amdgcn_s_barrier();
-      if (q + 2 < nq) issue(q + 2);      // into the slot the compute waves finished before this barrier
+      if (q + D < nq) issue(q + D);      // into the slot the compute waves finished before this barrier
     }
     return;
   }
@@ -168,67 +190,90 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
                               : __builtin_bit_cast(bf16x8_t, make_uint4(0u, 0u, 0u, 0u));
     }
 
-  // this lane's output pixel within a band, the LDS offset of its window corner (slot 2*ox of row
+  // this lane's output pixel(s) within a band, the LDS offset of the window corner (slot 2*ox of row
   // 2*oyl) and, per tap column v, the chunk permutation of slot 2*ox + v folded with the lane's k half
-  const int r = wm * 32 + l32;
-  const bool in_band = r < TR * Wo;  // lanes beyond the band compute on pixel 0; never stored
-  const int oyl = in_band ? r / Wo : 0, ox = in_band ? r - oyl * Wo : 0;
-  const uint32_t abase = (uint32_t)(((2 * oyl) * WP + 2 * ox) * PIX);
-  uint32_t hx[3];
+  // (for 64 channels the permutation also depends on the image row pair: rows 2*oyl, 2*oyl + 1 for the taps
+  // u < 2, row 2*oyl + 2 for u = 2)
+  constexpr int NU = (CIN == 32) ? 1 : 2;
+  uint32_t abase[TM], hx[TM][NU][3];
 #pragma unroll
-  for (int v = 0; v < 3; ++v) hx[v] = (uint32_t)(h * 16) ^ tile_swz_bits<CIN>((uint32_t)((2 * ox + v) * PIX));
+  for (int i = 0; i < TM; ++i) {
+    const int r = (wm * TM + i) * 32 + l32;
+    const bool in_band = r < TR * Wo;  // lanes beyond the band compute on pixel 0; never stored
+    const int oyl = in_band ? r / Wo : 0, ox = in_band ? r - oyl * Wo : 0;
+    abase[i] = (uint32_t)(((2 * oyl) * WP + 2 * ox) * PIX);
+#pragma unroll
+    for (int u2 = 0; u2 < NU; ++u2)
+#pragma unroll
+      for (int v = 0; v < 3; ++v)
+        hx[i][u2][v] = (uint32_t)(h * 16) ^ fwd_swz_bits<CIN>((uint32_t)((2 * ox + v) * PIX), (uint32_t)(Wo * (oyl + u2)));
+  }
 
   // the first tile's barrier also orders the pad fill and the bias table before their first use
+  int slot = 0;
   for (int q = 0; q < nq; ++q) {
     const int t = vb + q * gridDim.x;
     __builtin_amdgcn_s_barrier();  // band q is in LDS
-    const char* img_s = lds + (q % NBUF) * image_bytes;
+    const char* img_s = lds + slot * image_bytes;
+    slot = slot + 1 == NBUF ? 0 : slot + 1;
 
-    f32x16_t acc[TN];  // starts at the bias of the lane's columns j*32 + g*8 + h*4 + 0..3
+    f32x16_t acc[TM][TN];  // starts at the bias of the lane's columns j*32 + g*8 + h*4 + 0..3
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const float4 bv = *reinterpret_cast<const float4*>(bias_s + wn * NW + j * 32 + g * 8 + h * 4);
-        acc[j][g * 4] = bv.x; acc[j][g * 4 + 1] = bv.y; acc[j][g * 4 + 2] = bv.z; acc[j][g * 4 + 3] = bv.w;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) { acc[i][j][g * 4] = bv.x; acc[i][j][g * 4 + 1] = bv.y; acc[i][j][g * 4 + 2] = bv.z; acc[i][j][g * 4 + 3] = bv.w; }
       }
+    // The operand reads run RD steps ahead of the MFMAs through a rotation of RD + 1 registers (step s = tap, 16-deep
+    // chunk cc, pixel group i): with one compute wave per SIMD nothing else hides the LDS latency, and left to
+    // itself the compiler keeps a single read in flight.  Logical chunk 2*cc + h of a slot sits at position
+    // (2*cc + h) ^ f(slot, row) = (32*cc) ^ hx in bytes.
+    constexpr int NS = 9 * KC * TM, RD = 3;
+    auto operand = [&](int s) {
+      const int i = s % TM, cc = (s / TM) % KC, tap = s / (TM * KC), u = tap / 3, v = tap - 3 * u;
+      return *reinterpret_cast<const bf16x8_t*>(img_s + abase[i] + (u * WP + v) * PIX + ((uint32_t)(cc * 32) ^ hx[i][(NU == 2 && u == 2) ? 1 : 0][v]));
+    };
+    bf16x8_t av[RD + 1];
 #pragma unroll
-    for (int u = 0; u < 3; ++u)
+    for (int s = 0; s < RD; ++s) av[s] = operand(s);
 #pragma unroll
-      for (int v = 0; v < 3; ++v) {
-        const char* ap = img_s + abase + (u * WP + v) * PIX;
+    for (int s = 0; s < NS; ++s) {
+      if (s + RD < NS) av[(s + RD) % (RD + 1)] = operand(s + RD);
+      const int i = s % TM;
 #pragma unroll
-        for (int cc = 0; cc < KC; ++cc) {
-          // logical chunk 2*cc + h sits at position (2*cc + h) ^ f(slot) = (32*cc) ^ hx[v] in bytes
-          const bf16x8_t av = *reinterpret_cast<const bf16x8_t*>(ap + ((uint32_t)(cc * 32) ^ hx[v]));
-#pragma unroll
-          for (int j = 0; j < TN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[(u * 3 + v) * KC + cc][j], av, acc[j], 0, 0, 0);
-        }
-      }
-    // ---- epilogue: bf16, ReLU; lane holds pixel l32 of the wave, columns j*32 + g*8 + h*4 + 0..3
-    uint32_t pw[TN];  // this lane's 16 sign bits of the pixel's 32-column group j
+      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[s / TM][j], av[s % (RD + 1)], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);  // keep the read of step s + RD in front of the MFMA of step s
+    }
+    // ---- epilogue: bf16, ReLU; lane holds pixel l32 of the wave's pixel group i, columns j*32 + g*8 + h*4 + 0..3
+    const int img = t / a.NB, band = t - img * a.NB;
+    const int b = img / a.V, vw = img - b * a.V;
+    const int rows_here = min(TR, a.Ho - band * TR);
+    const int plim = rows_here * Wo;  // pixels of the band that exist
+    bf16_t* dst = a.out + (int64_t)b * a.out_stride_b + (int64_t)vw * a.out_stride_v + (int64_t)band * TR * Wo * a.Cout;
     const uint32_t negw = nonzero_weights(h);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      pw[j] = 0u;
+    for (int i = 0; i < TM; ++i) {
+      const int p0 = (wm * TM + i) * 32;  // the group's first pixel (the strip is reused per group: a wave's LDS
+                                          // accesses are served in order)
+      uint32_t pw[TN];  // this lane's 16 sign bits of the pixel's 32-column group j
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int cl = j * 32 + g * 8 + h * 4;
-        uint2 o;
-        o.x = relu_pack2bf(acc[j][g * 4], acc[j][g * 4 + 1]);
-        o.y = relu_pack2bf(acc[j][g * 4 + 2], acc[j][g * 4 + 3]);
-        *reinterpret_cast<uint2*>(stage + (l32 * SP + cl) * 2) = o;
-        pw[j] |= nonzero4(o.x, o.y, negw) << (g * 8);
+      for (int j = 0; j < TN; ++j) {
+        pw[j] = 0u;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int cl = j * 32 + g * 8 + h * 4;
+          uint2 o;
+          o.x = relu_pack2bf(acc[i][j][g * 4], acc[i][j][g * 4 + 1]);
+          o.y = relu_pack2bf(acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]);
+          *reinterpret_cast<uint2*>(stage + (l32 * SP + cl) * 2) = o;
+          pw[j] |= nonzero4(o.x, o.y, negw) << (g * 8);
+        }
       }
-    }
-    {
-      const int img = t / a.NB, band = t - img * a.NB;
-      const int b = img / a.V, vw = img - b * a.V;
-      const int rows_here = min(TR, a.Ho - band * TR);
-      const int plim = rows_here * Wo;  // pixels of the band that exist
       if (a.bits) {
         // the other half of the columns sits in lane ^ 32; lanes 0..31 write the pixel's words
-        const int wpp = (a.Cout + 31) >> 5, p = wm * 32 + l32;
+        const int wpp = (a.Cout + 31) >> 5, p = p0 + l32;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const uint32_t word = or_with_lane_xor32(pw[j]);
@@ -237,12 +282,11 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
             a.bits[((int64_t)img * a.Ho * Wo + (int64_t)band * TR * Wo + p) * wpp + wi] = word;
         }
       }
-      bf16_t* dst = a.out + (int64_t)b * a.out_stride_b + (int64_t)vw * a.out_stride_v + (int64_t)band * TR * Wo * a.Cout;
       constexpr int CPRO = NW / 8;  // 16-byte chunks per staged row
 #pragma unroll
-      for (int i = 0; i < 32 * CPRO / 64; ++i) {
-        const int ch = lane + 64 * i, rl = ch / CPRO, cg = ch - rl * CPRO;
-        const int p = wm * 32 + rl, n = n0 + cg * 8;
+      for (int e = 0; e < 32 * CPRO / 64; ++e) {
+        const int ch = lane + 64 * e, rl = ch / CPRO, cg = ch - rl * CPRO;
+        const int p = p0 + rl, n = n0 + cg * 8;
         if (p < plim && n < a.Cout)
           store_stream16(dst + (int64_t)p * a.Cout + n, *reinterpret_cast<const uint4*>(stage + (rl * SP + cg * 8) * 2));
       }
@@ -255,7 +299,7 @@ __global__ __launch_bounds__(512) void k_conv_fwd_tile(ConvTileArgs a) {
 // k = (u*3+v)*CIN + ci, with the same organisation.  A tile is (image, band of TR output rows); the
 // loader waves copy the band's input rows (LDS image as above) and the band's dY pixels (64 output
 // channels of this block, 128 bytes per pixel, NSTEP*16 pixels with zeros beyond the band) into a
-// ring of three buffers.  The contraction runs over pixels, 16 per MFMA step; both operands are
+// ring of nbuf buffers (three, or more where they fit: small bands need more of them in flight).  The contraction runs over pixels, 16 per MFMA step; both operands are
 // read through ds_read_b64_tr_b16 (lane r of a 16-lane group supplies 4 consecutive channels of
 // pixel r/4, lane i receives channel i of 4 pixels), the im2col being the per-lane pixel address.
 // Compute wave w owns the 32-wide k-tiles w, w+4, ... of both 32-row n-tiles; the accumulators live
@@ -272,16 +316,17 @@ struct ConvWgradArgs {
   float* bias_partial;        // [gridDim.x][Cout]
   int H, W, Ho, Wo, Cout;
   int TR, NB, ntiles, nstep;  // output rows per band, bands per image, nimg * NB, ceil(TR*Wo / 16)
+  int nbuf;                   // ring buffers (3 .. MAXBUF)
 };
 
 template <int CIN>
 struct ConvWgradShape {
   static constexpr int PIX = CIN * 2, KT = 9 * CIN / 32, KTW = (KT + 3) / 4;
-  static constexpr int MAXSEG = 6, MAXSTEP = (CIN == 32) ? 8 : 4, NBUF = 3, THREADS = 512;
+  static constexpr int MAXSEG = 6, MAXSTEP = (CIN == 32) ? 8 : 4, MAXBUF = 6, THREADS = 512;
   static_assert(3 + 4 * (KTW - 1) >= KT, "wave 3's last accumulator pair must be free for the bias sums");
   static int image_bytes(int W, int TR) { return (2 * TR + 1) * (W + 2) * PIX; }
   static int buf_bytes(int W, int TR, int nstep) { return image_bytes(W, TR) + nstep * 16 * 128; }
-  static int lds_bytes(int W, int TR, int nstep) { return NBUF * buf_bytes(W, TR, nstep) + 4 * 64 * 4; }
+  static int lds_bytes(int W, int TR, int nstep, int nbuf) { return nbuf * buf_bytes(W, TR, nstep) + 4 * 64 * 4; }
 };
 
 __device__ __forceinline__ bf16x8_t lds_read_tr8_2(const char* p_lo, const char* p_hi) {
@@ -295,10 +340,10 @@ __device__ __forceinline__ bf16x8_t lds_read_tr8_2(const char* p_lo, const char*
 template <int CIN>
 __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
   typedef ConvWgradShape<CIN> S;
-  constexpr int PIX = S::PIX, KT = S::KT, KTW = S::KTW, NBUF = S::NBUF, MAXSTEP = S::MAXSTEP;
+  constexpr int PIX = S::PIX, KT = S::KT, KTW = S::KTW, MAXSTEP = S::MAXSTEP;
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int W = a.W, WP = W + 2, TR = a.TR, Wo = a.Wo, nstep = a.nstep;
+  const int W = a.W, WP = W + 2, TR = a.TR, Wo = a.Wo, nstep = a.nstep, NBUF = a.nbuf;
   const int nrows = 2 * TR + 1, rowbytes = W * PIX, segs = (rowbytes + 1023) >> 10;
   const int image_bytes = nrows * WP * PIX, dy_bytes = nstep * 16 * 128, buf_bytes = image_bytes + dy_bytes;
   const int vb = xcd_block((int)blockIdx.x, (int)gridDim.x);  // this block's number in the dealing of tiles
@@ -323,6 +368,7 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
       const uint32_t phys = PIX + sg * 1024 + lane * 16, logi = phys ^ tile_swz_bits<CIN>(phys);
       xgoff[sg] = (sg < segs && (int)phys < (W + 1) * PIX) ? (int)logi - PIX : -1;
     }
+    int slot = 0;  // ring buffer the next issued band goes to
     auto issue = [&](int q) {
       const int t = vb + q * gridDim.x;
       const int img = t / a.NB, band = t - img * a.NB;
@@ -330,7 +376,8 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
       const char* xsrc = reinterpret_cast<const char*>(a.in.ptr_uniform(img)) + (int64_t)iy_lo * rowbytes;
       const int plim = min(TR, a.Ho - band * TR) * Wo;  // pixels of the band that exist
       const bf16_t* dsrc = a.dy.ptr_uniform(img) + (int64_t)band * TR * Wo * a.Cout + nb0;
-      char* buf = lds + (q % NBUF) * buf_bytes;
+      char* buf = lds + slot * buf_bytes;
+      slot = slot + 1 == NBUF ? 0 : slot + 1;
       const char* zp = reinterpret_cast<const char*>(a.zpage) + lane * 16;
       for (int row = lw; row < nrows; row += 4) {
         const int iy = iy_lo + row;
@@ -350,12 +397,12 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
         __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(buf + image_bytes + j * 1024), 16, 0, LOAD_NT);
       }
     };
-    if (nq > 0) issue(0);
-    if (nq > 1) issue(1);
+    const int D = NBUF - 1;  // bands in flight
+    for (int q = 0; q < D && q < nq; ++q) issue(q);
     for (int q = 0; q < nq; ++q) {
-      vm_wait_dyn(q + 1 < nq ? ni : 0);
+      vm_wait_dyn(min(D - 1, nq - 1 - q) * ni);  // band q has landed; the bands issued after it may still be in flight
       __builtin_amdgcn_s_barrier();
-      if (q + 2 < nq) issue(q + 2);
+      if (q + D < nq) issue(q + D);
     }
     __builtin_amdgcn_s_barrier();  // pairs with the compute waves' barrier before the bias reduction
     return;
@@ -397,9 +444,11 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
     tapc[t] = (uint32_t)((u * WP + v) * PIX); tapv2[t] = v == 2; taphi[t] = (CIN == 64) && (kt & 1);
   }
 
+  int slot = 0;
   for (int q = 0; q < nq; ++q) {
     __builtin_amdgcn_s_barrier();  // band q is in LDS (the first one also orders the pad fill)
-    const char* buf = lds + (q % NBUF) * buf_bytes;
+    const char* buf = lds + slot * buf_bytes;
+    slot = slot + 1 == NBUF ? 0 : slot + 1;
 #pragma unroll
     for (int s = 0; s < MAXSTEP; ++s) {
       if (s < nstep) {

@@ -222,13 +222,20 @@ struct MapDgrad {
   }
 };
 // out[off + n] = f(acc): optional bias, ReLU, and ReLU-derivative mask read from `mask` at the
-// output's own offset (the stored activation whose gradient is being formed).
+// output's own offset (the stored activation whose gradient is being formed).  With `mbits` set the
+// mask comes from the sign-bit words the forward kernel left instead (one bit per element, a
+// sixteenth of the bytes): bit (off + n) of the bit string; the output must then be dense.
 template <class MAP, typename OutT, bool BIAS, bool RELU, bool MASK>
 struct Ep {
   typedef OutT out_t;
   static constexpr bool kBias = BIAS, kRelu = RELU, kMask = MASK;
   MAP map; OutT* out; const float* bias; const bf16_t* mask; int N;
+  const uint32_t* mbits = nullptr;
 };
+// all-ones halves of a bf16 pair for the set bits among bits (2d, 2d + 1) of b
+__device__ __forceinline__ uint32_t keep_halves(uint32_t b, int d) {
+  return ((b >> (2 * d)) & 1u ? 0x0000ffffu : 0u) | ((b >> (2 * d + 1)) & 1u ? 0xffff0000u : 0u);
+}
 
 // Epilogue shared by the tile kernels.  acc[i][j][g*4+q] = C[m][n] with m = m0 + (wm*TM+i)*32 +
 // lane%32, n = n0 + (wn*TN+j)*32 + g*8 + (lane/32)*4 + q.  bf16 results are packed four at a
@@ -270,7 +277,11 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[TM][TN], const EP&
       const int64_t off = rowoff[rl];
       if (off < 0 || n >= N || n >= rowcols[rl]) continue;
       uint4 v = *reinterpret_cast<const uint4*>(&stage[rl * SP + cg * 8]);
-      if (EP::kMask) {
+      if (EP::kMask && ep.mbits) {
+        const int64_t bi = off + n;  // a multiple of 8
+        const uint32_t b = (ep.mbits[bi >> 5] >> (bi & 31)) & 0xffu;
+        v.x &= keep_halves(b, 0); v.y &= keep_halves(b, 1); v.z &= keep_halves(b, 2); v.w &= keep_halves(b, 3);
+      } else if (EP::kMask) {
         // keep a half where the stored activation is > 0 (sign bit clear and not zero)
         const uint4 mk = *reinterpret_cast<const uint4*>(ep.mask + off + n);
         auto keep = [](uint32_t m) -> uint32_t {

@@ -654,17 +654,20 @@ ImgAddr conv_out_addr(Ctx* c, int l, const bf16_t* contiguous, const bf16_t* str
 
 // Forward convolution through the LDS-image kernel; returns 1 when the layer's shape is not one
 // it covers (the caller then takes the implicit-GEMM path).
-template <int CIN>
-int launch_conv_fwd_tile_t(Ctx* c, const ConvTileArgs& a, const std::string& name, double flops, double abytes) {
-  typedef ConvTileShape<CIN> S;
+template <int CIN, int WIDE>
+int launch_conv_fwd_tile_t(Ctx* c, ConvTileArgs a, const std::string& name, double flops, double abytes) {
+  typedef ConvTileShape<CIN, WIDE> S;
   const int segs = cdiv(a.W * S::PIX, 1024), ni = cdiv(2 * a.TR + 1, 4) * segs;  // loads per loader wave per band
-  const int lds = S::lds_bytes(a.W, a.TR);
+  // as many ring images as fit: a loader wave has (nbuf - 2) * ni loads outstanding behind the band it waits for
+  a.nbuf = S::MAXBUF;
+  while (a.nbuf > 3 && (S::lds_bytes(a.W, a.TR, a.nbuf) > 160 * 1024 || (a.nbuf - 2) * ni > 63)) --a.nbuf;
+  const int lds = S::lds_bytes(a.W, a.TR, a.nbuf);
   if (segs > S::MAXSEG || ni > 63 || lds > 160 * 1024) return 1;
   const int gy = cdiv(a.Cout, S::BN);
   int gx = 256 / gy; if (gx > a.ntiles) gx = a.ntiles; if (gx < 1) gx = 1;
   // bands of four or more output rows share at most an eighth of their input rows with a neighbour: read once, non-temporal
   const bool nt = a.TR >= 4;
-  auto kfn = nt ? k_conv_fwd_tile<CIN, LOAD_NT> : k_conv_fwd_tile<CIN, 0>;
+  auto kfn = nt ? k_conv_fwd_tile<CIN, LOAD_NT, WIDE> : k_conv_fwd_tile<CIN, 0, WIDE>;
   static uint64_t attr_devs[2] = {0, 0};  // bit d: set on device d
   if (!((attr_devs[nt] >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_devs[nt] |= 1ull << c->dev; }
   ProfScope ps(c, name, flops, abytes);
@@ -683,9 +686,11 @@ int launch_conv_fwd_tile(Ctx* c, const AConvFwd& al, const ImgAddr& o, int Cout,
   a.w = w; a.bias = bias; a.zpage = c->zpage; a.bits = bits; a.V = o.V; a.H = al.H; a.W = al.W; a.Ho = al.Ho; a.Wo = al.Wo; a.Cout = Cout;
   const int trmax = BM / al.Wo < al.Ho ? BM / al.Wo : al.Ho;
   a.NB = cdiv(al.Ho, trmax); a.TR = cdiv(al.Ho, a.NB);  // balanced bands
-  a.ntiles = nimg * a.NB;
+  a.ntiles = nimg * a.NB; a.nbuf = 3;
   const double flops = 2.0 * (double)al.M * Cout * al.K;
-  return al.Cin == 32 ? launch_conv_fwd_tile_t<32>(c, a, name, flops, abytes) : launch_conv_fwd_tile_t<64>(c, a, name, flops, abytes);
+  if (al.Cin == 32) return launch_conv_fwd_tile_t<32, 0>(c, a, name, flops, abytes);
+  // more than 64 output channels: the 64 x 128 form reads the input once
+  return Cout > 64 ? launch_conv_fwd_tile_t<64, 1>(c, a, name, flops, abytes) : launch_conv_fwd_tile_t<64, 0>(c, a, name, flops, abytes);
 }
 
 // Weight (and bias) gradient of conv layer with 32 or 64 input channels through the LDS-image
@@ -696,13 +701,15 @@ int launch_conv_wgrad_tile_t(Ctx* c, ConvWgradArgs a, float* gw, float* gb, bool
   // largest band that fits the pixel-step table and three ring buffers, then balanced over the image
   int TR = 0;
   for (int tr = a.Ho; tr >= 1; --tr)
-    if (tr * a.Wo <= 16 * S::MAXSTEP && S::lds_bytes(a.W, tr, cdiv(tr * a.Wo, 16)) <= 158 * 1024) { TR = tr; break; }
+    if (tr * a.Wo <= 16 * S::MAXSTEP && S::lds_bytes(a.W, tr, cdiv(tr * a.Wo, 16), 3) <= 158 * 1024) { TR = tr; break; }
   if (TR == 0) return 1;
   a.NB = cdiv(a.Ho, TR); a.TR = cdiv(a.Ho, a.NB); a.nstep = cdiv(a.TR * a.Wo, 16);
   const int nimg = a.ntiles;  // passed in as the image count
   a.ntiles = nimg * a.NB;
-  const int segs = cdiv(a.W * S::PIX, 1024);
-  if (segs > S::MAXSEG || cdiv(2 * a.TR + 1, 4) * segs + cdiv(a.nstep * 2, 4) > 63) return 1;
+  const int segs = cdiv(a.W * S::PIX, 1024), ni = cdiv(2 * a.TR + 1, 4) * segs + cdiv(a.nstep * 2, 4);  // loads per loader wave per band
+  if (segs > S::MAXSEG || ni > 63) return 1;
+  a.nbuf = S::MAXBUF;  // as many ring buffers as fit (the balanced band may be smaller than the largest that fits three)
+  while (a.nbuf > 3 && (S::lds_bytes(a.W, a.TR, a.nstep, a.nbuf) > 158 * 1024 || (a.nbuf - 2) * ni > 63)) --a.nbuf;
   const int gy = cdiv(a.Cout, 64), K = 9 * CIN;
   int gx = 256 / gy; if (gx > a.ntiles) gx = a.ntiles; if (gx < 1) gx = 1;
   const int64_t per = (int64_t)a.Cout * K;
@@ -711,7 +718,7 @@ int launch_conv_wgrad_tile_t(Ctx* c, ConvWgradArgs a, float* gw, float* gb, bool
   if (gb && (int64_t)gx * a.Cout > c->bias_partial_elems) gx = (int)(c->bias_partial_elems / a.Cout);
   if (gx < 1) return 1;
   a.partial = c->partial; a.bias_partial = gb ? c->bias_partial : nullptr;
-  const int lds = S::lds_bytes(a.W, a.TR, a.nstep);
+  const int lds = S::lds_bytes(a.W, a.TR, a.nstep, a.nbuf);
   auto kfn = k_conv_wgrad_tile<CIN>;
   static uint64_t attr_devs = 0;  /* bit d: set on device d */
   if (!((attr_devs >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_devs |= 1ull << c->dev; }
@@ -728,7 +735,7 @@ int launch_conv_wgrad_tile(Ctx* c, const ImgAddr& dy, const AConvFwd& xl, int Co
   if ((xl.Cin != 32 && xl.Cin != 64) || Cout % 8 || nimg < 1 || xl.in.idx || dy.idx) return 1;
   ConvWgradArgs a;
   a.in = xl.in; a.in.prepare(); a.dy = dy; a.dy.prepare(); a.zpage = c->zpage; a.partial = nullptr; a.bias_partial = nullptr;
-  a.H = xl.H; a.W = xl.W; a.Ho = xl.Ho; a.Wo = xl.Wo; a.Cout = Cout; a.TR = 0; a.NB = 0; a.nstep = 0;
+  a.H = xl.H; a.W = xl.W; a.Ho = xl.Ho; a.Wo = xl.Wo; a.Cout = Cout; a.TR = 0; a.NB = 0; a.nstep = 0; a.nbuf = 3;
   a.ntiles = nimg;  // image count; the template turns it into tiles
   const double flops = 2.0 * (double)xl.M * Cout * xl.K;
   return xl.Cin == 32 ? launch_conv_wgrad_tile_t<32>(c, a, gw, gb, accumulate, name, flops, abytes)
@@ -1062,6 +1069,8 @@ int encoder_backward_ff(Ctx* c, const int32_t* idx, int n, bool acc, int cur) {
     Ep<MapDgrad, bf16_t, false, false, true> ep;
     ep.map.stride_b = xa.stride_b; ep.map.stride_v = xa.stride_v; ep.map.V = V; ep.map.H = H; ep.map.W = W; ep.map.Cin = Ci; ep.map.imgs = nimg;
     ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = xa.base; ep.N = 2 * Ci;
+    const bool dense_in = xa.stride_v == (int64_t)H * W * Ci && xa.stride_b == (int64_t)V * H * W * Ci;
+    if (c->abits_ok[l - 1] && Ci % 32 == 0 && dense_in) ep.mbits = c->abits[l - 1];  // bit index = element offset of the dense activation
     const double pix = (double)nimg * H * W;
     const int N2 = 2 * Ci, BNf = N2 > 64 ? 128 : (N2 > 32 ? 64 : 32);
     const size_t wlds = (size_t)6 * Co * BNf * sizeof(bf16_t);  // both parities' packed weights, resident in LDS
@@ -1103,7 +1112,7 @@ int encoder_backward_ff(Ctx* c, const int32_t* idx, int n, bool acc, int cur) {
       defer_reduce(c, 2, grid, npair, Ci, K0, c->g + c->convW[0], c->g + c->convB[0], acc, false, 0, nullptr);
       return flush_reduces(c);
     }
-    double ab = 2.0 * ((double)nimg * Ho * Wo * Co + pix * Ci + 9.0 * Ci * Co) + (c->abits_ok[l - 1] && Co == 64 ? pix * Ci / 8.0 : 2.0 * pix * Ci);
+    double ab = 2.0 * ((double)nimg * Ho * Wo * Co + pix * Ci + 9.0 * Ci * Co) + (c->abits_ok[l - 1] && (Co == 64 || ep.mbits) ? pix * Ci / 8.0 : 2.0 * pix * Ci);
     const double dflops = 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co;
     rc = launch_conv_dgrad_tile(c, dy, xa, c->abits_ok[l - 1] ? c->abits[l - 1] : nullptr, c->gbuf[cur ^ 1], c->wtap[l], Co, Ci, H, W, Ho, Wo, nimg, "conv_dgrad." + std::to_string(l), dflops, ab);
     if (rc == PPO_OK + 1) {
@@ -1309,6 +1318,8 @@ int encoder_backward_seq(Ctx* c, const int32_t* idx, int n, bool acc, const bf16
     Ep<MapDgrad, bf16_t, false, false, true> ep;
     ep.map.stride_b = xa.stride_b; ep.map.stride_v = xa.stride_v; ep.map.V = V; ep.map.H = H; ep.map.W = W; ep.map.Cin = Ci; ep.map.imgs = nimg;
     ep.out = c->gbuf[cur ^ 1]; ep.bias = nullptr; ep.mask = xa.base; ep.N = 2 * Ci;
+    const bool dense_in = xa.stride_v == (int64_t)H * W * Ci && xa.stride_b == (int64_t)V * H * W * Ci;
+    if (c->abits_ok[l - 1] && Ci % 32 == 0 && dense_in) ep.mbits = c->abits[l - 1];  // bit index = element offset of the dense activation
     const double pix = (double)nimg * H * W;
     rc = launch_gemm(c, al, M0, nullptr, 0, 2 * Ci, 4 * Co, ep, "conv_dgrad." + std::to_string(l),
                      2.0 * ((double)nimg * Ho * Wo * Co + 2.0 * pix * Ci + 9.0 * Ci * Co), 2, 2.0 * (double)nimg * Ho * Wo * 9.0 * Ci * Co);
