@@ -337,13 +337,15 @@ __device__ __forceinline__ bf16x8_t lds_read_tr8_2(const char* p_lo, const char*
   return __builtin_bit_cast(bf16x8_t, v);
 }
 
-template <int CIN>
+// NS > 0: the number of pixel steps per band is NS (known when the kernel is compiled), which lets the tile loop run
+// without a branch and its operand reads ahead of the MFMAs; NS = 0: any number of steps up to MAXSTEP.
+template <int CIN, int NS = 0>
 __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
   typedef ConvWgradShape<CIN> S;
   constexpr int PIX = S::PIX, KT = S::KT, KTW = S::KTW, MAXSTEP = S::MAXSTEP;
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int W = a.W, WP = W + 2, TR = a.TR, Wo = a.Wo, nstep = a.nstep, NBUF = a.nbuf;
+  const int W = a.W, WP = W + 2, TR = a.TR, Wo = a.Wo, nstep = NS ? NS : a.nstep, NBUF = a.nbuf;
   const int nrows = 2 * TR + 1, rowbytes = W * PIX, segs = (rowbytes + 1023) >> 10;
   const int image_bytes = nrows * WP * PIX, dy_bytes = nstep * 16 * 128, buf_bytes = image_bytes + dy_bytes;
   const int vb = xcd_block((int)blockIdx.x, (int)gridDim.x);  // this block's number in the dealing of tiles
@@ -440,7 +442,9 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
   uint32_t tapc[KTW]; bool tapv2[KTW], taphi[KTW];
 #pragma unroll
   for (int t = 0; t < KTW; ++t) {
-    const int kt = wave + 4 * t, tap = kt / (CIN / 32), u = tap / 3, v = tap - 3 * u;
+    // (a wave without a k-tile for t = KTW-1 reads its first one again where the loop has no branch: the product
+    // lands in an accumulator that is never stored, or is replaced by the bias operand)
+    const int kt = (wave + 4 * t < KT) ? wave + 4 * t : wave, tap = kt / (CIN / 32), u = tap / 3, v = tap - 3 * u;
     tapc[t] = (uint32_t)((u * WP + v) * PIX); tapv2[t] = v == 2; taphi[t] = (CIN == 64) && (kt & 1);
   }
 
@@ -449,6 +453,43 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
     __builtin_amdgcn_s_barrier();  // band q is in LDS (the first one also orders the pad fill)
     const char* buf = lds + slot * buf_bytes;
     slot = slot + 1 == NBUF ? 0 : slot + 1;
+    if constexpr (NS > 0) {
+      // The operand reads run ahead of the MFMAs (the window operand RD k-tiles, the dY operand a whole pixel
+      // step): with one compute wave per SIMD nothing else hides the LDS latency, and left to itself the compiler
+      // waits for each read right where it is used.  No branch inside: every wave runs KTW k-tiles per step.
+      constexpr int NU = NS * KTW, RD = 2;
+      bf16x8_t aq[2][2], bq[RD + 1];
+      const uint32_t bias_sel = (wave == 3) ? 0xffffffffu : 0u;  // wave 3's last k-tile is the bias column
+      auto read_a = [&](int s_) __attribute__((always_inline)) {
+        aq[s_ & 1][0] = lds_read_tr8_2(buf + db[s_][0], buf + db[s_][1]);
+        aq[s_ & 1][1] = lds_read_tr8_2(buf + (db[s_][0] ^ 64u), buf + (db[s_][1] ^ 64u));
+      };
+      auto read_b = [&](int u) __attribute__((always_inline)) {
+        const int s_ = u / KTW, t_ = u % KTW;
+        uint32_t o0 = tapv2[t_] ? xb[s_][0][1] : xb[s_][0][0], o1 = tapv2[t_] ? xb[s_][1][1] : xb[s_][1][0];
+        const uint32_t hi = taphi[t_] ? 64u : 0u;
+        o0 ^= hi; o1 ^= hi;
+        bq[u % (RD + 1)] = lds_read_tr8_2(buf + o0 + tapc[t_], buf + o1 + tapc[t_]);
+      };
+      read_a(0);
+#pragma unroll
+      for (int u = 0; u < RD && u < NU; ++u) read_b(u);
+#pragma unroll
+      for (int u = 0; u < NU; ++u) {
+        const int s_ = u / KTW, t = u % KTW;
+        if (t == 0 && s_ + 1 < NS) read_a(s_ + 1);
+        if (u + RD < NU) read_b(u + RD);
+        bf16x8_t bop = bq[u % (RD + 1)];
+        if (t == KTW - 1) {
+          const uint4 bu = __builtin_bit_cast(uint4, bop), on = __builtin_bit_cast(uint4, ones);
+          bop = __builtin_bit_cast(bf16x8_t, make_uint4((bu.x & ~bias_sel) | (on.x & bias_sel), (bu.y & ~bias_sel) | (on.y & bias_sel),
+                                                         (bu.z & ~bias_sel) | (on.z & bias_sel), (bu.w & ~bias_sel) | (on.w & bias_sel)));
+        }
+        acc[t][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[s_ & 1][0], bop, acc[t][0], 0, 0, 0);
+        acc[t][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[s_ & 1][1], bop, acc[t][1], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);  // keep the reads in front of the MFMAs they run ahead of
+      }
+    } else {
 #pragma unroll
     for (int s = 0; s < MAXSTEP; ++s) {
       if (s < nstep) {
@@ -469,6 +510,7 @@ __global__ __launch_bounds__(512) void k_conv_wgrad_tile(ConvWgradArgs a) {
           acc[KTW - 1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, ones, acc[KTW - 1][1], 0, 0, 0);
         }
       }
+    }
     }
   }
   // ---- this block's partial sums: acc[t][i][e] = G[n][k], k = (wave+4t)*32 + lane%32, n = nb0 + i*32 + (e/4)*8 + (lane/32)*4 + e%4.
