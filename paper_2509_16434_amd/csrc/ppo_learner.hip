@@ -1221,6 +1221,12 @@ int encoder_forward_generic(Ctx* c, const int32_t* idx, int n, int64_t first) {
     c->abits_ok[l] = false;
     if (c->ln) {
       ProfScope ps(c, "layer_norm_fwd", 8.0 * (double)nimg * e, 4.0 * (double)nimg * e);
+      // an image that fits one block's registers is read once
+      const int64_t pch = cdiv(e / 8, LN_RTHREADS);  // 16-byte chunks per thread
+      if (pch <= 2 && Co <= 512) hipLaunchKernelGGL(k_ln_fwd_reg<2>, dim3(nimg), dim3(LN_RTHREADS), 0, c->stream, c->pre[l], (int)e, Co, c->p + c->lnG[l], c->p + c->lnB[l], as_w(oa), c->lnstat[l]);
+      else if (pch <= 5 && Co <= 512) hipLaunchKernelGGL(k_ln_fwd_reg<5>, dim3(nimg), dim3(LN_RTHREADS), 0, c->stream, c->pre[l], (int)e, Co, c->p + c->lnG[l], c->p + c->lnB[l], as_w(oa), c->lnstat[l]);
+      else if (pch <= 10 && Co <= 512) hipLaunchKernelGGL(k_ln_fwd_reg<10>, dim3(nimg), dim3(LN_RTHREADS), 0, c->stream, c->pre[l], (int)e, Co, c->p + c->lnG[l], c->p + c->lnB[l], as_w(oa), c->lnstat[l]);
+      else
       hipLaunchKernelGGL(k_ln_fwd, dim3(nimg), dim3(LN_THREADS), 0, c->stream, c->pre[l], (int)e, Co, c->p + c->lnG[l], c->p + c->lnB[l], as_w(oa), c->lnstat[l]);
       LAUNCHCHK(c, "k_ln_fwd");
     }

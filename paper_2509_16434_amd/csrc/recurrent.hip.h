@@ -136,6 +136,54 @@ __global__ __launch_bounds__(LN_THREADS) void k_ln_bwd(ImgAddr dy, const bf16_t*
   }
 }
 
+// The forward kernel for images that fit the registers of one 1024-thread block (NCH 16-byte chunks per thread,
+// m <= 8192 * NCH): every element is read once instead of three times.  (The backward pass would need both tensors
+// in registers, which sixteen waves per block do not have for the larger layers.)
+#define LN_RTHREADS 1024
+template <int NCH>
+__global__ __launch_bounds__(LN_RTHREADS) void k_ln_fwd_reg(const bf16_t* __restrict__ x, int m, int C, const float* __restrict__ gain,
+                                                            const float* __restrict__ shift, ImgAddrW out, float2* __restrict__ stats) {
+  __shared__ float red[LN_RTHREADS / 64 + 1];
+  const int img = blockIdx.x, tid = threadIdx.x, nch = m >> 3;
+  const uint4* xi = reinterpret_cast<const uint4*>(x + (int64_t)img * m);
+  uint4 v[NCH];
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int k = tid + j * LN_RTHREADS;
+    v[j] = k < nch ? xi[k] : make_uint4(0u, 0u, 0u, 0u);
+    float f[8]; unpack8(v[j], f);
+    s += ((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7]));
+  }
+  const float mean = ln_block_sum(s, red) / (float)m;
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < NCH; ++j)
+    if (tid + j * LN_RTHREADS < nch) {
+      float f[8]; unpack8(v[j], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const float d = f[e] - mean; q += d * d; }
+    }
+  const float rstd = rsqrtf(ln_block_sum(q, red) / (float)m + LN_EPS);
+  if (tid == 0) stats[img] = make_float2(mean, rstd);
+  const int c0 = (tid * 8) & (C - 1);  // the same for all of a thread's chunks: 8 * LN_RTHREADS is a multiple of C
+  float g[8], b[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { g[e] = gain[c0 + e] * rstd; b[e] = shift[c0 + e] - mean * g[e]; }
+  uint4* yo = reinterpret_cast<uint4*>(out.ptr(img));
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int k = tid + j * LN_RTHREADS;
+    if (k < nch) {
+      float f[8]; unpack8(v[j], f);
+      float y[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) y[e] = fmaxf(f[e] * g[e] + b[e], 0.f);
+      yo[k] = make_uint4(pack2bf(y[0], y[1]), pack2bf(y[2], y[3]), pack2bf(y[4], y[5]), pack2bf(y[6], y[7]));
+    }
+  }
+}
+
 // State that enters the first step of the chunk's environments: h (as bf16, into the h columns of row block 0 of
 // the layer's input matrix xh [rows][ld], columns [col_h, col_h + H)) and c (fp32, c_enter row block 0), gathered
 // from the per-environment initial states h0 / c0 [N][H] of this layer.
