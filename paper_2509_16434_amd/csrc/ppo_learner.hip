@@ -23,6 +23,7 @@
 #include "conv_tile.hip.h"
 #include "conv_dgrad_tile.hip.h"
 #include "conv_dgrad_wgrad0_tile.hip.h"
+#include "conv_dgrad_k2_tile.hip.h"
 #include "conv0_tile.hip.h"
 #include "head_loss.hip.h"
 #include "wgrad_rs.hip.h"
@@ -798,8 +799,33 @@ ConvDgradArgs conv_dgrad_args(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, cons
   a.H0 = 0; a.W0 = 0; a.partial0 = nullptr;
   return a;
 }
+// The form for 128 gradient channels and 64 result channels (the contraction split over two pairs of compute waves).
+int launch_conv_dgrad_k2_tile(Ctx* c, ConvDgradArgs a, int nimg, const std::string& name, double flops, double abytes) {
+  typedef ConvDgradK2Shape S;
+  if (a.Wo > S::BQ) return 1;
+  auto fits = [&](int tq) { return S::stage_bytes(a.W, tq) <= S::MAXCH * S::NFT * 16 && S::lds_bytes(a.W, a.Wo, tq) <= 158 * 1024; };
+  int TQ = S::BQ / a.Wo < a.Ho ? S::BQ / a.Wo : a.Ho;
+  while (TQ > 1 && !fits(TQ)) --TQ;
+  if (!fits(TQ)) return 1;
+  a.NB = cdiv(a.Ho, TQ); TQ = cdiv(a.Ho, a.NB);  // balanced bands (fewer, larger tiles beat fuller ones: the cost of a tile is mostly fixed)
+  a.TQ = TQ; a.NB = cdiv(a.Ho, TQ); a.ntiles = nimg * a.NB;
+  const int segs = cdiv(a.Wo * S::PB, 1024);
+  if (segs > S::MAXSEG || (a.TQ + 1) * segs > 63) return 1;
+  const int gx = a.ntiles < 256 ? a.ntiles : 256;
+  auto kfn = k_conv_dgrad_k2_tile;
+  static uint64_t attr_devs = 0;  /* bit d: set on device d */
+  if (!((attr_devs >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_devs |= 1ull << c->dev; }
+  ProfScope ps(c, name, flops, abytes);
+  hipLaunchKernelGGL(kfn, dim3(gx), dim3(S::THREADS), S::lds_bytes(a.W, a.Wo, a.TQ), c->stream, a);
+  LAUNCHCHK(c, "k_conv_dgrad_k2_tile");
+  return PPO_OK;
+}
 int launch_conv_dgrad_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, const uint32_t* xbits, bf16_t* dx, const bf16_t* wt, int Co, int Ci, int H, int W, int Ho, int Wo,
                            int nimg, const std::string& name, double flops, double abytes) {
+  if (Co == 128 && Ci == 64 && !dy.idx && nimg >= 1 && xbits) {
+    ConvDgradArgs a2 = conv_dgrad_args(c, dy, xa, xbits, dx, wt, H, W, Ho, Wo);
+    return launch_conv_dgrad_k2_tile(c, a2, nimg, name, flops, abytes);
+  }
   if (Co != 64 || (Ci != 32 && Ci != 64) || dy.idx || nimg < 1 || !xbits) return 1;
   ConvDgradArgs a = conv_dgrad_args(c, dy, xa, xbits, dx, wt, H, W, Ho, Wo);
   return Ci == 32 ? launch_conv_dgrad_tile_t<32, 0>(c, a, nimg, name, flops, abytes, nullptr)
