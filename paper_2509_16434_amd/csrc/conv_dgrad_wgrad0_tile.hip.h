@@ -42,7 +42,7 @@ struct ConvDgradW0Shape {
   static int dyimg_bytes(int Wo, int TQ) { return (TQ + 1) * (Wo + 1) * 128; }
   static int img0_bytes(int W0, int C0, int TQ) { return (4 * TQ + 1) * W0 * C0 * 2; }
   static int mask_bytes(int W, int TQ) { return 2 * TQ * W * 4; }
-  static int slot_bytes(int W, int Wo, int W0, int C0, int TQ) { return dyimg_bytes(Wo, TQ) + img0_bytes(W0, C0, TQ) + 16 + mask_bytes(W, TQ) + 32; }
+  static int slot_bytes(int W, int Wo, int W0, int C0, int TQ) { return dyimg_bytes(Wo, TQ) + img0_bytes(W0, C0, TQ) + 16 + mask_bytes(W, TQ) + W * 4 + 32; }
   static int ring_bytes(int W, int Wo, int W0, int C0, int TQ) {
     const int r = NBUF * slot_bytes(W, Wo, W0, C0, TQ);
     return r > NCW * 2048 ? r : NCW * 2048;  // the final sums of the wave pairs reuse the ring
@@ -55,19 +55,20 @@ struct ConvDgradW0Shape {
 };
 
 // Requires (checked by the host): W % 8 == 0 (Wo % 4 == 0), (W0 * C0 * 2) % 16 == 0, Wo == W / 2 <= BQ, TQ * Wo <= BQ.
-template <int C0, int NCW>
+// WC: the width W of the result known at compile time (row pitches become instruction offsets), or 0: taken from a.W.
+template <int C0, int NCW, int WC>
 __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvDgradArgs a) {
   typedef ConvDgradW0Shape<NCW> S;
   constexpr int BQ = S::BQ;
   constexpr int NBUF = S::NBUF, K0 = 9 * C0, NV = K0 + 1, NT = (NV + 15) / 16;
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int W = a.W, Wo = a.Wo, TQ = a.TQ;
+  const int W = WC ? WC : a.W, Wo = WC ? WC / 2 : a.Wo, TQ = a.TQ;
   const int RP = (Wo + 1) * 128, dyimg_bytes = (TQ + 1) * RP;  // dY image: row pitch, bytes
-  const int RB0 = a.W0 * C0 * 2, img0_bytes = (4 * TQ + 1) * RB0;
+  const int RB0 = (WC ? 2 * WC : a.W0) * C0 * 2, img0_bytes = (4 * TQ + 1) * RB0;
   const int MRB = W * 4, mask_bytes = 2 * TQ * MRB;
-  // slot: dY image | image rows | 16 zero bytes | mask words | 32 zero bytes
-  const int OFF_IMG = dyimg_bytes, OFF_MSK = OFF_IMG + img0_bytes + 16, OFF_Z = OFF_MSK + mask_bytes, SLOT = OFF_Z + 32;
+  // slot: dY image | image rows | 16 zero bytes | mask words | one row of mask words + 32 bytes of zeros
+  const int OFF_IMG = dyimg_bytes, OFF_MSK = OFF_IMG + img0_bytes + 16, OFF_Z = OFF_MSK + mask_bytes, SLOT = OFF_Z + MRB + 32;
   const int vb = xcd_block((int)blockIdx.x, (int)gridDim.x);  // this block's number in the dealing of tiles
   const int nq = (a.ntiles > vb) ? (a.ntiles - 1 - vb) / (int)gridDim.x + 1 : 0;
 
@@ -76,9 +77,12 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     const int chunk = i & 7, row = i >> 3, s = row / (TQ + 1), rr = row - s * (TQ + 1);
     *reinterpret_cast<uint4*>(lds + s * SLOT + rr * RP + Wo * 128 + chunk * 16) = make_uint4(0u, 0u, 0u, 0u);
   }
-  if (tid < NBUF * 3) {
-    const int s = tid / 3, k = tid - 3 * s, off = k == 0 ? OFF_IMG + img0_bytes : OFF_Z + (k - 1) * 16;
-    *reinterpret_cast<uint4*>(lds + s * SLOT + off) = make_uint4(0u, 0u, 0u, 0u);
+  {
+    const int nz = 1 + (MRB + 32) / 16;  // 16-byte pieces of zeros per slot: one behind the image rows, the tail behind the mask words
+    for (int i = tid; i < NBUF * nz; i += S::THREADS) {
+      const int s = i / nz, k = i - nz * s, off = k == 0 ? OFF_IMG + img0_bytes : OFF_Z + (k - 1) * 16;
+      *reinterpret_cast<uint4*>(lds + s * SLOT + off) = make_uint4(0u, 0u, 0u, 0u);
+    }
   }
 
   if (wave >= NCW) {
@@ -178,17 +182,18 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
       wr[s][ks] = *reinterpret_cast<const bf16x8_t*>(a.wt + ((int64_t)s * 32 + ch * 16 + l16) * 64 + ks * 32 + r * 8);
-  // first operand: lane (row = quad gp*64 + m*16 + l16, 8 co at ks*32 + r*8); the quad's place in a dY image
-  int dyoff[4];
-  uint32_t cx[4][2];
+  // first operand: lane (row = quad gp*64 + m*16 + l16, 8 co at ks*32 + r*8); xa[m][dxo]: this lane's chunk of the quad's
+  // pixel (+ dxo) in a dY image for ks = 0; the chunk for ks = 1 is at xa ^ 64 (rows and pixels are multiples of 128 bytes)
+  int xa[4][2];
 #pragma unroll
   for (int m = 0; m < 4; ++m) {
     const int qi = gp * 64 + m * 16 + l16;
     const bool valid = qi < TQ * Wo;  // lanes beyond the band work on quad 0; their results meet zero mask words
     const int al = valid ? qi / Wo : 0, b = valid ? qi - al * Wo : 0;
-    dyoff[m] = al * RP + b * 128;
 #pragma unroll
-    for (int dxo = 0; dxo < 2; ++dxo) cx[m][dxo] = (uint32_t)(r * 16) ^ dy_swz_bits((uint32_t)((b + dxo) * 128));
+    for (int dxo = 0; dxo < 2; ++dxo) xa[m][dxo] = al * RP + (b + dxo) * 128 + (int)((uint32_t)(r * 16) ^ dy_swz_bits((uint32_t)((b + dxo) * 128)));
+    // (opaque from here on: a sum the compiler can see through is split again into parts that cost an addition per read)
+    asm volatile("" : "+v"(xa[m][0]), "+v"(xa[m][1]));
   }
   const int cibit = ch * 16 + l16;  // this lane's channel as a result column: its bit in a mask word
   // second product, second operand: lane (column k0 = nt*16 + l16, pixels of lane group r)
@@ -203,23 +208,30 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     // is the high half of dword 2b + px - 1 (v = 0), the low (v = 1) or high (v = 2) half of dword 2b + px.
     toffl[nt] = C0 == 1 ? u * RB0 + (v == 0 ? -4 : 0) : u * RB0 + ((v - 1) * C0 + cch) * 2;
     hsel[nt] = !real ? 0x0c0c0c0cu : (v == 1 ? 0x05040100u : 0x07060302u);  // selector bytes 0x0c give zero
-    lnv0[nt] = v != 0 ? 0xffffffffu : 0u;
+    lnv0[nt] = v != 0 ? 0xfu : 0u;
     lmask[nt] = real ? 0xffffffffu : 0u;
     bconst[nt] = k0 == K0 ? 0x3F803F80u : 0u;  // the bias column: 1.0
   }
   // this lane's four quads of M-tile m are q0 .. q0 + 3, q0 = gp*64 + m*16 + r*4, neighbours in one quad row;
-  // groups beyond the band read the zero words behind the mask (both pixel rows) and any real window
-  int mo[4][2], go[4];
-  uint32_t kp[4];
+  // groups beyond the band read the zero words behind the mask (both pixel rows: the second is one row of mask
+  // words further) and any real window.  kpb[nt], bit m: the first window value of M-tile m is kept (it is dropped
+  // where it is the column left of the image: lanes of column 0 with a tap of the window's first column).
+  int mo[4], go[4];
+  uint32_t kpb[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) kpb[nt] = lnv0[nt];
 #pragma unroll
   for (int m = 0; m < 4; ++m) {
     const int q0 = gp * 64 + m * 16 + r * 4;
     const bool valid = q0 < TQ * Wo;
     const int al = valid ? q0 / Wo : 0, b = valid ? q0 - al * Wo : 0;
-    mo[m][0] = valid ? OFF_MSK + ((2 * al) * W + 2 * b) * 4 : OFF_Z;
-    mo[m][1] = valid ? mo[m][0] + MRB : OFF_Z;
-    go[m] = OFF_IMG + 4 * al * RB0 + 8 * b * C0;
-    kp[m] = (valid && b == 0) ? 0u : 0xffffffffu;  // the window column left of the image is dropped (lanes of column 0)
+    mo[m] = valid ? OFF_MSK + ((2 * al) * W + 2 * b) * 4 : OFF_Z;
+    go[m] = OFF_IMG + 4 * al * RB0 + 8 * b * C0 + (NT == 1 ? toffl[0] : 0);
+    if (!(valid && b == 0)) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) kpb[nt] |= 1u << m;
+    }
+    asm volatile("" : "+v"(mo[m]), "+v"(go[m]));
   }
   f32x4_t accw[NT];
 #pragma unroll
@@ -228,13 +240,12 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
   auto dgrad = [&](const char* slot, int m, f32x4_t (&acc)[4]) __attribute__((always_inline)) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    const char* base = slot + dyoff[m];
 #pragma unroll
     for (int pi = 0; pi < 4; ++pi) {
       const int dyo = pi >> 1, dxo = pi & 1;
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8_t x = *reinterpret_cast<const bf16x8_t*>(base + dyo * RP + dxo * 128 + ((uint32_t)(ks * 64) ^ cx[m][dxo]));
+        const bf16x8_t x = *reinterpret_cast<const bf16x8_t*>(slot + dyo * RP + (xa[m][dxo] ^ (ks * 64)));
         // class (py, px) takes tap row py ? (dyo ? 0 : 2) : 1 from row offset dyo (even rows only from dyo = 0), same for columns
         if (pi == 0) {
           acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, wr[1 * 3 + 1][ks], acc[0], 0, 0, 0);
@@ -258,7 +269,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
 #pragma unroll
     for (int py = 0; py < 2; ++py) {
       // the mask words of the four quads' eight pixels in this row: word 2*i + px
-      const uint4 wa = *reinterpret_cast<const uint4*>(slot + mo[m][py]), wb = *reinterpret_cast<const uint4*>(slot + mo[m][py] + 16);
+      const uint4 wa = *reinterpret_cast<const uint4*>(slot + mo[m] + py * MRB), wb = *reinterpret_cast<const uint4*>(slot + mo[m] + py * MRB + 16);
       const uint32_t w[8] = {wa.x, wa.y, wa.z, wa.w, wb.x, wb.y, wb.z, wb.w};
       float v0[4], v1[4];
 #pragma unroll
@@ -271,8 +282,8 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
       const bf16x8_t av = __builtin_bit_cast(bf16x8_t, make_uint4(pack2bf(v0[0], v0[1]), pack2bf(v0[2], v0[3]), pack2bf(v1[0], v1[1]), pack2bf(v1[2], v1[3])));
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        const char* p = slot + go[m] + toffl[nt] + 2 * py * RB0;
-        const uint32_t km = kp[m] | lnv0[nt];
+        const char* p = slot + go[m] + (NT == 1 ? 0 : toffl[nt]) + 2 * py * RB0;
+        const uint32_t km = (uint32_t)__builtin_amdgcn_sbfe((int)kpb[nt], (uint32_t)m, 1u);
         uint4 bq;
         if constexpr (C0 == 1) {
           uint32_t d[8];  // dword k = 2*i + px
@@ -298,6 +309,79 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     }
   };
 
+  // One-channel images: the first product of M-tile m + 1 and the second product of M-tile m as ONE instruction
+  // stream in a fixed order.  A SIMD issues vector instructions in the shadow of a running MFMA only when they
+  // stand next to it in the wave's stream; left to itself the scheduler puts the 18 MFMAs of the first product in
+  // a row and the ~70 vector instructions of the second behind them, and the two streams then take the sum of
+  // their times.  Here every MFMA of the first product is followed by four or five vector instructions of the
+  // second (mask bits, masking, conversion, window halves), and every LDS read is issued three to eight MFMAs
+  // before its first use.  The order of the additions into each accumulator is the one of dgrad() / wgrad().
+  auto fused = [&](const char* slot, int m, const f32x4_t (&cur)[4], f32x4_t (&nxt)[4]) __attribute__((always_inline)) {
+    auto xr = [&](int xi) __attribute__((always_inline)) {
+      const int pi = xi >> 1, ks = xi & 1, dyo = pi >> 1, dxo = pi & 1;
+      return *reinterpret_cast<const bf16x8_t*>(slot + dyo * RP + (xa[m + 1][dxo] ^ (ks * 64)));
+    };
+    bf16x8_t x[8];
+    uint32_t w[8], v[8], d[8];
+    uint4 bq;
+    auto masks = [&](int py, int half) __attribute__((always_inline)) {  // words 4*half .. 4*half + 3 of the row
+      const uint4 wa = *reinterpret_cast<const uint4*>(slot + mo[m] + py * MRB + 16 * half);
+      w[4 * half + 0] = wa.x; w[4 * half + 1] = wa.y; w[4 * half + 2] = wa.z; w[4 * half + 3] = wa.w;
+    };
+    auto window = [&](int py) __attribute__((always_inline)) {
+      const char* p = slot + go[m] + 2 * py * RB0;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) d[k] = *reinterpret_cast<const uint32_t*>(p + 4 * k);
+    };
+    // word e = 2*i + px belongs to value i of class (py, px); the operand takes the values of px = 0 first
+    auto keep2 = [&](int py, int e0) __attribute__((always_inline)) {
+#pragma unroll
+      for (int e = e0; e < e0 + 2; ++e)
+        v[e] = (uint32_t)__float_as_int(cur[py * 2 + (e & 1)][e >> 1]) & (uint32_t)__builtin_amdgcn_sbfe((int)w[e], (uint32_t)cibit, 1u);
+    };
+    uint4 aq;
+    auto conv_lo = [&]() __attribute__((always_inline)) {
+      aq.x = pack2bf(__int_as_float((int)v[0]), __int_as_float((int)v[2])); aq.z = pack2bf(__int_as_float((int)v[1]), __int_as_float((int)v[3]));
+    };
+    auto conv_hi = [&]() __attribute__((always_inline)) {
+      aq.y = pack2bf(__int_as_float((int)v[4]), __int_as_float((int)v[6])); aq.w = pack2bf(__int_as_float((int)v[5]), __int_as_float((int)v[7]));
+    };
+    auto halves = [&]() __attribute__((always_inline)) {
+      d[0] &= (uint32_t)__builtin_amdgcn_sbfe((int)kpb[0], (uint32_t)m, 1u);
+      bq = make_uint4(__builtin_amdgcn_perm(d[2], d[0], hsel[0]), __builtin_amdgcn_perm(d[6], d[4], hsel[0]),
+                      __builtin_amdgcn_perm(d[3], d[1], hsel[0]), __builtin_amdgcn_perm(d[7], d[5], hsel[0]));
+    };
+    auto ones = [&]() __attribute__((always_inline)) { bq.x |= bconst[0]; bq.y |= bconst[0]; bq.z |= bconst[0]; bq.w |= bconst[0]; };
+    auto second = [&]() __attribute__((always_inline)) { accw[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aq), __builtin_bit_cast(bf16x8_t, bq), accw[0], 0, 0, 0); };
+#define DW0_MF(c, xi, s, ks) nxt[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[xi], wr[s][ks], nxt[c], 0, 0, 0)
+#define DW0_FENCE() __builtin_amdgcn_sched_barrier(0)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) nxt[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    masks(0, 0); x[0] = xr(0); DW0_FENCE();
+    DW0_MF(0, 0, 4, 0); keep2(0, 0); masks(0, 1); DW0_FENCE();
+    DW0_MF(1, 0, 5, 0); keep2(0, 2); conv_lo(); x[1] = xr(1); DW0_FENCE();
+    DW0_MF(2, 0, 7, 0); keep2(0, 4); window(0); DW0_FENCE();
+    DW0_MF(3, 0, 8, 0); keep2(0, 6); conv_hi(); DW0_FENCE();
+    DW0_MF(0, 1, 4, 1); masks(1, 0); DW0_FENCE();
+    DW0_MF(1, 1, 5, 1); halves(); DW0_FENCE();
+    DW0_MF(2, 1, 7, 1); ones(); x[2] = xr(2); DW0_FENCE();
+    DW0_MF(3, 1, 8, 1); masks(1, 1); DW0_FENCE();
+    second(); x[3] = xr(3); DW0_FENCE();
+    DW0_MF(1, 2, 3, 0); keep2(1, 0); DW0_FENCE();
+    DW0_MF(3, 2, 6, 0); keep2(1, 2); conv_lo(); DW0_FENCE();
+    DW0_MF(1, 3, 3, 1); keep2(1, 4); window(1); x[4] = xr(4); DW0_FENCE();
+    DW0_MF(3, 3, 6, 1); keep2(1, 6); conv_hi(); DW0_FENCE();
+    DW0_MF(2, 4, 1, 0); x[5] = xr(5); DW0_FENCE();
+    DW0_MF(3, 4, 2, 0); halves(); DW0_FENCE();
+    DW0_MF(2, 5, 1, 1); ones(); x[6] = xr(6); DW0_FENCE();
+    second(); x[7] = xr(7); DW0_FENCE();
+    DW0_MF(3, 5, 2, 1); DW0_FENCE();
+    DW0_MF(3, 6, 0, 0);
+    DW0_MF(3, 7, 0, 1); DW0_FENCE();
+#undef DW0_MF
+#undef DW0_FENCE
+  };
+
   for (int q = 0; q < nq; ++q) {
     __builtin_amdgcn_s_barrier();  // A(q): band q is in LDS (the first one also orders the zero pads)
     const char* slot = lds + (q % NBUF) * SLOT;
@@ -306,8 +390,13 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     dgrad(slot, 0, acc[0]);
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
-      if (m + 1 < 4) dgrad(slot, m + 1, acc[(m + 1) & 1]);
-      wgrad(slot, m, acc[m & 1]);
+      if constexpr (C0 == 1) {
+        if (m + 1 < 4) fused(slot, m, acc[m & 1], acc[(m + 1) & 1]);
+        else wgrad(slot, m, acc[m & 1]);
+      } else {
+        if (m + 1 < 4) dgrad(slot, m + 1, acc[(m + 1) & 1]);
+        wgrad(slot, m, acc[m & 1]);
+      }
     }
   }
   __builtin_amdgcn_s_barrier();    // C: nobody reads the ring any more

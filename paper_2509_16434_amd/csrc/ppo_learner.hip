@@ -832,9 +832,10 @@ int launch_conv_dgrad_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, const u
                   : launch_conv_dgrad_tile_t<64, 0>(c, a, nimg, name, flops, abytes, nullptr);
 }
 // Register-fused form of the same pair of layers (conv_dgrad_wgrad0_tile.hip.h); returns 1 when the shape is not covered.
-template <int C0, int NCW>
+template <int C0, int NCW, int WC = 0>
 int launch_conv_dgrad_wgrad0_reg_t(Ctx* c, ConvDgradArgs a, int nimg, const std::string& name, double flops, double abytes, int* grid_out) {
   typedef ConvDgradW0Shape<NCW> S;
+  if (WC && a.W != WC) return 1;
   const int rb0 = a.W0 * C0 * 2;
   if (a.W % 8 || rb0 % 16 || a.Wo * 2 != a.W || a.Wo > S::BQ || a.H != (a.H0 + 1) / 2 || a.W * 2 != a.W0) return 1;
   auto fits = [&](int tq) {
@@ -852,7 +853,7 @@ int launch_conv_dgrad_wgrad0_reg_t(Ctx* c, ConvDgradArgs a, int nimg, const std:
   if (gx < 1) return 1;
   a.partial0 = c->partial;
   *grid_out = gx;
-  auto kfn = k_conv_dgrad_wgrad0_tile<C0, NCW>;
+  auto kfn = k_conv_dgrad_wgrad0_tile<C0, NCW, WC>;
   static uint64_t attr_devs = 0;  /* bit d: set on device d */
   if (!((attr_devs >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_devs |= 1ull << c->dev; }
   ProfScope ps(c, name, flops, abytes);
@@ -867,8 +868,11 @@ int launch_conv_dgrad_wgrad0_tile(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, 
   ConvDgradArgs a = conv_dgrad_args(c, dy, xa, xbits, nullptr, wt, H, W, Ho, Wo);
   a.img0 = img0; a.img0.prepare(); a.H0 = H0; a.W0 = W0;
   // eight compute waves (two per SIMD) when the larger tile fits, else four
-  int rrc = C0 == 1 ? launch_conv_dgrad_wgrad0_reg_t<1, 8>(c, a, nimg, name, flops, abytes, grid_out)
-                    : launch_conv_dgrad_wgrad0_reg_t<3, 8>(c, a, nimg, name, flops, abytes, grid_out);
+  // (the 80-wide result of 120x160 depth images has a form of its own with the row pitches known at compile time)
+  int rrc = C0 == 1 ? launch_conv_dgrad_wgrad0_reg_t<1, 8, 80>(c, a, nimg, name, flops, abytes, grid_out) : 1;
+  if (rrc == 1)
+    rrc = C0 == 1 ? launch_conv_dgrad_wgrad0_reg_t<1, 8>(c, a, nimg, name, flops, abytes, grid_out)
+                  : launch_conv_dgrad_wgrad0_reg_t<3, 8>(c, a, nimg, name, flops, abytes, grid_out);
   if (rrc == 1)
     rrc = C0 == 1 ? launch_conv_dgrad_wgrad0_reg_t<1, 4>(c, a, nimg, name, flops, abytes, grid_out)
                   : launch_conv_dgrad_wgrad0_reg_t<3, 4>(c, a, nimg, name, flops, abytes, grid_out);
