@@ -42,7 +42,7 @@ struct ConvDgradW0Shape {
   static int dyimg_bytes(int Wo, int TQ) { return (TQ + 1) * (Wo + 1) * 128; }
   static int img0_bytes(int W0, int C0, int TQ) { return (4 * TQ + 1) * W0 * C0 * 2; }
   static int mask_bytes(int W, int TQ) { return 2 * TQ * W * 4; }
-  static int slot_bytes(int W, int Wo, int W0, int C0, int TQ) { return dyimg_bytes(Wo, TQ) + img0_bytes(W0, C0, TQ) + 16 + mask_bytes(W, TQ) + W * 4 + 32; }
+  static int slot_bytes(int W, int Wo, int W0, int C0, int TQ) { return dyimg_bytes(Wo, TQ) + img0_bytes(W0, C0, TQ) + 16 + mask_bytes(W, TQ) + W * 4 + 32 + (C0 == 1 ? 4 * W0 + 32 : 0); }
   static int ring_bytes(int W, int Wo, int W0, int C0, int TQ) {
     const int r = NBUF * slot_bytes(W, Wo, W0, C0, TQ);
     return r > NCW * 2048 ? r : NCW * 2048;  // the final sums of the wave pairs reuse the ring
@@ -67,8 +67,10 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
   const int RP = (Wo + 1) * 128, dyimg_bytes = (TQ + 1) * RP;  // dY image: row pitch, bytes
   const int RB0 = (WC ? 2 * WC : a.W0) * C0 * 2, img0_bytes = (4 * TQ + 1) * RB0;
   const int MRB = W * 4, mask_bytes = 2 * TQ * MRB;
-  // slot: dY image | image rows | 16 zero bytes | mask words | one row of mask words + 32 bytes of zeros
-  const int OFF_IMG = dyimg_bytes, OFF_MSK = OFF_IMG + img0_bytes + 16, OFF_Z = OFF_MSK + mask_bytes, SLOT = OFF_Z + MRB + 32;
+  // slot: dY image | image rows | 16 zero bytes | mask words | one row of mask words + 32 bytes of zeros |
+  // one-channel images: 32 bytes of bf16 ones, and 32 more two image rows further (the window of the bias column)
+  const int OFF_IMG = dyimg_bytes, OFF_MSK = OFF_IMG + img0_bytes + 16, OFF_Z = OFF_MSK + mask_bytes, OFF_ONES = OFF_Z + MRB + 32;
+  const int SLOT = OFF_ONES + (C0 == 1 ? 2 * RB0 + 32 : 0);
   const int vb = xcd_block((int)blockIdx.x, (int)gridDim.x);  // this block's number in the dealing of tiles
   const int nq = (a.ntiles > vb) ? (a.ntiles - 1 - vb) / (int)gridDim.x + 1 : 0;
 
@@ -82,6 +84,10 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     for (int i = tid; i < NBUF * nz; i += S::THREADS) {
       const int s = i / nz, k = i - nz * s, off = k == 0 ? OFF_IMG + img0_bytes : OFF_Z + (k - 1) * 16;
       *reinterpret_cast<uint4*>(lds + s * SLOT + off) = make_uint4(0u, 0u, 0u, 0u);
+    }
+    if (C0 == 1 && tid < NBUF * 4) {
+      const int s = tid >> 2, k = tid & 3;
+      *reinterpret_cast<uint4*>(lds + s * SLOT + OFF_ONES + (k >> 1) * 2 * RB0 + (k & 1) * 16) = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
     }
   }
 
@@ -207,7 +213,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     // window corner is (row - 1, column - 1).  One-channel images are read as dwords: column 4b + 2px + v - 1
     // is the high half of dword 2b + px - 1 (v = 0), the low (v = 1) or high (v = 2) half of dword 2b + px.
     toffl[nt] = C0 == 1 ? u * RB0 + (v == 0 ? -4 : 0) : u * RB0 + ((v - 1) * C0 + cch) * 2;
-    hsel[nt] = !real ? 0x0c0c0c0cu : (v == 1 ? 0x05040100u : 0x07060302u);  // selector bytes 0x0c give zero
+    hsel[nt] = (!real && !(C0 == 1 && k0 == K0)) ? 0x0c0c0c0cu : (v == 1 ? 0x05040100u : 0x07060302u);  // selector bytes 0x0c give zero
     lnv0[nt] = v != 0 ? 0xfu : 0u;
     lmask[nt] = real ? 0xffffffffu : 0u;
     bconst[nt] = k0 == K0 ? 0x3F803F80u : 0u;  // the bias column: 1.0
@@ -227,6 +233,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     const int al = valid ? q0 / Wo : 0, b = valid ? q0 - al * Wo : 0;
     mo[m] = valid ? OFF_MSK + ((2 * al) * W + 2 * b) * 4 : OFF_Z;
     go[m] = OFF_IMG + 4 * al * RB0 + 8 * b * C0 + (NT == 1 ? toffl[0] : 0);
+    if (C0 == 1 && l16 == K0) go[m] = OFF_ONES;  // the bias column of one-channel images reads ones
     if (!(valid && b == 0)) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) kpb[nt] |= 1u << m;
@@ -303,7 +310,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
           bq = make_uint4(x0[0] | (x0[1] << 16), x0[2] | (x0[3] << 16), x1[0] | (x1[1] << 16), x1[2] | (x1[3] << 16));
         }
         if constexpr (C0 != 1) { bq.x &= lmask[nt]; bq.y &= lmask[nt]; bq.z &= lmask[nt]; bq.w &= lmask[nt]; }
-        bq.x |= bconst[nt]; bq.y |= bconst[nt]; bq.z |= bconst[nt]; bq.w |= bconst[nt];
+        if constexpr (C0 != 1) { bq.x |= bconst[nt]; bq.y |= bconst[nt]; bq.z |= bconst[nt]; bq.w |= bconst[nt]; }
         accw[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8_t, bq), accw[nt], 0, 0, 0);
       }
     }
@@ -351,7 +358,6 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
       bq = make_uint4(__builtin_amdgcn_perm(d[2], d[0], hsel[0]), __builtin_amdgcn_perm(d[6], d[4], hsel[0]),
                       __builtin_amdgcn_perm(d[3], d[1], hsel[0]), __builtin_amdgcn_perm(d[7], d[5], hsel[0]));
     };
-    auto ones = [&]() __attribute__((always_inline)) { bq.x |= bconst[0]; bq.y |= bconst[0]; bq.z |= bconst[0]; bq.w |= bconst[0]; };
     auto second = [&]() __attribute__((always_inline)) { accw[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aq), __builtin_bit_cast(bf16x8_t, bq), accw[0], 0, 0, 0); };
 #define DW0_MF(c, xi, s, ks) nxt[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[xi], wr[s][ks], nxt[c], 0, 0, 0)
 #define DW0_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -364,7 +370,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     DW0_MF(3, 0, 8, 0); keep2(0, 6); conv_hi(); DW0_FENCE();
     DW0_MF(0, 1, 4, 1); masks(1, 0); DW0_FENCE();
     DW0_MF(1, 1, 5, 1); halves(); DW0_FENCE();
-    DW0_MF(2, 1, 7, 1); ones(); x[2] = xr(2); DW0_FENCE();
+    DW0_MF(2, 1, 7, 1); x[2] = xr(2); DW0_FENCE();
     DW0_MF(3, 1, 8, 1); masks(1, 1); DW0_FENCE();
     second(); x[3] = xr(3); DW0_FENCE();
     DW0_MF(1, 2, 3, 0); keep2(1, 0); DW0_FENCE();
@@ -373,7 +379,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     DW0_MF(3, 3, 6, 1); keep2(1, 6); conv_hi(); DW0_FENCE();
     DW0_MF(2, 4, 1, 0); x[5] = xr(5); DW0_FENCE();
     DW0_MF(3, 4, 2, 0); halves(); DW0_FENCE();
-    DW0_MF(2, 5, 1, 1); ones(); x[6] = xr(6); DW0_FENCE();
+    DW0_MF(2, 5, 1, 1); x[6] = xr(6); DW0_FENCE();
     second(); x[7] = xr(7); DW0_FENCE();
     DW0_MF(3, 5, 2, 1); DW0_FENCE();
     DW0_MF(3, 6, 0, 0);
