@@ -38,7 +38,7 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 template <int NCW>  // compute waves: 4 or 8
 struct ConvDgradW0Shape {
   static constexpr int CI = 32, CO = 64, BQ = 32 * NCW, NBUF = 3, NLW = 4, THREADS = (NCW + NLW) * 64;
-  static constexpr int MAXD = 12, MAXI = 4, MAXM = 2;  // 1 KiB loads per loader wave and band: dY, image rows, mask words
+  static constexpr int MAXSEG = 8, MAXI = 4, MAXM = 2;  // 1 KiB parts of a dY row; loads per loader wave and band: image rows, mask words
   static int dyimg_bytes(int Wo, int TQ) { return (TQ + 1) * (Wo + 1) * 128; }
   static int img0_bytes(int W0, int C0, int TQ) { return (4 * TQ + 1) * W0 * C0 * 2; }
   static int mask_bytes(int W, int TQ) { return 2 * TQ * W * 4; }
@@ -49,7 +49,8 @@ struct ConvDgradW0Shape {
   }
   static int lds_bytes(int W, int Wo, int W0, int C0, int TQ) { return ring_bytes(W, Wo, W0, C0, TQ); }
   static bool loads_fit(int W, int Wo, int W0, int C0, int TQ) {
-    return (TQ + 1) * ((Wo * 128 + 1023) / 1024) <= MAXD * NLW && (img0_bytes(W0, C0, TQ) + 1023) / 1024 <= MAXI * NLW &&
+    const int segs = (Wo * 128 + 1023) / 1024;
+    return segs <= MAXSEG && ((TQ + 1 + NLW - 1) / NLW) * segs + MAXI + MAXM <= 63 && (img0_bytes(W0, C0, TQ) + 1023) / 1024 <= MAXI * NLW &&
            (mask_bytes(W, TQ) + 1023) / 1024 <= MAXM * NLW;
   }
 };
@@ -95,26 +96,27 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     // ------------------------------------------------------------------ loaders: piece i of a band belongs to loader i % 4
     const int lw = wave - NCW;
     const int rowbytes = Wo * 128, segs = (rowbytes + 1023) >> 10;
-    const int n_dy = (TQ + 1) * segs, n_im = (img0_bytes + 1023) >> 10, n_mk = (mask_bytes + 1023) >> 10;
-    // piece j of a kind (dY row parts, 1 KiB pieces of the image rows, of the mask words) belongs to loader j % 4
+    const int n_im = (img0_bytes + 1023) >> 10, n_mk = (mask_bytes + 1023) >> 10;
+    // piece j of a kind (rows of the dY image, 1 KiB pieces of the image rows, of the mask words) belongs to loader j % 4
     auto mine = [&](int n) { return n > lw ? (n - lw + S::NLW - 1) / S::NLW : 0; };
-    const int nd = mine(n_dy), nm_i = mine(n_im), nm_m = mine(n_mk);
+    const int nd = mine(TQ + 1) * segs, nm_i = mine(n_im), nm_m = mine(n_mk);
     const int ni = nd + nm_i + nm_m;  // this wave's loads per band
     const char* const zp = reinterpret_cast<const char*>(a.zpage) + lane * 16;
-    // The pieces of a band are the same for every band; what differs is three base addresses and
-    // three row bounds.  Each piece is described once - LDS offset in the slot, this lane's source
-    // offset from the kind's base (-1: lane idle), the row it belongs to (for the test against the
-    // image's rows) - so that issuing a band is a short straight run per load.
-    constexpr int MAXD = S::MAXD, MAXI = S::MAXI, MAXM = S::MAXM;
-    int ddst[MAXD], drow[MAXD], dgo[MAXD], igo[MAXI], irow[MAXI], mgo[MAXM], mrow[MAXM];
+    // dY rows are copied whole, in parts of 1 KiB: what a lane adds to the row's address depends on the part alone
+    // (the 16-byte chunks of a pixel are permuted, dy_swz_bits, through the source address), and a row is inside
+    // the image or not for the whole wave, so that the choice between the image and the page of zeros (a.zpage:
+    // 64 KiB) and every other address part is scalar work: one vector instruction per load.  The lanes beyond
+    // the end of a row whose last part is shorter than 1 KiB sit out.
+    constexpr int MAXSEG = S::MAXSEG, MAXI = S::MAXI, MAXM = S::MAXM;
+    int lo[MAXSEG], igo[MAXI], irow[MAXI], mgo[MAXM], mrow[MAXM];
 #pragma unroll
-    for (int k = 0; k < MAXD; ++k) {
-      // a dY row part; the 16-byte chunks of a pixel are permuted (dy_swz_bits) through the source address
-      const int i = lw + S::NLW * k, row = i / segs, sg = i - row * segs;
-      const uint32_t phys = sg * 1024 + lane * 16, logi = phys ^ dy_swz_bits(phys);
-      ddst[k] = row * RP + sg * 1024; drow[k] = row;
-      dgo[k] = (int)phys < rowbytes ? row * rowbytes + (int)logi : -1;
+    for (int sg = 0; sg < MAXSEG; ++sg) {
+      const uint32_t phys = sg * 1024 + lane * 16;
+      lo[sg] = (int)(phys ^ dy_swz_bits(phys));
     }
+    const int tail = rowbytes - (segs - 1) * 1024;
+    const bool in_tail = lane * 16 < tail;
+    const char* const zbase = reinterpret_cast<const char*>(a.zpage);
 #pragma unroll
     for (int k = 0; k < MAXI; ++k) {
       const int o = (lw + S::NLW * k) * 1024 + lane * 16;
@@ -147,12 +149,21 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
       const Band b = nxt;
       if (q + 1 < nq) nxt = prep();
       char* const slot = lds + (q % NBUF) * SLOT;
+      const int nrows = a.Ho - b.r0[0];  // rows of the image from the band's first one on
+      for (int row = lw; row <= TQ; row += S::NLW) {
+        const char* const base = row < nrows ? b.base[0] + row * rowbytes : zbase;  // rows outside the image: zeros
+        char* const dst = slot + row * RP;
 #pragma unroll
-      for (int k = 0; k < MAXD; ++k)
-        if (k < nd) {
-          const char* p = (b.r0[0] + drow[k] < a.Ho) ? b.base[0] + dgo[k] : zp;  // rows outside the image: zeros
-          if (dgo[k] >= 0) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(slot + ddst[k]), 16, 0, LOAD_NT);
-        }
+        for (int sg = 0; sg < MAXSEG; ++sg)
+          if (sg < segs) {
+            const char* p = base + lo[sg];
+            if (sg == segs - 1 && tail < 1024) {
+              if (in_tail) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + sg * 1024), 16, 0, LOAD_NT);
+            } else {
+              __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + sg * 1024), 16, 0, LOAD_NT);
+            }
+          }
+      }
 #pragma unroll
       for (int k = 0; k < MAXI; ++k)
         if (k < nm_i) {

@@ -138,7 +138,7 @@ struct Ctx {
   bf16_t* dhead = nullptr;        // [CH][32]
   bf16_t* gbuf[2] = {nullptr, nullptr};
   float *partial = nullptr, *bias_partial = nullptr;
-  bf16_t* zpage = nullptr;  // 1 KiB of zeros: source of out-of-range operand fetches
+  bf16_t* zpage = nullptr;  // 64 KiB of zeros: source of out-of-range operand fetches (most kernels use its first KiB)
   // partial / bias_partial are cursors into the two workspaces and *_elems what is left behind them:
   // every weight-gradient kernel of a backward pass takes its partials from the cursor and queues its
   // reduction (defer_reduce); flush_reduces sums them all in one launch and rewinds the cursors
@@ -839,7 +839,8 @@ int launch_conv_dgrad_wgrad0_reg_t(Ctx* c, ConvDgradArgs a, int nimg, const std:
   const int rb0 = a.W0 * C0 * 2;
   if (a.W % 8 || rb0 % 16 || a.Wo * 2 != a.W || a.Wo > S::BQ || a.H != (a.H0 + 1) / 2 || a.W * 2 != a.W0) return 1;
   auto fits = [&](int tq) {
-    return tq * a.Wo <= S::BQ && S::lds_bytes(a.W, a.Wo, a.W0, C0, tq) <= 158 * 1024 && S::loads_fit(a.W, a.Wo, a.W0, C0, tq);
+    return tq * a.Wo <= S::BQ && S::lds_bytes(a.W, a.Wo, a.W0, C0, tq) <= 158 * 1024 && S::loads_fit(a.W, a.Wo, a.W0, C0, tq) &&
+           S::dyimg_bytes(a.Wo, tq) <= 65536;  // offsets into the page of zeros
   };
   int TQ = S::BQ / a.Wo < a.Ho ? S::BQ / a.Wo : a.Ho;
   while (TQ > 1 && !fits(TQ)) --TQ;
@@ -1756,8 +1757,8 @@ int create_impl(Ctx* c) {
   c->partial = c->partial_base; c->partial_elems = c->partial_cap;
   c->bias_partial = c->bias_partial_base; c->bias_partial_elems = c->bias_partial_cap;
   c->rjobs.njobs = 0; c->rjob_blocks = 0;
-  DALLOC(c, c->zpage, 512);
-  HIPCHK(c, hipMemsetAsync(c->zpage, 0, 1024, c->stream));
+  DALLOC(c, c->zpage, 32768);
+  HIPCHK(c, hipMemsetAsync(c->zpage, 0, 65536, c->stream));
   // loss / Adam partials
   {
     const int CU = c->nl > 0 ? c->CHe : CH, Lr = c->nl > 0 ? c->T : 1;
@@ -2208,8 +2209,8 @@ int ppo_diag_gemm(int32_t M, int32_t N, int32_t K, const float* h_a, const float
   auto body = [&]() -> int {
     DALLOC(c, da, (int64_t)M * K); DALLOC(c, db, (int64_t)N * K); DALLOC(c, dc, (int64_t)M * N);
     DALLOC(c, ba, (int64_t)M * K); DALLOC(c, bb, (int64_t)N * K);
-    DALLOC(c, c->zpage, 512);
-    HIPCHK(c, hipMemset(c->zpage, 0, 1024));
+    DALLOC(c, c->zpage, 32768);
+    HIPCHK(c, hipMemset(c->zpage, 0, 65536));
     HIPCHK(c, hipMemcpy(da, h_a, sizeof(float) * (size_t)M * K, hipMemcpyHostToDevice));
     HIPCHK(c, hipMemcpy(db, h_b, sizeof(float) * (size_t)N * K, hipMemcpyHostToDevice));
     hipLaunchKernelGGL(k_cast_bf16, dim3(cdiv((int64_t)M * K, 256)), dim3(256), 0, c->stream, da, ba, (int64_t)M * K);
