@@ -47,6 +47,7 @@ struct ConvDgradArgs {
   ImgAddr img0;               // the first layer's input images [H0][W0][C0] (gathered through idx)
   int H0, W0;
   float* partial0;            // [gridDim.x][CI][9*C0 + 1]
+  int seg_split;              // register-fused form: the loader waves share the parts of every dY row (1) or take whole rows in turn (0)
   FastDiv dv_rb0, dv_mrow;    // division by the bytes of an input-image row / of a row of mask words (register-fused form)
 };
 

@@ -38,19 +38,28 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 template <int NCW>  // compute waves: 4 or 8
 struct ConvDgradW0Shape {
   static constexpr int CI = 32, CO = 64, BQ = 32 * NCW, NBUF = 3, NLW = 4, THREADS = (NCW + NLW) * 64;
-  static constexpr int MAXSEG = 8, MAXI = 4, MAXM = 2;  // 1 KiB parts of a dY row; loads per loader wave and band: image rows, mask words
+  static constexpr int MAXSEG = 24, MAXI = 4, MAXM = 2;  // 1 KiB parts of a dY row; loads per loader wave and band: image rows, mask words
   static int dyimg_bytes(int Wo, int TQ) { return (TQ + 1) * (Wo + 1) * 128; }
   static int img0_bytes(int W0, int C0, int TQ) { return (4 * TQ + 1) * W0 * C0 * 2; }
   static int mask_bytes(int W, int TQ) { return 2 * TQ * W * 4; }
-  static int slot_bytes(int W, int Wo, int W0, int C0, int TQ) { return dyimg_bytes(Wo, TQ) + img0_bytes(W0, C0, TQ) + 16 + mask_bytes(W, TQ) + W * 4 + 32 + (C0 == 1 ? 4 * W0 + 32 : 0); }
-  static int ring_bytes(int W, int Wo, int W0, int C0, int TQ) {
-    const int r = NBUF * slot_bytes(W, Wo, W0, C0, TQ);
+  // ones: the slot ends with the block of bf16 ones of the forms whose width is known at compile time (one-channel images)
+  static int slot_bytes(int W, int Wo, int W0, int C0, int TQ, bool ones) {
+    return dyimg_bytes(Wo, TQ) + img0_bytes(W0, C0, TQ) + 16 + mask_bytes(W, TQ) + W * 4 + 32 + (ones ? 4 * W0 * C0 + 32 : 0);
+  }
+  static int ring_bytes(int W, int Wo, int W0, int C0, int TQ, bool ones) {
+    const int r = NBUF * slot_bytes(W, Wo, W0, C0, TQ, ones);
     return r > NCW * 2048 ? r : NCW * 2048;  // the final sums of the wave pairs reuse the ring
   }
-  static int lds_bytes(int W, int Wo, int W0, int C0, int TQ) { return ring_bytes(W, Wo, W0, C0, TQ); }
+  static int lds_bytes(int W, int Wo, int W0, int C0, int TQ, bool ones) { return ring_bytes(W, Wo, W0, C0, TQ, ones); }
+  // dY loads of the busiest loader wave per band: whole rows in turn, or a quarter of the parts of every row
+  static int dy_loads(int Wo, int TQ, int split) {
+    const int segs = (Wo * 128 + 1023) / 1024;
+    return split ? (TQ + 1) * ((segs + NLW - 1) / NLW) : ((TQ + 1 + NLW - 1) / NLW) * segs;
+  }
+  static int seg_split(int Wo, int TQ) { return dy_loads(Wo, TQ, 1) < dy_loads(Wo, TQ, 0) ? 1 : 0; }
   static bool loads_fit(int W, int Wo, int W0, int C0, int TQ) {
     const int segs = (Wo * 128 + 1023) / 1024;
-    return segs <= MAXSEG && ((TQ + 1 + NLW - 1) / NLW) * segs + MAXI + MAXM <= 63 && (img0_bytes(W0, C0, TQ) + 1023) / 1024 <= MAXI * NLW &&
+    return segs <= MAXSEG && dy_loads(Wo, TQ, seg_split(Wo, TQ)) + MAXI + MAXM <= 63 && (img0_bytes(W0, C0, TQ) + 1023) / 1024 <= MAXI * NLW &&
            (mask_bytes(W, TQ) + 1023) / 1024 <= MAXM * NLW;
   }
 };
@@ -71,7 +80,8 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
   // slot: dY image | image rows | 16 zero bytes | mask words | one row of mask words + 32 bytes of zeros |
   // one-channel images: 32 bytes of bf16 ones, and 32 more two image rows further (the window of the bias column)
   const int OFF_IMG = dyimg_bytes, OFF_MSK = OFF_IMG + img0_bytes + 16, OFF_Z = OFF_MSK + mask_bytes, OFF_ONES = OFF_Z + MRB + 32;
-  const int SLOT = OFF_ONES + (C0 == 1 ? 2 * RB0 + 32 : 0);
+  constexpr bool ONES = C0 == 1 && WC != 0;  // the bias column reads a block of ones (costs 2 image rows of LDS per slot) instead of being ORed in
+  const int SLOT = OFF_ONES + (ONES ? 2 * RB0 + 32 : 0);
   const int vb = xcd_block((int)blockIdx.x, (int)gridDim.x);  // this block's number in the dealing of tiles
   const int nq = (a.ntiles > vb) ? (a.ntiles - 1 - vb) / (int)gridDim.x + 1 : 0;
 
@@ -86,7 +96,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
       const int s = i / nz, k = i - nz * s, off = k == 0 ? OFF_IMG + img0_bytes : OFF_Z + (k - 1) * 16;
       *reinterpret_cast<uint4*>(lds + s * SLOT + off) = make_uint4(0u, 0u, 0u, 0u);
     }
-    if (C0 == 1 && tid < NBUF * 4) {
+    if (ONES && tid < NBUF * 4) {
       const int s = tid >> 2, k = tid & 3;
       *reinterpret_cast<uint4*>(lds + s * SLOT + OFF_ONES + (k >> 1) * 2 * RB0 + (k & 1) * 16) = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
     }
@@ -99,20 +109,28 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     const int n_im = (img0_bytes + 1023) >> 10, n_mk = (mask_bytes + 1023) >> 10;
     // piece j of a kind (rows of the dY image, 1 KiB pieces of the image rows, of the mask words) belongs to loader j % 4
     auto mine = [&](int n) { return n > lw ? (n - lw + S::NLW - 1) / S::NLW : 0; };
-    const int nd = mine(TQ + 1) * segs, nm_i = mine(n_im), nm_m = mine(n_mk);
+    const int mysegs = segs > lw ? (segs - lw + S::NLW - 1) / S::NLW : 0;  // parts lw, lw + 4, ... of a row
+    const int nd = a.seg_split ? (TQ + 1) * mysegs : mine(TQ + 1) * segs, nm_i = mine(n_im), nm_m = mine(n_mk);
     const int ni = nd + nm_i + nm_m;  // this wave's loads per band
     const char* const zp = reinterpret_cast<const char*>(a.zpage) + lane * 16;
-    // dY rows are copied whole, in parts of 1 KiB: what a lane adds to the row's address depends on the part alone
+    // dY rows are copied in parts of 1 KiB, a loader taking whole rows in turn or (few rows of many parts) its
+    // share of the parts of every row: what a lane adds to the row's address depends on the part alone
     // (the 16-byte chunks of a pixel are permuted, dy_swz_bits, through the source address), and a row is inside
     // the image or not for the whole wave, so that the choice between the image and the page of zeros (a.zpage:
     // 64 KiB) and every other address part is scalar work: one vector instruction per load.  The lanes beyond
     // the end of a row whose last part is shorter than 1 KiB sit out.
     constexpr int MAXSEG = S::MAXSEG, MAXI = S::MAXI, MAXM = S::MAXM;
-    int lo[MAXSEG], igo[MAXI], irow[MAXI], mgo[MAXM], mrow[MAXM];
+    constexpr int MYSEG = MAXSEG / S::NLW;
+    int lo[MAXSEG], mylo[MYSEG], igo[MAXI], irow[MAXI], mgo[MAXM], mrow[MAXM];
 #pragma unroll
     for (int sg = 0; sg < MAXSEG; ++sg) {
       const uint32_t phys = sg * 1024 + lane * 16;
       lo[sg] = (int)(phys ^ dy_swz_bits(phys));
+    }
+#pragma unroll
+    for (int j = 0; j < MYSEG; ++j) {
+      const uint32_t phys = (lw + S::NLW * j) * 1024 + lane * 16;
+      mylo[j] = (int)(phys ^ dy_swz_bits(phys));
     }
     const int tail = rowbytes - (segs - 1) * 1024;
     const bool in_tail = lane * 16 < tail;
@@ -150,19 +168,38 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
       if (q + 1 < nq) nxt = prep();
       char* const slot = lds + (q % NBUF) * SLOT;
       const int nrows = a.Ho - b.r0[0];  // rows of the image from the band's first one on
-      for (int row = lw; row <= TQ; row += S::NLW) {
-        const char* const base = row < nrows ? b.base[0] + row * rowbytes : zbase;  // rows outside the image: zeros
-        char* const dst = slot + row * RP;
+      if (a.seg_split) {
+        for (int row = 0; row <= TQ; ++row) {
+          const char* const base = row < nrows ? b.base[0] + row * rowbytes : zbase;  // rows outside the image: zeros
+          char* const dst = slot + row * RP;
 #pragma unroll
-        for (int sg = 0; sg < MAXSEG; ++sg)
-          if (sg < segs) {
-            const char* p = base + lo[sg];
-            if (sg == segs - 1 && tail < 1024) {
-              if (in_tail) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + sg * 1024), 16, 0, LOAD_NT);
-            } else {
-              __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + sg * 1024), 16, 0, LOAD_NT);
+          for (int j = 0; j < MYSEG; ++j) {
+            const int sg = lw + S::NLW * j;
+            if (sg < segs) {
+              const char* p = base + mylo[j];
+              if (sg == segs - 1 && tail < 1024) {
+                if (in_tail) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + sg * 1024), 16, 0, LOAD_NT);
+              } else {
+                __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + sg * 1024), 16, 0, LOAD_NT);
+              }
             }
           }
+        }
+      } else {
+        for (int row = lw; row <= TQ; row += S::NLW) {
+          const char* const base = row < nrows ? b.base[0] + row * rowbytes : zbase;  // rows outside the image: zeros
+          char* const dst = slot + row * RP;
+#pragma unroll
+          for (int sg = 0; sg < MAXSEG; ++sg)
+            if (sg < segs) {
+              const char* p = base + lo[sg];
+              if (sg == segs - 1 && tail < 1024) {
+                if (in_tail) __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + sg * 1024), 16, 0, LOAD_NT);
+              } else {
+                __builtin_amdgcn_global_load_lds(GLOBAL_AS(p), LDS_AS(dst + sg * 1024), 16, 0, LOAD_NT);
+              }
+            }
+        }
       }
 #pragma unroll
       for (int k = 0; k < MAXI; ++k)
@@ -224,7 +261,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     // window corner is (row - 1, column - 1).  One-channel images are read as dwords: column 4b + 2px + v - 1
     // is the high half of dword 2b + px - 1 (v = 0), the low (v = 1) or high (v = 2) half of dword 2b + px.
     toffl[nt] = C0 == 1 ? u * RB0 + (v == 0 ? -4 : 0) : u * RB0 + ((v - 1) * C0 + cch) * 2;
-    hsel[nt] = (!real && !(C0 == 1 && k0 == K0)) ? 0x0c0c0c0cu : (v == 1 ? 0x05040100u : 0x07060302u);  // selector bytes 0x0c give zero
+    hsel[nt] = (!real && !(ONES && k0 == K0)) ? 0x0c0c0c0cu : (v == 1 ? 0x05040100u : 0x07060302u);  // selector bytes 0x0c give zero
     lnv0[nt] = v != 0 ? 0xfu : 0u;
     lmask[nt] = real ? 0xffffffffu : 0u;
     bconst[nt] = k0 == K0 ? 0x3F803F80u : 0u;  // the bias column: 1.0
@@ -244,13 +281,19 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     const int al = valid ? q0 / Wo : 0, b = valid ? q0 - al * Wo : 0;
     mo[m] = valid ? OFF_MSK + ((2 * al) * W + 2 * b) * 4 : OFF_Z;
     go[m] = OFF_IMG + 4 * al * RB0 + 8 * b * C0 + (NT == 1 ? toffl[0] : 0);
-    if (C0 == 1 && l16 == K0) go[m] = OFF_ONES;  // the bias column of one-channel images reads ones
+    if (ONES && l16 == K0) go[m] = OFF_ONES;  // the bias column reads ones
     if (!(valid && b == 0)) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) kpb[nt] |= 1u << m;
     }
     asm volatile("" : "+v"(mo[m]), "+v"(go[m]));
   }
+  // (three-channel images have registers to spare: their keep masks are formed once)
+  uint32_t kmr[4][NT];
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) kmr[m][nt] = (uint32_t)__builtin_amdgcn_sbfe((int)kpb[nt], (uint32_t)m, 1u);
   f32x4_t accw[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) accw[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -301,7 +344,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const char* p = slot + go[m] + (NT == 1 ? 0 : toffl[nt]) + 2 * py * RB0;
-        const uint32_t km = (uint32_t)__builtin_amdgcn_sbfe((int)kpb[nt], (uint32_t)m, 1u);
+        const uint32_t km = C0 == 1 ? (uint32_t)__builtin_amdgcn_sbfe((int)kpb[nt], (uint32_t)m, 1u) : kmr[m][nt];
         uint4 bq;
         if constexpr (C0 == 1) {
           uint32_t d[8];  // dword k = 2*i + px
@@ -321,7 +364,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
           bq = make_uint4(x0[0] | (x0[1] << 16), x0[2] | (x0[3] << 16), x1[0] | (x1[1] << 16), x1[2] | (x1[3] << 16));
         }
         if constexpr (C0 != 1) { bq.x &= lmask[nt]; bq.y &= lmask[nt]; bq.z &= lmask[nt]; bq.w &= lmask[nt]; }
-        if constexpr (C0 != 1) { bq.x |= bconst[nt]; bq.y |= bconst[nt]; bq.z |= bconst[nt]; bq.w |= bconst[nt]; }
+        if constexpr (!ONES) { bq.x |= bconst[nt]; bq.y |= bconst[nt]; bq.z |= bconst[nt]; bq.w |= bconst[nt]; }
         accw[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8_t, bq), accw[nt], 0, 0, 0);
       }
     }
@@ -369,6 +412,9 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
       bq = make_uint4(__builtin_amdgcn_perm(d[2], d[0], hsel[0]), __builtin_amdgcn_perm(d[6], d[4], hsel[0]),
                       __builtin_amdgcn_perm(d[3], d[1], hsel[0]), __builtin_amdgcn_perm(d[7], d[5], hsel[0]));
     };
+    auto ones = [&]() __attribute__((always_inline)) {
+      if constexpr (!ONES) { bq.x |= bconst[0]; bq.y |= bconst[0]; bq.z |= bconst[0]; bq.w |= bconst[0]; }
+    };
     auto second = [&]() __attribute__((always_inline)) { accw[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aq), __builtin_bit_cast(bf16x8_t, bq), accw[0], 0, 0, 0); };
 #define DW0_MF(c, xi, s, ks) nxt[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[xi], wr[s][ks], nxt[c], 0, 0, 0)
 #define DW0_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -381,7 +427,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     DW0_MF(3, 0, 8, 0); keep2(0, 6); conv_hi(); DW0_FENCE();
     DW0_MF(0, 1, 4, 1); masks(1, 0); DW0_FENCE();
     DW0_MF(1, 1, 5, 1); halves(); DW0_FENCE();
-    DW0_MF(2, 1, 7, 1); x[2] = xr(2); DW0_FENCE();
+    DW0_MF(2, 1, 7, 1); ones(); x[2] = xr(2); DW0_FENCE();
     DW0_MF(3, 1, 8, 1); masks(1, 1); DW0_FENCE();
     second(); x[3] = xr(3); DW0_FENCE();
     DW0_MF(1, 2, 3, 0); keep2(1, 0); DW0_FENCE();
@@ -390,7 +436,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     DW0_MF(3, 3, 6, 1); keep2(1, 6); conv_hi(); DW0_FENCE();
     DW0_MF(2, 4, 1, 0); x[5] = xr(5); DW0_FENCE();
     DW0_MF(3, 4, 2, 0); halves(); DW0_FENCE();
-    DW0_MF(2, 5, 1, 1); x[6] = xr(6); DW0_FENCE();
+    DW0_MF(2, 5, 1, 1); ones(); x[6] = xr(6); DW0_FENCE();
     second(); x[7] = xr(7); DW0_FENCE();
     DW0_MF(3, 5, 2, 1); DW0_FENCE();
     DW0_MF(3, 6, 0, 0);

@@ -794,7 +794,7 @@ int launch_conv_dgrad_tile_t(Ctx* c, ConvDgradArgs a, int nimg, const std::strin
 ConvDgradArgs conv_dgrad_args(Ctx* c, const ImgAddr& dy, const ImgAddr& xa, const uint32_t* xbits, bf16_t* dx, const bf16_t* wt, int H, int W, int Ho, int Wo) {
   ConvDgradArgs a;
   a.dy = dy; a.dy.prepare(); a.dx = dx; a.xbits = xbits; a.x_stride_b = xa.stride_b; a.x_stride_v = xa.stride_v;
-  a.wt = wt; a.zpage = c->zpage; a.V = xa.V; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.TQ = 0; a.NB = 0; a.ntiles = 0;
+  a.wt = wt; a.zpage = c->zpage; a.V = xa.V; a.H = H; a.W = W; a.Ho = Ho; a.Wo = Wo; a.TQ = 0; a.NB = 0; a.ntiles = 0; a.seg_split = 0;
   a.img0 = ImgAddr(); a.img0.base = nullptr; a.img0.idx = nullptr; a.img0.stride_b = 0; a.img0.stride_v = 0; a.img0.V = 1;
   a.H0 = 0; a.W0 = 0; a.partial0 = nullptr;
   return a;
@@ -836,17 +836,18 @@ template <int C0, int NCW, int WC = 0>
 int launch_conv_dgrad_wgrad0_reg_t(Ctx* c, ConvDgradArgs a, int nimg, const std::string& name, double flops, double abytes, int* grid_out) {
   typedef ConvDgradW0Shape<NCW> S;
   if (WC && a.W != WC) return 1;
+  constexpr bool ones = C0 == 1 && WC != 0;  // the kernel's ONES
   const int rb0 = a.W0 * C0 * 2;
   if (a.W % 8 || rb0 % 16 || a.Wo * 2 != a.W || a.Wo > S::BQ || a.H != (a.H0 + 1) / 2 || a.W * 2 != a.W0) return 1;
   auto fits = [&](int tq) {
-    return tq * a.Wo <= S::BQ && S::lds_bytes(a.W, a.Wo, a.W0, C0, tq) <= 158 * 1024 && S::loads_fit(a.W, a.Wo, a.W0, C0, tq) &&
+    return tq * a.Wo <= S::BQ && S::lds_bytes(a.W, a.Wo, a.W0, C0, tq, ones) <= 160 * 1024 && S::loads_fit(a.W, a.Wo, a.W0, C0, tq) &&
            S::dyimg_bytes(a.Wo, tq) <= 65536;  // offsets into the page of zeros
   };
   int TQ = S::BQ / a.Wo < a.Ho ? S::BQ / a.Wo : a.Ho;
   while (TQ > 1 && !fits(TQ)) --TQ;
   if (TQ < 1 || !fits(TQ)) return 1;
   a.NB = cdiv(a.Ho, TQ); a.TQ = cdiv(a.Ho, a.NB); a.NB = cdiv(a.Ho, a.TQ); a.ntiles = nimg * a.NB;
-  a.dv_rb0 = make_fastdiv(rb0); a.dv_mrow = make_fastdiv(a.W * 4);
+  a.dv_rb0 = make_fastdiv(rb0); a.dv_mrow = make_fastdiv(a.W * 4); a.seg_split = S::seg_split(a.Wo, a.TQ);
   int gx = a.ntiles < 256 ? a.ntiles : 256;
   const int64_t npair = (int64_t)S::CI * (9 * C0 + 1);
   { const int erc = ensure_partial(c, gx * npair, 0); if (erc) return erc; }
@@ -858,7 +859,7 @@ int launch_conv_dgrad_wgrad0_reg_t(Ctx* c, ConvDgradArgs a, int nimg, const std:
   static uint64_t attr_devs = 0;  /* bit d: set on device d */
   if (!((attr_devs >> c->dev) & 1)) { HIPCHK(c, hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)); attr_devs |= 1ull << c->dev; }
   ProfScope ps(c, name, flops, abytes);
-  hipLaunchKernelGGL(kfn, dim3(gx), dim3(S::THREADS), S::lds_bytes(a.W, a.Wo, a.W0, C0, a.TQ), c->stream, a);
+  hipLaunchKernelGGL(kfn, dim3(gx), dim3(S::THREADS), S::lds_bytes(a.W, a.Wo, a.W0, C0, a.TQ, ones), c->stream, a);
   LAUNCHCHK(c, "k_conv_dgrad_wgrad0_tile");
   return PPO_OK;
 }
