@@ -70,11 +70,10 @@ struct ConvDgradShape {
 
 __device__ __forceinline__ uint32_t dy_swz_bits(uint32_t off) { return ((off >> 8) & 7u) << 4; }
 
-// all-ones halves for the set bits among bits (2d, 2d+1) of b
+// all-ones halves for the set bits among bits (2d, 2d+1) of b: two sign-extended one-bit fields, joined by a byte permute
 __device__ __forceinline__ uint32_t keep_pair(uint32_t b, int d) {
-  const uint32_t lo = (uint32_t)__builtin_amdgcn_sbfe((int)b, 2 * d, 1) & 0xffffu;  // 0 or -1 from one bit
-  const uint32_t hi = (uint32_t)__builtin_amdgcn_sbfe((int)b, 2 * d + 1, 1) << 16;
-  return lo | hi;
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_sbfe((int)b, 2 * d, 1), hi = (uint32_t)__builtin_amdgcn_sbfe((int)b, 2 * d + 1, 1);  // 0 or -1
+  return __builtin_amdgcn_perm(hi, lo, 0x07060100u);  // bytes 0, 1 of lo; bytes 2, 3 of hi
 }
 
 template <int CI, int C0>

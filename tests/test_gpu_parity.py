@@ -324,7 +324,10 @@ def test_ppo_single_minibatch_gradients(L, ci, N, T, chunk):
 # first-layer weight gradient takes them (odd output height, bands that do not divide the image).
 ODD_SHAPES = [(52, 76), (50, 72), (44, 88), (50, 96), (36, 80),
               # small and tall images, an odd height, several bands per image, rows of 13 to 15 sixteen-byte pieces
-              (24, 40), (70, 56), (33, 64), (16, 16), (90, 120), (28, 104)]
+              (24, 40), (70, 56), (33, 64), (16, 16), (90, 120), (28, 104),
+              # very wide rows: one quad row per band in the register-fused kernel, whose loader waves then share the
+              # 1 KiB parts of every gradient row (20 parts; 17 parts with a last part of 512 bytes)
+              (24, 640), (20, 528)]
 
 
 @pytest.mark.parametrize("h,w", ODD_SHAPES)
