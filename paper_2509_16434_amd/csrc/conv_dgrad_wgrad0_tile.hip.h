@@ -19,17 +19,27 @@
 // compute wave); with eight, two compute waves share a SIMD and hide each other's LDS latency.  The
 // loaders copy, per band, the dY rows (TQ+1), the image rows (4*TQ+1) and the mask words (2*TQ rows)
 // into a ring of three LDS slots with LDS-writing 16-byte loads, 1 KiB per instruction; rows outside
-// the images come from a page of zeros, so no lane tests a row bound.  One barrier per tile: the
+// the images come from a page of zeros (64 KiB, so that a whole dY row outside the image is a scalar
+// choice of base address), so no lane tests a row bound.  One barrier per tile: the
 // loaders arrive when the band has landed, the compute waves when they are done with the previous
 // one.
 //
-// The LDS pipe is the scarce resource here, so the second product reads as little as it can: the
-// width in quads is a multiple of four, hence the four quads of a lane are neighbours in one row,
-// their eight mask words are 32 contiguous bytes (two 16-byte reads) and, for one-channel images,
-// the eight window values of a tap are the low or high halves of eight consecutive dwords (read as
-// dwords, halves picked with a byte permute).  Every LDS offset of the second product is a per-lane
-// constant plus an immediate.  Each block leaves one fp32 partial [32][9*C0+1] (last column: bias
-// gradient, from a constant-one patch column).
+// The second product reads as little LDS as it can: the width in quads is a multiple of four, hence the
+// four quads of a lane are neighbours in one row, their eight mask words are 32 contiguous bytes (two
+// 16-byte reads) and, for one-channel images, the eight window values of a tap are the low or high halves
+// of eight consecutive dwords (read as dwords, halves picked with a byte permute).  Every LDS offset of the
+// second product is a per-lane constant plus an immediate.  Each block leaves one fp32 partial
+// [32][9*C0+1] (last column: bias gradient, from a constant-one patch column).
+//
+// The instruction issue of the SIMDs is what bounds the kernel: an MFMA and another vector instruction do
+// not run side by side on a SIMD, whichever waves they come from, so every vector instruction counts.
+// Hence: one per-lane offset per M-tile and kind of read (the second pixel row, the second half of the
+// gradient channels and the window's dwords are reached through instruction offsets, with the row pitches
+// known at compile time in the WC form); the bias column of that form reads a block of bf16 ones kept in
+// the slot instead of being ORed into every window; lanes beyond the band read a tail of zeros behind the
+// mask words, one mask row long, so that both pixel rows of a quad use one offset; loader waves whose
+// address work per load is scalar.  For one-channel images the first product of M-tile m+1 and the second
+// of M-tile m are written as ONE instruction stream in a fixed order (fused()).
 #pragma once
 #include "conv_dgrad_tile.hip.h"
 
