@@ -288,6 +288,9 @@ def run_peaks(args):
         out[kind] = round(learner.diag_peak(kind, nbytes=2 << 30, iters=20), 1)
         out[kind + "_128MiB"] = round(learner.diag_peak(kind, nbytes=128 << 20, iters=100), 1)
     out["mfma_bf16_loop"] = round(learner.diag_peak("mfma_bf16_loop", iters=20), 1)
+    # one 16x16x32 MFMA (16 cycles) + K independent vector instructions per group: do they run side by side on a SIMD?
+    for k in (0, 1, 2, 3, 4, 6, 8):
+        out[f"mfma16_valu_k{k}"] = round(learner.diag_peak("mfma_valu_loop", nbytes=k, iters=20), 1)
     print(json.dumps(out))
 
 

@@ -29,7 +29,9 @@ int ppo_diag_gemm(int32_t M, int32_t N, int32_t K, const float* h_a, const float
 /* Diagnostic: what a plain kernel reaches on the current GPU.  kind 0: streaming copy of nbytes with 16-byte
  * loads and stores (result: GB/s counting read + written bytes), 1: the read half alone, 2: the store half alone,
  * 3: the copy with non-temporal loads and stores, 4: a register-resident bf16 MFMA loop (result: TFLOP/s; nbytes
- * ignored).  Allocates its own buffers, times `iters` launches with events on the default stream, synchronises. */
+ * ignored), 5: a register-resident loop of one 16x16x32 bf16 MFMA followed by K = nbytes (0..8) independent vector
+ * instructions, two waves per SIMD (result: TFLOP/s of the MFMAs; shows whether the two kinds of instruction overlap).
+ * Allocates its own buffers, times `iters` launches with events on the default stream, synchronises. */
 int ppo_diag_peak(int32_t kind, int64_t nbytes, int32_t iters, float* h_result);
 
 #ifdef __cplusplus

@@ -31,8 +31,9 @@
 // second product is a per-lane constant plus an immediate.  Each block leaves one fp32 partial
 // [32][9*C0+1] (last column: bias gradient, from a constant-one patch column).
 //
-// The instruction issue of the SIMDs is what bounds the kernel: an MFMA and another vector instruction do
-// not run side by side on a SIMD, whichever waves they come from, so every vector instruction counts.
+// The instruction issue of the SIMDs is what bounds the kernel: at three to four vector instructions per
+// MFMA the two kinds hardly overlap on a SIMD, whichever waves they come from (measured with a loop of one
+// MFMA and K vector instructions), so every vector instruction counts.
 // Hence: one per-lane offset per M-tile and kind of read (the second pixel row, the second half of the
 // gradient channels and the window's dwords are reached through instruction offsets, with the row pitches
 // known at compile time in the WC form); the bias column of that form reads a block of bf16 ones kept in

@@ -1,10 +1,11 @@
 // Plain kernels that show what this GPU reaches: a streaming copy with 16-byte accesses, its read-only and
-// store-only halves, the same copy with non-temporal accesses, and a register-resident bf16 MFMA loop.  Used by
+// store-only halves, the same copy with non-temporal accesses, a register-resident bf16 MFMA loop, and a loop of
+// one MFMA followed by K other vector instructions (do the two kinds run side by side on a SIMD?).  Used by
 // ppo_diag_peak only; the learner's kernels are priced against the published peaks, these figures sit beside them.
 #pragma once
 #include "common.hip.h"
 
-enum { PEAK_COPY = 0, PEAK_READ = 1, PEAK_WRITE = 2, PEAK_COPY_NT = 3, PEAK_MFMA = 4 };
+enum { PEAK_COPY = 0, PEAK_READ = 1, PEAK_WRITE = 2, PEAK_COPY_NT = 3, PEAK_MFMA = 4, PEAK_MFMA_VALU = 5 };
 
 // Grid-stride over n16 16-byte pieces, four pieces in flight per thread.
 template <int MODE>
@@ -58,4 +59,41 @@ __global__ __launch_bounds__(512) void k_peak_mfma(int iters, float* __restrict_
 #pragma unroll
     for (int e = 0; e < 16; ++e) s += acc[q][e];
   if (s == -1.f) sink[0] = s;  // never true (all products are >= 0): keeps the loop alive
+}
+
+// Do MFMAs and other vector instructions overlap on a SIMD?  Every wave (two per SIMD) issues rounds of eight groups of
+// one v_mfma_f32_16x16x32_bf16 (four independent accumulators in turn) followed by K independent v_xor_b32 on K
+// registers of their own; nothing depends on anything nearby.  16384 flop per wave per group.  If the two kinds ran
+// side by side, the time per group would stay that of the MFMA (16 cycles) up to K = 4.
+typedef float f32x4_peak_t __attribute__((ext_vector_type(4)));
+template <int K>
+__global__ __launch_bounds__(512) void k_peak_mfma_valu(int iters, float* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  bf16x8_t a, b;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { a[j] = (__bf16)(float)((lane + j) & 3); b[j] = (__bf16)(float)((lane * 3 + j) & 1); }
+  f32x4_peak_t acc[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) acc[q] = f32x4_peak_t{0.f, 0.f, 0.f, 0.f};
+  uint32_t v[K > 0 ? K : 1];
+#pragma unroll
+  for (int j = 0; j < (K > 0 ? K : 1); ++j) v[j] = (uint32_t)(threadIdx.x * 17 + j);
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      acc[u & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[u & 3], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < K; ++j) asm volatile("v_xor_b32 %0, %0, %1" : "+v"(v[j]) : "v"(lane));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s += acc[q][e];
+  uint32_t r = 0;
+#pragma unroll
+  for (int j = 0; j < (K > 0 ? K : 1); ++j) r ^= v[j];
+  if (s == -1.f) sink[0] = s + (float)r;  // never true (all products are >= 0): keeps the loops alive
 }

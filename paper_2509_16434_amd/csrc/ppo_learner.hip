@@ -2233,8 +2233,10 @@ int ppo_diag_gemm(int32_t M, int32_t N, int32_t K, const float* h_a, const float
 }
 
 int ppo_diag_peak(int32_t kind, int64_t nbytes, int32_t iters, float* h_result) {
-  if (!h_result || kind < PEAK_COPY || kind > PEAK_MFMA || iters < 1 || iters > 100000) return fail(nullptr, PPO_EINVAL, "ppo_diag_peak: bad argument");
-  if (kind != PEAK_MFMA && (nbytes < (1 << 20) || nbytes > (16LL << 30) || nbytes % 16)) return fail(nullptr, PPO_EINVAL, "ppo_diag_peak: nbytes must be a multiple of 16 in [1 MiB, 16 GiB]");
+  if (!h_result || kind < PEAK_COPY || kind > PEAK_MFMA_VALU || iters < 1 || iters > 100000) return fail(nullptr, PPO_EINVAL, "ppo_diag_peak: bad argument");
+  const bool streams = kind != PEAK_MFMA && kind != PEAK_MFMA_VALU;
+  if (streams && (nbytes < (1 << 20) || nbytes > (16LL << 30) || nbytes % 16)) return fail(nullptr, PPO_EINVAL, "ppo_diag_peak: nbytes must be a multiple of 16 in [1 MiB, 16 GiB]");
+  if (kind == PEAK_MFMA_VALU && (nbytes < 0 || nbytes > 8)) return fail(nullptr, PPO_EINVAL, "ppo_diag_peak: kind 5 takes the number of vector instructions per MFMA (0..8) in nbytes");
   Ctx tmp;
   Ctx* c = &tmp;
   auto body = [&]() -> int {
@@ -2243,7 +2245,7 @@ int ppo_diag_peak(int32_t kind, int64_t nbytes, int32_t iters, float* h_result) 
     hipEvent_t e0, e1;
     DALLOC(c, sink, 4);
     const int64_t n16 = nbytes / 16;
-    if (kind != PEAK_MFMA) {
+    if (streams) {
       DALLOC(c, src, n16); DALLOC(c, dst, n16);
       HIPCHK(c, hipMemset(src, 0, (size_t)nbytes));
       HIPCHK(c, hipMemset(dst, 0, (size_t)nbytes));
@@ -2257,7 +2259,14 @@ int ppo_diag_peak(int32_t kind, int64_t nbytes, int32_t iters, float* h_result) 
         case PEAK_READ: hipLaunchKernelGGL(k_peak_stream<PEAK_READ>, grid, blk, 0, nullptr, src, dst, n16, (uint32_t*)sink); break;
         case PEAK_WRITE: hipLaunchKernelGGL(k_peak_stream<PEAK_WRITE>, grid, blk, 0, nullptr, src, dst, n16, (uint32_t*)sink); break;
         case PEAK_COPY_NT: hipLaunchKernelGGL(k_peak_stream<PEAK_COPY_NT>, grid, blk, 0, nullptr, src, dst, n16, (uint32_t*)sink); break;
-        default: hipLaunchKernelGGL(k_peak_mfma, dim3(256 * 2), dim3(512), 0, nullptr, mfma_rounds, sink); break;
+        case PEAK_MFMA: hipLaunchKernelGGL(k_peak_mfma, dim3(256 * 2), dim3(512), 0, nullptr, mfma_rounds, sink); break;
+        default:
+          switch ((int)nbytes) {
+#define PEAK_MV(K_) case K_: hipLaunchKernelGGL(k_peak_mfma_valu<K_>, dim3(256), dim3(512), 0, nullptr, mfma_rounds, sink); break;
+            PEAK_MV(0) PEAK_MV(1) PEAK_MV(2) PEAK_MV(3) PEAK_MV(4) PEAK_MV(5) PEAK_MV(6) PEAK_MV(7) PEAK_MV(8)
+#undef PEAK_MV
+          }
+          break;
       }
     };
     for (int i = 0; i < 2; ++i) launch();
@@ -2272,6 +2281,7 @@ int ppo_diag_peak(int32_t kind, int64_t nbytes, int32_t iters, float* h_result) 
     (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
     const double sec = (double)ms * 1e-3 / iters;
     if (kind == PEAK_MFMA) *h_result = (float)(256.0 * 2 * 8 * mfma_rounds * 4 * 32768.0 / sec / 1e12);   // TFLOP/s
+    else if (kind == PEAK_MFMA_VALU) *h_result = (float)(256.0 * 8 * mfma_rounds * 8 * 16384.0 / sec / 1e12);  // TFLOP/s of the MFMAs: 256 blocks of 8 waves
     else *h_result = (float)((kind == PEAK_COPY || kind == PEAK_COPY_NT ? 2.0 : 1.0) * (double)nbytes / sec / 1e9);  // GB/s
     return PPO_OK;
   };

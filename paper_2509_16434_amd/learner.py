@@ -172,11 +172,12 @@ def diag_gemm(a: np.ndarray, b: np.ndarray) -> np.ndarray:
     return c
 
 
-PEAK_KINDS = {"copy": 0, "copy_read_only": 1, "copy_write_only": 2, "copy_nt": 3, "mfma_bf16_loop": 4}
+PEAK_KINDS = {"copy": 0, "copy_read_only": 1, "copy_write_only": 2, "copy_nt": 3, "mfma_bf16_loop": 4, "mfma_valu_loop": 5}
 
 
 def diag_peak(kind: str, nbytes: int = 2 << 30, iters: int = 20) -> float:
-    """GB/s (copies; read + written bytes) or TFLOP/s (MFMA loop) of a plain kernel on the current GPU (diagnostic)."""
+    """GB/s (copies; read + written bytes) or TFLOP/s (MFMA loops; for "mfma_valu_loop" nbytes is the number of vector
+    instructions per MFMA, 0..8) of a plain kernel on the current GPU (diagnostic)."""
     r = C.c_float()
     rc = _lib.ppo_diag_peak(PEAK_KINDS[kind], nbytes, iters, C.byref(r))
     if rc:
