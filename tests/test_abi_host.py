@@ -125,6 +125,12 @@ def test_null_handles_are_einval_not_a_crash():
     assert lib.ppo_buffer_write_outcome(None, 0, None, None) == L.PPO_EINVAL
     assert lib.ppo_param_count(None) < 0
     assert lib.ppo_diag_gemm(4, 4, 7, None, None, None) == L.PPO_EINVAL
+    import ctypes
+    r = ctypes.c_float()
+    assert lib.ppo_diag_peak(6, 1 << 20, 1, ctypes.byref(r)) == L.PPO_EINVAL    # no such kind
+    assert lib.ppo_diag_peak(5, 9, 1, ctypes.byref(r)) == L.PPO_EINVAL          # at most 8 vector instructions per MFMA
+    assert lib.ppo_diag_peak(0, 100, 1, ctypes.byref(r)) == L.PPO_EINVAL        # a copy needs at least 1 MiB
+    assert lib.ppo_diag_peak(4, 0, 1, None) == L.PPO_EINVAL
     assert lib.ppo_get_adaptive_lr(None, None, None) == L.PPO_EINVAL
     assert lib.ppo_set_adaptive_lr(None, 1e-3, 1) == L.PPO_EINVAL
 

@@ -54,6 +54,16 @@ def test_mfma_gemm_tiles(L, M, N, K):
     assert np.abs(c - want).max() <= 1e-4 * max(1.0, np.abs(want).max())
 
 
+def test_peak_diagnostics_run(L):
+    """The plain kernels behind `bench.py --phase peaks`: each kind returns a positive rate; more vector instructions per
+    MFMA never make the MFMA loop faster."""
+    assert L.diag_peak("copy", nbytes=64 << 20, iters=2) > 100.0
+    assert L.diag_peak("mfma_bf16_loop", iters=2) > 100.0
+    r0 = L.diag_peak("mfma_valu_loop", nbytes=0, iters=3)
+    r8 = L.diag_peak("mfma_valu_loop", nbytes=8, iters=3)
+    assert r0 > 100.0 and 0.0 < r8 <= r0 * 1.02
+
+
 # ------------------------------------------------------------------ buffer
 @pytest.mark.parametrize("ci", [0, 1, 3])
 def test_buffer_write_read_back(L, ci):
