@@ -10,8 +10,8 @@
 // consecutive quads of each class: exactly the shape of the first operand of the second product
 // G0[ci][k0] += sum over pixels of dXmasked[pixel][ci] * patch[pixel][k0], whose contraction index
 // (32 per MFMA) runs over 4 lane groups x (2 horizontal classes x 4 quads).  The other operand,
-// patch[pixel][k0], is gathered from the band's image rows in LDS with 2-byte reads by lane
-// (k0 = lane % 16, same pixels).  The ReLU mask of the first layer's output arrives as one 32-bit
+// patch[pixel][k0], is gathered from the band's image rows in LDS by lane (k0 = lane % 16, same
+// pixels): the eight window values of a lane are the same half of eight dwords, C0 dwords apart.  The ReLU mask of the first layer's output arrives as one 32-bit
 // word per pixel (bit = channel); a lane keeps its value when bit ci of the pixel's word is set.
 //
 // A block has four or eight compute waves and four loader waves.  Compute wave w works on channels
@@ -26,8 +26,9 @@
 //
 // The second product reads as little LDS as it can: the width in quads is a multiple of four, hence the
 // four quads of a lane are neighbours in one row, their eight mask words are 32 contiguous bytes (two
-// 16-byte reads) and, for one-channel images, the eight window values of a tap are the low or high halves
-// of eight consecutive dwords (read as dwords, halves picked with a byte permute).  Every LDS offset of the
+// 16-byte reads) and the eight window values of a (tap, channel) are the low or high halves of eight
+// dwords at a fixed pitch (read as dwords, two per instruction, halves picked with a byte permute; lanes
+// without a patch column select zeros).  Every LDS offset of the
 // second product is a per-lane constant plus an immediate.  Each block leaves one fp32 partial
 // [32][9*C0+1] (last column: bias gradient, from a constant-one patch column).
 //
@@ -263,18 +264,20 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
   const int cibit = ch * 16 + l16;  // this lane's channel as a result column: its bit in a mask word
   // second product, second operand: lane (column k0 = nt*16 + l16, pixels of lane group r)
   int toffl[NT];
-  uint32_t lnv0[NT], lmask[NT], bconst[NT], hsel[NT];
+  uint32_t lnv0[NT], bconst[NT], hsel[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int k0 = nt * 16 + l16;
     const bool real = k0 < K0;
     const int tap = real ? k0 / C0 : 1, cch = real ? k0 - tap * C0 : 0, u = tap / 3, v = tap - 3 * u;
-    // window corner is (row - 1, column - 1).  One-channel images are read as dwords: column 4b + 2px + v - 1
-    // is the high half of dword 2b + px - 1 (v = 0), the low (v = 1) or high (v = 2) half of dword 2b + px.
-    toffl[nt] = C0 == 1 ? u * RB0 + (v == 0 ? -4 : 0) : u * RB0 + ((v - 1) * C0 + cch) * 2;
-    hsel[nt] = (!real && !(ONES && k0 == K0)) ? 0x0c0c0c0cu : (v == 1 ? 0x05040100u : 0x07060302u);  // selector bytes 0x0c give zero
+    // window corner is (row - 1, column - 1)
+    // The window value of (tap column v, channel cch) at pixel column x is element C0*(x + v - 1) + cch of the row; x
+    // advances by 2 per window value, an even number of elements: all eight values of a lane are the same half of
+    // dwords that are C0 dwords apart.  e0: the element for x = 0 (it may lie left of the image: -C0 .. -1).
+    const int e0 = C0 * (v - 1) + cch;
+    toffl[nt] = u * RB0 + 4 * (e0 >> 1);
+    hsel[nt] = (!real && !(ONES && k0 == K0)) ? 0x0c0c0c0cu : ((e0 & 1) ? 0x07060302u : 0x05040100u);  // selector bytes 0x0c give zero
     lnv0[nt] = v != 0 ? 0xfu : 0u;
-    lmask[nt] = real ? 0xffffffffu : 0u;
     bconst[nt] = k0 == K0 ? 0x3F803F80u : 0u;  // the bias column: 1.0
   }
   // this lane's four quads of M-tile m are q0 .. q0 + 3, q0 = gp*64 + m*16 + r*4, neighbours in one quad row;
@@ -357,24 +360,12 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
         const char* p = slot + go[m] + (NT == 1 ? 0 : toffl[nt]) + 2 * py * RB0;
         const uint32_t km = C0 == 1 ? (uint32_t)__builtin_amdgcn_sbfe((int)kpb[nt], (uint32_t)m, 1u) : kmr[m][nt];
         uint4 bq;
-        if constexpr (C0 == 1) {
-          uint32_t d[8];  // dword k = 2*i + px
+        uint32_t d[8];  // window value k = 2*i + px: dword C0*k from the lane's first
 #pragma unroll
-          for (int k = 0; k < 8; ++k) d[k] = *reinterpret_cast<const uint32_t*>(p + 4 * k);
-          d[0] &= km;
-          bq = make_uint4(__builtin_amdgcn_perm(d[2], d[0], hsel[nt]), __builtin_amdgcn_perm(d[6], d[4], hsel[nt]),
-                          __builtin_amdgcn_perm(d[3], d[1], hsel[nt]), __builtin_amdgcn_perm(d[7], d[5], hsel[nt]));
-        } else {
-          uint32_t x0[4], x1[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            x0[i] = (uint32_t)*reinterpret_cast<const unsigned short*>(p + 8 * C0 * i);
-            x1[i] = (uint32_t)*reinterpret_cast<const unsigned short*>(p + 8 * C0 * i + 4 * C0);
-          }
-          x0[0] &= km;
-          bq = make_uint4(x0[0] | (x0[1] << 16), x0[2] | (x0[3] << 16), x1[0] | (x1[1] << 16), x1[2] | (x1[3] << 16));
-        }
-        if constexpr (C0 != 1) { bq.x &= lmask[nt]; bq.y &= lmask[nt]; bq.z &= lmask[nt]; bq.w &= lmask[nt]; }
+        for (int k = 0; k < 8; ++k) d[k] = *reinterpret_cast<const uint32_t*>(p + 4 * C0 * k);
+        d[0] &= km;
+        bq = make_uint4(__builtin_amdgcn_perm(d[2], d[0], hsel[nt]), __builtin_amdgcn_perm(d[6], d[4], hsel[nt]),
+                        __builtin_amdgcn_perm(d[3], d[1], hsel[nt]), __builtin_amdgcn_perm(d[7], d[5], hsel[nt]));
         if constexpr (!ONES) { bq.x |= bconst[nt]; bq.y |= bconst[nt]; bq.z |= bconst[nt]; bq.w |= bconst[nt]; }
         accw[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8_t, bq), accw[nt], 0, 0, 0);
       }
@@ -382,10 +373,9 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
   };
 
   // One-channel images: the first product of M-tile m + 1 and the second product of M-tile m as ONE instruction
-  // stream in a fixed order.  A SIMD issues vector instructions in the shadow of a running MFMA only when they
-  // stand next to it in the wave's stream; left to itself the scheduler puts the 18 MFMAs of the first product in
-  // a row and the ~70 vector instructions of the second behind them, and the two streams then take the sum of
-  // their times.  Here every MFMA of the first product is followed by four or five vector instructions of the
+  // stream in a fixed order.  Left to itself the scheduler puts the 18 MFMAs of the first product in a row and the
+  // ~70 vector instructions of the second behind them, with the LDS reads of each right in front of their first
+  // use.  Here every MFMA of the first product is followed by four or five vector instructions of the
   // second (mask bits, masking, conversion, window halves), and every LDS read is issued three to eight MFMAs
   // before its first use.  The order of the additions into each accumulator is the one of dgrad() / wgrad().
   auto fused = [&](const char* slot, int m, const f32x4_t (&cur)[4], f32x4_t (&nxt)[4]) __attribute__((always_inline)) {
