@@ -302,12 +302,6 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     }
     asm volatile("" : "+v"(mo[m]), "+v"(go[m]));
   }
-  // (three-channel images have registers to spare: their keep masks are formed once)
-  uint32_t kmr[4][NT];
-#pragma unroll
-  for (int m = 0; m < 4; ++m)
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) kmr[m][nt] = (uint32_t)__builtin_amdgcn_sbfe((int)kpb[nt], (uint32_t)m, 1u);
   f32x4_t accw[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) accw[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -358,7 +352,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const char* p = slot + go[m] + (NT == 1 ? 0 : toffl[nt]) + 2 * py * RB0;
-        const uint32_t km = C0 == 1 ? (uint32_t)__builtin_amdgcn_sbfe((int)kpb[nt], (uint32_t)m, 1u) : kmr[m][nt];
+        const uint32_t km = (uint32_t)__builtin_amdgcn_sbfe((int)kpb[nt], (uint32_t)m, 1u);
         uint4 bq;
         uint32_t d[8];  // window value k = 2*i + px: dword C0*k from the lane's first
 #pragma unroll
@@ -372,7 +366,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     }
   };
 
-  // One-channel images: the first product of M-tile m + 1 and the second product of M-tile m as ONE instruction
+  // The first product of M-tile m + 1 and the second product of M-tile m as ONE instruction
   // stream in a fixed order.  Left to itself the scheduler puts the 18 MFMAs of the first product in a row and the
   // ~70 vector instructions of the second behind them, with the LDS reads of each right in front of their first
   // use.  Here every MFMA of the first product is followed by four or five vector instructions of the
@@ -390,10 +384,10 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
       const uint4 wa = *reinterpret_cast<const uint4*>(slot + mo[m] + py * MRB + 16 * half);
       w[4 * half + 0] = wa.x; w[4 * half + 1] = wa.y; w[4 * half + 2] = wa.z; w[4 * half + 3] = wa.w;
     };
-    auto window = [&](int py) __attribute__((always_inline)) {
-      const char* p = slot + go[m] + 2 * py * RB0;
+    auto window = [&](int py, int nt = 0) __attribute__((always_inline)) {
+      const char* p = slot + go[m] + (NT == 1 ? 0 : toffl[nt]) + 2 * py * RB0;
 #pragma unroll
-      for (int k = 0; k < 8; ++k) d[k] = *reinterpret_cast<const uint32_t*>(p + 4 * k);
+      for (int k = 0; k < 8; ++k) d[k] = *reinterpret_cast<const uint32_t*>(p + 4 * C0 * k);
     };
     // word e = 2*i + px belongs to value i of class (py, px); the operand takes the values of px = 0 first
     auto keep2 = [&](int py, int e0) __attribute__((always_inline)) {
@@ -408,19 +402,47 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     auto conv_hi = [&]() __attribute__((always_inline)) {
       aq.y = pack2bf(__int_as_float((int)v[4]), __int_as_float((int)v[6])); aq.w = pack2bf(__int_as_float((int)v[5]), __int_as_float((int)v[7]));
     };
-    auto halves = [&]() __attribute__((always_inline)) {
-      d[0] &= (uint32_t)__builtin_amdgcn_sbfe((int)kpb[0], (uint32_t)m, 1u);
-      bq = make_uint4(__builtin_amdgcn_perm(d[2], d[0], hsel[0]), __builtin_amdgcn_perm(d[6], d[4], hsel[0]),
-                      __builtin_amdgcn_perm(d[3], d[1], hsel[0]), __builtin_amdgcn_perm(d[7], d[5], hsel[0]));
+    auto halves = [&](int nt = 0) __attribute__((always_inline)) {
+      d[0] &= (uint32_t)__builtin_amdgcn_sbfe((int)kpb[nt], (uint32_t)m, 1u);
+      bq = make_uint4(__builtin_amdgcn_perm(d[2], d[0], hsel[nt]), __builtin_amdgcn_perm(d[6], d[4], hsel[nt]),
+                      __builtin_amdgcn_perm(d[3], d[1], hsel[nt]), __builtin_amdgcn_perm(d[7], d[5], hsel[nt]));
     };
-    auto ones = [&]() __attribute__((always_inline)) {
-      if constexpr (!ONES) { bq.x |= bconst[0]; bq.y |= bconst[0]; bq.z |= bconst[0]; bq.w |= bconst[0]; }
+    auto ones = [&](int nt = 0) __attribute__((always_inline)) {
+      if constexpr (!ONES) { bq.x |= bconst[nt]; bq.y |= bconst[nt]; bq.z |= bconst[nt]; bq.w |= bconst[nt]; }
     };
-    auto second = [&]() __attribute__((always_inline)) { accw[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aq), __builtin_bit_cast(bf16x8_t, bq), accw[0], 0, 0, 0); };
+    auto second = [&](int nt = 0) __attribute__((always_inline)) {
+      accw[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aq), __builtin_bit_cast(bf16x8_t, bq), accw[nt], 0, 0, 0);
+    };
 #define DW0_MF(c, xi, s, ks) nxt[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[xi], wr[s][ks], nxt[c], 0, 0, 0)
 #define DW0_FENCE() __builtin_amdgcn_sched_barrier(0)
 #pragma unroll
     for (int c = 0; c < 4; ++c) nxt[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    if constexpr (NT == 2) {
+      // two 16-column tiles of the second product per pixel row (the bias column is in the second)
+      masks(0, 0); x[0] = xr(0); DW0_FENCE();
+      DW0_MF(0, 0, 4, 0); keep2(0, 0); masks(0, 1); DW0_FENCE();
+      DW0_MF(1, 0, 5, 0); keep2(0, 2); conv_lo(); x[1] = xr(1); DW0_FENCE();
+      DW0_MF(2, 0, 7, 0); keep2(0, 4); window(0, 0); DW0_FENCE();
+      DW0_MF(3, 0, 8, 0); keep2(0, 6); conv_hi(); DW0_FENCE();
+      DW0_MF(0, 1, 4, 1); masks(1, 0); DW0_FENCE();
+      DW0_MF(1, 1, 5, 1); halves(0); DW0_FENCE();
+      DW0_MF(2, 1, 7, 1); window(0, 1); x[2] = xr(2); DW0_FENCE();
+      DW0_MF(3, 1, 8, 1); masks(1, 1); DW0_FENCE();
+      second(0); x[3] = xr(3); DW0_FENCE();
+      DW0_MF(1, 2, 3, 0); halves(1); ones(1); DW0_FENCE();
+      second(1); x[4] = xr(4); DW0_FENCE();
+      DW0_MF(3, 2, 6, 0); keep2(1, 0); DW0_FENCE();
+      DW0_MF(1, 3, 3, 1); keep2(1, 2); conv_lo(); DW0_FENCE();
+      DW0_MF(3, 3, 6, 1); keep2(1, 4); window(1, 0); x[5] = xr(5); DW0_FENCE();
+      DW0_MF(2, 4, 1, 0); keep2(1, 6); conv_hi(); DW0_FENCE();
+      DW0_MF(3, 4, 2, 0); x[6] = xr(6); DW0_FENCE();
+      DW0_MF(2, 5, 1, 1); halves(0); DW0_FENCE();
+      DW0_MF(3, 5, 2, 1); window(1, 1); x[7] = xr(7); DW0_FENCE();
+      second(0); DW0_FENCE();
+      DW0_MF(3, 6, 0, 0); DW0_FENCE();
+      DW0_MF(3, 7, 0, 1); halves(1); ones(1); DW0_FENCE();
+      second(1); DW0_FENCE();
+    } else {
     masks(0, 0); x[0] = xr(0); DW0_FENCE();
     DW0_MF(0, 0, 4, 0); keep2(0, 0); masks(0, 1); DW0_FENCE();
     DW0_MF(1, 0, 5, 0); keep2(0, 2); conv_lo(); x[1] = xr(1); DW0_FENCE();
@@ -442,6 +464,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     DW0_MF(3, 5, 2, 1); DW0_FENCE();
     DW0_MF(3, 6, 0, 0);
     DW0_MF(3, 7, 0, 1); DW0_FENCE();
+    }
 #undef DW0_MF
 #undef DW0_FENCE
   };
@@ -454,7 +477,7 @@ __global__ __launch_bounds__((NCW + 4) * 64) void k_conv_dgrad_wgrad0_tile(ConvD
     dgrad(slot, 0, acc[0]);
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
-      if constexpr (C0 == 1) {
+      if constexpr (NT <= 2) {
         if (m + 1 < 4) fused(slot, m, acc[m & 1], acc[(m + 1) & 1]);
         else wgrad(slot, m, acc[m & 1]);
       } else {
